@@ -1,0 +1,68 @@
+"""The five benchmark configurations and reduced copies of each.
+
+CONFIGS[c] are the full sizes; SMALL[c] keep the same recipe (distribution
+family, skew, rank) at sizes a CPU loop finishes in seconds, chosen so that
+slices, fibers and tiles are ragged (not multiples of any kernel tile).
+Seeds: BASE_SEED + config number.
+"""
+from .generators import make_ttmc3, make_ttmc4, make_mttkrp3, make_sptn3
+
+BASE_SEED = 20240104
+
+
+def _c1(device, **kw):
+    n = kw.get("n", 200)
+    return make_ttmc3("c1", BASE_SEED + 1,
+                      [("uniform", n), ("uniform", n), ("uniform", n)],
+                      kw.get("nnz", 8000), kw.get("ranks", (8, 8)), "u11", "u11", device)
+
+
+def _c2(device, **kw):
+    dims = kw.get("dims", (12000, 9000, 29000))
+    return make_mttkrp3("c2", BASE_SEED + 2,
+                        [("zipf", dims[0], 1.1), ("zipf", dims[1], 1.1), ("zipf", dims[2], 1.1)],
+                        kw.get("nnz", 76_000_000), kw.get("rank", 32), "u01", "u11", device)
+
+
+def _c3(device, **kw):
+    dims = kw.get("dims", (1000, 50000, 50000, 2000))
+    return make_ttmc4("c3", BASE_SEED + 3,
+                      [("uniform", dims[0]), ("zipf", dims[1], 1.05), ("zipf", dims[2], 1.05),
+                       ("zipf", dims[3], 1.05)],
+                      kw.get("nnz", 40_000_000), kw.get("ranks", (16, 16, 16)), "n01", "n01", device)
+
+
+def _c4(device, **kw):
+    dims = kw.get("dims", (2000, 2000, 400, 2000, 400))
+    nb = kw.get("nblocks", 20)
+    grid = nb ** 3
+    return make_sptn3("c4", BASE_SEED + 4, dims, nb,
+                      kw.get("n_sel_u", round(0.08 * grid)), kw.get("n_sel_w", round(0.10 * grid)),
+                      device)
+
+
+def _c5(device, **kw):
+    dims = kw.get("dims", (2_000_000, 2_000_000, 25_000))
+    return make_ttmc3("c5", BASE_SEED + 5,
+                      [("zipf", dims[0], 1.3), ("zipf", dims[1], 1.3), ("uniform", dims[2])],
+                      kw.get("nnz", 140_000_000), kw.get("ranks", (64, 64)), "u11", "u11", device,
+                      compact=True)
+
+
+CONFIGS = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5}
+
+# reduced copies: same recipe, sizes for CPU-second oracle runs
+SMALL = {
+    1: dict(),                                                       # C1 is already small
+    2: dict(dims=(1203, 907, 2903), nnz=150_001, rank=32),
+    3: dict(dims=(37, 1511, 1499, 211), nnz=60_007, ranks=(16, 16, 16)),
+    4: dict(dims=(60, 80, 40, 60, 40), nblocks=4, n_sel_u=6, n_sel_w=7),
+    5: dict(dims=(20_011, 19_997, 2503), nnz=200_003, ranks=(64, 64)),
+}
+
+
+def make(cid, device="cpu", small=False, **overrides):
+    """Build configuration `cid` (1..5); small=True gives the reduced copy."""
+    kw = dict(SMALL[cid]) if small else {}
+    kw.update(overrides)
+    return CONFIGS[cid](device, **kw)
