@@ -1,0 +1,198 @@
+/*
+ * conststn -- fused execution of sparse tensor contraction trees on one AMD CDNA4 GPU.
+ *
+ * The library executes the fused loop nest that the CoNST paper (arXiv 2401.04836)
+ * derives for a tree of binary contractions over a sparse tensor stored in CSF:
+ * the schedule (execution order, one loop permutation per contraction, CSF mode
+ * orders, fusion depth) is SUPPLIED by the caller as the plan -- the paper's
+ * constraint search (Sec. 3) is not part of this library.
+ *
+ * Three verbs:   conststn_build_csf  ->  conststn_plan  ->  conststn_execute
+ *
+ * Conventions
+ *   - "device pointer": memory of the current HIP device, owned by the caller
+ *     unless stated otherwise.  "host pointer": ordinary process memory.
+ *   - Every function returns a conststn_status; on failure a human-readable
+ *     message is available from conststn_last_error() (thread local).  The
+ *     library never aborts and never throws across this boundary.  After a
+ *     failed conststn_execute the contents of `out` are unspecified.
+ *   - All values are IEEE fp64.  Indices are int32, child pointers int64.
+ *   - Handles are not thread safe; use one handle from one thread at a time.
+ */
+#ifndef CONSTSTN_H
+#define CONSTSTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONSTSTN_MAX_ORDER 8
+
+typedef enum {
+    CONSTSTN_OK = 0,
+    CONSTSTN_EINVAL = 1,        /* null pointer, bad order/rank/size, malformed schedule text      */
+    CONSTSTN_ERANGE = 2,        /* a coordinate is negative or >= its mode extent                   */
+    CONSTSTN_EDUP = 3,          /* duplicate coordinate: the nonzero structure is a set (Sec. 2.1)  */
+    CONSTSTN_ESCHED = 4,        /* schedule violates a legality rule of Sec. 3.2                    */
+    CONSTSTN_EUNSUPPORTED = 5,  /* legal, but no kernel family implements it                        */
+    CONSTSTN_ENOMEM = 6,        /* device or host allocation failed                                 */
+    CONSTSTN_EHIP = 7           /* a HIP runtime call failed                                        */
+} conststn_status;
+
+typedef struct conststn_csf_s conststn_csf_t;     /* a sparse tensor in CSF, resident on the device */
+typedef struct conststn_plan_s conststn_plan_t;   /* a validated schedule bound to its kernels      */
+typedef void *conststn_stream;                    /* a hipStream_t (NULL = the default stream)      */
+
+/* flags of conststn_build_csf */
+#define CONSTSTN_COALESCE_DUPS 1u   /* sum duplicate coordinates in input order instead of failing  */
+/* flags of conststn_plan */
+#define CONSTSTN_OUT_COMPACT 1u     /* output holds one row block per NONEMPTY root index only      */
+
+/* ------------------------------------------------------------------------------------------
+ * (1) COO -> CSF on the GPU.      [Sec. 2.1 "Sparse tensors", "CSF representation"]
+ *
+ * A CSF is the tree fixed by a permutation of the tensor's modes: level l holds, for every
+ * distinct coordinate prefix of length l+1 (in mode_order), the index value in mode
+ * mode_order[l]; leaves carry the values.  mode_order[l] = the mode at level l, outermost
+ * first; it is the inverse of the paper's dp_{T,j} (position of mode j in the layout,
+ * Sec. 3.2 "Ordering of tensor modes").
+ *
+ *   order      number of modes, 1..CONSTSTN_MAX_ORDER
+ *   dims       host pointer, order extents (each 1 .. 2^31-1)
+ *   nnz        number of nonzeros (>= 0; 0 gives an empty CSF)
+ *   coords     host pointer to `order` DEVICE pointers; coords[m][n] = index of nonzero n in mode m
+ *   vals       device pointer, nnz values (stored zeros are kept as structural nonzeros)
+ *   mode_order host pointer, a permutation of 0..order-1
+ *   flags      0 or CONSTSTN_COALESCE_DUPS
+ *   stream     the work is enqueued on this stream and the call waits for it: on return the
+ *              CSF is complete and range / duplicate errors have been reported
+ *   out        receives the handle; the library owns every array inside it (the inputs are
+ *              copied/permuted, never aliased) until conststn_csf_destroy
+ *
+ * Array layout of the result (what conststn_csf_export hands out), for level l:
+ *   idx[l]  int32[nodes_l]      index value of each node, children of one parent strictly ascending
+ *   ptr[l]  int64[nodes_l + 1]  children of node p are nodes ptr[l][p] .. ptr[l][p+1]-1 of level
+ *                               l+1 (no ptr for the last level); ptr[l][0] = 0
+ *   vals    fp64[nnz]           aligned with the last level (nodes_{order-1} = nnz)
+ * No explicit root node: the root's children are all nodes of level 0.
+ *
+ * Errors: EINVAL, ERANGE, EDUP, EUNSUPPORTED (packed sort key wider than 64 bits), ENOMEM, EHIP.
+ */
+conststn_status conststn_build_csf(int order, const int64_t *dims, int64_t nnz,
+                                   const int32_t *const *coords, const double *vals,
+                                   const int *mode_order, unsigned flags,
+                                   conststn_stream stream, conststn_csf_t **out);
+
+/* Describe a CSF: any output pointer may be NULL.  dims/mode_order receive `order` entries. */
+conststn_status conststn_csf_info(const conststn_csf_t *csf, int *order, int64_t *dims,
+                                  int *mode_order, int64_t *nnz);
+
+/* Borrow the device arrays of one level (valid until destroy).  ptr is NULL for the last
+ * level; vals is non-NULL only for the last level.  Any output pointer may be NULL. */
+conststn_status conststn_csf_export(const conststn_csf_t *csf, int level, const int32_t **idx,
+                                    const int64_t **ptr, int64_t *nodes, const double **vals);
+
+void conststn_csf_destroy(conststn_csf_t *csf);
+
+/* ------------------------------------------------------------------------------------------
+ * (2) Plan: a schedule in the paper's abstraction -- the sequence S of pairs <A, pi>
+ *     (Sec. 4.2), in execution order (the ap_i of Sec. 3.2 "Ordering of assignments").
+ *
+ * schedule   host string, statements separated by ';', each
+ *                 OUT[i,j,..] = A[..] * B[..] | loop,order,of,all,indices
+ *            e.g. mode-0 TTMc of Sec. 5.3 with X stored i>j>k:
+ *                 "T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s ; Y[i,r,s] = T[i,j,s] * U2[j,r] | i,j,r,s"
+ *            A reference to a CSF operand lists its indices in LEVEL order (the paper writes
+ *            A_ipq stored <d1,d2,d0> as A[p,q,i], Sec. 2.1); a dense operand's reference lists
+ *            them in row-major storage order; the last statement's left side fixes the row-major
+ *            layout of the output.
+ * fusion     host pointer or NULL; fusion[p] = number of outermost loops statement p shares with
+ *            the consumer of its result (-1 or NULL: the longest legal common prefix, which is
+ *            what Algorithm 1 of Sec. 4.2 produces).  The entry of the last statement is ignored.
+ *            The order of an intermediate after fusion is its order minus this depth.
+ * operands   host pointer, n_operands descriptors naming every INPUT tensor of the schedule
+ * flags      0 or CONSTSTN_OUT_COMPACT
+ *
+ * Legality rules checked (CONSTSTN_ESCHED when violated), all from Sec. 3.2:
+ *   - every consumed intermediate is produced by an EARLIER statement, exactly once consumed
+ *     (topological order of a tree);
+ *   - each loop order is a permutation of the statement's indices; an index has one extent;
+ *   - for every CSF operand, level order implies loop order ("Consistency between mode order
+ *     and loop order"); not required of dense operands and of intermediates, which are dense
+ *     workspaces;
+ *   - the fused prefix of a producer consists of indices of its result ("Producer constraints"),
+ *     equals the consumer's prefix position by position ("Consumer constraints"), and every
+ *     statement between the two shares it ("Statements between producer and consumer").
+ * A legal schedule that matches no kernel family gives CONSTSTN_EUNSUPPORTED.
+ * The plan keeps pointers into the CSF handles: destroy the plan first.
+ */
+typedef enum { CONSTSTN_OPERAND_CSF = 0, CONSTSTN_OPERAND_DENSE = 1 } conststn_operand_kind;
+
+typedef struct {
+    const char *name;                    /* tensor name as written in the schedule             */
+    int kind;                            /* conststn_operand_kind                               */
+    const conststn_csf_t *csf;           /* CSF operands: the handle; otherwise NULL            */
+    int order;                           /* dense operands: number of modes                     */
+    int64_t dims[CONSTSTN_MAX_ORDER];    /* dense operands: extents in storage (row-major) order */
+} conststn_operand_desc;
+
+conststn_status conststn_plan(const char *schedule, const int *fusion, int n_operands,
+                              const conststn_operand_desc *operands, unsigned flags,
+                              conststn_plan_t **out);
+
+/* Host-only: parse and check a schedule exactly as conststn_plan does, and lower it to
+ * nested forall / where text (the concrete-index-notation shape of Sec. 4.1, produced by the
+ * grouping recursion of Sec. 4.2), without binding kernels or touching a device.  CSF operands
+ * may be described by structure only: csf = NULL, order and dims (extents in LEVEL order) set.
+ * reduced_orders (host pointer or NULL) receives, per statement, the order of its result
+ * after fusion.  Writes at most len-1 characters + NUL to buf (buf may be NULL). */
+conststn_status conststn_schedule_check(const char *schedule, const int *fusion, int n_operands,
+                                        const conststn_operand_desc *operands, char *buf,
+                                        size_t len, int *reduced_orders);
+
+/* Output shape: n_rows row blocks of row_elems fp64 each, row-major.  Without
+ * CONSTSTN_OUT_COMPACT n_rows is the extent of the output's first index (rows of empty
+ * slices are zero); with it n_rows is the number of nonempty root indices. */
+conststn_status conststn_plan_output_size(const conststn_plan_t *plan, int64_t *n_rows,
+                                          int64_t *row_elems);
+
+/* Compact output only: device pointer to the n_rows root index values (ascending) the row
+ * blocks belong to; borrowed, valid until the CSF is destroyed. */
+conststn_status conststn_plan_output_rows(const conststn_plan_t *plan, const int32_t **rows,
+                                          int64_t *n_rows);
+
+/* Text description of the lowered plan (kernel family, loop tree in forall/where form,
+ * order of each intermediate after fusion).  Writes at most len-1 characters + NUL. */
+conststn_status conststn_plan_describe(const conststn_plan_t *plan, char *buf, size_t len);
+
+void conststn_plan_destroy(conststn_plan_t *plan);
+
+/* ------------------------------------------------------------------------------------------
+ * (3) Execute the fused loop nest (Fig. 3b / Fig. 4 of the paper: outer fused loops walk
+ *     the top CSF levels, reduced-order dense temporaries live on chip, the consumer
+ *     accumulates into the output).
+ *
+ *   dense_factors  host pointer to device pointers, one per DENSE operand, in the order the
+ *                  dense operands appear in the plan's operand list; row-major, read only
+ *   out            device pointer, n_rows * row_elems fp64; fully overwritten
+ *   stream         all work is enqueued here; the call does not wait for it
+ *
+ * Scratch memory owned by the plan is reused by every execute of that plan: two executes of
+ * ONE plan must not overlap in time (different plans may).
+ */
+conststn_status conststn_execute(const conststn_plan_t *plan, const double *const *dense_factors,
+                                 double *out, conststn_stream stream);
+
+/* Message of the last failure on this thread ("" if none). */
+const char *conststn_last_error(void);
+
+/* Library version string. */
+const char *conststn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONSTSTN_H */

@@ -1,0 +1,342 @@
+// The C ABI of the conststn library: argument checking, handle lifetime, kernel-family
+// matching of a validated schedule, and dispatch.  See include/conststn.h for the contract.
+#include <cstring>
+#include <set>
+#include <new>
+
+#include "plan.hpp"
+
+namespace cst {
+
+static thread_local std::string g_error;
+
+void set_error(const char *fmt, ...) {
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_error = buf;
+}
+const char *get_error() { return g_error.c_str(); }
+void clear_error() { g_error.clear(); }
+
+// ---- kernel-family matching -------------------------------------------------------------
+//
+// "Chain" families (TTMc, MTTKRP): one CSF operand X with levels x0 > x1 > ... > x_{n-1};
+// statement p contracts the innermost remaining sparse index x_{n-1-p} with a dense factor
+// F[x, r]; every producer is fused with its consumer on all remaining sparse indices.
+static conststn_status match_chain(conststn_plan_s *plan) {
+    Schedule &s = plan->sched;
+    const int m = int(s.stmts.size());
+    const Stmt &s0 = s.stmts[0];
+    int xop = -1;
+    const Ref *xref = nullptr;
+    if (s0.op_a >= 0 && s.operands[s0.op_a].kind == CONSTSTN_OPERAND_CSF) { xop = s0.op_a; xref = &s0.a; }
+    else if (s0.op_b >= 0 && s.operands[s0.op_b].kind == CONSTSTN_OPERAND_CSF) { xop = s0.op_b; xref = &s0.b; }
+    if (xop < 0) return CONSTSTN_EUNSUPPORTED;
+    const OperandInfo &X = s.operands[xop];
+    const int n = X.order;
+    if (m != n - 1 || n < 3 || n > 4) return CONSTSTN_EUNSUPPORTED;
+    if (!X.csf) { set_error("CSF operand %s has no handle", X.name.c_str()); return CONSTSTN_EINVAL; }
+    const std::vector<std::string> &x = xref->idx;
+    std::vector<std::string> ranks;          // rank index introduced by statement p
+    for (int p = 0; p < m; ++p) {
+        const Stmt &st = s.stmts[p];
+        // which input is the factor, which the running tensor
+        const Ref *fac = nullptr, *run = nullptr;
+        int fop = -1;
+        if (p == 0) {
+            run = xref;
+            fac = (xref == &st.a) ? &st.b : &st.a;
+            fop = (xref == &st.a) ? st.op_b : st.op_a;
+        } else {
+            if (st.src_a == p - 1) { run = &st.a; fac = &st.b; fop = st.op_b; }
+            else if (st.src_b == p - 1) { run = &st.b; fac = &st.a; fop = st.op_a; }
+            else return CONSTSTN_EUNSUPPORTED;
+        }
+        (void)run;
+        if (fop < 0 || s.operands[fop].kind != CONSTSTN_OPERAND_DENSE || s.operands[fop].order != 2)
+            return CONSTSTN_EUNSUPPORTED;
+        const int level = n - 1 - p;
+        if (fac->idx[0] != x[level]) return CONSTSTN_EUNSUPPORTED;      // F[x_level, r], row-major
+        ranks.push_back(fac->idx[1]);
+        for (int l = 0; l < n; ++l) if (fac->idx[1] == x[l]) return CONSTSTN_EUNSUPPORTED;
+        plan->factor_of_level[level] = s.operands[fop].dense_ordinal;
+        plan->rank_of_level[level] = int(s.operands[fop].dims[1]);
+        // result holds the remaining sparse indices and the rank indices so far
+        std::set<std::string> want(x.begin(), x.begin() + level);
+        want.insert(ranks.begin(), ranks.end());
+        std::set<std::string> got(st.out.idx.begin(), st.out.idx.end());
+        if (want != got) return CONSTSTN_EUNSUPPORTED;
+        // loops: remaining sparse indices in level order first
+        for (int l = 0; l <= level; ++l)
+            if (st.loops[l] != x[l]) return CONSTSTN_EUNSUPPORTED;
+        if (p + 1 < m && st.fused_depth != level) {
+            set_error("statement %d is fused to depth %d; the TTMc/MTTKRP kernels need the full sparse prefix (%d)",
+                      p, st.fused_depth, level);
+            return CONSTSTN_EUNSUPPORTED;
+        }
+    }
+    bool all_same = true, all_distinct = true;
+    for (int p = 1; p < m; ++p) {
+        if (ranks[p] != ranks[0]) all_same = false;
+        for (int q = 0; q < p; ++q) if (ranks[p] == ranks[q]) all_distinct = false;
+    }
+    const Stmt &last = s.stmts[m - 1];
+    if (all_same && m > 1) {
+        // MTTKRP: batch index r; output M[x0, r]
+        if (n != 3) { set_error("MTTKRP kernels exist for order-3 tensors only"); return CONSTSTN_EUNSUPPORTED; }
+        if (last.out.idx.size() != 2 || last.out.idx[0] != x[0] || last.out.idx[1] != ranks[0]) return CONSTSTN_EUNSUPPORTED;
+        for (int l = 2; l < n; ++l)
+            if (plan->rank_of_level[l] != plan->rank_of_level[1]) { set_error("batch index with two extents"); return CONSTSTN_ESCHED; }
+        plan->family = FAM_MTTKRP3;
+        plan->row_elems = plan->rank_of_level[1];
+    } else if (all_distinct) {
+        // TTMc: output Y[x0, r(level 1), r(level 2), ...]
+        if (int(last.out.idx.size()) != n || last.out.idx[0] != x[0]) return CONSTSTN_EUNSUPPORTED;
+        for (int l = 1; l < n; ++l)
+            if (last.out.idx[l] != ranks[n - 1 - l]) {
+                set_error("TTMc output must list the rank indices in CSF level order after the root index");
+                return CONSTSTN_EUNSUPPORTED;
+            }
+        plan->family = n == 3 ? FAM_TTMC3 : FAM_TTMC4;
+        plan->row_elems = 1;
+        for (int l = 1; l < n; ++l) plan->row_elems *= plan->rank_of_level[l];
+    } else {
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    plan->X = X.csf;
+    return CONSTSTN_OK;
+}
+
+// Three-tensor network  T[i,k,l] = U[i,k,j] V[j,l] ; Z[i,m] = T[i,k,l] W[k,l,m], fused on i,k.
+static conststn_status match_sptn3(conststn_plan_s *plan) {
+    Schedule &s = plan->sched;
+    if (s.stmts.size() != 2) return CONSTSTN_EUNSUPPORTED;
+    const Stmt &p0 = s.stmts[0], &p1 = s.stmts[1];
+    const Ref *u = nullptr, *v = nullptr;
+    int uop = -1, vop = -1;
+    if (p0.op_a >= 0 && s.operands[p0.op_a].kind == CONSTSTN_OPERAND_CSF) { u = &p0.a; uop = p0.op_a; v = &p0.b; vop = p0.op_b; }
+    else if (p0.op_b >= 0 && s.operands[p0.op_b].kind == CONSTSTN_OPERAND_CSF) { u = &p0.b; uop = p0.op_b; v = &p0.a; vop = p0.op_a; }
+    if (uop < 0 || vop < 0 || s.operands[vop].kind != CONSTSTN_OPERAND_DENSE) return CONSTSTN_EUNSUPPORTED;
+    if (s.operands[uop].order != 3 || s.operands[vop].order != 2) return CONSTSTN_EUNSUPPORTED;
+    const Ref *t = nullptr, *w = nullptr;
+    int wop = -1;
+    if (p1.src_a == 0) { t = &p1.a; w = &p1.b; wop = p1.op_b; }
+    else if (p1.src_b == 0) { t = &p1.b; w = &p1.a; wop = p1.op_a; }
+    if (!t || wop < 0 || s.operands[wop].kind != CONSTSTN_OPERAND_CSF || s.operands[wop].order != 3) return CONSTSTN_EUNSUPPORTED;
+    const std::string &i = u->idx[0], &k = u->idx[1], &j = u->idx[2];
+    if (v->idx[0] != j) return CONSTSTN_EUNSUPPORTED;
+    const std::string &l = v->idx[1];
+    if (w->idx[0] != k || w->idx[1] != l) return CONSTSTN_EUNSUPPORTED;
+    const std::string &mm = w->idx[2];
+    std::set<std::string> tset(p0.out.idx.begin(), p0.out.idx.end());
+    if (tset != std::set<std::string>{i, k, l}) return CONSTSTN_EUNSUPPORTED;
+    if (p1.out.idx.size() != 2 || p1.out.idx[0] != i || p1.out.idx[1] != mm) return CONSTSTN_EUNSUPPORTED;
+    if (std::set<std::string>{i, j, k, l, mm}.size() != 5) return CONSTSTN_EUNSUPPORTED;
+    if (p0.fused_depth != 2) {
+        set_error("the three-tensor kernel needs producer and consumer fused on the two outer loops (depth 2), got %d",
+                  p0.fused_depth);
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    if (!s.operands[uop].csf || !s.operands[wop].csf) { set_error("CSF operand without handle"); return CONSTSTN_EINVAL; }
+    plan->family = FAM_SPTN3;
+    plan->X = s.operands[uop].csf;
+    plan->W = s.operands[wop].csf;
+    plan->row_elems = s.extent[mm];
+    plan->factor_of_level[0] = s.operands[vop].dense_ordinal;
+    return CONSTSTN_OK;
+}
+
+static const char *family_name(Family f) {
+    switch (f) {
+        case FAM_TTMC3: return "ttmc3";
+        case FAM_TTMC4: return "ttmc4";
+        case FAM_MTTKRP3: return "mttkrp3";
+        case FAM_SPTN3: return "sptn3";
+        default: return "none";
+    }
+}
+
+}  // namespace cst
+
+using namespace cst;
+
+extern "C" {
+
+const char *conststn_last_error(void) { return get_error(); }
+const char *conststn_version(void) { return "conststn 0.1 (gfx950)"; }
+
+conststn_status conststn_build_csf(int order, const int64_t *dims, int64_t nnz,
+                                   const int32_t *const *coords, const double *vals,
+                                   const int *mode_order, unsigned flags, conststn_stream stream,
+                                   conststn_csf_t **out) {
+    clear_error();
+    if (!out) { set_error("out is null"); return CONSTSTN_EINVAL; }
+    *out = nullptr;
+    if (order < 1 || order > CONSTSTN_MAX_ORDER) { set_error("order %d outside 1..%d", order, CONSTSTN_MAX_ORDER); return CONSTSTN_EINVAL; }
+    if (!dims || !mode_order || !coords) { set_error("null argument"); return CONSTSTN_EINVAL; }
+    if (nnz < 0) { set_error("nnz is negative"); return CONSTSTN_EINVAL; }
+    if (nnz >= (int64_t(1) << 31)) { set_error("nnz of 2^31 or more is not implemented"); return CONSTSTN_EUNSUPPORTED; }
+    if (flags & ~CONSTSTN_COALESCE_DUPS) { set_error("unknown flag bits"); return CONSTSTN_EINVAL; }
+    bool seen[CONSTSTN_MAX_ORDER] = {false};
+    for (int l = 0; l < order; ++l) {
+        if (dims[l] < 1 || dims[l] > 0x7fffffffll) { set_error("extent of mode %d outside 1..2^31-1", l); return CONSTSTN_EINVAL; }
+        const int m = mode_order[l];
+        if (m < 0 || m >= order || seen[m]) { set_error("mode_order is not a permutation of 0..%d", order - 1); return CONSTSTN_EINVAL; }
+        seen[m] = true;
+        if (nnz > 0 && !coords[l]) { set_error("coords[%d] is null", l); return CONSTSTN_EINVAL; }
+    }
+    if (nnz > 0 && !vals) { set_error("vals is null"); return CONSTSTN_EINVAL; }
+    conststn_csf_s *csf = new (std::nothrow) conststn_csf_s();
+    if (!csf) { set_error("host allocation failed"); return CONSTSTN_ENOMEM; }
+    const conststn_status st = build_csf_device(order, dims, nnz, coords, vals, mode_order, flags,
+                                                static_cast<hipStream_t>(stream), csf);
+    if (st != CONSTSTN_OK) { delete csf; return st; }
+    *out = csf;
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_csf_info(const conststn_csf_t *csf, int *order, int64_t *dims, int *mode_order, int64_t *nnz) {
+    clear_error();
+    if (!csf) { set_error("csf is null"); return CONSTSTN_EINVAL; }
+    if (order) *order = csf->order;
+    if (nnz) *nnz = csf->nnz;
+    for (int l = 0; l < csf->order; ++l) {
+        if (dims) dims[l] = csf->dims[l];
+        if (mode_order) mode_order[l] = csf->mode_order[l];
+    }
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_csf_export(const conststn_csf_t *csf, int level, const int32_t **idx,
+                                    const int64_t **ptr, int64_t *nodes, const double **vals) {
+    clear_error();
+    if (!csf) { set_error("csf is null"); return CONSTSTN_EINVAL; }
+    if (level < 0 || level >= csf->order) { set_error("level %d outside 0..%d", level, csf->order - 1); return CONSTSTN_EINVAL; }
+    if (idx) *idx = csf->idx[level].p;
+    if (ptr) *ptr = level < csf->order - 1 ? csf->ptr[level].p : nullptr;
+    if (nodes) *nodes = csf->nodes[level];
+    if (vals) *vals = level == csf->order - 1 ? csf->vals.p : nullptr;
+    return CONSTSTN_OK;
+}
+
+void conststn_csf_destroy(conststn_csf_t *csf) { delete csf; }
+
+conststn_status conststn_schedule_check(const char *schedule, const int *fusion, int n_operands,
+                                        const conststn_operand_desc *operands, char *buf, size_t len,
+                                        int *reduced_orders) {
+    clear_error();
+    Schedule s;
+    CST_TRY(parse_schedule(schedule, s));
+    CST_TRY(validate_schedule(s, fusion, n_operands, operands));
+    if (buf && len > 0) {
+        std::strncpy(buf, s.lowered.c_str(), len - 1);
+        buf[len - 1] = 0;
+    }
+    if (reduced_orders)
+        for (size_t p = 0; p < s.stmts.size(); ++p) reduced_orders[p] = s.stmts[p].reduced_order;
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan(const char *schedule, const int *fusion, int n_operands,
+                              const conststn_operand_desc *operands, unsigned flags,
+                              conststn_plan_t **out) {
+    clear_error();
+    if (!out) { set_error("out is null"); return CONSTSTN_EINVAL; }
+    *out = nullptr;
+    if (flags & ~CONSTSTN_OUT_COMPACT) { set_error("unknown flag bits"); return CONSTSTN_EINVAL; }
+    conststn_plan_s *plan = new (std::nothrow) conststn_plan_s();
+    if (!plan) { set_error("host allocation failed"); return CONSTSTN_ENOMEM; }
+    struct Guard { conststn_plan_s *p; ~Guard() { delete p; } } guard{plan};
+    plan->flags = flags;
+    plan->compact = (flags & CONSTSTN_OUT_COMPACT) != 0;
+    CST_TRY(parse_schedule(schedule, plan->sched));
+    CST_TRY(validate_schedule(plan->sched, fusion, n_operands, operands));
+    for (const auto &o : plan->sched.operands)
+        if (o.kind == CONSTSTN_OPERAND_CSF && !o.csf) { set_error("CSF operand %s has no handle", o.name.c_str()); return CONSTSTN_EINVAL; }
+    for (const auto &o : plan->sched.operands) if (o.kind == CONSTSTN_OPERAND_DENSE) plan->n_dense++;
+
+    clear_error();
+    conststn_status st = match_chain(plan);
+    if (st == CONSTSTN_EUNSUPPORTED && plan->family == FAM_NONE) {
+        std::string why = get_error();
+        clear_error();
+        st = match_sptn3(plan);
+        if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
+    }
+    if (st == CONSTSTN_EUNSUPPORTED && !*get_error())
+        set_error("the schedule is legal but matches no kernel family (TTMc order 3/4, MTTKRP order 3, (U.V).W)");
+    CST_TRY(st);
+
+    const conststn_csf_s *X = plan->X;
+    plan->out_rows = plan->compact ? X->nodes[0] : X->dims[X->mode_order[0]];
+    switch (plan->family) {
+        case FAM_MTTKRP3: CST_TRY(build_mttkrp3_tables(plan)); break;
+        case FAM_TTMC3:
+        case FAM_TTMC4: CST_TRY(build_ttmc_tables(plan)); break;
+        case FAM_SPTN3: CST_TRY(build_sptn3_tables(plan)); break;
+        default: break;
+    }
+    char head[256];
+    snprintf(head, sizeof(head), "family=%s rows=%lld row_elems=%lld compact=%d", family_name(plan->family),
+             (long long)plan->out_rows, (long long)plan->row_elems, plan->compact ? 1 : 0);
+    plan->description = head;
+    for (size_t p = 0; p + 1 < plan->sched.stmts.size(); ++p) {
+        char b[128];
+        snprintf(b, sizeof(b), " %s:order%d", plan->sched.stmts[p].out.name.c_str(), plan->sched.stmts[p].reduced_order);
+        plan->description += b;
+    }
+    plan->description += " | " + plan->sched.lowered;
+    guard.p = nullptr;
+    *out = plan;
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan_output_size(const conststn_plan_t *plan, int64_t *n_rows, int64_t *row_elems) {
+    clear_error();
+    if (!plan) { set_error("plan is null"); return CONSTSTN_EINVAL; }
+    if (n_rows) *n_rows = plan->out_rows;
+    if (row_elems) *row_elems = plan->row_elems;
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan_output_rows(const conststn_plan_t *plan, const int32_t **rows, int64_t *n_rows) {
+    clear_error();
+    if (!plan) { set_error("plan is null"); return CONSTSTN_EINVAL; }
+    if (!plan->compact) { set_error("the plan's output is not compact"); return CONSTSTN_EINVAL; }
+    if (rows) *rows = plan->X->idx[0].p;
+    if (n_rows) *n_rows = plan->X->nodes[0];
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan_describe(const conststn_plan_t *plan, char *buf, size_t len) {
+    clear_error();
+    if (!plan || !buf || len == 0) { set_error("null argument"); return CONSTSTN_EINVAL; }
+    std::strncpy(buf, plan->description.c_str(), len - 1);
+    buf[len - 1] = 0;
+    return CONSTSTN_OK;
+}
+
+void conststn_plan_destroy(conststn_plan_t *plan) { delete plan; }
+
+conststn_status conststn_execute(const conststn_plan_t *plan, const double *const *dense_factors,
+                                 double *out, conststn_stream stream) {
+    clear_error();
+    if (!plan) { set_error("plan is null"); return CONSTSTN_EINVAL; }
+    if (!out && plan->out_rows * plan->row_elems > 0) { set_error("out is null"); return CONSTSTN_EINVAL; }
+    if (plan->n_dense > 0 && !dense_factors) { set_error("dense_factors is null"); return CONSTSTN_EINVAL; }
+    for (int d = 0; d < plan->n_dense; ++d)
+        if (!dense_factors[d]) { set_error("dense_factors[%d] is null", d); return CONSTSTN_EINVAL; }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (plan->family) {
+        case FAM_MTTKRP3: return launch_mttkrp3(plan, dense_factors, out, st);
+        case FAM_TTMC3: return launch_ttmc3(plan, dense_factors, out, st);
+        case FAM_TTMC4: return launch_ttmc4(plan, dense_factors, out, st);
+        case FAM_SPTN3: return launch_sptn3(plan, dense_factors, out, st);
+        default: set_error("plan has no kernel family"); return CONSTSTN_EINVAL;
+    }
+}
+
+}  // extern "C"

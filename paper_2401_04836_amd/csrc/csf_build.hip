@@ -1,0 +1,334 @@
+// GPU construction of a CSF tree from coordinate lists (Sec. 2.1, "CSF representation").
+//
+// Steps, all on the device:
+//   1. pack each coordinate tuple, permuted into level order, into one 64-bit key (outermost
+//      level in the most significant bits) and check ranges;
+//   2. stable radix sort of (key, original position) -- lexicographic order in mode_order;
+//   3. per tile, count for every level the positions where the key prefix of that level
+//      changes ("head" of a node); a duplicate coordinate is a position whose full key
+//      equals its predecessor's;
+//   4. scan the tile counts; the host reads the node totals and allocates the level arrays;
+//   5. per tile, rank the heads (block scan) and emit idx[l], ptr[l] and the permuted values.
+// The result is the canonical array layout documented in include/conststn.h.
+#include <cstring>
+#include <algorithm>
+#include <rocprim/rocprim.hpp>
+
+#include "common.hpp"
+
+namespace cst {
+
+constexpr int kTileThreads = 256;
+constexpr int kItems = 8;
+constexpr int kTile = kTileThreads * kItems;
+
+struct Levels {
+    int order;
+    int shift[CONSTSTN_MAX_ORDER];          // bit offset of the level's field inside the key
+    uint64_t mask[CONSTSTN_MAX_ORDER];      // field mask (after shifting)
+    int64_t dim[CONSTSTN_MAX_ORDER];        // extent of the mode at this level
+    const int32_t *coord[CONSTSTN_MAX_ORDER];
+};
+
+struct LevelOut {
+    int32_t *idx[CONSTSTN_MAX_ORDER];
+    int64_t *ptr[CONSTSTN_MAX_ORDER];
+};
+
+__device__ __forceinline__ uint64_t prefix_of(uint64_t key, int shift) {
+    return shift >= 64 ? 0 : (key >> shift);
+}
+
+__global__ void __launch_bounds__(256)
+pack_keys_kernel(int64_t nnz, Levels lv, uint64_t *keys, uint32_t *payload, int *flags) {
+    int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    bool bad = false;
+    for (; n < nnz; n += stride) {
+        uint64_t key = 0;
+        for (int l = 0; l < lv.order; ++l) {
+            int32_t c = lv.coord[l][n];
+            if (c < 0 || int64_t(c) >= lv.dim[l]) { bad = true; c = 0; }
+            if (lv.shift[l] < 64) key |= uint64_t(uint32_t(c)) << lv.shift[l];
+        }
+        keys[n] = key;
+        payload[n] = uint32_t(n);
+    }
+    if (bad) atomicOr(&flags[0], 1);
+}
+
+__device__ __forceinline__ unsigned wave_sum(unsigned v) {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// For every level the number of node heads inside each tile; leaf-level non-heads are duplicates.
+__global__ void __launch_bounds__(kTileThreads)
+count_heads_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
+                   unsigned *__restrict__ tile_counts, int64_t ntiles, int *flags) {
+    __shared__ unsigned wsum[CONSTSTN_MAX_ORDER][kTileThreads / 64];
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile + int64_t(threadIdx.x) * kItems;
+    unsigned cnt[CONSTSTN_MAX_ORDER];
+    for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) cnt[l] = 0;
+    uint64_t prev = 0;
+    bool have_prev = false;
+    if (base > 0 && base <= nnz) { prev = keys[base - 1]; have_prev = true; }
+    bool dup = false;
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t n = base + i;
+        if (n >= nnz) break;
+        const uint64_t k = keys[n];
+        for (int l = 0; l < lv.order; ++l) {
+            const bool head = !have_prev || prefix_of(k, lv.shift[l]) != prefix_of(prev, lv.shift[l]);
+            cnt[l] += head ? 1u : 0u;
+            if (l == lv.order - 1 && !head) dup = true;
+        }
+        prev = k;
+        have_prev = true;
+    }
+    if (dup) atomicOr(&flags[1], 1);
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    for (int l = 0; l < lv.order; ++l) {
+        unsigned s = wave_sum(cnt[l]);
+        if (lane == 0) wsum[l][wave] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < lv.order) {
+        unsigned s = 0;
+        for (int w = 0; w < kTileThreads / 64; ++w) s += wsum[threadIdx.x][w];
+        tile_counts[int64_t(threadIdx.x) * ntiles + tile] = s;
+    }
+}
+
+// Exclusive scan of the tile counts of every level (one block per level); totals[l] = node count.
+__global__ void __launch_bounds__(1024)
+scan_tiles_kernel(const unsigned *__restrict__ tile_counts, int64_t *__restrict__ tile_offsets,
+                  int64_t ntiles, int64_t *totals) {
+    __shared__ int64_t part[1024];
+    const int l = blockIdx.x;
+    const unsigned *in = tile_counts + int64_t(l) * ntiles;
+    int64_t *out = tile_offsets + int64_t(l) * ntiles;
+    const int64_t per = (ntiles + blockDim.x - 1) / blockDim.x;
+    const int64_t b = int64_t(threadIdx.x) * per;
+    const int64_t e = b + per < ntiles ? b + per : ntiles;
+    int64_t s = 0;
+    for (int64_t t = b; t < e; ++t) s += in[t];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t run = 0;
+        for (unsigned t = 0; t < blockDim.x; ++t) { int64_t v = part[t]; part[t] = run; run += v; }
+        totals[l] = run;
+    }
+    __syncthreads();
+    int64_t run = part[threadIdx.x];
+    for (int64_t t = b; t < e; ++t) { out[t] = run; run += in[t]; }
+}
+
+__device__ __forceinline__ unsigned block_exclusive_scan(unsigned v, unsigned *wtot /*[4]*/) {
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    unsigned inc = v;
+    for (int off = 1; off < 64; off <<= 1) {
+        unsigned t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    unsigned add = 0;
+    for (int w = 0; w < wave; ++w) add += wtot[w];
+    __syncthreads();
+    return add + inc - v;
+}
+
+// Rank heads and write the level arrays.  A head at level l is also a head at every deeper
+// level, so its child pointer is simply its own rank one level down.
+__global__ void __launch_bounds__(kTileThreads)
+emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
+                   const uint32_t *__restrict__ payload, const double *__restrict__ vals_in,
+                   const int64_t *__restrict__ tile_offsets, int64_t ntiles, LevelOut out,
+                   double *__restrict__ vals_out) {
+    __shared__ unsigned wtot[kTileThreads / 64];
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile + int64_t(threadIdx.x) * kItems;
+    uint64_t k[kItems];
+    unsigned headbits[kItems];                       // bit l set: head at level l
+    uint64_t prev = 0;
+    bool have_prev = false;
+    if (base > 0 && base <= nnz) { prev = keys[base - 1]; have_prev = true; }
+    unsigned cnt[CONSTSTN_MAX_ORDER];
+    for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) cnt[l] = 0;
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t n = base + i;
+        headbits[i] = 0;
+        k[i] = 0;
+        if (n < nnz) {
+            k[i] = keys[n];
+            for (int l = 0; l < lv.order; ++l) {
+                const bool head = !have_prev || prefix_of(k[i], lv.shift[l]) != prefix_of(prev, lv.shift[l]);
+                if (head) { headbits[i] |= 1u << l; cnt[l]++; }
+            }
+            prev = k[i];
+            have_prev = true;
+        }
+    }
+    int64_t pos[CONSTSTN_MAX_ORDER];
+    for (int l = 0; l < lv.order; ++l)
+        pos[l] = tile_offsets[int64_t(l) * ntiles + tile] + block_exclusive_scan(cnt[l], wtot);
+    const int last = lv.order - 1;
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t n = base + i;
+        if (n >= nnz) break;
+        for (int l = 0; l < lv.order; ++l) {
+            if (headbits[i] & (1u << l)) {
+                out.idx[l][pos[l]] = int32_t((lv.shift[l] >= 64 ? 0 : (k[i] >> lv.shift[l])) & lv.mask[l]);
+                if (l < last) out.ptr[l][pos[l]] = pos[l + 1];
+            }
+        }
+        if (headbits[i] & (1u << last)) {
+            // leaf head: its value is the sum of the run of equal keys, in input order
+            // (the sort is stable); without duplicates the run has length one
+            double s = vals_in[payload[n]];
+            for (int64_t m = n + 1; m < nnz && keys[m] == k[i]; ++m) s += vals_in[payload[m]];
+            vals_out[pos[last]] = s;
+        }
+        for (int l = 0; l < lv.order; ++l)
+            if (headbits[i] & (1u << l)) pos[l]++;
+    }
+}
+
+__global__ void close_ptrs_kernel(LevelOut out, int order, const int64_t *totals) {
+    const int l = threadIdx.x;
+    if (l < order - 1) out.ptr[l][totals[l]] = totals[l + 1];
+}
+
+conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
+                                 const int32_t *const *coords, const double *vals,
+                                 const int *mode_order, unsigned flags, hipStream_t stream,
+                                 conststn_csf_s *csf) {
+    Levels lv{};
+    lv.order = order;
+    int total_bits = 0;
+    int bits[CONSTSTN_MAX_ORDER];
+    for (int l = 0; l < order; ++l) {
+        const int m = mode_order[l];
+        bits[l] = ceil_log2_u64(uint64_t(dims[m]));
+        total_bits += bits[l];
+        lv.dim[l] = dims[m];
+        lv.coord[l] = coords[m];
+    }
+    if (total_bits > 64) {
+        set_error("packed coordinate key needs %d bits; only keys up to 64 bits are implemented",
+                  total_bits);
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    int sh = 0;
+    for (int l = order - 1; l >= 0; --l) {
+        lv.shift[l] = sh;
+        lv.mask[l] = bits[l] >= 64 ? ~uint64_t(0) : ((uint64_t(1) << bits[l]) - 1);
+        sh += bits[l];
+    }
+
+    csf->order = order;
+    csf->nnz = nnz;
+    for (int l = 0; l < order; ++l) {
+        csf->dims[l] = dims[l];
+        csf->mode_order[l] = mode_order[l];
+    }
+    CST_HIP(hipGetDevice(&csf->device));
+
+    LevelOut lo{};
+    if (nnz == 0) {
+        for (int l = 0; l < order; ++l) {
+            csf->nodes[l] = 0;
+            CST_TRY(csf->idx[l].alloc(0));
+            if (l < order - 1) {
+                CST_TRY(csf->ptr[l].alloc(1));
+                CST_HIP(hipMemsetAsync(csf->ptr[l].p, 0, sizeof(int64_t), stream));
+            }
+        }
+        CST_TRY(csf->vals.alloc(0));
+        CST_HIP(hipStreamSynchronize(stream));
+        return CONSTSTN_OK;
+    }
+
+    DevBuf<uint64_t> keys_a, keys_b;
+    DevBuf<uint32_t> pay_a, pay_b;
+    DevBuf<int> dflags;
+    CST_TRY(keys_a.alloc(nnz));
+    CST_TRY(keys_b.alloc(nnz));
+    CST_TRY(pay_a.alloc(nnz));
+    CST_TRY(pay_b.alloc(nnz));
+    CST_TRY(dflags.alloc(2));
+    CST_HIP(hipMemsetAsync(dflags.p, 0, 2 * sizeof(int), stream));
+
+    {
+        const int64_t blocks = std::min<int64_t>(div_up(nnz, 256), 65536);
+        pack_keys_kernel<<<dim3(unsigned(blocks)), dim3(256), 0, stream>>>(nnz, lv, keys_a.p, pay_a.p, dflags.p);
+        CST_HIP(hipGetLastError());
+    }
+
+    const uint64_t *skeys = keys_a.p;
+    const uint32_t *spay = pay_a.p;
+    if (total_bits > 0 && nnz > 1) {
+        size_t temp_bytes = 0;
+        CST_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys_a.p, keys_b.p, pay_a.p, pay_b.p,
+                                          size_t(nnz), 0u, unsigned(total_bits), stream));
+        DevBuf<char> temp;
+        CST_TRY(temp.alloc(temp_bytes));
+        CST_HIP(rocprim::radix_sort_pairs(temp.p, temp_bytes, keys_a.p, keys_b.p, pay_a.p, pay_b.p,
+                                          size_t(nnz), 0u, unsigned(total_bits), stream));
+        CST_HIP(hipStreamSynchronize(stream));      // temp is released at scope exit
+        skeys = keys_b.p;
+        spay = pay_b.p;
+    }
+
+    const int64_t ntiles = div_up(nnz, kTile);
+    DevBuf<unsigned> tile_counts;
+    DevBuf<int64_t> tile_offsets, totals;
+    CST_TRY(tile_counts.alloc(size_t(ntiles) * order));
+    CST_TRY(tile_offsets.alloc(size_t(ntiles) * order));
+    CST_TRY(totals.alloc(CONSTSTN_MAX_ORDER));
+    count_heads_kernel<<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
+        nnz, lv, skeys, tile_counts.p, ntiles, dflags.p);
+    CST_HIP(hipGetLastError());
+    scan_tiles_kernel<<<dim3(unsigned(order)), dim3(1024), 0, stream>>>(tile_counts.p, tile_offsets.p,
+                                                                      ntiles, totals.p);
+    CST_HIP(hipGetLastError());
+
+    int hflags[2] = {0, 0};
+    int64_t htotals[CONSTSTN_MAX_ORDER] = {0};
+    CST_HIP(hipMemcpyAsync(hflags, dflags.p, sizeof(hflags), hipMemcpyDeviceToHost, stream));
+    CST_HIP(hipMemcpyAsync(htotals, totals.p, sizeof(int64_t) * order, hipMemcpyDeviceToHost, stream));
+    CST_HIP(hipStreamSynchronize(stream));
+    if (hflags[0]) {
+        set_error("a coordinate is negative or not below its mode extent");
+        return CONSTSTN_ERANGE;
+    }
+    if (hflags[1] && !(flags & CONSTSTN_COALESCE_DUPS)) {
+        set_error("duplicate coordinate in the input (the nonzero structure must be a set)");
+        return CONSTSTN_EDUP;
+    }
+
+    for (int l = 0; l < order; ++l) {
+        csf->nodes[l] = htotals[l];
+        CST_TRY(csf->idx[l].alloc(size_t(htotals[l])));
+        lo.idx[l] = csf->idx[l].p;
+        if (l < order - 1) {
+            CST_TRY(csf->ptr[l].alloc(size_t(htotals[l]) + 1));
+            lo.ptr[l] = csf->ptr[l].p;
+        }
+    }
+    CST_TRY(csf->vals.alloc(size_t(htotals[order - 1])));
+    csf->nnz = htotals[order - 1];
+
+    emit_levels_kernel<<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
+        nnz, lv, skeys, spay, vals, tile_offsets.p, ntiles, lo, csf->vals.p);
+    CST_HIP(hipGetLastError());
+    close_ptrs_kernel<<<dim3(1), dim3(64), 0, stream>>>(lo, order, totals.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipStreamSynchronize(stream));
+    return CONSTSTN_OK;
+}
+
+}  // namespace cst

@@ -1,0 +1,149 @@
+// Fused order-3 TTMc over a CSF tensor (Sec. 5.3):
+//     Y[i,r2,r3] = sum_{j,k} X[i,j,k] U2[j,r2] U3[k,r3]
+// as the tree  T[i,j,r3] = X[i,j,k] U3[k,r3] ; Y[i,r2,r3] = T[i,j,r3] U2[j,r2]  fused on the
+// loops i and j: the intermediate is one length-R3 vector per (i,j) fiber, the consumer is
+// the rank-1 update Y_i += U2[j,:]^T (x) T, i.e. per slice Y_i = U2[J_i,:]^T . T_i.
+//
+// General kernel (any ranks up to 64): one wavefront per work item (a leaf range inside one
+// slice, see partition.hip); lane = r3, the R2 accumulators of column r3 live in registers.
+// All control flow is wave-uniform, so leaf indices/values and the U2 row are fetched with
+// scalar loads and the update is R2 FMAs with a scalar operand.
+#include "plan.hpp"
+
+namespace cst {
+
+struct Ttmc3Args {
+    int64_t n_items, n_split;
+    int R2, R3;
+    const int64_t *ptr1;
+    const int32_t *idx0, *idx1, *idx2;
+    const double *vals;
+    const SliceItem *items;
+    const int32_t *split_slices;
+    const int64_t *split_first;
+    const int32_t *split_count;
+    const double *U2, *U3;
+    double *out, *partial;
+    int compact;
+};
+
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const int lo = __builtin_amdgcn_readfirstlane(int(v & 0xffffffffll));
+    const int hi = __builtin_amdgcn_readfirstlane(int(v >> 32));
+    return (int64_t(hi) << 32) | int64_t(uint32_t(lo));
+}
+
+template <int R2T>
+__global__ void __launch_bounds__(256)
+ttmc3_kernel(Ttmc3Args a) {
+    const int lane = threadIdx.x % 64;
+    const int64_t w = uniform64(int64_t(blockIdx.x) * 4 + threadIdx.x / 64);
+    if (w >= a.n_items) return;
+    const SliceItem it = a.items[w];
+    const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
+    const int64_t nb = uniform64(it.end);
+    int64_t f = uniform64(it.first);
+    const int64_t dest = uniform64(it.dest);
+    const int R2 = a.R2, R3 = a.R3;
+    const bool active = lane < R3;
+    const int col = active ? lane : 0;
+
+    double y[R2T];
+#pragma unroll
+    for (int r = 0; r < R2T; ++r) y[r] = 0.0;
+    double t = 0.0;
+    int64_t fiber_end = uniform64(a.ptr1[f + 1]);
+    if (fiber_end > nb) fiber_end = nb;
+    int32_t j = __builtin_amdgcn_readfirstlane(a.idx1[f]);
+
+    for (int64_t n = uniform64(it.begin); n < nb;) {
+        // leaves of the current fiber that fall inside this item
+        for (; n < fiber_end; ++n) {
+            const int32_t k = __builtin_amdgcn_readfirstlane(a.idx2[n]);
+            const double v = a.vals[n];
+            t = fma(v, a.U3[int64_t(k) * R3 + col], t);
+        }
+        const double *u2 = a.U2 + int64_t(j) * R2;
+#pragma unroll
+        for (int r = 0; r < R2T; ++r)
+            if (r < R2) y[r] = fma(u2[r], t, y[r]);
+        t = 0.0;
+        if (n < nb) {
+            ++f;
+            j = __builtin_amdgcn_readfirstlane(a.idx1[f]);
+            fiber_end = uniform64(a.ptr1[f + 1]);
+            if (fiber_end > nb) fiber_end = nb;
+        }
+    }
+    const int64_t RR = int64_t(R2) * R3;
+    double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
+                            : a.partial + dest * RR;
+    if (active) {
+#pragma unroll
+        for (int r = 0; r < R2T; ++r)
+            if (r < R2) base[int64_t(r) * R3 + lane] = y[r];
+    }
+}
+
+// Row blocks of slices made of several items: add the partial blocks in item order.
+__global__ void __launch_bounds__(256)
+ttmc_fixup_kernel(int64_t RR, const int32_t *__restrict__ split_slices,
+                  const int64_t *__restrict__ split_first, const int32_t *__restrict__ split_count,
+                  const int32_t *__restrict__ idx0, int compact, const double *__restrict__ partial,
+                  double *__restrict__ out) {
+    const int64_t q = blockIdx.x;
+    const int64_t s = split_slices[q];
+    const int64_t first = split_first[q];
+    const int cnt = split_count[q];
+    const int64_t row = compact ? s : int64_t(idx0[s]);
+    for (int64_t e = int64_t(blockIdx.y) * blockDim.x + threadIdx.x; e < RR; e += int64_t(gridDim.y) * blockDim.x) {
+        double sum = 0.0;
+        for (int p = 0; p < cnt; ++p) sum += partial[(first + p) * RR + e];
+        out[row * RR + e] = sum;
+    }
+}
+
+conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream) {
+    if (plan->n_split == 0) return CONSTSTN_OK;
+    const int64_t RR = plan->row_elems;
+    const unsigned gy = unsigned(std::min<int64_t>(div_up(RR, 256), 64));
+    ttmc_fixup_kernel<<<dim3(unsigned(plan->n_split), gy), dim3(256), 0, stream>>>(
+        RR, plan->split_slices.p, plan->split_first.p, plan->split_count.p, plan->X->idx[0].p,
+        plan->compact ? 1 : 0, plan->partial.p, out);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
+conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *dense, double *out,
+                             hipStream_t stream) {
+    const conststn_csf_s *X = plan->X;
+    Ttmc3Args a{};
+    a.n_items = plan->n_items;
+    a.n_split = plan->n_split;
+    a.R2 = plan->rank_of_level[1];
+    a.R3 = plan->rank_of_level[2];
+    a.ptr1 = X->ptr[1].p;
+    a.idx0 = X->idx[0].p;
+    a.idx1 = X->idx[1].p;
+    a.idx2 = X->idx[2].p;
+    a.vals = X->vals.p;
+    a.items = plan->items.p;
+    a.U2 = dense[plan->factor_of_level[1]];
+    a.U3 = dense[plan->factor_of_level[2]];
+    a.out = out;
+    a.partial = plan->partial.p;
+    a.compact = plan->compact ? 1 : 0;
+    if (a.R2 > 64 || a.R3 > 64) { set_error("TTMc ranks above 64 are not implemented"); return CONSTSTN_EUNSUPPORTED; }
+    if (!plan->compact && X->nodes[0] < plan->out_rows)
+        CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
+    if (a.n_items == 0) return CONSTSTN_OK;
+    const dim3 grid(unsigned(div_up(a.n_items, 4))), block(256);
+    if (a.R2 <= 8) ttmc3_kernel<8><<<grid, block, 0, stream>>>(a);
+    else if (a.R2 <= 16) ttmc3_kernel<16><<<grid, block, 0, stream>>>(a);
+    else if (a.R2 <= 32) ttmc3_kernel<32><<<grid, block, 0, stream>>>(a);
+    else ttmc3_kernel<64><<<grid, block, 0, stream>>>(a);
+    CST_HIP(hipGetLastError());
+    return launch_ttmc_fixup(plan, out, stream);
+}
+
+}  // namespace cst

@@ -1,0 +1,236 @@
+// Load-balanced partition of a CSF tree into work units, built on the device at plan time.
+//
+// Power-law tensors have a few root slices with millions of leaves and very many with a
+// handful.  Two partitions are used:
+//   * MTTKRP (small accumulators): the LEAF array is cut into equal chunks regardless of
+//     slice and fiber boundaries; a chunk that ends inside a fiber or slice contributes a
+//     partial sum (legal by distributivity), combined by a fix-up pass.
+//   * TTMc (a whole R2 x R3 row block per slice): every slice is cut into items of bounded
+//     size; a slice made of several items is summed from partial row blocks by a fix-up pass.
+#include <cstring>
+#include <algorithm>
+#include <rocprim/rocprim.hpp>
+
+#include <cstdlib>
+
+#include "plan.hpp"
+
+namespace cst {
+
+int64_t env_int(const char *name, int64_t dflt) {
+    const char *v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    char *end = nullptr;
+    long long x = std::strtoll(v, &end, 10);
+    return (end && *end == 0 && x > 0) ? int64_t(x) : dflt;
+}
+
+__global__ void zero_fill_kernel(double *p, int64_t n) {
+    int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0.0;
+}
+
+conststn_status zero_fill(double *p, int64_t n, hipStream_t stream) {
+    if (n <= 0) return CONSTSTN_OK;
+    const int64_t blocks = std::min<int64_t>(div_up(n, 256), 16384);
+    zero_fill_kernel<<<dim3(unsigned(blocks)), dim3(256), 0, stream>>>(p, n);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
+// largest p in [0, n) with ptr[p] <= x   (ptr ascending, ptr[0] <= x < ptr[n])
+__device__ __forceinline__ int64_t owner_of(const int64_t *__restrict__ ptr, int64_t lo, int64_t hi, int64_t x) {
+    // invariant: ptr[lo] <= x < ptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (ptr[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// slice_leaf[s] = first leaf position below root node s (composition of the child pointers)
+__global__ void slice_leaf_kernel(int64_t slices, int levels_below, const int64_t *p0,
+                                  const int64_t *p1, const int64_t *p2, int64_t *slice_leaf) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s > slices) return;
+    int64_t x = s;
+    if (levels_below >= 1) x = p0[x];
+    if (levels_below >= 2) x = p1[x];
+    if (levels_below >= 3) x = p2[x];
+    slice_leaf[s] = x;
+}
+
+static conststn_status make_slice_leaf(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t slices = X->nodes[0];
+    CST_TRY(plan->slice_leaf.alloc(size_t(slices) + 1));
+    const int below = X->order - 1;
+    if (below > 3) { set_error("CSF order above 4 is not implemented in the partitioner"); return CONSTSTN_EUNSUPPORTED; }
+    slice_leaf_kernel<<<dim3(unsigned(div_up(slices + 1, 256))), dim3(256)>>>(
+        slices, below, below >= 1 ? X->ptr[0].p : nullptr, below >= 2 ? X->ptr[1].p : nullptr,
+        below >= 3 ? X->ptr[2].p : nullptr, plan->slice_leaf.p);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
+// ---- MTTKRP: equal chunks of the leaf array ---------------------------------------------
+
+__global__ void mttkrp_chunks_kernel(int64_t n_chunks, int64_t q, int64_t slices, int64_t fibers,
+                                     const int64_t *__restrict__ ptr0, const int64_t *__restrict__ ptr1,
+                                     int64_t *chunk_fiber, int32_t *chunk_slice) {
+    const int64_t c = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (c >= n_chunks) return;
+    const int64_t n = c * q;
+    const int64_t f = owner_of(ptr1, 0, fibers, n);
+    const int64_t s = owner_of(ptr0, 0, slices, f);
+    chunk_fiber[c] = f;
+    chunk_slice[c] = int32_t(s);
+}
+
+conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t nnz = X->nnz;
+    const int R = plan->rank_of_level[1];
+    CST_TRY(make_slice_leaf(plan));
+    // chunk length: short enough for >= ~64K independent lane groups, long enough that the
+    // two partial rows per chunk stay a small fraction of the traffic
+    int64_t q = env_int("CONSTSTN_MTTKRP_CHUNK", 0);
+    if (q <= 0) {
+        q = nnz / 65536;
+        q = std::max<int64_t>(64, std::min<int64_t>(q, 1024));
+    }
+    plan->chunk_q = q;
+    plan->n_chunks = div_up(nnz, q);
+    CST_TRY(plan->chunk_fiber.alloc(size_t(plan->n_chunks)));
+    CST_TRY(plan->chunk_slice.alloc(size_t(plan->n_chunks)));
+    CST_TRY(plan->partial.alloc(size_t(plan->n_chunks) * 2 * size_t(R)));
+    if (plan->n_chunks > 0) {
+        mttkrp_chunks_kernel<<<dim3(unsigned(div_up(plan->n_chunks, 256))), dim3(256)>>>(
+            plan->n_chunks, q, X->nodes[0], X->nodes[1], X->ptr[0].p, X->ptr[1].p,
+            plan->chunk_fiber.p, plan->chunk_slice.p);
+        CST_HIP(hipGetLastError());
+    }
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
+// ---- TTMc: bounded items inside slices ----------------------------------------------------
+
+__global__ void ttmc_count_kernel(int64_t slices, const int64_t *__restrict__ unit_ptr, int64_t split,
+                                  int64_t *pieces, int64_t *part_cnt, int64_t *is_split) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s >= slices) return;
+    const int64_t len = unit_ptr[s + 1] - unit_ptr[s];
+    const int64_t p = len <= split ? 1 : (len + split - 1) / split;
+    pieces[s] = p;
+    part_cnt[s] = p > 1 ? p : 0;
+    is_split[s] = p > 1 ? 1 : 0;
+}
+
+__global__ void ttmc_fill_kernel(int64_t slices, const int64_t *__restrict__ unit_ptr,
+                                 const int64_t *__restrict__ pieces, const int64_t *__restrict__ item_off,
+                                 const int64_t *__restrict__ part_off, const int64_t *__restrict__ split_rank,
+                                 int order, const int64_t *__restrict__ ptr0, const int64_t *__restrict__ ptr1,
+                                 SliceItem *items, int32_t *split_slices, int64_t *split_first,
+                                 int32_t *split_count) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s >= slices) return;
+    const int64_t a = unit_ptr[s], len = unit_ptr[s + 1] - a, np = pieces[s];
+    for (int64_t p = 0; p < np; ++p) {
+        SliceItem it;
+        it.slice = int32_t(s);
+        it.pad = 0;
+        // 128-bit safe: len < 2^40 and np < 2^31 in practice; split products to stay in range
+        it.begin = a + (len / np) * p + ((len % np) * p) / np;
+        it.end = (p + 1 == np) ? a + len : a + (len / np) * (p + 1) + ((len % np) * (p + 1)) / np;
+        it.first = 0;
+        if (order == 3) it.first = owner_of(ptr1, ptr0[s], ptr0[s + 1], it.begin);
+        it.dest = np > 1 ? part_off[s] + p : -1;
+        items[item_off[s] + p] = it;
+    }
+    if (np > 1) {
+        const int64_t r = split_rank[s];
+        split_slices[r] = int32_t(s);
+        split_first[r] = part_off[s];
+        split_count[r] = int32_t(np);
+    }
+}
+
+static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host) {
+    size_t bytes = 0;
+    CST_HIP(rocprim::exclusive_scan(nullptr, bytes, in, out, int64_t(0), size_t(n), rocprim::plus<int64_t>(), hipStream_t(0)));
+    DevBuf<char> temp;
+    CST_TRY(temp.alloc(bytes));
+    CST_HIP(rocprim::exclusive_scan(temp.p, bytes, in, out, int64_t(0), size_t(n), rocprim::plus<int64_t>(), hipStream_t(0)));
+    int64_t last_in = 0, last_out = 0;
+    CST_HIP(hipMemcpy(&last_in, in + (n - 1), sizeof(int64_t), hipMemcpyDeviceToHost));
+    CST_HIP(hipMemcpy(&last_out, out + (n - 1), sizeof(int64_t), hipMemcpyDeviceToHost));
+    *total_host = last_in + last_out;
+    return CONSTSTN_OK;
+}
+
+conststn_status build_ttmc_tables(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t slices = X->nodes[0];
+    CST_TRY(make_slice_leaf(plan));
+    plan->n_items = plan->n_partials = plan->n_split = 0;
+    if (slices == 0) return CONSTSTN_OK;
+    const int order = X->order;
+    // order 3 splits by leaves, order 4 by level-1 fibers (each carries a whole sub-tree)
+    const int64_t *unit_ptr = order == 3 ? plan->slice_leaf.p : X->ptr[0].p;
+    int64_t split = order == 3 ? env_int("CONSTSTN_TTMC3_SPLIT", 4096) : env_int("CONSTSTN_TTMC4_SPLIT", 256);
+    DevBuf<int64_t> pieces, part_cnt, is_split, item_off, part_off, split_rank;
+    CST_TRY(pieces.alloc(slices));
+    CST_TRY(part_cnt.alloc(slices));
+    CST_TRY(is_split.alloc(slices));
+    CST_TRY(item_off.alloc(slices));
+    CST_TRY(part_off.alloc(slices));
+    CST_TRY(split_rank.alloc(slices));
+    const dim3 grid(unsigned(div_up(slices, 256))), block(256);
+    ttmc_count_kernel<<<grid, block>>>(slices, unit_ptr, split, pieces.p, part_cnt.p, is_split.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(exscan(pieces.p, item_off.p, slices, &plan->n_items));
+    CST_TRY(exscan(part_cnt.p, part_off.p, slices, &plan->n_partials));
+    CST_TRY(exscan(is_split.p, split_rank.p, slices, &plan->n_split));
+    CST_TRY(plan->items.alloc(size_t(plan->n_items)));
+    CST_TRY(plan->split_slices.alloc(size_t(plan->n_split)));
+    CST_TRY(plan->split_first.alloc(size_t(plan->n_split)));
+    CST_TRY(plan->split_count.alloc(size_t(plan->n_split)));
+    CST_TRY(plan->partial.alloc(size_t(plan->n_partials) * size_t(plan->row_elems)));
+    ttmc_fill_kernel<<<grid, block>>>(slices, unit_ptr, pieces.p, item_off.p, part_off.p, split_rank.p,
+                                      order, X->ptr[0].p, X->ptr[1].p, plan->items.p,
+                                      plan->split_slices.p, plan->split_first.p, plan->split_count.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
+// ---- three-tensor network: where does index k sit among W's root nodes ---------------------
+
+__global__ void fill_i64_kernel(int64_t *p, int64_t n, int64_t v) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void w_roots_kernel(int64_t roots, const int32_t *__restrict__ idx0, int64_t *root_of_k) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p < roots) root_of_k[idx0[p]] = p;
+}
+
+conststn_status build_sptn3_tables(conststn_plan_s *plan) {
+    const conststn_csf_s *W = plan->W;
+    const int64_t K = W->dims[W->mode_order[0]];
+    CST_TRY(plan->w_root_of_k.alloc(size_t(K)));
+    fill_i64_kernel<<<dim3(unsigned(div_up(K, 256))), dim3(256)>>>(plan->w_root_of_k.p, K, -1);
+    CST_HIP(hipGetLastError());
+    if (W->nodes[0] > 0) {
+        w_roots_kernel<<<dim3(unsigned(div_up(W->nodes[0], 256))), dim3(256)>>>(W->nodes[0], W->idx[0].p,
+                                                                              plan->w_root_of_k.p);
+        CST_HIP(hipGetLastError());
+    }
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
+}  // namespace cst

@@ -1,0 +1,87 @@
+// The plan handle: a validated schedule matched to one kernel family, plus the device-side
+// work tables (load-balanced partition of the CSF tree) and scratch the kernels need.
+#pragma once
+
+#include "common.hpp"
+#include "schedule.hpp"
+
+namespace cst {
+
+enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
+
+// One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1
+// fibers (order 4) inside ONE root slice.  dest < 0: the slice has a single item and its row
+// block is stored straight to the output; otherwise dest is the slot of a partial row block.
+struct SliceItem {
+    int32_t slice;
+    int32_t pad;
+    int64_t begin, end;     // order 3: leaf range; order 4: level-1 fiber range
+    int64_t first;          // order 3: level-1 fiber containing `begin`; order 4: unused
+    int64_t dest;
+};
+
+}  // namespace cst
+
+struct conststn_plan_s {
+    cst::Schedule sched;
+    cst::Family family = cst::FAM_NONE;
+    unsigned flags = 0;
+    std::string description;
+
+    const conststn_csf_s *X = nullptr;    // the sparse operand walked by the fused loops
+    const conststn_csf_s *W = nullptr;    // second sparse operand (three-tensor network only)
+    int n_dense = 0;
+    int factor_of_level[CONSTSTN_MAX_ORDER] = {0};   // dense ordinal of the factor contracted at CSF level l
+    int rank_of_level[CONSTSTN_MAX_ORDER] = {0};     // its rank extent
+    int64_t out_rows = 0, row_elems = 0;
+    bool compact = false;
+
+    // --- device tables ---
+    cst::DevBuf<int64_t> slice_leaf;       // [slices+1] leaf position where each root slice starts
+    // MTTKRP: equal leaf-count chunks
+    int64_t chunk_q = 0, n_chunks = 0;
+    cst::DevBuf<int64_t> chunk_fiber;      // level-1 fiber containing the chunk's first leaf
+    cst::DevBuf<int32_t> chunk_slice;      // root slice containing that fiber
+    // TTMc: items inside slices
+    int64_t n_items = 0, n_partials = 0, n_split = 0;
+    cst::DevBuf<cst::SliceItem> items;
+    cst::DevBuf<int32_t> split_slices;     // slices made of more than one item
+    cst::DevBuf<int64_t> split_first;      // [n_split] first partial slot of that slice
+    cst::DevBuf<int32_t> split_count;      // [n_split] number of partial slots
+    cst::DevBuf<double> partial;           // partial row blocks
+    // three-tensor network
+    cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1
+};
+
+namespace cst {
+
+// partition.hip
+conststn_status build_mttkrp3_tables(conststn_plan_s *plan);
+conststn_status build_ttmc_tables(conststn_plan_s *plan);
+conststn_status build_sptn3_tables(conststn_plan_s *plan);
+
+// kernels_*.hip
+conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const *dense, double *out,
+                               hipStream_t stream);
+conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *dense, double *out,
+                             hipStream_t stream);
+conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *dense, double *out,
+                             hipStream_t stream);
+conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *dense, double *out,
+                             hipStream_t stream);
+// sums the partial row blocks of slices made of several items (shared by the TTMc kernels)
+conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream);
+
+// csf_build.hip
+conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
+                                 const int32_t *const *coords, const double *vals,
+                                 const int *mode_order, unsigned flags, hipStream_t stream,
+                                 conststn_csf_s *csf);
+
+// fill `n` doubles with zero on `stream` (a kernel, so that it is safe inside graph capture)
+conststn_status zero_fill(double *p, int64_t n, hipStream_t stream);
+
+// tuning knob read from the environment (0 = use the built-in choice)
+int64_t env_int(const char *name, int64_t dflt);
+
+}  // namespace cst

@@ -1,0 +1,20 @@
+"""Schedule strings (the plan input) for the workload families, in the paper's terms:
+a sequence of <assignment, loop order> pairs in execution order (Sec. 4.2), CSF operands
+written in level order (Sec. 2.1)."""
+
+# mode-0 TTMc of Sec. 5.3, X stored i>j>k:  contract the innermost CSF mode first
+TTMC3 = ("T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s ; "
+         "Y[i,r,s] = T[i,j,s] * U2[j,r] | i,j,r,s")
+
+# mode-0 MTTKRP of Sec. 5.2 (r is a batch index), X stored i>j>k
+MTTKRP3 = ("T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; "
+           "M[i,r] = T[i,j,r] * B[j,r] | i,j,r")
+
+# order-4 TTMc, X stored i>j>k>l; intermediates reduce to order 1 and order 2
+TTMC4 = ("T1[i,j,k,t] = X[i,j,k,l] * U3[l,t] | i,j,k,l,t ; "
+         "T2[i,j,s,t] = T1[i,j,k,t] * U2[k,s] | i,j,k,s,t ; "
+         "Y[i,r,s,t] = T2[i,j,s,t] * U1[j,r] | i,j,r,s,t")
+
+# three-tensor network of Sec. 1 as the tree (U.V).W; U stored i>k>j, W stored k>l>m
+SPTN3 = ("T[i,k,l] = U[i,k,j] * V[j,l] | i,k,j,l ; "
+         "Z[i,m] = T[i,k,l] * W[k,l,m] | i,k,l,m")

@@ -1,0 +1,113 @@
+"""Shared test plumbing: run one workload through the GPU library and through the oracle."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2401_04836_amd as cst
+from paper_2401_04836_amd import schedules as S
+
+TOL = 1e-10        # max |err| / sum|terms|  (fp64 outputs)
+
+
+def to_dev(coo, device="cuda"):
+    return [c.to(device) for c in coo.coords], coo.vals.to(device)
+
+
+def check_csf_bit_exact(csf, coo_np, vals_np, dims, mode_order):
+    """Every level array of the GPU CSF equals the reference build, bit for bit."""
+    idx, ptr, v, _ = oracle.csf_build(coo_np, vals_np, dims, list(mode_order))
+    for l in range(len(dims)):
+        gi, gp, gv = csf.export(l)
+        assert gi.dtype == torch.int32
+        np.testing.assert_array_equal(gi.cpu().numpy(), idx[l], err_msg="idx level %d" % l)
+        if l < len(dims) - 1:
+            assert gp.dtype == torch.int64
+            np.testing.assert_array_equal(gp.cpu().numpy(), ptr[l], err_msg="ptr level %d" % l)
+        else:
+            assert gp is None
+            assert np.array_equal(gv.cpu().numpy().view(np.int64), v.view(np.int64)), "vals differ"
+
+
+def run_gpu(wl, flags=0, check_csf=False):
+    """Build CSF(s), plan, execute.  Returns (out tensor [rows, ...], plan, csf handles)."""
+    dev = "cuda"
+    if wl.kind in ("ttmc3", "ttmc4", "mttkrp3"):
+        X = wl.sparse["X"]
+        coords, vals = to_dev(X, dev)
+        csf = cst.build_csf(coords, vals, X.dims, list(range(X.order)))
+        if check_csf:
+            c, v = X.numpy()
+            check_csf_bit_exact(csf, c, v, X.dims, list(range(X.order)))
+        if wl.kind == "ttmc3":
+            U2, U3 = wl.dense["U2"].to(dev), wl.dense["U3"].to(dev)
+            pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags)
+            out = cst.execute(pl, [U3, U2])
+            shape = (pl.n_rows, U2.shape[1], U3.shape[1])
+        elif wl.kind == "ttmc4":
+            U1, U2, U3 = (wl.dense[k].to(dev) for k in ("U1", "U2", "U3"))
+            pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)], flags=flags)
+            out = cst.execute(pl, [U3, U2, U1])
+            shape = (pl.n_rows, U1.shape[1], U2.shape[1], U3.shape[1])
+        else:
+            B, C = wl.dense["B"].to(dev), wl.dense["C"].to(dev)
+            pl = cst.plan(S.MTTKRP3, [("X", csf), ("C", C), ("B", B)], flags=flags)
+            out = cst.execute(pl, [C, B])
+            shape = (pl.n_rows, B.shape[1])
+        torch.cuda.synchronize()
+        return out.reshape(shape), pl, [csf]
+    if wl.kind == "sptn3":
+        U, W = wl.sparse["U"], wl.sparse["W"]
+        uc, uv = to_dev(U, dev)
+        wc, wv = to_dev(W, dev)
+        ucsf = cst.build_csf(uc, uv, U.dims, [0, 2, 1])          # i > k > j
+        wcsf = cst.build_csf(wc, wv, W.dims, [0, 1, 2])          # k > l > m
+        if check_csf:
+            c, v = U.numpy()
+            check_csf_bit_exact(ucsf, c, v, U.dims, [0, 2, 1])
+            c, v = W.numpy()
+            check_csf_bit_exact(wcsf, c, v, W.dims, [0, 1, 2])
+        V = wl.dense["V"].to(dev)
+        pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)], flags=flags)
+        out = cst.execute(pl, [V])
+        torch.cuda.synchronize()
+        return out.reshape(pl.n_rows, W.dims[2]), pl, [ucsf, wcsf]
+    raise ValueError(wl.kind)
+
+
+def run_oracle(wl):
+    """(value, sum|terms|) from the CPU oracle, dense over the root mode."""
+    if wl.kind == "ttmc3":
+        c, v = wl.sparse["X"].numpy()
+        d = wl.sparse["X"].dims
+        U2, U3 = wl.dense["U2"].cpu().numpy(), wl.dense["U3"].cpu().numpy()
+        return oracle.ttmc3(c, v, d, U2, U3, 0), oracle.ttmc3_abs(c, v, d, U2, U3, 0)
+    if wl.kind == "ttmc4":
+        c, v = wl.sparse["X"].numpy()
+        d = wl.sparse["X"].dims
+        U = [wl.dense[k].cpu().numpy() for k in ("U1", "U2", "U3")]
+        return oracle.ttmc4(c, v, d, *U), oracle.ttmc4_abs(c, v, d, *U)
+    if wl.kind == "mttkrp3":
+        c, v = wl.sparse["X"].numpy()
+        d = wl.sparse["X"].dims
+        B, C = wl.dense["B"].cpu().numpy(), wl.dense["C"].cpu().numpy()
+        return oracle.mttkrp3(c, v, d, B, C, 0), oracle.mttkrp3_abs(c, v, d, B, C, 0)
+    if wl.kind == "sptn3":
+        uc, uv = wl.sparse["U"].numpy()
+        wc, wv = wl.sparse["W"].numpy()
+        V = wl.dense["V"].cpu().numpy()
+        a = (uc, uv, wl.sparse["U"].dims, V, wc, wv, wl.sparse["W"].dims)
+        return oracle.sptn3(*a), oracle.sptn3_abs(*a)
+    raise ValueError(wl.kind)
+
+
+def compare(out_gpu, want, S_abs, rows=None):
+    """rel. error of GPU output vs oracle; rows = root indices of a compact output."""
+    got = out_gpu.cpu().numpy()
+    if rows is not None:
+        r = rows.cpu().numpy().astype(np.int64)
+        mask = np.ones(want.shape[0], dtype=bool)
+        mask[r] = False
+        assert not S_abs[mask].any(), "a row absent from the compact output has terms"
+        want, S_abs = want[r], S_abs[r]
+    assert got.shape == want.shape, (got.shape, want.shape)
+    return oracle.rel_err(got, want, S_abs)

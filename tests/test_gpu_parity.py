@@ -1,0 +1,198 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs, element by
+element; CSF arrays bit-exact against the reference build; edge cases."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2401_04836_amd as cst
+import workloads as w
+from paper_2401_04836_amd import schedules as S
+from helpers import TOL, check_csf_bit_exact, compare, run_gpu, run_oracle, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+@pytest.mark.parametrize("dims,nnz", [((23, 17, 31), 3000), ((7, 9, 5, 11), 2000), ((50, 40), 700), ((97,), 40)])
+def test_csf_bit_exact_every_mode_order(dims, nnz):
+    rng = np.random.default_rng(5)
+    flat = rng.choice(int(np.prod(dims)), size=nnz, replace=False)
+    coords = [c.astype(np.int32) for c in np.unravel_index(flat, dims)]
+    vals = rng.normal(size=nnz)
+    dc = [torch.from_numpy(c).cuda() for c in coords]
+    dv = torch.from_numpy(vals).cuda()
+    for mo in itertools.permutations(range(len(dims))):
+        _say("csf dims=%s mode_order=%s" % (dims, mo))
+        csf = cst.build_csf(dc, dv, dims, list(mo))
+        check_csf_bit_exact(csf, coords, vals, dims, mo)
+        assert csf.nnz == nnz and csf.mode_order == tuple(mo)
+        csf.destroy()
+
+
+def test_csf_spans_many_tiles_with_ragged_tail():
+    wl = w.make(2, small=True)                       # 150 001 nonzeros: 74 tiles, ragged tail
+    X = wl.sparse["X"]
+    c, v = X.numpy()
+    dc, dv = to_dev(X)
+    for mo in ([0, 1, 2], [2, 1, 0], [1, 2, 0]):
+        _say("csf c2-small mode_order=%s" % mo)
+        csf = cst.build_csf(dc, dv, X.dims, mo)
+        check_csf_bit_exact(csf, c, v, X.dims, mo)
+
+
+def test_csf_errors_and_edge_cases():
+    dims = (4, 5, 6)
+    c = [torch.tensor([1, 1], dtype=torch.int32).cuda(), torch.tensor([2, 2], dtype=torch.int32).cuda(),
+         torch.tensor([3, 3], dtype=torch.int32).cuda()]
+    v = torch.tensor([1.5, 2.25], dtype=torch.float64).cuda()
+    with pytest.raises(cst.ConststnError) as e:
+        cst.build_csf(c, v, dims, [0, 1, 2])
+    assert e.value.status_name == "EDUP"
+    csf = cst.build_csf(c, v, dims, [0, 1, 2], flags=cst.COALESCE_DUPS)      # summed in input order
+    assert csf.nnz == 1 and csf.export(2)[2].cpu().tolist() == [3.75]
+    bad = [c[0], c[1], torch.tensor([3, 6], dtype=torch.int32).cuda()]
+    with pytest.raises(cst.ConststnError) as e:
+        cst.build_csf(bad, v, dims, [0, 1, 2])
+    assert e.value.status_name == "ERANGE"
+    with pytest.raises(cst.ConststnError) as e:
+        cst.build_csf(c, v, dims, [0, 1, 1])
+    assert e.value.status_name == "EINVAL"
+    empty = [torch.zeros(0, dtype=torch.int32).cuda()] * 3
+    csf = cst.build_csf(empty, torch.zeros(0, dtype=torch.float64).cuda(), dims, [2, 0, 1])
+    assert csf.nnz == 0 and [csf.nodes(l) for l in range(3)] == [0, 0, 0]
+    assert csf.export(0)[1].cpu().tolist() == [0] and csf.export(1)[1].cpu().tolist() == [0]
+    # one nonzero
+    one = [torch.tensor([3], dtype=torch.int32).cuda(), torch.tensor([4], dtype=torch.int32).cuda(),
+           torch.tensor([5], dtype=torch.int32).cuda()]
+    csf = cst.build_csf(one, torch.tensor([2.0], dtype=torch.float64).cuda(), dims, [0, 1, 2])
+    assert [csf.export(l)[0].cpu().tolist() for l in range(3)] == [[3], [4], [5]]
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_small_configs_match_oracle(cid):
+    _say("parity config %d (reduced copy, dense output)" % cid)
+    wl = w.make(cid, small=True)
+    out, pl, _ = run_gpu(wl, check_csf=True)
+    want, S_abs = run_oracle(wl)
+    err = compare(out, want, S_abs)
+    _say("  %s -> rel err %.3e" % (pl.describe().split("|")[0], err))
+    assert err <= TOL
+
+
+def test_config1_full_size():
+    _say("parity config 1 full size")
+    wl = w.make(1)
+    out, pl, _ = run_gpu(wl, check_csf=True)
+    want, S_abs = run_oracle(wl)
+    assert compare(out, want, S_abs) <= TOL
+
+
+@pytest.mark.parametrize("cid", [1, 5])
+def test_compact_output(cid):
+    _say("compact output config %d" % cid)
+    wl = w.make(cid, small=True)
+    out, pl, _ = run_gpu(wl, flags=cst.OUT_COMPACT)
+    rows = pl.output_rows()
+    want, S_abs = run_oracle(wl)
+    assert rows.numel() == pl.n_rows and bool((rows[1:] > rows[:-1]).all())
+    assert compare(out, want, S_abs, rows=rows) <= TOL
+
+
+def test_mttkrp_mode2_by_rerooted_csf():
+    """Mode-2 MTTKRP: CSF k>j>i puts the output mode at the root (layout chosen per output mode)."""
+    _say("mttkrp mode 2 via CSF k>j>i")
+    wl = w.make(2, small=True)
+    X = wl.sparse["X"]
+    dc, dv = to_dev(X)
+    csf = cst.build_csf(dc, dv, X.dims, [2, 1, 0])
+    A, B = wl.dense["A"].cuda(), wl.dense["B"].cuda()
+    pl = cst.plan("T[k,j,r] = X[k,j,i] * A[i,r] | k,j,i,r ; M[k,r] = T[k,j,r] * B[j,r] | k,j,r",
+                  [("X", csf), ("A", A), ("B", B)])
+    out = cst.execute(pl, [A, B]).reshape(pl.n_rows, -1)
+    torch.cuda.synchronize()
+    c, v = X.numpy()
+    want = oracle.mttkrp3(c, v, X.dims, A.cpu().numpy(), B.cpu().numpy(), 2)
+    S_abs = oracle.mttkrp3_abs(c, v, X.dims, A.cpu().numpy(), B.cpu().numpy(), 2)
+    assert compare(out, want, S_abs) <= TOL
+
+
+@pytest.mark.parametrize("rank", [1, 3, 8, 17, 32, 50, 64])
+def test_mttkrp_ranks_and_heavy_slices(rank):
+    _say("mttkrp rank %d" % rank)
+    wl = w.make(2, small=True, dims=(301, 211, 503), nnz=40_003, rank=rank)
+    out, pl, _ = run_gpu(wl)
+    want, S_abs = run_oracle(wl)
+    assert compare(out, want, S_abs) <= TOL
+
+
+@pytest.mark.parametrize("ranks", [(1, 1), (3, 5), (8, 8), (16, 33), (64, 64), (50, 50)])
+def test_ttmc3_ranks(ranks):
+    _say("ttmc3 ranks %s" % (ranks,))
+    wl = w.make(5, small=True, dims=(501, 409, 211), nnz=30_011, ranks=ranks)
+    out, pl, _ = run_gpu(wl)
+    want, S_abs = run_oracle(wl)
+    assert compare(out, want, S_abs) <= TOL
+
+
+@pytest.mark.parametrize("ranks", [(1, 1, 1), (3, 5, 2), (16, 16, 16), (7, 16, 9)])
+def test_ttmc4_ranks(ranks):
+    _say("ttmc4 ranks %s" % (ranks,))
+    wl = w.make(3, small=True, dims=(19, 211, 199, 53), nnz=20_011, ranks=ranks)
+    out, pl, _ = run_gpu(wl)
+    want, S_abs = run_oracle(wl)
+    assert compare(out, want, S_abs) <= TOL
+
+
+def test_determinism_bitwise():
+    for cid in (2, 3, 4, 5):
+        _say("determinism config %d" % cid)
+        wl = w.make(cid, small=True)
+        a, _, _ = run_gpu(wl)
+        b, _, _ = run_gpu(wl)
+        assert torch.equal(a, b)
+
+
+def test_empty_tensor_and_single_nonzero_execute():
+    _say("empty tensor / single nonzero")
+    dims = (6, 5, 4)
+    U2 = torch.ones(5, 3, dtype=torch.float64).cuda()
+    U3 = torch.ones(4, 2, dtype=torch.float64).cuda()
+    empty = [torch.zeros(0, dtype=torch.int32).cuda()] * 3
+    csf = cst.build_csf(empty, torch.zeros(0, dtype=torch.float64).cuda(), dims, [0, 1, 2])
+    pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)])
+    out = cst.execute(pl, [U3, U2])
+    assert out.numel() == 6 * 3 * 2 and not bool(out.any())
+    plc = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=cst.OUT_COMPACT)
+    assert plc.n_rows == 0 and cst.execute(plc, [U3, U2]).numel() == 0
+    plm = cst.plan(S.MTTKRP3, [("X", csf), ("C", torch.ones(4, 3, dtype=torch.float64).cuda()),
+                               ("B", U2)])
+    assert not bool(cst.execute(plm, [torch.ones(4, 3, dtype=torch.float64).cuda(), U2]).any())
+    one = [torch.tensor([2], dtype=torch.int32).cuda(), torch.tensor([4], dtype=torch.int32).cuda(),
+           torch.tensor([1], dtype=torch.int32).cuda()]
+    csf1 = cst.build_csf(one, torch.tensor([-0.5], dtype=torch.float64).cuda(), dims, [0, 1, 2])
+    pl1 = cst.plan(S.TTMC3, [("X", csf1), ("U3", U3), ("U2", U2)])
+    out = cst.execute(pl1, [U3, U2]).reshape(6, 3, 2).cpu()
+    want = torch.zeros(6, 3, 2, dtype=torch.float64)
+    want[2] = -0.5
+    assert torch.equal(out, want)
+
+
+def test_unsupported_and_illegal_plans():
+    _say("plan errors")
+    wl = w.make(1)
+    X = wl.sparse["X"]
+    dc, dv = to_dev(X)
+    csf = cst.build_csf(dc, dv, X.dims, [0, 1, 2])
+    U2, U3 = wl.dense["U2"].cuda(), wl.dense["U3"].cuda()
+    with pytest.raises(cst.ConststnError) as e:      # legal but unfused: no kernel family
+        cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], fusion=[0, 0])
+    assert e.value.status_name == "EUNSUPPORTED"
+    with pytest.raises(cst.ConststnError) as e:      # loop order against the CSF layout
+        cst.plan(S.TTMC3.replace("| i,j,k,s", "| j,i,k,s"), [("X", csf), ("U3", U3), ("U2", U2)])
+    assert e.value.status_name == "ESCHED"
