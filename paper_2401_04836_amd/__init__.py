@@ -105,7 +105,7 @@ def _borrow(ptr, count, dtype, device, owner):
     m = _Mem()
     typestr = {torch.int32: "<i4", torch.int64: "<i8", torch.float64: "<f8"}[dtype]
     m.__cuda_array_interface__ = {"shape": (int(count),), "typestr": typestr,
-                                  "data": (int(ptr), True), "version": 2, "strides": None}
+                                  "data": (int(ptr), False), "version": 2, "strides": None}
     m._owner = owner
     t = torch.as_tensor(m, device=device)
     assert t.element_size() == itemsize
