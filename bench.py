@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused sparse contraction path on one MI355X.
+
+A step is one pass of the fused contraction over one synthetic batch with the CSF already
+resident in HBM: for the default workload (configuration 2: order-3 MTTKRP, 76 M nonzeros,
+rank 32) a step is the mode-0 MTTKRP (CSF i>j>k) followed by the mode-2 MTTKRP (CSF k>j>i).
+The CSF build (sort + pointer construction + partition) is timed separately and reported
+under "csf_build".  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+FP64_PEAK_TFLOPS = 78.6
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def build_mttkrp(cst, S, wl, dev):
+    X = wl.sparse["X"]
+    coords = [c.to(dev) for c in X.coords]
+    vals = X.vals.to(dev)
+    A, B, C = (wl.dense[k].to(dev) for k in ("A", "B", "C"))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    csf0 = cst.build_csf(coords, vals, X.dims, [0, 1, 2])
+    csf2 = cst.build_csf(coords, vals, X.dims, [2, 1, 0])
+    pl0 = cst.plan(S.MTTKRP3, [("X", csf0), ("C", C), ("B", B)])
+    pl2 = cst.plan("T[k,j,r] = X[k,j,i] * A[i,r] | k,j,i,r ; M[k,r] = T[k,j,r] * B[j,r] | k,j,r",
+                   [("X", csf2), ("A", A), ("B", B)])
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    R = B.shape[1]
+    launches = []
+    for csf, pl, facs in ((csf0, pl0, [C, B]), (csf2, pl2, [A, B])):
+        nodes = [csf.nodes(l) for l in range(3)]
+        out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
+        # algorithmic HBM bytes of one launch: every CSF entry once (index 4 B + value or child
+        # pointer 8 B), both factor matrices once, the output once
+        alg_bytes = 12 * (nodes[2] + nodes[1] + nodes[0]) + 8 * R * (facs[0].shape[0] + facs[1].shape[0]) \
+            + 8 * pl.n_rows * pl.row_elems
+        flops = 2 * R * (nodes[2] + nodes[1])
+        launches.append(dict(plan=pl, factors=facs, out=out, nodes=nodes, bytes=alg_bytes, flops=flops))
+    return launches, build_s, 2 * X.nnz
+
+
+def build_chain(cst, S, wl, dev, compact):
+    X = wl.sparse["X"]
+    coords = [c.to(dev) for c in X.coords]
+    vals = X.vals.to(dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    csf = cst.build_csf(coords, vals, X.dims, list(range(X.order)))
+    flags = cst.OUT_COMPACT if compact else 0
+    if wl.kind == "ttmc3":
+        U2, U3 = wl.dense["U2"].to(dev), wl.dense["U3"].to(dev)
+        pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags)
+        facs = [U3, U2]
+    else:
+        U1, U2, U3 = (wl.dense[k].to(dev) for k in ("U1", "U2", "U3"))
+        pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)], flags=flags)
+        facs = [U3, U2, U1]
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    nodes = [csf.nodes(l) for l in range(X.order)]
+    out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
+    alg_bytes = 12 * sum(nodes) + 8 * sum(f.numel() for f in facs) + 8 * pl.n_rows * pl.row_elems
+    ranks = [f.shape[1] for f in facs]             # innermost level first
+    flops, width = 0, 1
+    for lvl, r in zip(reversed(range(1, X.order)), ranks):
+        width *= r
+        flops += 2 * width * nodes[lvl]
+    return [dict(plan=pl, factors=facs, out=out, nodes=nodes, bytes=alg_bytes, flops=flops)], build_s, X.nnz
+
+
+def build_sptn(cst, S, wl, dev):
+    U, W = wl.sparse["U"], wl.sparse["W"]
+    uc, uv = [c.to(dev) for c in U.coords], U.vals.to(dev)
+    wc, wv = [c.to(dev) for c in W.coords], W.vals.to(dev)
+    V = wl.dense["V"].to(dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ucsf = cst.build_csf(uc, uv, U.dims, [0, 2, 1])
+    wcsf = cst.build_csf(wc, wv, W.dims, [0, 1, 2])
+    pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)])
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
+    un = [ucsf.nodes(l) for l in range(3)]
+    wn = [wcsf.nodes(l) for l in range(3)]
+    alg_bytes = 12 * (sum(un) + sum(wn)) + 8 * V.numel() + 8 * out.numel()
+    L = V.shape[1]
+    # producer: 2L flop per U nonzero; consumer: per (i,k) fiber, 2 flop per W nonzero under k
+    w_per_k = W.nnz / max(wn[0], 1)
+    flops = 2 * L * un[2] + 2 * w_per_k * un[1]
+    return [dict(plan=pl, factors=[V], out=out, nodes=un, bytes=alg_bytes, flops=flops)], build_s, U.nnz + W.nnz
+
+
+def cpu_baseline(wl, budget_nnz):
+    """The CPU oracle, as it stands, on a bounded sample (first nonzeros) of the same workload."""
+    import oracle
+    if wl.kind == "mttkrp3":
+        X = wl.sparse["X"]
+        n = min(X.nnz, budget_nnz)
+        c = [x[:n].cpu().numpy() for x in X.coords]
+        v = X.vals[:n].cpu().numpy()
+        B, C = wl.dense["B"].cpu().numpy(), wl.dense["C"].cpu().numpy()
+        oracle.lib()
+        t0 = time.perf_counter()
+        oracle.mttkrp3(c, v, X.dims, B, C, 0)
+        dt = time.perf_counter() - t0
+        return dict(value=n / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
+                    sample="mode-0 MTTKRP of the first %d nonzeros (input order), %.2f s" % (n, dt))
+    if wl.kind == "ttmc3":
+        X = wl.sparse["X"]
+        R2, R3 = wl.params["ranks"]
+        n = min(X.nnz, max(1000, budget_nnz * 32 // (R2 * R3)))
+        c = [x[:n].cpu().numpy() for x in X.coords]
+        v = X.vals[:n].cpu().numpy()
+        # restrict to the rows touched so the dense output of the sample stays small
+        import numpy as np
+        rows, inv = np.unique(c[0], return_inverse=True)
+        c[0] = inv.astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.ttmc3(c, v, (len(rows), X.dims[1], X.dims[2]), wl.dense["U2"].cpu().numpy(),
+                     wl.dense["U3"].cpu().numpy(), 0)
+        dt = time.perf_counter() - t0
+        return dict(value=n / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
+                    sample="TTMc of the first %d nonzeros (rows renumbered), %.2f s" % (n, dt))
+    if wl.kind == "ttmc4":
+        X = wl.sparse["X"]
+        n = min(X.nnz, max(1000, budget_nnz // 128))
+        c = [x[:n].cpu().numpy() for x in X.coords]
+        v = X.vals[:n].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.ttmc4(c, v, X.dims, *(wl.dense[k].cpu().numpy() for k in ("U1", "U2", "U3")))
+        dt = time.perf_counter() - t0
+        return dict(value=n / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
+                    sample="order-4 TTMc of the first %d nonzeros, %.2f s" % (n, dt))
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
+    ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures ONE GPU: the path has no multi-GPU part (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    import paper_2401_04836_amd as cst
+    from paper_2401_04836_amd import schedules as S
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.perf_counter()
+    wl = workloads.make(args.config, device=dev, small=args.small)
+    torch.cuda.synchronize()
+    log("generated config %d (%s) in %.1f s: %s" % (
+        args.config, wl.kind, time.perf_counter() - t0,
+        {k: (v.dims, v.nnz) for k, v in wl.sparse.items()}))
+
+    if wl.kind == "mttkrp3":
+        launches, build_s, nnz_per_step = build_mttkrp(cst, S, wl, dev)
+        name = "C2 MTTKRP order-3 %s nnz=%d rank=%d, modes 0 and 2" % (
+            "x".join(map(str, wl.sparse["X"].dims)), wl.sparse["X"].nnz, wl.params["rank"])
+    elif wl.kind in ("ttmc3", "ttmc4"):
+        launches, build_s, nnz_per_step = build_chain(cst, S, wl, dev, wl.params.get("compact", False))
+        name = "C%d TTMc order-%d %s nnz=%d ranks=%s" % (
+            args.config, wl.sparse["X"].order, "x".join(map(str, wl.sparse["X"].dims)),
+            wl.sparse["X"].nnz, wl.params["ranks"])
+    else:
+        launches, build_s, nnz_per_step = build_sptn(cst, S, wl, dev)
+        name = "C4 Z=(U.V).W dims(i,j,k,l,m)=%s nnzU=%d nnzW=%d" % (
+            wl.params["dims"], wl.sparse["U"].nnz, wl.sparse["W"].nnz)
+    if args.small:
+        name += " (reduced copy)"
+    for L in launches:
+        log("plan: %s" % L["plan"].describe().split("|")[0])
+        log("  CSF nodes per level %s, algorithmic bytes %.3f GB, flops %.3f G" % (
+            L["nodes"], L["bytes"] / 1e9, L["flops"] / 1e9))
+    log("CSF build + plan: %.3f s" % build_s)
+
+    def step():
+        for L in launches:
+            cst.execute(L["plan"], L["factors"], out=L["out"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    for L in launches:
+        L["plan"].profile(max(args.steps, 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms = []
+    for L in launches:
+        kernel_ms += L["plan"].kernel_times()
+        L["plan"].profile(0)
+    ms_per_step = dt / args.steps * 1e3
+    avg_kernel_ms = sum(kernel_ms) / max(len(kernel_ms), 1)
+    alg_bytes = sum(L["bytes"] for L in launches) / len(launches)          # per launch
+    flops_step = sum(L["flops"] for L in launches)
+    achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "fused sparse contraction nnz/s", "value": nnz_per_step / (dt / args.steps),
+        "unit": "nnz/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": name, "step": "one fused contraction pass per CSF (build excluded)"},
+        "gflops": flops_step / (dt / args.steps) / 1e9,
+        "fp64_frac": flops_step / (dt / args.steps) / 1e12 / FP64_PEAK_TFLOPS,
+        "csf_build": {"seconds": build_s, "nnz_per_s": nnz_per_step / build_s},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": launches[0]["plan"].describe().split()[0],
+                     "kernel_ms_avg": avg_kernel_ms, "launches_timed": len(kernel_ms),
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+    if not args.no_cpu:
+        cb = cpu_baseline(wl, 20_000_000)
+        if cb is not None:
+            result["cpu_baseline"] = cb
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -186,6 +186,17 @@ void conststn_plan_destroy(conststn_plan_t *plan);
 conststn_status conststn_execute(const conststn_plan_t *plan, const double *const *dense_factors,
                                  double *out, conststn_stream stream);
 
+/* Measurement hook (for benchmarks; not part of the method).  After
+ * conststn_plan_profile(plan, capacity > 0) every conststn_execute of the plan brackets its
+ * DOMINANT kernel (the fused traversal kernel, not the zero-fill or fix-up passes) with a pair
+ * of HIP events recorded on the execute's stream; capacity pairs are kept (older ones are
+ * overwritten).  conststn_plan_kernel_times waits for the recorded events and writes up to
+ * max_n durations in milliseconds, oldest first, to the host array ms, and their count to n;
+ * it then forgets them.  capacity = 0 switches the hook off.  The name of the bracketed kernel
+ * family is given by conststn_plan_describe ("family=..."). */
+conststn_status conststn_plan_profile(conststn_plan_t *plan, int capacity);
+conststn_status conststn_plan_kernel_times(conststn_plan_t *plan, float *ms, int max_n, int *n);
+
 /* Message of the last failure on this thread ("" if none). */
 const char *conststn_last_error(void);
 

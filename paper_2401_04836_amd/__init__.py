@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "conststn_plan", "conststn_schedule_check", "conststn_plan_output_size",
     "conststn_plan_output_rows", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
+    "conststn_plan_profile", "conststn_plan_kernel_times",
 ]
 
 
@@ -67,6 +68,8 @@ def _load():
     L.conststn_plan_destroy.argtypes = [vp]
     L.conststn_plan_destroy.restype = None
     L.conststn_execute.argtypes = [vp, ctypes.POINTER(vp), vp, vp]
+    L.conststn_plan_profile.argtypes = [vp, ctypes.c_int]
+    L.conststn_plan_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.c_int, ip]
     for name in EXPORTED_SYMBOLS:
         getattr(L, name)
     return L
@@ -246,6 +249,17 @@ class Plan:
         p, n = ctypes.c_void_p(), ctypes.c_int64()
         _check(_lib.conststn_plan_output_rows(self._h, ctypes.byref(p), ctypes.byref(n)))
         return _borrow(p.value, n.value, torch.int32, self.device, self)
+
+    def profile(self, capacity):
+        """conststn_plan_profile: keep `capacity` event pairs around the dominant kernel."""
+        _check(_lib.conststn_plan_profile(self._h, int(capacity)))
+
+    def kernel_times(self, max_n=4096):
+        """conststn_plan_kernel_times: durations (ms) of the dominant kernel, oldest first."""
+        buf = (ctypes.c_float * max_n)()
+        n = ctypes.c_int()
+        _check(_lib.conststn_plan_kernel_times(self._h, buf, max_n, ctypes.byref(n)))
+        return [buf[i] for i in range(n.value)]
 
     def destroy(self):
         if self._h:

@@ -1,5 +1,6 @@
 // The C ABI of the conststn library: argument checking, handle lifetime, kernel-family
 // matching of a validated schedule, and dispatch.  See include/conststn.h for the contract.
+#include <algorithm>
 #include <cstring>
 #include <set>
 #include <new>
@@ -320,6 +321,42 @@ conststn_status conststn_plan_describe(const conststn_plan_t *plan, char *buf, s
 }
 
 void conststn_plan_destroy(conststn_plan_t *plan) { delete plan; }
+
+conststn_status conststn_plan_profile(conststn_plan_t *plan, int capacity) {
+    clear_error();
+    if (!plan || capacity < 0 || capacity > 4096) { set_error("bad argument"); return CONSTSTN_EINVAL; }
+    for (hipEvent_t e : plan->prof_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : plan->prof_stop) (void)hipEventDestroy(e);
+    plan->prof_start.clear();
+    plan->prof_stop.clear();
+    plan->prof_count = 0;
+    for (int i = 0; i < capacity; ++i) {
+        hipEvent_t a, b;
+        CST_HIP(hipEventCreate(&a));
+        plan->prof_start.push_back(a);
+        CST_HIP(hipEventCreate(&b));
+        plan->prof_stop.push_back(b);
+    }
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan_kernel_times(conststn_plan_t *plan, float *ms, int max_n, int *n) {
+    clear_error();
+    if (!plan || !n || (max_n > 0 && !ms)) { set_error("null argument"); return CONSTSTN_EINVAL; }
+    const int64_t cap = int64_t(plan->prof_start.size());
+    const int64_t have = std::min<int64_t>(plan->prof_count, cap);
+    const int64_t first = plan->prof_count - have;
+    int written = 0;
+    for (int64_t i = first; i < plan->prof_count && written < max_n; ++i) {
+        const int slot = int(i % cap);
+        CST_HIP(hipEventSynchronize(plan->prof_stop[slot]));
+        CST_HIP(hipEventElapsedTime(&ms[written], plan->prof_start[slot], plan->prof_stop[slot]));
+        ++written;
+    }
+    *n = written;
+    plan->prof_count = 0;
+    return CONSTSTN_OK;
+}
 
 conststn_status conststn_execute(const conststn_plan_t *plan, const double *const *dense_factors,
                                  double *out, conststn_stream stream) {

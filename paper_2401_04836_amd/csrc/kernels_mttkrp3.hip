@@ -167,13 +167,16 @@ mttkrp3_fixup_kernel(MttkrpArgs a) {
 }
 
 template <int LPR>
-static conststn_status launch_lpr(const MttkrpArgs &a, bool vec, hipStream_t stream) {
+static conststn_status launch_lpr(const conststn_plan_s *plan, const MttkrpArgs &a, bool vec, hipStream_t stream) {
     const int64_t groups_per_block = 256 / LPR;
     const dim3 grid(unsigned(div_up(a.n_chunks, groups_per_block))), block(256);
-    if (vec)
-        mttkrp3_kernel<LPR, true><<<grid, block, 0, stream>>>(a);
-    else
-        mttkrp3_kernel<LPR, false><<<grid, block, 0, stream>>>(a);
+    {
+        ProfScope prof(plan, stream);
+        if (vec)
+            mttkrp3_kernel<LPR, true><<<grid, block, 0, stream>>>(a);
+        else
+            mttkrp3_kernel<LPR, false><<<grid, block, 0, stream>>>(a);
+    }
     CST_HIP(hipGetLastError());
     mttkrp3_fixup_kernel<LPR><<<dim3(unsigned(a.slices)), block, 0, stream>>>(a);
     CST_HIP(hipGetLastError());
@@ -216,13 +219,13 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
     while (2 * lpr < R) lpr *= 2;
     const bool vec = aligned && (R % 2 == 0);
     switch (lpr) {
-        case 1: return launch_lpr<1>(a, vec, stream);
-        case 2: return launch_lpr<2>(a, vec, stream);
-        case 4: return launch_lpr<4>(a, vec, stream);
-        case 8: return launch_lpr<8>(a, vec, stream);
-        case 16: return launch_lpr<16>(a, vec, stream);
-        case 32: return launch_lpr<32>(a, vec, stream);
-        default: return launch_lpr<64>(a, vec, stream);
+        case 1: return launch_lpr<1>(plan, a, vec, stream);
+        case 2: return launch_lpr<2>(plan, a, vec, stream);
+        case 4: return launch_lpr<4>(plan, a, vec, stream);
+        case 8: return launch_lpr<8>(plan, a, vec, stream);
+        case 16: return launch_lpr<16>(plan, a, vec, stream);
+        case 32: return launch_lpr<32>(plan, a, vec, stream);
+        default: return launch_lpr<64>(plan, a, vec, stream);
     }
 }
 

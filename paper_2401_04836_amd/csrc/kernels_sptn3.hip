@@ -100,7 +100,10 @@ conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *d
     if (!plan->compact && a.slices < plan->out_rows)
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.slices == 0) return CONSTSTN_OK;
-    sptn3_kernel<<<dim3(unsigned(a.slices)), dim3(256), lds_bytes, stream>>>(a);
+    {
+        ProfScope prof(plan, stream);
+        sptn3_kernel<<<dim3(unsigned(a.slices)), dim3(256), lds_bytes, stream>>>(a);
+    }
     CST_HIP(hipGetLastError());
     return CONSTSTN_OK;
 }

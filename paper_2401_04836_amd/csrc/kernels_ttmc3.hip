@@ -138,10 +138,13 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.n_items == 0) return CONSTSTN_OK;
     const dim3 grid(unsigned(div_up(a.n_items, 4))), block(256);
-    if (a.R2 <= 8) ttmc3_kernel<8><<<grid, block, 0, stream>>>(a);
-    else if (a.R2 <= 16) ttmc3_kernel<16><<<grid, block, 0, stream>>>(a);
-    else if (a.R2 <= 32) ttmc3_kernel<32><<<grid, block, 0, stream>>>(a);
-    else ttmc3_kernel<64><<<grid, block, 0, stream>>>(a);
+    {
+        ProfScope prof(plan, stream);
+        if (a.R2 <= 8) ttmc3_kernel<8><<<grid, block, 0, stream>>>(a);
+        else if (a.R2 <= 16) ttmc3_kernel<16><<<grid, block, 0, stream>>>(a);
+        else if (a.R2 <= 32) ttmc3_kernel<32><<<grid, block, 0, stream>>>(a);
+        else ttmc3_kernel<64><<<grid, block, 0, stream>>>(a);
+    }
     CST_HIP(hipGetLastError());
     return launch_ttmc_fixup(plan, out, stream);
 }

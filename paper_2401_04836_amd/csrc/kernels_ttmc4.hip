@@ -131,7 +131,10 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
     if (!plan->compact && X->nodes[0] < plan->out_rows)
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.n_items == 0) return CONSTSTN_OK;
-    ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
+    {
+        ProfScope prof(plan, stream);
+        ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
+    }
     CST_HIP(hipGetLastError());
     return launch_ttmc_fixup(plan, out, stream);
 }

@@ -51,6 +51,14 @@ struct conststn_plan_s {
     cst::DevBuf<double> partial;           // partial row blocks
     // three-tensor network
     cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1
+
+    // measurement hook: event pairs around the dominant kernel of each execute
+    mutable std::vector<hipEvent_t> prof_start, prof_stop;
+    mutable int64_t prof_count = 0;        // executes recorded since the last read
+    ~conststn_plan_s() {
+        for (hipEvent_t e : prof_start) (void)hipEventDestroy(e);
+        for (hipEvent_t e : prof_stop) (void)hipEventDestroy(e);
+    }
 };
 
 namespace cst {
@@ -80,6 +88,25 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
 
 // fill `n` doubles with zero on `stream` (a kernel, so that it is safe inside graph capture)
 conststn_status zero_fill(double *p, int64_t n, hipStream_t stream);
+
+// Records the plan's event pair around the dominant kernel when the measurement hook is on.
+struct ProfScope {
+    const conststn_plan_s *plan;
+    hipStream_t stream;
+    int slot = -1;
+    ProfScope(const conststn_plan_s *p, hipStream_t s) : plan(p), stream(s) {
+        if (!plan->prof_start.empty()) {
+            slot = int(plan->prof_count % int64_t(plan->prof_start.size()));
+            (void)hipEventRecord(plan->prof_start[slot], stream);
+        }
+    }
+    ~ProfScope() {
+        if (slot >= 0) {
+            (void)hipEventRecord(plan->prof_stop[slot], stream);
+            plan->prof_count++;
+        }
+    }
+};
 
 // tuning knob read from the environment (0 = use the built-in choice)
 int64_t env_int(const char *name, int64_t dflt);
