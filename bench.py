@@ -160,6 +160,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for the FETCH_SIZE / "
+                         "WRITE_SIZE counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures ONE GPU: the path has no multi-GPU part (run with --gpus 1)", file=sys.stderr)
@@ -171,6 +174,15 @@ def main():
     from paper_2401_04836_amd import schedules as S
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.calibrate:
+        src = torch.ones(1 << 27, dtype=torch.float64, device=dev)        # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                                     # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        log("calibration copy: 1 GiB read + 1 GiB written by one copy kernel")
+        del src, dst
 
     t0 = time.perf_counter()
     wl = workloads.make(args.config, device=dev, small=args.small)
@@ -241,7 +253,7 @@ def main():
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
     if not args.no_cpu:
-        cb = cpu_baseline(wl, 20_000_000)
+        cb = cpu_baseline(wl, 400_000_000)
         if cb is not None:
             result["cpu_baseline"] = cb
     print(json.dumps(result), flush=True)

@@ -132,6 +132,209 @@ mttkrp3_kernel(MttkrpArgs a) {
     emit(s, acc0, acc1);
 }
 
+// ---- rank-32 path ---------------------------------------------------------------------------
+//
+// Same chunking and the same partial-row protocol as the general kernel, specialised for
+// R = 32 (a factor row is 256 B = 16 lanes x 16 B) and restructured around what limits the
+// general kernel, the rate of vector-memory instructions per compute unit:
+//   * the leaf stream is read 16 entries at a time, one entry per lane of the 16-lane group,
+//     and handed round with DPP row broadcasts instead of one broadcast load per leaf;
+//   * the stream is the plan's re-encoded copy: a leaf whose factor row is among the most
+//     referenced ("hot") rows carries an LDS slot, and the row comes from LDS, where the
+//     workgroup staged all hot rows once; power-law index distributions put most references
+//     there.  Other rows are fetched from L2/HBM as before;
+//   * end-of-fiber / end-of-slice marks travel in the stream, so the child-pointer arrays
+//     are not read at all;
+//   * workgroups are persistent and loop over chunks, so the staging cost is paid once.
+constexpr uint32_t kHotBit = 0x80000000u, kFiberEnd = 0x40000000u, kSliceEnd = 0x20000000u,
+                   kRowMask = 0x0fffffffu;
+
+struct MttkrpR32Args {
+    MttkrpArgs base;
+    const uint32_t *code;
+    const int32_t *hot_rows;
+    int n_hot;
+    int64_t fibers;
+};
+
+struct lds_pair { double x, y; };
+typedef __attribute__((address_space(3))) lds_pair lds_double2;
+
+template <int T>
+__device__ __forceinline__ uint32_t row_bcast(uint32_t x) {
+    return uint32_t(__builtin_amdgcn_update_dpp(0, int(x), 0x150 + T, 0xf, 0xf, false));
+}
+template <int T>
+__device__ __forceinline__ double row_bcast(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x150 + T, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x150 + T, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Exclusive count, inside each 16-lane row, of the lanes below this one whose flag is set.
+__device__ __forceinline__ int row_rank_of_flag(bool flag, int gl, int &row_total) {
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(flag);
+    const int shift = (threadIdx.x & 48);                 // first lane of this row inside the wave
+    const unsigned row = unsigned(m >> shift) & 0xffffu;
+    row_total = __popc(row);
+    return __popc(row & ((1u << gl) - 1u));
+}
+
+template <int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
+mttkrp3_r32_kernel(MttkrpR32Args aa) {
+    extern __shared__ double2 hot[];                       // n_hot rows x 16 double2
+    const MttkrpArgs &a = aa.base;
+    for (int e = threadIdx.x; e < aa.n_hot * 16; e += BLOCK)
+        hot[e] = reinterpret_cast<const double2 *>(a.C + int64_t(aa.hot_rows[e >> 4]) * 32)[e & 15];
+    __syncthreads();
+    const int gl = threadIdx.x & 15;
+    const lds_double2 *hot_lds = (const lds_double2 *)hot;
+    const double2 *Cv = reinterpret_cast<const double2 *>(a.C);
+    const double2 *Bv = reinterpret_cast<const double2 *>(a.B);
+    const int64_t groups = int64_t(gridDim.x) * (BLOCK / 16);
+    // every lane group of a wave runs the same number of rounds so that the wave-wide ballot
+    // and the row broadcasts below always execute with all rows present
+    const int64_t rounds = (a.n_chunks + groups - 1) / groups;
+    for (int64_t rnd = 0; rnd < rounds; ++rnd) {
+        const int64_t c = rnd * groups + int64_t(blockIdx.x) * (BLOCK / 16) + threadIdx.x / 16;
+        const bool live = c < a.n_chunks;
+        const int64_t n0 = live ? c * a.q : 0;
+        const int64_t n1 = live ? (n0 + a.q < a.nnz ? n0 + a.q : a.nnz) : 0;
+        int64_t f = live ? a.chunk_fiber[c] : 0;          // first fiber not yet closed
+        int32_t s = live ? a.chunk_slice[c] : 0;
+        const int32_t s_first = s;
+        double t0 = 0.0, t1 = 0.0, acc0 = 0.0, acc1 = 0.0;
+        bool open_fiber = false, open_slice = false;
+
+        auto emit = [&]() {
+            const int64_t lo = a.slice_leaf[s], hi = a.slice_leaf[s + 1];
+            double2 *dst;
+            if (lo >= n0 && hi <= n1) {
+                const int64_t row = a.compact ? int64_t(s) : int64_t(a.idx0[s]);
+                dst = reinterpret_cast<double2 *>(a.out + row * 32);
+            } else {
+                dst = reinterpret_cast<double2 *>(a.partial + (2 * c + (s == s_first ? 0 : 1)) * 32);
+            }
+            dst[gl] = make_double2(acc0, acc1);
+            acc0 = 0.0;
+            acc1 = 0.0;
+            open_slice = false;
+        };
+        // the LDS read goes through an explicitly LDS-qualified pointer: with two generic
+        // pointers the compiler merges both arms into one flat load, which sends LDS reads
+        // down the vector-memory path
+        auto fetch = [&](uint32_t cd) -> double2 {
+            const uint32_t row = cd & kRowMask;
+            double2 r;
+            if (cd & kHotBit) {
+                const lds_double2 *src = hot_lds + (row * 16 + gl);
+                r = make_double2(src->x, src->y);
+            } else {
+                r = Cv[int64_t(row) * 16 + gl];
+            }
+            return r;
+        };
+        // B row of the fiber that ends at this leaf (no load when the leaf ends no fiber)
+        auto fetch_b = [&](uint32_t cd, int32_t j) -> double2 {
+            double2 r = make_double2(0.0, 0.0);
+            if (cd & kFiberEnd) r = Bv[int64_t(j) * 16 + gl];
+            return r;
+        };
+        auto consume = [&](uint32_t cd, double v, double2 cv, double2 bv) {
+            t0 = fma(v, cv.x, t0);
+            t1 = fma(v, cv.y, t1);
+            open_fiber = true;
+            open_slice = true;
+            if (cd & kFiberEnd) {
+                acc0 = fma(bv.x, t0, acc0);
+                acc1 = fma(bv.y, t1, acc1);
+                t0 = 0.0;
+                t1 = 0.0;
+                open_fiber = false;
+                if (cd & kSliceEnd) { emit(); ++s; }
+            }
+        };
+
+        // software pipeline over blocks of 16 leaves: the leaf entries of block b+1 and the
+        // level-1 indices (j) of the fibers ending in block b are in flight while block b-1..b
+        // are consumed, so no step waits on a dependent load
+        const int64_t nblocks = (n1 - n0 + 15) / 16;
+        uint32_t code_cur = 0, code_nxt = 0;
+        double val_cur = 0.0, val_nxt = 0.0;
+        if (nblocks > 0 && n0 + gl < n1) { code_cur = aa.code[n0 + gl]; val_cur = a.vals[n0 + gl]; }
+        for (int64_t b = 0; b < nblocks; ++b) {
+            const int64_t base = n0 + b * 16;
+            // fibers ending in this block: lane t learns which fiber its leaf closes
+            int ends = 0;
+            const bool is_end = (code_cur & kFiberEnd) != 0;
+            const int rank = row_rank_of_flag(is_end, gl, ends);
+            int32_t myj = 0;
+            if (is_end) myj = a.idx1[f + rank];
+            // leaf entries of the next block
+            if (b + 1 < nblocks && base + 16 + gl < n1) {
+                code_nxt = aa.code[base + 16 + gl];
+                val_nxt = a.vals[base + 16 + gl];
+            } else {
+                code_nxt = 0;
+                val_nxt = 0.0;
+            }
+            f += ends;
+            if (base + 16 <= n1) {
+#define CST_HALF(T0)                                                                          \
+                {                                                                             \
+                    const uint32_t c0 = row_bcast<T0 + 0>(code_cur), c1 = row_bcast<T0 + 1>(code_cur), \
+                                   c2 = row_bcast<T0 + 2>(code_cur), c3 = row_bcast<T0 + 3>(code_cur), \
+                                   c4 = row_bcast<T0 + 4>(code_cur), c5 = row_bcast<T0 + 5>(code_cur), \
+                                   c6 = row_bcast<T0 + 6>(code_cur), c7 = row_bcast<T0 + 7>(code_cur); \
+                    const double2 r0 = fetch(c0), r1 = fetch(c1), r2 = fetch(c2), r3 = fetch(c3), \
+                                  r4 = fetch(c4), r5 = fetch(c5), r6 = fetch(c6), r7 = fetch(c7); \
+                    const double2 b0 = fetch_b(c0, int32_t(row_bcast<T0 + 0>(uint32_t(myj)))), \
+                                  b1 = fetch_b(c1, int32_t(row_bcast<T0 + 1>(uint32_t(myj)))), \
+                                  b2 = fetch_b(c2, int32_t(row_bcast<T0 + 2>(uint32_t(myj)))), \
+                                  b3 = fetch_b(c3, int32_t(row_bcast<T0 + 3>(uint32_t(myj)))), \
+                                  b4 = fetch_b(c4, int32_t(row_bcast<T0 + 4>(uint32_t(myj)))), \
+                                  b5 = fetch_b(c5, int32_t(row_bcast<T0 + 5>(uint32_t(myj)))), \
+                                  b6 = fetch_b(c6, int32_t(row_bcast<T0 + 6>(uint32_t(myj)))), \
+                                  b7 = fetch_b(c7, int32_t(row_bcast<T0 + 7>(uint32_t(myj)))); \
+                    consume(c0, row_bcast<T0 + 0>(val_cur), r0, b0);                          \
+                    consume(c1, row_bcast<T0 + 1>(val_cur), r1, b1);                          \
+                    consume(c2, row_bcast<T0 + 2>(val_cur), r2, b2);                          \
+                    consume(c3, row_bcast<T0 + 3>(val_cur), r3, b3);                          \
+                    consume(c4, row_bcast<T0 + 4>(val_cur), r4, b4);                          \
+                    consume(c5, row_bcast<T0 + 5>(val_cur), r5, b5);                          \
+                    consume(c6, row_bcast<T0 + 6>(val_cur), r6, b6);                          \
+                    consume(c7, row_bcast<T0 + 7>(val_cur), r7, b7);                          \
+                }
+                CST_HALF(0)
+                CST_HALF(8)
+#undef CST_HALF
+            } else {
+                // ragged tail of the last chunk: same steps, one leaf at a time, bounds-checked
+                const int left = int(n1 - base);
+#define CST_ONE(T)                                                                            \
+                {                                                                             \
+                    const uint32_t cd = row_bcast<T>(code_cur);                               \
+                    const double v = row_bcast<T>(val_cur);                                   \
+                    const int32_t jj = int32_t(row_bcast<T>(uint32_t(myj)));                  \
+                    if (T < left) consume(cd, v, fetch(cd), fetch_b(cd, jj));                 \
+                }
+                CST_ONE(0) CST_ONE(1) CST_ONE(2) CST_ONE(3) CST_ONE(4) CST_ONE(5) CST_ONE(6) CST_ONE(7)
+                CST_ONE(8) CST_ONE(9) CST_ONE(10) CST_ONE(11) CST_ONE(12) CST_ONE(13) CST_ONE(14) CST_ONE(15)
+#undef CST_ONE
+            }
+            code_cur = code_nxt;
+            val_cur = val_nxt;
+        }
+        if (open_fiber) {                                  // the chunk ends inside fiber f
+            const double2 bv = Bv[int64_t(a.idx1[f]) * 16 + gl];
+            acc0 = fma(bv.x, t0, acc0);
+            acc1 = fma(bv.y, t1, acc1);
+        }
+        if (open_slice) emit();
+    }
+}
+
 // Rows of slices shared by several chunks: add the partial rows in chunk order.
 // One block per slice; G lane groups stride over the chunks, then a fixed-order LDS reduction.
 template <int LPR>
@@ -213,6 +416,39 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
     const bool aligned = (reinterpret_cast<uintptr_t>(a.B) % 16 == 0) && (reinterpret_cast<uintptr_t>(a.C) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(out) % 16 == 0);
     if (R > 128) { set_error("MTTKRP rank %d above 128 is not implemented", R); return CONSTSTN_EUNSUPPORTED; }
+    if (R == 32 && aligned && plan->n_hot > 0 && plan->leaf_code.p) {
+        MttkrpR32Args aa{};
+        aa.base = a;
+        aa.code = plan->leaf_code.p;
+        aa.hot_rows = plan->hot_rows.p;
+        aa.n_hot = plan->n_hot;
+        aa.fibers = X->nodes[1];
+        const size_t lds = size_t(plan->n_hot) * 256;
+        int dev = 0, cus = 256;
+        CST_HIP(hipGetDevice(&dev));
+        CST_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        // as many resident workgroups per compute unit as the LDS footprint allows
+        const int64_t big = env_int("CONSTSTN_MTTKRP_BLOCK", lds > 80 * 1024 ? 1024 : 512);
+        const int per_cu = std::max<int>(1, std::min<int>(int(160 * 1024 / std::max<size_t>(lds, 1)), big == 1024 ? 2 : 4));
+        const int64_t chunks_per_wg = big / 16;
+        const int64_t wgs = std::min<int64_t>(div_up(a.n_chunks, chunks_per_wg), int64_t(cus) * per_cu);
+        {
+            ProfScope prof(plan, stream);
+            if (big == 1024) {
+                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<1024>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+                mttkrp3_r32_kernel<1024><<<dim3(unsigned(wgs)), dim3(1024), lds, stream>>>(aa);
+            } else {
+                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+                mttkrp3_r32_kernel<512><<<dim3(unsigned(wgs)), dim3(512), lds, stream>>>(aa);
+            }
+        }
+        CST_HIP(hipGetLastError());
+        mttkrp3_fixup_kernel<16><<<dim3(unsigned(a.slices)), dim3(256), 0, stream>>>(a);
+        CST_HIP(hipGetLastError());
+        return CONSTSTN_OK;
+    }
     // smallest power-of-two lane group covering ceil(R/2) lanes; 16-byte accesses when every
     // lane of the group holds two valid, aligned entries
     int lpr = 1;

@@ -88,6 +88,98 @@ __global__ void mttkrp_chunks_kernel(int64_t n_chunks, int64_t q, int64_t slices
     chunk_slice[c] = int32_t(s);
 }
 
+// ---- MTTKRP rank-32 path: hot-row selection and the re-encoded leaf stream ------------------
+
+__global__ void leaf_histogram_kernel(int64_t nnz, const int32_t *__restrict__ leaf, unsigned *counts) {
+    int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (; n < nnz; n += stride) atomicAdd(&counts[leaf[n]], 1u);
+}
+
+__global__ void iota_i32_kernel(int32_t *p, int64_t n) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = int32_t(i);
+}
+
+__global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void hot_slots_kernel(int n_hot, const int32_t *__restrict__ rows_by_count,
+                                 const unsigned *__restrict__ counts_sorted, int32_t *slot_of_row,
+                                 int32_t *hot_rows) {
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= n_hot) return;
+    hot_rows[h] = rows_by_count[h];
+    slot_of_row[rows_by_count[h]] = h;
+    (void)counts_sorted;
+}
+
+__global__ void encode_leaves_kernel(int64_t nnz, const int32_t *__restrict__ leaf,
+                                     const int32_t *__restrict__ slot_of_row, uint32_t *code) {
+    int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (; n < nnz; n += stride) {
+        const int32_t k = leaf[n];
+        const int32_t sl = slot_of_row[k];
+        code[n] = sl >= 0 ? (0x80000000u | uint32_t(sl)) : uint32_t(k);
+    }
+}
+
+// mark the last leaf of every fiber (bit 30) and of every slice (bit 29)
+__global__ void mark_ends_kernel(int64_t nodes, const int64_t *__restrict__ leaf_end, uint32_t bit,
+                                 uint32_t *code) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p < nodes) atomicOr(&code[leaf_end[p + 1] - 1], bit);
+}
+
+static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t nnz = X->nnz;
+    const int64_t dim = X->dims[X->mode_order[2]];
+    plan->n_hot = 0;
+    if (plan->rank_of_level[1] != 32 || dim >= (int64_t(1) << 28) || nnz == 0) return CONSTSTN_OK;
+    int64_t want = env_int("CONSTSTN_MTTKRP_HOT", 256);
+    if (want > dim) want = dim;
+    want = std::min<int64_t>(want, 608);                 // 608 rows x 256 B = 152 KB of LDS at most
+    DevBuf<unsigned> counts, counts_sorted;
+    DevBuf<int32_t> rows, rows_sorted, slot_of_row;
+    CST_TRY(counts.alloc(dim));
+    CST_TRY(counts_sorted.alloc(dim));
+    CST_TRY(rows.alloc(dim));
+    CST_TRY(rows_sorted.alloc(dim));
+    CST_TRY(slot_of_row.alloc(dim));
+    CST_HIP(hipMemset(counts.p, 0, size_t(dim) * sizeof(unsigned)));
+    const dim3 block(256);
+    leaf_histogram_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 8192))), block>>>(nnz, X->idx[2].p, counts.p);
+    CST_HIP(hipGetLastError());
+    iota_i32_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(rows.p, dim);
+    fill_i32_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(slot_of_row.p, dim, -1);
+    CST_HIP(hipGetLastError());
+    size_t bytes = 0;
+    CST_HIP(rocprim::radix_sort_pairs_desc(nullptr, bytes, counts.p, counts_sorted.p, rows.p, rows_sorted.p, size_t(dim)));
+    DevBuf<char> temp;
+    CST_TRY(temp.alloc(bytes));
+    CST_HIP(rocprim::radix_sort_pairs_desc(temp.p, bytes, counts.p, counts_sorted.p, rows.p, rows_sorted.p, size_t(dim)));
+    CST_TRY(plan->hot_rows.alloc(size_t(want)));
+    hot_slots_kernel<<<dim3(unsigned(div_up(want, 256))), block>>>(int(want), rows_sorted.p, counts_sorted.p,
+                                                                  slot_of_row.p, plan->hot_rows.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(plan->leaf_code.alloc(size_t(nnz)));
+    encode_leaves_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 16384))), block>>>(
+        nnz, X->idx[2].p, slot_of_row.p, plan->leaf_code.p);
+    CST_HIP(hipGetLastError());
+    mark_ends_kernel<<<dim3(unsigned(div_up(X->nodes[1], 256))), block>>>(X->nodes[1], X->ptr[1].p, 0x40000000u,
+                                                                        plan->leaf_code.p);
+    mark_ends_kernel<<<dim3(unsigned(div_up(X->nodes[0], 256))), block>>>(X->nodes[0], plan->slice_leaf.p,
+                                                                        0x20000000u, plan->leaf_code.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipDeviceSynchronize());
+    plan->n_hot = int(want);
+    return CONSTSTN_OK;
+}
+
 conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t nnz = X->nnz;
@@ -97,9 +189,10 @@ conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
     // two partial rows per chunk stay a small fraction of the traffic
     int64_t q = env_int("CONSTSTN_MTTKRP_CHUNK", 0);
     if (q <= 0) {
-        q = nnz / 65536;
-        q = std::max<int64_t>(64, std::min<int64_t>(q, 1024));
+        q = nnz / 262144;
+        q = std::max<int64_t>(64, std::min<int64_t>(q, 512));
     }
+    q = div_up(q, 16) * 16;                      // the rank-32 kernel reads leaves 16 at a time
     plan->chunk_q = q;
     plan->n_chunks = div_up(nnz, q);
     CST_TRY(plan->chunk_fiber.alloc(size_t(plan->n_chunks)));
@@ -112,7 +205,7 @@ conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
         CST_HIP(hipGetLastError());
     }
     CST_HIP(hipDeviceSynchronize());
-    return CONSTSTN_OK;
+    return build_mttkrp3_r32_encoding(plan);
 }
 
 // ---- TTMc: bounded items inside slices ----------------------------------------------------

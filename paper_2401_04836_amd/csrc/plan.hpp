@@ -42,6 +42,12 @@ struct conststn_plan_s {
     int64_t chunk_q = 0, n_chunks = 0;
     cst::DevBuf<int64_t> chunk_fiber;      // level-1 fiber containing the chunk's first leaf
     cst::DevBuf<int32_t> chunk_slice;      // root slice containing that fiber
+    // MTTKRP rank-32 path: private re-encoding of the leaf index stream.  Each entry holds the
+    // leaf index, or -- for the most frequently referenced ("hot") factor rows, which the kernel
+    // keeps in LDS -- the LDS slot, plus end-of-fiber / end-of-slice marks.
+    cst::DevBuf<uint32_t> leaf_code;
+    cst::DevBuf<int32_t> hot_rows;         // [n_hot] leaf index held by each LDS slot
+    int n_hot = 0;
     // TTMc: items inside slices
     int64_t n_items = 0, n_partials = 0, n_split = 0;
     cst::DevBuf<cst::SliceItem> items;
