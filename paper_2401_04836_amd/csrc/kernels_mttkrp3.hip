@@ -221,19 +221,23 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             acc1 = 0.0;
             open_slice = false;
         };
-        // the LDS read goes through an explicitly LDS-qualified pointer: with two generic
-        // pointers the compiler merges both arms into one flat load, which sends LDS reads
-        // down the vector-memory path
-        auto fetch = [&](uint32_t cd) -> double2 {
-            const uint32_t row = cd & kRowMask;
-            double2 r;
-            if (cd & kHotBit) {
-                const lds_double2 *src = hot_lds + (row * 16 + gl);
-                r = make_double2(src->x, src->y);
-            } else {
-                r = Cv[int64_t(row) * 16 + gl];
-            }
+        // The factor row of a leaf comes from LDS (hot) or from global memory (cold).  The two
+        // loads target different registers and the LDS one is unconditional (slot 0 for cold
+        // leaves): a shared destination would make the global load wait for the LDS read, and
+        // the LDS read goes through an explicitly LDS-qualified pointer so that the compiler
+        // cannot merge the two into one flat load.
+        auto fetch_hot = [&](uint32_t cd) -> double2 {
+            const uint32_t slot = (cd & kHotBit) ? (cd & kRowMask) : 0u;
+            const lds_double2 *src = hot_lds + (slot * 16 + gl);
+            return make_double2(src->x, src->y);
+        };
+        auto fetch_cold = [&](uint32_t cd) -> double2 {
+            double2 r = make_double2(0.0, 0.0);
+            if (!(cd & kHotBit)) r = Cv[int64_t(cd & kRowMask) * 16 + gl];
             return r;
+        };
+        auto pick = [&](uint32_t cd, double2 h, double2 g) -> double2 {
+            return (cd & kHotBit) ? h : g;
         };
         // B row of the fiber that ends at this leaf (no load when the leaf ends no fiber)
         auto fetch_b = [&](uint32_t cd, int32_t j) -> double2 {
@@ -256,59 +260,58 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             }
         };
 
-        // software pipeline over blocks of 16 leaves: the leaf entries of block b+1 and the
-        // level-1 indices (j) of the fibers ending in block b are in flight while block b-1..b
-        // are consumed, so no step waits on a dependent load
+        // Software pipeline over blocks of 16 leaves.  While block b is consumed, the leaf
+        // entries of block b+2 and the level-1 indices (j) of the fibers ending in block b+1
+        // are already in flight, and every load a block needs is issued before the first wait,
+        // so no step waits on a dependent load.
         const int64_t nblocks = (n1 - n0 + 15) / 16;
-        uint32_t code_cur = 0, code_nxt = 0;
-        double val_cur = 0.0, val_nxt = 0.0;
-        if (nblocks > 0 && n0 + gl < n1) { code_cur = aa.code[n0 + gl]; val_cur = a.vals[n0 + gl]; }
+        auto load_block = [&](int64_t blk, uint32_t &cd, double &vl) {
+            cd = 0;
+            vl = 0.0;
+            const int64_t pos = n0 + blk * 16 + gl;
+            if (blk < nblocks && pos < n1) { cd = aa.code[pos]; vl = a.vals[pos]; }
+        };
+        // j of the fiber closed by this lane's leaf, given the first fiber open at block start
+        auto load_j = [&](uint32_t cd, int64_t fbase, int &ends) -> int32_t {
+            const bool is_end = (cd & kFiberEnd) != 0;
+            const int rank = row_rank_of_flag(is_end, gl, ends);
+            int32_t j = 0;
+            if (is_end) j = a.idx1[fbase + rank];
+            return j;
+        };
+        uint32_t code_cur, code_nxt, code_n2 = 0;
+        double val_cur, val_nxt, val_n2 = 0.0;
+        load_block(0, code_cur, val_cur);
+        load_block(1, code_nxt, val_nxt);
+        int ends_cur = 0, ends_nxt = 0;
+        int32_t j_cur = load_j(code_cur, f, ends_cur), j_nxt = 0;
         for (int64_t b = 0; b < nblocks; ++b) {
             const int64_t base = n0 + b * 16;
-            // fibers ending in this block: lane t learns which fiber its leaf closes
-            int ends = 0;
-            const bool is_end = (code_cur & kFiberEnd) != 0;
-            const int rank = row_rank_of_flag(is_end, gl, ends);
-            int32_t myj = 0;
-            if (is_end) myj = a.idx1[f + rank];
-            // leaf entries of the next block
-            if (b + 1 < nblocks && base + 16 + gl < n1) {
-                code_nxt = aa.code[base + 16 + gl];
-                val_nxt = a.vals[base + 16 + gl];
-            } else {
-                code_nxt = 0;
-                val_nxt = 0.0;
-            }
-            f += ends;
+            load_block(b + 2, code_n2, val_n2);
+            j_nxt = load_j(code_nxt, f + ends_cur, ends_nxt);
             if (base + 16 <= n1) {
-#define CST_HALF(T0)                                                                          \
+#define CST_GROUP(T0)                                                                         \
                 {                                                                             \
                     const uint32_t c0 = row_bcast<T0 + 0>(code_cur), c1 = row_bcast<T0 + 1>(code_cur), \
-                                   c2 = row_bcast<T0 + 2>(code_cur), c3 = row_bcast<T0 + 3>(code_cur), \
-                                   c4 = row_bcast<T0 + 4>(code_cur), c5 = row_bcast<T0 + 5>(code_cur), \
-                                   c6 = row_bcast<T0 + 6>(code_cur), c7 = row_bcast<T0 + 7>(code_cur); \
-                    const double2 r0 = fetch(c0), r1 = fetch(c1), r2 = fetch(c2), r3 = fetch(c3), \
-                                  r4 = fetch(c4), r5 = fetch(c5), r6 = fetch(c6), r7 = fetch(c7); \
-                    const double2 b0 = fetch_b(c0, int32_t(row_bcast<T0 + 0>(uint32_t(myj)))), \
-                                  b1 = fetch_b(c1, int32_t(row_bcast<T0 + 1>(uint32_t(myj)))), \
-                                  b2 = fetch_b(c2, int32_t(row_bcast<T0 + 2>(uint32_t(myj)))), \
-                                  b3 = fetch_b(c3, int32_t(row_bcast<T0 + 3>(uint32_t(myj)))), \
-                                  b4 = fetch_b(c4, int32_t(row_bcast<T0 + 4>(uint32_t(myj)))), \
-                                  b5 = fetch_b(c5, int32_t(row_bcast<T0 + 5>(uint32_t(myj)))), \
-                                  b6 = fetch_b(c6, int32_t(row_bcast<T0 + 6>(uint32_t(myj)))), \
-                                  b7 = fetch_b(c7, int32_t(row_bcast<T0 + 7>(uint32_t(myj)))); \
-                    consume(c0, row_bcast<T0 + 0>(val_cur), r0, b0);                          \
-                    consume(c1, row_bcast<T0 + 1>(val_cur), r1, b1);                          \
-                    consume(c2, row_bcast<T0 + 2>(val_cur), r2, b2);                          \
-                    consume(c3, row_bcast<T0 + 3>(val_cur), r3, b3);                          \
-                    consume(c4, row_bcast<T0 + 4>(val_cur), r4, b4);                          \
-                    consume(c5, row_bcast<T0 + 5>(val_cur), r5, b5);                          \
-                    consume(c6, row_bcast<T0 + 6>(val_cur), r6, b6);                          \
-                    consume(c7, row_bcast<T0 + 7>(val_cur), r7, b7);                          \
+                                   c2 = row_bcast<T0 + 2>(code_cur), c3 = row_bcast<T0 + 3>(code_cur); \
+                    const double2 h0 = fetch_hot(c0), h1 = fetch_hot(c1), h2 = fetch_hot(c2),  \
+                                  h3 = fetch_hot(c3);                                         \
+                    const double2 g0 = fetch_cold(c0), g1 = fetch_cold(c1), g2 = fetch_cold(c2), \
+                                  g3 = fetch_cold(c3);                                        \
+                    const double2 b0 = fetch_b(c0, int32_t(row_bcast<T0 + 0>(uint32_t(j_cur)))), \
+                                  b1 = fetch_b(c1, int32_t(row_bcast<T0 + 1>(uint32_t(j_cur)))), \
+                                  b2 = fetch_b(c2, int32_t(row_bcast<T0 + 2>(uint32_t(j_cur)))), \
+                                  b3 = fetch_b(c3, int32_t(row_bcast<T0 + 3>(uint32_t(j_cur)))); \
+                    consume(c0, row_bcast<T0 + 0>(val_cur), pick(c0, h0, g0), b0);            \
+                    consume(c1, row_bcast<T0 + 1>(val_cur), pick(c1, h1, g1), b1);            \
+                    consume(c2, row_bcast<T0 + 2>(val_cur), pick(c2, h2, g2), b2);            \
+                    consume(c3, row_bcast<T0 + 3>(val_cur), pick(c3, h3, g3), b3);            \
                 }
-                CST_HALF(0)
-                CST_HALF(8)
-#undef CST_HALF
+                CST_GROUP(0)
+                CST_GROUP(4)
+                CST_GROUP(8)
+                CST_GROUP(12)
+#undef CST_GROUP
             } else {
                 // ragged tail of the last chunk: same steps, one leaf at a time, bounds-checked
                 const int left = int(n1 - base);
@@ -316,15 +319,20 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
                 {                                                                             \
                     const uint32_t cd = row_bcast<T>(code_cur);                               \
                     const double v = row_bcast<T>(val_cur);                                   \
-                    const int32_t jj = int32_t(row_bcast<T>(uint32_t(myj)));                  \
-                    if (T < left) consume(cd, v, fetch(cd), fetch_b(cd, jj));                 \
+                    const int32_t jj = int32_t(row_bcast<T>(uint32_t(j_cur)));                \
+                    if (T < left) consume(cd, v, pick(cd, fetch_hot(cd), fetch_cold(cd)), fetch_b(cd, jj)); \
                 }
                 CST_ONE(0) CST_ONE(1) CST_ONE(2) CST_ONE(3) CST_ONE(4) CST_ONE(5) CST_ONE(6) CST_ONE(7)
                 CST_ONE(8) CST_ONE(9) CST_ONE(10) CST_ONE(11) CST_ONE(12) CST_ONE(13) CST_ONE(14) CST_ONE(15)
 #undef CST_ONE
             }
+            f += ends_cur;
             code_cur = code_nxt;
             val_cur = val_nxt;
+            code_nxt = code_n2;
+            val_nxt = val_n2;
+            j_cur = j_nxt;
+            ends_cur = ends_nxt;
         }
         if (open_fiber) {                                  // the chunk ends inside fiber f
             const double2 bv = Bv[int64_t(a.idx1[f]) * 16 + gl];
