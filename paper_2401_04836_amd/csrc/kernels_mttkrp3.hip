@@ -26,6 +26,9 @@ struct MttkrpArgs {
     const double *B, *C;
     double *out, *partial;
     int compact;
+    const int32_t *heavy_slices;
+    double *heavy_partial;
+    int n_heavy;
 };
 
 template <bool VEC>
@@ -205,7 +208,7 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
         int32_t s = live ? a.chunk_slice[c] : 0;
         const int32_t s_first = s;
         double t0 = 0.0, t1 = 0.0, acc0 = 0.0, acc1 = 0.0;
-        bool open_fiber = false, open_slice = false;
+        uint32_t last = kFiberEnd | kSliceEnd;            // marks of the last leaf consumed
 
         auto emit = [&]() {
             const int64_t lo = a.slice_leaf[s], hi = a.slice_leaf[s + 1];
@@ -219,7 +222,6 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             dst[gl] = make_double2(acc0, acc1);
             acc0 = 0.0;
             acc1 = 0.0;
-            open_slice = false;
         };
         // The factor row of a leaf comes from LDS (hot) or from global memory (cold).  The two
         // loads target different registers and the LDS one is unconditional (slot 0 for cold
@@ -233,7 +235,7 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
         };
         auto fetch_cold = [&](uint32_t cd) -> double2 {
             double2 r = make_double2(0.0, 0.0);
-            if (!(cd & kHotBit)) r = Cv[int64_t(cd & kRowMask) * 16 + gl];
+            if (!(cd & kHotBit)) r = Cv[(cd & kRowMask) * 16u + uint32_t(gl)];
             return r;
         };
         auto pick = [&](uint32_t cd, double2 h, double2 g) -> double2 {
@@ -242,20 +244,18 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
         // B row of the fiber that ends at this leaf (no load when the leaf ends no fiber)
         auto fetch_b = [&](uint32_t cd, int32_t j) -> double2 {
             double2 r = make_double2(0.0, 0.0);
-            if (cd & kFiberEnd) r = Bv[int64_t(j) * 16 + gl];
+            if (cd & kFiberEnd) r = Bv[uint32_t(j) * 16u + uint32_t(gl)];
             return r;
         };
         auto consume = [&](uint32_t cd, double v, double2 cv, double2 bv) {
             t0 = fma(v, cv.x, t0);
             t1 = fma(v, cv.y, t1);
-            open_fiber = true;
-            open_slice = true;
+            last = cd;
             if (cd & kFiberEnd) {
                 acc0 = fma(bv.x, t0, acc0);
                 acc1 = fma(bv.y, t1, acc1);
                 t0 = 0.0;
                 t1 = 0.0;
-                open_fiber = false;
                 if (cd & kSliceEnd) { emit(); ++s; }
             }
         };
@@ -334,12 +334,12 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             j_cur = j_nxt;
             ends_cur = ends_nxt;
         }
-        if (open_fiber) {                                  // the chunk ends inside fiber f
+        if (!(last & kFiberEnd)) {                         // the chunk ends inside fiber f
             const double2 bv = Bv[int64_t(a.idx1[f]) * 16 + gl];
             acc0 = fma(bv.x, t0, acc0);
             acc1 = fma(bv.y, t1, acc1);
         }
-        if (open_slice) emit();
+        if (!(last & kSliceEnd)) emit();
     }
 }
 
@@ -354,6 +354,7 @@ mttkrp3_fixup_kernel(MttkrpArgs a) {
     const int64_t lo = a.slice_leaf[s], hi = a.slice_leaf[s + 1];
     const int64_t ca = lo / a.q, cb = (hi - 1) / a.q;
     if (ca == cb) return;                           // stored directly by the main kernel
+    if (cb - ca >= kHeavySpan) return;              // left to the two-stage kernels below
     const int g = threadIdx.x / LPR, gl = threadIdx.x % LPR;
     const int r0 = 2 * gl, R = a.R;
     double x = 0.0, y = 0.0;
@@ -377,6 +378,67 @@ mttkrp3_fixup_kernel(MttkrpArgs a) {
     }
 }
 
+// Heavy slices (shared by at least kHeavySpan chunks): stage 1 reduces kHeavySegments equal
+// segments of the slice's chunk range in parallel, stage 2 adds the segment sums in order.
+template <int LPR>
+__global__ void __launch_bounds__(256)
+mttkrp3_fixup_heavy_kernel(MttkrpArgs a) {
+    constexpr int G = 256 / LPR;
+    __shared__ double red[256 * 2];
+    const int64_t s = a.heavy_slices[blockIdx.x];
+    const int seg = blockIdx.y;
+    const int64_t lo = a.slice_leaf[s], hi = a.slice_leaf[s + 1];
+    const int64_t ca = lo / a.q, cb = (hi - 1) / a.q;
+    const int64_t n = cb - ca + 1;
+    const int64_t c0 = ca + n * seg / kHeavySegments, c1 = ca + n * (seg + 1) / kHeavySegments;
+    const int g = threadIdx.x / LPR, gl = threadIdx.x % LPR;
+    const int r0 = 2 * gl, R = a.R;
+    double x = 0.0, y = 0.0;
+    for (int64_t c = c0 + g; c < c1; c += G) {
+        const int64_t slot = 2 * c + ((c == ca && lo != ca * a.q) ? 1 : 0);
+        const double *row = a.partial + slot * R;
+        if (r0 < R) x += row[r0];
+        if (r0 + 1 < R) y += row[r0 + 1];
+    }
+    red[threadIdx.x * 2] = x;
+    red[threadIdx.x * 2 + 1] = y;
+    __syncthreads();
+    if (g == 0) {
+        for (int gg = 1; gg < G; ++gg) {
+            x += red[(gg * LPR + gl) * 2];
+            y += red[(gg * LPR + gl) * 2 + 1];
+        }
+        double *dst = a.heavy_partial + (int64_t(blockIdx.x) * kHeavySegments + seg) * R;
+        if (r0 < R) dst[r0] = x;
+        if (r0 + 1 < R) dst[r0 + 1] = y;
+    }
+}
+
+__global__ void __launch_bounds__(128)
+mttkrp3_fixup_final_kernel(MttkrpArgs a) {
+    const int64_t s = a.heavy_slices[blockIdx.x];
+    const int r = threadIdx.x;
+    if (r >= a.R) return;
+    double x = 0.0;
+    for (int seg = 0; seg < kHeavySegments; ++seg)
+        x += a.heavy_partial[(int64_t(blockIdx.x) * kHeavySegments + seg) * a.R + r];
+    const int64_t row = a.compact ? s : int64_t(a.idx0[s]);
+    a.out[row * a.R + r] = x;
+}
+
+template <int LPR>
+static conststn_status launch_fixup(const MttkrpArgs &a, hipStream_t stream) {
+    mttkrp3_fixup_kernel<LPR><<<dim3(unsigned(a.slices)), dim3(256), 0, stream>>>(a);
+    CST_HIP(hipGetLastError());
+    if (a.n_heavy > 0) {
+        mttkrp3_fixup_heavy_kernel<LPR><<<dim3(unsigned(a.n_heavy), kHeavySegments), dim3(256), 0, stream>>>(a);
+        CST_HIP(hipGetLastError());
+        mttkrp3_fixup_final_kernel<<<dim3(unsigned(a.n_heavy)), dim3(128), 0, stream>>>(a);
+        CST_HIP(hipGetLastError());
+    }
+    return CONSTSTN_OK;
+}
+
 template <int LPR>
 static conststn_status launch_lpr(const conststn_plan_s *plan, const MttkrpArgs &a, bool vec, hipStream_t stream) {
     const int64_t groups_per_block = 256 / LPR;
@@ -389,9 +451,7 @@ static conststn_status launch_lpr(const conststn_plan_s *plan, const MttkrpArgs 
             mttkrp3_kernel<LPR, false><<<grid, block, 0, stream>>>(a);
     }
     CST_HIP(hipGetLastError());
-    mttkrp3_fixup_kernel<LPR><<<dim3(unsigned(a.slices)), block, 0, stream>>>(a);
-    CST_HIP(hipGetLastError());
-    return CONSTSTN_OK;
+    return launch_fixup<LPR>(a, stream);
 }
 
 conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const *dense, double *out,
@@ -417,6 +477,9 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
     a.out = out;
     a.partial = plan->partial.p;
     a.compact = plan->compact ? 1 : 0;
+    a.heavy_slices = plan->heavy_slices.p;
+    a.heavy_partial = plan->heavy_partial.p;
+    a.n_heavy = plan->n_heavy;
     if (!plan->compact && a.slices < plan->out_rows)        // rows of empty slices are zero
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.nnz == 0) return CONSTSTN_OK;
@@ -453,9 +516,7 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
             }
         }
         CST_HIP(hipGetLastError());
-        mttkrp3_fixup_kernel<16><<<dim3(unsigned(a.slices)), dim3(256), 0, stream>>>(a);
-        CST_HIP(hipGetLastError());
-        return CONSTSTN_OK;
+        return launch_fixup<16>(a, stream);
     }
     // smallest power-of-two lane group covering ceil(R/2) lanes; 16-byte accesses when every
     // lane of the group holds two valid, aligned entries

@@ -88,6 +88,14 @@ __global__ void mttkrp_chunks_kernel(int64_t n_chunks, int64_t q, int64_t slices
     chunk_slice[c] = int32_t(s);
 }
 
+__global__ void heavy_slices_kernel(int64_t slices, const int64_t *__restrict__ slice_leaf, int64_t q,
+                                    int span, int32_t *list, int *count) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s >= slices) return;
+    const int64_t ca = slice_leaf[s] / q, cb = (slice_leaf[s + 1] - 1) / q;
+    if (cb - ca >= span) list[atomicAdd(count, 1)] = int32_t(s);
+}
+
 // ---- MTTKRP rank-32 path: hot-row selection and the re-encoded leaf stream ------------------
 
 __global__ void leaf_histogram_kernel(int64_t nnz, const int32_t *__restrict__ leaf, unsigned *counts) {
@@ -139,7 +147,9 @@ static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
     const int64_t nnz = X->nnz;
     const int64_t dim = X->dims[X->mode_order[2]];
     plan->n_hot = 0;
-    if (plan->rank_of_level[1] != 32 || dim >= (int64_t(1) << 28) || nnz == 0) return CONSTSTN_OK;
+    if (plan->rank_of_level[1] != 32 || dim >= (int64_t(1) << 28) || nnz == 0 ||
+        X->dims[X->mode_order[1]] >= (int64_t(1) << 28))
+        return CONSTSTN_OK;                               // the kernel indexes factor rows with 32 bits
     int64_t want = env_int("CONSTSTN_MTTKRP_HOT", 256);
     if (want > dim) want = dim;
     want = std::min<int64_t>(want, 608);                 // 608 rows x 256 B = 152 KB of LDS at most
@@ -204,6 +214,20 @@ conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
             plan->chunk_fiber.p, plan->chunk_slice.p);
         CST_HIP(hipGetLastError());
     }
+    // slices shared by many chunks: listed for the two-stage fix-up (at most nnz / (span * q))
+    plan->n_heavy = 0;
+    const int64_t max_heavy = nnz / (int64_t(kHeavySpan) * q) + 1;
+    CST_TRY(plan->heavy_slices.alloc(size_t(max_heavy)));
+    DevBuf<int> hcount;
+    CST_TRY(hcount.alloc(1));
+    CST_HIP(hipMemset(hcount.p, 0, sizeof(int)));
+    if (X->nodes[0] > 0) {
+        heavy_slices_kernel<<<dim3(unsigned(div_up(X->nodes[0], 256))), dim3(256)>>>(
+            X->nodes[0], plan->slice_leaf.p, q, kHeavySpan, plan->heavy_slices.p, hcount.p);
+        CST_HIP(hipGetLastError());
+    }
+    CST_HIP(hipMemcpy(&plan->n_heavy, hcount.p, sizeof(int), hipMemcpyDeviceToHost));
+    CST_TRY(plan->heavy_partial.alloc(size_t(plan->n_heavy) * kHeavySegments * size_t(R)));
     CST_HIP(hipDeviceSynchronize());
     return build_mttkrp3_r32_encoding(plan);
 }

@@ -7,6 +7,9 @@
 
 namespace cst {
 
+constexpr int kHeavySpan = 64;        // a slice spanning at least this many chunks is "heavy"
+constexpr int kHeavySegments = 32;    // its chunk range is reduced in this many parallel segments
+
 enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
 
 // One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1
@@ -48,6 +51,10 @@ struct conststn_plan_s {
     cst::DevBuf<uint32_t> leaf_code;
     cst::DevBuf<int32_t> hot_rows;         // [n_hot] leaf index held by each LDS slot
     int n_hot = 0;
+    // slices shared by very many chunks get a two-stage fix-up
+    cst::DevBuf<int32_t> heavy_slices;
+    cst::DevBuf<double> heavy_partial;     // [n_heavy x kHeavySegments x R]
+    int n_heavy = 0;
     // TTMc: items inside slices
     int64_t n_items = 0, n_partials = 0, n_split = 0;
     cst::DevBuf<cst::SliceItem> items;
