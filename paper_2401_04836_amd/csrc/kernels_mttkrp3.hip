@@ -165,12 +165,12 @@ typedef __attribute__((address_space(3))) lds_pair lds_double2;
 
 template <int T>
 __device__ __forceinline__ uint32_t row_bcast(uint32_t x) {
-    return uint32_t(__builtin_amdgcn_update_dpp(0, int(x), 0x150 + T, 0xf, 0xf, false));
+    return uint32_t(__builtin_amdgcn_mov_dpp(int(x), 0x150 + T, 0xf, 0xf, false));
 }
 template <int T>
 __device__ __forceinline__ double row_bcast(double x) {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x150 + T, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x150 + T, 0xf, 0xf, false);
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), 0x150 + T, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), 0x150 + T, 0xf, 0xf, false);
     return __hiloint2double(hi, lo);
 }
 
@@ -234,7 +234,7 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             return make_double2(src->x, src->y);
         };
         auto fetch_cold = [&](uint32_t cd) -> double2 {
-            double2 r = make_double2(0.0, 0.0);
+            double2 r;                                  // only read where the condition holds
             if (!(cd & kHotBit)) r = Cv[(cd & kRowMask) * 16u + uint32_t(gl)];
             return r;
         };
@@ -243,7 +243,7 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
         };
         // B row of the fiber that ends at this leaf (no load when the leaf ends no fiber)
         auto fetch_b = [&](uint32_t cd, int32_t j) -> double2 {
-            double2 r = make_double2(0.0, 0.0);
+            double2 r;                                  // only read where the condition holds
             if (cd & kFiberEnd) r = Bv[uint32_t(j) * 16u + uint32_t(gl)];
             return r;
         };
