@@ -1,0 +1,213 @@
+"""Full-size parity (configurations 2-5 at the sizes the benchmark times): CSF arrays
+bit-exact against an independent sort-based build, and sampled outputs against the CPU
+oracle.  The oracle cannot finish the heaviest slices whole, so those are checked element
+by element: restricting the factors to single columns makes the oracle compute exactly the
+chosen output elements."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2401_04836_amd as cst
+import workloads as w
+from paper_2401_04836_amd import schedules as S
+from helpers import TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def reference_levels(coords, vals, dims, mode_order):
+    """Level arrays from a torch sort + run detection (test infrastructure, GPU tensors)."""
+    order = len(dims)
+    key = torch.zeros_like(coords[0], dtype=torch.int64)
+    for m in mode_order:
+        key = key * int(dims[m]) + coords[m].long()
+    skey, perm = torch.sort(key, stable=True)
+    lv = [coords[m][perm] for m in mode_order]
+    idx, ptr = [], []
+    strides = []
+    acc = 1
+    for m in reversed(mode_order):
+        strides.append(acc)
+        acc *= int(dims[m])
+    strides = strides[::-1]                       # stride of level l inside the key
+    heads = []
+    for l in range(order):
+        pref = skey // strides[l]
+        h = torch.ones_like(pref, dtype=torch.bool)
+        h[1:] = pref[1:] != pref[:-1]
+        heads.append(h)
+        idx.append(lv[l][h])
+    for l in range(order - 1):
+        below = torch.cumsum(heads[l + 1].long(), 0) - heads[l + 1].long()    # exclusive rank
+        p = torch.cat([below[heads[l]], heads[l + 1].sum().reshape(1)])
+        ptr.append(p)
+    return idx, ptr, vals[perm]
+
+
+def check_csf_full(csf, coords, vals, dims, mode_order):
+    idx, ptr, v = reference_levels(coords, vals, dims, mode_order)
+    for l in range(len(dims)):
+        gi, gp, gv = csf.export(l)
+        assert torch.equal(gi, idx[l]), "idx level %d" % l
+        if l < len(dims) - 1:
+            assert torch.equal(gp, ptr[l]), "ptr level %d" % l
+        else:
+            assert torch.equal(gv.view(torch.int64), v.view(torch.int64)), "vals"
+
+
+def slice_sizes(csf):
+    """Leaves under every root node."""
+    below = None
+    for l in reversed(range(csf.order - 1)):
+        p = csf.export(l)[1]
+        below = p if below is None else below[p]
+    return below[1:] - below[:-1]
+
+
+def pick_slices(sizes, n_light=24, seed=0):
+    """Ordinals of sampled root slices: the heaviest, a few mid-size, random light ones."""
+    g = torch.Generator().manual_seed(seed)
+    order = torch.argsort(sizes.cpu(), descending=True)
+    n = order.numel()
+    picks = set(order[:2].tolist())
+    picks.update(order[[n // 100, n // 20, n // 4, n // 2, n - 1]].tolist())
+    picks.update(order[torch.randint(0, n, (n_light,), generator=g)].tolist())
+    # slices made of a few work items (sizes just above the split length)
+    sz = sizes.cpu()
+    for target in (5_000, 9_000, 20_000, 50_000):
+        picks.add(int(torch.argmin((sz - target).abs())))
+    return sorted(picks)
+
+
+def subset(coo_coords, coo_vals, mode, root_values):
+    """COO entries whose `mode` index is in root_values, with that index renumbered 0..len-1."""
+    rv = torch.as_tensor(root_values, device=coo_coords[0].device, dtype=torch.int64)
+    lut = torch.full((int(coo_coords[mode].max()) + 2,), -1, dtype=torch.int64, device=rv.device)
+    lut[rv] = torch.arange(rv.numel(), device=rv.device)
+    new = lut[coo_coords[mode].long()]
+    keep = new >= 0
+    cs = [c[keep].cpu().numpy() for c in coo_coords]
+    cs[mode] = new[keep].to(torch.int32).cpu().numpy()
+    return cs, coo_vals[keep].cpu().numpy()
+
+
+def test_config2_mttkrp_full_size_both_modes():
+    _say("config 2 full size: generate")
+    wl = w.make(2, device="cuda")
+    X = wl.sparse["X"]
+    A, B, C = wl.dense["A"], wl.dense["B"], wl.dense["C"]
+    cn = [c.cpu().numpy() for c in X.coords]
+    vn = X.vals.cpu().numpy()
+    for mode, mo, sched, facs, names in (
+            (0, [0, 1, 2], S.MTTKRP3, (C, B), ("C", "B")),
+            (2, [2, 1, 0], "T[k,j,r] = X[k,j,i] * A[i,r] | k,j,i,r ; M[k,r] = T[k,j,r] * B[j,r] | k,j,r",
+             (A, B), ("A", "B"))):
+        _say("config 2 mode %d: CSF %s" % (mode, mo))
+        csf = cst.build_csf(X.coords, X.vals, X.dims, mo)
+        check_csf_full(csf, X.coords, X.vals, X.dims, mo)
+        pl = cst.plan(sched, [("X", csf), (names[0], facs[0]), (names[1], facs[1])])
+        out = cst.execute(pl, list(facs)).reshape(pl.n_rows, -1)
+        torch.cuda.synchronize()
+        _say("config 2 mode %d: oracle over all %d nonzeros" % (mode, X.nnz))
+        others = [m for m in range(3) if m != mode]
+        Fa, Fb = ([A, B, C][others[0]].cpu().numpy(), [A, B, C][others[1]].cpu().numpy())
+        want = oracle.mttkrp3(cn, vn, X.dims, Fa, Fb, mode)
+        S_abs = oracle.mttkrp3_abs(cn, vn, X.dims, Fa, Fb, mode)
+        err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
+        _say("  rel err %.3e" % err)
+        assert err <= TOL
+        del pl, csf, out
+
+
+def test_config5_ttmc3_full_size_compact():
+    _say("config 5 full size: generate")
+    wl = w.make(5, device="cuda")
+    X = wl.sparse["X"]
+    U2, U3 = wl.dense["U2"], wl.dense["U3"]
+    csf = cst.build_csf(X.coords, X.vals, X.dims, [0, 1, 2])
+    _say("config 5: CSF check")
+    check_csf_full(csf, X.coords, X.vals, X.dims, [0, 1, 2])
+    pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=cst.OUT_COMPACT)
+    out = cst.execute(pl, [U3, U2]).reshape(pl.n_rows, 64, 64)
+    torch.cuda.synchronize()
+    rows = pl.output_rows()
+    sizes = slice_sizes(csf)
+    assert int(sizes.sum()) == X.nnz and rows.numel() == pl.n_rows
+    picks = pick_slices(sizes)
+    U2n, U3n = U2.cpu().numpy(), U3.cpu().numpy()
+    light = [p for p in picks if int(sizes[p]) <= 60_000]
+    heavy = [p for p in picks if int(sizes[p]) > 60_000]
+    _say("config 5: %d whole slices (up to %d leaves), %d heavy slices by elements (up to %d leaves)"
+         % (len(light), max(int(sizes[p]) for p in light), len(heavy), max([int(sizes[p]) for p in heavy] + [0])))
+    cs, vs = subset(X.coords, X.vals, 0, rows[light].long())
+    dims = (len(light), X.dims[1], X.dims[2])
+    want = oracle.ttmc3(cs, vs, dims, U2n, U3n, 0)
+    S_abs = oracle.ttmc3_abs(cs, vs, dims, U2n, U3n, 0)
+    err = oracle.rel_err(out[light].cpu().numpy(), want, S_abs)
+    _say("  whole slices rel err %.3e" % err)
+    assert err <= TOL
+    if heavy:
+        cs, vs = subset(X.coords, X.vals, 0, rows[heavy].long())
+        dims = (len(heavy), X.dims[1], X.dims[2])
+        for r2, r3 in ((0, 0), (63, 63), (17, 42), (5, 60)):
+            want = oracle.ttmc3(cs, vs, dims, U2n[:, [r2]], U3n[:, [r3]], 0)[:, 0, 0]
+            S_abs = oracle.ttmc3_abs(cs, vs, dims, U2n[:, [r2]], U3n[:, [r3]], 0)[:, 0, 0]
+            err = oracle.rel_err(out[heavy, r2, r3].cpu().numpy(), want, S_abs)
+            _say("  heavy slices element (%d,%d) rel err %.3e" % (r2, r3, err))
+            assert err <= TOL
+
+
+def test_config3_ttmc4_full_size():
+    _say("config 3 full size: generate")
+    wl = w.make(3, device="cuda")
+    X = wl.sparse["X"]
+    U1, U2, U3 = (wl.dense[k] for k in ("U1", "U2", "U3"))
+    csf = cst.build_csf(X.coords, X.vals, X.dims, [0, 1, 2, 3])
+    _say("config 3: CSF check")
+    check_csf_full(csf, X.coords, X.vals, X.dims, [0, 1, 2, 3])
+    pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)])
+    out = cst.execute(pl, [U3, U2, U1]).reshape(pl.n_rows, 16, 16, 16)
+    torch.cuda.synchronize()
+    sizes = slice_sizes(csf)
+    picks = pick_slices(sizes, n_light=10)
+    roots = csf.export(0)[0][picks].long()
+    _say("config 3: oracle on %d slices" % len(picks))
+    cs, vs = subset(X.coords, X.vals, 0, roots)
+    dims = (len(picks),) + tuple(X.dims[1:])
+    Un = [u.cpu().numpy() for u in (U1, U2, U3)]
+    want = oracle.ttmc4(cs, vs, dims, *Un)
+    S_abs = oracle.ttmc4_abs(cs, vs, dims, *Un)
+    err = oracle.rel_err(out[roots].cpu().numpy(), want, S_abs)
+    _say("  rel err %.3e" % err)
+    assert err <= TOL
+
+
+def test_config4_three_tensor_network_full_size():
+    _say("config 4 full size: generate")
+    wl = w.make(4, device="cuda")
+    U, W, V = wl.sparse["U"], wl.sparse["W"], wl.dense["V"]
+    ucsf = cst.build_csf(U.coords, U.vals, U.dims, [0, 2, 1])
+    wcsf = cst.build_csf(W.coords, W.vals, W.dims, [0, 1, 2])
+    _say("config 4: CSF checks")
+    check_csf_full(ucsf, U.coords, U.vals, U.dims, [0, 2, 1])
+    check_csf_full(wcsf, W.coords, W.vals, W.dims, [0, 1, 2])
+    pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)])
+    out = cst.execute(pl, [V]).reshape(pl.n_rows, W.dims[2])
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(4)
+    rows_i = sorted(set(torch.randint(0, U.dims[0], (12,), generator=g).tolist()) | {0, U.dims[0] - 1})
+    _say("config 4: oracle on %d output rows" % len(rows_i))
+    cs, vs = subset(U.coords, U.vals, 0, rows_i)
+    wc = [c.cpu().numpy() for c in W.coords]
+    wv = W.vals.cpu().numpy()
+    args = (cs, vs, (len(rows_i), U.dims[1], U.dims[2]), V.cpu().numpy(), wc, wv, W.dims)
+    want = oracle.sptn3(*args)
+    S_abs = oracle.sptn3_abs(*args)
+    err = oracle.rel_err(out[rows_i].cpu().numpy(), want, S_abs)
+    _say("  rel err %.3e" % err)
+    assert err <= TOL
