@@ -85,6 +85,118 @@ ttmc3_kernel(Ttmc3Args a) {
     }
 }
 
+// ---- MFMA kernel (ranks multiples of 16, up to 64) ------------------------------------------
+//
+// Per slice the consumer is a dense contraction, Y_i = U2[J_i,:]^T . T_i, with the fibers of the
+// slice as the K dimension.  It runs on the fp64 matrix cores, v_mfma_f64_16x16x4: K = 4 rows per
+// instruction.  The plan cuts every fiber into rows of at most kRowLeaves leaves (a long fiber
+// gives several rows with the same j: U2[j,:]^T (x) (T' + T'') = the sum of the two rank-1
+// updates), so the four rows of one K-step have similar lengths.
+// One wavefront per (item, column part): lane = (slot, c) with slot = lane/16 the K index.
+//   leaf stage   slot s walks the leaves of row g+s:  T_s[16q + c] += v * U3[k, 16q + c]
+//                (each 16-lane row reads 128-B segments of the factor row)     -> B operand
+//   A operand    U2[j_s, 16p + c]
+//   update       acc[p][q] += A_p (16x4) . T_q (4x16)   for every 16x16 tile of the row block
+// The accumulators (PN x QN tiles, 4 doubles per lane each) stay in registers for the whole item;
+// a wave covers QN of the R3/16 column tiles so that registers leave room for several waves per
+// SIMD (gridDim.y waves share an item).
+typedef double v4f64 __attribute__((ext_vector_type(4)));
+
+struct Ttmc3RowArgs {
+    int64_t n_items;
+    int R2, R3;
+    const int64_t *row_leaf;
+    const int32_t *row_j;
+    const int32_t *idx0, *idx2;
+    const double *vals;
+    const SliceItem *items;
+    const double *U2, *U3;
+    double *out, *partial;
+    int compact;
+};
+
+template <int PN, int QN>
+__global__ void __launch_bounds__(256)
+ttmc3_mfma_kernel(Ttmc3RowArgs a) {
+    const int lane = threadIdx.x % 64;
+    const int64_t w = uniform64(int64_t(blockIdx.x) * 4 + threadIdx.x / 64);
+    if (w >= a.n_items) return;
+    const SliceItem it = a.items[w];
+    const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
+    const int64_t ra = uniform64(it.begin), rb = uniform64(it.end), dest = uniform64(it.dest);
+    const int slot = lane >> 4, c = lane & 15;
+    const int R2 = a.R2, R3 = a.R3;
+    const int col0 = int(blockIdx.y) * QN * 16 + c;            // this lane's column in tile q = 0
+
+    v4f64 acc[PN][QN];
+#pragma unroll
+    for (int p = 0; p < PN; ++p)
+#pragma unroll
+        for (int q = 0; q < QN; ++q) acc[p][q] = v4f64{0.0, 0.0, 0.0, 0.0};
+
+    for (int64_t g = ra; g < rb; g += 4) {
+        const int64_t r = g + slot;
+        const bool valid = r < rb;
+        int64_t la = 0, lb = 0;
+        int32_t j = 0;
+        if (valid) { la = a.row_leaf[r]; lb = a.row_leaf[r + 1]; j = a.row_j[r]; }
+        double av[PN];
+#pragma unroll
+        for (int p = 0; p < PN; ++p) av[p] = valid ? a.U2[int64_t(j) * R2 + 16 * p + c] : 0.0;
+        double t[QN];
+#pragma unroll
+        for (int q = 0; q < QN; ++q) t[q] = 0.0;
+        for (int64_t n = la; n < lb; n += 4) {
+            int32_t kk[4];
+            double vv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = n + u < lb;
+                kk[u] = ok ? a.idx2[n + u] : -1;
+                vv[u] = ok ? a.vals[n + u] : 0.0;
+            }
+            double uu[4][QN];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < QN; ++q)
+                    uu[u][q] = kk[u] >= 0 ? a.U3[int64_t(kk[u]) * R3 + col0 + 16 * q] : 0.0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int q = 0; q < QN; ++q) t[q] = fma(vv[u], uu[u][q], t[q]);
+        }
+#pragma unroll
+        for (int p = 0; p < PN; ++p)
+#pragma unroll
+            for (int q = 0; q < QN; ++q)
+                acc[p][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[p], t[q], acc[p][q], 0, 0, 0);
+    }
+    const int64_t RR = int64_t(R2) * R3;
+    double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
+                            : a.partial + dest * RR;
+    // tile (p,q): accumulator register v of a lane holds row 16p + slot + 4v, column 16q + c
+#pragma unroll
+    for (int p = 0; p < PN; ++p)
+#pragma unroll
+        for (int q = 0; q < QN; ++q)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                base[int64_t(16 * p + slot + 4 * v) * R3 + col0 + 16 * q] = acc[p][q][v];
+}
+
+template <int PN>
+static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3RowArgs &a, hipStream_t stream) {
+    const int qt = a.R3 / 16;
+    const dim3 block(256);
+    ProfScope prof(plan, stream);
+    if (qt % 2 == 0)
+        ttmc3_mfma_kernel<PN, 2><<<dim3(unsigned(div_up(a.n_items, 4)), unsigned(qt / 2)), block, 0, stream>>>(a);
+    else
+        ttmc3_mfma_kernel<PN, 1><<<dim3(unsigned(div_up(a.n_items, 4)), unsigned(qt)), block, 0, stream>>>(a);
+    return CONSTSTN_OK;
+}
+
 // Row blocks of slices made of several items: add the partial blocks in item order.
 __global__ void __launch_bounds__(256)
 ttmc_fixup_kernel(int64_t RR, const int32_t *__restrict__ split_slices,
@@ -137,6 +249,31 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
     if (!plan->compact && X->nodes[0] < plan->out_rows)
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.n_items == 0) return CONSTSTN_OK;
+    if (plan->use_rows) {
+        Ttmc3RowArgs ra{};
+        ra.n_items = plan->n_items;
+        ra.R2 = a.R2;
+        ra.R3 = a.R3;
+        ra.row_leaf = plan->row_leaf.p;
+        ra.row_j = plan->row_j.p;
+        ra.idx0 = a.idx0;
+        ra.idx2 = a.idx2;
+        ra.vals = a.vals;
+        ra.items = a.items;
+        ra.U2 = a.U2;
+        ra.U3 = a.U3;
+        ra.out = out;
+        ra.partial = a.partial;
+        ra.compact = a.compact;
+        switch (a.R2 / 16) {
+            case 1: CST_TRY(launch_mfma_pn<1>(plan, ra, stream)); break;
+            case 2: CST_TRY(launch_mfma_pn<2>(plan, ra, stream)); break;
+            case 3: CST_TRY(launch_mfma_pn<3>(plan, ra, stream)); break;
+            default: CST_TRY(launch_mfma_pn<4>(plan, ra, stream)); break;
+        }
+        CST_HIP(hipGetLastError());
+        return launch_ttmc_fixup(plan, out, stream);
+    }
     const dim3 grid(unsigned(div_up(a.n_items, 4))), block(256);
     {
         ProfScope prof(plan, stream);

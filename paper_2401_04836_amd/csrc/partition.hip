@@ -287,16 +287,81 @@ static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *tot
     return CONSTSTN_OK;
 }
 
+// ---- TTMc order-3 MFMA path: fibers refined into rows of bounded length ----------------------
+
+__global__ void fiber_rows_kernel(int64_t fibers, const int64_t *__restrict__ ptr1, int64_t *rows_of) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f < fibers) rows_of[f] = (ptr1[f + 1] - ptr1[f] + kRowLeaves - 1) / kRowLeaves;
+}
+
+__global__ void fill_rows_kernel(int64_t fibers, const int64_t *__restrict__ ptr1,
+                                 const int32_t *__restrict__ idx1, const int64_t *__restrict__ row_off,
+                                 int64_t *row_leaf, int32_t *row_j, int64_t total_rows, int64_t nnz) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f == 0) row_leaf[total_rows] = nnz;
+    if (f >= fibers) return;
+    const int64_t a = ptr1[f], b = ptr1[f + 1];
+    int64_t r = row_off[f];
+    for (int64_t n = a; n < b; n += kRowLeaves, ++r) {
+        row_leaf[r] = n;
+        row_j[r] = idx1[f];
+    }
+}
+
+__global__ void slice_rows_kernel(int64_t slices, int64_t fibers, const int64_t *__restrict__ ptr0,
+                                  const int64_t *__restrict__ row_off, int64_t total_rows,
+                                  int64_t *slice_row) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s > slices) return;
+    const int64_t f = ptr0[s];
+    slice_row[s] = f < fibers ? row_off[f] : total_rows;
+}
+
+static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
+
+static conststn_status build_rows(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t fibers = X->nodes[1], slices = X->nodes[0];
+    DevBuf<int64_t> rows_of, row_off;
+    CST_TRY(rows_of.alloc(fibers));
+    CST_TRY(row_off.alloc(fibers));
+    const dim3 block(256);
+    fiber_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(fibers, X->ptr[1].p, rows_of.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(exscan(rows_of.p, row_off.p, fibers, &plan->n_rows_tab));
+    CST_TRY(plan->row_leaf.alloc(size_t(plan->n_rows_tab) + 1));
+    CST_TRY(plan->row_j.alloc(size_t(plan->n_rows_tab)));
+    CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));
+    fill_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
+        fibers, X->ptr[1].p, X->idx[1].p, row_off.p, plan->row_leaf.p, plan->row_j.p, plan->n_rows_tab, X->nnz);
+    CST_HIP(hipGetLastError());
+    slice_rows_kernel<<<dim3(unsigned(div_up(slices + 1, 256))), block>>>(
+        slices, fibers, X->ptr[0].p, row_off.p, plan->n_rows_tab, plan->slice_row.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
 conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t slices = X->nodes[0];
     CST_TRY(make_slice_leaf(plan));
     plan->n_items = plan->n_partials = plan->n_split = 0;
     if (slices == 0) return CONSTSTN_OK;
-    const int order = X->order;
+    int order = X->order;
     // order 3 splits by leaves, order 4 by level-1 fibers (each carries a whole sub-tree)
     const int64_t *unit_ptr = order == 3 ? plan->slice_leaf.p : X->ptr[0].p;
     int64_t split = order == 3 ? env_int("CONSTSTN_TTMC3_SPLIT", 4096) : env_int("CONSTSTN_TTMC4_SPLIT", 256);
+    // ranks that are multiples of 16 take the MFMA kernel, whose items are ranges of rows
+    plan->use_rows = order == 3 && plan->rank_of_level[1] % 16 == 0 && plan->rank_of_level[2] % 16 == 0 &&
+                     plan->rank_of_level[1] <= 64 && plan->rank_of_level[2] <= 64 &&
+                     env_int("CONSTSTN_TTMC3_NO_MFMA", 0) == 0;
+    if (plan->use_rows) {
+        CST_TRY(build_rows(plan));
+        unit_ptr = plan->slice_row.p;
+        split = env_int("CONSTSTN_TTMC3_ROWSPLIT", 256);
+        order = 0;                                   // items carry no 'first fiber'
+    }
     DevBuf<int64_t> pieces, part_cnt, is_split, item_off, part_off, split_rank;
     CST_TRY(pieces.alloc(slices));
     CST_TRY(part_cnt.alloc(slices));

@@ -8,7 +8,8 @@
 namespace cst {
 
 constexpr int kHeavySpan = 64;        // a slice spanning at least this many chunks is "heavy"
-constexpr int kHeavySegments = 32;    // its chunk range is reduced in this many parallel segments
+constexpr int kHeavySegments = 32;
+constexpr int kRowLeaves = 32;        // longest run of leaves one MFMA K-row sums    // its chunk range is reduced in this many parallel segments
 
 enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
 
@@ -61,6 +62,13 @@ struct conststn_plan_s {
     cst::DevBuf<int32_t> split_slices;     // slices made of more than one item
     cst::DevBuf<int64_t> split_first;      // [n_split] first partial slot of that slice
     cst::DevBuf<int32_t> split_count;      // [n_split] number of partial slots
+    // TTMc order-3 MFMA path: fibers cut into "rows" of at most kRowLeaves leaves (a long fiber
+    // becomes several rows with the same level-1 index); items are ranges of rows
+    bool use_rows = false;
+    int64_t n_rows_tab = 0;
+    cst::DevBuf<int64_t> row_leaf;         // [rows+1] first leaf of each row
+    cst::DevBuf<int32_t> row_j;            // [rows] level-1 index of the row's fiber
+    cst::DevBuf<int64_t> slice_row;        // [slices+1] first row of each slice
     cst::DevBuf<double> partial;           // partial row blocks
     // three-tensor network
     cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1

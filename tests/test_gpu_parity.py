@@ -131,7 +131,8 @@ def test_mttkrp_ranks_and_heavy_slices(rank):
     assert compare(out, want, S_abs) <= TOL
 
 
-@pytest.mark.parametrize("ranks", [(1, 1), (3, 5), (8, 8), (16, 33), (64, 64), (50, 50)])
+@pytest.mark.parametrize("ranks", [(1, 1), (3, 5), (8, 8), (16, 33), (64, 64), (50, 50), (16, 16),
+                                   (32, 48), (48, 16), (64, 32)])
 def test_ttmc3_ranks(ranks):
     _say("ttmc3 ranks %s" % (ranks,))
     wl = w.make(5, small=True, dims=(501, 409, 211), nnz=30_011, ranks=ranks)
