@@ -119,14 +119,19 @@ template <int PN, int QN>
 __global__ void __launch_bounds__(256)
 ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int lane = threadIdx.x % 64;
-    const int64_t w = uniform64(int64_t(blockIdx.x) * 4 + threadIdx.x / 64);
+    // Workgroups are dealt to the XCDs round-robin by their linear id, so the column part is
+    // taken from the low bits of blockIdx.x: every XCD then gathers only its own R3/parts
+    // columns of U3 and that slice of the factor stays resident in the XCD's L2.
+    const int parts = a.R3 / (16 * QN);
+    const int part = int(blockIdx.x % unsigned(parts));
+    const int64_t w = uniform64(int64_t(blockIdx.x / unsigned(parts)) * 4 + threadIdx.x / 64);
     if (w >= a.n_items) return;
     const SliceItem it = a.items[w];
     const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
     const int64_t ra = uniform64(it.begin), rb = uniform64(it.end), dest = uniform64(it.dest);
     const int slot = lane >> 4, c = lane & 15;
     const int R2 = a.R2, R3 = a.R3;
-    const int col0 = int(blockIdx.y) * QN * 16 + c;            // this lane's column in tile q = 0
+    const int col0 = part * QN * 16 + c;                       // this lane's column in tile q = 0
 
     v4f64 acc[PN][QN];
 #pragma unroll
@@ -134,12 +139,20 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
 #pragma unroll
         for (int q = 0; q < QN; ++q) acc[p][q] = v4f64{0.0, 0.0, 0.0, 0.0};
 
+    // row descriptors are fetched one K-step ahead
+    int64_t nla = 0, nlb = 0;
+    int32_t nj = 0;
+    if (ra + slot < rb) { nla = a.row_leaf[ra + slot]; nlb = a.row_leaf[ra + slot + 1]; nj = a.row_j[ra + slot]; }
     for (int64_t g = ra; g < rb; g += 4) {
-        const int64_t r = g + slot;
-        const bool valid = r < rb;
-        int64_t la = 0, lb = 0;
-        int32_t j = 0;
-        if (valid) { la = a.row_leaf[r]; lb = a.row_leaf[r + 1]; j = a.row_j[r]; }
+        const bool valid = g + slot < rb;
+        const int64_t la = nla, lb = nlb;
+        const int32_t j = nj;
+        nla = nlb = 0;
+        if (g + 4 + slot < rb) {
+            nla = a.row_leaf[g + 4 + slot];
+            nlb = a.row_leaf[g + 5 + slot];
+            nj = a.row_j[g + 4 + slot];
+        }
         double av[PN];
 #pragma unroll
         for (int p = 0; p < PN; ++p) av[p] = valid ? a.U2[int64_t(j) * R2 + 16 * p + c] : 0.0;
@@ -189,11 +202,12 @@ template <int PN>
 static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3RowArgs &a, hipStream_t stream) {
     const int qt = a.R3 / 16;
     const dim3 block(256);
+    const int64_t groups = div_up(a.n_items, 4);
     ProfScope prof(plan, stream);
-    if (qt % 2 == 0)
-        ttmc3_mfma_kernel<PN, 2><<<dim3(unsigned(div_up(a.n_items, 4)), unsigned(qt / 2)), block, 0, stream>>>(a);
+    if (env_int("CONSTSTN_TTMC3_QN", 1) == 2 && qt % 2 == 0)
+        ttmc3_mfma_kernel<PN, 2><<<dim3(unsigned(groups * (qt / 2))), block, 0, stream>>>(a);
     else
-        ttmc3_mfma_kernel<PN, 1><<<dim3(unsigned(div_up(a.n_items, 4)), unsigned(qt)), block, 0, stream>>>(a);
+        ttmc3_mfma_kernel<PN, 1><<<dim3(unsigned(groups * qt)), block, 0, stream>>>(a);
     return CONSTSTN_OK;
 }
 
