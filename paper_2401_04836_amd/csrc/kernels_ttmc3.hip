@@ -159,21 +159,27 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
         double t[QN];
 #pragma unroll
         for (int q = 0; q < QN; ++q) t[q] = 0.0;
-        for (int64_t n = la; n < lb; n += 4) {
+        // the (at most kRowLeaves = 16) leaves of the row: one coalesced load per array, one
+        // entry per lane of the slot, then handed round inside the slot with lane shuffles --
+        // a broadcast load per leaf would cost the memory pipeline 16 lanes' worth each time
+        const int cnt = int(lb - la);
+        int32_t myk = 0;
+        double myv = 0.0;
+        if (c < cnt) { myk = a.idx2[la + c]; myv = a.vals[la + c]; }
+        for (int t0 = 0; t0 < cnt; t0 += 4) {
             int32_t kk[4];
             double vv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const bool ok = n + u < lb;
-                kk[u] = ok ? a.idx2[n + u] : -1;
-                vv[u] = ok ? a.vals[n + u] : 0.0;
+                kk[u] = __shfl(myk, t0 + u, 16);
+                vv[u] = __shfl(myv, t0 + u, 16);
             }
             double uu[4][QN];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int q = 0; q < QN; ++q)
-                    uu[u][q] = kk[u] >= 0 ? a.U3[int64_t(kk[u]) * R3 + col0 + 16 * q] : 0.0;
+                    uu[u][q] = t0 + u < cnt ? a.U3[int64_t(kk[u]) * R3 + col0 + 16 * q] : 0.0;
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll

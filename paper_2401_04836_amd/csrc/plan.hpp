@@ -9,7 +9,7 @@ namespace cst {
 
 constexpr int kHeavySpan = 64;        // a slice spanning at least this many chunks is "heavy"
 constexpr int kHeavySegments = 32;
-constexpr int kRowLeaves = 32;        // longest run of leaves one MFMA K-row sums    // its chunk range is reduced in this many parallel segments
+constexpr int kRowLeaves = 16;        // longest run of leaves one MFMA K-row sums    // its chunk range is reduced in this many parallel segments
 
 enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
 
