@@ -116,7 +116,7 @@ struct Ttmc3RowArgs {
 };
 
 template <int PN, int QN>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QN == 1 ? 5 : 4, 8)))
 ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int lane = threadIdx.x % 64;
     // Workgroups are dealt to the XCDs round-robin by their linear id, so the column part is
@@ -139,33 +139,47 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
 #pragma unroll
         for (int q = 0; q < QN; ++q) acc[p][q] = v4f64{0.0, 0.0, 0.0, 0.0};
 
-    // row descriptors are fetched one K-step ahead
-    int64_t nla = 0, nlb = 0;
-    int32_t nj = 0;
-    if (ra + slot < rb) { nla = a.row_leaf[ra + slot]; nlb = a.row_leaf[ra + slot + 1]; nj = a.row_j[ra + slot]; }
-    for (int64_t g = ra; g < rb; g += 4) {
-        const bool valid = g + slot < rb;
-        const int64_t la = nla, lb = nlb;
-        const int32_t j = nj;
-        nla = nlb = 0;
-        if (g + 4 + slot < rb) {
-            nla = a.row_leaf[g + 4 + slot];
-            nlb = a.row_leaf[g + 5 + slot];
-            nj = a.row_j[g + 4 + slot];
+    // Three-stage software pipeline over K-steps (4 rows each): while step g is computed, the
+    // leaf entries and U2 segments of step g+4 and the row descriptors of step g+8 are in
+    // flight, so a step waits only for its own U3 gathers.
+    struct Desc { int64_t la; int cnt; int32_t j; };
+    auto load_desc = [&](int64_t g) -> Desc {
+        Desc d{0, 0, 0};
+        if (g + slot < rb) {
+            d.la = a.row_leaf[g + slot];
+            d.cnt = int(a.row_leaf[g + slot + 1] - d.la);
+            d.j = a.row_j[g + slot];
         }
-        double av[PN];
-#pragma unroll
-        for (int p = 0; p < PN; ++p) av[p] = valid ? a.U2[int64_t(j) * R2 + 16 * p + c] : 0.0;
+        return d;
+    };
+    struct Feed { int32_t k; double v; int cnt; int32_t j; };
+    auto load_feed = [&](const Desc &d) -> Feed {
+        Feed f;
+        f.k = 0;
+        f.v = 0.0;
+        f.cnt = d.cnt;
+        f.j = d.j;
+        if (c < d.cnt) { f.k = a.idx2[d.la + c]; f.v = a.vals[d.la + c]; }
+        return f;
+    };
+    Desc d1 = load_desc(ra);
+    Desc d2 = load_desc(ra + 4);
+    Feed cur = load_feed(d1);
+    for (int64_t g = ra; g < rb; g += 4) {
+        const Feed nxt = load_feed(d2);          // step g+4 (its descriptor arrived a step ago)
+        d2 = load_desc(g + 8);
         double t[QN];
 #pragma unroll
         for (int q = 0; q < QN; ++q) t[q] = 0.0;
-        // the (at most kRowLeaves = 16) leaves of the row: one coalesced load per array, one
-        // entry per lane of the slot, then handed round inside the slot with lane shuffles --
-        // a broadcast load per leaf would cost the memory pipeline 16 lanes' worth each time
-        const int cnt = int(lb - la);
-        int32_t myk = 0;
-        double myv = 0.0;
-        if (c < cnt) { myk = a.idx2[la + c]; myv = a.vals[la + c]; }
+        // the (at most kRowLeaves = 16) leaves of the row were loaded one entry per lane of the
+        // slot and are handed round inside the slot with lane shuffles -- a broadcast load per
+        // leaf would cost the memory pipeline 16 lanes' worth each time
+        const int cnt = cur.cnt;
+        const int32_t myk = cur.k;
+        const double myv = cur.v;
+        double av[PN];                               // issued with the step's U3 gathers
+#pragma unroll
+        for (int p = 0; p < PN; ++p) av[p] = cnt > 0 ? a.U2[int64_t(cur.j) * R2 + 16 * p + c] : 0.0;
         for (int t0 = 0; t0 < cnt; t0 += 4) {
             int32_t kk[4];
             double vv[4];
@@ -190,6 +204,7 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
 #pragma unroll
             for (int q = 0; q < QN; ++q)
                 acc[p][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[p], t[q], acc[p][q], 0, 0, 0);
+        cur = nxt;
     }
     const int64_t RR = int64_t(R2) * R3;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
