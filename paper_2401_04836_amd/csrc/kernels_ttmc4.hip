@@ -102,6 +102,125 @@ ttmc4_kernel(Ttmc4Args a) {
     }
 }
 
+// ---- MFMA kernel (all three ranks equal to 16) ----------------------------------------------
+//
+// Both dense stages run on the fp64 matrix cores (v_mfma_f64_16x16x4, K = 4):
+//   mid level   T2_f (16x16) = U2[K_f,:]^T . T1_f       K = the (i,j,k) nodes of fiber f
+//   slice level Y_i (16x256) = U1[J_i,:]^T . T2_i       K = the (i,j) fibers of the item
+// One wavefront per item, lane = (slot, c), slot = lane/16.  A K-step takes four fibers.  For
+// each of them the slots are four nodes of the fiber: lane (s,c) builds T1_node_s[r3 = c] from
+// the node's leaves (VALU) and supplies U2[k_s, r2 = c]; one MFMA per four nodes gives T2_f in
+// the accumulator layout (register v of lane (s,c) holds T2[r2 = s+4v][r3 = c]).  The four T2
+// tiles go through a wave-private LDS buffer so that in the slice-level MFMAs slot s can supply
+// the tile of fiber s: B_t = T2_s[r2 = t][r3 = c] for the 16 column tiles t, A = U1[j_s, r1 = c].
+// The loads of the four fibers of a K-step are issued stage by stage for all four together
+// (node descriptors, then leaf entries + U2, then U3 rows), so a K-step costs about four memory
+// round trips instead of four per fiber; the fibers' own descriptors are fetched a step ahead.
+typedef double v4d __attribute__((ext_vector_type(4)));
+constexpr int kT2Stride = 16 * 16 + 16;        // doubles per fiber tile in LDS (+16: bank skew)
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4)))
+ttmc4_mfma_kernel(Ttmc4Args a) {
+    __shared__ double t2buf[4][4 * kT2Stride];
+    const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
+    const int64_t w = uni64(int64_t(blockIdx.x) * 4 + wv);
+    if (w >= a.n_items) return;
+    const SliceItem it = a.items[w];
+    const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
+    const int64_t fa = uni64(it.begin), fb = uni64(it.end), dest = uni64(it.dest);
+    const int slot = lane >> 4, c = lane & 15;
+    double *lds = t2buf[wv];
+
+    v4d acc[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
+
+    // per-lane view of the K-step's fibers: lane (slot, c) needs fiber g+slot for the A operand,
+    // and every lane needs the node range of all four fibers (kept per lane, loaded once)
+    auto fiber_desc = [&](int64_t g, int64_t na[4], int64_t nb[4], int32_t &j) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            na[u] = nb[u] = 0;
+            if (g + u < fb) { na[u] = a.ptr1[g + u]; nb[u] = a.ptr1[g + u + 1]; }
+        }
+        j = g + slot < fb ? a.idx1[g + slot] : -1;
+    };
+    int64_t na[4], nb[4], nna[4], nnb[4];
+    int32_t j, nj;
+    fiber_desc(fa, nna, nnb, nj);
+    for (int64_t g = fa; g < fb; g += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { na[u] = nna[u]; nb[u] = nnb[u]; }
+        j = nj;
+        fiber_desc(g + 4, nna, nnb, nj);
+        const double av = j >= 0 ? a.U1[int64_t(j) * 16 + c] : 0.0;
+
+        // stage 1: node descriptors of the first four nodes of each fiber
+        int32_t k[4];
+        int64_t la[4], lb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t n = na[u] + slot;
+            k[u] = -1;
+            la[u] = lb[u] = 0;
+            if (n < nb[u]) { k[u] = a.idx2[n]; la[u] = a.ptr2[n]; lb[u] = a.ptr2[n + 1]; }
+        }
+        // stage 2: U2 row entry, first two leaves of each node
+        double u2[4], v0[4], v1[4];
+        int32_t l0[4], l1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            u2[u] = k[u] >= 0 ? a.U2[int64_t(k[u]) * 16 + c] : 0.0;
+            l0[u] = l1[u] = -1;
+            v0[u] = v1[u] = 0.0;
+            if (la[u] < lb[u]) { l0[u] = a.idx3[la[u]]; v0[u] = a.vals[la[u]]; }
+            if (la[u] + 1 < lb[u]) { l1[u] = a.idx3[la[u] + 1]; v1[u] = a.vals[la[u] + 1]; }
+        }
+        // stage 3: U3 rows
+        double x0[4], x1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            x0[u] = l0[u] >= 0 ? a.U3[int64_t(l0[u]) * 16 + c] : 0.0;
+            x1[u] = l1[u] >= 0 ? a.U3[int64_t(l1[u]) * 16 + c] : 0.0;
+        }
+        // stage 4: T1, mid-level MFMA, remainders (nodes with > 2 leaves, fibers with > 4 nodes)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            double t1 = fma(v1[u], x1[u], v0[u] * x0[u]);
+            for (int64_t e = la[u] + 2; e < lb[u]; ++e)
+                t1 = fma(a.vals[e], a.U3[int64_t(a.idx3[e]) * 16 + c], t1);
+            v4d t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(u2[u], t1, v4d{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
+            for (int64_t n0 = na[u] + 4; n0 < nb[u]; n0 += 4) {          // wave-uniform bounds
+                const int64_t n = n0 + slot;
+                double uu = 0.0, tt = 0.0;
+                if (n < nb[u]) {
+                    uu = a.U2[int64_t(a.idx2[n]) * 16 + c];
+                    for (int64_t e = a.ptr2[n]; e < a.ptr2[n + 1]; ++e)
+                        tt = fma(a.vals[e], a.U3[int64_t(a.idx3[e]) * 16 + c], tt);
+                }
+                t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(uu, tt, t2, 0, 0, 0);
+            }
+            // accumulator layout -> LDS tile of fiber u: element (r2 = slot + 4v, r3 = c)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) lds[u * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];
+        }
+        // slice level: slot s supplies fiber s; 16 column tiles t = r2
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const double bv = lds[slot * kT2Stride + t * 16 + c];
+            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[t], 0, 0, 0);
+        }
+    }
+    const int64_t RR = 4096;
+    double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
+                            : a.partial + dest * RR;
+    // acc[t][v] = Y[r1 = slot + 4v][r2 = t][r3 = c]
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) base[((slot + 4 * v) * 16 + t) * 16 + c] = acc[t][v];
+}
+
 conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream) {
     const conststn_csf_s *X = plan->X;
@@ -133,7 +252,10 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
     if (a.n_items == 0) return CONSTSTN_OK;
     {
         ProfScope prof(plan, stream);
-        ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
+        if (a.R1 == 16 && a.R2 == 16 && a.R3 == 16 && env_int("CONSTSTN_TTMC4_NO_MFMA", 0) == 0)
+            ttmc4_mfma_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
+        else
+            ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
     }
     CST_HIP(hipGetLastError());
     return launch_ttmc_fixup(plan, out, stream);
