@@ -105,29 +105,44 @@ ttmc4_kernel(Ttmc4Args a) {
 // ---- MFMA kernel (all three ranks equal to 16) ----------------------------------------------
 //
 // Both dense stages run on the fp64 matrix cores (v_mfma_f64_16x16x4, K = 4):
-//   mid level   T2_f (16x16) = U2[K_f,:]^T . T1_f       K = the (i,j,k) nodes of fiber f
-//   slice level Y_i (16x256) = U1[J_i,:]^T . T2_i       K = the (i,j) fibers of the item
-// One wavefront per item, lane = (slot, c), slot = lane/16.  A K-step takes four fibers.  For
-// each of them the slots are four nodes of the fiber: lane (s,c) builds T1_node_s[r3 = c] from
-// the node's leaves (VALU) and supplies U2[k_s, r2 = c]; one MFMA per four nodes gives T2_f in
-// the accumulator layout (register v of lane (s,c) holds T2[r2 = s+4v][r3 = c]).  The four T2
-// tiles go through a wave-private LDS buffer so that in the slice-level MFMAs slot s can supply
-// the tile of fiber s: B_t = T2_s[r2 = t][r3 = c] for the 16 column tiles t, A = U1[j_s, r1 = c].
-// The loads of the four fibers of a K-step are issued stage by stage for all four together
-// (node descriptors, then leaf entries + U2, then U3 rows), so a K-step costs about four memory
-// round trips instead of four per fiber; the fibers' own descriptors are fetched a step ahead.
+//   mid level   T2 (16x16) = U2[K,:]^T . T1        K = four "pieces" of (i,j,k) nodes
+//   slice level Y_i (16x256) = U1[J,:]^T . T2      K = four "rows" of (i,j) fibers
+// The plan cuts every node into pieces of at most two leaves and every fiber into rows of at most
+// four pieces (partition.hip); a long node or fiber simply contributes several K entries with the
+// same factor row, which is legal by distributivity.  Every K-step therefore does the same,
+// loop-free amount of work whatever the skew of the tensor.
+// One wavefront per item (a range of rows of one slice), lane = (slot, c), slot = lane/16.
+// A K-step takes four rows.  For each of them the slots are the row's four pieces: lane (s,c)
+// builds T1_piece_s[r3 = c] from at most two leaves and supplies U2[k_s, r2 = c]; one MFMA gives
+// the row's T2 in the accumulator layout (register v of lane (s,c) = T2[r2 = s+4v][r3 = c]).  The
+// four T2 tiles pass through a wave-private LDS buffer so that in the slice-level MFMAs slot s
+// supplies the tile of row s: B_t = T2_s[r2 = t][r3 = c] for the 16 column tiles, A = U1[j_s, c].
+// Loads are issued stage by stage for all four rows together and row / piece descriptors are
+// fetched one and two K-steps ahead, so a K-step waits for two memory round trips.
 typedef double v4d __attribute__((ext_vector_type(4)));
-constexpr int kT2Stride = 16 * 16 + 16;        // doubles per fiber tile in LDS (+16: bank skew)
+constexpr int kT2Stride = 16 * 16 + 16;        // doubles per tile in LDS (+16: bank skew)
+
+struct Ttmc4RowArgs {
+    int64_t n_items;
+    const int64_t *row_piece, *piece_leaf;
+    const int32_t *row_j, *piece_k;
+    const int32_t *idx0, *idx3;
+    const double *vals;
+    const SliceItem *items;
+    const double *U1, *U2, *U3;
+    double *out, *partial;
+    int compact;
+};
 
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4)))
-ttmc4_mfma_kernel(Ttmc4Args a) {
+ttmc4_mfma_kernel(Ttmc4RowArgs a) {
     __shared__ double t2buf[4][4 * kT2Stride];
     const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
     const int64_t w = uni64(int64_t(blockIdx.x) * 4 + wv);
     if (w >= a.n_items) return;
     const SliceItem it = a.items[w];
     const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
-    const int64_t fa = uni64(it.begin), fb = uni64(it.end), dest = uni64(it.dest);
+    const int64_t ra = uni64(it.begin), rb = uni64(it.end), dest = uni64(it.dest);
     const int slot = lane >> 4, c = lane & 15;
     double *lds = t2buf[wv];
 
@@ -135,81 +150,78 @@ ttmc4_mfma_kernel(Ttmc4Args a) {
 #pragma unroll
     for (int t = 0; t < 16; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
 
-    // per-lane view of the K-step's fibers: lane (slot, c) needs fiber g+slot for the A operand,
-    // and every lane needs the node range of all four fibers (kept per lane, loaded once)
-    auto fiber_desc = [&](int64_t g, int64_t na[4], int64_t nb[4], int32_t &j) {
+    // row descriptors of a K-step: piece ranges of its four rows (every lane), j of row g+slot
+    struct Rows { int64_t pa[4]; int pn[4]; int32_t j; };
+    auto load_rows = [&](int64_t g) -> Rows {
+        Rows r;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            na[u] = nb[u] = 0;
-            if (g + u < fb) { na[u] = a.ptr1[g + u]; nb[u] = a.ptr1[g + u + 1]; }
+            r.pa[u] = 0;
+            r.pn[u] = 0;
+            if (g + u < rb) { r.pa[u] = a.row_piece[g + u]; r.pn[u] = int(a.row_piece[g + u + 1] - r.pa[u]); }
         }
-        j = g + slot < fb ? a.idx1[g + slot] : -1;
+        r.j = g + slot < rb ? a.row_j[g + slot] : -1;
+        return r;
     };
-    int64_t na[4], nb[4], nna[4], nnb[4];
-    int32_t j, nj;
-    fiber_desc(fa, nna, nnb, nj);
-    for (int64_t g = fa; g < fb; g += 4) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { na[u] = nna[u]; nb[u] = nnb[u]; }
-        j = nj;
-        fiber_desc(g + 4, nna, nnb, nj);
-        const double av = j >= 0 ? a.U1[int64_t(j) * 16 + c] : 0.0;
-
-        // stage 1: node descriptors of the first four nodes of each fiber
-        int32_t k[4];
-        int64_t la[4], lb[4];
+    // piece descriptors: piece pa[u]+slot of each row
+    struct Pieces { int32_t k[4]; int64_t la[4]; int ln[4]; int32_t j; };
+    auto load_pieces = [&](const Rows &r) -> Pieces {
+        Pieces p;
+        p.j = r.j;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int64_t n = na[u] + slot;
-            k[u] = -1;
-            la[u] = lb[u] = 0;
-            if (n < nb[u]) { k[u] = a.idx2[n]; la[u] = a.ptr2[n]; lb[u] = a.ptr2[n + 1]; }
+            p.k[u] = -1;
+            p.la[u] = 0;
+            p.ln[u] = 0;
+            if (slot < r.pn[u]) {
+                const int64_t q = r.pa[u] + slot;
+                p.k[u] = a.piece_k[q];
+                p.la[u] = a.piece_leaf[q];
+                p.ln[u] = int(a.piece_leaf[q + 1] - p.la[u]);
+            }
         }
-        // stage 2: U2 row entry, first two leaves of each node
+        return p;
+    };
+    Rows r2 = load_rows(ra);
+    Pieces cur = load_pieces(r2);
+    r2 = load_rows(ra + 4);
+    for (int64_t g = ra; g < rb; g += 4) {
+        const Pieces nxt = load_pieces(r2);              // K-step g+4
+        r2 = load_rows(g + 8);
+        const double av = cur.j >= 0 ? a.U1[int64_t(cur.j) * 16 + c] : 0.0;
+        // stage A: U2 entry and the (at most two) leaves of each piece
         double u2[4], v0[4], v1[4];
         int32_t l0[4], l1[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            u2[u] = k[u] >= 0 ? a.U2[int64_t(k[u]) * 16 + c] : 0.0;
+            u2[u] = cur.k[u] >= 0 ? a.U2[int64_t(cur.k[u]) * 16 + c] : 0.0;
             l0[u] = l1[u] = -1;
             v0[u] = v1[u] = 0.0;
-            if (la[u] < lb[u]) { l0[u] = a.idx3[la[u]]; v0[u] = a.vals[la[u]]; }
-            if (la[u] + 1 < lb[u]) { l1[u] = a.idx3[la[u] + 1]; v1[u] = a.vals[la[u] + 1]; }
+            if (cur.ln[u] > 0) { l0[u] = a.idx3[cur.la[u]]; v0[u] = a.vals[cur.la[u]]; }
+            if (cur.ln[u] > 1) { l1[u] = a.idx3[cur.la[u] + 1]; v1[u] = a.vals[cur.la[u] + 1]; }
         }
-        // stage 3: U3 rows
+        // stage B: U3 rows
         double x0[4], x1[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             x0[u] = l0[u] >= 0 ? a.U3[int64_t(l0[u]) * 16 + c] : 0.0;
             x1[u] = l1[u] >= 0 ? a.U3[int64_t(l1[u]) * 16 + c] : 0.0;
         }
-        // stage 4: T1, mid-level MFMA, remainders (nodes with > 2 leaves, fibers with > 4 nodes)
+        // mid level
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            double t1 = fma(v1[u], x1[u], v0[u] * x0[u]);
-            for (int64_t e = la[u] + 2; e < lb[u]; ++e)
-                t1 = fma(a.vals[e], a.U3[int64_t(a.idx3[e]) * 16 + c], t1);
-            v4d t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(u2[u], t1, v4d{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
-            for (int64_t n0 = na[u] + 4; n0 < nb[u]; n0 += 4) {          // wave-uniform bounds
-                const int64_t n = n0 + slot;
-                double uu = 0.0, tt = 0.0;
-                if (n < nb[u]) {
-                    uu = a.U2[int64_t(a.idx2[n]) * 16 + c];
-                    for (int64_t e = a.ptr2[n]; e < a.ptr2[n + 1]; ++e)
-                        tt = fma(a.vals[e], a.U3[int64_t(a.idx3[e]) * 16 + c], tt);
-                }
-                t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(uu, tt, t2, 0, 0, 0);
-            }
-            // accumulator layout -> LDS tile of fiber u: element (r2 = slot + 4v, r3 = c)
+            const double t1 = fma(v1[u], x1[u], v0[u] * x0[u]);
+            const v4d t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(u2[u], t1, v4d{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 4; ++v) lds[u * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];
         }
-        // slice level: slot s supplies fiber s; 16 column tiles t = r2
+        // slice level: slot s supplies row s; 16 column tiles t = r2
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             const double bv = lds[slot * kT2Stride + t * 16 + c];
             acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[t], 0, 0, 0);
         }
+        cur = nxt;
     }
     const int64_t RR = 4096;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
@@ -252,9 +264,25 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
     if (a.n_items == 0) return CONSTSTN_OK;
     {
         ProfScope prof(plan, stream);
-        if (a.R1 == 16 && a.R2 == 16 && a.R3 == 16 && env_int("CONSTSTN_TTMC4_NO_MFMA", 0) == 0)
-            ttmc4_mfma_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
-        else
+        if (plan->use_rows) {
+            Ttmc4RowArgs ra{};
+            ra.n_items = plan->n_items;
+            ra.row_piece = plan->row_piece.p;
+            ra.piece_leaf = plan->piece_leaf.p;
+            ra.row_j = plan->row_j.p;
+            ra.piece_k = plan->piece_k.p;
+            ra.idx0 = a.idx0;
+            ra.idx3 = a.idx3;
+            ra.vals = a.vals;
+            ra.items = a.items;
+            ra.U1 = a.U1;
+            ra.U2 = a.U2;
+            ra.U3 = a.U3;
+            ra.out = out;
+            ra.partial = a.partial;
+            ra.compact = a.compact;
+            ttmc4_mfma_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(ra);
+        } else
             ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
     }
     CST_HIP(hipGetLastError());

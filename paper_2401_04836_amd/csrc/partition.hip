@@ -342,6 +342,88 @@ static conststn_status build_rows(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// ---- TTMc order-4 MFMA path: nodes -> pieces (<= kPieceLeaves leaves), fibers -> rows (<= 4 pieces)
+
+__global__ void count_units_kernel(int64_t n, const int64_t *__restrict__ ptr, int64_t per, int64_t *cnt) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) cnt[i] = (ptr[i + 1] - ptr[i] + per - 1) / per;
+}
+
+__global__ void fill_pieces_kernel(int64_t nodes, const int64_t *__restrict__ ptr2,
+                                   const int32_t *__restrict__ idx2, const int64_t *__restrict__ piece_off,
+                                   int64_t *piece_leaf, int32_t *piece_k, int64_t total, int64_t nnz) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n == 0) piece_leaf[total] = nnz;
+    if (n >= nodes) return;
+    int64_t p = piece_off[n];
+    for (int64_t e = ptr2[n]; e < ptr2[n + 1]; e += kPieceLeaves, ++p) {
+        piece_leaf[p] = e;
+        piece_k[p] = idx2[n];
+    }
+}
+
+// pieces of fiber f: piece_off[ptr1[f]] .. piece_off[ptr1[f+1]] (piece_off_end = total for the last)
+__global__ void fiber_piece_rows_kernel(int64_t fibers, int64_t nodes, const int64_t *__restrict__ ptr1,
+                                        const int64_t *__restrict__ piece_off, int64_t total_pieces,
+                                        int64_t *rows_of) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f >= fibers) return;
+    const int64_t a = piece_off[ptr1[f]];
+    const int64_t b = ptr1[f + 1] < nodes ? piece_off[ptr1[f + 1]] : total_pieces;
+    rows_of[f] = (b - a + 3) / 4;
+}
+
+__global__ void fill_piece_rows_kernel(int64_t fibers, int64_t nodes, const int64_t *__restrict__ ptr1,
+                                       const int32_t *__restrict__ idx1, const int64_t *__restrict__ piece_off,
+                                       int64_t total_pieces, const int64_t *__restrict__ row_off,
+                                       int64_t *row_piece, int32_t *row_j, int64_t total_rows) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f == 0) row_piece[total_rows] = total_pieces;
+    if (f >= fibers) return;
+    const int64_t a = piece_off[ptr1[f]];
+    const int64_t b = ptr1[f + 1] < nodes ? piece_off[ptr1[f + 1]] : total_pieces;
+    int64_t r = row_off[f];
+    for (int64_t p = a; p < b; p += 4, ++r) {
+        row_piece[r] = p;
+        row_j[r] = idx1[f];
+    }
+}
+
+static conststn_status build_piece_rows(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t slices = X->nodes[0], fibers = X->nodes[1], nodes = X->nodes[2];
+    const dim3 block(256);
+    DevBuf<int64_t> cnt, piece_off, rows_of, row_off;
+    CST_TRY(cnt.alloc(nodes));
+    CST_TRY(piece_off.alloc(nodes));
+    count_units_kernel<<<dim3(unsigned(div_up(nodes, 256))), block>>>(nodes, X->ptr[2].p, kPieceLeaves, cnt.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(exscan(cnt.p, piece_off.p, nodes, &plan->n_pieces));
+    CST_TRY(plan->piece_leaf.alloc(size_t(plan->n_pieces) + 1));
+    CST_TRY(plan->piece_k.alloc(size_t(plan->n_pieces)));
+    fill_pieces_kernel<<<dim3(unsigned(div_up(nodes, 256))), block>>>(
+        nodes, X->ptr[2].p, X->idx[2].p, piece_off.p, plan->piece_leaf.p, plan->piece_k.p, plan->n_pieces, X->nnz);
+    CST_HIP(hipGetLastError());
+    CST_TRY(rows_of.alloc(fibers));
+    CST_TRY(row_off.alloc(fibers));
+    fiber_piece_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
+        fibers, nodes, X->ptr[1].p, piece_off.p, plan->n_pieces, rows_of.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(exscan(rows_of.p, row_off.p, fibers, &plan->n_rows_tab));
+    CST_TRY(plan->row_piece.alloc(size_t(plan->n_rows_tab) + 1));
+    CST_TRY(plan->row_j.alloc(size_t(plan->n_rows_tab)));
+    CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));
+    fill_piece_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
+        fibers, nodes, X->ptr[1].p, X->idx[1].p, piece_off.p, plan->n_pieces, row_off.p, plan->row_piece.p,
+        plan->row_j.p, plan->n_rows_tab);
+    CST_HIP(hipGetLastError());
+    slice_rows_kernel<<<dim3(unsigned(div_up(slices + 1, 256))), block>>>(
+        slices, fibers, X->ptr[0].p, row_off.p, plan->n_rows_tab, plan->slice_row.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
 conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t slices = X->nodes[0];
@@ -361,6 +443,13 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
         unit_ptr = plan->slice_row.p;
         split = env_int("CONSTSTN_TTMC3_ROWSPLIT", 256);
         order = 0;                                   // items carry no 'first fiber'
+    }
+    if (order == 4 && plan->rank_of_level[1] == 16 && plan->rank_of_level[2] == 16 &&
+        plan->rank_of_level[3] == 16 && env_int("CONSTSTN_TTMC4_NO_MFMA", 0) == 0) {
+        plan->use_rows = true;
+        CST_TRY(build_piece_rows(plan));
+        unit_ptr = plan->slice_row.p;
+        split = env_int("CONSTSTN_TTMC4_ROWSPLIT", 256);
     }
     DevBuf<int64_t> pieces, part_cnt, is_split, item_off, part_off, split_rank;
     CST_TRY(pieces.alloc(slices));

@@ -9,7 +9,8 @@ namespace cst {
 
 constexpr int kHeavySpan = 64;        // a slice spanning at least this many chunks is "heavy"
 constexpr int kHeavySegments = 32;
-constexpr int kRowLeaves = 16;        // longest run of leaves one MFMA K-row sums    // its chunk range is reduced in this many parallel segments
+constexpr int kRowLeaves = 16;
+constexpr int kPieceLeaves = 2;       // order-4 path: leaves per piece of a level-2 node        // longest run of leaves one MFMA K-row sums    // its chunk range is reduced in this many parallel segments
 
 enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
 
@@ -69,6 +70,12 @@ struct conststn_plan_s {
     cst::DevBuf<int64_t> row_leaf;         // [rows+1] first leaf of each row
     cst::DevBuf<int32_t> row_j;            // [rows] level-1 index of the row's fiber
     cst::DevBuf<int64_t> slice_row;        // [slices+1] first row of each slice
+    // TTMc order-4 MFMA path: level-2 nodes cut into "pieces" of at most kPieceLeaves leaves,
+    // level-1 fibers cut into rows of at most 4 pieces; rows index pieces, pieces index leaves
+    int64_t n_pieces = 0;
+    cst::DevBuf<int64_t> piece_leaf;       // [pieces+1] first leaf of each piece
+    cst::DevBuf<int32_t> piece_k;          // [pieces] level-2 index of the piece's node
+    cst::DevBuf<int64_t> row_piece;        // [rows+1] first piece of each row
     cst::DevBuf<double> partial;           // partial row blocks
     // three-tensor network
     cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1
