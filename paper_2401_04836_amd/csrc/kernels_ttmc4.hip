@@ -134,11 +134,16 @@ struct Ttmc4RowArgs {
     int compact;
 };
 
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4)))
+// PARTS waves share an item, each owning 16/PARTS of the column tiles (fewer accumulator
+// registers, more resident waves; the cheap mid level is repeated by every part).
+template <int PARTS>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PARTS == 1 ? 2 : (PARTS == 2 ? 3 : 5), 8)))
 ttmc4_mfma_kernel(Ttmc4RowArgs a) {
+    constexpr int TN = 16 / PARTS;
     __shared__ double t2buf[4][4 * kT2Stride];
     const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
-    const int64_t w = uni64(int64_t(blockIdx.x) * 4 + wv);
+    const int part = int(blockIdx.x % unsigned(PARTS));
+    const int64_t w = uni64(int64_t(blockIdx.x / unsigned(PARTS)) * 4 + wv);
     if (w >= a.n_items) return;
     const SliceItem it = a.items[w];
     const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
@@ -146,9 +151,9 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
     const int slot = lane >> 4, c = lane & 15;
     double *lds = t2buf[wv];
 
-    v4d acc[16];
+    v4d acc[TN];
 #pragma unroll
-    for (int t = 0; t < 16; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < TN; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
 
     // row descriptors of a K-step: piece ranges of its four rows (every lane), j of row g+slot
     struct Rows { int64_t pa[4]; int pn[4]; int32_t j; };
@@ -217,8 +222,8 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
         }
         // slice level: slot s supplies row s; 16 column tiles t = r2
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const double bv = lds[slot * kT2Stride + t * 16 + c];
+        for (int t = 0; t < TN; ++t) {
+            const double bv = lds[slot * kT2Stride + (part * TN + t) * 16 + c];
             acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[t], 0, 0, 0);
         }
         cur = nxt;
@@ -226,11 +231,11 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
     const int64_t RR = 4096;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
                             : a.partial + dest * RR;
-    // acc[t][v] = Y[r1 = slot + 4v][r2 = t][r3 = c]
+    // acc[t][v] = Y[r1 = slot + 4v][r2 = part*TN + t][r3 = c]
 #pragma unroll
-    for (int t = 0; t < 16; ++t)
+    for (int t = 0; t < TN; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) base[((slot + 4 * v) * 16 + t) * 16 + c] = acc[t][v];
+        for (int v = 0; v < 4; ++v) base[((slot + 4 * v) * 16 + part * TN + t) * 16 + c] = acc[t][v];
 }
 
 conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *dense, double *out,
@@ -281,7 +286,14 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
             ra.out = out;
             ra.partial = a.partial;
             ra.compact = a.compact;
-            ttmc4_mfma_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(ra);
+            const int64_t groups = div_up(a.n_items, 4);
+            const int64_t parts = env_int("CONSTSTN_TTMC4_PARTS", 1);
+            if (parts == 4)
+                ttmc4_mfma_kernel<4><<<dim3(unsigned(groups * 4)), dim3(256), 0, stream>>>(ra);
+            else if (parts == 2)
+                ttmc4_mfma_kernel<2><<<dim3(unsigned(groups * 2)), dim3(256), 0, stream>>>(ra);
+            else
+                ttmc4_mfma_kernel<1><<<dim3(unsigned(groups)), dim3(256), 0, stream>>>(ra);
         } else
             ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
     }
