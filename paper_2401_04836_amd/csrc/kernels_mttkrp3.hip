@@ -29,6 +29,7 @@ struct MttkrpArgs {
     const int32_t *heavy_slices;
     double *heavy_partial;
     int n_heavy;
+    int accumulate;            // add to what `out` already holds (second sub-tensor of the split path)
 };
 
 template <bool VEC>
@@ -183,14 +184,20 @@ __device__ __forceinline__ int row_rank_of_flag(bool flag, int gl, int &row_tota
     return __popc(row & ((1u << gl) - 1u));
 }
 
-template <int BLOCK>
+// MODE 0: hot and cold leaves mixed in one stream; MODE 1: every leaf is hot (LDS only);
+// MODE 2: every leaf is cold (no LDS).  Modes 1 and 2 serve the split path, where the plan has
+// separated the tensor into a hot and a cold sub-tensor: the hot pass then issues no gather to
+// the vector-memory path for leaf rows and the cold pass issues only fully populated ones.
+template <int BLOCK, int MODE>
 __global__ void __launch_bounds__(BLOCK)
 mttkrp3_r32_kernel(MttkrpR32Args aa) {
     extern __shared__ double2 hot[];                       // n_hot rows x 16 double2
     const MttkrpArgs &a = aa.base;
-    for (int e = threadIdx.x; e < aa.n_hot * 16; e += BLOCK)
-        hot[e] = reinterpret_cast<const double2 *>(a.C + int64_t(aa.hot_rows[e >> 4]) * 32)[e & 15];
-    __syncthreads();
+    if (MODE != 2) {
+        for (int e = threadIdx.x; e < aa.n_hot * 16; e += BLOCK)
+            hot[e] = reinterpret_cast<const double2 *>(a.C + int64_t(aa.hot_rows[e >> 4]) * 32)[e & 15];
+        __syncthreads();
+    }
     const int gl = threadIdx.x & 15;
     const lds_double2 *hot_lds = (const lds_double2 *)hot;
     const double2 *Cv = reinterpret_cast<const double2 *>(a.C);
@@ -219,6 +226,11 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             } else {
                 dst = reinterpret_cast<double2 *>(a.partial + (2 * c + (s == s_first ? 0 : 1)) * 32);
             }
+            if (a.accumulate && lo >= n0 && hi <= n1) {
+                const double2 old = dst[gl];
+                acc0 += old.x;
+                acc1 += old.y;
+            }
             dst[gl] = make_double2(acc0, acc1);
             acc0 = 0.0;
             acc1 = 0.0;
@@ -229,16 +241,21 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
         // the LDS read goes through an explicitly LDS-qualified pointer so that the compiler
         // cannot merge the two into one flat load.
         auto fetch_hot = [&](uint32_t cd) -> double2 {
-            const uint32_t slot = (cd & kHotBit) ? (cd & kRowMask) : 0u;
+            if (MODE == 2) return make_double2(0.0, 0.0);
+            const uint32_t slot = (MODE == 1 || (cd & kHotBit)) ? (cd & kRowMask) : 0u;
             const lds_double2 *src = hot_lds + (slot * 16 + gl);
             return make_double2(src->x, src->y);
         };
         auto fetch_cold = [&](uint32_t cd) -> double2 {
             double2 r;                                  // only read where the condition holds
+            if (MODE == 1) return make_double2(0.0, 0.0);
+            if (MODE == 2) return Cv[(cd & kRowMask) * 16u + uint32_t(gl)];
             if (!(cd & kHotBit)) r = Cv[(cd & kRowMask) * 16u + uint32_t(gl)];
             return r;
         };
         auto pick = [&](uint32_t cd, double2 h, double2 g) -> double2 {
+            if (MODE == 1) return h;
+            if (MODE == 2) return g;
             return (cd & kHotBit) ? h : g;
         };
         // B row of the fiber that ends at this leaf (no load when the leaf ends no fiber)
@@ -373,6 +390,10 @@ mttkrp3_fixup_kernel(MttkrpArgs a) {
             y += red[(gg * LPR + gl) * 2 + 1];
         }
         const int64_t row = a.compact ? s : int64_t(a.idx0[s]);
+        if (a.accumulate) {
+            if (r0 < R) x += a.out[row * R + r0];
+            if (r0 + 1 < R) y += a.out[row * R + r0 + 1];
+        }
         if (r0 < R) a.out[row * R + r0] = x;
         if (r0 + 1 < R) a.out[row * R + r0 + 1] = y;
     }
@@ -423,6 +444,7 @@ mttkrp3_fixup_final_kernel(MttkrpArgs a) {
     for (int seg = 0; seg < kHeavySegments; ++seg)
         x += a.heavy_partial[(int64_t(blockIdx.x) * kHeavySegments + seg) * a.R + r];
     const int64_t row = a.compact ? s : int64_t(a.idx0[s]);
+    if (a.accumulate) x += a.out[row * a.R + r];
     a.out[row * a.R + r] = x;
 }
 
@@ -488,34 +510,81 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
                          (reinterpret_cast<uintptr_t>(out) % 16 == 0);
     if (R > 128) { set_error("MTTKRP rank %d above 128 is not implemented", R); return CONSTSTN_EUNSUPPORTED; }
     if (R == 32 && aligned && plan->n_hot > 0 && plan->leaf_code.p) {
+        int dev = 0, cus = 256;
+        CST_HIP(hipGetDevice(&dev));
+        CST_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const size_t lds = size_t(plan->n_hot) * 256;
+        auto run = [&](const MttkrpR32Args &aa, int mode) -> conststn_status {
+            const size_t l = mode == 2 ? 0 : lds;
+            const int per_cu = mode == 2 ? 4 : std::max<int>(1, std::min<int>(int(160 * 1024 / std::max<size_t>(l, 1)), 4));
+            const int64_t wgs = std::min<int64_t>(div_up(aa.base.n_chunks, 32), int64_t(cus) * per_cu);
+            const dim3 grid(unsigned(std::max<int64_t>(wgs, 1))), block(512);
+            if (mode == 0) {
+                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 0>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(l)));
+                mttkrp3_r32_kernel<512, 0><<<grid, block, l, stream>>>(aa);
+            } else if (mode == 1) {
+                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 1>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(l)));
+                mttkrp3_r32_kernel<512, 1><<<grid, block, l, stream>>>(aa);
+            } else {
+                mttkrp3_r32_kernel<512, 2><<<grid, block, 0, stream>>>(aa);
+            }
+            CST_HIP(hipGetLastError());
+            return CONSTSTN_OK;
+        };
+        if (plan->split) {
+            // X = X_hot + X_cold: the hot sub-tensor writes the output, the cold one adds to it
+            CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
+            MttkrpR32Args pa[2];
+            for (int part = 0; part < 2; ++part) {
+                const MttkrpPart &P = plan->part[part];
+                MttkrpR32Args &aa = pa[part];
+                aa = MttkrpR32Args{};
+                aa.base = a;
+                aa.base.nnz = P.nnz;
+                aa.base.q = P.chunk_q;
+                aa.base.n_chunks = P.n_chunks;
+                aa.base.slices = P.slices;
+                aa.base.ptr0 = P.ptr0.p;
+                aa.base.ptr1 = P.ptr1.p;
+                aa.base.idx0 = P.row_of_slice.p;
+                aa.base.idx1 = P.idx1.p;
+                aa.base.idx2 = nullptr;
+                aa.base.vals = P.vals.p;
+                aa.base.chunk_fiber = P.chunk_fiber.p;
+                aa.base.chunk_slice = P.chunk_slice.p;
+                aa.base.slice_leaf = P.slice_leaf.p;
+                aa.base.partial = P.partial.p;
+                aa.base.compact = 0;                      // row_of_slice already maps to output rows
+                aa.base.heavy_slices = P.heavy_slices.p;
+                aa.base.heavy_partial = P.heavy_partial.p;
+                aa.base.n_heavy = P.n_heavy;
+                aa.base.accumulate = 1;                   // every writer adds to the zero-filled output
+                aa.code = P.code.p;
+                aa.hot_rows = plan->hot_rows.p;
+                aa.n_hot = plan->n_hot;
+                aa.fibers = P.fibers;
+            }
+            {
+                ProfScope prof(plan, stream);             // the two traversal kernels, back to back
+                if (plan->part[0].nnz > 0) CST_TRY(run(pa[0], 1));
+                if (plan->part[1].nnz > 0) CST_TRY(run(pa[1], 2));
+            }
+            for (int part = 0; part < 2; ++part)
+                if (plan->part[part].nnz > 0) CST_TRY(launch_fixup<16>(pa[part].base, stream));
+            return CONSTSTN_OK;
+        }
         MttkrpR32Args aa{};
         aa.base = a;
         aa.code = plan->leaf_code.p;
         aa.hot_rows = plan->hot_rows.p;
         aa.n_hot = plan->n_hot;
         aa.fibers = X->nodes[1];
-        const size_t lds = size_t(plan->n_hot) * 256;
-        int dev = 0, cus = 256;
-        CST_HIP(hipGetDevice(&dev));
-        CST_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        // as many resident workgroups per compute unit as the LDS footprint allows
-        const int64_t big = env_int("CONSTSTN_MTTKRP_BLOCK", lds > 80 * 1024 ? 1024 : 512);
-        const int per_cu = std::max<int>(1, std::min<int>(int(160 * 1024 / std::max<size_t>(lds, 1)), big == 1024 ? 2 : 4));
-        const int64_t chunks_per_wg = big / 16;
-        const int64_t wgs = std::min<int64_t>(div_up(a.n_chunks, chunks_per_wg), int64_t(cus) * per_cu);
         {
             ProfScope prof(plan, stream);
-            if (big == 1024) {
-                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<1024>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
-                mttkrp3_r32_kernel<1024><<<dim3(unsigned(wgs)), dim3(1024), lds, stream>>>(aa);
-            } else {
-                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
-                mttkrp3_r32_kernel<512><<<dim3(unsigned(wgs)), dim3(512), lds, stream>>>(aa);
-            }
+            CST_TRY(run(aa, 0));
         }
-        CST_HIP(hipGetLastError());
         return launch_fixup<16>(a, stream);
     }
     // smallest power-of-two lane group covering ceil(R/2) lanes; 16-byte accesses when every

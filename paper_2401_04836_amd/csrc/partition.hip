@@ -142,6 +142,166 @@ __global__ void mark_ends_kernel(int64_t nodes, const int64_t *__restrict__ leaf
     if (p < nodes) atomicOr(&code[leaf_end[p + 1] - 1], bit);
 }
 
+// ---- MTTKRP rank-32 path, split form: filter the CSF by a leaf predicate ----------------------
+
+__global__ void hot_flags_kernel(int64_t nnz, const int32_t *__restrict__ leaf,
+                                 const int32_t *__restrict__ slot_of_row, int64_t *flag) {
+    int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (; n < nnz; n += stride) flag[n] = slot_of_row[leaf[n]] >= 0 ? 1 : 0;
+}
+
+// position of leaf boundary x inside the part (part 0: hot leaves, part 1: the others)
+__device__ __forceinline__ int64_t part_pos(int64_t x, const int64_t *__restrict__ pos_hot, int64_t nnz,
+                                            int64_t total_hot, int part) {
+    const int64_t h = x < nnz ? pos_hot[x] : total_hot;
+    return part == 0 ? h : x - h;
+}
+
+__global__ void part_fiber_keep_kernel(int64_t fibers, const int64_t *__restrict__ ptr1,
+                                       const int64_t *__restrict__ pos_hot, int64_t nnz, int64_t total_hot,
+                                       int part, int64_t *keep) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f >= fibers) return;
+    keep[f] = part_pos(ptr1[f + 1], pos_hot, nnz, total_hot, part) > part_pos(ptr1[f], pos_hot, nnz, total_hot, part) ? 1 : 0;
+}
+
+__global__ void part_slice_keep_kernel(int64_t slices, const int64_t *__restrict__ ptr0,
+                                       const int64_t *__restrict__ fpos, int64_t fibers, int64_t kept_fibers,
+                                       int64_t *keep) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s >= slices) return;
+    const int64_t a = fpos[ptr0[s]];
+    const int64_t b = ptr0[s + 1] < fibers ? fpos[ptr0[s + 1]] : kept_fibers;
+    keep[s] = b > a ? 1 : 0;
+}
+
+__global__ void part_fill_leaves_kernel(int64_t nnz, const int32_t *__restrict__ leaf,
+                                        const double *__restrict__ vals, const int32_t *__restrict__ slot_of_row,
+                                        const int64_t *__restrict__ pos_hot, int part, uint32_t *code, double *out_vals) {
+    int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (; n < nnz; n += stride) {
+        const int32_t k = leaf[n];
+        const int32_t sl = slot_of_row[k];
+        if ((sl >= 0) != (part == 0)) continue;
+        const int64_t p = part == 0 ? pos_hot[n] : n - pos_hot[n];
+        code[p] = part == 0 ? (0x80000000u | uint32_t(sl)) : uint32_t(k);
+        out_vals[p] = vals[n];
+    }
+}
+
+__global__ void part_fill_fibers_kernel(int64_t fibers, const int64_t *__restrict__ ptr1,
+                                        const int32_t *__restrict__ idx1, const int64_t *__restrict__ pos_hot,
+                                        int64_t nnz, int64_t total_hot, int part, const int64_t *__restrict__ keep,
+                                        const int64_t *__restrict__ fpos, int64_t kept, int64_t part_nnz,
+                                        int64_t *ptr1_out, int32_t *idx1_out) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f == 0) ptr1_out[kept] = part_nnz;
+    if (f >= fibers || !keep[f]) return;
+    ptr1_out[fpos[f]] = part_pos(ptr1[f], pos_hot, nnz, total_hot, part);
+    idx1_out[fpos[f]] = idx1[f];
+}
+
+__global__ void part_fill_slices_kernel(int64_t slices, const int64_t *__restrict__ ptr0,
+                                        const int32_t *__restrict__ idx0, int compact,
+                                        const int64_t *__restrict__ keep, const int64_t *__restrict__ spos,
+                                        const int64_t *__restrict__ fpos, int64_t kept_slices, int64_t kept_fibers,
+                                        int64_t *ptr0_out, int32_t *row_out) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s == 0) ptr0_out[kept_slices] = kept_fibers;
+    if (s >= slices || !keep[s]) return;
+    ptr0_out[spos[s]] = fpos[ptr0[s]];
+    row_out[spos[s]] = compact ? int32_t(s) : idx0[s];
+}
+
+static conststn_status build_part_tables(MttkrpPart &P, int R, int64_t q) {
+    const dim3 block(256);
+    CST_TRY(P.slice_leaf.alloc(size_t(P.slices) + 1));
+    slice_leaf_kernel<<<dim3(unsigned(div_up(P.slices + 1, 256))), block>>>(P.slices, 2, P.ptr0.p, P.ptr1.p, nullptr,
+                                                                          P.slice_leaf.p);
+    CST_HIP(hipGetLastError());
+    mark_ends_kernel<<<dim3(unsigned(div_up(P.fibers, 256))), block>>>(P.fibers, P.ptr1.p, 0x40000000u, P.code.p);
+    mark_ends_kernel<<<dim3(unsigned(div_up(P.slices, 256))), block>>>(P.slices, P.slice_leaf.p, 0x20000000u, P.code.p);
+    CST_HIP(hipGetLastError());
+    P.chunk_q = q;
+    P.n_chunks = div_up(P.nnz, q);
+    CST_TRY(P.chunk_fiber.alloc(size_t(P.n_chunks)));
+    CST_TRY(P.chunk_slice.alloc(size_t(P.n_chunks)));
+    CST_TRY(P.partial.alloc(size_t(P.n_chunks) * 2 * size_t(R)));
+    mttkrp_chunks_kernel<<<dim3(unsigned(div_up(P.n_chunks, 256))), block>>>(P.n_chunks, q, P.slices, P.fibers,
+                                                                           P.ptr0.p, P.ptr1.p, P.chunk_fiber.p,
+                                                                           P.chunk_slice.p);
+    CST_HIP(hipGetLastError());
+    const int64_t max_heavy = P.nnz / (int64_t(kHeavySpan) * q) + 1;
+    CST_TRY(P.heavy_slices.alloc(size_t(max_heavy)));
+    DevBuf<int> hcount;
+    CST_TRY(hcount.alloc(1));
+    CST_HIP(hipMemset(hcount.p, 0, sizeof(int)));
+    heavy_slices_kernel<<<dim3(unsigned(div_up(P.slices, 256))), block>>>(P.slices, P.slice_leaf.p, q, kHeavySpan,
+                                                                         P.heavy_slices.p, hcount.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipMemcpy(&P.n_heavy, hcount.p, sizeof(int), hipMemcpyDeviceToHost));
+    CST_TRY(P.heavy_partial.alloc(size_t(P.n_heavy) * kHeavySegments * size_t(R)));
+    return CONSTSTN_OK;
+}
+
+static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
+
+static conststn_status build_mttkrp3_split(conststn_plan_s *plan, const int32_t *slot_of_row) {
+    const conststn_csf_s *X = plan->X;
+    const int64_t nnz = X->nnz, fibers = X->nodes[1], slices = X->nodes[0];
+    const int R = plan->rank_of_level[1];
+    const dim3 block(256);
+    DevBuf<int64_t> flag, pos_hot;
+    CST_TRY(flag.alloc(nnz));
+    CST_TRY(pos_hot.alloc(nnz));
+    hot_flags_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 16384))), block>>>(nnz, X->idx[2].p, slot_of_row, flag.p);
+    CST_HIP(hipGetLastError());
+    int64_t total_hot = 0;
+    CST_TRY(exscan(flag.p, pos_hot.p, nnz, &total_hot));
+    flag.release();
+    for (int part = 0; part < 2; ++part) {
+        MttkrpPart &P = plan->part[part];
+        P.nnz = part == 0 ? total_hot : nnz - total_hot;
+        P.slices = P.fibers = 0;
+        P.n_chunks = 0;
+        if (P.nnz == 0) continue;
+        DevBuf<int64_t> keepf, fpos, keeps, spos;
+        CST_TRY(keepf.alloc(fibers));
+        CST_TRY(fpos.alloc(fibers));
+        CST_TRY(keeps.alloc(slices));
+        CST_TRY(spos.alloc(slices));
+        part_fiber_keep_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(fibers, X->ptr[1].p, pos_hot.p, nnz,
+                                                                              total_hot, part, keepf.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(keepf.p, fpos.p, fibers, &P.fibers));
+        part_slice_keep_kernel<<<dim3(unsigned(div_up(slices, 256))), block>>>(slices, X->ptr[0].p, fpos.p, fibers,
+                                                                              P.fibers, keeps.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(keeps.p, spos.p, slices, &P.slices));
+        CST_TRY(P.code.alloc(size_t(P.nnz)));
+        CST_TRY(P.vals.alloc(size_t(P.nnz)));
+        CST_TRY(P.ptr1.alloc(size_t(P.fibers) + 1));
+        CST_TRY(P.idx1.alloc(size_t(P.fibers)));
+        CST_TRY(P.ptr0.alloc(size_t(P.slices) + 1));
+        CST_TRY(P.row_of_slice.alloc(size_t(P.slices)));
+        part_fill_leaves_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 16384))), block>>>(
+            nnz, X->idx[2].p, X->vals.p, slot_of_row, pos_hot.p, part, P.code.p, P.vals.p);
+        part_fill_fibers_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
+            fibers, X->ptr[1].p, X->idx[1].p, pos_hot.p, nnz, total_hot, part, keepf.p, fpos.p, P.fibers, P.nnz,
+            P.ptr1.p, P.idx1.p);
+        part_fill_slices_kernel<<<dim3(unsigned(div_up(slices, 256))), block>>>(
+            slices, X->ptr[0].p, X->idx[0].p, plan->compact ? 1 : 0, keeps.p, spos.p, fpos.p, P.slices, P.fibers,
+            P.ptr0.p, P.row_of_slice.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(build_part_tables(P, R, plan->chunk_q));
+        CST_HIP(hipDeviceSynchronize());
+    }
+    plan->split = true;
+    return CONSTSTN_OK;
+}
+
 static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t nnz = X->nnz;
@@ -187,6 +347,7 @@ static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
     CST_HIP(hipGetLastError());
     CST_HIP(hipDeviceSynchronize());
     plan->n_hot = int(want);
+    if (env_int("CONSTSTN_MTTKRP_SPLIT", 1) == 1) CST_TRY(build_mttkrp3_split(plan, slot_of_row.p));
     return CONSTSTN_OK;
 }
 

@@ -25,6 +25,25 @@ struct SliceItem {
     int64_t dest;
 };
 
+// One of the two sub-tensors of the split rank-32 MTTKRP path: the leaves whose factor row is
+// "hot" (kept in LDS) or the rest.  X = X_hot + X_cold and the contraction is linear in X, so each
+// part is a CSF tensor of its own (only the slices and fibers that keep a leaf) with its own
+// chunk tables; the second part accumulates onto the output of the first.
+struct MttkrpPart {
+    int64_t slices = 0, fibers = 0, nnz = 0;
+    DevBuf<int32_t> row_of_slice, idx1;
+    DevBuf<int64_t> ptr0, ptr1;
+    DevBuf<uint32_t> code;                 // leaf index or LDS slot, with end-of-fiber / end-of-slice marks
+    DevBuf<double> vals;
+    DevBuf<int64_t> slice_leaf, chunk_fiber;
+    DevBuf<int32_t> chunk_slice;
+    int64_t chunk_q = 0, n_chunks = 0;
+    DevBuf<double> partial;
+    DevBuf<int32_t> heavy_slices;
+    DevBuf<double> heavy_partial;
+    int n_heavy = 0;
+};
+
 }  // namespace cst
 
 struct conststn_plan_s {
@@ -53,6 +72,8 @@ struct conststn_plan_s {
     cst::DevBuf<uint32_t> leaf_code;
     cst::DevBuf<int32_t> hot_rows;         // [n_hot] leaf index held by each LDS slot
     int n_hot = 0;
+    bool split = false;                    // hot and cold leaves run as two sub-tensors
+    cst::MttkrpPart part[2];
     // slices shared by very many chunks get a two-stage fix-up
     cst::DevBuf<int32_t> heavy_slices;
     cst::DevBuf<double> heavy_partial;     // [n_heavy x kHeavySegments x R]
