@@ -209,14 +209,16 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int64_t RR = int64_t(R2) * R3;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
                             : a.partial + dest * RR;
-    // tile (p,q): accumulator register v of a lane holds row 16p + slot + 4v, column 16q + c
+    // tile (p,q): accumulator register v of a lane holds row 16p + slot + 4v, column 16q + c.
+    // The row block is written once and never re-read by this kernel: streaming (non-temporal)
+    // stores keep the gathered factor rows resident in L2 instead of the output.
 #pragma unroll
     for (int p = 0; p < PN; ++p)
 #pragma unroll
         for (int q = 0; q < QN; ++q)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                base[int64_t(16 * p + slot + 4 * v) * R3 + col0 + 16 * q] = acc[p][q][v];
+                __builtin_nontemporal_store(acc[p][q][v], base + int64_t(16 * p + slot + 4 * v) * R3 + col0 + 16 * q);
 }
 
 template <int PN>
