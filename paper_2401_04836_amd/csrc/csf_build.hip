@@ -3,16 +3,16 @@
 // Steps, all on the device:
 //   1. pack each coordinate tuple, permuted into level order, into one 64-bit key (outermost
 //      level in the most significant bits) and check ranges;
-//   2. stable radix sort of (key, original position) -- lexicographic order in mode_order;
+//   2. stable radix sort of (key, original position) -- lexicographic order in mode_order
+//      (own LSD sort, 8 bits per pass, see below);
 //   3. per tile, count for every level the positions where the key prefix of that level
 //      changes ("head" of a node); a duplicate coordinate is a position whose full key
 //      equals its predecessor's;
 //   4. scan the tile counts; the host reads the node totals and allocates the level arrays;
 //   5. per tile, rank the heads (block scan) and emit idx[l], ptr[l] and the permuted values.
 // The result is the canonical array layout documented in include/conststn.h.
-#include <cstring>
 #include <algorithm>
-#include <rocprim/rocprim.hpp>
+#include <cstring>
 
 #include "common.hpp"
 
@@ -126,6 +126,87 @@ scan_tiles_kernel(const unsigned *__restrict__ tile_counts, int64_t *__restrict_
     for (int64_t t = b; t < e; ++t) { out[t] = run; run += in[t]; }
 }
 
+// ---- stable LSD radix sort of (key, position) pairs, 8 bits per pass ------------------------
+//
+// One wavefront owns a tile of kSortItems*64 consecutive pairs.  Per pass: (1) every wave counts
+// the digits of its tile; (2) scan_tiles_kernel (one block per digit value) turns the counts into
+// the tile's starting offset inside each digit's bucket, a one-wave kernel turns the bucket totals
+// into bucket bases; (3) every wave re-reads its tile in order, 64 pairs at a time, ranks each
+// pair among the lanes holding the same digit (eight ballots narrow the set of peers) and scatters.
+// Tiles are visited in index order inside a bucket and pairs in order inside a tile, so the sort
+// is stable, which the CSF needs: equal keys (duplicates) must keep input order.
+constexpr int kSortItems = 16;
+constexpr int kSortTile = kSortItems * 64;
+
+__global__ void __launch_bounds__(256)
+radix_count_kernel(int64_t n, const uint64_t *__restrict__ keys, int shift, unsigned *__restrict__ tile_counts,
+                   int64_t ntiles) {
+    __shared__ unsigned hist[4][256];
+    const int wv = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int64_t tile = int64_t(blockIdx.x) * 4 + wv;
+    for (int d = lane; d < 256; d += 64) hist[wv][d] = 0;
+    __builtin_amdgcn_wave_barrier();
+    if (tile < ntiles) {
+        const int64_t base = tile * kSortTile;
+        for (int i = 0; i < kSortItems; ++i) {
+            const int64_t e = base + int64_t(i) * 64 + lane;
+            if (e < n) atomicAdd(&hist[wv][unsigned(keys[e] >> shift) & 255u], 1u);
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int d = lane; d < 256; d += 64) tile_counts[int64_t(d) * ntiles + tile] = hist[wv][d];
+    }
+}
+
+__global__ void radix_bases_kernel(const int64_t *__restrict__ totals, int64_t *__restrict__ bases) {
+    // one wave: exclusive scan of the 256 bucket totals
+    const int lane = threadIdx.x;
+    int64_t v[4], s = 0;
+    for (int i = 0; i < 4; ++i) { v[i] = totals[lane * 4 + i]; s += v[i]; }
+    int64_t inc = s;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    int64_t run = inc - s;
+    for (int i = 0; i < 4; ++i) { bases[lane * 4 + i] = run; run += v[i]; }
+}
+
+__global__ void __launch_bounds__(256)
+radix_scatter_kernel(int64_t n, const uint64_t *__restrict__ keys_in, const uint32_t *__restrict__ pay_in,
+                     uint64_t *__restrict__ keys_out, uint32_t *__restrict__ pay_out, int shift,
+                     const int64_t *__restrict__ tile_offsets, const int64_t *__restrict__ bases, int64_t ntiles) {
+    __shared__ int64_t run[4][256];
+    const int wv = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int64_t tile = int64_t(blockIdx.x) * 4 + wv;
+    if (tile >= ntiles) return;
+    for (int d = lane; d < 256; d += 64) run[wv][d] = bases[d] + tile_offsets[int64_t(d) * ntiles + tile];
+    __builtin_amdgcn_wave_barrier();
+    const int64_t base = tile * kSortTile;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t e = base + int64_t(i) * 64 + lane;
+        const bool live = e < n;
+        uint64_t key = 0;
+        uint32_t pay = 0;
+        if (live) { key = keys_in[e]; pay = pay_in[e]; }
+        const unsigned digit = unsigned(key >> shift) & 255u;
+        unsigned long long peers = __builtin_amdgcn_ballot_w64(live);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (digit >> b) & 1u;
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(bit);
+            peers &= bit ? m : ~m;
+        }
+        const int rank = __popcll(peers & lt);
+        int64_t pos = 0;
+        if (live) pos = run[wv][digit] + rank;
+        __builtin_amdgcn_wave_barrier();
+        if (live && rank == 0) run[wv][digit] += __popcll(peers);      // the lowest peer advances the bucket
+        __builtin_amdgcn_wave_barrier();
+        if (live) { keys_out[pos] = key; pay_out[pos] = pay; }
+    }
+}
+
 __device__ __forceinline__ unsigned block_exclusive_scan(unsigned v, unsigned *wtot /*[4]*/) {
     const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
     unsigned inc = v;
@@ -147,7 +228,7 @@ __global__ void __launch_bounds__(kTileThreads)
 emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
                    const uint32_t *__restrict__ payload, const double *__restrict__ vals_in,
                    const int64_t *__restrict__ tile_offsets, int64_t ntiles, LevelOut out,
-                   double *__restrict__ vals_out) {
+                   double *__restrict__ vals_out, int has_dups) {
     __shared__ unsigned wtot[kTileThreads / 64];
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile + int64_t(threadIdx.x) * kItems;
@@ -189,7 +270,8 @@ emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
             // leaf head: its value is the sum of the run of equal keys, in input order
             // (the sort is stable); without duplicates the run has length one
             double s = vals_in[payload[n]];
-            for (int64_t m = n + 1; m < nnz && keys[m] == k[i]; ++m) s += vals_in[payload[m]];
+            if (has_dups)
+                for (int64_t m = n + 1; m < nnz && keys[m] == k[i]; ++m) s += vals_in[payload[m]];
             vals_out[pos[last]] = s;
         }
         for (int l = 0; l < lv.order; ++l)
@@ -271,16 +353,29 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     const uint64_t *skeys = keys_a.p;
     const uint32_t *spay = pay_a.p;
     if (total_bits > 0 && nnz > 1) {
-        size_t temp_bytes = 0;
-        CST_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys_a.p, keys_b.p, pay_a.p, pay_b.p,
-                                          size_t(nnz), 0u, unsigned(total_bits), stream));
-        DevBuf<char> temp;
-        CST_TRY(temp.alloc(temp_bytes));
-        CST_HIP(rocprim::radix_sort_pairs(temp.p, temp_bytes, keys_a.p, keys_b.p, pay_a.p, pay_b.p,
-                                          size_t(nnz), 0u, unsigned(total_bits), stream));
-        CST_HIP(hipStreamSynchronize(stream));      // temp is released at scope exit
-        skeys = keys_b.p;
-        spay = pay_b.p;
+        const int64_t stiles = div_up(nnz, kSortTile);
+        DevBuf<unsigned> scounts;
+        DevBuf<int64_t> soffsets, stotals, sbases;
+        CST_TRY(scounts.alloc(size_t(stiles) * 256));
+        CST_TRY(soffsets.alloc(size_t(stiles) * 256));
+        CST_TRY(stotals.alloc(256));
+        CST_TRY(sbases.alloc(256));
+        uint64_t *kin = keys_a.p, *kout = keys_b.p;
+        uint32_t *pin = pay_a.p, *pout = pay_b.p;
+        const dim3 sgrid(unsigned(div_up(stiles, 4))), sblock(256);
+        for (int shift = 0; shift < total_bits; shift += 8) {
+            radix_count_kernel<<<sgrid, sblock, 0, stream>>>(nnz, kin, shift, scounts.p, stiles);
+            scan_tiles_kernel<<<dim3(256), dim3(1024), 0, stream>>>(scounts.p, soffsets.p, stiles, stotals.p);
+            radix_bases_kernel<<<dim3(1), dim3(64), 0, stream>>>(stotals.p, sbases.p);
+            radix_scatter_kernel<<<sgrid, sblock, 0, stream>>>(nnz, kin, pin, kout, pout, shift, soffsets.p,
+                                                             sbases.p, stiles);
+            CST_HIP(hipGetLastError());
+            std::swap(kin, kout);
+            std::swap(pin, pout);
+        }
+        CST_HIP(hipStreamSynchronize(stream));      // the pass tables are released at scope exit
+        skeys = kin;
+        spay = pin;
     }
 
     const int64_t ntiles = div_up(nnz, kTile);
@@ -323,7 +418,7 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     csf->nnz = htotals[order - 1];
 
     emit_levels_kernel<<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
-        nnz, lv, skeys, spay, vals, tile_offsets.p, ntiles, lo, csf->vals.p);
+        nnz, lv, skeys, spay, vals, tile_offsets.p, ntiles, lo, csf->vals.p, hflags[1]);
     CST_HIP(hipGetLastError());
     close_ptrs_kernel<<<dim3(1), dim3(64), 0, stream>>>(lo, order, totals.p);
     CST_HIP(hipGetLastError());

@@ -104,6 +104,26 @@ __global__ void leaf_histogram_kernel(int64_t nnz, const int32_t *__restrict__ l
     for (; n < nnz; n += stride) atomicAdd(&counts[leaf[n]], 1u);
 }
 
+// The same histogram with block-private LDS counters for one window of kHistWindow bins; the
+// power-law tensors this path is meant for put a large share of the leaves in a few bins, which
+// serialises global atomics.
+constexpr int kHistWindow = 16384;
+__global__ void __launch_bounds__(256)
+leaf_histogram_window_kernel(int64_t nnz, const int32_t *__restrict__ leaf, int32_t lo, unsigned *counts, int64_t dim) {
+    __shared__ unsigned h[kHistWindow];
+    for (int b = threadIdx.x; b < kHistWindow; b += 256) h[b] = 0;
+    __syncthreads();
+    int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+    for (; n < nnz; n += stride) {
+        const unsigned k = unsigned(leaf[n] - lo);
+        if (k < unsigned(kHistWindow)) atomicAdd(&h[k], 1u);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < kHistWindow; b += 256)
+        if (h[b] && lo + b < dim) atomicAdd(&counts[lo + b], h[b]);
+}
+
 __global__ void iota_i32_kernel(int32_t *p, int64_t n) {
     const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n) p[i] = int32_t(i);
@@ -322,7 +342,13 @@ static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
     CST_TRY(slot_of_row.alloc(dim));
     CST_HIP(hipMemset(counts.p, 0, size_t(dim) * sizeof(unsigned)));
     const dim3 block(256);
-    leaf_histogram_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 8192))), block>>>(nnz, X->idx[2].p, counts.p);
+    if (dim <= 4 * kHistWindow) {
+        for (int64_t lo = 0; lo < dim; lo += kHistWindow)
+            leaf_histogram_window_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256 * 64), 2048))), block>>>(
+                nnz, X->idx[2].p, int32_t(lo), counts.p, dim);
+    } else {
+        leaf_histogram_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 8192))), block>>>(nnz, X->idx[2].p, counts.p);
+    }
     CST_HIP(hipGetLastError());
     iota_i32_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(rows.p, dim);
     fill_i32_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(slot_of_row.p, dim, -1);
