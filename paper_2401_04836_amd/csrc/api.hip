@@ -284,6 +284,14 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
     snprintf(head, sizeof(head), "family=%s rows=%lld row_elems=%lld compact=%d", family_name(plan->family),
              (long long)plan->out_rows, (long long)plan->row_elems, plan->compact ? 1 : 0);
     plan->description = head;
+    if (plan->family == FAM_SPTN3) {
+        char b[96];
+        if (plan->w_tiled)
+            snprintf(b, sizeof(b), " kernel=tiled k chunks %d w tiles %lld", plan->sp_kc, (long long)plan->n_w_tiles);
+        else
+            snprintf(b, sizeof(b), " kernel=baseline");
+        plan->description += b;
+    }
     for (size_t p = 0; p + 1 < plan->sched.stmts.size(); ++p) {
         char b[128];
         snprintf(b, sizeof(b), " %s:order%d", plan->sched.stmts[p].out.name.c_str(), plan->sched.stmts[p].reduced_order);

@@ -10,6 +10,8 @@
 // fibers of W below root k: lanes take the m leaves and add T[l]*W into a per-wavefront copy
 // of Z_i in LDS (no atomics: leaves of one fiber have distinct m).  The copies are added in
 // fixed order at the end, so results are bit-reproducible.
+#include <type_traits>
+
 #include "plan.hpp"
 
 namespace cst {
@@ -69,8 +71,399 @@ sptn3_kernel(Sptn3Args a) {
         a.out[row * M + m] = ((Zw[m] + Zw[M + m]) + Zw[2 * M + m]) + Zw[3 * M + m];
 }
 
+// ---- tiled kernel: both stages on the fp64 matrix cores --------------------------------------
+//
+// Sixteen root slices of U are taken together (a "group"); a workgroup owns one group and one
+// chunk of the k range and walks the k values present in any of its slices (a 16-way merge of
+// the slices' level-1 lists).  For one k:
+//   1. the j indices of the up to sixteen (i,k) fibers are merged through a bit mask in LDS into
+//      their sorted union; the fibers are scattered into a dense LDS tile Uc[union rank][i]
+//      (zero where a slice has no such j) -- at most kCap union rows per pass, more passes if
+//      the union is longer (each pass is a unit of its own: the consumer is linear in T);
+//   2. producer, per tile of 16 l values:  T^t[l, i] = sum_j V[j, l] Uc[j, i]  as 16x16x4 matrix
+//      instructions, A = V[j_s, l0 + c] (row segments of 128 B from L2), B = Uc[j_s, c];
+//   3. consumer: the accumulator registers of T^t are exactly the B operand layout, so
+//      Z^t[m, i] += sum_l W[l, m] T^t[l, i]  follows without any data movement, A = the dense
+//      16 x 16 tiles of W that the plan prepared (only tiles that hold a nonzero).
+// A wavefront owns every fourth l tile and accumulates its own Z^t (all m tiles) in registers
+// while it works on one k; after each k the four wavefronts add theirs, one after the other, to
+// the group's Z^t in LDS, and the partial results of the k chunks are added by a fix-up kernel in
+// chunk order, so results are bit-reproducible.  One wavefront per SIMD: latency is hidden by a
+// three-deep software pipeline over batches of four K-steps that runs across l tile boundaries;
+// every load in it is unconditional (clamped addresses), and the W tiles of the current l tile
+// are parked in a per-lane LDS area (indexable at run time, which registers are not).
+// The zero entries of Uc and of the W tiles multiply real factor values, so V must be finite.
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+typedef double v2d __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) v2d lds_v2d;
+
+constexpr int kCap = 320;             // union rows of Uc per pass (40 KB)
+constexpr int kStage = 6;             // W tiles parked in LDS per l tile and wavefront
+constexpr int kBatch = 4;             // K-steps per pipeline batch
+
+struct Sptn3TileArgs {
+    int64_t slices, L, M, LT;
+    int MT, nwords, n_groups, n_kc;
+    int64_t k_per;
+    const int64_t *uptr0, *uptr1;
+    const int32_t *uidx0, *uidx1, *uidx2;
+    const double *uvals;
+    const int64_t *w_root_of_k;
+    const uint32_t *wmask, *wfirst;
+    const double *wtiles;
+    uint32_t zero_tile;
+    const double *V;
+    double *out, *partial;
+    int compact;
+};
+
+__device__ inline int64_t lower_bound_i32(const int32_t *__restrict__ a, int64_t lo, int64_t hi, int64_t key) {
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (int64_t(a[mid]) < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+struct SpPipe {
+    double Vr[3][kBatch], Ur[3][kBatch];
+    int32_t Jr[3][kBatch];
+    v2d Wr[3][2];
+};
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+sptn3_tiled_kernel(Sptn3TileArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *Uc = reinterpret_cast<double *>(smem);                        // kCap x 16
+    double *Wb = Uc + kCap * 16;                                          // 4 x kStage x 256
+    double *Zs = Wb + 4 * kStage * 256;                                   // MT x 16 x 16: Z^t[m][i]
+    int32_t *jl = reinterpret_cast<int32_t *>(Zs + a.MT * 256);           // kCap: row offset j*L
+    uint32_t *mask = reinterpret_cast<uint32_t *>(jl + kCap);             // nwords
+    int32_t *wpre = reinterpret_cast<int32_t *>(mask + a.nwords);         // nwords
+    int32_t *scan = wpre + a.nwords;                                      // 8
+
+    const int tid = threadIdx.x, lane = tid & 63, slot = lane >> 4, c = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform, and known to be
+    const int group = int(blockIdx.x) % a.n_groups, kc = int(blockIdx.x) / a.n_groups;
+    const int64_t s0 = int64_t(group) * kSpGroup;
+    const int64_t k_lo = int64_t(kc) * a.k_per, k_hi = k_lo + a.k_per;
+    const int64_t L = a.L;
+    const int nwords = a.nwords;
+    double *Wbw = Wb + wave * (kStage * 256);
+    // the same area through an LDS-typed pointer, so that reads of it stay LDS instructions
+    const lds_v2d *Wpark = (const lds_v2d *)(Wbw);
+
+    // lane c (in each of the four lane rows) holds the cursor of slice s0 + c
+    int64_t cur = 0, end = 0;
+    if (s0 + c < a.slices) {
+        const int64_t na = a.uptr0[s0 + c], nb = a.uptr0[s0 + c + 1];
+        cur = lower_bound_i32(a.uidx1, na, nb, k_lo);
+        end = lower_bound_i32(a.uidx1, cur, nb, k_hi);
+    }
+    for (int x = tid; x < a.MT * 256; x += 256) Zs[x] = 0.0;
+
+    const int NTw = a.LT > wave ? int((a.LT - wave + 3) >> 2) : 0;       // l tiles of this wavefront
+
+    for (;;) {
+        const int32_t kk = cur < end ? a.uidx1[cur] : INT32_MAX;
+        int32_t kmin = kk;
+        kmin = min(kmin, __shfl_xor(kmin, 8, 16));
+        kmin = min(kmin, __shfl_xor(kmin, 4, 16));
+        kmin = min(kmin, __shfl_xor(kmin, 2, 16));
+        kmin = min(kmin, __shfl_xor(kmin, 1, 16));
+        kmin = __builtin_amdgcn_readfirstlane(kmin);
+        if (kmin == INT32_MAX) break;
+        const bool has = kk == kmin;
+        const int64_t f = cur;
+        cur += has ? 1 : 0;
+        const int64_t root = a.w_root_of_k[kmin];                         // same address in every lane
+        if (root < 0) continue;                                           // W has nothing at this k
+        int64_t la = 0, lb = 0;
+        if (has) { la = a.uptr1[f]; lb = a.uptr1[f + 1]; }
+        // this lane row scatters the fiber of slice 4*wave + slot
+        const int irow = 4 * wave + slot;
+        const int64_t ea = __shfl(la, irow), eb = __shfl(lb, irow);
+
+        __syncthreads();                                                  // LDS of the previous k is free
+        for (int w = tid; w < nwords; w += 256) mask[w] = 0u;
+        __syncthreads();
+        for (int64_t e = ea + c; e < eb; e += 16) {
+            const int32_t j = a.uidx2[e];
+            atomicOr(&mask[j >> 5], 1u << (j & 31));
+        }
+        __syncthreads();
+        {   // exclusive prefix of the set-bit counts of the mask words (thread t: words 4t .. 4t+3)
+            int cnt[4], mine = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int w = 4 * tid + q;
+                cnt[q] = w < nwords ? __popc(mask[w]) : 0;
+                mine += cnt[q];
+            }
+            int incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d);
+                if (lane >= d) incl += up;
+            }
+            if (lane == 63) scan[wave] = incl;
+            __syncthreads();
+            int base = 0;
+            for (int w = 0; w < wave; ++w) base += scan[w];
+            int run = base + incl - mine;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int w = 4 * tid + q;
+                if (w < nwords) wpre[w] = run;
+                run += cnt[q];
+            }
+        }
+        const int n_union = __builtin_amdgcn_readfirstlane(scan[0] + scan[1] + scan[2] + scan[3]);
+        __syncthreads();
+
+        for (int p0 = 0; p0 < n_union; p0 += kCap) {
+            const int np = min(kCap, n_union - p0);
+            const int npad = (np + 4 * kBatch - 1) & ~(4 * kBatch - 1);   // whole batches
+            if (p0 > 0) __syncthreads();
+            for (int x = tid; x < npad * 16; x += 256) Uc[x] = 0.0;
+            if (tid < npad - np) jl[np + tid] = 0;
+            for (int w = tid; w < nwords; w += 256) {
+                uint32_t m = mask[w];
+                int r = wpre[w] - p0;
+                while (m) {
+                    const int b = __builtin_ctz(m);
+                    m &= m - 1u;
+                    if (r >= 0 && r < np) jl[r] = int32_t(int64_t(w * 32 + b) * L);
+                    ++r;
+                }
+            }
+            __syncthreads();
+            for (int64_t e = ea + c; e < eb; e += 16) {
+                const int32_t j = a.uidx2[e];
+                const int r = wpre[j >> 5] + __popc(mask[j >> 5] & ((1u << (j & 31)) - 1u)) - p0;
+                if (r >= 0 && r < np) Uc[r * 16 + irow] = a.uvals[e];
+            }
+            __syncthreads();
+
+            // ---- the two matrix stages over this wavefront's l tiles, 64 tiles per round ----
+            v4d accZ[kSpMaxMTiles];
+#pragma unroll
+            for (int mt = 0; mt < kSpMaxMTiles; ++mt) accZ[mt] = v4d{0.0, 0.0, 0.0, 0.0};
+            const int nBt = npad / (4 * kBatch);                          // batches per l tile
+            for (int tr = 0; tr < NTw; tr += 64) {
+                const int NT = min(64, NTw - tr);
+                // lane t holds mask and first tile of its t-th l tile of this round
+                uint32_t mreg = 0u, freg = a.zero_tile;
+                if (lane < NT) {
+                    const int64_t cell = root * a.LT + (wave + 4 * (tr + lane));
+                    mreg = a.wmask[cell];
+                    freg = mreg ? a.wfirst[cell] : a.zero_tile;
+                }
+                const int TB = NT * nBt;
+                SpPipe P;
+                v4d accT0 = v4d{0.0, 0.0, 0.0, 0.0}, accT1 = accT0;
+                // stream positions: (t, q) = (l tile of the round, batch inside it)
+                int t0 = 0, q0 = 0;                                       // batch being consumed
+                int t2 = 0, q2 = 0;                                       // batch whose V/U/W loads are issued
+                int q3 = 0;                                               // batch whose j offsets are read
+
+                auto read_j = [&](int32_t (&J)[kBatch]) {
+#pragma unroll
+                    for (int ks = 0; ks < kBatch; ++ks) J[ks] = jl[q3 * (4 * kBatch) + ks * 4 + slot];
+                    q3 = q3 + 1 == nBt ? 0 : q3 + 1;
+                };
+                auto issue = [&](const int32_t (&J)[kBatch], double (&Vv)[kBatch], double (&Uu)[kBatch], v2d (&Ww)[2]) {
+                    const int tt = min(t2, NT - 1);
+                    const int col = int(min(int64_t(16 * (wave + 4 * (tr + tt)) + c), L - 1));
+#pragma unroll
+                    for (int ks = 0; ks < kBatch; ++ks) {
+                        Vv[ks] = a.V[J[ks] + col];
+                        Uu[ks] = Uc[q2 * (64 * kBatch) + ks * 64 + lane];
+                    }
+                    const uint32_t m2 = __builtin_amdgcn_readlane(mreg, tt);
+                    const uint32_t f2 = __builtin_amdgcn_readlane(freg, tt);
+                    const int have = __popc(m2);
+                    const int tq = max(min(min(q2, kStage - 1), have - 1), 0);
+                    const double *tp = a.wtiles + (int64_t(f2) + tq) * 256 + lane * 2;
+                    Ww[0] = *reinterpret_cast<const v2d *>(tp);
+                    Ww[1] = *reinterpret_cast<const v2d *>(tp + 128);
+                    if (q2 + 1 == nBt) { q2 = 0; ++t2; } else ++q2;
+                };
+                auto consume = [&](int b, const double (&Vv)[kBatch], const double (&Uu)[kBatch], const v2d (&Ww)[2]) {
+                    // park the W tile that came with this batch
+                    double *wp = Wbw + min(q0, kStage - 1) * 256 + lane * 2;
+                    *reinterpret_cast<v2d *>(wp) = Ww[0];
+                    *reinterpret_cast<v2d *>(wp + 128) = Ww[1];
+                    if (b < TB) {
+                        accT0 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[0], Uu[0], accT0, 0, 0, 0);
+                        accT1 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[1], Uu[1], accT1, 0, 0, 0);
+                        accT0 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[2], Uu[2], accT0, 0, 0, 0);
+                        accT1 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[3], Uu[3], accT1, 0, 0, 0);
+                        if (q0 + 1 == nBt) {
+                            // consumer: Z^t += W^t . T^t for the m tiles present below this l tile
+                            const v4d T = accT0 + accT1;
+                            const uint32_t m0 = __builtin_amdgcn_readlane(mreg, t0);
+                            const uint32_t f0 = __builtin_amdgcn_readlane(freg, t0);
+                            const int staged = min(nBt, kStage);
+                            auto tiles = [&](auto from_memory) {
+                                int p = 0;
+#pragma unroll
+                                for (int mt = 0; mt < kSpMaxMTiles; ++mt) {
+                                    if ((m0 >> mt) & 1u) {
+                                        // parked tile (the address is always inside the area)
+                                        const lds_v2d *rp = Wpark + (min(p, staged - 1) * 128 + lane);
+                                        v2d w0 = rp[0], w1 = rp[64];
+                                        if (decltype(from_memory)::value && p >= staged) {
+                                            const double *tp = a.wtiles + (int64_t(f0) + p) * 256 + lane * 2;
+                                            w0 = *reinterpret_cast<const v2d *>(tp);
+                                            w1 = *reinterpret_cast<const v2d *>(tp + 128);
+                                        }
+                                        v4d z = accZ[mt];
+                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.x, T.x, z, 0, 0, 0);
+                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.y, T.y, z, 0, 0, 0);
+                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.x, T.z, z, 0, 0, 0);
+                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.y, T.w, z, 0, 0, 0);
+                                        accZ[mt] = z;
+                                        ++p;
+                                    }
+                                }
+                            };
+                            // the usual case has every tile parked and touches no memory, so it
+                            // does not wait for the loads in flight; more tiles than parked: rare
+                            if (__popc(m0) <= staged) tiles(std::false_type{});
+                            else tiles(std::true_type{});
+                            accT0 = v4d{0.0, 0.0, 0.0, 0.0};
+                            accT1 = accT0;
+                            q0 = 0;
+                            ++t0;
+                        } else {
+                            ++q0;
+                        }
+                    }
+                };
+
+                if (TB > 0) {
+                    read_j(P.Jr[0]);
+                    read_j(P.Jr[1]);
+                    read_j(P.Jr[2]);
+                    issue(P.Jr[0], P.Vr[0], P.Ur[0], P.Wr[0]);
+                    issue(P.Jr[1], P.Vr[1], P.Ur[1], P.Wr[1]);
+                    for (int b = 0; b < TB; b += 3) {
+                        issue(P.Jr[2], P.Vr[2], P.Ur[2], P.Wr[2]);
+                        read_j(P.Jr[0]);
+                        consume(b, P.Vr[0], P.Ur[0], P.Wr[0]);
+                        issue(P.Jr[0], P.Vr[0], P.Ur[0], P.Wr[0]);
+                        read_j(P.Jr[1]);
+                        consume(b + 1, P.Vr[1], P.Ur[1], P.Wr[1]);
+                        issue(P.Jr[1], P.Vr[1], P.Ur[1], P.Wr[1]);
+                        read_j(P.Jr[2]);
+                        consume(b + 2, P.Vr[2], P.Ur[2], P.Wr[2]);
+                    }
+                }
+            }
+            // add this k's contribution to the group's Z^t, wavefront after wavefront
+            for (int w = 0; w < 4; ++w) {
+                if (wave == w) {
+#pragma unroll
+                    for (int mt = 0; mt < kSpMaxMTiles; ++mt) {
+                        if (mt < a.MT) {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) Zs[(16 * mt + slot + 4 * v) * 16 + c] += accZ[mt][v];
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+
+    // ---- store the group's rows ----------------------------------------------------------------
+    __syncthreads();
+    const int64_t M = a.M;
+    for (int64_t x = tid; x < 16 * M; x += 256) {
+        const int64_t i = x / M, m = x - i * M;
+        const int64_t s = s0 + i;
+        if (s >= a.slices) break;
+        const double z = Zs[m * 16 + i];
+        if (a.n_kc == 1) {
+            const int64_t row = a.compact ? s : int64_t(a.uidx0[s]);
+            a.out[row * M + m] = z;
+        } else {
+            a.partial[(int64_t(kc) * a.slices + s) * M + m] = z;
+        }
+    }
+}
+
+// sums the partial results of the k chunks in chunk order
+__global__ void sptn3_fixup_kernel(int64_t slices, int64_t M, int n_kc, const int32_t *__restrict__ uidx0,
+                                   const double *__restrict__ partial, double *out, int compact) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x >= slices * M) return;
+    const int64_t s = x / M, m = x - s * M;
+    double z = 0.0;
+    for (int kc = 0; kc < n_kc; ++kc) z += partial[(int64_t(kc) * slices + s) * M + m];
+    const int64_t row = compact ? s : int64_t(uidx0[s]);
+    out[row * M + m] = z;
+}
+
+static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const double *const *dense, double *out,
+                                          hipStream_t stream) {
+    const conststn_csf_s *U = plan->X, *W = plan->W;
+    Sptn3TileArgs a{};
+    a.slices = U->nodes[0];
+    a.L = W->dims[W->mode_order[1]];
+    a.M = W->dims[W->mode_order[2]];
+    a.LT = (a.L + 15) / 16;
+    a.MT = int((a.M + 15) / 16);
+    const int64_t J = U->dims[U->mode_order[2]];
+    a.nwords = int((J + 31) / 32);
+    a.n_groups = int((a.slices + kSpGroup - 1) / kSpGroup);
+    a.n_kc = plan->sp_kc;
+    a.k_per = plan->sp_k_per;
+    a.uptr0 = U->ptr[0].p;
+    a.uptr1 = U->ptr[1].p;
+    a.uidx0 = U->idx[0].p;
+    a.uidx1 = U->idx[1].p;
+    a.uidx2 = U->idx[2].p;
+    a.uvals = U->vals.p;
+    a.w_root_of_k = plan->w_root_of_k.p;
+    a.wmask = plan->w_tile_mask.p;
+    a.wfirst = plan->w_tile_first.p;
+    a.wtiles = plan->w_tiles.p;
+    a.zero_tile = uint32_t(plan->n_w_tiles);
+    a.V = dense[0];
+    a.out = out;
+    a.partial = plan->partial.p;
+    a.compact = plan->compact ? 1 : 0;
+    const size_t lds_bytes = size_t(kCap) * 16 * 8 + size_t(4 * kStage) * 256 * 8 + size_t(a.MT) * 256 * 8 +
+                             size_t(kCap) * 4 + size_t(a.nwords) * 8 + 64;
+    static bool attr_set = false;
+    if (!attr_set) {
+        CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sptn3_tiled_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set = true;
+    }
+    if (!plan->compact && a.slices < plan->out_rows)
+        CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
+    if (a.slices == 0) return CONSTSTN_OK;
+    {
+        ProfScope prof(plan, stream);
+        sptn3_tiled_kernel<<<dim3(unsigned(a.n_groups) * unsigned(a.n_kc)), dim3(256), lds_bytes, stream>>>(a);
+    }
+    CST_HIP(hipGetLastError());
+    if (a.n_kc > 1) {
+        const int64_t n = a.slices * a.M;
+        sptn3_fixup_kernel<<<dim3(unsigned((n + 255) / 256)), dim3(256), 0, stream>>>(
+            a.slices, a.M, a.n_kc, a.uidx0, a.partial, out, a.compact);
+        CST_HIP(hipGetLastError());
+    }
+    return CONSTSTN_OK;
+}
+
 conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream) {
+    if (plan->w_tiled) return launch_sptn3_tiled(plan, dense, out, stream);
     const conststn_csf_s *U = plan->X, *W = plan->W;
     Sptn3Args a{};
     a.slices = U->nodes[0];

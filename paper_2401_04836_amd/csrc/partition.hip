@@ -676,6 +676,116 @@ __global__ void w_roots_kernel(int64_t roots, const int32_t *__restrict__ idx0, 
     if (p < roots) root_of_k[idx0[p]] = p;
 }
 
+// ---- three-tensor network, tiled path: W re-stored as dense 16 x 16 (l, m) tiles -------------
+//
+// Below one root k of W the (l, m) plane is cut into tiles of 16 x 16; only the tiles that hold
+// a nonzero are kept, zero-filled elsewhere.  Per (root, l tile): a bit mask of the m tiles
+// present and the index of the first of them (tiles of one l tile are stored in m order).
+// Inside a tile the 256 values are laid out for the consumer's matrix instruction: value
+// (l', m') with l' = 4v + s sits at  (v/2)*128 + (s*16 + m')*2 + (v&1), so that lane (s, m') of
+// a wavefront reads its four values as two 16-byte words, the wavefront 1 KB at a time.
+
+__device__ inline int64_t root_of_fiber(const int64_t *__restrict__ ptr0, int64_t roots, int64_t g) {
+    int64_t lo = 0, hi = roots;                 // last root with ptr0[root] <= g
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr0[mid] <= g) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void w_tile_mask_kernel(int64_t fibers, int64_t roots, int64_t LT,
+                                   const int64_t *__restrict__ ptr0, const int64_t *__restrict__ ptr1,
+                                   const int32_t *__restrict__ idx1, const int32_t *__restrict__ idx2,
+                                   uint32_t *mask) {
+    const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g >= fibers) return;
+    const int64_t r = root_of_fiber(ptr0, roots, g);
+    uint32_t mine = 0;
+    for (int64_t e = ptr1[g]; e < ptr1[g + 1]; ++e) mine |= 1u << (idx2[e] >> 4);
+    atomicOr(&mask[r * LT + (idx1[g] >> 4)], mine);
+}
+
+__global__ void w_tile_count_kernel(int64_t n, const uint32_t *__restrict__ mask, int64_t *cnt) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < n) cnt[x] = __popc(mask[x]);
+}
+
+__global__ void w_tile_fill_kernel(int64_t fibers, int64_t roots, int64_t LT,
+                                   const int64_t *__restrict__ ptr0, const int64_t *__restrict__ ptr1,
+                                   const int32_t *__restrict__ idx1, const int32_t *__restrict__ idx2,
+                                   const double *__restrict__ vals, const uint32_t *__restrict__ mask,
+                                   const int64_t *__restrict__ first, double *tiles) {
+    const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g >= fibers) return;
+    const int64_t r = root_of_fiber(ptr0, roots, g);
+    const int32_t l = idx1[g];
+    const int64_t cell = r * LT + (l >> 4);
+    const uint32_t present = mask[cell];
+    const int64_t base = first[cell];
+    const int lp = l & 15, v = lp >> 2, sl = lp & 3;
+    for (int64_t e = ptr1[g]; e < ptr1[g + 1]; ++e) {
+        const int32_t m = idx2[e];
+        const int mt = m >> 4;
+        const int64_t tile = base + __popc(present & ((1u << mt) - 1u));
+        tiles[tile * 256 + (v >> 1) * 128 + (sl * 16 + (m & 15)) * 2 + (v & 1)] = vals[e];
+    }
+}
+
+__global__ void w_first_u32_kernel(int64_t n, const int64_t *__restrict__ first, uint32_t *out) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < n) out[x] = uint32_t(first[x]);
+}
+
+static conststn_status build_w_tiles(conststn_plan_s *plan) {
+    const conststn_csf_s *U = plan->X, *W = plan->W;
+    const int64_t J = U->dims[U->mode_order[2]];
+    const int64_t L = W->dims[W->mode_order[1]], M = W->dims[W->mode_order[2]];
+    const int64_t K = W->dims[W->mode_order[0]];
+    plan->w_tiled = false;
+    if (env_int("CONSTSTN_SPTN3_TILED", 1) == 2) return CONSTSTN_OK;          // 2 = baseline kernel
+    if (M > 16 * kSpMaxMTiles || J > kSpMaxJ || J * L >= (int64_t(1) << 31) || W->nnz == 0 || U->nnz == 0)
+        return CONSTSTN_OK;
+    const int64_t roots = W->nodes[0], fibers = W->nodes[1];
+    const int64_t LT = div_up(L, 16), cells = roots * LT;
+    CST_TRY(plan->w_tile_mask.alloc(size_t(cells)));
+    const dim3 block(256), fgrid(unsigned(div_up(fibers, 256))), cgrid(unsigned(div_up(cells, 256)));
+    fill_i32_kernel<<<cgrid, block>>>(reinterpret_cast<int32_t *>(plan->w_tile_mask.p), cells, 0);
+    CST_HIP(hipGetLastError());
+    w_tile_mask_kernel<<<fgrid, block>>>(fibers, roots, LT, W->ptr[0].p, W->ptr[1].p, W->idx[1].p,
+                                         W->idx[2].p, plan->w_tile_mask.p);
+    CST_HIP(hipGetLastError());
+    DevBuf<int64_t> cnt, first;
+    CST_TRY(cnt.alloc(size_t(cells)));
+    CST_TRY(first.alloc(size_t(cells)));
+    w_tile_count_kernel<<<cgrid, block>>>(cells, plan->w_tile_mask.p, cnt.p);
+    CST_HIP(hipGetLastError());
+    int64_t n_tiles = 0;
+    CST_TRY(exscan(cnt.p, first.p, cells, &n_tiles));
+    if (n_tiles >= (int64_t(1) << 31) - 1) return CONSTSTN_OK;
+    plan->n_w_tiles = n_tiles;
+    // one more, all-zero tile at the end: the target of loads that have nothing to fetch
+    CST_TRY(plan->w_tiles.alloc(size_t(n_tiles + 1) * 256));
+    CST_TRY(zero_fill(plan->w_tiles.p, (n_tiles + 1) * 256, hipStream_t(0)));
+    w_tile_fill_kernel<<<fgrid, block>>>(fibers, roots, LT, W->ptr[0].p, W->ptr[1].p, W->idx[1].p,
+                                         W->idx[2].p, W->vals.p, plan->w_tile_mask.p, first.p,
+                                         plan->w_tiles.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(plan->w_tile_first.alloc(size_t(cells)));
+    w_first_u32_kernel<<<cgrid, block>>>(cells, first.p, plan->w_tile_first.p);
+    CST_HIP(hipGetLastError());
+    // slices go in groups of 16; the k range is cut into chunks so that the grid fills the chip
+    const int64_t groups = div_up(U->nodes[0], kSpGroup);
+    int64_t want = env_int("CONSTSTN_SPTN3_WGS", 3000);
+    int64_t n_kc = std::min<int64_t>(std::max<int64_t>(div_up(want, groups), 1), std::min<int64_t>(K, 64));
+    plan->sp_k_per = div_up(K, n_kc);
+    plan->sp_kc = int(div_up(K, plan->sp_k_per));
+    if (plan->sp_kc > 1)
+        CST_TRY(plan->partial.alloc(size_t(plan->sp_kc) * size_t(U->nodes[0]) * size_t(M)));
+    plan->w_tiled = true;
+    return CONSTSTN_OK;
+}
+
 conststn_status build_sptn3_tables(conststn_plan_s *plan) {
     const conststn_csf_s *W = plan->W;
     const int64_t K = W->dims[W->mode_order[0]];
@@ -687,6 +797,7 @@ conststn_status build_sptn3_tables(conststn_plan_s *plan) {
                                                                               plan->w_root_of_k.p);
         CST_HIP(hipGetLastError());
     }
+    CST_TRY(build_w_tiles(plan));
     CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
 }

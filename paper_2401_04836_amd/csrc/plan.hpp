@@ -8,9 +8,13 @@
 namespace cst {
 
 constexpr int kHeavySpan = 64;        // a slice spanning at least this many chunks is "heavy"
-constexpr int kHeavySegments = 32;
-constexpr int kRowLeaves = 16;
-constexpr int kPieceLeaves = 2;       // order-4 path: leaves per piece of a level-2 node        // longest run of leaves one MFMA K-row sums    // its chunk range is reduced in this many parallel segments
+constexpr int kHeavySegments = 32;    // its chunk range is reduced in this many parallel segments
+constexpr int kRowLeaves = 16;        // longest run of leaves one MFMA K-row sums
+constexpr int kPieceLeaves = 2;       // order-4 path: leaves per piece of a level-2 node
+// three-tensor network, tiled path
+constexpr int kSpGroup = 16;          // root slices of U processed together (one MFMA operand side)
+constexpr int kSpMaxMTiles = 25;      // m tiles whose accumulators a wavefront holds (M <= 400)
+constexpr int kSpMaxJ = 32768;        // extent of the contracted mode j the LDS bit mask covers
 
 enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
 
@@ -100,6 +104,13 @@ struct conststn_plan_s {
     cst::DevBuf<double> partial;           // partial row blocks
     // three-tensor network
     cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1
+    bool w_tiled = false;                  // W also stored as dense 16 x 16 (l, m) tiles
+    int64_t n_w_tiles = 0;
+    cst::DevBuf<uint32_t> w_tile_mask;     // [roots x ceil(L/16)] m tiles present
+    cst::DevBuf<uint32_t> w_tile_first;    // [roots x ceil(L/16)] index of the first of them
+    cst::DevBuf<double> w_tiles;           // [(tiles + 1) x 256], the last one all zero
+    int sp_kc = 1;                         // chunks of the k range (one workgroup per group and chunk)
+    int64_t sp_k_per = 0;                  // k values per chunk
 
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;

@@ -233,3 +233,16 @@ def make_sptn3(name, seed, dims_ijklm, nblocks, n_sel_u, n_sel_w, device="cpu"):
     V = dense_factor(seed, name + "/V", J, L, "n01", device)
     return Workload("sptn3", name, {"U": U, "W": W}, {"V": V},
                     {"dims": tuple(dims_ijklm), "seed": seed})
+
+
+def make_sptn3_scattered(name, seed, dims_ijklm, nnz_u, nnz_w, device="cpu"):
+    """Same network as make_sptn3 with U and W scattered (uniform distinct coordinates, no block
+    structure): the fibers of neighbouring slices share few indices."""
+    I, J, K, L, M = dims_ijklm
+    cu = distinct_coords(seed, name + "/U", [("uniform", I), ("uniform", J), ("uniform", K)], nnz_u, device)
+    cw = distinct_coords(seed, name + "/W", [("uniform", K), ("uniform", L), ("uniform", M)], nnz_w, device)
+    U = SparseCOO((I, J, K), cu, sparse_values(seed, name + "/U", cu[0].numel(), "n01", device))
+    W = SparseCOO((K, L, M), cw, sparse_values(seed, name + "/W", cw[0].numel(), "n01", device))
+    V = dense_factor(seed, name + "/V", J, L, "n01", device)
+    return Workload("sptn3", name, {"U": U, "W": W}, {"V": V},
+                    {"dims": tuple(dims_ijklm), "seed": seed})
