@@ -27,7 +27,11 @@ KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "ttmc3": ["kernels_ttmc3.hip", "partition.hip"],
                   "ttmc4": ["kernels_ttmc4.hip", "partition.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
-                "ttmc3": "ttmc3_mfma_kernel<4,1>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_kernel"}
+                "ttmc3": "ttmc3_mfma_kernel<4,1>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel"}
+# what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they
+# compute (HBM); the order-4 TTMc and the three-tensor network are dense contractions per fiber
+# (fp64 matrix cores)
+BOUND = {"mttkrp3": "hbm", "ttmc3": "hbm", "ttmc4": "mfma", "sptn3": "mfma"}
 
 
 def measured_traffic(family):
@@ -279,6 +283,12 @@ def main():
                      "kernel_ms_avg": avg_kernel_ms, "launches_timed": len(kernel_ms),
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
+    if BOUND.get(family) == "mfma":
+        flops_launch = flops_step / len(launches)
+        tf = flops_launch / (avg_kernel_ms * 1e-3) / 1e12
+        result["roofline"].update({"bound": "mfma", "achieved": tf, "peak": FP64_PEAK_TFLOPS,
+                                   "unit": "TFLOP/s", "frac": tf / FP64_PEAK_TFLOPS,
+                                   "algorithmic_flops_per_launch": flops_launch})
     if not args.no_cpu:
         cb = cpu_baseline(wl, 400_000_000)
         if cb is not None:

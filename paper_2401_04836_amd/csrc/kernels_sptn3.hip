@@ -10,8 +10,6 @@
 // fibers of W below root k: lanes take the m leaves and add T[l]*W into a per-wavefront copy
 // of Z_i in LDS (no atomics: leaves of one fiber have distinct m).  The copies are added in
 // fixed order at the end, so results are bit-reproducible.
-#include <type_traits>
-
 #include "plan.hpp"
 
 namespace cst {
@@ -89,7 +87,7 @@ sptn3_kernel(Sptn3Args a) {
 // while it works on one k; after each k the four wavefronts add theirs, one after the other, to
 // the group's Z^t in LDS, and the partial results of the k chunks are added by a fix-up kernel in
 // chunk order, so results are bit-reproducible.  One wavefront per SIMD: latency is hidden by a
-// three-deep software pipeline over batches of four K-steps that runs across l tile boundaries;
+// software pipeline (kRing batches of four K-steps in flight) that runs across l tile boundaries;
 // every load in it is unconditional (clamped addresses), and the W tiles of the current l tile
 // are parked in a per-lane LDS area (indexable at run time, which registers are not).
 // The zero entries of Uc and of the W tiles multiply real factor values, so V must be finite.
@@ -101,6 +99,7 @@ typedef __attribute__((address_space(3))) v2d lds_v2d;
 constexpr int kCap = 320;             // union rows of Uc per pass (40 KB)
 constexpr int kStage = 6;             // W tiles parked in LDS per l tile and wavefront
 constexpr int kBatch = 4;             // K-steps per pipeline batch
+constexpr int kRing = 3;              // batches in flight (loads issued kRing - 1 batches ahead)
 
 struct Sptn3TileArgs {
     int64_t slices, L, M, LT;
@@ -115,7 +114,7 @@ struct Sptn3TileArgs {
     uint32_t zero_tile;
     const double *V;
     double *out, *partial;
-    int compact;
+    int compact, xcd_ranges;
 };
 
 __device__ inline int64_t lower_bound_i32(const int32_t *__restrict__ a, int64_t lo, int64_t hi, int64_t key) {
@@ -127,9 +126,9 @@ __device__ inline int64_t lower_bound_i32(const int32_t *__restrict__ a, int64_t
 }
 
 struct SpPipe {
-    double Vr[3][kBatch], Ur[3][kBatch];
-    int32_t Jr[3][kBatch];
-    v2d Wr[3][2];
+    double Vr[kRing][kBatch], Ur[kRing][kBatch];
+    int32_t Jr[kRing][kBatch];
+    v2d Wr[kRing][2];
 };
 
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
@@ -145,7 +144,13 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, slot = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform, and known to be
-    const int group = int(blockIdx.x) % a.n_groups, kc = int(blockIdx.x) / a.n_groups;
+    // Workgroups are dealt to the 8 XCDs round-robin.  Optionally each XCD gets a contiguous range
+    // of (k chunk, group) pairs instead, so that the workgroups sharing one L2 walk the same k
+    // values over neighbouring groups (same W tiles, largely the same rows of V).
+    const int n_wg = a.n_groups * a.n_kc, per_xcd = (n_wg + 7) / 8;
+    const int logical = a.xcd_ranges ? (int(blockIdx.x) % 8) * per_xcd + int(blockIdx.x) / 8 : int(blockIdx.x);
+    if (logical >= n_wg) return;
+    const int group = logical % a.n_groups, kc = logical / a.n_groups;
     const int64_t s0 = int64_t(group) * kSpGroup;
     const int64_t k_lo = int64_t(kc) * a.k_per, k_hi = k_lo + a.k_per;
     const int64_t L = a.L;
@@ -305,34 +310,41 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
                             const v4d T = accT0 + accT1;
                             const uint32_t m0 = __builtin_amdgcn_readlane(mreg, t0);
                             const uint32_t f0 = __builtin_amdgcn_readlane(freg, t0);
-                            const int staged = min(nBt, kStage);
-                            auto tiles = [&](auto from_memory) {
+                            const int have = __popc(m0);
+                            int staged = min(nBt, kStage);                // tiles parked so far
+                            int first_p = 0;                              // tile held by slot 0
+                            for (;;) {
                                 int p = 0;
 #pragma unroll
                                 for (int mt = 0; mt < kSpMaxMTiles; ++mt) {
                                     if ((m0 >> mt) & 1u) {
-                                        // parked tile (the address is always inside the area)
-                                        const lds_v2d *rp = Wpark + (min(p, staged - 1) * 128 + lane);
-                                        v2d w0 = rp[0], w1 = rp[64];
-                                        if (decltype(from_memory)::value && p >= staged) {
-                                            const double *tp = a.wtiles + (int64_t(f0) + p) * 256 + lane * 2;
-                                            w0 = *reinterpret_cast<const v2d *>(tp);
-                                            w1 = *reinterpret_cast<const v2d *>(tp + 128);
+                                        if (p >= first_p && p < first_p + staged) {
+                                            const lds_v2d *rp = Wpark + ((p - first_p) * 128 + lane);
+                                            const v2d w0 = rp[0], w1 = rp[64];
+                                            v4d z = accZ[mt];
+                                            z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.x, T.x, z, 0, 0, 0);
+                                            z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.y, T.y, z, 0, 0, 0);
+                                            z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.x, T.z, z, 0, 0, 0);
+                                            z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.y, T.w, z, 0, 0, 0);
+                                            accZ[mt] = z;
                                         }
-                                        v4d z = accZ[mt];
-                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.x, T.x, z, 0, 0, 0);
-                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.y, T.y, z, 0, 0, 0);
-                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.x, T.z, z, 0, 0, 0);
-                                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.y, T.w, z, 0, 0, 0);
-                                        accZ[mt] = z;
                                         ++p;
                                     }
                                 }
-                            };
-                            // the usual case has every tile parked and touches no memory, so it
-                            // does not wait for the loads in flight; more tiles than parked: rare
-                            if (__popc(m0) <= staged) tiles(std::false_type{});
-                            else tiles(std::true_type{});
+                                first_p += staged;
+                                if (first_p >= have) break;               // the usual case: one round
+                                // more tiles below this l tile than were parked (rare): fetch the
+                                // next ones and park them, then go round again
+                                staged = min(kStage, have - first_p);
+                                for (int sl = 0; sl < staged; ++sl) {
+                                    const double *tp = a.wtiles + (int64_t(f0) + first_p + sl) * 256 + lane * 2;
+                                    const v2d w0 = *reinterpret_cast<const v2d *>(tp);
+                                    const v2d w1 = *reinterpret_cast<const v2d *>(tp + 128);
+                                    double *wp = Wbw + sl * 256 + lane * 2;
+                                    *reinterpret_cast<v2d *>(wp) = w0;
+                                    *reinterpret_cast<v2d *>(wp + 128) = w1;
+                                }
+                            }
                             accT0 = v4d{0.0, 0.0, 0.0, 0.0};
                             accT1 = accT0;
                             q0 = 0;
@@ -344,21 +356,18 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
                 };
 
                 if (TB > 0) {
-                    read_j(P.Jr[0]);
-                    read_j(P.Jr[1]);
-                    read_j(P.Jr[2]);
-                    issue(P.Jr[0], P.Vr[0], P.Ur[0], P.Wr[0]);
-                    issue(P.Jr[1], P.Vr[1], P.Ur[1], P.Wr[1]);
-                    for (int b = 0; b < TB; b += 3) {
-                        issue(P.Jr[2], P.Vr[2], P.Ur[2], P.Wr[2]);
-                        read_j(P.Jr[0]);
-                        consume(b, P.Vr[0], P.Ur[0], P.Wr[0]);
-                        issue(P.Jr[0], P.Vr[0], P.Ur[0], P.Wr[0]);
-                        read_j(P.Jr[1]);
-                        consume(b + 1, P.Vr[1], P.Ur[1], P.Wr[1]);
-                        issue(P.Jr[1], P.Vr[1], P.Ur[1], P.Wr[1]);
-                        read_j(P.Jr[2]);
-                        consume(b + 2, P.Vr[2], P.Ur[2], P.Wr[2]);
+#pragma unroll
+                    for (int u = 0; u < kRing; ++u) read_j(P.Jr[u]);
+#pragma unroll
+                    for (int u = 0; u < kRing - 1; ++u) issue(P.Jr[u], P.Vr[u], P.Ur[u], P.Wr[u]);
+                    for (int b = 0; b < TB; b += kRing) {
+#pragma unroll
+                        for (int u = 0; u < kRing; ++u) {
+                            const int su = (u + kRing - 1) % kRing;
+                            issue(P.Jr[su], P.Vr[su], P.Ur[su], P.Wr[su]);
+                            read_j(P.Jr[u]);
+                            consume(b + u, P.Vr[u], P.Ur[u], P.Wr[u]);
+                        }
                     }
                 }
             }
@@ -436,6 +445,7 @@ static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const dou
     a.out = out;
     a.partial = plan->partial.p;
     a.compact = plan->compact ? 1 : 0;
+    a.xcd_ranges = env_int("CONSTSTN_SPTN3_XCD", 0) == 1 ? 1 : 0;      // measured: halves the HBM fetch, 4 % slower
     const size_t lds_bytes = size_t(kCap) * 16 * 8 + size_t(4 * kStage) * 256 * 8 + size_t(a.MT) * 256 * 8 +
                              size_t(kCap) * 4 + size_t(a.nwords) * 8 + 64;
     static bool attr_set = false;
@@ -449,7 +459,8 @@ static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const dou
     if (a.slices == 0) return CONSTSTN_OK;
     {
         ProfScope prof(plan, stream);
-        sptn3_tiled_kernel<<<dim3(unsigned(a.n_groups) * unsigned(a.n_kc)), dim3(256), lds_bytes, stream>>>(a);
+        const unsigned n_wg = unsigned(a.n_groups) * unsigned(a.n_kc);
+        sptn3_tiled_kernel<<<dim3((n_wg + 7) / 8 * 8), dim3(256), lds_bytes, stream>>>(a);
     }
     CST_HIP(hipGetLastError());
     if (a.n_kc > 1) {
