@@ -10,6 +10,8 @@
 // fibers of W below root k: lanes take the m leaves and add T[l]*W into a per-wavefront copy
 // of Z_i in LDS (no atomics: leaves of one fiber have distinct m).  The copies are added in
 // fixed order at the end, so results are bit-reproducible.
+#include <type_traits>
+
 #include "plan.hpp"
 
 namespace cst {
@@ -99,6 +101,7 @@ typedef __attribute__((address_space(3))) v2d lds_v2d;
 constexpr int kCap = 320;             // union rows of Uc per pass (40 KB)
 constexpr int kStage = 6;             // W tiles parked in LDS per l tile and wavefront
 constexpr int kBatch = 4;             // K-steps per pipeline batch
+constexpr int kHeld = 16;             // leaves per lane kept in registers between mask and scatter
 constexpr int kRing = 3;              // batches in flight (loads issued kRing - 1 batches ahead)
 
 struct Sptn3TileArgs {
@@ -193,7 +196,20 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
         __syncthreads();                                                  // LDS of the previous k is free
         for (int w = tid; w < nwords; w += 256) mask[w] = 0u;
         __syncthreads();
-        for (int64_t e = ea + c; e < eb; e += 16) {
+        // the first kHeld leaves per lane stay in registers for the scatter below: all their loads
+        // are in flight together instead of one memory round trip per loop iteration
+        int32_t jheld[kHeld];
+        double vheld[kHeld];
+#pragma unroll
+        for (int h = 0; h < kHeld; ++h) {
+            const int64_t e = ea + c + 16 * h;
+            jheld[h] = e < eb ? a.uidx2[e] : -1;
+            vheld[h] = e < eb ? a.uvals[e] : 0.0;
+        }
+#pragma unroll
+        for (int h = 0; h < kHeld; ++h)
+            if (jheld[h] >= 0) atomicOr(&mask[jheld[h] >> 5], 1u << (jheld[h] & 31));
+        for (int64_t e = ea + c + 16 * kHeld; e < eb; e += 16) {
             const int32_t j = a.uidx2[e];
             atomicOr(&mask[j >> 5], 1u << (j & 31));
         }
@@ -227,10 +243,10 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
         const int n_union = __builtin_amdgcn_readfirstlane(scan[0] + scan[1] + scan[2] + scan[3]);
         __syncthreads();
 
-        for (int p0 = 0; p0 < n_union; p0 += kCap) {
-            const int np = min(kCap, n_union - p0);
-            const int npad = (np + 4 * kBatch - 1) & ~(4 * kBatch - 1);   // whole batches
-            if (p0 > 0) __syncthreads();
+        // Prepare one pass: union rows [p0, p0 + np) -> Uc rows and j offsets.  The first pass takes
+        // the leaves held in registers (they are dead before the matrix stages start); later passes
+        // re-read the fibers.
+        auto prepare = [&](int p0, int np, int npad, auto first) {
             for (int x = tid; x < npad * 16; x += 256) Uc[x] = 0.0;
             if (tid < npad - np) jl[np + tid] = 0;
             for (int w = tid; w < nwords; w += 256) {
@@ -244,13 +260,24 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
                 }
             }
             __syncthreads();
-            for (int64_t e = ea + c; e < eb; e += 16) {
-                const int32_t j = a.uidx2[e];
+            auto place = [&](int32_t j, double v) {
                 const int r = wpre[j >> 5] + __popc(mask[j >> 5] & ((1u << (j & 31)) - 1u)) - p0;
-                if (r >= 0 && r < np) Uc[r * 16 + irow] = a.uvals[e];
+                if (r >= 0 && r < np) Uc[r * 16 + irow] = v;
+            };
+            if (decltype(first)::value) {
+#pragma unroll
+                for (int h = 0; h < kHeld; ++h)
+                    if (jheld[h] >= 0) place(jheld[h], vheld[h]);
             }
+            for (int64_t e = ea + c + (decltype(first)::value ? 16 * kHeld : 0); e < eb; e += 16)
+                place(a.uidx2[e], a.uvals[e]);
             __syncthreads();
-
+        };
+        int p0 = 0;
+        int np = min(kCap, n_union);
+        int npad = (np + 4 * kBatch - 1) & ~(4 * kBatch - 1);                 // whole batches
+        if (n_union > 0) prepare(0, np, npad, std::true_type{});
+        while (p0 < n_union) {
             // ---- the two matrix stages over this wavefront's l tiles, 64 tiles per round ----
             v4d accZ[kSpMaxMTiles];
 #pragma unroll
@@ -383,6 +410,12 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
                     }
                 }
                 __syncthreads();
+            }
+            p0 += kCap;
+            if (p0 < n_union) {
+                np = min(kCap, n_union - p0);
+                npad = (np + 4 * kBatch - 1) & ~(4 * kBatch - 1);
+                prepare(p0, np, npad, std::false_type{});
             }
         }
     }
