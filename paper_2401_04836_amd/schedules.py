@@ -18,3 +18,34 @@ TTMC4 = ("T1[i,j,k,t] = X[i,j,k,l] * U3[l,t] | i,j,k,l,t ; "
 # three-tensor network of Sec. 1 as the tree (U.V).W; U stored i>k>j, W stored k>l>m
 SPTN3 = ("T[i,k,l] = U[i,k,j] * V[j,l] | i,k,j,l ; "
          "Z[i,m] = T[i,k,l] * W[k,l,m] | i,k,l,m")
+
+
+# ---- any output mode by re-rooting the CSF (Sec. 5.2-5.3: one contraction per mode) ------------
+#
+# The layout is chosen per output mode (Sec. 2.1: the CSF level order fixes the loop order), so
+# the output mode goes to the CSF root and the same fused kernels apply.  `levels` names the
+# tensor modes in CSF level order, e.g. (1, 2, 0) = output mode 1, then mode 2, leaves on mode 0.
+
+_MODE_NAMES = "ijkl"
+
+
+def mttkrp3_for(levels):
+    """(schedule, operand names) of the order-3 MTTKRP whose CSF level order is `levels`.
+    Operands after X: the factor of the leaf mode, then the factor of the middle mode."""
+    a, b, c = (_MODE_NAMES[m] for m in levels)
+    fb, fc = "F%d" % levels[1], "F%d" % levels[2]
+    text = ("T[%s,%s,r] = X[%s,%s,%s] * %s[%s,r] | %s,%s,%s,r ; "
+            "M[%s,r] = T[%s,%s,r] * %s[%s,r] | %s,%s,r") % (
+        a, b, a, b, c, fc, c, a, b, c, a, a, b, fb, b, a, b)
+    return text, ("X", fc, fb)
+
+
+def ttmc3_for(levels):
+    """(schedule, operand names) of the order-3 TTMc whose CSF level order is `levels`; the
+    output is [root, rank of the middle mode, rank of the leaf mode]."""
+    a, b, c = (_MODE_NAMES[m] for m in levels)
+    fb, fc = "F%d" % levels[1], "F%d" % levels[2]
+    text = ("T[%s,%s,s] = X[%s,%s,%s] * %s[%s,s] | %s,%s,%s,s ; "
+            "Y[%s,r,s] = T[%s,%s,s] * %s[%s,r] | %s,%s,r,s") % (
+        a, b, a, b, c, fc, c, a, b, c, a, a, b, fb, b, a, b)
+    return text, ("X", fc, fb)
