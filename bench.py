@@ -27,7 +27,8 @@ KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "ttmc3": ["kernels_ttmc3.hip", "partition.hip"],
                   "ttmc4": ["kernels_ttmc4.hip", "partition.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
-                "ttmc3": "ttmc3_mfma_kernel<4,1>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel"}
+                "ttmc3": "ttmc3_mfma_kernel<4,1>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
+                "generic": "generic_stmt_kernel (one launch per statement)"}
 # what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they
 # compute (HBM); the order-4 TTMc and the three-tensor network are dense contractions per fiber
 # (fp64 matrix cores)
@@ -190,6 +191,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--generic", action="store_true",
+                    help="plan with the generic executor instead of the tuned kernels (configs 1, 2, 3, 5)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the FETCH_SIZE / "
                          "WRITE_SIZE counters of a profiler run)")
@@ -200,6 +203,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.generic:
+        os.environ["CONSTSTN_FORCE_GENERIC"] = "1"
     import paper_2401_04836_amd as cst
     from paper_2401_04836_amd import schedules as S
     dev = torch.device("cuda:0")
@@ -268,6 +273,8 @@ def main():
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
 
     family = launches[0]["plan"].describe().split()[0].split("=")[1]
+    if family == "generic":
+        name += " [generic executor]"
     result = {
         "metric": "fused sparse contraction nnz/s", "value": nnz_per_step / (dt / args.steps),
         "unit": "nnz/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

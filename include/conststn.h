@@ -126,7 +126,15 @@ void conststn_csf_destroy(conststn_csf_t *csf);
  *   - the fused prefix of a producer consists of indices of its result ("Producer constraints"),
  *     equals the consumer's prefix position by position ("Consumer constraints"), and every
  *     statement between the two shares it ("Statements between producer and consumer").
- * A legal schedule that matches no kernel family gives CONSTSTN_EUNSUPPORTED.
+ * Kernel choice.  Tuned kernels take: TTMc of order 3 (ranks up to 64) and order 4 (ranks up to
+ * 16), MTTKRP of order 3 (rank up to 128), each with the sparse prefix fully fused, and the
+ * three-tensor network (U.V).W fused on its two outer loops.  Every other legal tree over ONE CSF
+ * operand and dense operands -- other orders and ranks, dense-only subtrees, several CSF levels
+ * summed by one statement, a fully contracted result, any fusion choice -- runs on a generic
+ * executor (one pass per statement, intermediates held whole in device memory; environment
+ * variable CONSTSTN_GENERIC_MAX_GB bounds them, default 64), provided every tensor between the
+ * CSF operand and the result keeps a PREFIX of the CSF levels and the result keeps at most the
+ * root level.  A legal schedule outside both gives CONSTSTN_EUNSUPPORTED with the reason.
  * The plan keeps pointers into the CSF handles: destroy the plan first.
  */
 typedef enum { CONSTSTN_OPERAND_CSF = 0, CONSTSTN_OPERAND_DENSE = 1 } conststn_operand_kind;

@@ -150,12 +150,23 @@ static conststn_status match_sptn3(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// rank extents the tuned kernels are built for
+static bool tuned_kernel_fits(const conststn_plan_s *plan) {
+    switch (plan->family) {
+        case FAM_MTTKRP3: return plan->rank_of_level[1] <= 128;
+        case FAM_TTMC3: return plan->rank_of_level[1] <= 64 && plan->rank_of_level[2] <= 64;
+        case FAM_TTMC4: return plan->rank_of_level[1] <= 16 && plan->rank_of_level[2] <= 16 && plan->rank_of_level[3] <= 16;
+        default: return true;
+    }
+}
+
 static const char *family_name(Family f) {
     switch (f) {
         case FAM_TTMC3: return "ttmc3";
         case FAM_TTMC4: return "ttmc4";
         case FAM_MTTKRP3: return "mttkrp3";
         case FAM_SPTN3: return "sptn3";
+        case FAM_GENERIC: return "generic";
         default: return "none";
     }
 }
@@ -267,12 +278,28 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
         st = match_sptn3(plan);
         if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
     }
-    if (st == CONSTSTN_EUNSUPPORTED && !*get_error())
-        set_error("the schedule is legal but matches no kernel family (TTMc order 3/4, MTTKRP order 3, (U.V).W)");
+    // tuned kernels have rank limits; beyond them, and for every other tree over one CSF operand,
+    // the generic executor takes over
+    if (st == CONSTSTN_OK && !tuned_kernel_fits(plan)) st = CONSTSTN_EUNSUPPORTED;
+    if (st == CONSTSTN_OK && env_int("CONSTSTN_FORCE_GENERIC", 0) == 1 && plan->family != FAM_SPTN3)
+        st = CONSTSTN_EUNSUPPORTED;
+    if (st == CONSTSTN_EUNSUPPORTED) {
+        std::string why = get_error();
+        clear_error();
+        plan->family = FAM_NONE;
+        st = build_generic(plan);
+        if (st == CONSTSTN_EUNSUPPORTED) {
+            std::string why2 = get_error();
+            set_error("the schedule is legal but no kernel takes it.  Tuned families (TTMc order 3/4, MTTKRP order 3, "
+                      "(U.V).W): %s.  Generic executor: %s", why.empty() ? "no match" : why.c_str(),
+                      why2.empty() ? "no match" : why2.c_str());
+        }
+    }
     CST_TRY(st);
 
     const conststn_csf_s *X = plan->X;
     plan->out_rows = plan->compact ? X->nodes[0] : X->dims[X->mode_order[0]];
+    if (plan->family == FAM_GENERIC && !plan->gen_rooted) plan->out_rows = 1;    // fully contracted sparse modes
     switch (plan->family) {
         case FAM_MTTKRP3: CST_TRY(build_mttkrp3_tables(plan)); break;
         case FAM_TTMC3:
@@ -380,6 +407,7 @@ conststn_status conststn_execute(const conststn_plan_t *plan, const double *cons
         case FAM_TTMC3: return launch_ttmc3(plan, dense_factors, out, st);
         case FAM_TTMC4: return launch_ttmc4(plan, dense_factors, out, st);
         case FAM_SPTN3: return launch_sptn3(plan, dense_factors, out, st);
+        case FAM_GENERIC: return launch_generic(plan, dense_factors, out, st);
         default: set_error("plan has no kernel family"); return CONSTSTN_EINVAL;
     }
 }

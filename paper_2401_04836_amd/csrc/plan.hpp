@@ -2,6 +2,8 @@
 // work tables (load-balanced partition of the CSF tree) and scratch the kernels need.
 #pragma once
 
+#include <memory>
+
 #include "common.hpp"
 #include "schedule.hpp"
 
@@ -16,7 +18,28 @@ constexpr int kSpGroup = 16;          // root slices of U processed together (on
 constexpr int kSpMaxMTiles = 25;      // m tiles whose accumulators a wavefront holds (M <= 400)
 constexpr int kSpMaxJ = 32768;        // extent of the contracted mode j the LDS bit mask covers
 
-enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3 };
+enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GENERIC };
+
+// One statement of the generic executor (generic.hip), passed to its kernel by value.
+// Dense loop indices: the first n_out are the result's dense indices in storage order, the
+// next n_red are summed over; strides are in elements, 0 where a tensor lacks the index.
+constexpr int kGenMaxIdx = 8;
+struct GenStmt {
+    int d_in, d_out;                           // CSF prefix depth of the sparse-side input / of the result
+    int in_is_leaf;                            // the sparse-side input is the CSF operand itself
+    int n_out, n_red;
+    int scatter_rows;                          // result row = root index instead of root node number
+    int64_t extent[kGenMaxIdx];
+    int64_t in_stride[kGenMaxIdx], f_stride[kGenMaxIdx], out_stride[kGenMaxIdx];
+    int64_t f_level_stride[CONSTSTN_MAX_ORDER];   // stride in the dense input of each summed CSF level's index
+    int64_t in_block, out_block;               // elements per CSF node of input / result
+    int64_t out_nodes, roots;
+    const int32_t *idx[CONSTSTN_MAX_ORDER];
+    const int64_t *ptr[CONSTSTN_MAX_ORDER];
+    const double *in, *f;
+    double *out;
+    int in_operand, in_buffer, f_operand, f_buffer, out_buffer;   // resolved to pointers at launch
+};
 
 // One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1
 // fibers (order 4) inside ONE root slice.  dest < 0: the slice has a single item and its row
@@ -112,6 +135,11 @@ struct conststn_plan_s {
     int sp_kc = 1;                         // chunks of the k range (one workgroup per group and chunk)
     int64_t sp_k_per = 0;                  // k values per chunk
 
+    // generic executor: one entry per statement, intermediates held whole
+    std::vector<cst::GenStmt> gen;
+    std::vector<std::unique_ptr<cst::DevBuf<double>>> gen_buffers;
+    bool gen_rooted = false;               // the result has one row block per root index
+
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;
     mutable int64_t prof_count = 0;        // executes recorded since the last read
@@ -137,6 +165,10 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
                              hipStream_t stream);
 conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream);
+// generic.hip: any tree over one CSF operand that the tuned families do not take
+conststn_status build_generic(conststn_plan_s *plan);
+conststn_status launch_generic(const conststn_plan_s *plan, const double *const *dense, double *out,
+                               hipStream_t stream);
 // sums the partial row blocks of slices made of several items (shared by the TTMc kernels)
 conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream);
 
