@@ -191,8 +191,11 @@ def test_unsupported_and_illegal_plans():
     dc, dv = to_dev(X)
     csf = cst.build_csf(dc, dv, X.dims, [0, 1, 2])
     U2, U3 = wl.dense["U2"].cuda(), wl.dense["U3"].cuda()
-    with pytest.raises(cst.ConststnError) as e:      # legal but unfused: no kernel family
-        cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], fusion=[0, 0])
+    # legal but unfused: none of the tuned kernels, so the generic executor takes it
+    pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], fusion=[0, 0])
+    assert "family=generic" in pl.describe()
+    with pytest.raises(cst.ConststnError) as e:      # two CSF operands outside the (U.V).W form
+        cst.plan("Z[i,j] = X[i,j,k] * W[i,j,k] | i,j,k", [("X", csf), ("W", csf)])
     assert e.value.status_name == "EUNSUPPORTED"
     with pytest.raises(cst.ConststnError) as e:      # loop order against the CSF layout
         cst.plan(S.TTMC3.replace("| i,j,k,s", "| j,i,k,s"), [("X", csf), ("U3", U3), ("U2", U2)])
