@@ -116,7 +116,7 @@ struct Ttmc3RowArgs {
 };
 
 template <int PN, int QN>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QN == 1 ? 5 : 4, 8)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QN == 1 ? 5 : (QN == 2 ? 4 : 2), 8)))
 ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int lane = threadIdx.x % 64;
     // The wavefronts of a workgroup take the column parts of the same item(s): they gather the same
@@ -135,7 +135,10 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int64_t ra = uniform64(it.begin), rb = uniform64(it.end), dest = uniform64(it.dest);
     const int slot = lane >> 4, c = lane & 15;
     const int R2 = a.R2, R3 = a.R3;
-    const int col0 = part * QN * 16 + c;                       // this lane's column in tile q = 0
+    // A lane's QN columns are adjacent in memory (column of tile q = col0 + q): one vector load
+    // per factor row and one vector store per output row instead of QN scalar ones.  Which
+    // columns form a tile is free to choose -- a tile is a set of 16 columns of the result.
+    const int col0 = part * QN * 16 + QN * c;
 
     v4f64 acc[PN][QN];
 #pragma unroll
@@ -192,12 +195,20 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
                 kk[u] = __shfl(myk, t0 + u, 16);
                 vv[u] = __shfl(myv, t0 + u, 16);
             }
+            typedef double vq __attribute__((ext_vector_type(QN == 1 ? 2 : QN)));
             double uu[4][QN];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 4; ++u) {
+                const double *src = a.U3 + int64_t(kk[u]) * R3 + col0;
+                if (QN == 1) {
+                    uu[u][0] = t0 + u < cnt ? src[0] : 0.0;
+                } else {
+                    vq x = {};
+                    if (t0 + u < cnt) x = *reinterpret_cast<const vq *>(src);
 #pragma unroll
-                for (int q = 0; q < QN; ++q)
-                    uu[u][q] = t0 + u < cnt ? a.U3[int64_t(kk[u]) * R3 + col0 + 16 * q] : 0.0;
+                    for (int q = 0; q < QN; ++q) uu[u][q] = x[q];
+                }
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -213,16 +224,24 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int64_t RR = int64_t(R2) * R3;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
                             : a.partial + dest * RR;
-    // tile (p,q): accumulator register v of a lane holds row 16p + slot + 4v, column 16q + c.
+    // tile (p,q): accumulator register v of a lane holds row 16p + slot + 4v, column col0 + q.
     // The row block is written once and never re-read by this kernel: streaming (non-temporal)
     // stores keep the gathered factor rows resident in L2 instead of the output.
 #pragma unroll
     for (int p = 0; p < PN; ++p)
 #pragma unroll
-        for (int q = 0; q < QN; ++q)
+        for (int v = 0; v < 4; ++v) {
+            double *dst = base + int64_t(16 * p + slot + 4 * v) * R3 + col0;
+            if (QN == 1) {
+                __builtin_nontemporal_store(acc[p][0][v], dst);
+            } else {
+                typedef double vq __attribute__((ext_vector_type(QN == 1 ? 2 : QN)));
+                vq x;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                __builtin_nontemporal_store(acc[p][q][v], base + int64_t(16 * p + slot + 4 * v) * R3 + col0 + 16 * q);
+                for (int q = 0; q < QN; ++q) x[q] = acc[p][q][v];
+                __builtin_nontemporal_store(x, reinterpret_cast<vq *>(dst));
+            }
+        }
 }
 
 template <int PN>
@@ -234,7 +253,16 @@ static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3Ro
         const int per_block = 4 / parts > 0 ? 4 / parts : 1;
         return dim3(unsigned(div_up(a.n_items, per_block)));
     };
-    if (env_int("CONSTSTN_TTMC3_QN", 1) == 2 && qt % 2 == 0)
+    // column tiles per wavefront: two where R3 allows it (vector accesses need the alignment)
+    int qn = int(env_int("CONSTSTN_TTMC3_QN", 2));
+    if (qn != 1 && qn != 2 && qn != 4) qn = 2;
+    while (qn > 1 && (qt % qn != 0 ||
+                      (reinterpret_cast<uintptr_t>(a.U3) | reinterpret_cast<uintptr_t>(a.out) |
+                       reinterpret_cast<uintptr_t>(a.partial)) % (8u * unsigned(qn)) != 0))
+        qn /= 2;
+    if (qn == 4)
+        ttmc3_mfma_kernel<PN, 4><<<grid(qt / 4), block, 0, stream>>>(a);
+    else if (qn == 2)
         ttmc3_mfma_kernel<PN, 2><<<grid(qt / 2), block, 0, stream>>>(a);
     else
         ttmc3_mfma_kernel<PN, 1><<<grid(qt), block, 0, stream>>>(a);
