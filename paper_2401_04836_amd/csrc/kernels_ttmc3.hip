@@ -106,7 +106,7 @@ struct Ttmc3RowArgs {
     int64_t n_items;
     int R2, R3;
     const int64_t *row_leaf;
-    const int32_t *row_j;
+    const int32_t *row_j, *row_cnt;
     const int32_t *idx0, *idx2;
     const double *vals;
     const SliceItem *items;
@@ -154,7 +154,7 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
         Desc d{0, 0, 0};
         if (g + slot < rb) {
             d.la = a.row_leaf[g + slot];
-            d.cnt = int(a.row_leaf[g + slot + 1] - d.la);
+            d.cnt = a.row_cnt[g + slot];
             d.j = a.row_j[g + slot];
         }
         return d;
@@ -328,6 +328,7 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
         ra.R3 = a.R3;
         ra.row_leaf = plan->row_leaf.p;
         ra.row_j = plan->row_j.p;
+        ra.row_cnt = plan->row_cnt.p;
         ra.idx0 = a.idx0;
         ra.idx2 = a.idx2;
         ra.vals = a.vals;

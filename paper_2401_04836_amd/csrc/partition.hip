@@ -481,18 +481,42 @@ __global__ void fiber_rows_kernel(int64_t fibers, const int64_t *__restrict__ pt
     if (f < fibers) rows_of[f] = (ptr1[f + 1] - ptr1[f] + kRowLeaves - 1) / kRowLeaves;
 }
 
-__global__ void fill_rows_kernel(int64_t fibers, const int64_t *__restrict__ ptr1,
-                                 const int32_t *__restrict__ idx1, const int64_t *__restrict__ row_off,
-                                 int64_t *row_leaf, int32_t *row_j, int64_t total_rows, int64_t nnz) {
+// Besides the tables, a sort key per row: (slice, 16 - leaves).  Sorting by it orders the rows of
+// a slice from long to short, so the four rows of one K-step have (nearly) the same number of
+// leaves and the leaf stage wastes no gather instructions on the shortest of them.
+__global__ void fill_rows_kernel(int64_t fibers, int64_t slices, const int64_t *__restrict__ ptr0,
+                                 const int64_t *__restrict__ ptr1, const int32_t *__restrict__ idx1,
+                                 const int64_t *__restrict__ row_off, int64_t *row_leaf, int32_t *row_j,
+                                 int32_t *row_cnt, uint64_t *row_key, int32_t *row_id) {
     const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (f == 0) row_leaf[total_rows] = nnz;
     if (f >= fibers) return;
+    int64_t lo = 0, hi = slices;                // slice of fiber f: last s with ptr0[s] <= f
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr0[mid] <= f) lo = mid; else hi = mid;
+    }
     const int64_t a = ptr1[f], b = ptr1[f + 1];
     int64_t r = row_off[f];
     for (int64_t n = a; n < b; n += kRowLeaves, ++r) {
+        const int cnt = int(b - n < kRowLeaves ? b - n : kRowLeaves);
         row_leaf[r] = n;
         row_j[r] = idx1[f];
+        row_cnt[r] = cnt;
+        row_key[r] = (uint64_t(lo) << 8) | uint64_t(kRowLeaves - cnt);
+        row_id[r] = int32_t(r);
     }
+}
+
+__global__ void permute_rows_kernel(int64_t rows, const int32_t *__restrict__ order,
+                                    const int64_t *__restrict__ leaf_in, const int32_t *__restrict__ j_in,
+                                    const int32_t *__restrict__ cnt_in, int64_t *leaf_out, int32_t *j_out,
+                                    int32_t *cnt_out) {
+    const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    const int32_t src = order[r];
+    leaf_out[r] = leaf_in[src];
+    j_out[r] = j_in[src];
+    cnt_out[r] = cnt_in[src];
 }
 
 __global__ void slice_rows_kernel(int64_t slices, int64_t fibers, const int64_t *__restrict__ ptr0,
@@ -516,12 +540,40 @@ static conststn_status build_rows(conststn_plan_s *plan) {
     fiber_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(fibers, X->ptr[1].p, rows_of.p);
     CST_HIP(hipGetLastError());
     CST_TRY(exscan(rows_of.p, row_off.p, fibers, &plan->n_rows_tab));
-    CST_TRY(plan->row_leaf.alloc(size_t(plan->n_rows_tab) + 1));
-    CST_TRY(plan->row_j.alloc(size_t(plan->n_rows_tab)));
+    const int64_t rows = plan->n_rows_tab;
+    if (rows >= (int64_t(1) << 31)) { set_error("more than 2^31 rows"); return CONSTSTN_EUNSUPPORTED; }
+    CST_TRY(plan->row_leaf.alloc(size_t(rows)));
+    CST_TRY(plan->row_j.alloc(size_t(rows)));
+    CST_TRY(plan->row_cnt.alloc(size_t(rows)));
     CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));
-    fill_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
-        fibers, X->ptr[1].p, X->idx[1].p, row_off.p, plan->row_leaf.p, plan->row_j.p, plan->n_rows_tab, X->nnz);
-    CST_HIP(hipGetLastError());
+    {
+        DevBuf<int64_t> leaf0;
+        DevBuf<int32_t> j0, cnt0, id0, order;
+        DevBuf<uint64_t> key0, key1;
+        CST_TRY(leaf0.alloc(size_t(rows)));
+        CST_TRY(j0.alloc(size_t(rows)));
+        CST_TRY(cnt0.alloc(size_t(rows)));
+        CST_TRY(id0.alloc(size_t(rows)));
+        CST_TRY(order.alloc(size_t(rows)));
+        CST_TRY(key0.alloc(size_t(rows)));
+        CST_TRY(key1.alloc(size_t(rows)));
+        fill_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
+            fibers, slices, X->ptr[0].p, X->ptr[1].p, X->idx[1].p, row_off.p, leaf0.p, j0.p, cnt0.p, key0.p, id0.p);
+        CST_HIP(hipGetLastError());
+        if (rows > 0) {
+            // stable sort by (slice, 16 - leaves): rows stay inside their slice, longest first
+            const unsigned end_bit = unsigned(8 + ceil_log2_u64(uint64_t(slices) + 1));
+            size_t bytes = 0;
+            CST_HIP(rocprim::radix_sort_pairs(nullptr, bytes, key0.p, key1.p, id0.p, order.p, size_t(rows), 0u, end_bit));
+            DevBuf<char> temp;
+            CST_TRY(temp.alloc(bytes));
+            CST_HIP(rocprim::radix_sort_pairs(temp.p, bytes, key0.p, key1.p, id0.p, order.p, size_t(rows), 0u, end_bit));
+            permute_rows_kernel<<<dim3(unsigned(div_up(rows, 256))), block>>>(
+                rows, order.p, leaf0.p, j0.p, cnt0.p, plan->row_leaf.p, plan->row_j.p, plan->row_cnt.p);
+            CST_HIP(hipGetLastError());
+        }
+        CST_HIP(hipDeviceSynchronize());
+    }
     slice_rows_kernel<<<dim3(unsigned(div_up(slices + 1, 256))), block>>>(
         slices, fibers, X->ptr[0].p, row_off.p, plan->n_rows_tab, plan->slice_row.p);
     CST_HIP(hipGetLastError());

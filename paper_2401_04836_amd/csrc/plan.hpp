@@ -115,8 +115,10 @@ struct conststn_plan_s {
     // becomes several rows with the same level-1 index); items are ranges of rows
     bool use_rows = false;
     int64_t n_rows_tab = 0;
-    cst::DevBuf<int64_t> row_leaf;         // [rows+1] first leaf of each row
+    cst::DevBuf<int64_t> row_leaf;         // [rows] first leaf of each row (order-4 path: [rows+1])
     cst::DevBuf<int32_t> row_j;            // [rows] level-1 index of the row's fiber
+    cst::DevBuf<int32_t> row_cnt;          // [rows] leaves of the row (order-3 path; rows of a slice
+                                           //        are ordered from long to short)
     cst::DevBuf<int64_t> slice_row;        // [slices+1] first row of each slice
     // TTMc order-4 MFMA path: level-2 nodes cut into "pieces" of at most kPieceLeaves leaves,
     // level-1 fibers cut into rows of at most 4 pieces; rows index pieces, pieces index leaves
