@@ -105,8 +105,7 @@ typedef double v4f64 __attribute__((ext_vector_type(4)));
 struct Ttmc3RowArgs {
     int64_t n_items;
     int R2, R3;
-    const int64_t *row_leaf;
-    const int32_t *row_j, *row_cnt;
+    const RowDesc *rows;
     const int32_t *idx0, *idx2;
     const double *vals;
     const SliceItem *items;
@@ -153,9 +152,10 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     auto load_desc = [&](int64_t g) -> Desc {
         Desc d{0, 0, 0};
         if (g + slot < rb) {
-            d.la = a.row_leaf[g + slot];
-            d.cnt = a.row_cnt[g + slot];
-            d.j = a.row_j[g + slot];
+            const RowDesc r = a.rows[g + slot];          // one 16-byte load
+            d.la = r.leaf;
+            d.cnt = r.cnt;
+            d.j = r.j;
         }
         return d;
     };
@@ -184,9 +184,23 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
         const int cnt = cur.cnt;
         const int32_t myk = cur.k;
         const double myv = cur.v;
-        double av[PN];                               // issued with the step's U3 gathers
+        // A operands, issued with the step's U3 gathers.  As with the columns, which 16 rows of
+        // the result form tile p is free to choose: tile p takes rows PN*i + p, so a lane's PN
+        // entries of the U2 row are adjacent and come with one vector load.
+        double av[PN];
+        {
+            typedef double vp __attribute__((ext_vector_type(PN == 3 ? 4 : (PN == 1 ? 2 : PN))));
+            const double *src = a.U2 + int64_t(cur.j) * R2 + PN * c;
+            if (PN == 2 || PN == 4) {
+                vp x = {};
+                if (cnt > 0) x = *reinterpret_cast<const vp *>(src);
 #pragma unroll
-        for (int p = 0; p < PN; ++p) av[p] = cnt > 0 ? a.U2[int64_t(cur.j) * R2 + 16 * p + c] : 0.0;
+                for (int p = 0; p < PN; ++p) av[p] = x[p];
+            } else {
+#pragma unroll
+                for (int p = 0; p < PN; ++p) av[p] = cnt > 0 ? src[p] : 0.0;
+            }
+        }
         for (int t0 = 0; t0 < cnt; t0 += 4) {
             int32_t kk[4];
             double vv[4];
@@ -224,14 +238,14 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     const int64_t RR = int64_t(R2) * R3;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
                             : a.partial + dest * RR;
-    // tile (p,q): accumulator register v of a lane holds row 16p + slot + 4v, column col0 + q.
+    // tile (p,q): accumulator register v of a lane holds row PN*(slot + 4v) + p, column col0 + q.
     // The row block is written once and never re-read by this kernel: streaming (non-temporal)
     // stores keep the gathered factor rows resident in L2 instead of the output.
 #pragma unroll
     for (int p = 0; p < PN; ++p)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            double *dst = base + int64_t(16 * p + slot + 4 * v) * R3 + col0;
+            double *dst = base + int64_t(PN * (slot + 4 * v) + p) * R3 + col0;
             if (QN == 1) {
                 __builtin_nontemporal_store(acc[p][0][v], dst);
             } else {
@@ -326,9 +340,7 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
         ra.n_items = plan->n_items;
         ra.R2 = a.R2;
         ra.R3 = a.R3;
-        ra.row_leaf = plan->row_leaf.p;
-        ra.row_j = plan->row_j.p;
-        ra.row_cnt = plan->row_cnt.p;
+        ra.rows = plan->rows.p;
         ra.idx0 = a.idx0;
         ra.idx2 = a.idx2;
         ra.vals = a.vals;

@@ -509,14 +509,11 @@ __global__ void fill_rows_kernel(int64_t fibers, int64_t slices, const int64_t *
 
 __global__ void permute_rows_kernel(int64_t rows, const int32_t *__restrict__ order,
                                     const int64_t *__restrict__ leaf_in, const int32_t *__restrict__ j_in,
-                                    const int32_t *__restrict__ cnt_in, int64_t *leaf_out, int32_t *j_out,
-                                    int32_t *cnt_out) {
+                                    const int32_t *__restrict__ cnt_in, RowDesc *out) {
     const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (r >= rows) return;
     const int32_t src = order[r];
-    leaf_out[r] = leaf_in[src];
-    j_out[r] = j_in[src];
-    cnt_out[r] = cnt_in[src];
+    out[r] = RowDesc{leaf_in[src], cnt_in[src], j_in[src]};
 }
 
 __global__ void slice_rows_kernel(int64_t slices, int64_t fibers, const int64_t *__restrict__ ptr0,
@@ -542,9 +539,7 @@ static conststn_status build_rows(conststn_plan_s *plan) {
     CST_TRY(exscan(rows_of.p, row_off.p, fibers, &plan->n_rows_tab));
     const int64_t rows = plan->n_rows_tab;
     if (rows >= (int64_t(1) << 31)) { set_error("more than 2^31 rows"); return CONSTSTN_EUNSUPPORTED; }
-    CST_TRY(plan->row_leaf.alloc(size_t(rows)));
-    CST_TRY(plan->row_j.alloc(size_t(rows)));
-    CST_TRY(plan->row_cnt.alloc(size_t(rows)));
+    CST_TRY(plan->rows.alloc(size_t(rows)));
     CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));
     {
         DevBuf<int64_t> leaf0;
@@ -569,7 +564,7 @@ static conststn_status build_rows(conststn_plan_s *plan) {
             CST_TRY(temp.alloc(bytes));
             CST_HIP(rocprim::radix_sort_pairs(temp.p, bytes, key0.p, key1.p, id0.p, order.p, size_t(rows), 0u, end_bit));
             permute_rows_kernel<<<dim3(unsigned(div_up(rows, 256))), block>>>(
-                rows, order.p, leaf0.p, j0.p, cnt0.p, plan->row_leaf.p, plan->row_j.p, plan->row_cnt.p);
+                rows, order.p, leaf0.p, j0.p, cnt0.p, plan->rows.p);
             CST_HIP(hipGetLastError());
         }
         CST_HIP(hipDeviceSynchronize());

@@ -52,6 +52,13 @@ struct SliceItem {
     int64_t dest;
 };
 
+// One row of the order-3 TTMc MFMA path: at most kRowLeaves consecutive leaves of one fiber.
+struct alignas(16) RowDesc {
+    int64_t leaf;           // first leaf
+    int32_t cnt;            // number of leaves
+    int32_t j;              // level-1 index of the fiber
+};
+
 // One of the two sub-tensors of the split rank-32 MTTKRP path: the leaves whose factor row is
 // "hot" (kept in LDS) or the rest.  X = X_hot + X_cold and the contraction is linear in X, so each
 // part is a CSF tensor of its own (only the slices and fibers that keep a leaf) with its own
@@ -115,10 +122,8 @@ struct conststn_plan_s {
     // becomes several rows with the same level-1 index); items are ranges of rows
     bool use_rows = false;
     int64_t n_rows_tab = 0;
-    cst::DevBuf<int64_t> row_leaf;         // [rows] first leaf of each row (order-4 path: [rows+1])
-    cst::DevBuf<int32_t> row_j;            // [rows] level-1 index of the row's fiber
-    cst::DevBuf<int32_t> row_cnt;          // [rows] leaves of the row (order-3 path; rows of a slice
-                                           //        are ordered from long to short)
+    cst::DevBuf<cst::RowDesc> rows;        // [rows] order-3 path; rows of a slice ordered from long to short
+    cst::DevBuf<int32_t> row_j;            // [rows] order-4 path: level-1 index of the row's fiber
     cst::DevBuf<int64_t> slice_row;        // [slices+1] first row of each slice
     // TTMc order-4 MFMA path: level-2 nodes cut into "pieces" of at most kPieceLeaves leaves,
     // level-1 fibers cut into rows of at most 4 pieces; rows index pieces, pieces index leaves
