@@ -117,15 +117,17 @@ ttmc4_kernel(Ttmc4Args a) {
 // the row's T2 in the accumulator layout (register v of lane (s,c) = T2[r2 = s+4v][r3 = c]).  The
 // four T2 tiles pass through a wave-private LDS buffer so that in the slice-level MFMAs slot s
 // supplies the tile of row s: B_t = T2_s[r2 = t][r3 = c] for the 16 column tiles, A = U1[j_s, c].
-// Loads are issued stage by stage for all four rows together and row / piece descriptors are
-// fetched one and two K-steps ahead, so a K-step waits for two memory round trips.
+// The plan copies each piece's level-2 index, leaf indices and leaf values into one 32-byte record;
+// row ranges are fetched two K-steps ahead and piece records one ahead, so a K-step waits for one
+// memory round trip (the factor rows) and issues 21 vector loads.
 typedef double v4d __attribute__((ext_vector_type(4)));
 constexpr int kT2Stride = 16 * 16 + 16;        // doubles per tile in LDS (+16: bank skew)
 
 struct Ttmc4RowArgs {
     int64_t n_items;
-    const int64_t *row_piece, *piece_leaf;
-    const int32_t *row_j, *piece_k;
+    const int64_t *row_piece;
+    const PieceDesc *pieces;
+    const int32_t *row_j;
     const int32_t *idx0, *idx3;
     const double *vals;
     const SliceItem *items;
@@ -168,21 +170,22 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
         r.j = g + slot < rb ? a.row_j[g + slot] : -1;
         return r;
     };
-    // piece descriptors: piece pa[u]+slot of each row
-    struct Pieces { int32_t k[4]; int64_t la[4]; int ln[4]; int32_t j; };
+    // pieces: piece pa[u]+slot of each row -- level-2 index, leaf indices and leaf values in one read
+    struct Pieces { int32_t k[4], l0[4], l1[4]; double v0[4], v1[4]; int32_t j; };
     auto load_pieces = [&](const Rows &r) -> Pieces {
         Pieces p;
         p.j = r.j;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            p.k[u] = -1;
-            p.la[u] = 0;
-            p.ln[u] = 0;
+            p.k[u] = p.l0[u] = p.l1[u] = -1;
+            p.v0[u] = p.v1[u] = 0.0;
             if (slot < r.pn[u]) {
-                const int64_t q = r.pa[u] + slot;
-                p.k[u] = a.piece_k[q];
-                p.la[u] = a.piece_leaf[q];
-                p.ln[u] = int(a.piece_leaf[q + 1] - p.la[u]);
+                const PieceDesc d = a.pieces[r.pa[u] + slot];
+                p.k[u] = d.k;
+                p.l0[u] = d.l0;
+                p.l1[u] = d.l1;
+                p.v0[u] = d.v0;
+                p.v1[u] = d.v1;
             }
         }
         return p;
@@ -194,28 +197,18 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
         const Pieces nxt = load_pieces(r2);              // K-step g+4
         r2 = load_rows(g + 8);
         const double av = cur.j >= 0 ? a.U1[int64_t(cur.j) * 16 + c] : 0.0;
-        // stage A: U2 entry and the (at most two) leaves of each piece
-        double u2[4], v0[4], v1[4];
-        int32_t l0[4], l1[4];
+        // factor rows: U2 entry of each piece, U3 rows of its (at most two) leaves
+        double u2[4], x0[4], x1[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             u2[u] = cur.k[u] >= 0 ? a.U2[int64_t(cur.k[u]) * 16 + c] : 0.0;
-            l0[u] = l1[u] = -1;
-            v0[u] = v1[u] = 0.0;
-            if (cur.ln[u] > 0) { l0[u] = a.idx3[cur.la[u]]; v0[u] = a.vals[cur.la[u]]; }
-            if (cur.ln[u] > 1) { l1[u] = a.idx3[cur.la[u] + 1]; v1[u] = a.vals[cur.la[u] + 1]; }
-        }
-        // stage B: U3 rows
-        double x0[4], x1[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            x0[u] = l0[u] >= 0 ? a.U3[int64_t(l0[u]) * 16 + c] : 0.0;
-            x1[u] = l1[u] >= 0 ? a.U3[int64_t(l1[u]) * 16 + c] : 0.0;
+            x0[u] = cur.l0[u] >= 0 ? a.U3[int64_t(cur.l0[u]) * 16 + c] : 0.0;
+            x1[u] = cur.l1[u] >= 0 ? a.U3[int64_t(cur.l1[u]) * 16 + c] : 0.0;
         }
         // mid level
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const double t1 = fma(v1[u], x1[u], v0[u] * x0[u]);
+            const double t1 = fma(cur.v1[u], x1[u], cur.v0[u] * x0[u]);
             const v4d t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(u2[u], t1, v4d{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 4; ++v) lds[u * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];
@@ -273,9 +266,8 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
             Ttmc4RowArgs ra{};
             ra.n_items = plan->n_items;
             ra.row_piece = plan->row_piece.p;
-            ra.piece_leaf = plan->piece_leaf.p;
+            ra.pieces = plan->pieces.p;
             ra.row_j = plan->row_j.p;
-            ra.piece_k = plan->piece_k.p;
             ra.idx0 = a.idx0;
             ra.idx3 = a.idx3;
             ra.vals = a.vals;

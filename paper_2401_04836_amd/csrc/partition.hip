@@ -584,15 +584,22 @@ __global__ void count_units_kernel(int64_t n, const int64_t *__restrict__ ptr, i
 }
 
 __global__ void fill_pieces_kernel(int64_t nodes, const int64_t *__restrict__ ptr2,
-                                   const int32_t *__restrict__ idx2, const int64_t *__restrict__ piece_off,
-                                   int64_t *piece_leaf, int32_t *piece_k, int64_t total, int64_t nnz) {
+                                   const int32_t *__restrict__ idx2, const int32_t *__restrict__ idx3,
+                                   const double *__restrict__ vals, const int64_t *__restrict__ piece_off,
+                                   PieceDesc *pieces) {
     const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (n == 0) piece_leaf[total] = nnz;
     if (n >= nodes) return;
     int64_t p = piece_off[n];
-    for (int64_t e = ptr2[n]; e < ptr2[n + 1]; e += kPieceLeaves, ++p) {
-        piece_leaf[p] = e;
-        piece_k[p] = idx2[n];
+    const int64_t end = ptr2[n + 1];
+    for (int64_t e = ptr2[n]; e < end; e += kPieceLeaves, ++p) {
+        PieceDesc d;
+        d.k = idx2[n];
+        d.l0 = idx3[e];
+        d.v0 = vals[e];
+        d.l1 = e + 1 < end ? idx3[e + 1] : -1;
+        d.v1 = e + 1 < end ? vals[e + 1] : 0.0;
+        d.pad = 0;
+        pieces[p] = d;
     }
 }
 
@@ -633,10 +640,9 @@ static conststn_status build_piece_rows(conststn_plan_s *plan) {
     count_units_kernel<<<dim3(unsigned(div_up(nodes, 256))), block>>>(nodes, X->ptr[2].p, kPieceLeaves, cnt.p);
     CST_HIP(hipGetLastError());
     CST_TRY(exscan(cnt.p, piece_off.p, nodes, &plan->n_pieces));
-    CST_TRY(plan->piece_leaf.alloc(size_t(plan->n_pieces) + 1));
-    CST_TRY(plan->piece_k.alloc(size_t(plan->n_pieces)));
+    CST_TRY(plan->pieces.alloc(size_t(plan->n_pieces)));
     fill_pieces_kernel<<<dim3(unsigned(div_up(nodes, 256))), block>>>(
-        nodes, X->ptr[2].p, X->idx[2].p, piece_off.p, plan->piece_leaf.p, plan->piece_k.p, plan->n_pieces, X->nnz);
+        nodes, X->ptr[2].p, X->idx[2].p, X->idx[3].p, X->vals.p, piece_off.p, plan->pieces.p);
     CST_HIP(hipGetLastError());
     CST_TRY(rows_of.alloc(fibers));
     CST_TRY(row_off.alloc(fibers));

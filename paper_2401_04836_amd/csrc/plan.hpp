@@ -59,6 +59,17 @@ struct alignas(16) RowDesc {
     int32_t j;              // level-1 index of the fiber
 };
 
+// One piece of the order-4 TTMc MFMA path: at most kPieceLeaves (= 2) consecutive leaves of one
+// (i,j,k) node, copied out of the CSF so that one 32-byte read brings everything the leaf stage
+// needs and no second, dependent load of the leaves follows.
+struct alignas(32) PieceDesc {
+    int32_t k;              // level-2 index of the node
+    int32_t l0, l1;         // leaf indices; l1 = -1 when the piece has one leaf
+    int32_t pad;
+    double v0, v1;          // leaf values (v1 = 0 when absent)
+};
+static_assert(kPieceLeaves == 2, "PieceDesc holds two leaves");
+
 // One of the two sub-tensors of the split rank-32 MTTKRP path: the leaves whose factor row is
 // "hot" (kept in LDS) or the rest.  X = X_hot + X_cold and the contraction is linear in X, so each
 // part is a CSF tensor of its own (only the slices and fibers that keep a leaf) with its own
@@ -128,8 +139,7 @@ struct conststn_plan_s {
     // TTMc order-4 MFMA path: level-2 nodes cut into "pieces" of at most kPieceLeaves leaves,
     // level-1 fibers cut into rows of at most 4 pieces; rows index pieces, pieces index leaves
     int64_t n_pieces = 0;
-    cst::DevBuf<int64_t> piece_leaf;       // [pieces+1] first leaf of each piece
-    cst::DevBuf<int32_t> piece_k;          // [pieces] level-2 index of the piece's node
+    cst::DevBuf<cst::PieceDesc> pieces;    // [pieces] first leaf, level-2 index, leaf count
     cst::DevBuf<int64_t> row_piece;        // [rows+1] first piece of each row
     cst::DevBuf<double> partial;           // partial row blocks
     // three-tensor network
