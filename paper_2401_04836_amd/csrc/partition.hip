@@ -422,11 +422,12 @@ conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
 // ---- TTMc: bounded items inside slices ----------------------------------------------------
 
 __global__ void ttmc_count_kernel(int64_t slices, const int64_t *__restrict__ unit_ptr, int64_t split,
-                                  int64_t *pieces, int64_t *part_cnt, int64_t *is_split) {
+                                  int64_t max_pieces, int64_t *pieces, int64_t *part_cnt, int64_t *is_split) {
     const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (s >= slices) return;
     const int64_t len = unit_ptr[s + 1] - unit_ptr[s];
-    const int64_t p = len <= split ? 1 : (len + split - 1) / split;
+    int64_t p = len <= split ? 1 : (len + split - 1) / split;
+    if (max_pieces > 0 && p > max_pieces) p = max_pieces;     // bounds the partial blocks of one slice
     pieces[s] = p;
     part_cnt[s] = p > 1 ? p : 0;
     is_split[s] = p > 1 ? 1 : 0;
@@ -527,20 +528,20 @@ __global__ void slice_rows_kernel(int64_t slices, int64_t fibers, const int64_t 
 
 static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
 
-static conststn_status build_rows(conststn_plan_s *plan) {
-    const conststn_csf_s *X = plan->X;
-    const int64_t fibers = X->nodes[1], slices = X->nodes[0];
+static conststn_status build_rows_core(int64_t slices, int64_t fibers, const int64_t *ptr0, const int64_t *ptr1,
+                                       const int32_t *idx1, DevBuf<RowDesc> &rows_out, DevBuf<int64_t> &slice_row,
+                                       int64_t &n_rows) {
     DevBuf<int64_t> rows_of, row_off;
     CST_TRY(rows_of.alloc(fibers));
     CST_TRY(row_off.alloc(fibers));
     const dim3 block(256);
-    fiber_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(fibers, X->ptr[1].p, rows_of.p);
+    fiber_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(fibers, ptr1, rows_of.p);
     CST_HIP(hipGetLastError());
-    CST_TRY(exscan(rows_of.p, row_off.p, fibers, &plan->n_rows_tab));
-    const int64_t rows = plan->n_rows_tab;
+    CST_TRY(exscan(rows_of.p, row_off.p, fibers, &n_rows));
+    const int64_t rows = n_rows;
     if (rows >= (int64_t(1) << 31)) { set_error("more than 2^31 rows"); return CONSTSTN_EUNSUPPORTED; }
-    CST_TRY(plan->rows.alloc(size_t(rows)));
-    CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));
+    CST_TRY(rows_out.alloc(size_t(rows)));
+    CST_TRY(slice_row.alloc(size_t(slices) + 1));
     {
         DevBuf<int64_t> leaf0;
         DevBuf<int32_t> j0, cnt0, id0, order;
@@ -553,7 +554,7 @@ static conststn_status build_rows(conststn_plan_s *plan) {
         CST_TRY(key0.alloc(size_t(rows)));
         CST_TRY(key1.alloc(size_t(rows)));
         fill_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
-            fibers, slices, X->ptr[0].p, X->ptr[1].p, X->idx[1].p, row_off.p, leaf0.p, j0.p, cnt0.p, key0.p, id0.p);
+            fibers, slices, ptr0, ptr1, idx1, row_off.p, leaf0.p, j0.p, cnt0.p, key0.p, id0.p);
         CST_HIP(hipGetLastError());
         if (rows > 0) {
             // stable sort by (slice, 16 - leaves): rows stay inside their slice, longest first
@@ -564,16 +565,22 @@ static conststn_status build_rows(conststn_plan_s *plan) {
             CST_TRY(temp.alloc(bytes));
             CST_HIP(rocprim::radix_sort_pairs(temp.p, bytes, key0.p, key1.p, id0.p, order.p, size_t(rows), 0u, end_bit));
             permute_rows_kernel<<<dim3(unsigned(div_up(rows, 256))), block>>>(
-                rows, order.p, leaf0.p, j0.p, cnt0.p, plan->rows.p);
+                rows, order.p, leaf0.p, j0.p, cnt0.p, rows_out.p);
             CST_HIP(hipGetLastError());
         }
         CST_HIP(hipDeviceSynchronize());
     }
     slice_rows_kernel<<<dim3(unsigned(div_up(slices + 1, 256))), block>>>(
-        slices, fibers, X->ptr[0].p, row_off.p, plan->n_rows_tab, plan->slice_row.p);
+        slices, fibers, ptr0, row_off.p, n_rows, slice_row.p);
     CST_HIP(hipGetLastError());
     CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
+}
+
+static conststn_status build_rows(conststn_plan_s *plan) {
+    const conststn_csf_s *X = plan->X;
+    return build_rows_core(X->nodes[0], X->nodes[1], X->ptr[0].p, X->ptr[1].p, X->idx[1].p, plan->rows,
+                           plan->slice_row, plan->n_rows_tab);
 }
 
 // ---- TTMc order-4 MFMA path: nodes -> pieces (<= kPieceLeaves leaves), fibers -> rows (<= 4 pieces)
@@ -664,6 +671,39 @@ static conststn_status build_piece_rows(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// Cuts every slice (a range of units: leaves, fibers or rows) into items of about `split` units
+// (at most max_pieces items per slice when max_pieces > 0); slices made of several items get
+// partial-result slots.
+static conststn_status build_items_core(int64_t slices, const int64_t *unit_ptr, int64_t split, int64_t max_pieces,
+                                        int order, const int64_t *ptr0, const int64_t *ptr1, int64_t row_elems,
+                                        DevBuf<SliceItem> &items, int64_t &n_items, int64_t &n_partials,
+                                        int64_t &n_split, DevBuf<int32_t> &split_slices,
+                                        DevBuf<int64_t> &split_first, DevBuf<int32_t> &split_count,
+                                        DevBuf<double> &partial) {
+    DevBuf<int64_t> pieces, part_cnt, is_split, item_off, part_off, split_rank;
+    CST_TRY(pieces.alloc(slices));
+    CST_TRY(part_cnt.alloc(slices));
+    CST_TRY(is_split.alloc(slices));
+    CST_TRY(item_off.alloc(slices));
+    CST_TRY(part_off.alloc(slices));
+    CST_TRY(split_rank.alloc(slices));
+    const dim3 grid(unsigned(div_up(slices, 256))), block(256);
+    ttmc_count_kernel<<<grid, block>>>(slices, unit_ptr, split, max_pieces, pieces.p, part_cnt.p, is_split.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(exscan(pieces.p, item_off.p, slices, &n_items));
+    CST_TRY(exscan(part_cnt.p, part_off.p, slices, &n_partials));
+    CST_TRY(exscan(is_split.p, split_rank.p, slices, &n_split));
+    CST_TRY(items.alloc(size_t(n_items)));
+    CST_TRY(split_slices.alloc(size_t(n_split)));
+    CST_TRY(split_first.alloc(size_t(n_split)));
+    CST_TRY(split_count.alloc(size_t(n_split)));
+    CST_TRY(partial.alloc(size_t(n_partials) * size_t(row_elems)));
+    ttmc_fill_kernel<<<grid, block>>>(slices, unit_ptr, pieces.p, item_off.p, part_off.p, split_rank.p, order, ptr0,
+                                      ptr1, items.p, split_slices.p, split_first.p, split_count.p);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
 conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t slices = X->nodes[0];
@@ -691,28 +731,9 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
         unit_ptr = plan->slice_row.p;
         split = env_int("CONSTSTN_TTMC4_ROWSPLIT", 256);
     }
-    DevBuf<int64_t> pieces, part_cnt, is_split, item_off, part_off, split_rank;
-    CST_TRY(pieces.alloc(slices));
-    CST_TRY(part_cnt.alloc(slices));
-    CST_TRY(is_split.alloc(slices));
-    CST_TRY(item_off.alloc(slices));
-    CST_TRY(part_off.alloc(slices));
-    CST_TRY(split_rank.alloc(slices));
-    const dim3 grid(unsigned(div_up(slices, 256))), block(256);
-    ttmc_count_kernel<<<grid, block>>>(slices, unit_ptr, split, pieces.p, part_cnt.p, is_split.p);
-    CST_HIP(hipGetLastError());
-    CST_TRY(exscan(pieces.p, item_off.p, slices, &plan->n_items));
-    CST_TRY(exscan(part_cnt.p, part_off.p, slices, &plan->n_partials));
-    CST_TRY(exscan(is_split.p, split_rank.p, slices, &plan->n_split));
-    CST_TRY(plan->items.alloc(size_t(plan->n_items)));
-    CST_TRY(plan->split_slices.alloc(size_t(plan->n_split)));
-    CST_TRY(plan->split_first.alloc(size_t(plan->n_split)));
-    CST_TRY(plan->split_count.alloc(size_t(plan->n_split)));
-    CST_TRY(plan->partial.alloc(size_t(plan->n_partials) * size_t(plan->row_elems)));
-    ttmc_fill_kernel<<<grid, block>>>(slices, unit_ptr, pieces.p, item_off.p, part_off.p, split_rank.p,
-                                      order, X->ptr[0].p, X->ptr[1].p, plan->items.p,
-                                      plan->split_slices.p, plan->split_first.p, plan->split_count.p);
-    CST_HIP(hipGetLastError());
+    CST_TRY(build_items_core(slices, unit_ptr, split, 0, order, X->ptr[0].p, X->ptr[1].p, plan->row_elems,
+                             plan->items, plan->n_items, plan->n_partials, plan->n_split, plan->split_slices,
+                             plan->split_first, plan->split_count, plan->partial));
     CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
 }
