@@ -25,9 +25,10 @@ FP64_PEAK_TFLOPS = 78.6
 CSRC = os.path.join(ROOT, "paper_2401_04836_amd", "csrc")
 KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "ttmc3": ["kernels_ttmc3.hip", "partition.hip"],
-                  "ttmc4": ["kernels_ttmc4.hip", "partition.hip"]}
+                  "ttmc4": ["kernels_ttmc4.hip", "partition.hip"],
+                  "sptn3": ["kernels_sptn3.hip", "partition.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
-                "ttmc3": "ttmc3_mfma_kernel<4,1>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
+                "ttmc3": "ttmc3_mfma_kernel<4,2>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
                 "generic": "generic_stmt_kernel (one launch per statement)"}
 # what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they
 # compute (HBM); the order-4 TTMc and the three-tensor network are dense contractions per fiber
