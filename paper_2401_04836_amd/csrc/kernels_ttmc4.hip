@@ -105,130 +105,115 @@ ttmc4_kernel(Ttmc4Args a) {
 // ---- MFMA kernel (all three ranks equal to 16) ----------------------------------------------
 //
 // Both dense stages run on the fp64 matrix cores (v_mfma_f64_16x16x4, K = 4):
-//   mid level   T2 (16x16) = U2[K,:]^T . T1        K = four "pieces" of (i,j,k) nodes
-//   slice level Y_i (16x256) = U1[J,:]^T . T2      K = four "rows" of (i,j) fibers
-// The plan cuts every node into pieces of at most two leaves and every fiber into rows of at most
-// four pieces (partition.hip); a long node or fiber simply contributes several K entries with the
-// same factor row, which is legal by distributivity.  Every K-step therefore does the same,
-// loop-free amount of work whatever the skew of the tensor.
-// One wavefront per item (a range of rows of one slice), lane = (slot, c), slot = lane/16.
-// A K-step takes four rows.  For each of them the slots are the row's four pieces: lane (s,c)
-// builds T1_piece_s[r3 = c] from at most two leaves and supplies U2[k_s, r2 = c]; one MFMA gives
-// the row's T2 in the accumulator layout (register v of lane (s,c) = T2[r2 = s+4v][r3 = c]).  The
-// four T2 tiles pass through a wave-private LDS buffer so that in the slice-level MFMAs slot s
-// supplies the tile of row s: B_t = T2_s[r2 = t][r3 = c] for the 16 column tiles, A = U1[j_s, c].
-// The plan copies each piece's level-2 index, leaf indices and leaf values into one 32-byte record;
-// row ranges are fetched two K-steps ahead and piece records one ahead, so a K-step waits for one
-// memory round trip (the factor rows) and issues 21 vector loads.
+//   mid level   T2_f (16x16) = sum over the fiber's pieces  U2[k,:]^T . T1      K = four pieces
+//   slice level Y_i (16x256) += U1[J,:]^T . T2                                  K = four fibers
+// A piece is at most two leaves of one (i,j,k) node.  The plan stores the pieces of a fiber four
+// at a time in "groups" (the last group of a fiber padded with empty records) and the fibers of
+// a slice four at a time in "K-steps"; a long node or fiber simply gives several pieces or
+// groups, which is legal by distributivity, so the kernel walks ONE flat stream of groups whatever
+// the skew of the tensor.  Per group: lane (s,c) takes record s -- level-2 index, two leaf indices,
+// two leaf values, one 32-byte read -- builds T1_s[r3 = c] and supplies U2[k_s, r2 = c]; one
+// matrix instruction adds the group to the fiber's T2 (accumulator layout: register v of lane
+// (s,c) = T2[r2 = s+4v][r3 = c]).  When a group ends its fiber the tile goes to the wave-private
+// LDS buffer; when it ends its K-step, slot s reads back the tile of fiber s as the B operand
+// of the 16 slice-level instructions, A = U1[j_s, c].  The structure (ends a fiber / ends a
+// K-step / starts a K-step, and the four j of a K-step) travels in the records, so nothing
+// but the stream itself is read.  A fiber costs ceil(pieces/4) mid-level instructions and
+// exactly four slice-level ones, however many pieces it has.
+// Records are fetched three groups ahead and the factor rows one group ahead (register rings,
+// loop unrolled four times), so a group waits for no load issued in its own iteration.
 typedef double v4d __attribute__((ext_vector_type(4)));
 constexpr int kT2Stride = 16 * 16 + 16;        // doubles per tile in LDS (+16: bank skew)
 
 struct Ttmc4RowArgs {
     int64_t n_items;
-    const int64_t *row_piece;
-    const PieceDesc *pieces;
-    const int32_t *row_j;
-    const int32_t *idx0, *idx3;
-    const double *vals;
-    const SliceItem *items;
+    const int64_t *kstep_group;
+    const PieceDesc *rec;
+    const int32_t *idx0;
+    const SliceItem *items;                 // ranges of K-steps inside one slice
     const double *U1, *U2, *U3;
     double *out, *partial;
     int compact;
 };
 
-// PARTS waves share an item, each owning 16/PARTS of the column tiles (fewer accumulator
-// registers, more resident waves; the cheap mid level is repeated by every part).
-template <int PARTS>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PARTS == 1 ? 2 : (PARTS == 2 ? 3 : 5), 8)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8)))
 ttmc4_mfma_kernel(Ttmc4RowArgs a) {
-    constexpr int TN = 16 / PARTS;
     __shared__ double t2buf[4][4 * kT2Stride];
     const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
-    const int part = int(blockIdx.x % unsigned(PARTS));
-    const int64_t w = uni64(int64_t(blockIdx.x / unsigned(PARTS)) * 4 + wv);
+    const int slot = lane >> 4, c = lane & 15;
+    double *lds = t2buf[wv];
+    // tiles of absent fibers (a slice's last K-step may hold fewer than four) are multiplied by a
+    // zero A operand: whatever they hold must be finite
+    for (int e = lane; e < 4 * kT2Stride; e += 64) lds[e] = 0.0;
+    const int64_t w = uni64(int64_t(blockIdx.x) * 4 + wv);
     if (w >= a.n_items) return;
     const SliceItem it = a.items[w];
     const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
-    const int64_t ra = uni64(it.begin), rb = uni64(it.end), dest = uni64(it.dest);
-    const int slot = lane >> 4, c = lane & 15;
-    double *lds = t2buf[wv];
+    const int64_t dest = uni64(it.dest);
+    const int64_t ga = uni64(a.kstep_group[it.begin]), gb = uni64(a.kstep_group[it.end]);
 
-    v4d acc[TN];
+    v4d acc[16];
 #pragma unroll
-    for (int t = 0; t < TN; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < 16; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
+    v4d t2 = v4d{0.0, 0.0, 0.0, 0.0};
+    double av = 0.0;                         // U1[j_s, c] of the current K-step
+    int ft = 0;                              // fibers of the current K-step already parked in LDS
 
-    // row descriptors of a K-step: piece ranges of its four rows (every lane), j of row g+slot
-    struct Rows { int64_t pa[4]; int pn[4]; int32_t j; };
-    auto load_rows = [&](int64_t g) -> Rows {
-        Rows r;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            r.pa[u] = 0;
-            r.pn[u] = 0;
-            if (g + u < rb) { r.pa[u] = a.row_piece[g + u]; r.pn[u] = int(a.row_piece[g + u + 1] - r.pa[u]); }
-        }
-        r.j = g + slot < rb ? a.row_j[g + slot] : -1;
-        return r;
+    constexpr int kRec = 4;                  // record ring (fetched kRec - 1 groups ahead)
+    PieceDesc rec[kRec];
+    double gu2[2], gx0[2], gx1[2];           // factor-row ring (fetched one group ahead)
+    auto load_rec = [&](int64_t g) -> PieceDesc {
+        return a.rec[(g < gb ? g : gb - 1) * 4 + slot];
     };
-    // pieces: piece pa[u]+slot of each row -- level-2 index, leaf indices and leaf values in one read
-    struct Pieces { int32_t k[4], l0[4], l1[4]; double v0[4], v1[4]; int32_t j; };
-    auto load_pieces = [&](const Rows &r) -> Pieces {
-        Pieces p;
-        p.j = r.j;
+    auto load_rows = [&](const PieceDesc &r, double &u2, double &x0, double &x1) {
+        const int32_t k = r.k >= 0 ? int32_t(uint32_t(r.k) & kGrpIndexMask) : 0;      // empty record: row 0, value 0
+        u2 = a.U2[int64_t(k) * 16 + c];
+        x0 = a.U3[int64_t(r.l0 >= 0 ? r.l0 : 0) * 16 + c];
+        x1 = a.U3[int64_t(r.l1 >= 0 ? r.l1 : 0) * 16 + c];
+    };
+    auto consume = [&](const PieceDesc &r, double u2, double x0, double x1) {
+        const uint32_t flags = uint32_t(__builtin_amdgcn_readfirstlane(r.k));          // same on the four records
+        if (flags & kGrpStartsKstep) av = r.pad >= 0 ? a.U1[int64_t(r.pad) * 16 + c] : 0.0;
+        // empty records and absent second leaves carry value 0
+        const double t1 = fma(r.v1, x1, r.v0 * x0);
+        t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(r.k >= 0 ? u2 : 0.0, t1, t2, 0, 0, 0);
+        if (flags & kGrpEndsFiber) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            p.k[u] = p.l0[u] = p.l1[u] = -1;
-            p.v0[u] = p.v1[u] = 0.0;
-            if (slot < r.pn[u]) {
-                const PieceDesc d = a.pieces[r.pa[u] + slot];
-                p.k[u] = d.k;
-                p.l0[u] = d.l0;
-                p.l1[u] = d.l1;
-                p.v0[u] = d.v0;
-                p.v1[u] = d.v1;
+            for (int v = 0; v < 4; ++v) lds[ft * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];
+            t2 = v4d{0.0, 0.0, 0.0, 0.0};
+            ++ft;
+            if (flags & kGrpEndsKstep) {
+                // slot s supplies fiber s; fibers the K-step lacks have av = 0
+                const double a_op = slot < ft ? av : 0.0;
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {
+                    const double bv = lds[slot * kT2Stride + t * 16 + c];
+                    acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a_op, bv, acc[t], 0, 0, 0);
+                }
+                ft = 0;
             }
         }
-        return p;
     };
-    Rows r2 = load_rows(ra);
-    Pieces cur = load_pieces(r2);
-    r2 = load_rows(ra + 4);
-    for (int64_t g = ra; g < rb; g += 4) {
-        const Pieces nxt = load_pieces(r2);              // K-step g+4
-        r2 = load_rows(g + 8);
-        const double av = cur.j >= 0 ? a.U1[int64_t(cur.j) * 16 + c] : 0.0;
-        // factor rows: U2 entry of each piece, U3 rows of its (at most two) leaves
-        double u2[4], x0[4], x1[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            u2[u] = cur.k[u] >= 0 ? a.U2[int64_t(cur.k[u]) * 16 + c] : 0.0;
-            x0[u] = cur.l0[u] >= 0 ? a.U3[int64_t(cur.l0[u]) * 16 + c] : 0.0;
-            x1[u] = cur.l1[u] >= 0 ? a.U3[int64_t(cur.l1[u]) * 16 + c] : 0.0;
+    for (int u = 0; u < kRec - 1; ++u) rec[u] = load_rec(ga + u);
+    load_rows(rec[0], gu2[0], gx0[0], gx1[0]);
+    for (int64_t g0 = ga; g0 < gb; g0 += kRec) {
+#pragma unroll
+        for (int u = 0; u < kRec; ++u) {
+            const int64_t g = g0 + u;
+            rec[(u + kRec - 1) % kRec] = load_rec(g + kRec - 1);
+            load_rows(rec[(u + 1) % kRec], gu2[(u + 1) % 2], gx0[(u + 1) % 2], gx1[(u + 1) % 2]);
+            if (g < gb) consume(rec[u], gu2[u % 2], gx0[u % 2], gx1[u % 2]);
         }
-        // mid level
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const double t1 = fma(cur.v1[u], x1[u], cur.v0[u] * x0[u]);
-            const v4d t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(u2[u], t1, v4d{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) lds[u * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];
-        }
-        // slice level: slot s supplies row s; 16 column tiles t = r2
-#pragma unroll
-        for (int t = 0; t < TN; ++t) {
-            const double bv = lds[slot * kT2Stride + (part * TN + t) * 16 + c];
-            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[t], 0, 0, 0);
-        }
-        cur = nxt;
     }
     const int64_t RR = 4096;
     double *base = dest < 0 ? a.out + (a.compact ? int64_t(s) : int64_t(a.idx0[s])) * RR
                             : a.partial + dest * RR;
-    // acc[t][v] = Y[r1 = slot + 4v][r2 = part*TN + t][r3 = c]
+    // acc[t][v] = Y[r1 = slot + 4v][r2 = t][r3 = c]
 #pragma unroll
-    for (int t = 0; t < TN; ++t)
+    for (int t = 0; t < 16; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) base[((slot + 4 * v) * 16 + part * TN + t) * 16 + c] = acc[t][v];
+        for (int v = 0; v < 4; ++v) base[((slot + 4 * v) * 16 + t) * 16 + c] = acc[t][v];
 }
 
 conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *dense, double *out,
@@ -265,12 +250,9 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
         if (plan->use_rows) {
             Ttmc4RowArgs ra{};
             ra.n_items = plan->n_items;
-            ra.row_piece = plan->row_piece.p;
-            ra.pieces = plan->pieces.p;
-            ra.row_j = plan->row_j.p;
+            ra.kstep_group = plan->kstep_group.p;
+            ra.rec = plan->pieces.p;
             ra.idx0 = a.idx0;
-            ra.idx3 = a.idx3;
-            ra.vals = a.vals;
             ra.items = a.items;
             ra.U1 = a.U1;
             ra.U2 = a.U2;
@@ -278,14 +260,7 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
             ra.out = out;
             ra.partial = a.partial;
             ra.compact = a.compact;
-            const int64_t groups = div_up(a.n_items, 4);
-            const int64_t parts = env_int("CONSTSTN_TTMC4_PARTS", 1);
-            if (parts == 4)
-                ttmc4_mfma_kernel<4><<<dim3(unsigned(groups * 4)), dim3(256), 0, stream>>>(ra);
-            else if (parts == 2)
-                ttmc4_mfma_kernel<2><<<dim3(unsigned(groups * 2)), dim3(256), 0, stream>>>(ra);
-            else
-                ttmc4_mfma_kernel<1><<<dim3(unsigned(groups)), dim3(256), 0, stream>>>(ra);
+            ttmc4_mfma_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(ra);
         } else
             ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
     }

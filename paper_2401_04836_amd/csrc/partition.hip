@@ -590,82 +590,123 @@ __global__ void count_units_kernel(int64_t n, const int64_t *__restrict__ ptr, i
     if (i < n) cnt[i] = (ptr[i + 1] - ptr[i] + per - 1) / per;
 }
 
-__global__ void fill_pieces_kernel(int64_t nodes, const int64_t *__restrict__ ptr2,
-                                   const int32_t *__restrict__ idx2, const int32_t *__restrict__ idx3,
-                                   const double *__restrict__ vals, const int64_t *__restrict__ piece_off,
-                                   PieceDesc *pieces) {
-    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (n >= nodes) return;
-    int64_t p = piece_off[n];
-    const int64_t end = ptr2[n + 1];
-    for (int64_t e = ptr2[n]; e < end; e += kPieceLeaves, ++p) {
+// Order-4 MFMA path.  The pieces of a fiber are taken four at a time ("groups", the K = 4 of the
+// mid-level matrix instruction; the last group of a fiber is padded with empty records) and the
+// fibers of a slice four at a time ("K-steps", the K = 4 of the slice-level instruction).  The
+// kernel then walks one flat stream of groups; everything it needs to know about the structure
+// travels in the records: flag bits in the k field say whether a group ends its fiber, ends its
+// K-step or starts one, and in the first group of a K-step the spare field of slot s holds the
+// level-1 index of the K-step's fiber s.
+__global__ void fiber_groups_kernel(int64_t fibers, int64_t nodes, const int64_t *__restrict__ ptr1,
+                                    const int64_t *__restrict__ piece_off, int64_t total_pieces,
+                                    int64_t *groups_of) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f >= fibers) return;
+    const int64_t a = piece_off[ptr1[f]];
+    const int64_t b = ptr1[f + 1] < nodes ? piece_off[ptr1[f + 1]] : total_pieces;
+    groups_of[f] = (b - a + 3) / 4;
+}
+
+__global__ void slice_ksteps_kernel(int64_t slices, const int64_t *__restrict__ ptr0, int64_t *ksteps_of) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s < slices) ksteps_of[s] = (ptr0[s + 1] - ptr0[s] + 3) / 4;
+}
+
+__global__ void kstep_groups_kernel(int64_t slices, const int64_t *__restrict__ ptr0,
+                                    const int64_t *__restrict__ slice_kstep, const int64_t *__restrict__ grp_off,
+                                    int64_t total_ksteps, int64_t total_groups, int64_t *kstep_group) {
+    const int64_t s = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (s == 0) kstep_group[total_ksteps] = total_groups;
+    if (s >= slices) return;
+    int64_t k = slice_kstep[s];
+    for (int64_t f = ptr0[s]; f < ptr0[s + 1]; f += 4, ++k) kstep_group[k] = grp_off[f];
+}
+
+__global__ void fill_groups_kernel(int64_t fibers, int64_t slices, const int64_t *__restrict__ ptr0,
+                                   const int64_t *__restrict__ ptr1, const int64_t *__restrict__ ptr2,
+                                   const int32_t *__restrict__ idx1, const int32_t *__restrict__ idx2,
+                                   const int32_t *__restrict__ idx3, const double *__restrict__ vals,
+                                   const int64_t *__restrict__ grp_off, PieceDesc *rec) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f >= fibers) return;
+    int64_t lo = 0, hi = slices;                // slice of fiber f: last s with ptr0[s] <= f
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr0[mid] <= f) lo = mid; else hi = mid;
+    }
+    const int64_t fa = ptr0[lo], fb = ptr0[lo + 1];
+    const int q = int((f - fa) & 3);
+    const bool closes_kstep = q == 3 || f + 1 == fb;
+    int64_t r = grp_off[f] * 4;                 // next record
+    const int64_t r0 = r;
+    auto put = [&](int32_t k, int32_t l0, int32_t l1, double v0, double v1) {
         PieceDesc d;
-        d.k = idx2[n];
-        d.l0 = idx3[e];
-        d.v0 = vals[e];
-        d.l1 = e + 1 < end ? idx3[e + 1] : -1;
-        d.v1 = e + 1 < end ? vals[e + 1] : 0.0;
+        d.k = k;
+        d.l0 = l0;
+        d.l1 = l1;
         d.pad = 0;
-        pieces[p] = d;
+        d.v0 = v0;
+        d.v1 = v1;
+        rec[r++] = d;
+    };
+    for (int64_t n = ptr1[f]; n < ptr1[f + 1]; ++n) {
+        const int64_t end = ptr2[n + 1];
+        for (int64_t e = ptr2[n]; e < end; e += kPieceLeaves)
+            put(idx2[n], idx3[e], e + 1 < end ? idx3[e + 1] : -1, vals[e], e + 1 < end ? vals[e + 1] : 0.0);
+    }
+    while ((r - r0) & 3) put(int32_t(0x80000000u), -1, -1, 0.0, 0.0);          // empty records
+    // structure flags on every record of a group; level-1 indices on the first group of a K-step
+    const int64_t groups = (r - r0) >> 2;
+    for (int64_t g = 0; g < groups; ++g) {
+        uint32_t flags = 0;
+        if (g + 1 == groups) flags |= kGrpEndsFiber | (closes_kstep ? kGrpEndsKstep : 0u);
+        if (g == 0 && q == 0) flags |= kGrpStartsKstep;
+        for (int sl = 0; sl < 4; ++sl) {
+            PieceDesc &d = rec[r0 + g * 4 + sl];
+            d.k = int32_t(uint32_t(d.k) | flags);
+            if (g == 0 && q == 0) d.pad = f + sl < fb ? idx1[f + sl] : -1;
+        }
     }
 }
 
-// pieces of fiber f: piece_off[ptr1[f]] .. piece_off[ptr1[f+1]] (piece_off_end = total for the last)
-__global__ void fiber_piece_rows_kernel(int64_t fibers, int64_t nodes, const int64_t *__restrict__ ptr1,
-                                        const int64_t *__restrict__ piece_off, int64_t total_pieces,
-                                        int64_t *rows_of) {
-    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (f >= fibers) return;
-    const int64_t a = piece_off[ptr1[f]];
-    const int64_t b = ptr1[f + 1] < nodes ? piece_off[ptr1[f + 1]] : total_pieces;
-    rows_of[f] = (b - a + 3) / 4;
-}
-
-__global__ void fill_piece_rows_kernel(int64_t fibers, int64_t nodes, const int64_t *__restrict__ ptr1,
-                                       const int32_t *__restrict__ idx1, const int64_t *__restrict__ piece_off,
-                                       int64_t total_pieces, const int64_t *__restrict__ row_off,
-                                       int64_t *row_piece, int32_t *row_j, int64_t total_rows) {
-    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (f == 0) row_piece[total_rows] = total_pieces;
-    if (f >= fibers) return;
-    const int64_t a = piece_off[ptr1[f]];
-    const int64_t b = ptr1[f + 1] < nodes ? piece_off[ptr1[f + 1]] : total_pieces;
-    int64_t r = row_off[f];
-    for (int64_t p = a; p < b; p += 4, ++r) {
-        row_piece[r] = p;
-        row_j[r] = idx1[f];
-    }
-}
-
-static conststn_status build_piece_rows(conststn_plan_s *plan) {
+static conststn_status build_piece_groups(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t slices = X->nodes[0], fibers = X->nodes[1], nodes = X->nodes[2];
+    const int64_t K = X->dims[X->mode_order[2]];
+    if (K >= (int64_t(1) << 28)) { set_error("level-2 extent of 2^28 or more"); return CONSTSTN_EUNSUPPORTED; }
     const dim3 block(256);
-    DevBuf<int64_t> cnt, piece_off, rows_of, row_off;
+    DevBuf<int64_t> cnt, piece_off, groups_of, grp_off, ksteps_of;
     CST_TRY(cnt.alloc(nodes));
     CST_TRY(piece_off.alloc(nodes));
     count_units_kernel<<<dim3(unsigned(div_up(nodes, 256))), block>>>(nodes, X->ptr[2].p, kPieceLeaves, cnt.p);
     CST_HIP(hipGetLastError());
-    CST_TRY(exscan(cnt.p, piece_off.p, nodes, &plan->n_pieces));
+    int64_t total_pieces = 0;
+    CST_TRY(exscan(cnt.p, piece_off.p, nodes, &total_pieces));
+    CST_TRY(groups_of.alloc(fibers));
+    CST_TRY(grp_off.alloc(fibers));
+    fiber_groups_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(fibers, nodes, X->ptr[1].p, piece_off.p,
+                                                                       total_pieces, groups_of.p);
+    CST_HIP(hipGetLastError());
+    int64_t total_groups = 0;
+    CST_TRY(exscan(groups_of.p, grp_off.p, fibers, &total_groups));
+    plan->n_pieces = total_groups * 4;
+    CST_TRY(ksteps_of.alloc(slices));
+    CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));             // first K-step of each slice
+    slice_ksteps_kernel<<<dim3(unsigned(div_up(slices, 256))), block>>>(slices, X->ptr[0].p, ksteps_of.p);
+    CST_HIP(hipGetLastError());
+    int64_t total_ksteps = 0;
+    CST_TRY(exscan(ksteps_of.p, plan->slice_row.p, slices, &total_ksteps));
+    CST_HIP(hipMemcpy(plan->slice_row.p + slices, &total_ksteps, sizeof(int64_t), hipMemcpyHostToDevice));
+    plan->n_rows_tab = total_ksteps;
+    CST_TRY(plan->kstep_group.alloc(size_t(total_ksteps) + 1));
+    kstep_groups_kernel<<<dim3(unsigned(div_up(slices, 256))), block>>>(slices, X->ptr[0].p, plan->slice_row.p,
+                                                                       grp_off.p, total_ksteps, total_groups,
+                                                                       plan->kstep_group.p);
+    CST_HIP(hipGetLastError());
     CST_TRY(plan->pieces.alloc(size_t(plan->n_pieces)));
-    fill_pieces_kernel<<<dim3(unsigned(div_up(nodes, 256))), block>>>(
-        nodes, X->ptr[2].p, X->idx[2].p, X->idx[3].p, X->vals.p, piece_off.p, plan->pieces.p);
-    CST_HIP(hipGetLastError());
-    CST_TRY(rows_of.alloc(fibers));
-    CST_TRY(row_off.alloc(fibers));
-    fiber_piece_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
-        fibers, nodes, X->ptr[1].p, piece_off.p, plan->n_pieces, rows_of.p);
-    CST_HIP(hipGetLastError());
-    CST_TRY(exscan(rows_of.p, row_off.p, fibers, &plan->n_rows_tab));
-    CST_TRY(plan->row_piece.alloc(size_t(plan->n_rows_tab) + 1));
-    CST_TRY(plan->row_j.alloc(size_t(plan->n_rows_tab)));
-    CST_TRY(plan->slice_row.alloc(size_t(slices) + 1));
-    fill_piece_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
-        fibers, nodes, X->ptr[1].p, X->idx[1].p, piece_off.p, plan->n_pieces, row_off.p, plan->row_piece.p,
-        plan->row_j.p, plan->n_rows_tab);
-    CST_HIP(hipGetLastError());
-    slice_rows_kernel<<<dim3(unsigned(div_up(slices + 1, 256))), block>>>(
-        slices, fibers, X->ptr[0].p, row_off.p, plan->n_rows_tab, plan->slice_row.p);
+    fill_groups_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
+        fibers, slices, X->ptr[0].p, X->ptr[1].p, X->ptr[2].p, X->idx[1].p, X->idx[2].p, X->idx[3].p, X->vals.p,
+        grp_off.p, plan->pieces.p);
     CST_HIP(hipGetLastError());
     CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
@@ -727,9 +768,9 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     if (order == 4 && plan->rank_of_level[1] == 16 && plan->rank_of_level[2] == 16 &&
         plan->rank_of_level[3] == 16 && env_int("CONSTSTN_TTMC4_NO_MFMA", 0) == 0) {
         plan->use_rows = true;
-        CST_TRY(build_piece_rows(plan));
-        unit_ptr = plan->slice_row.p;
-        split = env_int("CONSTSTN_TTMC4_ROWSPLIT", 256);
+        CST_TRY(build_piece_groups(plan));
+        unit_ptr = plan->slice_row.p;                 // items are ranges of K-steps (four fibers each)
+        split = env_int("CONSTSTN_TTMC4_KSPLIT", 64);
     }
     CST_TRY(build_items_core(slices, unit_ptr, split, 0, order, X->ptr[0].p, X->ptr[1].p, plan->row_elems,
                              plan->items, plan->n_items, plan->n_partials, plan->n_split, plan->split_slices,

@@ -63,12 +63,15 @@ struct alignas(16) RowDesc {
 // (i,j,k) node, copied out of the CSF so that one 32-byte read brings everything the leaf stage
 // needs and no second, dependent load of the leaves follows.
 struct alignas(32) PieceDesc {
-    int32_t k;              // level-2 index of the node
+    int32_t k;              // level-2 index of the node | kGrp* flags; negative: empty record
     int32_t l0, l1;         // leaf indices; l1 = -1 when the piece has one leaf
-    int32_t pad;
+    int32_t pad;            // first group of a K-step, slot s: level-1 index of the K-step's fiber s (-1: none)
     double v0, v1;          // leaf values (v1 = 0 when absent)
 };
 static_assert(kPieceLeaves == 2, "PieceDesc holds two leaves");
+// structure flags carried in PieceDesc::k (the same on the four records of a group)
+constexpr uint32_t kGrpEndsFiber = 1u << 28, kGrpEndsKstep = 1u << 29, kGrpStartsKstep = 1u << 30,
+                   kGrpIndexMask = (1u << 28) - 1u;
 
 // One of the two sub-tensors of the split rank-32 MTTKRP path: the leaves whose factor row is
 // "hot" (kept in LDS) or the rest.  X = X_hot + X_cold and the contraction is linear in X, so each
@@ -140,7 +143,7 @@ struct conststn_plan_s {
     // level-1 fibers cut into rows of at most 4 pieces; rows index pieces, pieces index leaves
     int64_t n_pieces = 0;
     cst::DevBuf<cst::PieceDesc> pieces;    // [pieces] first leaf, level-2 index, leaf count
-    cst::DevBuf<int64_t> row_piece;        // [rows+1] first piece of each row
+    cst::DevBuf<int64_t> kstep_group;      // [K-steps+1] first group (of four piece records) of each K-step
     cst::DevBuf<double> partial;           // partial row blocks
     // three-tensor network
     cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1
