@@ -10,6 +10,8 @@
 // slice).  Lane = (q, r3) with q = lane/16: the four lane rows split the leaves of a node for
 // T1 (then an xor-shuffle sum), and row q holds T2[r2, r3] for r2 = q, q+4, q+8, q+12 and the
 // matching 16 x 4 part of Y_i in registers.
+#include <type_traits>
+
 #include "plan.hpp"
 
 namespace cst {
@@ -112,7 +114,7 @@ ttmc4_kernel(Ttmc4Args a) {
 // a slice four at a time in "K-steps"; a long node or fiber simply gives several pieces or
 // groups, which is legal by distributivity, so the kernel walks ONE flat stream of groups whatever
 // the skew of the tensor.  Per group: lane (s,c) takes record s -- level-2 index, two leaf indices,
-// two leaf values, one 32-byte read -- builds T1_s[r3 = c] and supplies U2[k_s, r2 = c]; one
+// two leaf values, 32 bytes -- builds T1_s[r3 = c] and supplies U2[k_s, r2 = c]; one
 // matrix instruction adds the group to the fiber's T2 (accumulator layout: register v of lane
 // (s,c) = T2[r2 = s+4v][r3 = c]).  When a group ends its fiber the tile goes to the wave-private
 // LDS buffer; when it ends its K-step, slot s reads back the tile of fiber s as the B operand
@@ -159,24 +161,47 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
     double av = 0.0;                         // U1[j_s, c] of the current K-step
     int ft = 0;                              // fibers of the current K-step already parked in LDS
 
+    // A group's four records are 128 bytes.  Lane (s, c) fetches dword c mod 8 of record s -- one
+    // 4-byte load per lane for the whole group instead of two 16-byte ones -- and the eight
+    // dwords of a record are handed round inside the 16-lane row when they are needed.
     constexpr int kRec = 4;                  // record ring (fetched kRec - 1 groups ahead)
-    PieceDesc rec[kRec];
+    uint32_t raw[kRec];
     double gu2[2], gx0[2], gx1[2];           // factor-row ring (fetched one group ahead)
-    auto load_rec = [&](int64_t g) -> PieceDesc {
-        return a.rec[(g < gb ? g : gb - 1) * 4 + slot];
+    const uint32_t *words = reinterpret_cast<const uint32_t *>(a.rec);
+    auto load_rec = [&](int64_t g) -> uint32_t {
+        return words[((g < gb ? g : gb - 1) * 4 + slot) * 8 + (c & 7)];
     };
-    auto load_rows = [&](const PieceDesc &r, double &u2, double &x0, double &x1) {
-        const int32_t k = r.k >= 0 ? int32_t(uint32_t(r.k) & kGrpIndexMask) : 0;      // empty record: row 0, value 0
+    auto field = [&](uint32_t x, auto which) -> int32_t {
+        return __builtin_amdgcn_mov_dpp(int(x), 0x150 + decltype(which)::value, 0xf, 0xf, false);
+    };
+    auto field64 = [&](uint32_t x, auto lo, auto hi) -> double {
+        return __hiloint2double(field(x, hi), field(x, lo));
+    };
+    using W0 = std::integral_constant<int, 0>;
+    using W1 = std::integral_constant<int, 1>;
+    using W2 = std::integral_constant<int, 2>;
+    using W3 = std::integral_constant<int, 3>;
+    using W4 = std::integral_constant<int, 4>;
+    using W5 = std::integral_constant<int, 5>;
+    using W6 = std::integral_constant<int, 6>;
+    using W7 = std::integral_constant<int, 7>;
+    auto load_rows = [&](uint32_t x, double &u2, double &x0, double &x1) {
+        const int32_t kf = field(x, W0{}), l0 = field(x, W1{}), l1 = field(x, W2{});
+        const int32_t k = kf >= 0 ? int32_t(uint32_t(kf) & kGrpIndexMask) : 0;         // empty record: row 0, value 0
         u2 = a.U2[int64_t(k) * 16 + c];
-        x0 = a.U3[int64_t(r.l0 >= 0 ? r.l0 : 0) * 16 + c];
-        x1 = a.U3[int64_t(r.l1 >= 0 ? r.l1 : 0) * 16 + c];
+        x0 = a.U3[int64_t(l0 >= 0 ? l0 : 0) * 16 + c];
+        x1 = a.U3[int64_t(l1 >= 0 ? l1 : 0) * 16 + c];
     };
-    auto consume = [&](const PieceDesc &r, double u2, double x0, double x1) {
-        const uint32_t flags = uint32_t(__builtin_amdgcn_readfirstlane(r.k));          // same on the four records
-        if (flags & kGrpStartsKstep) av = r.pad >= 0 ? a.U1[int64_t(r.pad) * 16 + c] : 0.0;
+    auto consume = [&](uint32_t x, double u2, double x0, double x1) {
+        const int32_t kf = field(x, W0{});
+        const uint32_t flags = uint32_t(__builtin_amdgcn_readfirstlane(kf));            // same on the four records
+        if (flags & kGrpStartsKstep) {
+            const int32_t j = field(x, W3{});
+            av = j >= 0 ? a.U1[int64_t(j) * 16 + c] : 0.0;
+        }
         // empty records and absent second leaves carry value 0
-        const double t1 = fma(r.v1, x1, r.v0 * x0);
-        t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(r.k >= 0 ? u2 : 0.0, t1, t2, 0, 0, 0);
+        const double t1 = fma(field64(x, W6{}, W7{}), x1, field64(x, W4{}, W5{}) * x0);
+        t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(kf >= 0 ? u2 : 0.0, t1, t2, 0, 0, 0);
         if (flags & kGrpEndsFiber) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) lds[ft * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];
@@ -195,15 +220,15 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
         }
     };
 #pragma unroll
-    for (int u = 0; u < kRec - 1; ++u) rec[u] = load_rec(ga + u);
-    load_rows(rec[0], gu2[0], gx0[0], gx1[0]);
+    for (int u = 0; u < kRec - 1; ++u) raw[u] = load_rec(ga + u);
+    load_rows(raw[0], gu2[0], gx0[0], gx1[0]);
     for (int64_t g0 = ga; g0 < gb; g0 += kRec) {
 #pragma unroll
         for (int u = 0; u < kRec; ++u) {
             const int64_t g = g0 + u;
-            rec[(u + kRec - 1) % kRec] = load_rec(g + kRec - 1);
-            load_rows(rec[(u + 1) % kRec], gu2[(u + 1) % 2], gx0[(u + 1) % 2], gx1[(u + 1) % 2]);
-            if (g < gb) consume(rec[u], gu2[u % 2], gx0[u % 2], gx1[u % 2]);
+            raw[(u + kRec - 1) % kRec] = load_rec(g + kRec - 1);
+            load_rows(raw[(u + 1) % kRec], gu2[(u + 1) % 2], gx0[(u + 1) % 2], gx1[(u + 1) % 2]);
+            if (g < gb) consume(raw[u], gu2[u % 2], gx0[u % 2], gx1[u % 2]);
         }
     }
     const int64_t RR = 4096;
