@@ -138,17 +138,18 @@ struct Ttmc4RowArgs {
     int compact;
 };
 
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8)))
+// One wavefront per workgroup: items differ in length, and a wavefront slot shared with three
+// others stays idle until the longest of them is done.
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 8)))
 ttmc4_mfma_kernel(Ttmc4RowArgs a) {
-    __shared__ double t2buf[4][4 * kT2Stride];
-    const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
+    __shared__ double t2buf[4 * kT2Stride];
+    const int lane = threadIdx.x;
     const int slot = lane >> 4, c = lane & 15;
-    double *lds = t2buf[wv];
+    double *lds = t2buf;
     // tiles of absent fibers (a slice's last K-step may hold fewer than four) are multiplied by a
     // zero A operand: whatever they hold must be finite
     for (int e = lane; e < 4 * kT2Stride; e += 64) lds[e] = 0.0;
-    const int64_t w = uni64(int64_t(blockIdx.x) * 4 + wv);
-    if (w >= a.n_items) return;
+    const int64_t w = int64_t(blockIdx.x);
     const SliceItem it = a.items[w];
     const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
     const int64_t dest = uni64(it.dest);
@@ -285,7 +286,7 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
             ra.out = out;
             ra.partial = a.partial;
             ra.compact = a.compact;
-            ttmc4_mfma_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(ra);
+            ttmc4_mfma_kernel<<<dim3(unsigned(a.n_items)), dim3(64), 0, stream>>>(ra);
         } else
             ttmc4_kernel<<<dim3(unsigned(div_up(a.n_items, 4))), dim3(256), 0, stream>>>(a);
     }
