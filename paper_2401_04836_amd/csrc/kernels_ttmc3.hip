@@ -123,11 +123,10 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
     // each XCD one column part of U3: 6 % faster on the 2M x 2M x 25000 tensor, where the U2
     // rows, not U3, are the larger stream).
     const int parts = a.R3 / (16 * QN);
-    const int per_block = 4 / parts > 0 ? 4 / parts : 1;       // items per workgroup
-    const int wave = threadIdx.x / 64;
-    if (wave >= per_block * parts) return;
-    const int part = wave % parts;
-    const int64_t w = uniform64(int64_t(blockIdx.x) * per_block + wave / parts);
+    // one item per workgroup (its `parts` wavefronts): items differ in length, and a slot shared
+    // with a longer item would stay idle until that one is done
+    const int part = threadIdx.x / 64;
+    const int64_t w = uniform64(int64_t(blockIdx.x));
     if (w >= a.n_items) return;
     const SliceItem it = a.items[w];
     const int32_t s = __builtin_amdgcn_readfirstlane(it.slice);
@@ -261,12 +260,8 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
 template <int PN>
 static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3RowArgs &a, hipStream_t stream) {
     const int qt = a.R3 / 16;
-    const dim3 block(256);
     ProfScope prof(plan, stream);
-    auto grid = [&](int parts) {
-        const int per_block = 4 / parts > 0 ? 4 / parts : 1;
-        return dim3(unsigned(div_up(a.n_items, per_block)));
-    };
+    const dim3 grid(unsigned(a.n_items));
     // column tiles per wavefront: two where R3 allows it (vector accesses need the alignment)
     int qn = int(env_int("CONSTSTN_TTMC3_QN", 2));
     if (qn != 1 && qn != 2 && qn != 4) qn = 2;
@@ -275,11 +270,11 @@ static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3Ro
                        reinterpret_cast<uintptr_t>(a.partial)) % (8u * unsigned(qn)) != 0))
         qn /= 2;
     if (qn == 4)
-        ttmc3_mfma_kernel<PN, 4><<<grid(qt / 4), block, 0, stream>>>(a);
+        ttmc3_mfma_kernel<PN, 4><<<grid, dim3(64 * (qt / 4)), 0, stream>>>(a);
     else if (qn == 2)
-        ttmc3_mfma_kernel<PN, 2><<<grid(qt / 2), block, 0, stream>>>(a);
+        ttmc3_mfma_kernel<PN, 2><<<grid, dim3(64 * (qt / 2)), 0, stream>>>(a);
     else
-        ttmc3_mfma_kernel<PN, 1><<<grid(qt), block, 0, stream>>>(a);
+        ttmc3_mfma_kernel<PN, 1><<<grid, dim3(64 * qt), 0, stream>>>(a);
     return CONSTSTN_OK;
 }
 
