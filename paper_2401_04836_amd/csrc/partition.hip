@@ -762,7 +762,9 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     if (plan->use_rows) {
         CST_TRY(build_rows(plan));
         unit_ptr = plan->slice_row.p;
-        split = env_int("CONSTSTN_TTMC3_ROWSPLIT", 256);
+        // larger items mean fewer partial row blocks for the fix-up pass to add; keep at least
+        // about 8192 items for the chip
+        split = env_int("CONSTSTN_TTMC3_ROWSPLIT", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 256), 2048));
         order = 0;                                   // items carry no 'first fiber'
     }
     if (order == 4 && plan->rank_of_level[1] == 16 && plan->rank_of_level[2] == 16 &&
@@ -770,7 +772,7 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
         plan->use_rows = true;
         CST_TRY(build_piece_groups(plan));
         unit_ptr = plan->slice_row.p;                 // items are ranges of K-steps (four fibers each)
-        split = env_int("CONSTSTN_TTMC4_KSPLIT", 64);
+        split = env_int("CONSTSTN_TTMC4_KSPLIT", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 64), 192));
     }
     CST_TRY(build_items_core(slices, unit_ptr, split, 0, order, X->ptr[0].p, X->ptr[1].p, plan->row_elems,
                              plan->items, plan->n_items, plan->n_partials, plan->n_split, plan->split_slices,
