@@ -893,7 +893,7 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     CST_HIP(hipGetLastError());
     // slices go in groups of 16; the k range is cut into chunks so that the grid fills the chip
     const int64_t groups = div_up(U->nodes[0], kSpGroup);
-    int64_t want = env_int("CONSTSTN_SPTN3_WGS", 3000);
+    int64_t want = env_int("CONSTSTN_SPTN3_WGS", 8000);
     int64_t n_kc = std::min<int64_t>(std::max<int64_t>(div_up(want, groups), 1), std::min<int64_t>(K, 64));
     plan->sp_k_per = div_up(K, n_kc);
     plan->sp_kc = int(div_up(K, plan->sp_k_per));
