@@ -1,22 +1,31 @@
 // Generic executor for contraction trees over ONE CSF tensor and dense operands -- any order,
-// any rank extents, any legal loop order and fusion choice (Sec. 2.2 / 4.2: a schedule is a tree
-// of binary contractions; fusion changes the size of the intermediates, never their values).
+// any rank extents, any legal loop order and fusion choice, any output mode (Sec. 2.2 / 4.2: a
+// schedule is a tree of binary contractions; fusion changes the size of the intermediates, never
+// their values).
 //
-// Supported shape of a tree: the CSF operand X is contracted from its innermost level upwards.
-// Every tensor on the path from X to the result is indexed by a PREFIX of X's CSF levels plus
-// dense indices, so it is stored as one dense block per CSF node of that depth ("sparse like
-// X above, dense below" -- the sparsity structure the paper's Sec. 2.1 assigns to a contraction
-// result, restricted to prefixes).  A statement
+// A tensor on the path from the CSF operand X to the result is stored in one of two ways:
+//   by prefix  indexed by a PREFIX of X's CSF levels plus dense indices: one dense block per CSF
+//              node of that depth ("sparse like X above, dense below" -- the sparsity structure
+//              Sec. 2.1 assigns to a contraction result, restricted to prefixes);
+//   dense      when it keeps CSF indices that are not a prefix (an output mode other than the
+//              root, Sec. 5.3): a dense array over the extents of all its indices.
+// A product of two dense tensors whose leading indices are a CSF prefix, and whose consumer joins it
+// with a tensor that is sparse like X to at least that depth, is computed by prefix too ("lifted"):
+// inside the fused loop nest of Fig. 3b only the entries at X's nodes are ever read.
+//
+// Two kernels.  A statement
 //        out[x_0..x_{d'-1}, O...] = in[x_0..x_{d-1}, I...] * F[...]        (d' <= d)
-// sums over the CSF levels d'..d-1 and over the dense indices that are in `in` or F but not in
-// `out`.  F is a dense operand or the result of a dense-only subtree, and may be indexed by the
-// contracted level indices and by dense indices.  Statements whose two inputs are both dense are
-// handled by the same kernel with an empty prefix.
+// whose result is stored by prefix and whose other input F is a dense tensor not indexed by a kept
+// level runs with one thread per result element, which walks the CSF subtree below its node and
+// the contracted dense indices in a fixed order: deterministic, no atomics.  Every other statement
+// (a result that keeps a non-prefix level, an input indexed by a kept level, a lifted input or
+// result) runs with one thread per (node of the deeper input, dense result element): the thread
+// finds its ancestors by binary search in the pointer arrays, forms its term and, where several
+// nodes meet in one result element, adds it with a hardware fp64 atomic.  Statements whose two
+// inputs are both dense and not lifted use the first kernel with an empty prefix.
 //
-// One thread per output element walks the CSF subtree below its node and the contracted dense
-// indices in a fixed order: deterministic, no atomics, intermediates held whole in device
-// memory.  This is the slow, always-applicable path; the tuned kernels of the other files take
-// the schedules they match.
+// Intermediates are held whole in device memory.  This is the slow, always-applicable path; the
+// tuned kernels of the other files take the schedules they match.
 #include <algorithm>
 #include <set>
 
@@ -92,16 +101,75 @@ generic_stmt_kernel(GenStmt g) {
     g.out[row * g.out_block + out_off] = acc;
 }
 
+// parent of node c: the last p with ptr[p] <= c
+__device__ __forceinline__ int64_t parent_of(const int64_t *ptr, int64_t n, int64_t c) {
+    int64_t lo = 0, hi = n;                       // invariant: ptr[lo] <= c < ptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr[mid] <= c) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(256)
+generic_node_kernel(GenStmt g) {
+    const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int d = g.d_node;
+    if (gid >= g.nodes[d - 1] * g.out_threads) return;
+    const int64_t node = gid / g.out_threads;
+    int64_t rem = gid - node * g.out_threads;
+    int64_t anc[CONSTSTN_MAX_ORDER];
+    anc[d - 1] = node;
+    for (int L = d - 1; L >= 1; --L) anc[L - 1] = parent_of(g.ptr[L - 1], g.nodes[L - 1], anc[L]);
+    int64_t in_off = g.d_in > 0 ? anc[g.d_in - 1] * g.in_block : 0;
+    int64_t f_off = g.d_f > 0 ? anc[g.d_f - 1] * g.f_block : 0;
+    int64_t out_off = 0;
+    if (g.d_out > 0) {
+        const int64_t row = g.scatter_rows ? int64_t(g.idx[0][anc[0]]) : anc[g.d_out - 1];
+        out_off = row * g.out_block;
+    }
+    for (int L = 0; L < d; ++L) {
+        const int64_t x = g.idx[L][anc[L]];
+        in_off += x * g.in_level_stride[L];
+        f_off += x * g.f_level_stride[L];
+        out_off += x * g.out_level_stride[L];
+    }
+    for (int q = g.n_out - 1; q >= 0; --q) {
+        const int64_t o = rem % g.extent[q];
+        rem /= g.extent[q];
+        in_off += o * g.in_stride[q];
+        f_off += o * g.f_stride[q];
+        out_off += o * g.out_stride[q];
+    }
+    double acc = 0.0;
+    int64_t cnt[kGenMaxIdx] = {0};
+    for (;;) {
+        acc = fma(g.in[in_off], g.f[f_off], acc);
+        int q = g.n_out + g.n_red - 1;
+        for (; q >= g.n_out; --q) {
+            in_off += g.in_stride[q];
+            f_off += g.f_stride[q];
+            if (++cnt[q] < g.extent[q]) break;
+            in_off -= g.in_stride[q] * g.extent[q];
+            f_off -= g.f_stride[q] * g.extent[q];
+            cnt[q] = 0;
+        }
+        if (q < g.n_out) break;
+    }
+    if (g.atomic) unsafeAtomicAdd(g.out + out_off, acc);
+    else g.out[out_off] = acc;
+}
+
 namespace {
 
 // a tensor on the way from X to the result, or a dense one
 struct GenTensor {
-    int depth = 0;                        // CSF prefix depth (0 = dense)
+    int depth = 0;                        // CSF prefix depth of the storage (0 = stored dense)
     bool leaf = false;                    // X itself
-    std::vector<std::string> dense;       // dense index names in storage order (last fastest)
+    std::vector<std::string> dense;       // index names in storage order after the prefix (last fastest)
     int operand = -1;                     // dense operand ordinal among ALL operands, or -1
     int buffer = -1;                      // intermediate buffer number, or -1
-    bool from_x = false;                  // descends from the CSF operand
+    bool from_x = false;                  // descends from the CSF operand and is stored by prefix
 };
 
 int find_name(const std::vector<std::string> &v, const std::string &n) {
@@ -132,13 +200,46 @@ conststn_status build_generic(conststn_plan_s *plan) {
             if (r->name == X.name) { level_name = r->idx; ++x_uses; }
     if (x_uses != 1) { set_error("the generic executor needs the CSF operand to be used exactly once"); return CONSTSTN_EUNSUPPORTED; }
     auto level_of = [&](const std::string &nm) { return find_name(level_name, nm); };
+    // leading names of a result that are CSF levels 0,1,.. in order, at most `limit` of them
+    auto front_prefix = [&](const std::vector<std::string> &names, int limit) {
+        int d = 0;
+        while (d < int(names.size()) && d < limit && names[d] == level_name[d]) ++d;
+        return d;
+    };
+    // does the result keep a level below `limit` that is not part of its front prefix of depth d?
+    auto keeps_beyond_prefix = [&](const std::vector<std::string> &names, int d, int limit) {
+        for (size_t q = size_t(d); q < names.size(); ++q) {
+            const int L = level_of(names[q]);
+            if (L >= 0 && L < limit) return true;
+        }
+        return false;
+    };
+
+    // first pass: how deep each statement's result is sparse like X (-1: not at all), from the
+    // index names alone; decides which products of dense tensors are computed at X's nodes only
+    std::vector<int> xdepth(m, -1);
+    auto ref_xdepth = [&](int src, int op) {
+        if (src >= 0) return xdepth[src];
+        return s.operands[op].kind == CONSTSTN_OPERAND_CSF ? n : -1;
+    };
+    for (int p = 0; p < m; ++p) {
+        const Stmt &st = s.stmts[p];
+        const int da = ref_xdepth(st.src_a, st.op_a), db = ref_xdepth(st.src_b, st.op_b);
+        const int d_in = std::max(da, db);
+        if (d_in < 1) continue;
+        const int d = front_prefix(st.out.idx, d_in);
+        const bool last = st.consumer < 0;
+        if (keeps_beyond_prefix(st.out.idx, d, d_in) || (last && d > 1)) continue;       // stored dense
+        xdepth[p] = d >= 1 ? d : -1;
+    }
 
     std::vector<GenTensor> result(m);             // the tensor each statement produces
     plan->gen.clear();
     plan->gen_buffers.clear();
+    plan->gen_zero_out = false;
     std::vector<int64_t> buffer_elems;
-    auto tensor_of_ref = [&](const Ref &r, int src, int op, GenTensor &t) -> conststn_status {
-        if (src >= 0) { t = result[src]; return CONSTSTN_OK; }
+    auto tensor_of_ref = [&](const Ref &r, int src, int op, GenTensor &t) {
+        if (src >= 0) { t = result[src]; return; }
         const OperandInfo &oi = s.operands[op];
         t = GenTensor();
         if (oi.kind == CONSTSTN_OPERAND_CSF) {
@@ -149,34 +250,54 @@ conststn_status build_generic(conststn_plan_s *plan) {
             t.dense = r.idx;
             t.operand = op;
         }
-        return CONSTSTN_OK;
+    };
+    // strides of an index list stored row-major in the given order; returns the element count
+    auto strides = [&](const std::vector<std::string> &names, std::map<std::string, int64_t> &out) {
+        int64_t stride = 1;
+        for (int q = int(names.size()) - 1; q >= 0; --q) { out[names[q]] = stride; stride *= s.extent[names[q]]; }
+        return stride;
     };
 
     for (int p = 0; p < m; ++p) {
         const Stmt &st = s.stmts[p];
+        const bool last = st.consumer < 0;
         GenTensor ta, tb;
-        CST_TRY(tensor_of_ref(st.a, st.src_a, st.op_a, ta));
-        CST_TRY(tensor_of_ref(st.b, st.src_b, st.op_b, tb));
+        tensor_of_ref(st.a, st.src_a, st.op_a, ta);
+        tensor_of_ref(st.b, st.src_b, st.op_b, tb);
         if (ta.from_x && tb.from_x) { set_error("statement %d multiplies two tensors that both descend from the CSF operand", p); return CONSTSTN_EUNSUPPORTED; }
         const GenTensor &in = tb.from_x ? tb : ta;            // sparse side (or first dense input)
-        const GenTensor &fa = tb.from_x ? ta : tb;            // dense side
-        if (fa.from_x) { set_error("internal: dense side descends from the CSF operand"); return CONSTSTN_EINVAL; }
-        const int d_in = in.from_x ? in.depth : 0;
+        const GenTensor &fa = tb.from_x ? ta : tb;            // the other side
+        if (!in.from_x && (in.depth > 0 || fa.depth > 0)) { set_error("internal: a tensor stored by prefix meets no sparse partner in statement %d", p); return CONSTSTN_EINVAL; }
+        if (fa.depth > in.depth) { set_error("internal: statement %d joins a deeper prefix with a shallower one", p); return CONSTSTN_EINVAL; }
 
-        // output: leading CSF level names (a prefix, in level order), then dense names
-        int d_out = 0;
-        while (d_out < int(st.out.idx.size()) && d_out < d_in && st.out.idx[d_out] == level_name[d_out]) ++d_out;
-        std::vector<std::string> out_dense(st.out.idx.begin() + d_out, st.out.idx.end());
-        for (const auto &nm : out_dense)
-            if (in.from_x && level_of(nm) >= 0 && level_of(nm) < d_in) {
-                set_error("statement %d: result %s keeps CSF index %s without the levels above it; the generic "
-                          "executor stores results by CSF prefix only", p, st.out.name.c_str(), nm.c_str());
-                return CONSTSTN_EUNSUPPORTED;
+        // which kernel, and how the result is stored
+        int kind = 0, d_node = in.from_x ? in.depth : 0, d_out = 0;
+        bool out_by_prefix = true;
+        if (d_node == 0) {
+            // two dense inputs: computed at X's nodes when the consumer's other input is sparse to that depth
+            const int d = front_prefix(st.out.idx, n);
+            int other = -1;
+            if (!last) {
+                const Stmt &c = s.stmts[st.consumer];
+                other = c.src_a == p ? ref_xdepth(c.src_b, c.op_b) : ref_xdepth(c.src_a, c.op_a);
             }
-        // dense loop indices
+            if (d >= 1 && other >= d) { kind = 1; d_node = d; d_out = d; }
+        } else {
+            d_out = front_prefix(st.out.idx, d_node);
+            bool f_uses_kept = false;
+            for (const auto &nm : fa.dense) { const int L = level_of(nm); if (L >= 0 && L < d_out) f_uses_kept = true; }
+            if (keeps_beyond_prefix(st.out.idx, d_out, d_node) || (last && d_out > 1)) { kind = 1; out_by_prefix = false; d_out = 0; }
+            else if (fa.depth > 0 || f_uses_kept) kind = 1;
+        }
+        auto is_level = [&](const std::string &nm) { const int L = level_of(nm); return L >= 0 && L < d_node; };
+
+        // dense loop indices: the result's first, then the summed ones
+        std::vector<std::string> out_dense;
+        for (size_t q = out_by_prefix ? size_t(d_out) : 0; q < st.out.idx.size(); ++q)
+            if (!is_level(st.out.idx[q])) out_dense.push_back(st.out.idx[q]);
         std::vector<std::string> red;
         auto consider = [&](const std::string &nm) {
-            if (in.from_x && level_of(nm) >= 0 && level_of(nm) < d_in) return;        // a CSF level
+            if (is_level(nm)) return;
             if (find_name(out_dense, nm) >= 0 || find_name(red, nm) >= 0) return;
             red.push_back(nm);
         };
@@ -185,69 +306,75 @@ conststn_status build_generic(conststn_plan_s *plan) {
         if (out_dense.size() + red.size() > size_t(kGenMaxIdx)) { set_error("statement %d has more than %d dense indices", p, kGenMaxIdx); return CONSTSTN_EUNSUPPORTED; }
 
         GenStmt g{};
-        g.d_in = d_in;
+        g.kind = kind;
+        g.d_node = d_node;
+        g.d_in = kind == 1 ? in.depth : d_node;
+        g.d_f = fa.depth;
         g.d_out = d_out;
+        g.atomic = (kind == 1 && d_out != d_node) ? 1 : 0;
         g.in_is_leaf = in.leaf ? 1 : 0;
         g.n_out = int(out_dense.size());
         g.n_red = int(red.size());
         std::vector<std::string> loopn = out_dense;
         loopn.insert(loopn.end(), red.begin(), red.end());
         for (size_t q = 0; q < loopn.size(); ++q) g.extent[q] = s.extent[loopn[q]];
-        // strides of a dense index list stored row-major in the given order
-        auto strides = [&](const std::vector<std::string> &names, std::map<std::string, int64_t> &out) {
-            int64_t stride = 1;
-            for (int q = int(names.size()) - 1; q >= 0; --q) { out[names[q]] = stride; stride *= s.extent[names[q]]; }
-            return stride;
-        };
         std::map<std::string, int64_t> sin, sf, sout;
         g.in_block = strides(in.dense, sin);
-        strides(fa.dense, sf);
-        g.out_block = strides(out_dense, sout);
+        g.f_block = strides(fa.dense, sf);
+        std::vector<std::string> out_names = out_by_prefix ? std::vector<std::string>(st.out.idx.begin() + d_out, st.out.idx.end())
+                                                           : st.out.idx;
+        g.out_block = strides(out_names, sout);
+        g.out_threads = 1;
+        for (size_t q = 0; q < out_dense.size(); ++q) g.out_threads *= g.extent[q];
         for (size_t q = 0; q < loopn.size(); ++q) {
             g.in_stride[q] = sin.count(loopn[q]) ? sin[loopn[q]] : 0;
             g.f_stride[q] = sf.count(loopn[q]) ? sf[loopn[q]] : 0;
-            g.out_stride[q] = q < out_dense.size() ? sout[loopn[q]] : 0;
+            g.out_stride[q] = (q < out_dense.size() && sout.count(loopn[q])) ? sout[loopn[q]] : 0;
         }
-        for (const auto &nm : fa.dense) {
-            const int L = in.from_x ? level_of(nm) : -1;
-            if (L < 0 || L >= d_in) continue;
-            if (L < d_out) {
-                set_error("statement %d: dense input is indexed by CSF index %s that the result keeps; not implemented "
-                          "in the generic executor", p, nm.c_str());
-                return CONSTSTN_EUNSUPPORTED;
-            }
-            g.f_level_stride[L] = sf[nm];
+        for (int L = 0; L < d_node; ++L) {
+            const std::string &nm = level_name[L];
+            if (sin.count(nm)) g.in_level_stride[L] = sin[nm];
+            if (sf.count(nm)) g.f_level_stride[L] = sf[nm];
+            if (sout.count(nm)) g.out_level_stride[L] = sout[nm];
+        }
+        if (kind == 0 && d_node > 0) {
+            // the first kernel knows the other input's level strides only, and only below the result's depth
+            for (int L = 0; L < d_node; ++L)
+                if (g.in_level_stride[L] || g.out_level_stride[L] || (L < d_out && g.f_level_stride[L])) {
+                    set_error("internal: statement %d was given to the subtree kernel with a level-indexed tensor", p);
+                    return CONSTSTN_EINVAL;
+                }
         }
         // where the inputs live
         g.in_operand = in.operand;
         g.in_buffer = in.buffer;
         g.f_operand = fa.operand;
         g.f_buffer = fa.buffer;
-        g.out_nodes = d_out == 0 ? 1 : csf->nodes[d_out - 1];
+        g.out_nodes = (out_by_prefix && d_out > 0) ? csf->nodes[d_out - 1] : 1;
+        g.out_elems = g.out_nodes * g.out_block;
         g.roots = csf->nodes[0];
         for (int l = 0; l < n; ++l) {
+            g.nodes[l] = csf->nodes[l];
             g.idx[l] = csf->idx[l].p;
             g.ptr[l] = l + 1 < n ? csf->ptr[l].p : nullptr;
         }
         // the result
         GenTensor &res = result[p];
-        res.depth = d_out;
-        res.from_x = in.from_x;
-        res.dense = out_dense;
-        if (st.consumer >= 0) {
+        res.depth = out_by_prefix ? d_out : 0;
+        res.from_x = in.from_x && out_by_prefix && d_out > 0;
+        res.dense = out_names;
+        if (in.from_x && (res.from_x ? res.depth : -1) != xdepth[p]) { set_error("internal: storage of statement %d's result decided two ways", p); return CONSTSTN_EINVAL; }
+        if (!last) {
             res.buffer = int(buffer_elems.size());
-            buffer_elems.push_back(g.out_nodes * g.out_block);
+            buffer_elems.push_back(g.out_elems);
             g.out_buffer = res.buffer;
         } else {
-            if (res.from_x && d_out > 1) {
-                set_error("the result keeps %d CSF indices; the generic executor writes dense results or one "
-                          "row block per root index", d_out);
-                return CONSTSTN_EUNSUPPORTED;
-            }
             g.out_buffer = -1;
-            g.scatter_rows = (d_out == 1 && !plan->compact) ? 1 : 0;
-            plan->gen_rooted = d_out == 1;
+            const bool rooted = out_by_prefix && d_out == 1;
+            g.scatter_rows = (rooted && !plan->compact) ? 1 : 0;
+            plan->gen_rooted = rooted;
             plan->row_elems = g.out_block;
+            plan->gen_zero_out = g.atomic != 0;
         }
         plan->gen.push_back(g);
     }
@@ -273,8 +400,9 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
                                hipStream_t stream) {
     const Schedule &s = plan->sched;
     const conststn_csf_s *csf = plan->X;
-    // rows of root indices that hold no nonzero are never written by a kernel
-    if (plan->gen_rooted && !plan->compact && csf->nodes[0] < plan->out_rows)
+    // rows of root indices that hold no nonzero are never written by a kernel; a result that is
+    // added into starts from zero
+    if (plan->gen_zero_out || (plan->gen_rooted && !plan->compact && csf->nodes[0] < plan->out_rows))
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     ProfScope prof(plan, stream);
     for (const GenStmt &g0 : plan->gen) {
@@ -288,10 +416,13 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         g.f = where(g.f_operand, g.f_buffer);
         g.out = g.out_buffer >= 0 ? plan->gen_buffers[size_t(g.out_buffer)]->p : out;
         if (!g.in || !g.f || !g.out) { set_error("internal: unresolved tensor in the generic executor"); return CONSTSTN_EINVAL; }
-        const int64_t total = g.out_nodes * g.out_block;
+        if (g.atomic && g.out_buffer >= 0) CST_TRY(zero_fill(g.out, g.out_elems, stream));
+        const int64_t total = g.kind == 1 ? g.nodes[g.d_node - 1] * g.out_threads : g.out_nodes * g.out_block;
         if (total == 0) continue;
         if (total > (int64_t(1) << 31) * 256) { set_error("statement result too large for one launch"); return CONSTSTN_EUNSUPPORTED; }
-        generic_stmt_kernel<<<dim3(unsigned((total + 255) / 256)), dim3(256), 0, stream>>>(g);
+        const dim3 grid(unsigned((total + 255) / 256)), block(256);
+        if (g.kind == 1) generic_node_kernel<<<grid, block, 0, stream>>>(g);
+        else generic_stmt_kernel<<<grid, block, 0, stream>>>(g);
         CST_HIP(hipGetLastError());
     }
     return CONSTSTN_OK;

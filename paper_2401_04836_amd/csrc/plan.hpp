@@ -25,15 +25,24 @@ enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GE
 // next n_red are summed over; strides are in elements, 0 where a tensor lacks the index.
 constexpr int kGenMaxIdx = 8;
 struct GenStmt {
-    int d_in, d_out;                           // CSF prefix depth of the sparse-side input / of the result
+    int kind;                                  // 0: one thread per result element walks the subtree below its node;
+                                               // 1: one thread per (node of depth d_node, dense result element)
+    int d_in, d_out;                           // CSF prefix depth of the sparse-side input / of the result (kind 1: 0 = stored dense)
+    int d_f, d_node;                           // kind 1: prefix depth of the other input; depth of the nodes the threads stand on
+    int atomic;                                // kind 1: several threads add to one result element
     int in_is_leaf;                            // the sparse-side input is the CSF operand itself
     int n_out, n_red;
     int scatter_rows;                          // result row = root index instead of root node number
     int64_t extent[kGenMaxIdx];
     int64_t in_stride[kGenMaxIdx], f_stride[kGenMaxIdx], out_stride[kGenMaxIdx];
-    int64_t f_level_stride[CONSTSTN_MAX_ORDER];   // stride in the dense input of each summed CSF level's index
-    int64_t in_block, out_block;               // elements per CSF node of input / result
+    // stride of each CSF level's index in a tensor stored dense (0 where it lacks the index); kind 0 uses
+    // f_level_stride only, for the summed levels
+    int64_t in_level_stride[CONSTSTN_MAX_ORDER], f_level_stride[CONSTSTN_MAX_ORDER], out_level_stride[CONSTSTN_MAX_ORDER];
+    int64_t in_block, f_block, out_block;      // elements per CSF node of a tensor stored by prefix
+    int64_t out_threads;                       // kind 1: dense result elements per node
+    int64_t out_elems;                         // elements of the result's storage
     int64_t out_nodes, roots;
+    int64_t nodes[CONSTSTN_MAX_ORDER];
     const int32_t *idx[CONSTSTN_MAX_ORDER];
     const int64_t *ptr[CONSTSTN_MAX_ORDER];
     const double *in, *f;
@@ -159,6 +168,7 @@ struct conststn_plan_s {
     std::vector<cst::GenStmt> gen;
     std::vector<std::unique_ptr<cst::DevBuf<double>>> gen_buffers;
     bool gen_rooted = false;               // the result has one row block per root index
+    bool gen_zero_out = false;             // the last statement adds into the result: cleared before every run
 
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;

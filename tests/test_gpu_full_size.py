@@ -124,6 +124,41 @@ def test_config2_mttkrp_full_size_both_modes():
         del pl, csf, out
 
 
+def test_config2_mttkrp_other_modes_on_the_mode0_csf():
+    """Modes 1 and 2 without re-rooting the CSF (Sec. 5.3 runs every mode): results indexed by the
+    middle and by the leaf level, added into a dense array."""
+    _say("config 2 full size, one CSF for every mode: generate")
+    wl = w.make(2, device="cuda")
+    X = wl.sparse["X"]
+    A, B, C = wl.dense["A"], wl.dense["B"], wl.dense["C"]
+    cn = [c.cpu().numpy() for c in X.coords]
+    vn = X.vals.cpu().numpy()
+    csf = cst.build_csf(X.coords, X.vals, X.dims, [0, 1, 2])
+    for mode, sched, ops in (
+            (1, "T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,j,r] * A[i,r] | i,j,r", (("C", C), ("A", A))),
+            (2, "T[i,j,r] = A[i,r] * B[j,r] | i,j,r ; M[k,r] = X[i,j,k] * T[i,j,r] | i,j,k,r", (("A", A), ("B", B)))):
+        pl = cst.plan(sched, [("X", csf)] + list(ops))
+        _say("config 2 mode %d on CSF [0,1,2]: %s" % (mode, pl.describe().split("|")[0]))
+        facs = [t for _, t in ops]
+        out = cst.execute(pl, facs)
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        out = cst.execute(pl, facs)
+        t1.record()
+        torch.cuda.synchronize()
+        _say("  %.2f ms per contraction" % t0.elapsed_time(t1))
+        out = out.reshape(X.dims[mode], -1)
+        others = [m for m in range(3) if m != mode]
+        Fa, Fb = ([A, B, C][others[0]].cpu().numpy(), [A, B, C][others[1]].cpu().numpy())
+        want = oracle.mttkrp3(cn, vn, X.dims, Fa, Fb, mode)
+        S_abs = oracle.mttkrp3_abs(cn, vn, X.dims, Fa, Fb, mode)
+        err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
+        _say("  rel err %.3e" % err)
+        assert err <= TOL
+        del pl, out
+
+
 def test_config5_ttmc3_full_size_compact():
     _say("config 5 full size: generate")
     wl = w.make(5, device="cuda")

@@ -163,17 +163,63 @@ def test_generic_matches_tuned_kernels_and_compact_rows():
     np.testing.assert_array_equal(comp, gen[rows])
 
 
-def test_generic_refuses_what_it_cannot_store():
+def test_every_output_mode_on_one_csf():
+    # Sec. 5.3 runs MTTKRP / TTMc for every mode; here all of them on the SAME CSF (i > j > k): a result
+    # that keeps a level other than the root is stored dense and added into
+    dims = (33, 21, 27)
+    coords, vals = _tensor(371, dims, 3500)
+    x = (coords, vals, dims)
+    A, B, C = _dense(372, 33, 12), _dense(373, 21, 12), _dense(374, 27, 12)
+    _say("MTTKRP mode 1: leaf factor first, then the root factor, result indexed by the middle level")
+    got, _ = _run("T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,j,r] * A[i,r] | i,j,r",
+                  x, [0, 1, 2], [("C", C), ("A", A)], (21, 12))
+    _check(got, coords, vals, "ijk", [(A, "ir"), (C, "kr")], "jr", {"j": 21, "r": 12})
+    _say("MTTKRP mode 2: Khatri-Rao rows of the two upper levels at X's fibers only, result indexed by the leaf level")
+    got, pl = _run("T[i,j,r] = A[i,r] * B[j,r] | i,j,r ; M[k,r] = X[i,j,k] * T[i,j,r] | i,j,k,r",
+                   x, [0, 1, 2], [("A", A), ("B", B)], (27, 12))
+    _check(got, coords, vals, "ijk", [(A, "ir"), (B, "jr")], "kr", {"k": 27, "r": 12})
+    again = cst.execute(pl, [A.cuda(), B.cuda()]).cpu().numpy().reshape(27, 12)     # cleared before each run
+    np.testing.assert_allclose(again, got, rtol=0, atol=1e-9)
+    U1, U2, U3 = _dense(375, 33, 3), _dense(376, 21, 4), _dense(377, 27, 5)
+    _say("TTMc mode 1")
+    got, _ = _run("T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s ; Y[j,a,s] = T[i,j,s] * U1[i,a] | i,j,a,s",
+                  x, [0, 1, 2], [("U3", U3), ("U1", U1)], (21, 3, 5))
+    _check(got, coords, vals, "ijk", [(U1, "ia"), (U3, "ks")], "jas", {"j": 21, "a": 3, "s": 5})
+    _say("TTMc mode 2")
+    got, _ = _run("P[i,j,a,b] = U1[i,a] * U2[j,b] | i,j,a,b ; Y[k,a,b] = X[i,j,k] * P[i,j,a,b] | i,j,k,a,b",
+                  x, [0, 1, 2], [("U1", U1), ("U2", U2)], (27, 3, 4))
+    _check(got, coords, vals, "ijk", [(U1, "ia"), (U2, "jb")], "kab", {"k": 27, "a": 3, "b": 4})
+
+
+def test_inputs_indexed_by_kept_levels_and_results_with_several_sparse_indices():
     dims = (20, 12, 9)
     coords, vals = _tensor(361, dims, 500)
+    x = (coords, vals, dims)
+    B, C, U3, wj = _dense(362, 12, 4), _dense(364, 9, 4), _dense(363, 9, 4), _dense(365, 12)
+    _say("a factor indexed by a level the result keeps, result still a CSF prefix")
+    got, _ = _run("T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; S[i,j,r] = T[i,j,r] * B[j,r] | i,j,r ; "
+                  "M[i,r] = S[i,j,r] * w[j] | i,j,r", x, [0, 1, 2], [("C", C), ("B", B), ("w", wj)], (20, 4))
+    _check(got, coords, vals, "ijk", [(B, "jr"), (C, "kr"), (wj, "j")], "ir", {"i": 20, "r": 4})
+    _say("contracting the middle level first leaves (i,k): held dense, the rest of the tree is dense")
+    got, _ = _run("T[i,k,r] = X[i,j,k] * B[j,r] | i,j,k,r ; Y[i,r,s] = T[i,k,r] * U3[k,s] | i,k,r,s",
+                  x, [0, 1, 2], [("B", B), ("U3", U3)], (20, 4, 4))
+    _check(got, coords, vals, "ijk", [(B, "jr"), (U3, "ks")], "irs", {"i": 20, "r": 4, "s": 4})
+    _say("a result that keeps two sparse indices comes out dense over both")
+    got, _ = _run("T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s", x, [0, 1, 2], [("U3", U3)], (20, 12, 4))
+    _check(got, coords, vals, "ijk", [(U3, "ks")], "ijs", {"i": 20, "j": 12, "s": 4})
+
+
+def test_generic_refuses_what_it_cannot_store():
+    # a Khatri-Rao product over two non-root levels is not a CSF prefix: held dense, 2 GB here
+    dims = (20, 4000, 4000)
+    coords, vals = _tensor(361, dims, 500)
     csf = cst.build_csf([c.cuda() for c in coords], vals.cuda(), dims, [0, 1, 2])
-    B, U3 = _dense(362, 12, 4).cuda(), _dense(363, 9, 4).cuda()
-    # contracting the middle level first leaves (i,k): not a CSF prefix
-    with pytest.raises(cst.ConststnError) as e:
-        cst.plan("T[i,k,r] = X[i,j,k] * B[j,r] | i,j,k,r ; Y[i,r,s] = T[i,k,r] * U3[k,s] | i,k,r,s",
-                 [("X", csf), ("B", B), ("U3", U3)])
-    assert "prefix" in str(e.value)
-    # a result that keeps two sparse indices
-    with pytest.raises(cst.ConststnError) as e:
-        cst.plan("T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s", [("X", csf), ("U3", U3)])
-    assert "CSF indices" in str(e.value)
+    B, C = _dense(362, 4000, 16).cuda(), _dense(363, 4000, 16).cuda()
+    text = "P[j,k,r] = B[j,r] * C[k,r] | j,k,r ; M[i,r] = X[i,j,k] * P[j,k,r] | i,j,k,r"
+    os.environ["CONSTSTN_GENERIC_MAX_GB"] = "1"
+    try:
+        with pytest.raises(cst.ConststnError) as e:
+            cst.plan(text, [("X", csf), ("B", B), ("C", C)])
+        assert "intermediates" in str(e.value)
+    finally:
+        del os.environ["CONSTSTN_GENERIC_MAX_GB"]
