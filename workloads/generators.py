@@ -246,3 +246,89 @@ def make_sptn3_scattered(name, seed, dims_ijklm, nnz_u, nnz_w, device="cpu"):
     V = dense_factor(seed, name + "/V", J, L, "n01", device)
     return Workload("sptn3", name, {"U": U, "W": W}, {"V": V},
                     {"dims": tuple(dims_ijklm), "seed": seed})
+
+
+def _disc_offsets(radius):
+    """Integer offsets (dx, dy) with dx^2 + dy^2 <= radius^2, in row-major order."""
+    r = int(radius)
+    return [(dx, dy) for dx in range(-r, r + 1) for dy in range(-r, r + 1) if dx * dx + dy * dy <= radius * radius]
+
+
+def _atom_pairs(side, radius, device):
+    """All ordered atom pairs (a, b) of a side x side lattice within `radius` (no wrap-around)."""
+    atoms = torch.arange(side * side, dtype=torch.int64, device=device)
+    ax, ay = atoms // side, atoms % side
+    pa, pb = [], []
+    for dx, dy in _disc_offsets(radius):
+        bx, by = ax + dx, ay + dy
+        ok = (bx >= 0) & (bx < side) & (by >= 0) & (by < side)
+        pa.append(atoms[ok])
+        pb.append((bx * side + by)[ok])
+    return torch.cat(pa), torch.cat(pb)
+
+
+def _thin(seed, stream, count, keep, device):
+    """Seeded keep/drop decision per position."""
+    if keep >= 1.0:
+        return torch.ones(count, dtype=torch.bool, device=device)
+    return rng.uniform01(seed, stream, 0, count, device) < keep
+
+
+def _expand_pairs(pa, pb, na, nb):
+    """Atom pairs -> function pairs: every one of `na` functions on a with every one of `nb` on b."""
+    n = pa.numel()
+    fa = torch.arange(na, device=pa.device).repeat_interleave(nb).repeat(n)
+    fb = torch.arange(nb, device=pa.device).repeat(na).repeat(n)
+    return (pa.repeat_interleave(na * nb) * na + fa), (pb.repeat_interleave(na * nb) * nb + fb)
+
+
+def make_lattice_chain(name, seed, side, n_ao, n_df, r_int, r_mo, r_pao, r_filter,
+                       keep_int=0.7, keep_mo=0.85, keep_pao=0.85, device="cpu"):
+    """E[K,i,m] = I[K,u,v] C[u,i] P[v,m] (x L[K,i]): the sparse three-index integral transformation
+    of Sec. 5.1 on synthetic sparse maps.  Atoms sit on a side x side square lattice; every atom
+    carries one localized orbital (index i), n_ao atomic orbitals (u, v), n_ao projected atomic
+    orbitals (m) and n_df fitting functions (K).  An entry is structurally nonzero when the atoms
+    of its indices lie within a cut-off radius of each other (lattice units), thinned at random:
+        I[K,u,v]  K-u, K-v and u-v within r_int, kept with probability keep_int
+        C[u,i]    within r_mo,  kept with probability keep_mo
+        P[v,m]    within r_pao, kept with probability keep_pao
+        L[K,i]    within r_filter, all ones (the K -> i sparse map used as a filter)
+    Values N(0,1).  Stands in for the quantum-chemistry inputs of Sec. 5.1, which are not public."""
+    atoms = side * side
+    n_i, n_u, n_m, n_K = atoms, atoms * n_ao, atoms * n_ao, atoms * n_df
+    # I: atom triples (aK, au, av), pairwise within r_int
+    ka, ua = _atom_pairs(side, r_int, device)               # (aK, au)
+    trip_k, trip_u, trip_v = [], [], []
+    kx, ky = ka // side, ka % side
+    ux, uy = ua // side, ua % side
+    for dx, dy in _disc_offsets(r_int):
+        vx, vy = kx + dx, ky + dy
+        ok = (vx >= 0) & (vx < side) & (vy >= 0) & (vy < side)
+        ok &= ((vx - ux) ** 2 + (vy - uy) ** 2) <= r_int * r_int
+        trip_k.append(ka[ok]); trip_u.append(ua[ok]); trip_v.append((vx * side + vy)[ok])
+    tk, tu, tv = torch.cat(trip_k), torch.cat(trip_u), torch.cat(trip_v)
+    nt = tk.numel()
+    per = n_df * n_ao * n_ao
+    f = torch.arange(per, device=device)
+    fK, fu, fv = f // (n_ao * n_ao), (f // n_ao) % n_ao, f % n_ao
+    cK = (tk.repeat_interleave(per) * n_df + fK.repeat(nt))
+    cu = (tu.repeat_interleave(per) * n_ao + fu.repeat(nt))
+    cv = (tv.repeat_interleave(per) * n_ao + fv.repeat(nt))
+    keep = _thin(seed, name + "/I/keep", cK.numel(), keep_int, device)
+    ci = [cK[keep].to(torch.int32), cu[keep].to(torch.int32), cv[keep].to(torch.int32)]
+    I = SparseCOO((n_K, n_u, n_u), ci, sparse_values(seed, name + "/I", ci[0].numel(), "n01", device))
+
+    def pair_tensor(tag, radius, na, nb, keep_p, dims, ones=False):
+        pa, pb = _atom_pairs(side, radius, device)
+        ca, cb = _expand_pairs(pa, pb, na, nb)
+        k = _thin(seed, name + "/" + tag + "/keep", ca.numel(), keep_p, device)
+        cc = [ca[k].to(torch.int32), cb[k].to(torch.int32)]
+        vals = (torch.ones(cc[0].numel(), dtype=torch.float64, device=device) if ones
+                else sparse_values(seed, name + "/" + tag, cc[0].numel(), "n01", device))
+        return SparseCOO(dims, cc, vals)
+
+    C = pair_tensor("C", r_mo, n_ao, 1, keep_mo, (n_u, n_i))
+    P = pair_tensor("P", r_pao, n_ao, n_ao, keep_pao, (n_u, n_m))
+    L = pair_tensor("L", r_filter, n_df, 1, 1.0, (n_K, n_i), ones=True)
+    return Workload("spchain3", name, {"I": I, "C": C, "P": P, "L": L}, {},
+                    {"dims": (n_K, n_i, n_u, n_m), "side": side, "seed": seed})
