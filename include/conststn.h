@@ -128,13 +128,18 @@ void conststn_csf_destroy(conststn_csf_t *csf);
  *     statement between the two shares it ("Statements between producer and consumer").
  * Kernel choice.  Tuned kernels take: TTMc of order 3 (ranks up to 64) and order 4 (ranks up to
  * 16), MTTKRP of order 3 (rank up to 128), each with the sparse prefix fully fused, and the
- * three-tensor network (U.V).W fused on its two outer loops.  Every other legal tree over ONE CSF
+ * three-tensor network (U.V).W fused on its two outer loops.  The chain of three sparse tensors of
+ * Sec. 5.1 (every operand a CSF handle, sparse result: see conststn_plan_output_csf),
+ *      "T[K,i,v] = I[K,u,v] * C[i,u] | K,i,u,v ; E[K,i,m] = T[K,i,v] * P[m,v] | K,i,m,v"
+ * and its restricted form with a statement "F[K,i,v] = T[K,i,v] * L[K,i] | K,i,v" in between,
+ * fused on the two outer loops, has a kernel of its own.  Every other legal tree over ONE CSF
  * operand and dense operands -- other orders and ranks, dense-only subtrees, several CSF levels
- * summed by one statement, a fully contracted result, any fusion choice -- runs on a generic
+ * summed by one statement, a fully contracted result, a result indexed by CSF levels other than
+ * the root (every output mode on one CSF; such a result is a dense array over the extents of all
+ * its indices and is added into with fp64 atomics), any fusion choice -- runs on a generic
  * executor (one pass per statement, intermediates held whole in device memory; environment
- * variable CONSTSTN_GENERIC_MAX_GB bounds them, default 64), provided every tensor between the
- * CSF operand and the result keeps a PREFIX of the CSF levels and the result keeps at most the
- * root level.  A legal schedule outside both gives CONSTSTN_EUNSUPPORTED with the reason.
+ * variable CONSTSTN_GENERIC_MAX_GB bounds them, default 64).  A legal schedule outside all of
+ * these gives CONSTSTN_EUNSUPPORTED with the reason.
  * The plan keeps pointers into the CSF handles: destroy the plan first.
  */
 typedef enum { CONSTSTN_OPERAND_CSF = 0, CONSTSTN_OPERAND_DENSE = 1 } conststn_operand_kind;
@@ -171,6 +176,16 @@ conststn_status conststn_plan_output_size(const conststn_plan_t *plan, int64_t *
  * blocks belong to; borrowed, valid until the CSF is destroyed. */
 conststn_status conststn_plan_output_rows(const conststn_plan_t *plan, const int32_t **rows,
                                           int64_t *n_rows);
+
+/* Sparse result (Sec. 5.1: a product of sparse tensors whose result is sparse too).  The
+ * structure of the result -- its structural nonzeros by the join of Sec. 2.1, independent of the
+ * values -- is computed when the plan is made and is returned here as a CSF handle without
+ * values (conststn_csf_export gives idx/ptr per level, vals = NULL; levels in the order of the
+ * result's indices in the schedule).  conststn_plan_output_size then reports n_rows = number of
+ * structural nonzeros, row_elems = 1, and conststn_execute writes one value per leaf of that
+ * structure, in leaf order.  Borrowed: valid until the plan is destroyed; never pass it to
+ * conststn_csf_destroy.  CONSTSTN_EINVAL when the plan's result is dense. */
+conststn_status conststn_plan_output_csf(const conststn_plan_t *plan, const conststn_csf_t **structure);
 
 /* Text description of the lowered plan (kernel family, loop tree in forall/where form,
  * order of each intermediate after fusion).  Writes at most len-1 characters + NUL. */

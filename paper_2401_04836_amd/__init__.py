@@ -23,7 +23,7 @@ OPERAND_CSF, OPERAND_DENSE = 0, 1
 EXPORTED_SYMBOLS = [
     "conststn_build_csf", "conststn_csf_info", "conststn_csf_export", "conststn_csf_destroy",
     "conststn_plan", "conststn_schedule_check", "conststn_plan_output_size",
-    "conststn_plan_output_rows", "conststn_plan_describe", "conststn_plan_destroy",
+    "conststn_plan_output_rows", "conststn_plan_output_csf", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
     "conststn_plan_profile", "conststn_plan_kernel_times",
 ]
@@ -64,6 +64,7 @@ def _load():
                                           ctypes.c_char_p, ctypes.c_size_t, ip]
     L.conststn_plan_output_size.argtypes = [vp, i64p, i64p]
     L.conststn_plan_output_rows.argtypes = [vp, ctypes.POINTER(vp), i64p]
+    L.conststn_plan_output_csf.argtypes = [vp, ctypes.POINTER(vp)]
     L.conststn_plan_describe.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t]
     L.conststn_plan_destroy.argtypes = [vp]
     L.conststn_plan_destroy.restype = None
@@ -249,6 +250,15 @@ class Plan:
         p, n = ctypes.c_void_p(), ctypes.c_int64()
         _check(_lib.conststn_plan_output_rows(self._h, ctypes.byref(p), ctypes.byref(n)))
         return _borrow(p.value, n.value, torch.int32, self.device, self)
+
+    def output_csf(self):
+        """conststn_plan_output_csf: structure of a sparse result (borrowed; lives as long as the plan)."""
+        h = ctypes.c_void_p()
+        _check(_lib.conststn_plan_output_csf(self._h, ctypes.byref(h)))
+        csf = CSF(h, self.device)
+        csf.destroy = lambda: None          # owned by the plan
+        csf._plan = self
+        return csf
 
     def profile(self, capacity):
         """conststn_plan_profile: keep `capacity` event pairs around the dominant kernel."""

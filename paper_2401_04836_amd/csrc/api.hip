@@ -150,6 +150,62 @@ static conststn_status match_sptn3(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// Chain of three sparse tensors with a sparse result (Sec. 5.1):
+//   T[K,i,v] = I[K,u,v] * C[i,u] ; E[K,i,m] = T[K,i,v] * P[m,v]                      (unrestricted)
+//   T[K,i,v] = I[K,u,v] * C[i,u] ; F[K,i,v] = T[K,i,v] * L[K,i] ; E[K,i,m] = F[K,i,v] * P[m,v]
+// every operand a CSF tensor whose reference lists its indices in level order.
+static conststn_status match_spchain3(conststn_plan_s *plan) {
+    Schedule &s = plan->sched;
+    const size_t m = s.stmts.size();
+    if (m != 2 && m != 3) return CONSTSTN_EUNSUPPORTED;
+    for (const auto &o : s.operands) if (o.kind != CONSTSTN_OPERAND_CSF) return CONSTSTN_EUNSUPPORTED;
+    if (s.operands.size() != m + 1) return CONSTSTN_EUNSUPPORTED;
+    const Stmt &p0 = s.stmts[0];
+    if (p0.op_a < 0 || p0.op_b < 0) return CONSTSTN_EUNSUPPORTED;
+    const Ref *ri = &p0.a, *rc = &p0.b;
+    int iop = p0.op_a, cop = p0.op_b;
+    if (s.operands[iop].order != 3) { std::swap(ri, rc); std::swap(iop, cop); }
+    if (s.operands[iop].order != 3 || s.operands[cop].order != 2) return CONSTSTN_EUNSUPPORTED;
+    const std::string &K = ri->idx[0], &u = ri->idx[1], &v = ri->idx[2];
+    const std::string &i = rc->idx[0];
+    if (rc->idx[1] != u) return CONSTSTN_EUNSUPPORTED;
+    if (std::set<std::string>(p0.out.idx.begin(), p0.out.idx.end()) != std::set<std::string>{K, i, v}) return CONSTSTN_EUNSUPPORTED;
+    // the other input of a later statement, which must be an operand
+    auto partner = [&](const Stmt &st, int src, const Ref *&r, int &op) {
+        if (st.src_a == src && st.op_b >= 0) { r = &st.b; op = st.op_b; return true; }
+        if (st.src_b == src && st.op_a >= 0) { r = &st.a; op = st.op_a; return true; }
+        return false;
+    };
+    const Ref *rl = nullptr, *rp = nullptr;
+    int lop = -1, pop = -1;
+    if (m == 3) {
+        const Stmt &p1 = s.stmts[1];
+        if (!partner(p1, 0, rl, lop) || s.operands[lop].order != 2) return CONSTSTN_EUNSUPPORTED;
+        if (rl->idx[0] != K || rl->idx[1] != i) return CONSTSTN_EUNSUPPORTED;
+        if (std::set<std::string>(p1.out.idx.begin(), p1.out.idx.end()) != std::set<std::string>{K, i, v}) return CONSTSTN_EUNSUPPORTED;
+    }
+    const Stmt &pe = s.stmts[m - 1];
+    if (!partner(pe, int(m) - 2, rp, pop) || s.operands[pop].order != 2) return CONSTSTN_EUNSUPPORTED;
+    const std::string &mm = rp->idx[0];
+    if (rp->idx[1] != v) return CONSTSTN_EUNSUPPORTED;
+    if (pe.out.idx != std::vector<std::string>{K, i, mm}) return CONSTSTN_EUNSUPPORTED;
+    if (std::set<std::string>{K, i, u, v, mm}.size() != 5) return CONSTSTN_EUNSUPPORTED;
+    for (size_t p = 0; p + 1 < m; ++p)
+        if (s.stmts[p].fused_depth != 2) {
+            set_error("the sparse-chain kernel needs every producer fused with its consumer on the two outer loops "
+                      "(depth 2); statement %zu has depth %d", p, s.stmts[p].fused_depth);
+            return CONSTSTN_EUNSUPPORTED;
+        }
+    if (plan->compact) { set_error("the result of the sparse chain is sparse; the compact-rows flag does not apply"); return CONSTSTN_EINVAL; }
+    plan->family = FAM_SPCHAIN3;
+    plan->X = s.operands[iop].csf;
+    plan->sc_C = s.operands[cop].csf;
+    plan->sc_P = s.operands[pop].csf;
+    plan->sc_L = lop >= 0 ? s.operands[lop].csf : nullptr;
+    if (!plan->X || !plan->sc_C || !plan->sc_P || (lop >= 0 && !plan->sc_L)) { set_error("CSF operand without handle"); return CONSTSTN_EINVAL; }
+    return CONSTSTN_OK;
+}
+
 // rank extents the tuned kernels are built for
 static bool tuned_kernel_fits(const conststn_plan_s *plan) {
     switch (plan->family) {
@@ -167,6 +223,7 @@ static const char *family_name(Family f) {
         case FAM_MTTKRP3: return "mttkrp3";
         case FAM_SPTN3: return "sptn3";
         case FAM_GENERIC: return "generic";
+        case FAM_SPCHAIN3: return "spchain3";
         default: return "none";
     }
 }
@@ -278,10 +335,17 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
         st = match_sptn3(plan);
         if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
     }
+    if (st == CONSTSTN_EUNSUPPORTED && plan->family == FAM_NONE) {
+        std::string why = get_error();
+        clear_error();
+        st = match_spchain3(plan);
+        if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
+    }
     // tuned kernels have rank limits; beyond them, and for every other tree over one CSF operand,
     // the generic executor takes over
     if (st == CONSTSTN_OK && !tuned_kernel_fits(plan)) st = CONSTSTN_EUNSUPPORTED;
-    if (st == CONSTSTN_OK && env_int("CONSTSTN_FORCE_GENERIC", 0) == 1 && plan->family != FAM_SPTN3)
+    if (st == CONSTSTN_OK && env_int("CONSTSTN_FORCE_GENERIC", 0) == 1 && plan->family != FAM_SPTN3 &&
+        plan->family != FAM_SPCHAIN3)
         st = CONSTSTN_EUNSUPPORTED;
     if (st == CONSTSTN_EUNSUPPORTED) {
         std::string why = get_error();
@@ -305,6 +369,7 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
         case FAM_TTMC3:
         case FAM_TTMC4: CST_TRY(build_ttmc_tables(plan)); break;
         case FAM_SPTN3: CST_TRY(build_sptn3_tables(plan)); break;
+        case FAM_SPCHAIN3: CST_TRY(build_spchain3_tables(plan)); break;
         default: break;
     }
     char head[256];
@@ -344,6 +409,14 @@ conststn_status conststn_plan_output_rows(const conststn_plan_t *plan, const int
     if (!plan->compact) { set_error("the plan's output is not compact"); return CONSTSTN_EINVAL; }
     if (rows) *rows = plan->X->idx[0].p;
     if (n_rows) *n_rows = plan->X->nodes[0];
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan_output_csf(const conststn_plan_t *plan, const conststn_csf_t **structure) {
+    clear_error();
+    if (!plan || !structure) { set_error("null argument"); return CONSTSTN_EINVAL; }
+    if (!plan->sc_E) { set_error("the plan's result is dense"); return CONSTSTN_EINVAL; }
+    *structure = plan->sc_E.get();
     return CONSTSTN_OK;
 }
 
@@ -407,6 +480,7 @@ conststn_status conststn_execute(const conststn_plan_t *plan, const double *cons
         case FAM_TTMC3: return launch_ttmc3(plan, dense_factors, out, st);
         case FAM_TTMC4: return launch_ttmc4(plan, dense_factors, out, st);
         case FAM_SPTN3: return launch_sptn3(plan, dense_factors, out, st);
+        case FAM_SPCHAIN3: return launch_spchain3(plan, out, st);
         case FAM_GENERIC: return launch_generic(plan, dense_factors, out, st);
         default: set_error("plan has no kernel family"); return CONSTSTN_EINVAL;
     }

@@ -101,16 +101,6 @@ generic_stmt_kernel(GenStmt g) {
     g.out[row * g.out_block + out_off] = acc;
 }
 
-// parent of node c: the last p with ptr[p] <= c
-__device__ __forceinline__ int64_t parent_of(const int64_t *ptr, int64_t n, int64_t c) {
-    int64_t lo = 0, hi = n;                       // invariant: ptr[lo] <= c < ptr[hi]
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (ptr[mid] <= c) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 __global__ void __launch_bounds__(256)
 generic_node_kernel(GenStmt g) {
     const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;

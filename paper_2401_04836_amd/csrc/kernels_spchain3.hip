@@ -1,0 +1,540 @@
+// Chain of three SPARSE tensors with a SPARSE result (Sec. 5.1):
+//        E[K,i,m] = sum_{u,v} I[K,u,v] * C[u,i] * P[v,m]                  (unrestricted form)
+//        E[K,i,m] = sum_{u,v} I[K,u,v] * C[u,i] * P[v,m] * L[K,i]         (restricted form)
+// as the fused tree  T[K,i,v] = I[K,u,v] * C[i,u]  (loops K,i,u,v);  E[K,i,m] = T[K,i,v] * P[m,v]
+// (loops K,i,m,v), fused on (K,i): the intermediate shrinks to a vector over v (Sec. 2.2), which is
+// the dense workspace of Sec. 2.2's last paragraph -- here compressed to the v that occur under K.
+// Operand layouts: I as CSF (K > u > v), C as CSF (i > u), P as CSF (m > v), L as CSF (K > i).
+//
+// The structure of E does not depend on the values, so it is found once, when the plan is made
+// (symbolic pass), and every execute only fills the values (numeric pass):
+//
+//   symbolic  one wavefront per candidate (K,i) pair -- every pair of a K of I with an i of C,
+//             or the stored pairs of L -- intersects the u lists of I[K] and C[i] (co-iteration
+//             by binary search), marks the v below the matching u in a bit set, then the m that P
+//             joins to those v (through a transposed copy of P) in a second bit set.  Counts are
+//             scanned into the pointer arrays of E (CSF K > i > m) and a second run writes the m.
+//   numeric   one workgroup per K of E.  A table v -> slot (position of v among the distinct v
+//             under K) sits in LDS.  Each wavefront takes (K,i) nodes in turn: clears its
+//             workspace t[slot], adds I[K,u,v]*C[i,u] row by row for the matching u (lanes over
+//             v: no two lanes meet in one slot, rows in ascending u: a fixed summation order),
+//             then every lane owns one stored m of E[K,i,:] and gathers
+//             sum_v t[slot(v)] * P[m,v] along P's row, and stores the value in place.
+//             No atomics; the result is bit-reproducible.
+#include "plan.hpp"
+
+namespace cst {
+
+constexpr int kScWaves = 4;                 // wavefronts per workgroup
+constexpr uint16_t kNoSlot = 0xFFFF;
+
+struct ScArgs {
+    // I: levels (K,u,v)
+    const int32_t *i_idx0, *i_idx1;
+    const int64_t *i_ptr0, *i_ptr1;
+    const double *i_vals;
+    int64_t i_roots;
+    // C: levels (i,u)
+    const int32_t *c_idx0, *c_idx1;
+    const int64_t *c_ptr0;
+    const double *c_vals;
+    int64_t c_roots;
+    // P: levels (m,v), and which root node holds m
+    const int32_t *p_idx1;
+    const int64_t *p_ptr0;
+    const double *p_vals;
+    const int32_t *p_node_of_m;
+    // P transposed, levels (v,m), and which of its root nodes holds v (symbolic pass only)
+    const int32_t *pt_idx1;
+    const int64_t *pt_ptr0;
+    const int32_t *pt_node_of_v;
+    // distinct v under each K node of I, ascending; slot of every leaf of I in that list
+    const int64_t *nu_ptr;
+    const int32_t *nu_list;
+    const uint16_t *i_slot;
+    int64_t n_v, n_m;
+    int max_slots;
+    // candidate (K,i) pairs: all of them (restricted = 0) or the leaves of L
+    int64_t n_cand;
+    int restricted;
+    const int32_t *l_knode, *l_cnode;       // node of I / of C per leaf of L, -1 where absent
+    const double *l_vals;
+};
+
+// the result's structure and, per (K,i) node, where its operands are
+struct ScOut {
+    int32_t *idx0, *idx1, *idx2;
+    int64_t *ptr0, *ptr1;
+    int32_t *knode, *cnode;                 // per level-1 node: K node of I, root node of C
+    double *lval;                           // per level-1 node: value of L, or 1
+    int32_t *root_knode;                    // per root: K node of I
+    int64_t roots, nodes, nnz;
+};
+
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ int wave_sum(int x) {
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
+    return x;
+}
+
+// position of `key` in the ascending list a[lo..hi), or -1
+__device__ __forceinline__ int64_t find_in(const int32_t *a, int64_t lo, int64_t hi, int32_t key) {
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int32_t x = a[mid];
+        if (x == key) return mid;
+        if (x < key) lo = mid + 1; else hi = mid;
+    }
+    return -1;
+}
+
+__device__ __forceinline__ void decode_candidate(const ScArgs &A, int64_t c, int64_t &a, int64_t &b) {
+    if (A.restricted) { a = A.l_knode[c]; b = A.l_cnode[c]; }
+    else { a = c / A.c_roots; b = c - a * A.c_roots; }
+}
+
+// Bit sets of one (K node a, C root b) pair: slots of the v reached through a matching u, then
+// the m joined to those v.  Returns false (sets undefined) when no u matches.
+__device__ bool pair_sets(const ScArgs &A, int64_t a, int64_t b, uint32_t *smask, uint32_t *mmask, int lane) {
+    const int sw = (A.max_slots + 31) >> 5, mw = int((A.n_m + 31) >> 5);
+    for (int w = lane; w < sw; w += 64) smask[w] = 0;
+    wave_sync();
+    const int64_t n0 = A.i_ptr0[a], n1 = A.i_ptr0[a + 1];
+    const int64_t c0 = A.c_ptr0[b], c1 = A.c_ptr0[b + 1];
+    bool any = false;
+    for (int64_t base = n0; base < n1; base += 64) {
+        const int64_t n = base + lane;
+        bool hit = false;
+        if (n < n1) hit = find_in(A.c_idx1, c0, c1, A.i_idx1[n]) >= 0;
+        uint64_t bal = __ballot(hit);
+        any = any || bal != 0;
+        while (bal) {
+            const int bit = __ffsll((unsigned long long)bal) - 1;
+            bal &= bal - 1;
+            const int64_t l0 = A.i_ptr1[base + bit], l1 = A.i_ptr1[base + bit + 1];
+            for (int64_t l = l0 + lane; l < l1; l += 64) {
+                const uint32_t s = A.i_slot[l];
+                atomicOr(&smask[s >> 5], 1u << (s & 31));
+            }
+        }
+    }
+    if (!any) return false;
+    for (int w = lane; w < mw; w += 64) mmask[w] = 0;
+    wave_sync();
+    const int64_t nu0 = A.nu_ptr[a];
+    for (int w = 0; w < sw; ++w) {
+        uint32_t word = smask[w];                                   // the same word in every lane
+        while (word) {
+            const int s = (w << 5) + __ffs(word) - 1;
+            word &= word - 1;
+            const int32_t pn = A.pt_node_of_v[A.nu_list[nu0 + s]];
+            if (pn < 0) continue;
+            const int64_t q0 = A.pt_ptr0[pn], q1 = A.pt_ptr0[pn + 1];
+            for (int64_t q = q0 + lane; q < q1; q += 64) {
+                const uint32_t m = uint32_t(A.pt_idx1[q]);
+                atomicOr(&mmask[m >> 5], 1u << (m & 31));
+            }
+        }
+    }
+    wave_sync();
+    return true;
+}
+
+__global__ void __launch_bounds__(64 * kScWaves)
+spchain3_count_kernel(ScArgs A, int64_t *count) {
+    extern __shared__ uint32_t sets[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sw = (A.max_slots + 31) >> 5, mw = int((A.n_m + 31) >> 5);
+    uint32_t *smask = sets + size_t(wave) * (sw + mw), *mmask = smask + sw;
+    const int64_t c = int64_t(blockIdx.x) * kScWaves + wave;
+    if (c >= A.n_cand) return;
+    int64_t a, b;
+    decode_candidate(A, c, a, b);
+    int total = 0;
+    if (a >= 0 && b >= 0 && pair_sets(A, a, b, smask, mmask, lane)) {
+        int n = 0;
+        for (int w = lane; w < mw; w += 64) n += __popc(mmask[w]);
+        total = wave_sum(n);
+    }
+    if (lane == 0) count[c] = total;
+}
+
+__global__ void __launch_bounds__(64 * kScWaves)
+spchain3_fill_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ count, const int64_t *__restrict__ leaf_off,
+                     const int64_t *__restrict__ node_of) {
+    extern __shared__ uint32_t sets[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sw = (A.max_slots + 31) >> 5, mw = int((A.n_m + 31) >> 5);
+    uint32_t *smask = sets + size_t(wave) * (sw + mw), *mmask = smask + sw;
+    const int64_t c = int64_t(blockIdx.x) * kScWaves + wave;
+    if (c >= A.n_cand || count[c] == 0) return;
+    int64_t a, b;
+    decode_candidate(A, c, a, b);
+    pair_sets(A, a, b, smask, mmask, lane);
+    const int64_t node = node_of[c];
+    int64_t off = leaf_off[c];
+    if (lane == 0) {
+        E.idx1[node] = A.c_idx0[b];
+        E.ptr1[node] = off;
+        E.knode[node] = int32_t(a);
+        E.cnode[node] = int32_t(b);
+        E.lval[node] = A.restricted ? A.l_vals[c] : 1.0;
+    }
+    for (int wb = 0; wb < mw; wb += 64) {
+        const int w = wb + lane;
+        uint32_t word = w < mw ? mmask[w] : 0u;
+        const int n = __popc(word);
+        int incl = n;                                               // inclusive scan over the lanes
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        int64_t at = off + incl - n;
+        while (word) {
+            E.idx2[at++] = (w << 5) + __ffs(word) - 1;
+            word &= word - 1;
+        }
+        off += __shfl(incl, 63, 64);
+    }
+}
+
+// roots of E: the K nodes that own at least one (K,i) node
+__global__ void spchain3_root_flag_kernel(ScOut E, int64_t *flag) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n >= E.nodes) return;
+    flag[n] = (n == 0 || E.knode[n - 1] != E.knode[n]) ? 1 : 0;
+}
+
+__global__ void spchain3_root_fill_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ flag,
+                                          const int64_t *__restrict__ root_of) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n > E.nodes) return;
+    if (n == E.nodes) {
+        E.ptr0[E.roots] = E.nodes;
+        E.ptr1[E.nodes] = E.nnz;
+        return;
+    }
+    if (flag[n]) {
+        const int64_t r = root_of[n];
+        E.idx0[r] = A.i_idx0[E.knode[n]];
+        E.ptr0[r] = n;
+        E.root_knode[r] = E.knode[n];
+    }
+}
+
+__global__ void __launch_bounds__(64 * kScWaves)
+spchain3_kernel(ScArgs A, ScOut E, double *__restrict__ out, int map_bytes) {
+    extern __shared__ unsigned char lds[];
+    uint16_t *map = reinterpret_cast<uint16_t *>(lds);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double *t = reinterpret_cast<double *>(lds + map_bytes) + size_t(wave) * A.max_slots;
+    const int64_t r = blockIdx.x;
+    const int64_t a = E.root_knode[r];
+    const int64_t nu0 = A.nu_ptr[a];
+    const int ns = int(A.nu_ptr[a + 1] - nu0);
+    for (int64_t x = threadIdx.x; x < (A.n_v + 1) / 2; x += blockDim.x) reinterpret_cast<uint32_t *>(map)[x] = 0xFFFFFFFFu;
+    __syncthreads();
+    for (int s = threadIdx.x; s < ns; s += blockDim.x) map[A.nu_list[nu0 + s]] = uint16_t(s);
+    __syncthreads();
+    const int64_t n0 = A.i_ptr0[a], n1 = A.i_ptr0[a + 1];
+    for (int64_t node = E.ptr0[r] + wave; node < E.ptr0[r + 1]; node += kScWaves) {
+        for (int s = lane; s < ns; s += 64) t[s] = 0.0;
+        wave_sync();
+        const int64_t b = E.cnode[node];
+        const int64_t c0 = A.c_ptr0[b], c1 = A.c_ptr0[b + 1];
+        // producer: t[v] += I[K,u,v] * C[i,u] over the u stored in both
+        for (int64_t base = n0; base < n1; base += 64) {
+            const int64_t n = base + lane;
+            int64_t pos = -1;
+            if (n < n1) pos = find_in(A.c_idx1, c0, c1, A.i_idx1[n]);
+            const double cv = pos >= 0 ? A.c_vals[pos] : 0.0;
+            uint64_t bal = __ballot(pos >= 0);
+            while (bal) {
+                const int bit = __ffsll((unsigned long long)bal) - 1;
+                bal &= bal - 1;
+                const double c = __shfl(cv, bit, 64);
+                const int64_t l0 = A.i_ptr1[base + bit], l1 = A.i_ptr1[base + bit + 1];
+                for (int64_t l = l0 + lane; l < l1; l += 64) {
+                    const int s = A.i_slot[l];
+                    t[s] = fma(A.i_vals[l], c, t[s]);
+                }
+                wave_sync();
+            }
+        }
+        // consumer: E[K,i,m] = sum_v t[v] * P[m,v], one stored m per lane
+        const double lv = E.lval[node];
+        for (int64_t q = E.ptr1[node] + lane; q < E.ptr1[node + 1]; q += 64) {
+            const int32_t pn = A.p_node_of_m[E.idx2[q]];
+            double acc = 0.0;
+            for (int64_t p = A.p_ptr0[pn]; p < A.p_ptr0[pn + 1]; ++p) {
+                const uint16_t s = map[A.p_idx1[p]];
+                if (s != kNoSlot) acc = fma(t[s], A.p_vals[p], acc);
+            }
+            out[q] = acc * lv;
+        }
+        wave_sync();
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------------
+
+// index of the level-`level` ancestor of every leaf of a CSF tensor
+__global__ void leaf_ancestor_index_kernel(int order, int level, int64_t nnz, const int64_t *p0, int64_t n0,
+                                           const int64_t *p1, int64_t n1, const int32_t *idx, int32_t *out) {
+    const int64_t l = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (l >= nnz) return;
+    int64_t c = l;
+    if (order == 3) {
+        c = parent_of(p1, n1, c);
+        if (level == 0) c = parent_of(p0, n0, c);
+    } else {
+        c = parent_of(p0, n0, c);
+    }
+    out[l] = idx[c];
+}
+
+__global__ void sc_fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < n) p[x] = v;
+}
+
+__global__ void node_of_index_kernel(const int32_t *idx0, int64_t roots, int32_t *node_of) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < roots) node_of[idx0[x]] = int32_t(x);
+}
+
+__global__ void leaf_slot_kernel(int64_t nnz, const int64_t *p0, int64_t n0, const int64_t *p1, int64_t n1,
+                                 const int32_t *idx2, const int64_t *nu_ptr, const int32_t *nu_list, uint16_t *slot) {
+    const int64_t l = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (l >= nnz) return;
+    const int64_t a = parent_of(p0, n0, parent_of(p1, n1, l));
+    const int64_t at = find_in(nu_list, nu_ptr[a], nu_ptr[a + 1], idx2[l]);
+    slot[l] = uint16_t(at - nu_ptr[a]);
+}
+
+// per leaf of L: node of I holding its K, root node of C holding its i (-1 where absent)
+__global__ void filter_nodes_kernel(int64_t nnz, const int64_t *lp0, int64_t ln0, const int32_t *l_idx0,
+                                    const int32_t *l_idx1, const int32_t *i_idx0, int64_t i_roots,
+                                    const int32_t *c_idx0, int64_t c_roots, int32_t *knode, int32_t *cnode) {
+    const int64_t l = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (l >= nnz) return;
+    const int32_t K = l_idx0[parent_of(lp0, ln0, l)];
+    knode[l] = int32_t(find_in(i_idx0, 0, i_roots, K));
+    cnode[l] = int32_t(find_in(c_idx0, 0, c_roots, l_idx1[l]));
+}
+
+__global__ void nonzero_flag_kernel(const int64_t *count, int64_t n, int64_t *flag) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < n) flag[x] = count[x] > 0 ? 1 : 0;
+}
+
+static inline dim3 grid_for(int64_t n, int block = 256) { return dim3(unsigned(std::max<int64_t>(1, div_up(n, block)))); }
+
+static ScArgs make_args(const conststn_plan_s *plan) {
+    const conststn_csf_s *I = plan->X, *C = plan->sc_C, *P = plan->sc_P, *L = plan->sc_L;
+    ScArgs A{};
+    A.i_idx0 = I->idx[0].p; A.i_idx1 = I->idx[1].p;
+    A.i_ptr0 = I->ptr[0].p; A.i_ptr1 = I->ptr[1].p;
+    A.i_vals = I->vals.p;
+    A.i_roots = I->nodes[0];
+    A.c_idx0 = C->idx[0].p; A.c_idx1 = C->idx[1].p; A.c_ptr0 = C->ptr[0].p; A.c_vals = C->vals.p;
+    A.c_roots = C->nodes[0];
+    A.p_idx1 = P->idx[1].p; A.p_ptr0 = P->ptr[0].p; A.p_vals = P->vals.p;
+    A.p_node_of_m = plan->sc_p_node_of_m.p;
+    A.nu_ptr = plan->sc_nu_ptr.p;
+    A.nu_list = plan->sc_nu_list.p;
+    A.i_slot = plan->sc_i_slot.p;
+    A.n_v = I->dims[I->mode_order[2]];
+    A.n_m = P->dims[P->mode_order[0]];
+    A.max_slots = plan->sc_max_slots;
+    A.restricted = L ? 1 : 0;
+    A.n_cand = L ? L->nnz : A.i_roots * A.c_roots;
+    A.l_knode = plan->sc_l_knode.p;
+    A.l_cnode = plan->sc_l_cnode.p;
+    A.l_vals = L ? L->vals.p : nullptr;
+    return A;
+}
+
+static ScOut make_out(const conststn_plan_s *plan) {
+    conststn_csf_s *E = plan->sc_E.get();
+    ScOut o{};
+    o.idx0 = E->idx[0].p; o.idx1 = E->idx[1].p; o.idx2 = E->idx[2].p;
+    o.ptr0 = E->ptr[0].p; o.ptr1 = E->ptr[1].p;
+    o.knode = plan->sc_e_knode.p; o.cnode = plan->sc_e_cnode.p; o.lval = plan->sc_e_lval.p;
+    o.root_knode = plan->sc_e_root_knode.p;
+    o.roots = E->nodes[0]; o.nodes = E->nodes[1]; o.nnz = E->nodes[2];
+    return o;
+}
+
+conststn_status build_spchain3_tables(conststn_plan_s *plan) {
+    const conststn_csf_s *I = plan->X, *C = plan->sc_C, *P = plan->sc_P, *L = plan->sc_L;
+    const hipStream_t st = nullptr;
+    const int64_t n_K = I->dims[I->mode_order[0]], n_u = I->dims[I->mode_order[1]], n_v = I->dims[I->mode_order[2]];
+    const int64_t n_i = C->dims[C->mode_order[0]], n_m = P->dims[P->mode_order[0]];
+    if (n_v > 70000) { set_error("the sparse-chain kernel keeps a v -> slot table of 2 bytes per v in LDS; extent %lld is beyond it", (long long)n_v); return CONSTSTN_EUNSUPPORTED; }
+
+    // P transposed to (v > m), for the symbolic pass only
+    conststn_csf_s pt;
+    {
+        DevBuf<int32_t> cm;
+        CST_TRY(cm.alloc(size_t(P->nnz)));
+        if (P->nnz)
+            leaf_ancestor_index_kernel<<<grid_for(P->nnz), 256, 0, st>>>(2, 0, P->nnz, P->ptr[0].p, P->nodes[0], nullptr, 0,
+                                                                        P->idx[0].p, cm.p);
+        CST_HIP(hipGetLastError());
+        const int32_t *coords[2] = {P->idx[1].p, cm.p};
+        const int64_t dims2[2] = {n_v, n_m};
+        const int mo[2] = {0, 1};
+        CST_TRY(build_csf_device(2, dims2, P->nnz, coords, P->vals.p, mo, 0, st, &pt));
+    }
+    DevBuf<int32_t> pt_node_of_v;
+    CST_TRY(pt_node_of_v.alloc(size_t(n_v)));
+    CST_TRY(plan->sc_p_node_of_m.alloc(size_t(n_m)));
+    sc_fill_i32_kernel<<<grid_for(n_v), 256, 0, st>>>(pt_node_of_v.p, n_v, -1);
+    sc_fill_i32_kernel<<<grid_for(n_m), 256, 0, st>>>(plan->sc_p_node_of_m.p, n_m, -1);
+    node_of_index_kernel<<<grid_for(pt.nodes[0]), 256, 0, st>>>(pt.idx[0].p, pt.nodes[0], pt_node_of_v.p);
+    node_of_index_kernel<<<grid_for(P->nodes[0]), 256, 0, st>>>(P->idx[0].p, P->nodes[0], plan->sc_p_node_of_m.p);
+    CST_HIP(hipGetLastError());
+
+    // distinct v under every K: the level-1 nodes of I re-sorted as (K > v > u)
+    {
+        conststn_csf_s kvu;
+        DevBuf<int32_t> cK, cu;
+        CST_TRY(cK.alloc(size_t(I->nnz)));
+        CST_TRY(cu.alloc(size_t(I->nnz)));
+        if (I->nnz) {
+            leaf_ancestor_index_kernel<<<grid_for(I->nnz), 256, 0, st>>>(3, 0, I->nnz, I->ptr[0].p, I->nodes[0], I->ptr[1].p,
+                                                                        I->nodes[1], I->idx[0].p, cK.p);
+            leaf_ancestor_index_kernel<<<grid_for(I->nnz), 256, 0, st>>>(3, 1, I->nnz, I->ptr[0].p, I->nodes[0], I->ptr[1].p,
+                                                                        I->nodes[1], I->idx[1].p, cu.p);
+        }
+        CST_HIP(hipGetLastError());
+        const int32_t *coords[3] = {cK.p, cu.p, I->idx[2].p};
+        const int64_t dims3[3] = {n_K, n_u, n_v};
+        const int mo[3] = {0, 2, 1};
+        CST_TRY(build_csf_device(3, dims3, I->nnz, coords, I->vals.p, mo, 0, st, &kvu));
+        if (kvu.nodes[0] != I->nodes[0]) { set_error("internal: re-sorted copy of I has %lld roots, I has %lld", (long long)kvu.nodes[0], (long long)I->nodes[0]); return CONSTSTN_EINVAL; }
+        CST_TRY(plan->sc_nu_ptr.alloc(size_t(kvu.nodes[0] + 1)));
+        CST_TRY(plan->sc_nu_list.alloc(size_t(kvu.nodes[1])));
+        CST_HIP(hipMemcpy(plan->sc_nu_ptr.p, kvu.ptr[0].p, size_t(kvu.nodes[0] + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice));
+        if (kvu.nodes[1])
+            CST_HIP(hipMemcpy(plan->sc_nu_list.p, kvu.idx[1].p, size_t(kvu.nodes[1]) * sizeof(int32_t), hipMemcpyDeviceToDevice));
+        std::vector<int64_t> h(size_t(kvu.nodes[0] + 1));
+        CST_HIP(hipMemcpy(h.data(), kvu.ptr[0].p, h.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+        int64_t mx = 1;
+        for (size_t a = 0; a + 1 < h.size(); ++a) mx = std::max(mx, h[a + 1] - h[a]);
+        if (mx > 65534) { set_error("a K of I joins %lld distinct v; the sparse-chain kernel numbers them with 16 bits", (long long)mx); return CONSTSTN_EUNSUPPORTED; }
+        plan->sc_max_slots = int(mx);
+    }
+    CST_TRY(plan->sc_i_slot.alloc(size_t(I->nnz)));
+    if (I->nnz)
+        leaf_slot_kernel<<<grid_for(I->nnz), 256, 0, st>>>(I->nnz, I->ptr[0].p, I->nodes[0], I->ptr[1].p, I->nodes[1], I->idx[2].p,
+                                                          plan->sc_nu_ptr.p, plan->sc_nu_list.p, plan->sc_i_slot.p);
+    CST_HIP(hipGetLastError());
+
+    // candidates
+    if (L) {
+        CST_TRY(plan->sc_l_knode.alloc(size_t(L->nnz)));
+        CST_TRY(plan->sc_l_cnode.alloc(size_t(L->nnz)));
+        if (L->nnz)
+            filter_nodes_kernel<<<grid_for(L->nnz), 256, 0, st>>>(L->nnz, L->ptr[0].p, L->nodes[0], L->idx[0].p, L->idx[1].p,
+                                                                 I->idx[0].p, I->nodes[0], C->idx[0].p, C->nodes[0],
+                                                                 plan->sc_l_knode.p, plan->sc_l_cnode.p);
+        CST_HIP(hipGetLastError());
+    }
+    ScArgs A = make_args(plan);
+    A.pt_idx1 = pt.idx[1].p;
+    A.pt_ptr0 = pt.ptr[0].p;
+    A.pt_node_of_v = pt_node_of_v.p;
+    if (A.n_cand > (int64_t(1) << 30)) {
+        set_error("%lld candidate (K,i) pairs; the symbolic pass holds one counter per pair -- use the restricted form "
+                  "with a K -> i map", (long long)A.n_cand);
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    const size_t set_bytes = size_t(kScWaves) * (size_t((A.max_slots + 31) >> 5) + size_t((n_m + 31) >> 5)) * 4;
+    if (set_bytes > 160 * 1024) { set_error("bit sets of %zu bytes per workgroup do not fit LDS (extent of m %lld)", set_bytes, (long long)n_m); return CONSTSTN_EUNSUPPORTED; }
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_count_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(set_bytes)));
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_fill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(set_bytes)));
+
+    plan->sc_E.reset(new conststn_csf_s());
+    conststn_csf_s *E = plan->sc_E.get();
+    E->order = 3;
+    E->dims[0] = n_K; E->dims[1] = n_i; E->dims[2] = n_m;
+    for (int l = 0; l < 3; ++l) E->mode_order[l] = l;
+    E->device = I->device;
+    int64_t nnz = 0, nodes = 0, roots = 0;
+    DevBuf<int64_t> count, leaf_off, flag, node_of;
+    const int64_t nc = A.n_cand;
+    if (nc > 0) {
+        CST_TRY(count.alloc(size_t(nc)));
+        CST_TRY(leaf_off.alloc(size_t(nc)));
+        CST_TRY(flag.alloc(size_t(nc)));
+        CST_TRY(node_of.alloc(size_t(nc)));
+        spchain3_count_kernel<<<grid_for(nc, kScWaves), 64 * kScWaves, set_bytes, st>>>(A, count.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(count.p, leaf_off.p, nc, &nnz));
+        nonzero_flag_kernel<<<grid_for(nc), 256, 0, st>>>(count.p, nc, flag.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(flag.p, node_of.p, nc, &nodes));
+    }
+    CST_TRY(E->idx[1].alloc(size_t(nodes)));
+    CST_TRY(E->ptr[1].alloc(size_t(nodes + 1)));
+    CST_TRY(E->idx[2].alloc(size_t(nnz)));
+    CST_TRY(plan->sc_e_knode.alloc(size_t(nodes)));
+    CST_TRY(plan->sc_e_cnode.alloc(size_t(nodes)));
+    CST_TRY(plan->sc_e_lval.alloc(size_t(nodes)));
+    E->nodes[1] = nodes;
+    E->nodes[2] = nnz;
+    E->nnz = nnz;
+    ScOut O = make_out(plan);
+    if (nodes > 0) {
+        spchain3_fill_kernel<<<grid_for(nc, kScWaves), 64 * kScWaves, set_bytes, st>>>(A, O, count.p, leaf_off.p, node_of.p);
+        CST_HIP(hipGetLastError());
+    }
+    // roots
+    DevBuf<int64_t> rflag, root_of;
+    CST_TRY(rflag.alloc(size_t(nodes)));
+    CST_TRY(root_of.alloc(size_t(nodes)));
+    if (nodes > 0) {
+        spchain3_root_flag_kernel<<<grid_for(nodes), 256, 0, st>>>(O, rflag.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(rflag.p, root_of.p, nodes, &roots));
+    }
+    CST_TRY(E->idx[0].alloc(size_t(roots)));
+    CST_TRY(E->ptr[0].alloc(size_t(roots + 1)));
+    CST_TRY(plan->sc_e_root_knode.alloc(size_t(roots)));
+    E->nodes[0] = roots;
+    O = make_out(plan);
+    spchain3_root_fill_kernel<<<grid_for(nodes + 1), 256, 0, st>>>(A, O, rflag.p, root_of.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipStreamSynchronize(st));
+
+    // numeric pass: LDS = v -> slot table + one workspace per wavefront
+    plan->sc_map_bytes = int(((n_v + 1) / 2 * 4 + 15) / 16 * 16);
+    const size_t lds = size_t(plan->sc_map_bytes) + size_t(kScWaves) * size_t(plan->sc_max_slots) * sizeof(double);
+    if (lds > 160 * 1024) {
+        set_error("v -> slot table (%d bytes) and %d workspaces of %d slots do not fit LDS", plan->sc_map_bytes, kScWaves, plan->sc_max_slots);
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    plan->sc_lds_bytes = int(lds);
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+    plan->out_rows = nnz;
+    plan->row_elems = 1;
+    return CONSTSTN_OK;
+}
+
+conststn_status launch_spchain3(const conststn_plan_s *plan, double *out, hipStream_t stream) {
+    const ScArgs A = make_args(plan);
+    const ScOut O = make_out(plan);
+    ProfScope prof(plan, stream);
+    if (O.roots == 0) return CONSTSTN_OK;
+    spchain3_kernel<<<dim3(unsigned(O.roots)), 64 * kScWaves, size_t(plan->sc_lds_bytes), stream>>>(A, O, out, plan->sc_map_bytes);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
+}  // namespace cst

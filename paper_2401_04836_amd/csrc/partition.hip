@@ -266,7 +266,6 @@ static conststn_status build_part_tables(MttkrpPart &P, int R, int64_t q) {
     return CONSTSTN_OK;
 }
 
-static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
 
 static conststn_status build_mttkrp3_split(conststn_plan_s *plan, const int32_t *slot_of_row) {
     const conststn_csf_s *X = plan->X;
@@ -462,7 +461,7 @@ __global__ void ttmc_fill_kernel(int64_t slices, const int64_t *__restrict__ uni
     }
 }
 
-static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host) {
+conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host) {
     size_t bytes = 0;
     CST_HIP(rocprim::exclusive_scan(nullptr, bytes, in, out, int64_t(0), size_t(n), rocprim::plus<int64_t>(), hipStream_t(0)));
     DevBuf<char> temp;
@@ -526,7 +525,6 @@ __global__ void slice_rows_kernel(int64_t slices, int64_t fibers, const int64_t 
     slice_row[s] = f < fibers ? row_off[f] : total_rows;
 }
 
-static conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
 
 static conststn_status build_rows_core(int64_t slices, int64_t fibers, const int64_t *ptr0, const int64_t *ptr1,
                                        const int32_t *idx1, DevBuf<RowDesc> &rows_out, DevBuf<int64_t> &slice_row,

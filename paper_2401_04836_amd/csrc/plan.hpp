@@ -18,7 +18,7 @@ constexpr int kSpGroup = 16;          // root slices of U processed together (on
 constexpr int kSpMaxMTiles = 25;      // m tiles whose accumulators a wavefront holds (M <= 400)
 constexpr int kSpMaxJ = 32768;        // extent of the contracted mode j the LDS bit mask covers
 
-enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GENERIC };
+enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GENERIC, FAM_SPCHAIN3 };
 
 // One statement of the generic executor (generic.hip), passed to its kernel by value.
 // Dense loop indices: the first n_out are the result's dense indices in storage order, the
@@ -170,6 +170,19 @@ struct conststn_plan_s {
     bool gen_rooted = false;               // the result has one row block per root index
     bool gen_zero_out = false;             // the last statement adds into the result: cleared before every run
 
+    // chain of three sparse tensors with a sparse result (X is the order-3 tensor)
+    const conststn_csf_s *sc_C = nullptr, *sc_P = nullptr, *sc_L = nullptr;
+    std::unique_ptr<conststn_csf_s> sc_E;  // structure of the result (no values): CSF K > i > m
+    cst::DevBuf<int32_t> sc_p_node_of_m;   // [extent of m] root node of P holding m, or -1
+    cst::DevBuf<int64_t> sc_nu_ptr;        // [K nodes + 1] into sc_nu_list
+    cst::DevBuf<int32_t> sc_nu_list;       // distinct v under each K node, ascending
+    cst::DevBuf<uint16_t> sc_i_slot;       // [leaves of X] position of the leaf's v in its K's list
+    cst::DevBuf<int32_t> sc_l_knode, sc_l_cnode;        // per leaf of L: K node of X, root node of C (-1: absent)
+    cst::DevBuf<int32_t> sc_e_knode, sc_e_cnode;        // per (K,i) node of the result: the same
+    cst::DevBuf<double> sc_e_lval;         // per (K,i) node: value of L (1 without a filter)
+    cst::DevBuf<int32_t> sc_e_root_knode;  // per root of the result: K node of X
+    int sc_max_slots = 0, sc_map_bytes = 0, sc_lds_bytes = 0;
+
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;
     mutable int64_t prof_count = 0;        // executes recorded since the last read
@@ -195,6 +208,9 @@ conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *d
                              hipStream_t stream);
 conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream);
+// kernels_spchain3.hip: three sparse tensors, sparse result
+conststn_status build_spchain3_tables(conststn_plan_s *plan);
+conststn_status launch_spchain3(const conststn_plan_s *plan, double *out, hipStream_t stream);
 // generic.hip: any tree over one CSF operand that the tuned families do not take
 conststn_status build_generic(conststn_plan_s *plan);
 conststn_status launch_generic(const conststn_plan_s *plan, const double *const *dense, double *out,
@@ -207,6 +223,19 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
                                  const int32_t *const *coords, const double *vals,
                                  const int *mode_order, unsigned flags, hipStream_t stream,
                                  conststn_csf_s *csf);
+
+// exclusive prefix sum of n int64 on the default stream; *total_host = sum of all inputs
+conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
+
+// parent of CSF node c one level up: the last p in [0, n) with ptr[p] <= c
+__device__ __forceinline__ int64_t parent_of(const int64_t *ptr, int64_t n, int64_t c) {
+    int64_t lo = 0, hi = n;                       // invariant: ptr[lo] <= c < ptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr[mid] <= c) lo = mid; else hi = mid;
+    }
+    return lo;
+}
 
 // fill `n` doubles with zero on `stream` (a kernel, so that it is safe inside graph capture)
 conststn_status zero_fill(double *p, int64_t n, hipStream_t stream);
