@@ -26,14 +26,16 @@ CSRC = os.path.join(ROOT, "paper_2401_04836_amd", "csrc")
 KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "ttmc3": ["kernels_ttmc3.hip", "partition.hip"],
                   "ttmc4": ["kernels_ttmc4.hip", "partition.hip"],
-                  "sptn3": ["kernels_sptn3.hip", "partition.hip"]}
+                  "sptn3": ["kernels_sptn3.hip", "partition.hip"],
+                  "spchain3": ["kernels_spchain3.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
                 "ttmc3": "ttmc3_mfma_kernel<4,2>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
+                "spchain3": "spchain3_kernel",
                 "generic": "generic_stmt_kernel (one launch per statement)"}
 # what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they
 # compute (HBM); the order-4 TTMc and the three-tensor network are dense contractions per fiber
 # (fp64 matrix cores)
-BOUND = {"mttkrp3": "hbm", "ttmc3": "hbm", "ttmc4": "mfma", "sptn3": "mfma"}
+BOUND = {"mttkrp3": "hbm", "ttmc3": "hbm", "ttmc4": "mfma", "sptn3": "mfma", "spchain3": "hbm"}
 
 
 def measured_traffic(family):
@@ -137,6 +139,33 @@ def build_sptn(cst, S, wl, dev):
     return [dict(plan=pl, factors=[V], out=out, nodes=un, bytes=alg_bytes, flops=flops)], build_s, U.nnz + W.nnz
 
 
+def build_spchain(cst, S, wl, dev, restricted):
+    I, C, P, L = (wl.sparse[k] for k in "ICPL")
+    on = lambda t: ([c.to(dev) for c in t.coords], t.vals.to(dev))
+    (ic, iv), (cc, cv), (pc, pv), (lc, lv) = on(I), on(C), on(P), on(L)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    hI = cst.build_csf(ic, iv, I.dims, [0, 1, 2])
+    hC = cst.build_csf(cc, cv, C.dims, [1, 0])
+    hP = cst.build_csf(pc, pv, P.dims, [1, 0])
+    ops = [("I", hI), ("C", hC), ("P", hP)]
+    if restricted:
+        hL = cst.build_csf(lc, lv, L.dims, [0, 1])
+        ops = [("I", hI), ("C", hC), ("L", hL), ("P", hP)]
+    pl = cst.plan(S.SPCHAIN3_RESTRICTED if restricted else S.SPCHAIN3, ops)
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    E = pl.output_csf()
+    en = [E.nodes(l) for l in range(3)]
+    nodes = [hI.nodes(l) for l in range(3)]
+    out = torch.empty(pl.n_rows, dtype=torch.float64, device=dev)
+    # algorithmic HBM bytes: I once (slot 2 B + value 8 B per leaf, index + pointer per upper node), C and P
+    # once, the structure of E once (4 B per leaf, 12 B + operand references per upper node), its values once
+    alg_bytes = 10 * nodes[2] + 12 * (nodes[1] + nodes[0]) + 12 * (C.nnz + P.nnz) + 4 * en[2] + 28 * en[1] + 8 * en[2]
+    nnz_in = I.nnz + C.nnz + P.nnz + (L.nnz if restricted else 0)
+    return [dict(plan=pl, factors=[], out=out, nodes=nodes, bytes=alg_bytes, flops=0, keep=ops)], build_s, nnz_in
+
+
 def cpu_baseline(wl, budget_nnz):
     """The CPU oracle, as it stands, on a bounded sample (first nonzeros) of the same workload."""
     import oracle
@@ -181,6 +210,26 @@ def cpu_baseline(wl, budget_nnz):
         dt = time.perf_counter() - t0
         return dict(value=n / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
                     sample="order-4 TTMc of the first %d nonzeros, %.2f s" % (n, dt))
+    if wl.kind == "spchain3":
+        from oracle import spsp
+        I, C, P, L = (wl.sparse[k] for k in "ICPL")
+        as_np = lambda t: ([c.cpu().numpy() for c in t.coords], t.vals.cpu().numpy())
+        n_K = wl.params["dims"][0]
+        ks = sorted(set(int(k) for k in torch.linspace(0, n_K - 1, 6 if n_K > 1000 else n_K)))
+        Inp = as_np(I)
+        in_sample = int(sum((Inp[0][0] == k).sum() for k in ks))
+        t0 = time.perf_counter()
+        spsp.chain3(Inp, as_np(C), as_np(P), wl.params["dims"], as_np(L) if wl.params.get("restricted") else None,
+                    K_values=ks)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+        except ImportError:
+            cores = 1
+        return dict(value=in_sample / dt, unit="nnz/s", cores=cores, kind="oracle",
+                    sample="%d of the %d slices K (evenly spaced), %d nonzeros of I, dense slice products, %.2f s"
+                           % (len(ks), n_K, in_sample, dt))
     return None
 
 
@@ -189,7 +238,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="benchmark configuration 1..5 (default 2); 6 = the sparse chain of Sec. 5.1 on lattice maps")
+    ap.add_argument("--restricted", action="store_true", help="configuration 6: the form with the K -> i filter")
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--generic", action="store_true",
@@ -236,6 +287,12 @@ def main():
         name = "C%d TTMc order-%d %s nnz=%d ranks=%s" % (
             args.config, wl.sparse["X"].order, "x".join(map(str, wl.sparse["X"].dims)),
             wl.sparse["X"].nnz, wl.params["ranks"])
+    elif wl.kind == "spchain3":
+        wl.params["restricted"] = args.restricted
+        launches, build_s, nnz_per_step = build_spchain(cst, S, wl, dev, args.restricted)
+        name = "C6 E=I.C.P%s lattice %dx%d dims(K,i,u,m)=%s nnzI=%d nnzE=%d" % (
+            ".L (restricted)" if args.restricted else "", wl.params["side"], wl.params["side"], wl.params["dims"],
+            wl.sparse["I"].nnz, launches[0]["plan"].n_rows)
     else:
         launches, build_s, nnz_per_step = build_sptn(cst, S, wl, dev)
         name = "C4 Z=(U.V).W dims(i,j,k,l,m)=%s nnzU=%d nnzW=%d" % (

@@ -384,6 +384,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
             snprintf(b, sizeof(b), " kernel=baseline");
         plan->description += b;
     }
+    if (plan->family == FAM_SPCHAIN3)
+        plan->description += plan->sc_local ? " kernel=block-local" : " kernel=general";
     for (size_t p = 0; p + 1 < plan->sched.stmts.size(); ++p) {
         char b[128];
         snprintf(b, sizeof(b), " %s:order%d", plan->sched.stmts[p].out.name.c_str(), plan->sched.stmts[p].reduced_order);

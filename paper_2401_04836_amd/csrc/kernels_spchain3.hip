@@ -21,6 +21,14 @@
 //             then every lane owns one stored m of E[K,i,:] and gathers
 //             sum_v t[slot(v)] * P[m,v] along P's row, and stores the value in place.
 //             No atomics; the result is bit-reproducible.
+//   numeric, block-local form.  The sparse maps of Sec. 5.1 are local: under one K only a few
+//             u, v and m occur.  When the blocks  I_K [u rows of K x v slots of K]  and
+//             P_K [v slots of K x m of K]  fit LDS as dense arrays, the workgroup of K builds them
+//             once and every (K,i) node becomes two small dense products out of LDS,
+//             t = c_i . I_K  (c_i: the entries of C[i,:] that meet a u row of K) and
+//             E[K,i,:] = t . P_K  at the stored m only: no global gathers in the inner loops.
+//             Terms are visited in the same order as in the general form; the extra terms are
+//             exact zeros.  Chosen by the plan when every K fits; otherwise the general form.
 #include "plan.hpp"
 
 namespace cst {
@@ -59,6 +67,11 @@ struct ScArgs {
     int restricted;
     const int32_t *l_knode, *l_cnode;       // node of I / of C per leaf of L, -1 where absent
     const double *l_vals;
+    // block-local form: the m that occur under each root of E, ascending
+    const int64_t *mu_ptr;
+    const int32_t *mu_list;
+    int64_t n_u;
+    int ik_elems, pk_elems;                 // LDS doubles set aside for I_K and P_K
 };
 
 // the result's structure and, per (K,i) node, where its operands are
@@ -280,6 +293,131 @@ spchain3_kernel(ScArgs A, ScOut E, double *__restrict__ out, int map_bytes) {
     }
 }
 
+// The m that occur anywhere under one root of E: mode 0 counts them, mode 1 lists them (ascending).
+__global__ void __launch_bounds__(256)
+spchain3_root_mset_kernel(ScOut E, int64_t n_m, int mode, int64_t *count, const int64_t *__restrict__ off, int32_t *list) {
+    extern __shared__ uint32_t mset[];
+    __shared__ int wave_tot[4];
+    const int mw = int((n_m + 31) >> 5);
+    const int64_t r = blockIdx.x;
+    for (int w = threadIdx.x; w < mw; w += 256) mset[w] = 0;
+    __syncthreads();
+    const int64_t q0 = E.ptr1[E.ptr0[r]], q1 = E.ptr1[E.ptr0[r + 1]];
+    for (int64_t q = q0 + threadIdx.x; q < q1; q += 256) {
+        const uint32_t m = uint32_t(E.idx2[q]);
+        atomicOr(&mset[m >> 5], 1u << (m & 31));
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t base = mode ? off[r] : 0;
+    int total = 0;
+    for (int wb = 0; wb < mw; wb += 256) {
+        const int w = wb + threadIdx.x;
+        uint32_t word = w < mw ? mset[w] : 0u;
+        const int n = __popc(word);
+        int incl = n;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int before = 0, all = 0;
+        for (int x = 0; x < 4; ++x) { if (x < wave) before += wave_tot[x]; all += wave_tot[x]; }
+        if (mode) {
+            int64_t at = base + before + incl - n;
+            while (word) {
+                list[at++] = (w << 5) + __ffs(word) - 1;
+                word &= word - 1;
+            }
+        }
+        base += all;
+        total += all;
+        __syncthreads();
+    }
+    if (!mode && threadIdx.x == 0) count[r] = total;
+}
+
+constexpr int kScLocalWaves = 8;
+
+__global__ void __launch_bounds__(64 * kScLocalWaves)
+spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out) {
+    extern __shared__ unsigned char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nthreads = 64 * kScLocalWaves;
+    // LDS: I_K, P_K, one workspace per wavefront, then the two index tables
+    double *Ik = reinterpret_cast<double *>(lds);
+    double *Pk = Ik + A.ik_elems;
+    double *t = Pk + A.pk_elems + size_t(wave) * A.max_slots;
+    uint16_t *mmap = reinterpret_cast<uint16_t *>(Pk + A.pk_elems + size_t(kScLocalWaves) * A.max_slots);
+    uint16_t *uvmap = mmap + ((A.n_m + 7) & ~int64_t(7));            // v -> slot while P_K is built, then u -> row
+    const int64_t r = blockIdx.x;
+    const int64_t a = E.root_knode[r];
+    const int64_t nu0 = A.nu_ptr[a];
+    const int ns = int(A.nu_ptr[a + 1] - nu0);
+    const int64_t n0 = A.i_ptr0[a];
+    const int nrows = int(A.i_ptr0[a + 1] - n0);
+    const int64_t mu0 = A.mu_ptr[r];
+    const int nm = int(A.mu_ptr[r + 1] - mu0);
+
+    for (int64_t x = threadIdx.x; x < (A.n_v + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(uvmap)[x] = 0xFFFFFFFFu;
+    for (int x = threadIdx.x; x < nrows * ns; x += nthreads) Ik[x] = 0.0;
+    for (int x = threadIdx.x; x < ns * nm; x += nthreads) Pk[x] = 0.0;
+    __syncthreads();
+    for (int s = threadIdx.x; s < ns; s += nthreads) uvmap[A.nu_list[nu0 + s]] = uint16_t(s);
+    for (int j = threadIdx.x; j < nm; j += nthreads) mmap[A.mu_list[mu0 + j]] = uint16_t(j);
+    __syncthreads();
+    // I_K: one wavefront per u row; P_K: one wavefront per m of K, keeping the v that occur under K
+    for (int row = wave; row < nrows; row += kScLocalWaves) {
+        const int64_t l0 = A.i_ptr1[n0 + row], l1 = A.i_ptr1[n0 + row + 1];
+        for (int64_t l = l0 + lane; l < l1; l += 64) Ik[row * ns + A.i_slot[l]] = A.i_vals[l];
+    }
+    for (int j = wave; j < nm; j += kScLocalWaves) {
+        const int32_t pn = A.p_node_of_m[A.mu_list[mu0 + j]];
+        const int64_t p0 = A.p_ptr0[pn], p1 = A.p_ptr0[pn + 1];
+        for (int64_t p = p0 + lane; p < p1; p += 64) {
+            const uint16_t s = uvmap[A.p_idx1[p]];
+            if (s != kNoSlot) Pk[int(s) * nm + j] = A.p_vals[p];
+        }
+    }
+    __syncthreads();
+    for (int64_t x = threadIdx.x; x < (A.n_u + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(uvmap)[x] = 0xFFFFFFFFu;
+    __syncthreads();
+    for (int row = threadIdx.x; row < nrows; row += nthreads) uvmap[A.i_idx1[n0 + row]] = uint16_t(row);
+    __syncthreads();
+
+    for (int64_t node = E.ptr0[r] + wave; node < E.ptr0[r + 1]; node += kScLocalWaves) {
+        for (int s = lane; s < ns; s += 64) t[s] = 0.0;
+        const int64_t b = E.cnode[node];
+        const int64_t c0 = A.c_ptr0[b], c1 = A.c_ptr0[b + 1];
+        // t = c_i . I_K : lanes over the slots, the matching entries of C[i,:] one after the other
+        for (int64_t base = c0; base < c1; base += 64) {
+            const int64_t c = base + lane;
+            uint16_t row = kNoSlot;
+            double cv = 0.0;
+            if (c < c1) { row = uvmap[A.c_idx1[c]]; cv = A.c_vals[c]; }
+            uint64_t bal = __ballot(row != kNoSlot);
+            while (bal) {
+                const int bit = __ffsll((unsigned long long)bal) - 1;
+                bal &= bal - 1;
+                const int rr = __shfl(int(row), bit, 64);
+                const double cc = __shfl(cv, bit, 64);
+                const double *ik = Ik + rr * ns;
+                for (int s = lane; s < ns; s += 64) t[s] = fma(ik[s], cc, t[s]);      // each lane owns its slots
+            }
+        }
+        wave_sync();
+        const double lv = E.lval[node];
+        for (int64_t q = E.ptr1[node] + lane; q < E.ptr1[node + 1]; q += 64) {
+            const double *pk = Pk + mmap[E.idx2[q]];
+            double acc = 0.0;
+            for (int s = 0; s < ns; ++s) acc = fma(t[s], pk[s * nm], acc);
+            out[q] = acc * lv;
+        }
+        wave_sync();
+    }
+}
+
 // ---- host side -------------------------------------------------------------------------------
 
 // index of the level-`level` ancestor of every leaf of a CSF tensor
@@ -356,6 +494,11 @@ static ScArgs make_args(const conststn_plan_s *plan) {
     A.l_knode = plan->sc_l_knode.p;
     A.l_cnode = plan->sc_l_cnode.p;
     A.l_vals = L ? L->vals.p : nullptr;
+    A.mu_ptr = plan->sc_mu_ptr.p;
+    A.mu_list = plan->sc_mu_list.p;
+    A.n_u = I->dims[I->mode_order[1]];
+    A.ik_elems = plan->sc_ik_elems;
+    A.pk_elems = plan->sc_pk_elems;
     return A;
 }
 
@@ -401,6 +544,7 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
     CST_HIP(hipGetLastError());
 
     // distinct v under every K: the level-1 nodes of I re-sorted as (K > v > u)
+    std::vector<int64_t> h_nu_ptr;
     {
         conststn_csf_s kvu;
         DevBuf<int32_t> cK, cu;
@@ -423,7 +567,8 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
         CST_HIP(hipMemcpy(plan->sc_nu_ptr.p, kvu.ptr[0].p, size_t(kvu.nodes[0] + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice));
         if (kvu.nodes[1])
             CST_HIP(hipMemcpy(plan->sc_nu_list.p, kvu.idx[1].p, size_t(kvu.nodes[1]) * sizeof(int32_t), hipMemcpyDeviceToDevice));
-        std::vector<int64_t> h(size_t(kvu.nodes[0] + 1));
+        std::vector<int64_t> &h = h_nu_ptr;
+        h.resize(size_t(kvu.nodes[0] + 1));
         CST_HIP(hipMemcpy(h.data(), kvu.ptr[0].p, h.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
         int64_t mx = 1;
         for (size_t a = 0; a + 1 < h.size(); ++a) mx = std::max(mx, h[a + 1] - h[a]);
@@ -513,7 +658,7 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
     CST_HIP(hipGetLastError());
     CST_HIP(hipStreamSynchronize(st));
 
-    // numeric pass: LDS = v -> slot table + one workspace per wavefront
+    // numeric pass, general form: LDS = v -> slot table + one workspace per wavefront
     plan->sc_map_bytes = int(((n_v + 1) / 2 * 4 + 15) / 16 * 16);
     const size_t lds = size_t(plan->sc_map_bytes) + size_t(kScWaves) * size_t(plan->sc_max_slots) * sizeof(double);
     if (lds > 160 * 1024) {
@@ -522,6 +667,49 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
     }
     plan->sc_lds_bytes = int(lds);
     CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+
+    // block-local form: the m under every root of E, and whether every K's dense blocks fit LDS
+    plan->sc_local = false;
+    CST_TRY(plan->sc_mu_ptr.alloc(size_t(roots + 1)));
+    if (roots > 0 && n_m <= 65534) {
+        DevBuf<int64_t> mcount;
+        CST_TRY(mcount.alloc(size_t(roots)));
+        const size_t mset_bytes = size_t((n_m + 31) >> 5) * 4;
+        spchain3_root_mset_kernel<<<dim3(unsigned(roots)), 256, mset_bytes, st>>>(O, n_m, 0, mcount.p, nullptr, nullptr);
+        CST_HIP(hipGetLastError());
+        int64_t total_m = 0;
+        CST_TRY(exscan(mcount.p, plan->sc_mu_ptr.p, roots, &total_m));
+        CST_HIP(hipMemcpy(plan->sc_mu_ptr.p + roots, &total_m, sizeof(int64_t), hipMemcpyHostToDevice));
+        CST_TRY(plan->sc_mu_list.alloc(size_t(total_m)));
+        spchain3_root_mset_kernel<<<dim3(unsigned(roots)), 256, mset_bytes, st>>>(O, n_m, 1, nullptr, plan->sc_mu_ptr.p, plan->sc_mu_list.p);
+        CST_HIP(hipGetLastError());
+        std::vector<int64_t> h_mu(size_t(roots + 1)), h_iptr(size_t(I->nodes[0] + 1));
+        std::vector<int32_t> h_rk(static_cast<size_t>(roots), 0);
+        CST_HIP(hipMemcpy(h_mu.data(), plan->sc_mu_ptr.p, h_mu.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+        CST_HIP(hipMemcpy(h_iptr.data(), I->ptr[0].p, h_iptr.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+        CST_HIP(hipMemcpy(h_rk.data(), plan->sc_e_root_knode.p, h_rk.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+        int64_t ik = 1, pk = 1, rows_max = 1;
+        for (int64_t r = 0; r < roots; ++r) {
+            const int64_t a = h_rk[size_t(r)];
+            const int64_t ns = h_nu_ptr[size_t(a + 1)] - h_nu_ptr[size_t(a)];
+            const int64_t rows = h_iptr[size_t(a + 1)] - h_iptr[size_t(a)];
+            const int64_t nm = h_mu[size_t(r + 1)] - h_mu[size_t(r)];
+            ik = std::max(ik, rows * ns);
+            pk = std::max(pk, ns * nm);
+            rows_max = std::max(rows_max, rows);
+        }
+        const int64_t uv = std::max(n_u, n_v);
+        const int64_t bytes = 8 * (ik + pk + int64_t(kScLocalWaves) * plan->sc_max_slots) + 2 * ((n_m + 7) & ~int64_t(7)) + 4 * ((uv + 1) / 2);
+        const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 72) * 1024;     // two workgroups per compute unit
+        if (rows_max <= 65534 && bytes <= budget && bytes <= 160 * 1024 && env_int("CONSTSTN_SPCHAIN3_FORM", 1) == 1) {
+            plan->sc_local = true;
+            plan->sc_ik_elems = int(ik);
+            plan->sc_pk_elems = int(pk);
+            plan->sc_local_lds = int(bytes);
+            CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_local_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes)));
+        }
+    }
+    CST_HIP(hipStreamSynchronize(st));
     plan->out_rows = nnz;
     plan->row_elems = 1;
     return CONSTSTN_OK;
@@ -532,7 +720,10 @@ conststn_status launch_spchain3(const conststn_plan_s *plan, double *out, hipStr
     const ScOut O = make_out(plan);
     ProfScope prof(plan, stream);
     if (O.roots == 0) return CONSTSTN_OK;
-    spchain3_kernel<<<dim3(unsigned(O.roots)), 64 * kScWaves, size_t(plan->sc_lds_bytes), stream>>>(A, O, out, plan->sc_map_bytes);
+    if (plan->sc_local)
+        spchain3_local_kernel<<<dim3(unsigned(O.roots)), 64 * kScLocalWaves, size_t(plan->sc_local_lds), stream>>>(A, O, out);
+    else
+        spchain3_kernel<<<dim3(unsigned(O.roots)), 64 * kScWaves, size_t(plan->sc_lds_bytes), stream>>>(A, O, out, plan->sc_map_bytes);
     CST_HIP(hipGetLastError());
     return CONSTSTN_OK;
 }

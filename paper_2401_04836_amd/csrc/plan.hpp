@@ -182,6 +182,10 @@ struct conststn_plan_s {
     cst::DevBuf<double> sc_e_lval;         // per (K,i) node: value of L (1 without a filter)
     cst::DevBuf<int32_t> sc_e_root_knode;  // per root of the result: K node of X
     int sc_max_slots = 0, sc_map_bytes = 0, sc_lds_bytes = 0;
+    cst::DevBuf<int64_t> sc_mu_ptr;        // [roots of the result + 1] into sc_mu_list
+    cst::DevBuf<int32_t> sc_mu_list;       // distinct m under each root of the result, ascending
+    bool sc_local = false;                 // every K's dense blocks fit LDS: block-local numeric kernel
+    int sc_ik_elems = 0, sc_pk_elems = 0, sc_local_lds = 0;
 
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;

@@ -49,3 +49,10 @@ def ttmc3_for(levels):
             "Y[%s,r,s] = T[%s,%s,s] * %s[%s,r] | %s,%s,r,s") % (
         a, b, a, b, c, fc, c, a, b, c, a, a, b, fb, b, a, b)
     return text, ("X", fc, fb)
+
+
+# Sec. 5.1: the three-index integral transformation, every operand sparse, sparse result.
+# I stored K > u > v, C stored i > u, P stored m > v, L stored K > i.
+SPCHAIN3 = "T[K,i,v] = I[K,u,v] * C[i,u] | K,i,u,v ; E[K,i,m] = T[K,i,v] * P[m,v] | K,i,m,v"
+SPCHAIN3_RESTRICTED = ("T[K,i,v] = I[K,u,v] * C[i,u] | K,i,u,v ; F[K,i,v] = T[K,i,v] * L[K,i] | K,i,v ; "
+                       "E[K,i,m] = F[K,i,v] * P[m,v] | K,i,m,v")

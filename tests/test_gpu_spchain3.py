@@ -1,6 +1,8 @@
 """Chain of three sparse tensors with a sparse result (Sec. 5.1, both forms) on the GPU against
 the dense-slice reference: the structure of the result must be identical (it is index work), the
 values within the tolerance of every other contraction."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -26,16 +28,24 @@ def _csf(t, mode_order):
     return cst.build_csf([c.cuda() for c in t.coords], t.vals.cuda(), t.dims, mode_order)
 
 
-def _run(I, C, P, L=None):
-    """Returns (coords of E as three host arrays, values, plan description)."""
+def _run(I, C, P, L=None, kernel=None):
+    """Returns (coords of E as three host arrays, values, plan description).  kernel: None = the
+    plan's choice, "general" = the form without dense blocks, "block-local" = expect that form."""
     hI, hC, hP = _csf(I, [0, 1, 2]), _csf(C, [1, 0]), _csf(P, [1, 0])
-    if L is None:
-        pl = cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)])
-    else:
-        hL = _csf(L, [0, 1])
-        pl = cst.plan(RESTRICTED, [("I", hI), ("C", hC), ("L", hL), ("P", hP)])
+    if kernel == "general":
+        os.environ["CONSTSTN_SPCHAIN3_FORM"] = "2"
+    try:
+        if L is None:
+            pl = cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)])
+        else:
+            hL = _csf(L, [0, 1])
+            pl = cst.plan(RESTRICTED, [("I", hI), ("C", hC), ("L", hL), ("P", hP)])
+    finally:
+        os.environ.pop("CONSTSTN_SPCHAIN3_FORM", None)
     desc = pl.describe()
     assert "family=spchain3" in desc, desc
+    if kernel is not None:
+        assert ("kernel=" + kernel) in desc, desc
     vals = cst.execute(pl, [])
     again = cst.execute(pl, [])
     torch.cuda.synchronize()
@@ -106,16 +116,17 @@ def test_small_lattice_both_forms():
     I, C, P, L = (wl.sparse[k] for k in "ICPL")
     _say("5 x 5 lattice: dims %s, nnz I %d C %d P %d L %d" % (dims, I.nnz, C.nnz, P.nnz, L.nnz))
     Ks = range(dims[0])
-    coords, vals, desc = _run(I, C, P)
-    ref = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=Ks)
-    err = _compare(coords, vals, ref, dims, Ks)
-    _say("  unrestricted: %s nnz(E) %d rel err %.3e" % (desc.split("|")[0], vals.size, err))
-    assert err <= TOL
-    coords, vals, desc = _run(I, C, P, L)
-    ref = spsp.chain3(_np(I), _np(C), _np(P), dims, _np(L), K_values=Ks)
-    err = _compare(coords, vals, ref, dims, Ks)
-    _say("  restricted:   nnz(E) %d rel err %.3e" % (vals.size, err))
-    assert err <= TOL
+    ref_u = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=Ks)
+    ref_r = spsp.chain3(_np(I), _np(C), _np(P), dims, _np(L), K_values=Ks)
+    for kernel in ("block-local", "general"):
+        coords, vals, desc = _run(I, C, P, kernel=kernel)
+        err = _compare(coords, vals, ref_u, dims, Ks)
+        _say("  unrestricted: %s nnz(E) %d rel err %.3e" % (desc.split("T:")[0], vals.size, err))
+        assert err <= TOL
+        coords, vals, desc = _run(I, C, P, L, kernel=kernel)
+        err = _compare(coords, vals, ref_r, dims, Ks)
+        _say("  restricted:   nnz(E) %d rel err %.3e" % (vals.size, err))
+        assert err <= TOL
 
 
 def test_scattered_inputs_ragged_extents_and_missing_indices():
@@ -137,11 +148,27 @@ def test_long_lists_span_several_wavefront_passes():
     dims = (6, 9, 300, 400)
     I, C, P, L = _scattered(4103, dims, 60000, 900, 9000, 30)
     Ks = range(dims[0])
-    coords, vals, _ = _run(I, C, P)
+    coords, vals, desc = _run(I, C, P, kernel="general")          # blocks of 300 x 300 do not fit LDS
     ref = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=Ks)
     err = _compare(coords, vals, ref, dims, Ks)
     _say("long lists: nnz(E) %d rel err %.3e" % (vals.size, err))
     assert err <= TOL
+
+
+def test_block_local_with_more_slots_and_entries_than_a_wavefront():
+    # K-local blocks with > 64 v slots, > 64 u rows and C rows of > 64 entries, still within LDS
+    dims = (5, 7, 70, 40)
+    I, C, P, L = _scattered(4106, dims, 9000, 480, 1500, 20)
+    Ks = range(dims[0])
+    ref = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=Ks)
+    got = {}
+    for kernel in ("block-local", "general"):
+        coords, vals, _ = _run(I, C, P, kernel=kernel)
+        err = _compare(coords, vals, ref, dims, Ks)
+        _say("dense blocks, %s: nnz(E) %d rel err %.3e" % (kernel, vals.size, err))
+        assert err <= TOL
+        got[kernel] = vals
+    np.testing.assert_array_equal(got["block-local"], got["general"])      # same terms in the same order
 
 
 def test_empty_result_and_empty_operands():
@@ -168,7 +195,7 @@ def test_medium_lattice_sampled_slices():
     _say("12 x 12 lattice: dims %s, nnz I %d C %d P %d L %d" % (dims, I.nnz, C.nnz, P.nnz, L.nnz))
     Ks = sorted(set(np.random.default_rng(1).integers(0, dims[0], 40).tolist()) | {0, dims[0] - 1})
     for form, Lx in (("unrestricted", None), ("restricted", L)):
-        coords, vals, _ = _run(I, C, P, Lx)
+        coords, vals, _ = _run(I, C, P, Lx, kernel="block-local")
         ref = spsp.chain3(_np(I), _np(C), _np(P), dims, _np(Lx) if Lx is not None else None, K_values=Ks)
         err = _compare(coords, vals, ref, dims, Ks)
         _say("  %s: nnz(E) %d, %d sampled K, rel err %.3e" % (form, vals.size, len(Ks), err))

@@ -1,11 +1,13 @@
-"""The five benchmark configurations and reduced copies of each.
+"""The five benchmark configurations and reduced copies of each, plus configuration 6: the
+sparse three-index integral transformation of Sec. 5.1 on lattice sparse maps (a stand-in for
+the quantum-chemistry inputs, which are not public).
 
 CONFIGS[c] are the full sizes; SMALL[c] keep the same recipe (distribution
 family, skew, rank) at sizes a CPU loop finishes in seconds, chosen so that
 slices, fibers and tiles are ragged (not multiples of any kernel tile).
 Seeds: BASE_SEED + config number.
 """
-from .generators import make_ttmc3, make_ttmc4, make_mttkrp3, make_sptn3
+from .generators import make_ttmc3, make_ttmc4, make_mttkrp3, make_sptn3, make_lattice_chain
 
 BASE_SEED = 20240104
 
@@ -49,7 +51,15 @@ def _c5(device, **kw):
                       compact=True)
 
 
-CONFIGS = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5}
+def _c6(device, **kw):
+    # 32 x 32 atoms, 3 orbitals and 14 fitting functions per atom: I 14336 x 3072 x 3072 with ~8 M
+    # nonzeros, result E with ~53 M (unrestricted) / ~40 M (restricted) structural nonzeros
+    return make_lattice_chain("c6", BASE_SEED + 6, kw.get("side", 32), kw.get("n_ao", 3), kw.get("n_df", 14),
+                              kw.get("r_int", 2.0), kw.get("r_mo", 2.0), kw.get("r_pao", 2.0),
+                              kw.get("r_filter", 3.0), device=device)
+
+
+CONFIGS = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5, 6: _c6}
 
 # reduced copies: same recipe, sizes for CPU-second oracle runs
 SMALL = {
@@ -58,11 +68,12 @@ SMALL = {
     3: dict(dims=(37, 1511, 1499, 211), nnz=60_007, ranks=(16, 16, 16)),
     4: dict(dims=(60, 80, 40, 60, 40), nblocks=4, n_sel_u=6, n_sel_w=7),
     5: dict(dims=(20_011, 19_997, 2503), nnz=200_003, ranks=(64, 64)),
+    6: dict(side=5, n_df=6, r_int=1.5, r_pao=1.5, r_filter=2.5),
 }
 
 
 def make(cid, device="cpu", small=False, **overrides):
-    """Build configuration `cid` (1..5); small=True gives the reduced copy."""
+    """Build configuration `cid` (1..6); small=True gives the reduced copy."""
     kw = dict(SMALL[cid]) if small else {}
     kw.update(overrides)
     return CONFIGS[cid](device, **kw)
