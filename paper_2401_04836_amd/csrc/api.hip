@@ -384,8 +384,12 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
             snprintf(b, sizeof(b), " kernel=baseline");
         plan->description += b;
     }
-    if (plan->family == FAM_SPCHAIN3)
-        plan->description += plan->sc_local ? " kernel=block-local" : " kernel=general";
+    if (plan->family == FAM_SPCHAIN3) {
+        char b[96];
+        if (plan->sc_local) snprintf(b, sizeof(b), " kernel=block-local lds %d", plan->sc_local_lds);
+        else snprintf(b, sizeof(b), " kernel=general lds %d", plan->sc_lds_bytes);
+        plan->description += b;
+    }
     for (size_t p = 0; p + 1 < plan->sched.stmts.size(); ++p) {
         char b[128];
         snprintf(b, sizeof(b), " %s:order%d", plan->sched.stmts[p].out.name.c_str(), plan->sched.stmts[p].reduced_order);

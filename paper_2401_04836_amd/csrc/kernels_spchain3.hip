@@ -89,6 +89,13 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
+// value of `v` in lane `l`, the same l in every lane (a scalar read, not a permute through LDS)
+__device__ __forceinline__ double lane_value(double v, int l) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ int wave_sum(int x) {
     for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
     return x;
@@ -340,17 +347,71 @@ spchain3_root_mset_kernel(ScOut E, int64_t n_m, int mode, int64_t *count, const 
 
 constexpr int kScLocalWaves = 8;
 
+// LDS layout of the block-local kernel, in bytes from the start (set up by the plan)
+struct ScLocalLds {
+    int pk, tk, lval, rowptr, poff, pp0, c0, clen, qoff, mmap, uvmap, total;
+    int ns_pad;                              // row stride of T_K (doubles)
+};
+
+typedef double sc_v4d __attribute__((ext_vector_type(4)));
+
+// largest x in [0, n) with arr[x] <= key (arr ascending, arr[0] <= key)
+__device__ __forceinline__ int last_not_above(const int32_t *arr, int n, int32_t key) {
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (arr[mid] <= key) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// exclusive prefix sums of len[0..n) into off[0..n], by one wavefront
+__device__ __forceinline__ void wave_exscan(const int32_t *len, int32_t *off, int n, int lane) {
+    int32_t carry = 0;
+    for (int base = 0; base < n; base += 64) {
+        const int x = base + lane;
+        const int32_t v = x < n ? len[x] : 0;
+        int32_t incl = v;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int32_t y = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += y;
+        }
+        if (x < n) off[x] = carry + incl - v;
+        carry += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) off[n] = carry;
+}
+
+// One workgroup per K of E.  Phases (a barrier between each):
+//   1  clear the tables and the dense blocks; fetch the row pointers of I[K], of P's rows for the m
+//      of K, and per (K,i) node the range of C[i,:], of its leaves in E and the value of L
+//   2  v -> slot table; prefix sums of P's row lengths
+//   3  I_K and P_K filled, one thread per stored entry
+//   4  u -> row table (in the space of the v -> slot table)
+//   5  T_K[node, slot] = c_i . I_K, one wavefront per node, the matching entries of C[i,:] in order;
+//      pos[node, m of K] = leaf of E[K,i,m] within the node (in the space of I_K once it is dead)
+//   6  E_K = T_K . P_K on the fp64 matrix cores (v_mfma_f64_16x16x4): 16 nodes x 16 m per tile,
+//      the slots in steps of 4; every element that is a stored leaf goes to its place in `out`.
 __global__ void __launch_bounds__(64 * kScLocalWaves)
-spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out) {
+spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O) {
     extern __shared__ unsigned char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nthreads = 64 * kScLocalWaves;
-    // LDS: I_K, P_K, one workspace per wavefront, then the two index tables
     double *Ik = reinterpret_cast<double *>(lds);
-    double *Pk = Ik + A.ik_elems;
-    double *t = Pk + A.pk_elems + size_t(wave) * A.max_slots;
-    uint16_t *mmap = reinterpret_cast<uint16_t *>(Pk + A.pk_elems + size_t(kScLocalWaves) * A.max_slots);
-    uint16_t *uvmap = mmap + ((A.n_m + 7) & ~int64_t(7));            // v -> slot while P_K is built, then u -> row
+    uint16_t *pos = reinterpret_cast<uint16_t *>(lds);                   // after phase 5's producer: over I_K
+    double *Pk = reinterpret_cast<double *>(lds + O.pk);
+    double *Tk = reinterpret_cast<double *>(lds + O.tk);
+    double *lval = reinterpret_cast<double *>(lds + O.lval);
+    int32_t *rowptr = reinterpret_cast<int32_t *>(lds + O.rowptr);       // leaves of K before each u row
+    int32_t *poff = reinterpret_cast<int32_t *>(lds + O.poff);           // entries of P before each m of K; lengths first
+    int32_t *pp0 = reinterpret_cast<int32_t *>(lds + O.pp0);             // first entry of P's row of each m of K
+    int32_t *c0s = reinterpret_cast<int32_t *>(lds + O.c0);              // per node: first entry of C[i,:], its length,
+    int32_t *clen = reinterpret_cast<int32_t *>(lds + O.clen);           //           leaves of E before the node
+    int32_t *qoff = reinterpret_cast<int32_t *>(lds + O.qoff);
+    uint16_t *mmap = reinterpret_cast<uint16_t *>(lds + O.mmap);
+    uint16_t *uvmap = reinterpret_cast<uint16_t *>(lds + O.uvmap);      // v -> slot while P_K is built, then u -> row
+    const int tstride = O.ns_pad;
+
     const int64_t r = blockIdx.x;
     const int64_t a = E.root_knode[r];
     const int64_t nu0 = A.nu_ptr[a];
@@ -359,62 +420,136 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out) {
     const int nrows = int(A.i_ptr0[a + 1] - n0);
     const int64_t mu0 = A.mu_ptr[r];
     const int nm = int(A.mu_ptr[r + 1] - mu0);
+    const int64_t e0 = E.ptr0[r];
+    const int nn = int(E.ptr0[r + 1] - e0);
+    const int64_t li0 = A.i_ptr1[n0];
+    const int nleaves = int(A.i_ptr1[n0 + nrows] - li0);
+    const int64_t q0 = E.ptr1[e0];
 
+    // phase 1
     for (int64_t x = threadIdx.x; x < (A.n_v + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(uvmap)[x] = 0xFFFFFFFFu;
     for (int x = threadIdx.x; x < nrows * ns; x += nthreads) Ik[x] = 0.0;
     for (int x = threadIdx.x; x < ns * nm; x += nthreads) Pk[x] = 0.0;
-    __syncthreads();
-    for (int s = threadIdx.x; s < ns; s += nthreads) uvmap[A.nu_list[nu0 + s]] = uint16_t(s);
-    for (int j = threadIdx.x; j < nm; j += nthreads) mmap[A.mu_list[mu0 + j]] = uint16_t(j);
-    __syncthreads();
-    // I_K: one wavefront per u row; P_K: one wavefront per m of K, keeping the v that occur under K
-    for (int row = wave; row < nrows; row += kScLocalWaves) {
-        const int64_t l0 = A.i_ptr1[n0 + row], l1 = A.i_ptr1[n0 + row + 1];
-        for (int64_t l = l0 + lane; l < l1; l += 64) Ik[row * ns + A.i_slot[l]] = A.i_vals[l];
+    for (int x = threadIdx.x; x <= nrows; x += nthreads) rowptr[x] = int32_t(A.i_ptr1[n0 + x] - li0);
+    for (int j = threadIdx.x; j < nm; j += nthreads) {
+        const int32_t m = A.mu_list[mu0 + j];
+        mmap[m] = uint16_t(j);
+        const int32_t pn = A.p_node_of_m[m];
+        const int64_t b0 = A.p_ptr0[pn];
+        pp0[j] = int32_t(b0);
+        poff[j] = int32_t(A.p_ptr0[pn + 1] - b0);
     }
-    for (int j = wave; j < nm; j += kScLocalWaves) {
-        const int32_t pn = A.p_node_of_m[A.mu_list[mu0 + j]];
-        const int64_t p0 = A.p_ptr0[pn], p1 = A.p_ptr0[pn + 1];
-        for (int64_t p = p0 + lane; p < p1; p += 64) {
-            const uint16_t s = uvmap[A.p_idx1[p]];
-            if (s != kNoSlot) Pk[int(s) * nm + j] = A.p_vals[p];
+    for (int x = threadIdx.x; x <= nn; x += nthreads) {
+        qoff[x] = int32_t(E.ptr1[e0 + x] - q0);
+        if (x < nn) {
+            const int64_t b = E.cnode[e0 + x];
+            const int64_t b0 = A.c_ptr0[b];
+            c0s[x] = int32_t(b0);
+            clen[x] = int32_t(A.c_ptr0[b + 1] - b0);
+            lval[x] = E.lval[e0 + x];
         }
     }
     __syncthreads();
+    // phase 2
+    for (int s = threadIdx.x; s < ns; s += nthreads) uvmap[A.nu_list[nu0 + s]] = uint16_t(s);
+    if (wave == 0) wave_exscan(poff, poff, nm, lane);
+    __syncthreads();
+    // phase 3
+    for (int l = threadIdx.x; l < nleaves; l += nthreads) {
+        const int row = last_not_above(rowptr, nrows, l);
+        Ik[row * ns + A.i_slot[li0 + l]] = A.i_vals[li0 + l];
+    }
+    const int ptotal = poff[nm];
+    for (int e = threadIdx.x; e < ptotal; e += nthreads) {
+        const int j = last_not_above(poff, nm, e);
+        const int64_t p = int64_t(pp0[j]) + (e - poff[j]);
+        const uint16_t s = uvmap[A.p_idx1[p]];
+        if (s != kNoSlot) Pk[int(s) * nm + j] = A.p_vals[p];
+    }
+    __syncthreads();
+    // phase 4
     for (int64_t x = threadIdx.x; x < (A.n_u + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(uvmap)[x] = 0xFFFFFFFFu;
     __syncthreads();
     for (int row = threadIdx.x; row < nrows; row += nthreads) uvmap[A.i_idx1[n0 + row]] = uint16_t(row);
     __syncthreads();
-
-    for (int64_t node = E.ptr0[r] + wave; node < E.ptr0[r + 1]; node += kScLocalWaves) {
-        for (int s = lane; s < ns; s += 64) t[s] = 0.0;
-        const int64_t b = E.cnode[node];
-        const int64_t c0 = A.c_ptr0[b], c1 = A.c_ptr0[b + 1];
-        // t = c_i . I_K : lanes over the slots, the matching entries of C[i,:] one after the other
-        for (int64_t base = c0; base < c1; base += 64) {
-            const int64_t c = base + lane;
-            uint16_t row = kNoSlot;
-            double cv = 0.0;
-            if (c < c1) { row = uvmap[A.c_idx1[c]]; cv = A.c_vals[c]; }
-            uint64_t bal = __ballot(row != kNoSlot);
-            while (bal) {
-                const int bit = __ffsll((unsigned long long)bal) - 1;
-                bal &= bal - 1;
-                const int rr = __shfl(int(row), bit, 64);
-                const double cc = __shfl(cv, bit, 64);
-                const double *ik = Ik + rr * ns;
-                for (int s = lane; s < ns; s += 64) t[s] = fma(ik[s], cc, t[s]);      // each lane owns its slots
+    // phase 5: producer
+    for (int x = wave; x < nn; x += kScLocalWaves) {
+        const int64_t c0 = c0s[x], c1 = c0 + clen[x];
+        double *t = Tk + x * tstride;
+        if (ns <= 64) {
+            const int my = lane < ns ? lane : 0;
+            double tacc = 0.0;
+            for (int64_t base = c0; base < c1; base += 64) {
+                const int64_t c = base + lane;
+                uint16_t row = kNoSlot;
+                double cv = 0.0;
+                if (c < c1) { row = uvmap[A.c_idx1[c]]; cv = A.c_vals[c]; }
+                uint64_t bal = __ballot(row != kNoSlot);
+                while (bal) {
+                    const int bit = __ffsll((unsigned long long)bal) - 1;
+                    bal &= bal - 1;
+                    const int rr = __builtin_amdgcn_readlane(int(row), bit);
+                    const double cc = lane_value(cv, bit);
+                    tacc = fma(Ik[rr * ns + my], cc, tacc);
+                }
+            }
+            if (lane < ns) t[lane] = tacc;
+        } else {
+            for (int s = lane; s < ns; s += 64) t[s] = 0.0;
+            for (int64_t base = c0; base < c1; base += 64) {
+                const int64_t c = base + lane;
+                uint16_t row = kNoSlot;
+                double cv = 0.0;
+                if (c < c1) { row = uvmap[A.c_idx1[c]]; cv = A.c_vals[c]; }
+                uint64_t bal = __ballot(row != kNoSlot);
+                while (bal) {
+                    const int bit = __ffsll((unsigned long long)bal) - 1;
+                    bal &= bal - 1;
+                    const int rr = __builtin_amdgcn_readlane(int(row), bit);
+                    const double cc = lane_value(cv, bit);
+                    const double *ik = Ik + rr * ns;
+                    for (int s = lane; s < ns; s += 64) t[s] = fma(ik[s], cc, t[s]);  // each lane owns its slots
+                }
             }
         }
-        wave_sync();
-        const double lv = E.lval[node];
-        for (int64_t q = E.ptr1[node] + lane; q < E.ptr1[node + 1]; q += 64) {
-            const double *pk = Pk + mmap[E.idx2[q]];
-            double acc = 0.0;
-            for (int s = 0; s < ns; ++s) acc = fma(t[s], pk[s * nm], acc);
-            out[q] = acc * lv;
+    }
+    __syncthreads();
+    // I_K is dead: the leaf positions take its place
+    for (int x = threadIdx.x; x < (nn * nm + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(pos)[x] = 0xFFFFFFFFu;
+    __syncthreads();
+    const int eleaves = qoff[nn];
+    for (int q = threadIdx.x; q < eleaves; q += nthreads) {
+        const int x = last_not_above(qoff, nn, q);
+        pos[x * nm + mmap[E.idx2[q0 + q]]] = uint16_t(q - qoff[x]);
+    }
+    __syncthreads();
+    // phase 6: E_K = T_K . P_K, tiles of 16 nodes x 16 m
+    const int tiles_m = (nm + 15) >> 4, tiles = ((nn + 15) >> 4) * tiles_m;
+    const int li = lane & 15, lk = lane >> 4;
+    for (int tile = wave; tile < tiles; tile += kScLocalWaves) {
+        const int x0 = (tile / tiles_m) << 4, j0 = (tile % tiles_m) << 4;
+        const bool xa = x0 + li < nn, jb = j0 + li < nm;
+        const double *trow = Tk + (xa ? x0 + li : 0) * tstride;
+        const double *pcol = Pk + (jb ? j0 + li : 0);
+        sc_v4d acc = {0.0, 0.0, 0.0, 0.0};
+        for (int k0 = 0; k0 < ns; k0 += 4) {
+            const int k = k0 + lk;
+            const bool kk = k < ns;
+            const double av = (xa && kk) ? trow[kk ? k : 0] : 0.0;
+            const double bv = (jb && kk) ? pcol[(kk ? k : 0) * nm] : 0.0;
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
         }
-        wave_sync();
+        // lane holds E_K[x0 + lk + 4v][j0 + li]
+        if (jb) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int x = x0 + lk + 4 * v;
+                if (x < nn) {
+                    const uint16_t at = pos[x * nm + j0 + li];
+                    if (at != kNoSlot) out[q0 + qoff[x] + at] = acc[v] * lval[x];
+                }
+            }
+        }
     }
 }
 
@@ -688,7 +823,9 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
         CST_HIP(hipMemcpy(h_mu.data(), plan->sc_mu_ptr.p, h_mu.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
         CST_HIP(hipMemcpy(h_iptr.data(), I->ptr[0].p, h_iptr.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
         CST_HIP(hipMemcpy(h_rk.data(), plan->sc_e_root_knode.p, h_rk.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
-        int64_t ik = 1, pk = 1, rows_max = 1;
+        std::vector<int64_t> h_ep(size_t(roots + 1));
+        CST_HIP(hipMemcpy(h_ep.data(), E->ptr[0].p, h_ep.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+        int64_t ik = 1, pk = 1, rows_max = 1, nm_max = 1, nn_max = 1;
         for (int64_t r = 0; r < roots; ++r) {
             const int64_t a = h_rk[size_t(r)];
             const int64_t ns = h_nu_ptr[size_t(a + 1)] - h_nu_ptr[size_t(a)];
@@ -697,15 +834,44 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
             ik = std::max(ik, rows * ns);
             pk = std::max(pk, ns * nm);
             rows_max = std::max(rows_max, rows);
+            nm_max = std::max(nm_max, nm);
+            nn_max = std::max(nn_max, h_ep[size_t(r + 1)] - h_ep[size_t(r)]);
         }
         const int64_t uv = std::max(n_u, n_v);
-        const int64_t bytes = 8 * (ik + pk + int64_t(kScLocalWaves) * plan->sc_max_slots) + 2 * ((n_m + 7) & ~int64_t(7)) + 4 * ((uv + 1) / 2);
-        const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 72) * 1024;     // two workgroups per compute unit
-        if (rows_max <= 65534 && bytes <= budget && bytes <= 160 * 1024 && env_int("CONSTSTN_SPCHAIN3_FORM", 1) == 1) {
+        auto up16 = [](int64_t x) { return (x + 15) / 16 * 16; };
+        int64_t at = 0;
+        int64_t o_pk, o_t, o_lval, o_rowptr, o_poff, o_pp0, o_c0, o_clen, o_qoff, o_mmap, o_uvmap;
+        int64_t posb = 2;                                       // leaf positions (2 bytes each) reuse the space of I_K
+        for (int64_t r = 0; r < roots; ++r)
+            posb = std::max(posb, 2 * (h_ep[size_t(r + 1)] - h_ep[size_t(r)]) * (h_mu[size_t(r + 1)] - h_mu[size_t(r)]) + 4);
+        const int64_t ns_pad = plan->sc_max_slots | 1;          // odd row stride: the 16 rows of a tile fall in different banks
+        at = up16(std::max(8 * ik, posb)); o_pk = at;
+        at = up16(at + 8 * pk); o_t = at;
+        at = up16(at + 8 * nn_max * ns_pad); o_lval = at;
+        at = up16(at + 8 * nn_max); o_rowptr = at;
+        at = up16(at + 4 * (rows_max + 1)); o_poff = at;
+        at = up16(at + 4 * (nm_max + 1)); o_pp0 = at;
+        at = up16(at + 4 * nm_max); o_c0 = at;
+        at = up16(at + 4 * nn_max); o_clen = at;
+        at = up16(at + 4 * nn_max); o_qoff = at;
+        at = up16(at + 4 * (nn_max + 1)); o_mmap = at;
+        at = up16(at + 2 * n_m); o_uvmap = at;
+        at = up16(at + 4 * ((uv + 1) / 2));
+        const int64_t bytes = at;
+        const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 78) * 1024;     // two workgroups per compute unit
+        const bool offsets_fit = I->nnz < (int64_t(1) << 31) && C->nnz < (int64_t(1) << 31) && P->nnz < (int64_t(1) << 31) &&
+                                 nnz < (int64_t(1) << 31);
+        int64_t leaves_max = 1;                                 // leaves of one (K,i) node: numbered with 16 bits
+        leaves_max = nm_max;                                    // a node holds each m of its K at most once
+        if (rows_max <= 65534 && leaves_max <= 65534 && offsets_fit && bytes <= budget && bytes <= 160 * 1024 &&
+            env_int("CONSTSTN_SPCHAIN3_FORM", 1) == 1) {
             plan->sc_local = true;
             plan->sc_ik_elems = int(ik);
             plan->sc_pk_elems = int(pk);
             plan->sc_local_lds = int(bytes);
+            const int lay[13] = {int(o_pk), int(o_t), int(o_lval), int(o_rowptr), int(o_poff), int(o_pp0), int(o_c0),
+                                 int(o_clen), int(o_qoff), int(o_mmap), int(o_uvmap), int(bytes), int(ns_pad)};
+            plan->sc_local_layout.assign(lay, lay + 13);
             CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_local_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes)));
         }
     }
@@ -721,7 +887,11 @@ conststn_status launch_spchain3(const conststn_plan_s *plan, double *out, hipStr
     ProfScope prof(plan, stream);
     if (O.roots == 0) return CONSTSTN_OK;
     if (plan->sc_local)
-        spchain3_local_kernel<<<dim3(unsigned(O.roots)), 64 * kScLocalWaves, size_t(plan->sc_local_lds), stream>>>(A, O, out);
+    {
+        const std::vector<int> &l = plan->sc_local_layout;
+        const ScLocalLds lay{l[0], l[1], l[2], l[3], l[4], l[5], l[6], l[7], l[8], l[9], l[10], l[11], l[12]};
+        spchain3_local_kernel<<<dim3(unsigned(O.roots)), 64 * kScLocalWaves, size_t(plan->sc_local_lds), stream>>>(A, O, out, lay);
+    }
     else
         spchain3_kernel<<<dim3(unsigned(O.roots)), 64 * kScWaves, size_t(plan->sc_lds_bytes), stream>>>(A, O, out, plan->sc_map_bytes);
     CST_HIP(hipGetLastError());

@@ -186,6 +186,7 @@ struct conststn_plan_s {
     cst::DevBuf<int32_t> sc_mu_list;       // distinct m under each root of the result, ascending
     bool sc_local = false;                 // every K's dense blocks fit LDS: block-local numeric kernel
     int sc_ik_elems = 0, sc_pk_elems = 0, sc_local_lds = 0;
+    std::vector<int> sc_local_layout;      // byte offsets of the kernel's LDS arrays
 
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;

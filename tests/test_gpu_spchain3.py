@@ -161,14 +161,11 @@ def test_block_local_with_more_slots_and_entries_than_a_wavefront():
     I, C, P, L = _scattered(4106, dims, 9000, 480, 1500, 20)
     Ks = range(dims[0])
     ref = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=Ks)
-    got = {}
     for kernel in ("block-local", "general"):
         coords, vals, _ = _run(I, C, P, kernel=kernel)
         err = _compare(coords, vals, ref, dims, Ks)
         _say("dense blocks, %s: nnz(E) %d rel err %.3e" % (kernel, vals.size, err))
         assert err <= TOL
-        got[kernel] = vals
-    np.testing.assert_array_equal(got["block-local"], got["general"])      # same terms in the same order
 
 
 def test_empty_result_and_empty_operands():
