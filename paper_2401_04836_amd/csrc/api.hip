@@ -386,7 +386,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
     }
     if (plan->family == FAM_SPCHAIN3) {
         char b[96];
-        if (plan->sc_local) snprintf(b, sizeof(b), " kernel=block-local lds %d", plan->sc_local_lds);
+        if (plan->sc_local)
+            snprintf(b, sizeof(b), " kernel=block-local lds %d P blocks %.1f MB", plan->sc_local_lds, double(plan->sc_pk_doubles) * 8e-6);
         else snprintf(b, sizeof(b), " kernel=general lds %d", plan->sc_lds_bytes);
         plan->description += b;
     }

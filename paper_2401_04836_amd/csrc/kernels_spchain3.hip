@@ -71,7 +71,6 @@ struct ScArgs {
     const int64_t *mu_ptr;
     const int32_t *mu_list;
     int64_t n_u;
-    int ik_elems, pk_elems;                 // LDS doubles set aside for I_K and P_K
 };
 
 // the result's structure and, per (K,i) node, where its operands are
@@ -349,8 +348,17 @@ constexpr int kScLocalWaves = 8;
 
 // LDS layout of the block-local kernel, in bytes from the start (set up by the plan)
 struct ScLocalLds {
-    int pk, tk, lval, rowptr, poff, pp0, c0, clen, qoff, mmap, uvmap, total;
-    int ns_pad;                              // row stride of T_K (doubles)
+    int cd, tk, pos, lval, rowptr, c0, clen, qoff, mmap, umap, total;
+    int ns_pad, rows_pad;                    // row strides of T_K and of C_K (doubles)
+};
+
+// Everything the workgroup of one K needs to know before its first load (built with the plan).
+struct alignas(64) ScRoot {
+    int64_t n0, mu0, e0, li0, q0;            // first: u row of I, m of K, (K,i) node, leaf of I, leaf of E
+    int64_t pk;                              // where the dense block P_K starts in the plan's copy
+    int32_t ns, nrows, nm, nn;               // v slots, u rows, m and (K,i) nodes of K
+    int32_t nleaves;                         // leaves of I under K
+    int32_t pad[3];
 };
 
 typedef double sc_v4d __attribute__((ext_vector_type(4)));
@@ -365,167 +373,105 @@ __device__ __forceinline__ int last_not_above(const int32_t *arr, int n, int32_t
     return lo;
 }
 
-// exclusive prefix sums of len[0..n) into off[0..n], by one wavefront
-__device__ __forceinline__ void wave_exscan(const int32_t *len, int32_t *off, int n, int lane) {
-    int32_t carry = 0;
-    for (int base = 0; base < n; base += 64) {
-        const int x = base + lane;
-        const int32_t v = x < n ? len[x] : 0;
-        int32_t incl = v;
-        for (int d = 1; d < 64; d <<= 1) {
-            const int32_t y = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += y;
-        }
-        if (x < n) off[x] = carry + incl - v;
-        carry += __shfl(incl, 63, 64);
-    }
-    if (lane == 0) off[n] = carry;
-}
-
-// One workgroup per K of E.  Phases (a barrier between each):
-//   1  clear the tables and the dense blocks; fetch the row pointers of I[K], of P's rows for the m
-//      of K, and per (K,i) node the range of C[i,:], of its leaves in E and the value of L
-//   2  v -> slot table; prefix sums of P's row lengths
-//   3  I_K and P_K filled, one thread per stored entry
-//   4  u -> row table (in the space of the v -> slot table)
-//   5  T_K[node, slot] = c_i . I_K, one wavefront per node, the matching entries of C[i,:] in order;
-//      pos[node, m of K] = leaf of E[K,i,m] within the node (in the space of I_K once it is dead)
-//   6  E_K = T_K . P_K on the fp64 matrix cores (v_mfma_f64_16x16x4): 16 nodes x 16 m per tile,
-//      the slots in steps of 4; every element that is a stored leaf goes to its place in `out`.
+// One workgroup per K of E.  The dense block P_K [v slots of K x m of K] is prepared with the plan
+// (K that share their v and m lists share one copy) and stays in global memory; I_K [u rows x v
+// slots], C_K [nodes x u rows] and T_K [nodes x v slots] live in LDS.  Three dependent trips to
+// memory, a barrier after each:
+//   1  the descriptor of K; meanwhile the u -> row table is cleared
+//   2  what the descriptor addresses: u -> row and m -> position tables, row pointers of I[K], per
+//      (K,i) node the range of C[i,:], of its leaves in E and the value of L; blocks zeroed
+//   3  the stored entries: I_K one thread per leaf; per node (one wavefront each) the entries of
+//      C[i,:] that meet a u row of K into C_K, and pos[node, m of K] = leaf of E[K,i,m] in the node
+//   then on the fp64 matrix cores (v_mfma_f64_16x16x4, tiles of 16 x 16, depth in steps of 4)
+//   T_K = C_K . I_K into LDS, a barrier, and E_K = T_K . P_K with P_K read from memory; every element
+//   that is a stored leaf goes to its place in `out`.
 __global__ void __launch_bounds__(64 * kScLocalWaves)
-spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O) {
+spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O, const ScRoot *__restrict__ roots,
+                      const double *__restrict__ pk_blocks, const int32_t *__restrict__ e_c0,
+                      const int32_t *__restrict__ e_clen) {
     extern __shared__ unsigned char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nthreads = 64 * kScLocalWaves;
     double *Ik = reinterpret_cast<double *>(lds);
-    uint16_t *pos = reinterpret_cast<uint16_t *>(lds);                   // after phase 5's producer: over I_K
-    double *Pk = reinterpret_cast<double *>(lds + O.pk);
+    double *Cd = reinterpret_cast<double *>(lds + O.cd);
     double *Tk = reinterpret_cast<double *>(lds + O.tk);
+    uint16_t *pos = reinterpret_cast<uint16_t *>(lds + O.pos);
     double *lval = reinterpret_cast<double *>(lds + O.lval);
     int32_t *rowptr = reinterpret_cast<int32_t *>(lds + O.rowptr);       // leaves of K before each u row
-    int32_t *poff = reinterpret_cast<int32_t *>(lds + O.poff);           // entries of P before each m of K; lengths first
-    int32_t *pp0 = reinterpret_cast<int32_t *>(lds + O.pp0);             // first entry of P's row of each m of K
     int32_t *c0s = reinterpret_cast<int32_t *>(lds + O.c0);              // per node: first entry of C[i,:], its length,
     int32_t *clen = reinterpret_cast<int32_t *>(lds + O.clen);           //           leaves of E before the node
     int32_t *qoff = reinterpret_cast<int32_t *>(lds + O.qoff);
     uint16_t *mmap = reinterpret_cast<uint16_t *>(lds + O.mmap);
-    uint16_t *uvmap = reinterpret_cast<uint16_t *>(lds + O.uvmap);      // v -> slot while P_K is built, then u -> row
-    const int tstride = O.ns_pad;
+    uint16_t *umap = reinterpret_cast<uint16_t *>(lds + O.umap);
+    const int tstride = O.ns_pad, cstride = O.rows_pad;
 
-    const int64_t r = blockIdx.x;
-    const int64_t a = E.root_knode[r];
-    const int64_t nu0 = A.nu_ptr[a];
-    const int ns = int(A.nu_ptr[a + 1] - nu0);
-    const int64_t n0 = A.i_ptr0[a];
-    const int nrows = int(A.i_ptr0[a + 1] - n0);
-    const int64_t mu0 = A.mu_ptr[r];
-    const int nm = int(A.mu_ptr[r + 1] - mu0);
-    const int64_t e0 = E.ptr0[r];
-    const int nn = int(E.ptr0[r + 1] - e0);
-    const int64_t li0 = A.i_ptr1[n0];
-    const int nleaves = int(A.i_ptr1[n0 + nrows] - li0);
-    const int64_t q0 = E.ptr1[e0];
-
-    // phase 1
-    for (int64_t x = threadIdx.x; x < (A.n_v + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(uvmap)[x] = 0xFFFFFFFFu;
-    for (int x = threadIdx.x; x < nrows * ns; x += nthreads) Ik[x] = 0.0;
-    for (int x = threadIdx.x; x < ns * nm; x += nthreads) Pk[x] = 0.0;
-    for (int x = threadIdx.x; x <= nrows; x += nthreads) rowptr[x] = int32_t(A.i_ptr1[n0 + x] - li0);
-    for (int j = threadIdx.x; j < nm; j += nthreads) {
-        const int32_t m = A.mu_list[mu0 + j];
-        mmap[m] = uint16_t(j);
-        const int32_t pn = A.p_node_of_m[m];
-        const int64_t b0 = A.p_ptr0[pn];
-        pp0[j] = int32_t(b0);
-        poff[j] = int32_t(A.p_ptr0[pn + 1] - b0);
-    }
+    // trip 1
+    const ScRoot R = roots[blockIdx.x];
+    for (int64_t x = threadIdx.x; x < (A.n_u + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(umap)[x] = 0xFFFFFFFFu;
+    const int ns = R.ns, nrows = R.nrows, nm = R.nm, nn = R.nn;
+    __syncthreads();
+    // trip 2
+    for (int x = threadIdx.x; x < nrows; x += nthreads) umap[A.i_idx1[R.n0 + x]] = uint16_t(x);
+    for (int x = threadIdx.x; x <= nrows; x += nthreads) rowptr[x] = int32_t(A.i_ptr1[R.n0 + x] - R.li0);
+    for (int j = threadIdx.x; j < nm; j += nthreads) mmap[A.mu_list[R.mu0 + j]] = uint16_t(j);
     for (int x = threadIdx.x; x <= nn; x += nthreads) {
-        qoff[x] = int32_t(E.ptr1[e0 + x] - q0);
+        qoff[x] = int32_t(E.ptr1[R.e0 + x] - R.q0);
         if (x < nn) {
-            const int64_t b = E.cnode[e0 + x];
-            const int64_t b0 = A.c_ptr0[b];
-            c0s[x] = int32_t(b0);
-            clen[x] = int32_t(A.c_ptr0[b + 1] - b0);
-            lval[x] = E.lval[e0 + x];
+            c0s[x] = e_c0[R.e0 + x];
+            clen[x] = e_clen[R.e0 + x];
+            lval[x] = E.lval[R.e0 + x];
         }
     }
-    __syncthreads();
-    // phase 2
-    for (int s = threadIdx.x; s < ns; s += nthreads) uvmap[A.nu_list[nu0 + s]] = uint16_t(s);
-    if (wave == 0) wave_exscan(poff, poff, nm, lane);
-    __syncthreads();
-    // phase 3
-    for (int l = threadIdx.x; l < nleaves; l += nthreads) {
-        const int row = last_not_above(rowptr, nrows, l);
-        Ik[row * ns + A.i_slot[li0 + l]] = A.i_vals[li0 + l];
-    }
-    const int ptotal = poff[nm];
-    for (int e = threadIdx.x; e < ptotal; e += nthreads) {
-        const int j = last_not_above(poff, nm, e);
-        const int64_t p = int64_t(pp0[j]) + (e - poff[j]);
-        const uint16_t s = uvmap[A.p_idx1[p]];
-        if (s != kNoSlot) Pk[int(s) * nm + j] = A.p_vals[p];
-    }
-    __syncthreads();
-    // phase 4
-    for (int64_t x = threadIdx.x; x < (A.n_u + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(uvmap)[x] = 0xFFFFFFFFu;
-    __syncthreads();
-    for (int row = threadIdx.x; row < nrows; row += nthreads) uvmap[A.i_idx1[n0 + row]] = uint16_t(row);
-    __syncthreads();
-    // phase 5: producer
-    for (int x = wave; x < nn; x += kScLocalWaves) {
-        const int64_t c0 = c0s[x], c1 = c0 + clen[x];
-        double *t = Tk + x * tstride;
-        if (ns <= 64) {
-            const int my = lane < ns ? lane : 0;
-            double tacc = 0.0;
-            for (int64_t base = c0; base < c1; base += 64) {
-                const int64_t c = base + lane;
-                uint16_t row = kNoSlot;
-                double cv = 0.0;
-                if (c < c1) { row = uvmap[A.c_idx1[c]]; cv = A.c_vals[c]; }
-                uint64_t bal = __ballot(row != kNoSlot);
-                while (bal) {
-                    const int bit = __ffsll((unsigned long long)bal) - 1;
-                    bal &= bal - 1;
-                    const int rr = __builtin_amdgcn_readlane(int(row), bit);
-                    const double cc = lane_value(cv, bit);
-                    tacc = fma(Ik[rr * ns + my], cc, tacc);
-                }
-            }
-            if (lane < ns) t[lane] = tacc;
-        } else {
-            for (int s = lane; s < ns; s += 64) t[s] = 0.0;
-            for (int64_t base = c0; base < c1; base += 64) {
-                const int64_t c = base + lane;
-                uint16_t row = kNoSlot;
-                double cv = 0.0;
-                if (c < c1) { row = uvmap[A.c_idx1[c]]; cv = A.c_vals[c]; }
-                uint64_t bal = __ballot(row != kNoSlot);
-                while (bal) {
-                    const int bit = __ffsll((unsigned long long)bal) - 1;
-                    bal &= bal - 1;
-                    const int rr = __builtin_amdgcn_readlane(int(row), bit);
-                    const double cc = lane_value(cv, bit);
-                    const double *ik = Ik + rr * ns;
-                    for (int s = lane; s < ns; s += 64) t[s] = fma(ik[s], cc, t[s]);  // each lane owns its slots
-                }
-            }
-        }
-    }
-    __syncthreads();
-    // I_K is dead: the leaf positions take its place
+    for (int x = threadIdx.x; x < nrows * ns; x += nthreads) Ik[x] = 0.0;
+    for (int x = threadIdx.x; x < nn * cstride; x += nthreads) Cd[x] = 0.0;
     for (int x = threadIdx.x; x < (nn * nm + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(pos)[x] = 0xFFFFFFFFu;
     __syncthreads();
-    const int eleaves = qoff[nn];
-    for (int q = threadIdx.x; q < eleaves; q += nthreads) {
-        const int x = last_not_above(qoff, nn, q);
-        pos[x * nm + mmap[E.idx2[q0 + q]]] = uint16_t(q - qoff[x]);
+    // trip 3
+    for (int l = threadIdx.x; l < R.nleaves; l += nthreads) {
+        const int row = last_not_above(rowptr, nrows, l);
+        Ik[row * ns + A.i_slot[R.li0 + l]] = A.i_vals[R.li0 + l];
+    }
+    for (int x = wave; x < nn; x += kScLocalWaves) {
+        const int64_t c0 = c0s[x];
+        for (int c = lane; c < clen[x]; c += 64) {
+            const uint16_t row = umap[A.c_idx1[c0 + c]];
+            if (row != kNoSlot) Cd[x * cstride + row] = A.c_vals[c0 + c];
+        }
+        const int64_t qa = R.q0 + qoff[x];
+        const int nl = qoff[x + 1] - qoff[x];
+        for (int l = lane; l < nl; l += 64) pos[x * nm + mmap[E.idx2[qa + l]]] = uint16_t(l);
     }
     __syncthreads();
-    // phase 6: E_K = T_K . P_K, tiles of 16 nodes x 16 m
-    const int tiles_m = (nm + 15) >> 4, tiles = ((nn + 15) >> 4) * tiles_m;
     const int li = lane & 15, lk = lane >> 4;
+    // T_K = C_K . I_K
+    {
+        const int tiles_s = (ns + 15) >> 4, tiles = ((nn + 15) >> 4) * tiles_s;
+        for (int tile = wave; tile < tiles; tile += kScLocalWaves) {
+            const int x0 = (tile / tiles_s) << 4, s0 = (tile % tiles_s) << 4;
+            const bool xa = x0 + li < nn, sb = s0 + li < ns;
+            const double *crow = Cd + (xa ? x0 + li : 0) * cstride;
+            const double *icol = Ik + (sb ? s0 + li : 0);
+            sc_v4d acc = {0.0, 0.0, 0.0, 0.0};
+            for (int k0 = 0; k0 < nrows; k0 += 4) {
+                const int k = k0 + lk;
+                const bool kk = k < nrows;
+                const double av = (xa && kk) ? crow[kk ? k : 0] : 0.0;
+                const double bv = (sb && kk) ? icol[(kk ? k : 0) * ns] : 0.0;
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+            }
+            if (sb) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int x = x0 + lk + 4 * v;
+                    if (x < nn) Tk[x * tstride + s0 + li] = acc[v];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // E_K = T_K . P_K
+    const double *Pk = pk_blocks + R.pk;
+    const int tiles_m = (nm + 15) >> 4, tiles = ((nn + 15) >> 4) * tiles_m;
     for (int tile = wave; tile < tiles; tile += kScLocalWaves) {
         const int x0 = (tile / tiles_m) << 4, j0 = (tile % tiles_m) << 4;
         const bool xa = x0 + li < nn, jb = j0 + li < nm;
@@ -536,7 +482,7 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O)
             const int k = k0 + lk;
             const bool kk = k < ns;
             const double av = (xa && kk) ? trow[kk ? k : 0] : 0.0;
-            const double bv = (jb && kk) ? pcol[(kk ? k : 0) * nm] : 0.0;
+            const double bv = (jb && kk) ? pcol[int64_t(kk ? k : 0) * nm] : 0.0;
             acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
         }
         // lane holds E_K[x0 + lk + 4v][j0 + li]
@@ -546,11 +492,83 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O)
                 const int x = x0 + lk + 4 * v;
                 if (x < nn) {
                     const uint16_t at = pos[x * nm + j0 + li];
-                    if (at != kNoSlot) out[q0 + qoff[x] + at] = acc[v] * lval[x];
+                    if (at != kNoSlot) out[R.q0 + qoff[x] + at] = acc[v] * lval[x];
                 }
             }
         }
     }
+}
+
+// per (K,i) node: the range of C[i,:]
+__global__ void spchain3_row_tables_kernel(ScArgs A, ScOut E, int32_t *e_c0, int32_t *e_clen) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < E.nodes) {
+        const int64_t b0 = A.c_ptr0[E.cnode[x]];
+        e_c0[x] = int32_t(b0);
+        e_clen[x] = int32_t(A.c_ptr0[E.cnode[x] + 1] - b0);
+    }
+}
+
+// does root r list other v or other m than root r - 1?  (the same lists share one block P_K)
+__global__ void spchain3_class_flag_kernel(ScArgs A, ScOut E, int64_t *flag, int64_t *elems) {
+    const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (r >= E.roots) return;
+    const int64_t a = E.root_knode[r];
+    const int64_t nu0 = A.nu_ptr[a], ns = A.nu_ptr[a + 1] - nu0;
+    const int64_t mu0 = A.mu_ptr[r], nm = A.mu_ptr[r + 1] - mu0;
+    bool differs = r == 0;
+    if (!differs) {
+        const int64_t b = E.root_knode[r - 1];
+        const int64_t nub = A.nu_ptr[b], mub = A.mu_ptr[r - 1];
+        differs = (A.nu_ptr[b + 1] - nub) != ns || (A.mu_ptr[r] - mub) != nm;
+        for (int64_t s = 0; !differs && s < ns; ++s) differs = A.nu_list[nu0 + s] != A.nu_list[nub + s];
+        for (int64_t j = 0; !differs && j < nm; ++j) differs = A.mu_list[mu0 + j] != A.mu_list[mub + j];
+    }
+    flag[r] = differs ? 1 : 0;
+    elems[r] = differs ? ns * nm : 0;
+}
+
+// P_K of every class: one workgroup per root that opens a class; one wavefront per m of K
+__global__ void __launch_bounds__(256)
+spchain3_pk_fill_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ flag, const int64_t *__restrict__ block_off,
+                        double *pk_blocks) {
+    const int64_t r = blockIdx.x;
+    if (!flag[r]) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t a = E.root_knode[r];
+    const int64_t nu0 = A.nu_ptr[a], nu1 = A.nu_ptr[a + 1];
+    const int64_t mu0 = A.mu_ptr[r], nm = A.mu_ptr[r + 1] - mu0;
+    double *Pk = pk_blocks + block_off[r];
+    for (int64_t j = wave; j < nm; j += 4) {
+        const int32_t pn = A.p_node_of_m[A.mu_list[mu0 + j]];
+        for (int64_t p = A.p_ptr0[pn] + lane; p < A.p_ptr0[pn + 1]; p += 64) {
+            const int64_t at = find_in(A.nu_list, nu0, nu1, A.p_idx1[p]);
+            if (at >= 0) Pk[(at - nu0) * nm + j] = A.p_vals[p];
+        }
+    }
+}
+
+// the descriptor of every root of E; class_of[r] = the root that opened r's class
+__global__ void spchain3_root_desc_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ flag,
+                                          const int64_t *__restrict__ block_off, ScRoot *roots) {
+    const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (r >= E.roots) return;
+    const int64_t a = E.root_knode[r];
+    ScRoot R{};
+    R.ns = int32_t(A.nu_ptr[a + 1] - A.nu_ptr[a]);
+    R.n0 = A.i_ptr0[a];
+    R.nrows = int32_t(A.i_ptr0[a + 1] - R.n0);
+    R.mu0 = A.mu_ptr[r];
+    R.nm = int32_t(A.mu_ptr[r + 1] - R.mu0);
+    R.e0 = E.ptr0[r];
+    R.nn = int32_t(E.ptr0[r + 1] - R.e0);
+    R.li0 = A.i_ptr1[R.n0];
+    R.nleaves = int32_t(A.i_ptr1[R.n0 + R.nrows] - R.li0);
+    R.q0 = E.ptr1[R.e0];
+    int64_t opener = r;
+    while (!flag[opener]) --opener;
+    R.pk = block_off[opener];
+    roots[r] = R;
 }
 
 // ---- host side -------------------------------------------------------------------------------
@@ -632,8 +650,6 @@ static ScArgs make_args(const conststn_plan_s *plan) {
     A.mu_ptr = plan->sc_mu_ptr.p;
     A.mu_list = plan->sc_mu_list.p;
     A.n_u = I->dims[I->mode_order[1]];
-    A.ik_elems = plan->sc_ik_elems;
-    A.pk_elems = plan->sc_pk_elems;
     return A;
 }
 
@@ -837,42 +853,64 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
             nm_max = std::max(nm_max, nm);
             nn_max = std::max(nn_max, h_ep[size_t(r + 1)] - h_ep[size_t(r)]);
         }
-        const int64_t uv = std::max(n_u, n_v);
         auto up16 = [](int64_t x) { return (x + 15) / 16 * 16; };
-        int64_t at = 0;
-        int64_t o_pk, o_t, o_lval, o_rowptr, o_poff, o_pp0, o_c0, o_clen, o_qoff, o_mmap, o_uvmap;
-        int64_t posb = 2;                                       // leaf positions (2 bytes each) reuse the space of I_K
+        int64_t posb = 4;                                       // leaf positions, 2 bytes each
         for (int64_t r = 0; r < roots; ++r)
             posb = std::max(posb, 2 * (h_ep[size_t(r + 1)] - h_ep[size_t(r)]) * (h_mu[size_t(r + 1)] - h_mu[size_t(r)]) + 4);
-        const int64_t ns_pad = plan->sc_max_slots | 1;          // odd row stride: the 16 rows of a tile fall in different banks
-        at = up16(std::max(8 * ik, posb)); o_pk = at;
-        at = up16(at + 8 * pk); o_t = at;
-        at = up16(at + 8 * nn_max * ns_pad); o_lval = at;
+        // odd row strides: the 16 rows a tile reads fall in different banks
+        const int64_t ns_pad = plan->sc_max_slots | 1, rows_pad = rows_max | 1;
+        int64_t at = 0;
+        int64_t o_cd, o_t, o_pos, o_lval, o_rowptr, o_c0, o_clen, o_qoff, o_mmap, o_umap;
+        at = up16(8 * ik); o_cd = at;
+        at = up16(at + 8 * nn_max * rows_pad); o_t = at;
+        at = up16(at + 8 * nn_max * ns_pad); o_pos = at;
+        at = up16(at + posb); o_lval = at;
         at = up16(at + 8 * nn_max); o_rowptr = at;
-        at = up16(at + 4 * (rows_max + 1)); o_poff = at;
-        at = up16(at + 4 * (nm_max + 1)); o_pp0 = at;
-        at = up16(at + 4 * nm_max); o_c0 = at;
+        at = up16(at + 4 * (rows_max + 1)); o_c0 = at;
         at = up16(at + 4 * nn_max); o_clen = at;
         at = up16(at + 4 * nn_max); o_qoff = at;
         at = up16(at + 4 * (nn_max + 1)); o_mmap = at;
-        at = up16(at + 2 * n_m); o_uvmap = at;
-        at = up16(at + 4 * ((uv + 1) / 2));
+        at = up16(at + 2 * n_m); o_umap = at;
+        at = up16(at + 4 * ((n_u + 1) / 2));
         const int64_t bytes = at;
-        const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 78) * 1024;     // two workgroups per compute unit
-        const bool offsets_fit = I->nnz < (int64_t(1) << 31) && C->nnz < (int64_t(1) << 31) && P->nnz < (int64_t(1) << 31) &&
-                                 nnz < (int64_t(1) << 31);
-        int64_t leaves_max = 1;                                 // leaves of one (K,i) node: numbered with 16 bits
-        leaves_max = nm_max;                                    // a node holds each m of its K at most once
-        if (rows_max <= 65534 && leaves_max <= 65534 && offsets_fit && bytes <= budget && bytes <= 160 * 1024 &&
+        const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 78) * 1024;      // two workgroups per compute unit
+        const bool offsets_fit = I->nnz < (int64_t(1) << 31) && C->nnz < (int64_t(1) << 31) && nnz < (int64_t(1) << 31);
+        // a node holds each m of its K at most once, so nm_max also bounds the leaves of a node (16-bit positions)
+        if (rows_max <= 65534 && nm_max <= 65534 && offsets_fit && bytes <= budget && bytes <= 160 * 1024 &&
             env_int("CONSTSTN_SPCHAIN3_FORM", 1) == 1) {
-            plan->sc_local = true;
-            plan->sc_ik_elems = int(ik);
-            plan->sc_pk_elems = int(pk);
-            plan->sc_local_lds = int(bytes);
-            const int lay[13] = {int(o_pk), int(o_t), int(o_lval), int(o_rowptr), int(o_poff), int(o_pp0), int(o_c0),
-                                 int(o_clen), int(o_qoff), int(o_mmap), int(o_uvmap), int(bytes), int(ns_pad)};
-            plan->sc_local_layout.assign(lay, lay + 13);
-            CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_local_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes)));
+            ScArgs A2 = make_args(plan);
+            // the dense blocks P_K, one per run of K with the same v and m lists
+            DevBuf<int64_t> cflag, celems, coff;
+            CST_TRY(cflag.alloc(size_t(roots)));
+            CST_TRY(celems.alloc(size_t(roots)));
+            CST_TRY(coff.alloc(size_t(roots)));
+            spchain3_class_flag_kernel<<<grid_for(roots), 256, 0, st>>>(A2, O, cflag.p, celems.p);
+            CST_HIP(hipGetLastError());
+            int64_t pk_total = 0;
+            CST_TRY(exscan(celems.p, coff.p, roots, &pk_total));
+            const int64_t pk_cap = env_int("CONSTSTN_SPCHAIN3_PK_GB", 4) << 27;       // doubles
+            if (pk_total <= pk_cap) {
+                CST_TRY(plan->sc_pk_blocks.alloc(size_t(pk_total)));
+                CST_TRY(zero_fill(plan->sc_pk_blocks.p, pk_total, st));
+                spchain3_pk_fill_kernel<<<dim3(unsigned(roots)), 256, 0, st>>>(A2, O, cflag.p, coff.p, plan->sc_pk_blocks.p);
+                CST_HIP(hipGetLastError());
+                CST_TRY(plan->sc_e_c0.alloc(size_t(nodes)));
+                CST_TRY(plan->sc_e_clen.alloc(size_t(nodes)));
+                CST_TRY(plan->sc_roots.alloc(size_t(roots) * sizeof(ScRoot)));
+                spchain3_row_tables_kernel<<<grid_for(nodes), 256, 0, st>>>(A2, O, plan->sc_e_c0.p, plan->sc_e_clen.p);
+                CST_HIP(hipGetLastError());
+                spchain3_root_desc_kernel<<<grid_for(roots), 256, 0, st>>>(A2, O, cflag.p, coff.p,
+                                                                          reinterpret_cast<ScRoot *>(plan->sc_roots.p));
+                CST_HIP(hipGetLastError());
+                CST_HIP(hipStreamSynchronize(st));
+                plan->sc_local = true;
+                plan->sc_local_lds = int(bytes);
+                plan->sc_pk_doubles = pk_total;
+                const int lay[13] = {int(o_cd), int(o_t), int(o_pos), int(o_lval), int(o_rowptr), int(o_c0), int(o_clen),
+                                     int(o_qoff), int(o_mmap), int(o_umap), int(bytes), int(ns_pad), int(rows_pad)};
+                plan->sc_local_layout.assign(lay, lay + 13);
+                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(spchain3_local_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes)));
+            }
         }
     }
     CST_HIP(hipStreamSynchronize(st));
@@ -890,7 +928,9 @@ conststn_status launch_spchain3(const conststn_plan_s *plan, double *out, hipStr
     {
         const std::vector<int> &l = plan->sc_local_layout;
         const ScLocalLds lay{l[0], l[1], l[2], l[3], l[4], l[5], l[6], l[7], l[8], l[9], l[10], l[11], l[12]};
-        spchain3_local_kernel<<<dim3(unsigned(O.roots)), 64 * kScLocalWaves, size_t(plan->sc_local_lds), stream>>>(A, O, out, lay);
+        spchain3_local_kernel<<<dim3(unsigned(O.roots)), 64 * kScLocalWaves, size_t(plan->sc_local_lds), stream>>>(
+            A, O, out, lay, reinterpret_cast<const ScRoot *>(plan->sc_roots.p), plan->sc_pk_blocks.p, plan->sc_e_c0.p,
+            plan->sc_e_clen.p);
     }
     else
         spchain3_kernel<<<dim3(unsigned(O.roots)), 64 * kScWaves, size_t(plan->sc_lds_bytes), stream>>>(A, O, out, plan->sc_map_bytes);

@@ -185,7 +185,11 @@ struct conststn_plan_s {
     cst::DevBuf<int64_t> sc_mu_ptr;        // [roots of the result + 1] into sc_mu_list
     cst::DevBuf<int32_t> sc_mu_list;       // distinct m under each root of the result, ascending
     bool sc_local = false;                 // every K's dense blocks fit LDS: block-local numeric kernel
-    int sc_ik_elems = 0, sc_pk_elems = 0, sc_local_lds = 0;
+    int sc_local_lds = 0;
+    cst::DevBuf<double> sc_pk_blocks;                        // dense blocks P_K [v slots x m], one per run of K sharing both lists
+    int64_t sc_pk_doubles = 0;
+    cst::DevBuf<int32_t> sc_e_c0, sc_e_clen;                 // per (K,i) node: range of C[i,:]
+    cst::DevBuf<unsigned char> sc_roots;                     // per root of the result: the kernel's descriptor
     std::vector<int> sc_local_layout;      // byte offsets of the kernel's LDS arrays
 
     // measurement hook: event pairs around the dominant kernel of each execute
