@@ -22,13 +22,14 @@
 //             sum_v t[slot(v)] * P[m,v] along P's row, and stores the value in place.
 //             No atomics; the result is bit-reproducible.
 //   numeric, block-local form.  The sparse maps of Sec. 5.1 are local: under one K only a few
-//             u, v and m occur.  When the blocks  I_K [u rows of K x v slots of K]  and
-//             P_K [v slots of K x m of K]  fit LDS as dense arrays, the workgroup of K builds them
-//             once and every (K,i) node becomes two small dense products out of LDS,
-//             t = c_i . I_K  (c_i: the entries of C[i,:] that meet a u row of K) and
-//             E[K,i,:] = t . P_K  at the stored m only: no global gathers in the inner loops.
-//             Terms are visited in the same order as in the general form; the extra terms are
-//             exact zeros.  Chosen by the plan when every K fits; otherwise the general form.
+//             u, v and m occur, and the blocks  I_K [u rows of K x v slots of K],
+//             C_K [(K,i) nodes x u rows of K]  and  P_K [v slots of K x m of K]  are small and
+//             fairly dense.  The whole slice then is two dense products,
+//             T_K = C_K . I_K  and  E_K = T_K . P_K,  of which only the stored (node, m) elements
+//             are kept: a dense contraction, run on the fp64 matrix cores.  I_K, C_K and T_K live
+//             in LDS; P_K depends on the lists of v and m only, so it is prepared with the plan,
+//             once per run of K that share both lists, and read from memory.  The extra terms are
+//             exact zeros.  Chosen by the plan when every K fits LDS; otherwise the general form.
 #include "plan.hpp"
 
 namespace cst {
@@ -86,13 +87,6 @@ struct ScOut {
 __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-}
-
-// value of `v` in lane `l`, the same l in every lane (a scalar read, not a permute through LDS)
-__device__ __forceinline__ double lane_value(double v, int l) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
-    return __hiloint2double(hi, lo);
 }
 
 __device__ __forceinline__ int wave_sum(int x) {
@@ -362,6 +356,8 @@ struct alignas(64) ScRoot {
 };
 
 typedef double sc_v4d __attribute__((ext_vector_type(4)));
+constexpr int kScAhead = 6;                  // (K,i) nodes per wavefront whose loads are issued together
+constexpr int kScDepth = 10;                 // depth steps (of 4 slots) of a result tile whose P_K values sit in registers
 
 // largest x in [0, n) with arr[x] <= key (arr ascending, arr[0] <= key)
 __device__ __forceinline__ int last_not_above(const int32_t *arr, int n, int32_t key) {
@@ -381,11 +377,12 @@ __device__ __forceinline__ int last_not_above(const int32_t *arr, int n, int32_t
 //   2  what the descriptor addresses: u -> row and m -> position tables, row pointers of I[K], per
 //      (K,i) node the range of C[i,:], of its leaves in E and the value of L; blocks zeroed
 //   3  the stored entries: I_K one thread per leaf; per node (one wavefront each) the entries of
-//      C[i,:] that meet a u row of K into C_K, and pos[node, m of K] = leaf of E[K,i,m] in the node
+//      C[i,:] that meet a u row of K into C_K; the m of the node's leaves wait in registers and become
+//      pos[node, m of K] = leaf of E[K,i,m] in the node once I_K is dead and its space free
 //   then on the fp64 matrix cores (v_mfma_f64_16x16x4, tiles of 16 x 16, depth in steps of 4)
 //   T_K = C_K . I_K into LDS, a barrier, and E_K = T_K . P_K with P_K read from memory; every element
 //   that is a stored leaf goes to its place in `out`.
-__global__ void __launch_bounds__(64 * kScLocalWaves)
+__global__ void __launch_bounds__(64 * kScLocalWaves, 6)
 spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O, const ScRoot *__restrict__ roots,
                       const double *__restrict__ pk_blocks, const int32_t *__restrict__ e_c0,
                       const int32_t *__restrict__ e_clen) {
@@ -424,25 +421,60 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
     }
     for (int x = threadIdx.x; x < nrows * ns; x += nthreads) Ik[x] = 0.0;
     for (int x = threadIdx.x; x < nn * cstride; x += nthreads) Cd[x] = 0.0;
-    for (int x = threadIdx.x; x < (nn * nm + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(pos)[x] = 0xFFFFFFFFu;
     __syncthreads();
-    // trip 3
+    // trip 3: every load of this wavefront's first kScAhead nodes is issued before any is used
+    int cidx[kScAhead], m0[kScAhead], m1[kScAhead];
+    double cval[kScAhead];
+#pragma unroll
+    for (int b = 0; b < kScAhead; ++b) {
+        const int x = wave + b * kScLocalWaves;
+        cidx[b] = -1;
+        cval[b] = 0.0;
+        m0[b] = m1[b] = -1;
+        if (x < nn) {
+            if (lane < clen[x]) { cidx[b] = A.c_idx1[int64_t(c0s[x]) + lane]; cval[b] = A.c_vals[int64_t(c0s[x]) + lane]; }
+            const int64_t qa = R.q0 + qoff[x];
+            const int nl = qoff[x + 1] - qoff[x];
+            if (lane < nl) m0[b] = E.idx2[qa + lane];
+            if (lane + 64 < nl) m1[b] = E.idx2[qa + lane + 64];
+        }
+    }
     for (int l = threadIdx.x; l < R.nleaves; l += nthreads) {
         const int row = last_not_above(rowptr, nrows, l);
         Ik[row * ns + A.i_slot[R.li0 + l]] = A.i_vals[R.li0 + l];
     }
+#pragma unroll
+    for (int b = 0; b < kScAhead; ++b) {
+        const int x = wave + b * kScLocalWaves;
+        if (cidx[b] >= 0) {
+            const uint16_t row = umap[cidx[b]];
+            if (row != kNoSlot) Cd[x * cstride + row] = cval[b];
+        }
+    }
+    // what the registers did not cover: entries of C[i,:] beyond 64, nodes beyond the first kScAhead
     for (int x = wave; x < nn; x += kScLocalWaves) {
+        const bool ahead = x < kScAhead * kScLocalWaves;
         const int64_t c0 = c0s[x];
-        for (int c = lane; c < clen[x]; c += 64) {
+        for (int c = (ahead ? 64 : 0) + lane; c < clen[x]; c += 64) {
             const uint16_t row = umap[A.c_idx1[c0 + c]];
             if (row != kNoSlot) Cd[x * cstride + row] = A.c_vals[c0 + c];
         }
-        const int64_t qa = R.q0 + qoff[x];
-        const int nl = qoff[x + 1] - qoff[x];
-        for (int l = lane; l < nl; l += 64) pos[x * nm + mmap[E.idx2[qa + l]]] = uint16_t(l);
     }
     __syncthreads();
     const int li = lane & 15, lk = lane >> 4;
+    // the first tile of E_K this wavefront will compute: its part of P_K is fetched now
+    const double *Pk = pk_blocks + R.pk;
+    const int tiles_m = (nm + 15) >> 4, tiles_e = ((nn + 15) >> 4) * tiles_m;
+    double bpre[kScDepth];
+    {
+        const int j0 = (wave % tiles_m) << 4;
+        const bool jb = wave < tiles_e && j0 + li < nm;
+#pragma unroll
+        for (int kb = 0; kb < kScDepth; ++kb) {
+            const int k = 4 * kb + lk;
+            bpre[kb] = (jb && k < ns) ? Pk[int64_t(k) * nm + j0 + li] : 0.0;
+        }
+    }
     // T_K = C_K . I_K
     {
         const int tiles_s = (ns + 15) >> 4, tiles = ((nn + 15) >> 4) * tiles_s;
@@ -469,16 +501,50 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
         }
     }
     __syncthreads();
+    // I_K is dead: pos[node, m of K] = leaf of E[K,i,m] within the node takes its place
+    for (int x = threadIdx.x; x < (nn * nm + 1) / 2; x += nthreads) reinterpret_cast<uint32_t *>(pos)[x] = 0xFFFFFFFFu;
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < kScAhead; ++b) {
+        const int x = wave + b * kScLocalWaves;
+        if (m0[b] >= 0) pos[x * nm + mmap[m0[b]]] = uint16_t(lane);
+        if (m1[b] >= 0) pos[x * nm + mmap[m1[b]]] = uint16_t(lane + 64);
+    }
+    for (int x = wave; x < nn; x += kScLocalWaves) {
+        const bool ahead = x < kScAhead * kScLocalWaves;
+        const int64_t qa = R.q0 + qoff[x];
+        const int nl = qoff[x + 1] - qoff[x];
+        for (int l = (ahead ? 128 : 0) + lane; l < nl; l += 64) pos[x * nm + mmap[E.idx2[qa + l]]] = uint16_t(l);
+    }
+    __syncthreads();
     // E_K = T_K . P_K
-    const double *Pk = pk_blocks + R.pk;
-    const int tiles_m = (nm + 15) >> 4, tiles = ((nn + 15) >> 4) * tiles_m;
-    for (int tile = wave; tile < tiles; tile += kScLocalWaves) {
+    for (int tile = wave; tile < tiles_e; tile += kScLocalWaves) {
         const int x0 = (tile / tiles_m) << 4, j0 = (tile % tiles_m) << 4;
         const bool xa = x0 + li < nn, jb = j0 + li < nm;
         const double *trow = Tk + (xa ? x0 + li : 0) * tstride;
         const double *pcol = Pk + (jb ? j0 + li : 0);
+        // the next tile's part of P_K, fetched while this tile is computed
+        double bnext[kScDepth];
+        {
+            const int tn = tile + kScLocalWaves;
+            const int jn = (tn % tiles_m) << 4;
+            const bool jnb = tn < tiles_e && jn + li < nm;
+#pragma unroll
+            for (int kb = 0; kb < kScDepth; ++kb) {
+                const int k = 4 * kb + lk;
+                bnext[kb] = (jnb && k < ns) ? Pk[int64_t(k) * nm + jn + li] : 0.0;
+            }
+        }
         sc_v4d acc = {0.0, 0.0, 0.0, 0.0};
-        for (int k0 = 0; k0 < ns; k0 += 4) {
+#pragma unroll
+        for (int kb = 0; kb < kScDepth; ++kb) {
+            if (4 * kb < ns) {
+                const int k = 4 * kb + lk;
+                const double av = (xa && k < ns) ? trow[k < ns ? k : 0] : 0.0;
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bpre[kb], acc, 0, 0, 0);
+            }
+        }
+        for (int k0 = 4 * kScDepth; k0 < ns; k0 += 4) {                 // more than 4 * kScDepth slots
             const int k = k0 + lk;
             const bool kk = k < ns;
             const double av = (xa && kk) ? trow[kk ? k : 0] : 0.0;
@@ -496,6 +562,8 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
                 }
             }
         }
+#pragma unroll
+        for (int kb = 0; kb < kScDepth; ++kb) bpre[kb] = bnext[kb];
     }
 }
 
@@ -861,10 +929,10 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
         const int64_t ns_pad = plan->sc_max_slots | 1, rows_pad = rows_max | 1;
         int64_t at = 0;
         int64_t o_cd, o_t, o_pos, o_lval, o_rowptr, o_c0, o_clen, o_qoff, o_mmap, o_umap;
-        at = up16(8 * ik); o_cd = at;
+        at = up16(std::max(8 * ik, posb)); o_cd = at;           // I_K, later the leaf positions
         at = up16(at + 8 * nn_max * rows_pad); o_t = at;
-        at = up16(at + 8 * nn_max * ns_pad); o_pos = at;
-        at = up16(at + posb); o_lval = at;
+        at = up16(at + 8 * nn_max * ns_pad); o_pos = 0;
+        o_lval = at;
         at = up16(at + 8 * nn_max); o_rowptr = at;
         at = up16(at + 4 * (rows_max + 1)); o_c0 = at;
         at = up16(at + 4 * nn_max); o_clen = at;
