@@ -30,7 +30,7 @@ KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "spchain3": ["kernels_spchain3.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
                 "ttmc3": "ttmc3_mfma_kernel<4,2>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
-                "spchain3": "spchain3_kernel",
+                "spchain3": "spchain3_local_kernel",
                 "generic": "generic_stmt_kernel (one launch per statement)"}
 # what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they
 # compute (HBM); the order-4 TTMc and the three-tensor network are dense contractions per fiber
@@ -215,7 +215,7 @@ def cpu_baseline(wl, budget_nnz):
         I, C, P, L = (wl.sparse[k] for k in "ICPL")
         as_np = lambda t: ([c.cpu().numpy() for c in t.coords], t.vals.cpu().numpy())
         n_K = wl.params["dims"][0]
-        ks = sorted(set(int(k) for k in torch.linspace(0, n_K - 1, 6 if n_K > 1000 else n_K)))
+        ks = sorted(set(int(k) for k in torch.linspace(0, n_K - 1, 128 if n_K > 1000 else n_K)))
         Inp = as_np(I)
         in_sample = int(sum((Inp[0][0] == k).sum() for k in ks))
         t0 = time.perf_counter()

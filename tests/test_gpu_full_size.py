@@ -246,3 +246,52 @@ def test_config4_three_tensor_network_full_size():
     err = oracle.rel_err(out[rows_i].cpu().numpy(), want, S_abs)
     _say("  rel err %.3e" % err)
     assert err <= TOL
+
+
+def test_config6_sparse_chain_full_size_sampled_slices():
+    """The sparse chain of Sec. 5.1 at the size the benchmark times (32 x 32 lattice), both forms:
+    structure and values of sampled slices K against the dense-slice reference."""
+    from oracle import spsp
+    from paper_2401_04836_amd import schedules as S
+    _say("config 6 full size: generate")
+    wl = w.make(6, device="cuda")
+    dims = wl.params["dims"]
+    I, C, P, L = (wl.sparse[k] for k in "ICPL")
+    as_np = lambda t: ([c.cpu().numpy() for c in t.coords], t.vals.cpu().numpy())
+    nI, nC, nP, nL = as_np(I), as_np(C), as_np(P), as_np(L)
+    hI = cst.build_csf(I.coords, I.vals, I.dims, [0, 1, 2])
+    hC = cst.build_csf(C.coords, C.vals, C.dims, [1, 0])
+    hP = cst.build_csf(P.coords, P.vals, P.dims, [1, 0])
+    hL = cst.build_csf(L.coords, L.vals, L.dims, [0, 1])
+    Ks = [0, 517, 7001, 9999, dims[0] - 1]
+    for form, text, ops, Lx in (("unrestricted", S.SPCHAIN3, [("I", hI), ("C", hC), ("P", hP)], None),
+                                ("restricted", S.SPCHAIN3_RESTRICTED, [("I", hI), ("C", hC), ("L", hL), ("P", hP)], nL)):
+        pl = cst.plan(text, ops)
+        _say("config 6 %s: %s" % (form, pl.describe().split("|")[0]))
+        assert "kernel=block-local" in pl.describe()
+        vals = cst.execute(pl, [])
+        torch.cuda.synchronize()
+        E = pl.output_csf()
+        i0, p0, _ = E.export(0)
+        i1, p1, _ = E.export(1)
+        i2, _, _ = E.export(2)
+        ref = spsp.chain3(nI, nC, nP, dims, Lx, K_values=Ks)
+        worst = 0.0
+        for K in Ks:
+            want, S_abs, N = ref[K]
+            r = int(torch.searchsorted(i0, torch.tensor([K], device=i0.device, dtype=i0.dtype))[0])
+            G = np.zeros_like(want)
+            M = np.zeros(want.shape, dtype=bool)
+            if r < i0.numel() and int(i0[r]) == K:
+                na, nb = int(p0[r]), int(p0[r + 1])
+                qa, qb = int(p1[na]), int(p1[nb])
+                counts = (p1[na + 1:nb + 1] - p1[na:nb]).cpu().numpy()
+                ii = np.repeat(i1[na:nb].cpu().numpy(), counts)
+                mm = i2[qa:qb].cpu().numpy()
+                G[ii, mm] = vals[qa:qb].cpu().numpy()
+                M[ii, mm] = True
+            np.testing.assert_array_equal(M, N, err_msg="structure of E[%d]" % K)
+            worst = max(worst, oracle.rel_err(G, want, S_abs))
+        _say("  %d result nonzeros, sampled K %s, rel err %.3e" % (pl.n_rows, Ks, worst))
+        assert worst <= TOL
+        del pl, vals
