@@ -166,6 +166,33 @@ conststn_status conststn_schedule_check(const char *schedule, const int *fusion,
                                         const conststn_operand_desc *operands, char *buf,
                                         size_t len, int *reduced_orders);
 
+/* Host-only: schedule search -- the question of Sec. 3 asked for l = 1, 2, ... until it has an answer.
+ * tree        statements "OUT[..] = A[..] * B[..]" separated by ';', WITHOUT loop orders, forming
+ *             a tree (every intermediate consumed once; any statement order).  At most 6
+ *             statements of at most 8 indices each; every operand referenced once.
+ * operands    as for conststn_schedule_check, CSF operands by structure only (csf = NULL); their
+ *             extents follow the order of the reference in `tree`
+ * flags       0: a reference to a CSF operand lists its MODES and the level order is chosen (the
+ *             dp variables of Sec. 3.2); CONSTSTN_SEARCH_KEEP_LAYOUT: it is a level order to keep
+ * max_order   stop after this l (0: no bound other than the largest intermediate)
+ * buf, len    receives a schedule in the form conststn_plan takes: statements in the order found,
+ *             CSF references rewritten in level order, one loop order each
+ * order_found receives the smallest l for which every intermediate has order <= l after fusion
+ * level_modes NULL or n_operands * CONSTSTN_MAX_ORDER ints: for operand o, entry
+ *             [o * CONSTSTN_MAX_ORDER + level] = position in the tree's reference of the mode stored
+ *             at that level (-1 beyond the operand's order) -- pass it, composed with the modes of
+ *             the reference, as mode_order to conststn_build_csf
+ * The space of Sec. 3.2 (topological orders x loop permutations; layouts follow the loops) is
+ * enumerated with pruning instead of being given to a solver.  Among the schedules for the smallest
+ * l found within a bounded walk the one with the fewest statements whose summed index is the
+ * innermost loop, then with the smallest intermediates, is returned.  CONSTSTN_ESCHED when layouts
+ * that were fixed admit no schedule up to max_order. */
+#define CONSTSTN_SEARCH_KEEP_LAYOUT 1u
+conststn_status conststn_schedule_search(const char *tree, int n_operands,
+                                         const conststn_operand_desc *operands, unsigned flags,
+                                         int max_order, char *buf, size_t len, int *order_found,
+                                         int *level_modes);
+
 /* Output shape: n_rows row blocks of row_elems fp64 each, row-major.  Without
  * CONSTSTN_OUT_COMPACT n_rows is the extent of the output's first index (rows of empty
  * slices are zero); with it n_rows is the number of nonempty root indices. */

@@ -22,7 +22,7 @@ OPERAND_CSF, OPERAND_DENSE = 0, 1
 
 EXPORTED_SYMBOLS = [
     "conststn_build_csf", "conststn_csf_info", "conststn_csf_export", "conststn_csf_destroy",
-    "conststn_plan", "conststn_schedule_check", "conststn_plan_output_size",
+    "conststn_plan", "conststn_schedule_check", "conststn_schedule_search", "conststn_plan_output_size",
     "conststn_plan_output_rows", "conststn_plan_output_csf", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
     "conststn_plan_profile", "conststn_plan_kernel_times",
@@ -62,6 +62,8 @@ def _load():
                                 ctypes.c_uint, ctypes.POINTER(vp)]
     L.conststn_schedule_check.argtypes = [ctypes.c_char_p, ip, ctypes.c_int, ctypes.POINTER(_OperandDesc),
                                           ctypes.c_char_p, ctypes.c_size_t, ip]
+    L.conststn_schedule_search.argtypes = [ctypes.c_char_p, ctypes.c_int, ctypes.POINTER(_OperandDesc), ctypes.c_uint,
+                                           ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t, ip, ip]
     L.conststn_plan_output_size.argtypes = [vp, i64p, i64p]
     L.conststn_plan_output_rows.argtypes = [vp, ctypes.POINTER(vp), i64p]
     L.conststn_plan_output_csf.argtypes = [vp, ctypes.POINTER(vp)]
@@ -228,6 +230,24 @@ def schedule_check(schedule, operands, fusion=None):
     cf = (ctypes.c_int * len(fusion))(*fusion) if fusion is not None else None
     _check(_lib.conststn_schedule_check(schedule.encode(), cf, len(operands), descs, buf, len(buf), red))
     return buf.value.decode(), [red[i] for i in range(nst)]
+
+
+SEARCH_KEEP_LAYOUT = 1
+
+
+def schedule_search(tree, operands, flags=0, max_order=0):
+    """conststn_schedule_search (host only): returns (schedule_text, l, level_modes) where
+    level_modes[o] lists, per level of operand o, the position of its mode in the tree's reference."""
+    descs, keep = _make_descs(operands)
+    buf = ctypes.create_string_buffer(1 << 16)
+    l = ctypes.c_int()
+    modes = (ctypes.c_int * (len(operands) * MAX_ORDER))()
+    _check(_lib.conststn_schedule_search(tree.encode(), len(operands), descs, flags, max_order, buf, len(buf),
+                                         ctypes.byref(l), modes))
+    out = []
+    for o in range(len(operands)):
+        out.append([modes[o * MAX_ORDER + d] for d in range(MAX_ORDER) if modes[o * MAX_ORDER + d] >= 0])
+    return buf.value.decode(), l.value, out
 
 
 class Plan:

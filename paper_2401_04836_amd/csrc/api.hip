@@ -309,6 +309,49 @@ conststn_status conststn_schedule_check(const char *schedule, const int *fusion,
     return CONSTSTN_OK;
 }
 
+conststn_status conststn_schedule_search(const char *tree, int n_operands, const conststn_operand_desc *operands,
+                                         unsigned flags, int max_order, char *buf, size_t len, int *order_found,
+                                         int *level_modes) {
+    clear_error();
+    if (!tree) { set_error("tree is null"); return CONSTSTN_EINVAL; }
+    if (flags & ~CONSTSTN_SEARCH_KEEP_LAYOUT) { set_error("unknown flag bits"); return CONSTSTN_EINVAL; }
+    for (int o = 0; o < n_operands; ++o)
+        if (operands[o].kind == CONSTSTN_OPERAND_CSF && operands[o].csf) {
+            set_error("describe CSF operands by structure (csf = NULL, order, extents in the order of the reference)");
+            return CONSTSTN_EINVAL;
+        }
+    Schedule found;
+    std::vector<std::vector<int>> modes;
+    int l = 0;
+    CST_TRY(search_schedule(tree, n_operands, operands, (flags & CONSTSTN_SEARCH_KEEP_LAYOUT) != 0, max_order, found, &l, modes));
+    const std::string text = schedule_text(found);
+    // the result must pass the same checks as any schedule handed to conststn_plan
+    std::vector<conststn_operand_desc> permuted(operands, operands + n_operands);
+    for (int o = 0; o < n_operands; ++o)
+        for (int d = 0; d < operands[o].order; ++d) permuted[size_t(o)].dims[d] = operands[o].dims[modes[size_t(o)][size_t(d)]];
+    Schedule check;
+    CST_TRY(parse_schedule(text.c_str(), check));
+    conststn_status st = validate_schedule(check, nullptr, n_operands, permuted.data());
+    if (st != CONSTSTN_OK) {
+        std::string why = get_error();
+        set_error("internal: the schedule found (%s) fails the legality check: %s", text.c_str(), why.c_str());
+        return CONSTSTN_EINVAL;
+    }
+    for (size_t p = 0; p + 1 < check.stmts.size(); ++p)
+        if (check.stmts[p].reduced_order > l) { set_error("internal: the schedule found leaves an intermediate of order %d > %d", check.stmts[p].reduced_order, l); return CONSTSTN_EINVAL; }
+    if (buf && len > 0) {
+        if (text.size() + 1 > len) { set_error("buffer of %zu bytes is too small for the schedule (%zu)", len, text.size() + 1); return CONSTSTN_EINVAL; }
+        std::strncpy(buf, text.c_str(), len - 1);
+        buf[len - 1] = 0;
+    }
+    if (order_found) *order_found = l;
+    if (level_modes)
+        for (int o = 0; o < n_operands; ++o)
+            for (int d = 0; d < CONSTSTN_MAX_ORDER; ++d)
+                level_modes[o * CONSTSTN_MAX_ORDER + d] = d < operands[o].order ? modes[size_t(o)][size_t(d)] : -1;
+    return CONSTSTN_OK;
+}
+
 conststn_status conststn_plan(const char *schedule, const int *fusion, int n_operands,
                               const conststn_operand_desc *operands, unsigned flags,
                               conststn_plan_t **out) {

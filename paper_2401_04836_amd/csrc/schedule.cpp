@@ -76,22 +76,23 @@ conststn_status parse_schedule(const char *text, Schedule &sched) {
     sched.stmts.clear();
     while (!c.at_end()) {
         Stmt st;
-        if (!parse_ref(c, st.out) || !c.eat('=') || !parse_ref(c, st.a) || !c.eat('*') ||
-            !parse_ref(c, st.b) || !c.eat('|')) {
+        if (!parse_ref(c, st.out) || !c.eat('=') || !parse_ref(c, st.a) || !c.eat('*') || !parse_ref(c, st.b)) {
             set_error("malformed statement %zu near offset %zu: expected OUT[..] = A[..] * B[..] | loops",
                       sched.stmts.size(), c.i);
             return CONSTSTN_EINVAL;
         }
-        for (;;) {
-            std::string id;
-            if (!c.ident(id)) {
-                if (st.loops.empty() && (c.at_end() || text[c.i] == ';')) break;   // no loops
-                set_error("malformed loop order in statement %zu", sched.stmts.size());
-                return CONSTSTN_EINVAL;
+        // the loop order may be left out (a contraction tree handed to the schedule search)
+        if (c.eat('|'))
+            for (;;) {
+                std::string id;
+                if (!c.ident(id)) {
+                    if (st.loops.empty() && (c.at_end() || text[c.i] == ';')) break;   // no loops
+                    set_error("malformed loop order in statement %zu", sched.stmts.size());
+                    return CONSTSTN_EINVAL;
+                }
+                st.loops.push_back(id);
+                if (!c.eat(',')) break;
             }
-            st.loops.push_back(id);
-            if (!c.eat(',')) break;
-        }
         sched.stmts.push_back(st);
         if (!c.eat(';')) break;
     }

@@ -50,6 +50,17 @@ conststn_status parse_schedule(const char *text, Schedule &sched);
 conststn_status validate_schedule(Schedule &sched, const int *fusion, int n_operands,
                                   const conststn_operand_desc *operands);
 
+// Schedule search (search.cpp): the smallest l for which the tree given in `tree` (statements without
+// loop orders) has a legal schedule with every intermediate of order <= l, and one such schedule.
+// keep_layout: references to CSF operands are level orders to keep; otherwise they list the modes
+// and the level order is chosen.  level_modes[o][level] = position in the tree's reference.
+conststn_status search_schedule(const char *tree, int n_operands, const conststn_operand_desc *operands,
+                                bool keep_layout, int max_order, Schedule &result, int *order_found,
+                                std::vector<std::vector<int>> &level_modes);
+
+// "OUT[..] = A[..] * B[..] | loops ; ..." of a schedule
+std::string schedule_text(const Schedule &s);
+
 // Lowering of a sequence of <A, pi> into nested forall / where text (Sec. 4.2, Algorithm 1).
 std::string lower_schedule(const Schedule &sched);
 
