@@ -24,6 +24,11 @@
 // nodes meet in one result element, adds it with a hardware fp64 atomic.  Statements whose two
 // inputs are both dense and not lifted use the first kernel with an empty prefix.
 //
+// A sum over more than CONSTSTN_GENERIC_SPAN nodes below one result node (a power-law slice) is
+// not left to a single thread: the node's children are cut into segments, the first kernel writes
+// one partial sum per (segment, element) and a second pass adds them in segment order --
+// still a fixed order.
+//
 // Intermediates are held whole in device memory.  This is the slow, always-applicable path; the
 // tuned kernels of the other files take the schedules they match.
 #include <algorithm>
@@ -36,9 +41,11 @@ namespace cst {
 __global__ void __launch_bounds__(256)
 generic_stmt_kernel(GenStmt g) {
     const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (gid >= g.out_nodes * g.out_block) return;
-    const int64_t p = gid / g.out_block;
-    int64_t rem = gid - p * g.out_block;
+    const bool segmented = g.n_segs > 0;
+    if (gid >= (segmented ? g.n_segs : g.out_nodes) * g.out_block) return;
+    const int64_t unit = gid / g.out_block;                 // a result node, or a segment of one
+    const int64_t p = segmented ? g.seg[3 * unit] : unit;
+    int64_t rem = gid - unit * g.out_block;
     int64_t in_off = 0, f_off0 = 0, out_off = 0;
     for (int q = g.n_out - 1; q >= 0; --q) {
         const int64_t o = rem % g.extent[q];
@@ -72,10 +79,22 @@ generic_stmt_kernel(GenStmt g) {
     const int D = g.d_in - g.d_out;               // CSF levels summed over
     if (D == 0) {
         inner(p, f_off0, acc);
+    } else if (D == 1 && nr == 0) {
+        // the common shape (one level summed, no dense index summed) without the bookkeeping arrays,
+        // which the compiler can only keep in scratch memory
+        int64_t c0, c1;
+        if (segmented) { c0 = g.seg[3 * unit + 1]; c1 = g.seg[3 * unit + 2]; }
+        else if (g.d_out == 0) { c0 = 0; c1 = g.roots; }
+        else { c0 = g.ptr[g.d_out - 1][p]; c1 = g.ptr[g.d_out - 1][p + 1]; }
+        const int32_t *ix = g.idx[g.d_out];
+        const int64_t fs = g.f_level_stride[g.d_out];
+        for (int64_t c = c0; c < c1; ++c)
+            acc = fma(g.in[c * g.in_block + in_off], g.f[f_off0 + int64_t(ix[c]) * fs], acc);
     } else {
         int64_t cur[CONSTSTN_MAX_ORDER], end[CONSTSTN_MAX_ORDER], foff[CONSTSTN_MAX_ORDER];
         int l = 0;
-        if (g.d_out == 0) { cur[0] = 0; end[0] = g.roots; }
+        if (segmented) { cur[0] = g.seg[3 * unit + 1]; end[0] = g.seg[3 * unit + 2]; }
+        else if (g.d_out == 0) { cur[0] = 0; end[0] = g.roots; }
         else { cur[0] = g.ptr[g.d_out - 1][p]; end[0] = g.ptr[g.d_out - 1][p + 1]; }
         foff[0] = f_off0;
         for (;;) {
@@ -97,8 +116,41 @@ generic_stmt_kernel(GenStmt g) {
             }
         }
     }
+    if (segmented) { g.partial[unit * g.out_block + out_off] = acc; return; }
     const int64_t row = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
     g.out[row * g.out_block + out_off] = acc;
+}
+
+// second pass of a long sum: the partial sums of each result node, added in segment order
+__global__ void __launch_bounds__(256)
+generic_segsum_kernel(GenStmt g) {
+    const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (gid >= g.out_nodes * g.out_block) return;
+    const int64_t p = gid / g.out_block, o = gid - p * g.out_block;
+    double acc = 0.0;
+    for (int64_t sg = g.seg_ptr[p]; sg < g.seg_ptr[p + 1]; ++sg) acc += g.partial[sg * g.out_block + o];
+    const int64_t row = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
+    g.out[row * g.out_block + o] = acc;
+}
+
+// segments of kGenSegment children: how many per result node, then their ranges
+constexpr int64_t kGenSegment = 256;
+__global__ void generic_seg_count_kernel(const int64_t *ptr, int64_t nodes, int64_t roots, int64_t *count) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= nodes) return;
+    const int64_t children = ptr ? ptr[p + 1] - ptr[p] : roots;
+    count[p] = (children + kGenSegment - 1) / kGenSegment;
+}
+__global__ void generic_seg_fill_kernel(const int64_t *ptr, int64_t nodes, int64_t roots, const int64_t *seg_ptr, int64_t *seg) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= nodes) return;
+    const int64_t c0 = ptr ? ptr[p] : 0, c1 = ptr ? ptr[p + 1] : roots;
+    int64_t sg = seg_ptr[p];
+    for (int64_t c = c0; c < c1; c += kGenSegment, ++sg) {
+        seg[3 * sg] = p;
+        seg[3 * sg + 1] = c;
+        seg[3 * sg + 2] = c + kGenSegment < c1 ? c + kGenSegment : c1;
+    }
 }
 
 __global__ void __launch_bounds__(256)
@@ -148,6 +200,15 @@ generic_node_kernel(GenStmt g) {
     }
     if (g.atomic) unsafeAtomicAdd(g.out + out_off, acc);
     else g.out[out_off] = acc;
+}
+
+// largest number of depth-d_in nodes below one depth-d_out node (d_out >= 1)
+__global__ void generic_span_kernel(GenStmt g, int d_out, int d_in, unsigned long long *result) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= g.nodes[d_out - 1]) return;
+    int64_t lo = p, hi = p + 1;
+    for (int L = d_out - 1; L <= d_in - 2; ++L) { lo = g.ptr[L][lo]; hi = g.ptr[L][hi]; }
+    atomicMax(result, (unsigned long long)(hi - lo));
 }
 
 namespace {
@@ -223,9 +284,32 @@ conststn_status build_generic(conststn_plan_s *plan) {
         xdepth[p] = d >= 1 ? d : -1;
     }
 
+    // one thread summing a whole subtree is fine for short fibers and hopeless for a power-law slice:
+    // beyond span_limit nodes below one result node the sum is cut into segments (two passes)
+    const int64_t span_limit = env_int("CONSTSTN_GENERIC_SPAN", 4096);
+    std::map<std::pair<int, int>, int64_t> span_cache;
+    conststn_status span_status = CONSTSTN_OK;
+    auto max_span = [&](int d_out, int d_in) -> int64_t {
+        if (d_out == 0) return csf->nodes[d_in - 1];
+        const auto key = std::make_pair(d_out, d_in);
+        auto it = span_cache.find(key);
+        if (it != span_cache.end()) return it->second;
+        GenStmt g{};
+        for (int l = 0; l < n; ++l) { g.nodes[l] = csf->nodes[l]; g.ptr[l] = l + 1 < n ? csf->ptr[l].p : nullptr; }
+        DevBuf<unsigned long long> dmax;
+        unsigned long long h = 0;
+        if (dmax.alloc(1) != CONSTSTN_OK || hipMemset(dmax.p, 0, sizeof(h)) != hipSuccess) { span_status = CONSTSTN_ENOMEM; return 0; }
+        if (csf->nodes[d_out - 1] > 0)
+            generic_span_kernel<<<dim3(unsigned((csf->nodes[d_out - 1] + 255) / 256)), dim3(256)>>>(g, d_out, d_in, dmax.p);
+        if (hipMemcpy(&h, dmax.p, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) { span_status = CONSTSTN_EHIP; return 0; }
+        span_cache[key] = int64_t(h);
+        return int64_t(h);
+    };
+
     std::vector<GenTensor> result(m);             // the tensor each statement produces
     plan->gen.clear();
     plan->gen_buffers.clear();
+    plan->gen_tables.clear();
     plan->gen_zero_out = false;
     std::vector<int64_t> buffer_elems;
     auto tensor_of_ref = [&](const Ref &r, int src, int op, GenTensor &t) {
@@ -279,6 +363,8 @@ conststn_status build_generic(conststn_plan_s *plan) {
             if (keeps_beyond_prefix(st.out.idx, d_out, d_node) || (last && d_out > 1)) { kind = 1; out_by_prefix = false; d_out = 0; }
             else if (fa.depth > 0 || f_uses_kept) kind = 1;
         }
+        const bool long_sum = kind == 0 && d_node > 0 && d_out < d_node && max_span(d_out, d_node) > span_limit;
+        if (span_status != CONSTSTN_OK) { set_error("could not measure the subtree sizes of the CSF operand"); return span_status; }
         auto is_level = [&](const std::string &nm) { const int L = level_of(nm); return L >= 0 && L < d_node; };
 
         // dense loop indices: the result's first, then the summed ones
@@ -348,6 +434,31 @@ conststn_status build_generic(conststn_plan_s *plan) {
             g.idx[l] = csf->idx[l].p;
             g.ptr[l] = l + 1 < n ? csf->ptr[l].p : nullptr;
         }
+        if (long_sum) {
+            // the children of every result node in segments of kGenSegment
+            const int64_t on = g.out_nodes;
+            const int64_t *cptr = d_out > 0 ? csf->ptr[d_out - 1].p : nullptr;
+            DevBuf<int64_t> count;
+            CST_TRY(count.alloc(size_t(on)));
+            plan->gen_tables.emplace_back(new DevBuf<int64_t>());
+            DevBuf<int64_t> &sptr = *plan->gen_tables.back();
+            CST_TRY(sptr.alloc(size_t(on + 1)));
+            generic_seg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], count.p);
+            CST_HIP(hipGetLastError());
+            int64_t n_segs = 0;
+            CST_TRY(exscan(count.p, sptr.p, on, &n_segs));
+            CST_HIP(hipMemcpy(sptr.p + on, &n_segs, sizeof(int64_t), hipMemcpyHostToDevice));
+            plan->gen_tables.emplace_back(new DevBuf<int64_t>());
+            DevBuf<int64_t> &seg = *plan->gen_tables.back();
+            CST_TRY(seg.alloc(size_t(3 * n_segs)));
+            generic_seg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], sptr.p, seg.p);
+            CST_HIP(hipGetLastError());
+            CST_HIP(hipDeviceSynchronize());
+            g.n_segs = n_segs;
+            g.seg_table = int(plan->gen_tables.size()) - 2;
+            g.partial_buffer = int(buffer_elems.size());
+            buffer_elems.push_back(n_segs * g.out_block);
+        }
         // the result
         GenTensor &res = result[p];
         res.depth = out_by_prefix ? d_out : 0;
@@ -407,13 +518,24 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         g.out = g.out_buffer >= 0 ? plan->gen_buffers[size_t(g.out_buffer)]->p : out;
         if (!g.in || !g.f || !g.out) { set_error("internal: unresolved tensor in the generic executor"); return CONSTSTN_EINVAL; }
         if (g.atomic && g.out_buffer >= 0) CST_TRY(zero_fill(g.out, g.out_elems, stream));
-        const int64_t total = g.kind == 1 ? g.nodes[g.d_node - 1] * g.out_threads : g.out_nodes * g.out_block;
+        if (g.n_segs > 0) {
+            g.seg_ptr = plan->gen_tables[size_t(g.seg_table)]->p;
+            g.seg = plan->gen_tables[size_t(g.seg_table) + 1]->p;
+            g.partial = plan->gen_buffers[size_t(g.partial_buffer)]->p;
+        }
+        const int64_t total = g.kind == 1 ? g.nodes[g.d_node - 1] * g.out_threads
+                                          : (g.n_segs > 0 ? g.n_segs : g.out_nodes) * g.out_block;
         if (total == 0) continue;
         if (total > (int64_t(1) << 31) * 256) { set_error("statement result too large for one launch"); return CONSTSTN_EUNSUPPORTED; }
         const dim3 grid(unsigned((total + 255) / 256)), block(256);
         if (g.kind == 1) generic_node_kernel<<<grid, block, 0, stream>>>(g);
         else generic_stmt_kernel<<<grid, block, 0, stream>>>(g);
         CST_HIP(hipGetLastError());
+        if (g.kind == 0 && g.n_segs > 0) {
+            const int64_t t2 = g.out_nodes * g.out_block;
+            generic_segsum_kernel<<<dim3(unsigned((t2 + 255) / 256)), block, 0, stream>>>(g);
+            CST_HIP(hipGetLastError());
+        }
     }
     return CONSTSTN_OK;
 }

@@ -48,6 +48,13 @@ struct GenStmt {
     const double *in, *f;
     double *out;
     int in_operand, in_buffer, f_operand, f_buffer, out_buffer;   // resolved to pointers at launch
+    // kind 0, long sums: the children of a result node cut into segments, one thread per (segment,
+    // element) writes a partial sum, a second pass adds the partial sums of each node in order
+    int64_t n_segs;
+    const int64_t *seg;                        // [3 * n_segs] result node, first child, end child
+    const int64_t *seg_ptr;                    // [out_nodes + 1] segments of each result node
+    double *partial;                           // [n_segs * out_block]
+    int seg_table, partial_buffer;             // resolved to pointers at launch
 };
 
 // One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1
@@ -167,6 +174,7 @@ struct conststn_plan_s {
     // generic executor: one entry per statement, intermediates held whole
     std::vector<cst::GenStmt> gen;
     std::vector<std::unique_ptr<cst::DevBuf<double>>> gen_buffers;
+    std::vector<std::unique_ptr<cst::DevBuf<int64_t>>> gen_tables;   // segment tables of long sums
     bool gen_rooted = false;               // the result has one row block per root index
     bool gen_zero_out = false;             // the last statement adds into the result: cleared before every run
 
