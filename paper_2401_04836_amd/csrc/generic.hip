@@ -198,8 +198,18 @@ generic_node_kernel(GenStmt g) {
         }
         if (q < g.n_out) break;
     }
-    if (g.atomic) unsafeAtomicAdd(g.out + out_off, acc);
+    if (g.atomic) unsafeAtomicAdd(g.out + (g.copies > 1 ? int64_t(blockIdx.x % unsigned(g.copies)) * g.out_elems : 0) + out_off, acc);
     else g.out[out_off] = acc;
+}
+
+// the private copies of an added-into result, summed in copy order
+__global__ void __launch_bounds__(256)
+generic_copysum_kernel(const double *copies, int n_copies, int64_t elems, double *out) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x >= elems) return;
+    double acc = 0.0;
+    for (int c = 0; c < n_copies; ++c) acc += copies[int64_t(c) * elems + x];
+    out[x] = acc;
 }
 
 // largest number of depth-d_in nodes below one depth-d_out node (d_out >= 1)
@@ -459,6 +469,15 @@ conststn_status build_generic(conststn_plan_s *plan) {
             g.partial_buffer = int(buffer_elems.size());
             buffer_elems.push_back(n_segs * g.out_block);
         }
+        if (g.atomic) {
+            const int64_t bytes = g.out_elems * 8;
+            int copies = int(std::min<int64_t>(64, (int64_t(512) << 20) / std::max<int64_t>(bytes, 1)));
+            if (copies >= 2 && !(last && out_by_prefix && d_out == 1 && !plan->compact)) {     // rows scattered by root index keep one copy
+                g.copies = copies;
+                g.copies_buffer = int(buffer_elems.size());
+                buffer_elems.push_back(g.out_elems * copies);
+            }
+        }
         // the result
         GenTensor &res = result[p];
         res.depth = out_by_prefix ? d_out : 0;
@@ -517,7 +536,13 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         g.f = where(g.f_operand, g.f_buffer);
         g.out = g.out_buffer >= 0 ? plan->gen_buffers[size_t(g.out_buffer)]->p : out;
         if (!g.in || !g.f || !g.out) { set_error("internal: unresolved tensor in the generic executor"); return CONSTSTN_EINVAL; }
-        if (g.atomic && g.out_buffer >= 0) CST_TRY(zero_fill(g.out, g.out_elems, stream));
+        double *final_out = g.out;
+        if (g.copies > 1) {
+            g.out = plan->gen_buffers[size_t(g.copies_buffer)]->p;
+            CST_TRY(zero_fill(g.out, g.out_elems * g.copies, stream));
+        } else if (g.atomic && g.out_buffer >= 0) {
+            CST_TRY(zero_fill(g.out, g.out_elems, stream));
+        }
         if (g.n_segs > 0) {
             g.seg_ptr = plan->gen_tables[size_t(g.seg_table)]->p;
             g.seg = plan->gen_tables[size_t(g.seg_table) + 1]->p;
@@ -525,13 +550,18 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         }
         const int64_t total = g.kind == 1 ? g.nodes[g.d_node - 1] * g.out_threads
                                           : (g.n_segs > 0 ? g.n_segs : g.out_nodes) * g.out_block;
-        if (total == 0) continue;
         if (total > (int64_t(1) << 31) * 256) { set_error("statement result too large for one launch"); return CONSTSTN_EUNSUPPORTED; }
         const dim3 grid(unsigned((total + 255) / 256)), block(256);
-        if (g.kind == 1) generic_node_kernel<<<grid, block, 0, stream>>>(g);
-        else generic_stmt_kernel<<<grid, block, 0, stream>>>(g);
-        CST_HIP(hipGetLastError());
-        if (g.kind == 0 && g.n_segs > 0) {
+        if (total > 0) {
+            if (g.kind == 1) generic_node_kernel<<<grid, block, 0, stream>>>(g);
+            else generic_stmt_kernel<<<grid, block, 0, stream>>>(g);
+            CST_HIP(hipGetLastError());
+        }
+        if (g.copies > 1 && g.out_elems > 0) {
+            generic_copysum_kernel<<<dim3(unsigned((g.out_elems + 255) / 256)), block, 0, stream>>>(g.out, g.copies, g.out_elems, final_out);
+            CST_HIP(hipGetLastError());
+        }
+        if (g.kind == 0 && g.n_segs > 0 && total > 0) {
             const int64_t t2 = g.out_nodes * g.out_block;
             generic_segsum_kernel<<<dim3(unsigned((t2 + 255) / 256)), block, 0, stream>>>(g);
             CST_HIP(hipGetLastError());

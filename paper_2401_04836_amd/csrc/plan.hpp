@@ -55,6 +55,9 @@ struct GenStmt {
     const int64_t *seg_ptr;                    // [out_nodes + 1] segments of each result node
     double *partial;                           // [n_segs * out_block]
     int seg_table, partial_buffer;             // resolved to pointers at launch
+    // kind 1 with atomics: workgroups add into `copies` private copies of the result in turn, so that a
+    // result element every node meets in (a power-law index) is not one queue; a second pass adds the copies
+    int copies, copies_buffer;
 };
 
 // One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1
