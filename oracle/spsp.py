@@ -80,3 +80,22 @@ def pair4(E_coords, E_vals, dims):
     def shape4(G):                                       # [(i,m),(j,n)] -> [i,j,m,n]
         return G.reshape(n_i, n_m, n_i, n_m).transpose(0, 2, 1, 3)
     return shape4(Ed.T @ Ed), shape4(np.abs(Ed).T @ np.abs(Ed)), shape4((Ep.T @ Ep) > 0.5)
+
+
+def pair4_block(E_coords, E_vals, dims, i, j):
+    """One (i,j) block of V = E x E (Sec. 5.1, four-index integrals): V[i,j,:,:] = E_i^T . E_j with
+    E_i the n_K x n_m matrix of the entries E[K,i,m].  Returns (V_ij, S_ij, N_ij), each n_m x n_m."""
+    n_K, n_i, n_m = (int(d) for d in dims)
+    ek, ei, em = [np.asarray(c, dtype=np.int64) for c in E_coords]
+    ev = np.asarray(E_vals, dtype=np.float64)
+
+    def slab(x):
+        sel = ei == x
+        D = np.zeros((n_K, n_m), dtype=np.float64)
+        Pm = np.zeros((n_K, n_m), dtype=np.float64)
+        D[ek[sel], em[sel]] = ev[sel]
+        Pm[ek[sel], em[sel]] = 1.0
+        return D, Pm
+    Di, Pi = slab(i)
+    Dj, Pj = slab(j)
+    return Di.T @ Dj, np.abs(Di).T @ np.abs(Dj), (Pi.T @ Pj) > 0.5

@@ -142,6 +142,19 @@ def test_pair4_against_brute_force_and_symmetry():
     np.testing.assert_allclose(V, V.transpose(1, 0, 3, 2), rtol=0, atol=1e-13 * S.max())
 
 
+def test_pair4_block_is_a_block_of_pair4():
+    rng = np.random.default_rng(16)
+    n_K, n_i, n_m = 6, 4, 5
+    Ec, Ev = _rand_sparse(rng, (n_K, n_i, n_m), 50)
+    V, S, N = spsp.pair4(Ec, Ev, (n_K, n_i, n_m))
+    for i in range(n_i):
+        for j in range(n_i):
+            v, s, n = spsp.pair4_block(Ec, Ev, (n_K, n_i, n_m), i, j)
+            np.testing.assert_allclose(v, V[i, j], rtol=0, atol=1e-13 * max(1.0, S.max()))
+            np.testing.assert_allclose(s, S[i, j], rtol=1e-13, atol=0)
+            np.testing.assert_array_equal(n, N[i, j])
+
+
 def test_lattice_workload_has_the_stated_shape():
     from workloads.generators import make_lattice_chain
     wl = make_lattice_chain("t", 77, 5, 3, 6, 1.5, 2.0, 1.5, 2.5)
