@@ -206,6 +206,26 @@ static conststn_status match_spchain3(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// Four-index product of Sec. 5.1: one statement V[i,j,m,n] = Ea[i,K,m] * Eb[j,K,n], both operands CSF
+// tensors of order 3 referenced in level order, sparse result.
+static conststn_status match_sppair4(conststn_plan_s *plan) {
+    Schedule &s = plan->sched;
+    if (s.stmts.size() != 1 || s.operands.size() != 2) return CONSTSTN_EUNSUPPORTED;
+    const Stmt &p0 = s.stmts[0];
+    if (p0.op_a < 0 || p0.op_b < 0 || p0.op_a == p0.op_b) return CONSTSTN_EUNSUPPORTED;
+    const OperandInfo &oa = s.operands[p0.op_a], &ob = s.operands[p0.op_b];
+    if (oa.kind != CONSTSTN_OPERAND_CSF || ob.kind != CONSTSTN_OPERAND_CSF || oa.order != 3 || ob.order != 3) return CONSTSTN_EUNSUPPORTED;
+    if (p0.a.idx[1] != p0.b.idx[1]) return CONSTSTN_EUNSUPPORTED;
+    if (p0.out.idx != std::vector<std::string>{p0.a.idx[0], p0.b.idx[0], p0.a.idx[2], p0.b.idx[2]}) return CONSTSTN_EUNSUPPORTED;
+    if (std::set<std::string>{p0.a.idx[0], p0.a.idx[1], p0.a.idx[2], p0.b.idx[0], p0.b.idx[2]}.size() != 5) return CONSTSTN_EUNSUPPORTED;
+    if (plan->compact) { set_error("the result of the sparse product is sparse; the compact-rows flag does not apply"); return CONSTSTN_EINVAL; }
+    if (!oa.csf || !ob.csf) { set_error("CSF operand without handle"); return CONSTSTN_EINVAL; }
+    plan->family = FAM_SPPAIR4;
+    plan->X = oa.csf;
+    plan->W = ob.csf;
+    return CONSTSTN_OK;
+}
+
 // rank extents the tuned kernels are built for
 static bool tuned_kernel_fits(const conststn_plan_s *plan) {
     switch (plan->family) {
@@ -224,6 +244,7 @@ static const char *family_name(Family f) {
         case FAM_SPTN3: return "sptn3";
         case FAM_GENERIC: return "generic";
         case FAM_SPCHAIN3: return "spchain3";
+        case FAM_SPPAIR4: return "sppair4";
         default: return "none";
     }
 }
@@ -384,11 +405,17 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
         st = match_spchain3(plan);
         if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
     }
+    if (st == CONSTSTN_EUNSUPPORTED && plan->family == FAM_NONE) {
+        std::string why = get_error();
+        clear_error();
+        st = match_sppair4(plan);
+        if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
+    }
     // tuned kernels have rank limits; beyond them, and for every other tree over one CSF operand,
     // the generic executor takes over
     if (st == CONSTSTN_OK && !tuned_kernel_fits(plan)) st = CONSTSTN_EUNSUPPORTED;
     if (st == CONSTSTN_OK && env_int("CONSTSTN_FORCE_GENERIC", 0) == 1 && plan->family != FAM_SPTN3 &&
-        plan->family != FAM_SPCHAIN3)
+        plan->family != FAM_SPCHAIN3 && plan->family != FAM_SPPAIR4)
         st = CONSTSTN_EUNSUPPORTED;
     if (st == CONSTSTN_EUNSUPPORTED) {
         std::string why = get_error();
@@ -413,6 +440,7 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
         case FAM_TTMC4: CST_TRY(build_ttmc_tables(plan)); break;
         case FAM_SPTN3: CST_TRY(build_sptn3_tables(plan)); break;
         case FAM_SPCHAIN3: CST_TRY(build_spchain3_tables(plan)); break;
+        case FAM_SPPAIR4: CST_TRY(build_sppair4_tables(plan)); break;
         default: break;
     }
     char head[256];
@@ -531,6 +559,7 @@ conststn_status conststn_execute(const conststn_plan_t *plan, const double *cons
         case FAM_TTMC4: return launch_ttmc4(plan, dense_factors, out, st);
         case FAM_SPTN3: return launch_sptn3(plan, dense_factors, out, st);
         case FAM_SPCHAIN3: return launch_spchain3(plan, out, st);
+        case FAM_SPPAIR4: return launch_sppair4(plan, out, st);
         case FAM_GENERIC: return launch_generic(plan, dense_factors, out, st);
         default: set_error("plan has no kernel family"); return CONSTSTN_EINVAL;
     }

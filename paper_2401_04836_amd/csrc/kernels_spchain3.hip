@@ -732,6 +732,49 @@ static ScOut make_out(const conststn_plan_s *plan) {
     return o;
 }
 
+// Order-3 CSF tensor T (levels a > b > c): the distinct c under every root a, ascending (u_ptr over the
+// root nodes, u_list), found as the level-1 nodes of T re-sorted a > c > b, and for every leaf the
+// position of its c in the list of its root (16 bits).
+conststn_status csf3_leaf_universe(const conststn_csf_s *T, DevBuf<int64_t> &u_ptr, DevBuf<int32_t> &u_list,
+                                   DevBuf<uint16_t> &slot, int64_t *largest, std::vector<int64_t> *host_ptr) {
+    const hipStream_t st = nullptr;
+    if (T->order != 3) { set_error("internal: leaf universe of an order-%d tensor", T->order); return CONSTSTN_EINVAL; }
+    conststn_csf_s acb;
+    DevBuf<int32_t> ca, cb;
+    CST_TRY(ca.alloc(size_t(T->nnz)));
+    CST_TRY(cb.alloc(size_t(T->nnz)));
+    if (T->nnz) {
+        leaf_ancestor_index_kernel<<<grid_for(T->nnz), 256, 0, st>>>(3, 0, T->nnz, T->ptr[0].p, T->nodes[0], T->ptr[1].p,
+                                                                    T->nodes[1], T->idx[0].p, ca.p);
+        leaf_ancestor_index_kernel<<<grid_for(T->nnz), 256, 0, st>>>(3, 1, T->nnz, T->ptr[0].p, T->nodes[0], T->ptr[1].p,
+                                                                    T->nodes[1], T->idx[1].p, cb.p);
+    }
+    CST_HIP(hipGetLastError());
+    const int32_t *coords[3] = {ca.p, cb.p, T->idx[2].p};
+    const int64_t dims3[3] = {T->dims[T->mode_order[0]], T->dims[T->mode_order[1]], T->dims[T->mode_order[2]]};
+    const int mo[3] = {0, 2, 1};
+    CST_TRY(build_csf_device(3, dims3, T->nnz, coords, T->vals.p, mo, 0, st, &acb));
+    if (acb.nodes[0] != T->nodes[0]) { set_error("internal: re-sorted copy has %lld roots, the tensor has %lld", (long long)acb.nodes[0], (long long)T->nodes[0]); return CONSTSTN_EINVAL; }
+    CST_TRY(u_ptr.alloc(size_t(acb.nodes[0] + 1)));
+    CST_TRY(u_list.alloc(size_t(acb.nodes[1])));
+    CST_HIP(hipMemcpy(u_ptr.p, acb.ptr[0].p, size_t(acb.nodes[0] + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice));
+    if (acb.nodes[1])
+        CST_HIP(hipMemcpy(u_list.p, acb.idx[1].p, size_t(acb.nodes[1]) * sizeof(int32_t), hipMemcpyDeviceToDevice));
+    std::vector<int64_t> h(size_t(acb.nodes[0] + 1));
+    CST_HIP(hipMemcpy(h.data(), acb.ptr[0].p, h.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+    int64_t mx = 1;
+    for (size_t a = 0; a + 1 < h.size(); ++a) mx = std::max(mx, h[a + 1] - h[a]);
+    if (mx > 65534) { set_error("one root index joins %lld distinct innermost indices; they are numbered with 16 bits", (long long)mx); return CONSTSTN_EUNSUPPORTED; }
+    *largest = mx;
+    if (host_ptr) host_ptr->swap(h);
+    CST_TRY(slot.alloc(size_t(T->nnz)));
+    if (T->nnz)
+        leaf_slot_kernel<<<grid_for(T->nnz), 256, 0, st>>>(T->nnz, T->ptr[0].p, T->nodes[0], T->ptr[1].p, T->nodes[1], T->idx[2].p,
+                                                          u_ptr.p, u_list.p, slot.p);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
 conststn_status build_spchain3_tables(conststn_plan_s *plan) {
     const conststn_csf_s *I = plan->X, *C = plan->sc_C, *P = plan->sc_P, *L = plan->sc_L;
     const hipStream_t st = nullptr;
@@ -762,43 +805,13 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
     node_of_index_kernel<<<grid_for(P->nodes[0]), 256, 0, st>>>(P->idx[0].p, P->nodes[0], plan->sc_p_node_of_m.p);
     CST_HIP(hipGetLastError());
 
-    // distinct v under every K: the level-1 nodes of I re-sorted as (K > v > u)
+    // distinct v under every K, and the place of every leaf's v among them
     std::vector<int64_t> h_nu_ptr;
     {
-        conststn_csf_s kvu;
-        DevBuf<int32_t> cK, cu;
-        CST_TRY(cK.alloc(size_t(I->nnz)));
-        CST_TRY(cu.alloc(size_t(I->nnz)));
-        if (I->nnz) {
-            leaf_ancestor_index_kernel<<<grid_for(I->nnz), 256, 0, st>>>(3, 0, I->nnz, I->ptr[0].p, I->nodes[0], I->ptr[1].p,
-                                                                        I->nodes[1], I->idx[0].p, cK.p);
-            leaf_ancestor_index_kernel<<<grid_for(I->nnz), 256, 0, st>>>(3, 1, I->nnz, I->ptr[0].p, I->nodes[0], I->ptr[1].p,
-                                                                        I->nodes[1], I->idx[1].p, cu.p);
-        }
-        CST_HIP(hipGetLastError());
-        const int32_t *coords[3] = {cK.p, cu.p, I->idx[2].p};
-        const int64_t dims3[3] = {n_K, n_u, n_v};
-        const int mo[3] = {0, 2, 1};
-        CST_TRY(build_csf_device(3, dims3, I->nnz, coords, I->vals.p, mo, 0, st, &kvu));
-        if (kvu.nodes[0] != I->nodes[0]) { set_error("internal: re-sorted copy of I has %lld roots, I has %lld", (long long)kvu.nodes[0], (long long)I->nodes[0]); return CONSTSTN_EINVAL; }
-        CST_TRY(plan->sc_nu_ptr.alloc(size_t(kvu.nodes[0] + 1)));
-        CST_TRY(plan->sc_nu_list.alloc(size_t(kvu.nodes[1])));
-        CST_HIP(hipMemcpy(plan->sc_nu_ptr.p, kvu.ptr[0].p, size_t(kvu.nodes[0] + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice));
-        if (kvu.nodes[1])
-            CST_HIP(hipMemcpy(plan->sc_nu_list.p, kvu.idx[1].p, size_t(kvu.nodes[1]) * sizeof(int32_t), hipMemcpyDeviceToDevice));
-        std::vector<int64_t> &h = h_nu_ptr;
-        h.resize(size_t(kvu.nodes[0] + 1));
-        CST_HIP(hipMemcpy(h.data(), kvu.ptr[0].p, h.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
         int64_t mx = 1;
-        for (size_t a = 0; a + 1 < h.size(); ++a) mx = std::max(mx, h[a + 1] - h[a]);
-        if (mx > 65534) { set_error("a K of I joins %lld distinct v; the sparse-chain kernel numbers them with 16 bits", (long long)mx); return CONSTSTN_EUNSUPPORTED; }
+        CST_TRY(csf3_leaf_universe(I, plan->sc_nu_ptr, plan->sc_nu_list, plan->sc_i_slot, &mx, &h_nu_ptr));
         plan->sc_max_slots = int(mx);
     }
-    CST_TRY(plan->sc_i_slot.alloc(size_t(I->nnz)));
-    if (I->nnz)
-        leaf_slot_kernel<<<grid_for(I->nnz), 256, 0, st>>>(I->nnz, I->ptr[0].p, I->nodes[0], I->ptr[1].p, I->nodes[1], I->idx[2].p,
-                                                          plan->sc_nu_ptr.p, plan->sc_nu_list.p, plan->sc_i_slot.p);
-    CST_HIP(hipGetLastError());
 
     // candidates
     if (L) {

@@ -1,0 +1,484 @@
+// Product of two SPARSE order-3 tensors over a shared index with a SPARSE order-4 result (Sec. 5.1,
+// the four-index integrals):
+//        V[i,j,m,n] = sum_K  Ea[K,i,m] * Eb[K,j,n]
+// as the single statement  V[i,j,m,n] = Ea[i,K,m] * Eb[j,K,n]  with loops i,j,K,m,n: the summed index
+// in the middle, the two innermost loops fill a dense m x n workspace per (i,j) (the workspace of
+// Sec. 2.2's last paragraph), which is then compressed to the stored elements.  Operand layouts:
+// Ea as CSF (i > K > m), Eb as CSF (j > K > n); the two may be one tensor under two names.
+//
+// For one (i,j) the sum over K is a dense contraction: with A = Ea[i] as a (K x m) matrix restricted
+// to the m that occur under i, and B = Eb[j] likewise, V[i,j] = A^T . B over the K stored in both.
+// It runs on the fp64 matrix cores (v_mfma_f64_16x16x4), the K in chunks staged densely in LDS.
+//
+//   symbolic (with the plan)  one workgroup per (i,j): co-iterates the two K lists (binary search),
+//             and for every shared K marks, for each m of Ea[i,K,:], the n of Eb[j,K,:] in a bit
+//             matrix [m of i x n of j] -- the join of Sec. 2.1.  Counts are scanned into the pointer
+//             arrays of V (CSF i > j > m > n), a second run lists the m and n (ascending).
+//   numeric   one workgroup per stored (i,j): the list of shared K in order, the same bit matrix
+//             (it gives every stored element its place), then per chunk of shared K the two dense
+//             chunk matrices and one matrix-core pass over the 16 x 16 tiles of the block, whose
+//             accumulators stay in registers; stored elements are written in place.  No atomics on
+//             values; the K are visited in ascending order.
+#include "plan.hpp"
+
+namespace cst {
+
+constexpr int kP4Waves = 8;                 // wavefronts per workgroup
+constexpr int kP4Chunk = 16;                // shared K staged per pass
+constexpr int kP4Tiles = 16;                // result tiles a wavefront keeps in registers
+
+typedef double p4_v4d __attribute__((ext_vector_type(4)));
+
+struct P4Side {                             // one operand: levels (root, K, leaf index)
+    const int32_t *idx0, *idx1;
+    const int64_t *ptr0, *ptr1;
+    const double *vals;
+    const int64_t *u_ptr;                   // per root: its distinct leaf indices (ascending) ...
+    const int32_t *u_list;
+    const uint16_t *slot;                   // ... and every leaf's place among them
+    int64_t roots;
+};
+
+struct P4Args {
+    P4Side a, b;
+    int W;                                  // 32-bit words per row of the bit matrix (n of j)
+    int max_ua, max_ub, max_common;
+    int mp, np;                             // row strides of the two chunk matrices (doubles)
+};
+
+struct P4Out {
+    int32_t *idx0, *idx1, *idx2, *idx3;
+    int64_t *ptr0, *ptr1, *ptr2;
+    int32_t *node_a, *node_b;               // per (i,j) node: root node of Ea, of Eb
+    int32_t *root_a;                        // per root of V: root node of Ea
+    int64_t roots, pairs, rows, nnz;
+};
+
+__device__ __forceinline__ int64_t p4_find(const int32_t *a, int64_t lo, int64_t hi, int32_t key) {
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int32_t x = a[mid];
+        if (x == key) return mid;
+        if (x < key) lo = mid + 1; else hi = mid;
+    }
+    return -1;
+}
+
+__device__ __forceinline__ void p4_wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The K stored under both roots, in ascending order: match_a / match_b receive the level-1 nodes.
+// Returns the count (the same in every thread).  `scratch` holds one int per wavefront + 1.
+template <int WAVES>
+__device__ int p4_shared_k(const P4Args &A, int64_t ra, int64_t rb, int32_t *match_a, int32_t *match_b, int cap,
+                           int *scratch) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t a0 = A.a.ptr0[ra], a1 = A.a.ptr0[ra + 1];
+    const int64_t b0 = A.b.ptr0[rb], b1 = A.b.ptr0[rb + 1];
+    int total = 0;
+    for (int64_t base = a0; base < a1; base += 64 * WAVES) {
+        const int64_t n = base + threadIdx.x;
+        int64_t at = -1;
+        if (n < a1) at = p4_find(A.b.idx1, b0, b1, A.a.idx1[n]);
+        const uint64_t bal = __ballot(at >= 0);
+        if (lane == 0) scratch[wave] = __popcll(bal);
+        __syncthreads();
+        int before = 0, all = 0;
+        for (int w = 0; w < WAVES; ++w) { if (w < wave) before += scratch[w]; all += scratch[w]; }
+        if (at >= 0) {
+            const int pos = total + before + __popcll(bal & ((uint64_t(1) << lane) - 1));
+            if (pos < cap) { match_a[pos] = int32_t(n); match_b[pos] = int32_t(at); }
+        }
+        total += all;
+        __syncthreads();
+    }
+    return total;
+}
+
+// Bit matrix of one (i,j): bit (m slot, n slot) set when some shared K stores both.  One wavefront
+// per shared K; rows are OR-ed with LDS atomics (the result does not depend on the order).
+template <int WAVES>
+__device__ void p4_bit_matrix(const P4Args &A, const int32_t *match_a, const int32_t *match_b, int n_shared,
+                              int n_ua, uint32_t *rowmask, uint32_t *nmask_all) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int W = A.W;
+    uint32_t *nmask = nmask_all + wave * W;
+    for (int x = threadIdx.x; x < n_ua * W; x += 64 * WAVES) rowmask[x] = 0;
+    __syncthreads();
+    for (int k = wave; k < n_shared; k += WAVES) {
+        for (int w = lane; w < W; w += 64) nmask[w] = 0;
+        p4_wave_sync();
+        const int64_t nb = match_b[k], na = match_a[k];
+        for (int64_t l = A.b.ptr1[nb] + lane; l < A.b.ptr1[nb + 1]; l += 64) {
+            const uint32_t s = A.b.slot[l];
+            atomicOr(&nmask[s >> 5], 1u << (s & 31));
+        }
+        p4_wave_sync();
+        for (int64_t l = A.a.ptr1[na] + lane; l < A.a.ptr1[na + 1]; l += 64) {
+            const int row = A.a.slot[l];
+            for (int w = 0; w < W; ++w) {
+                const uint32_t bits = nmask[w];
+                if (bits) atomicOr(&rowmask[row * W + w], bits);
+            }
+        }
+        p4_wave_sync();
+    }
+    __syncthreads();
+}
+
+// Per row of the bit matrix: number of set bits -> rowcnt; then (by the first wavefront) the set bits
+// before each row -> rowleaf[0..n_ua] and the nonempty rows before each row -> rowrank[0..n_ua].
+template <int WAVES>
+__device__ void p4_row_offsets(const P4Args &A, const uint32_t *rowmask, int n_ua, int32_t *rowleaf, int32_t *rowrank) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int W = A.W;
+    for (int r = threadIdx.x; r < n_ua; r += 64 * WAVES) {
+        int c = 0;
+        for (int w = 0; w < W; ++w) c += __popc(rowmask[r * W + w]);
+        rowleaf[r] = c;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int carry_l = 0, carry_r = 0;
+        for (int base = 0; base < n_ua; base += 64) {
+            const int r = base + lane;
+            const int c = r < n_ua ? rowleaf[r] : 0;
+            const int f = c > 0 ? 1 : 0;
+            int il = c, ir = f;
+            for (int d = 1; d < 64; d <<= 1) {
+                const int yl = __shfl_up(il, d, 64), yr = __shfl_up(ir, d, 64);
+                if (lane >= d) { il += yl; ir += yr; }
+            }
+            if (r < n_ua) { rowleaf[r] = carry_l + il - c; rowrank[r] = carry_r + ir - f; }
+            carry_l += __shfl(il, 63, 64);
+            carry_r += __shfl(ir, 63, 64);
+        }
+        if (lane == 0) { rowleaf[n_ua] = carry_l; rowrank[n_ua] = carry_r; }
+    }
+    __syncthreads();
+}
+
+// LDS of the symbolic kernels: match lists, bit matrix, per-wavefront n masks, row offsets
+struct P4SymLds {
+    int match_a, match_b, rowmask, nmask, rowleaf, rowrank, scratch, total;
+};
+
+// mode 0: count rows and leaves of every candidate (i,j); mode 1: write them
+__global__ void __launch_bounds__(64 * kP4Waves)
+sppair4_symbolic_kernel(P4Args A, P4Out V, P4SymLds O, int mode, int64_t *rows, int64_t *leaves,
+                        const int64_t *__restrict__ row_off, const int64_t *__restrict__ leaf_off,
+                        const int64_t *__restrict__ node_of) {
+    extern __shared__ unsigned char lds[];
+    int32_t *match_a = reinterpret_cast<int32_t *>(lds + O.match_a), *match_b = reinterpret_cast<int32_t *>(lds + O.match_b);
+    uint32_t *rowmask = reinterpret_cast<uint32_t *>(lds + O.rowmask), *nmask = reinterpret_cast<uint32_t *>(lds + O.nmask);
+    int32_t *rowleaf = reinterpret_cast<int32_t *>(lds + O.rowleaf), *rowrank = reinterpret_cast<int32_t *>(lds + O.rowrank);
+    int *scratch = reinterpret_cast<int *>(lds + O.scratch);
+    const int64_t c = blockIdx.x;
+    const int64_t ra = c / A.b.roots, rb = c - ra * A.b.roots;
+    if (mode == 1 && leaves[c] == 0) return;
+    const int n_ua = int(A.a.u_ptr[ra + 1] - A.a.u_ptr[ra]);
+    // the lists hold max_common entries, the longest K list of any root of Ea: every shared K fits
+    const int n_shared = p4_shared_k<kP4Waves>(A, ra, rb, match_a, match_b, A.max_common, scratch);
+    if (n_shared == 0) {
+        if (mode == 0 && threadIdx.x == 0) { rows[c] = 0; leaves[c] = 0; }
+        return;
+    }
+    p4_bit_matrix<kP4Waves>(A, match_a, match_b, n_shared, n_ua, rowmask, nmask);
+    p4_row_offsets<kP4Waves>(A, rowmask, n_ua, rowleaf, rowrank);
+    if (mode == 0) {
+        if (threadIdx.x == 0) { rows[c] = rowrank[n_ua]; leaves[c] = rowleaf[n_ua]; }
+        return;
+    }
+    const int64_t node = node_of[c], r0 = row_off[c], l0 = leaf_off[c];
+    if (threadIdx.x == 0) {
+        V.idx1[node] = A.b.idx0[rb];
+        V.ptr1[node] = r0;
+        V.node_a[node] = int32_t(ra);
+        V.node_b[node] = int32_t(rb);
+    }
+    const int64_t ua0 = A.a.u_ptr[ra], ub0 = A.b.u_ptr[rb];
+    for (int r = threadIdx.x; r < n_ua; r += 64 * kP4Waves) {
+        const int cnt = rowleaf[r + 1] - rowleaf[r];
+        if (cnt == 0) continue;
+        const int64_t row = r0 + rowrank[r];
+        V.idx2[row] = A.a.u_list[ua0 + r];
+        V.ptr2[row] = l0 + rowleaf[r];
+        int64_t at = l0 + rowleaf[r];
+        for (int w = 0; w < A.W; ++w) {
+            uint32_t word = rowmask[r * A.W + w];
+            while (word) {
+                V.idx3[at++] = A.b.u_list[ub0 + (w << 5) + __ffs(word) - 1];
+                word &= word - 1;
+            }
+        }
+    }
+}
+
+__global__ void sppair4_flag_kernel(const int64_t *leaves, int64_t n, int64_t *flag) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < n) flag[x] = leaves[x] > 0 ? 1 : 0;
+}
+
+__global__ void sppair4_root_flag_kernel(P4Out V, int64_t *flag) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n >= V.pairs) return;
+    flag[n] = (n == 0 || V.node_a[n - 1] != V.node_a[n]) ? 1 : 0;
+}
+
+__global__ void sppair4_root_fill_kernel(P4Args A, P4Out V, const int64_t *__restrict__ flag,
+                                         const int64_t *__restrict__ root_of) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n > V.pairs) return;
+    if (n == V.pairs) {
+        V.ptr0[V.roots] = V.pairs;
+        V.ptr1[V.pairs] = V.rows;
+        V.ptr2[V.rows] = V.nnz;
+        return;
+    }
+    if (flag[n]) {
+        const int64_t r = root_of[n];
+        V.idx0[r] = A.a.idx0[V.node_a[n]];
+        V.ptr0[r] = n;
+        V.root_a[r] = V.node_a[n];
+    }
+}
+
+// LDS of the numeric kernel
+struct P4NumLds {
+    int match_a, match_b, rowmask, nmask, rowleaf, rowrank, scratch, achunk, bchunk, total;
+};
+
+__global__ void __launch_bounds__(64 * kP4Waves)
+sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
+    extern __shared__ unsigned char lds[];
+    int32_t *match_a = reinterpret_cast<int32_t *>(lds + O.match_a), *match_b = reinterpret_cast<int32_t *>(lds + O.match_b);
+    uint32_t *rowmask = reinterpret_cast<uint32_t *>(lds + O.rowmask), *nmask = reinterpret_cast<uint32_t *>(lds + O.nmask);
+    int32_t *rowleaf = reinterpret_cast<int32_t *>(lds + O.rowleaf), *rowrank = reinterpret_cast<int32_t *>(lds + O.rowrank);
+    int *scratch = reinterpret_cast<int *>(lds + O.scratch);
+    double *Ac = reinterpret_cast<double *>(lds + O.achunk), *Bc = reinterpret_cast<double *>(lds + O.bchunk);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nthreads = 64 * kP4Waves;
+    const int64_t node = blockIdx.x;
+    const int64_t ra = V.node_a[node], rb = V.node_b[node];
+    const int n_ua = int(A.a.u_ptr[ra + 1] - A.a.u_ptr[ra]), n_ub = int(A.b.u_ptr[rb + 1] - A.b.u_ptr[rb]);
+    const int64_t leaf0 = V.ptr2[V.ptr1[node]];
+    const int n_shared = p4_shared_k<kP4Waves>(A, ra, rb, match_a, match_b, A.max_common, scratch);
+    p4_bit_matrix<kP4Waves>(A, match_a, match_b, n_shared, n_ua, rowmask, nmask);
+    p4_row_offsets<kP4Waves>(A, rowmask, n_ua, rowleaf, rowrank);
+
+    const int tiles_n = (n_ub + 15) >> 4, tiles = ((n_ua + 15) >> 4) * tiles_n;
+    const int li = lane & 15, lk = lane >> 4;
+    const int mp = A.mp, np = A.np;
+    for (int g0 = 0; g0 < tiles; g0 += kP4Waves * kP4Tiles) {          // groups of tiles whose accumulators fit
+        p4_v4d acc[kP4Tiles];
+#pragma unroll
+        for (int s = 0; s < kP4Tiles; ++s) acc[s] = p4_v4d{0.0, 0.0, 0.0, 0.0};
+        for (int k0 = 0; k0 < n_shared; k0 += kP4Chunk) {
+            const int kc = min(kP4Chunk, n_shared - k0);
+            __syncthreads();                                           // the previous chunk is no longer read
+            for (int x = threadIdx.x; x < kP4Chunk * mp; x += nthreads) Ac[x] = 0.0;
+            for (int x = threadIdx.x; x < kP4Chunk * np; x += nthreads) Bc[x] = 0.0;
+            __syncthreads();
+            for (int k = wave; k < kc; k += kP4Waves) {
+                const int64_t na = match_a[k0 + k], nb = match_b[k0 + k];
+                for (int64_t l = A.a.ptr1[na] + lane; l < A.a.ptr1[na + 1]; l += 64) Ac[k * mp + A.a.slot[l]] = A.a.vals[l];
+                for (int64_t l = A.b.ptr1[nb] + lane; l < A.b.ptr1[nb + 1]; l += 64) Bc[k * np + A.b.slot[l]] = A.b.vals[l];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < kP4Tiles; ++s) {
+                const int tile = g0 + wave + s * kP4Waves;
+                if (tile < tiles) {
+                    const int m0 = (tile / tiles_n) << 4, n0 = (tile % tiles_n) << 4;
+                    // chunk matrices are zero beyond the block, so no guards: strides cover the padded tiles
+#pragma unroll
+                    for (int kk = 0; kk < kP4Chunk; kk += 4)
+                        acc[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(Ac[(kk + lk) * mp + m0 + li], Bc[(kk + lk) * np + n0 + li],
+                                                                       acc[s], 0, 0, 0);
+                }
+            }
+        }
+        // lane holds V[i,j][m0 + lk + 4v][n0 + li]; stored elements go to their place
+#pragma unroll
+        for (int s = 0; s < kP4Tiles; ++s) {
+            const int tile = g0 + wave + s * kP4Waves;
+            if (tile < tiles) {
+                const int m0 = (tile / tiles_n) << 4, n0 = (tile % tiles_n) << 4;
+                const int n = n0 + li;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = m0 + lk + 4 * v;
+                    if (m < n_ua && n < n_ub) {
+                        const uint32_t *row = rowmask + m * A.W;
+                        const uint32_t word = row[n >> 5];
+                        if ((word >> (n & 31)) & 1u) {
+                            int before = __popc(word & ((1u << (n & 31)) - 1u));
+                            for (int w = 0; w < (n >> 5); ++w) before += __popc(row[w]);
+                            out[leaf0 + rowleaf[m] + before] = acc[s][v];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------------
+
+static inline dim3 p4_grid(int64_t n, int block = 256) { return dim3(unsigned(std::max<int64_t>(1, div_up(n, block)))); }
+
+static void p4_side(const conststn_csf_s *T, const DevBuf<int64_t> &u_ptr, const DevBuf<int32_t> &u_list,
+                    const DevBuf<uint16_t> &slot, P4Side &s) {
+    s.idx0 = T->idx[0].p; s.idx1 = T->idx[1].p;
+    s.ptr0 = T->ptr[0].p; s.ptr1 = T->ptr[1].p;
+    s.vals = T->vals.p;
+    s.u_ptr = u_ptr.p; s.u_list = u_list.p; s.slot = slot.p;
+    s.roots = T->nodes[0];
+}
+
+static P4Args p4_args(const conststn_plan_s *plan) {
+    P4Args A{};
+    p4_side(plan->X, plan->p4_ua_ptr, plan->p4_ua_list, plan->p4_a_slot, A.a);
+    p4_side(plan->W, plan->p4_ub_ptr, plan->p4_ub_list, plan->p4_b_slot, A.b);
+    A.W = plan->p4_words;
+    A.max_ua = plan->p4_max_ua;
+    A.max_ub = plan->p4_max_ub;
+    A.max_common = plan->p4_max_common;
+    A.mp = plan->p4_mp;
+    A.np = plan->p4_np;
+    return A;
+}
+
+static P4Out p4_out(const conststn_plan_s *plan) {
+    conststn_csf_s *E = plan->sc_E.get();
+    P4Out o{};
+    o.idx0 = E->idx[0].p; o.idx1 = E->idx[1].p; o.idx2 = E->idx[2].p; o.idx3 = E->idx[3].p;
+    o.ptr0 = E->ptr[0].p; o.ptr1 = E->ptr[1].p; o.ptr2 = E->ptr[2].p;
+    o.node_a = plan->p4_node_a.p; o.node_b = plan->p4_node_b.p; o.root_a = plan->p4_root_a.p;
+    o.roots = E->nodes[0]; o.pairs = E->nodes[1]; o.rows = E->nodes[2]; o.nnz = E->nodes[3];
+    return o;
+}
+
+conststn_status build_sppair4_tables(conststn_plan_s *plan) {
+    const conststn_csf_s *Ea = plan->X, *Eb = plan->W;
+    const hipStream_t st = nullptr;
+    int64_t max_ua = 1, max_ub = 1;
+    CST_TRY(csf3_leaf_universe(Ea, plan->p4_ua_ptr, plan->p4_ua_list, plan->p4_a_slot, &max_ua, nullptr));
+    CST_TRY(csf3_leaf_universe(Eb, plan->p4_ub_ptr, plan->p4_ub_list, plan->p4_b_slot, &max_ub, nullptr));
+    // the longest K list of a root of Ea bounds the K two roots can share
+    std::vector<int64_t> hp(size_t(Ea->nodes[0] + 1));
+    CST_HIP(hipMemcpy(hp.data(), Ea->ptr[0].p, hp.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+    int64_t max_k = 1;
+    for (size_t r = 0; r + 1 < hp.size(); ++r) max_k = std::max(max_k, hp[r + 1] - hp[r]);
+    plan->p4_max_ua = int(max_ua);
+    plan->p4_max_ub = int(max_ub);
+    plan->p4_words = int((max_ub + 31) / 32);
+    plan->p4_max_common = int(std::min<int64_t>(max_k, int64_t(1) << 20));
+    // chunk matrices: rows padded to whole tiles
+    plan->p4_mp = int((max_ua + 15) / 16 * 16);
+    plan->p4_np = int((max_ub + 15) / 16 * 16);
+    auto up16 = [](int64_t x) { return (x + 15) / 16 * 16; };
+    int64_t at = 0;
+    P4NumLds L{};
+    L.match_a = int(at); at = up16(at + 4 * int64_t(plan->p4_max_common));
+    L.match_b = int(at); at = up16(at + 4 * int64_t(plan->p4_max_common));
+    L.rowmask = int(at); at = up16(at + 4 * int64_t(plan->p4_words) * max_ua);
+    L.nmask = int(at); at = up16(at + 4 * int64_t(plan->p4_words) * kP4Waves);
+    L.rowleaf = int(at); at = up16(at + 4 * (max_ua + 1));
+    L.rowrank = int(at); at = up16(at + 4 * (max_ua + 1));
+    L.scratch = int(at); at = up16(at + 4 * (kP4Waves + 1));
+    const int64_t sym_bytes = at;
+    L.achunk = int(at); at = up16(at + 8 * int64_t(kP4Chunk) * plan->p4_mp);
+    L.bchunk = int(at); at = up16(at + 8 * int64_t(kP4Chunk) * plan->p4_np);
+    L.total = int(at);
+    if (at > 160 * 1024) {
+        set_error("the blocks of one (i,j) pair need %lld bytes of LDS (shared K up to %d, %lld x %lld distinct inner indices)",
+                  (long long)at, plan->p4_max_common, (long long)max_ua, (long long)max_ub);
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    const int lay[10] = {L.match_a, L.match_b, L.rowmask, L.nmask, L.rowleaf, L.rowrank, L.scratch, L.achunk, L.bchunk, L.total};
+    plan->p4_layout.assign(lay, lay + 10);
+    const P4SymLds S{L.match_a, L.match_b, L.rowmask, L.nmask, L.rowleaf, L.rowrank, L.scratch, int(sym_bytes)};
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sppair4_symbolic_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(sym_bytes)));
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sppair4_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, L.total));
+
+    const int64_t nc = Ea->nodes[0] * Eb->nodes[0];
+    if (nc > (int64_t(1) << 28)) { set_error("%lld candidate (i,j) pairs; the symbolic pass holds counters per pair", (long long)nc); return CONSTSTN_EUNSUPPORTED; }
+    plan->sc_E.reset(new conststn_csf_s());
+    conststn_csf_s *E = plan->sc_E.get();
+    E->order = 4;
+    E->dims[0] = Ea->dims[Ea->mode_order[0]]; E->dims[1] = Eb->dims[Eb->mode_order[0]];
+    E->dims[2] = Ea->dims[Ea->mode_order[2]]; E->dims[3] = Eb->dims[Eb->mode_order[2]];
+    for (int l = 0; l < 4; ++l) E->mode_order[l] = l;
+    E->device = Ea->device;
+    P4Args A = p4_args(plan);
+    int64_t pairs = 0, rows = 0, nnz = 0, roots = 0;
+    DevBuf<int64_t> c_rows, c_leaves, row_off, leaf_off, flag, node_of;
+    if (nc > 0) {
+        CST_TRY(c_rows.alloc(size_t(nc)));
+        CST_TRY(c_leaves.alloc(size_t(nc)));
+        CST_TRY(row_off.alloc(size_t(nc)));
+        CST_TRY(leaf_off.alloc(size_t(nc)));
+        CST_TRY(flag.alloc(size_t(nc)));
+        CST_TRY(node_of.alloc(size_t(nc)));
+        P4Out none{};
+        sppair4_symbolic_kernel<<<dim3(unsigned(nc)), 64 * kP4Waves, size_t(sym_bytes), st>>>(A, none, S, 0, c_rows.p, c_leaves.p,
+                                                                                           nullptr, nullptr, nullptr);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(c_rows.p, row_off.p, nc, &rows));
+        CST_TRY(exscan(c_leaves.p, leaf_off.p, nc, &nnz));
+        sppair4_flag_kernel<<<p4_grid(nc), 256, 0, st>>>(c_leaves.p, nc, flag.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(flag.p, node_of.p, nc, &pairs));
+    }
+    CST_TRY(E->idx[1].alloc(size_t(pairs)));
+    CST_TRY(E->ptr[1].alloc(size_t(pairs + 1)));
+    CST_TRY(E->idx[2].alloc(size_t(rows)));
+    CST_TRY(E->ptr[2].alloc(size_t(rows + 1)));
+    CST_TRY(E->idx[3].alloc(size_t(nnz)));
+    CST_TRY(plan->p4_node_a.alloc(size_t(pairs)));
+    CST_TRY(plan->p4_node_b.alloc(size_t(pairs)));
+    E->nodes[1] = pairs; E->nodes[2] = rows; E->nodes[3] = nnz;
+    E->nnz = nnz;
+    P4Out O = p4_out(plan);
+    if (pairs > 0) {
+        sppair4_symbolic_kernel<<<dim3(unsigned(nc)), 64 * kP4Waves, size_t(sym_bytes), st>>>(A, O, S, 1, c_rows.p, c_leaves.p,
+                                                                                           row_off.p, leaf_off.p, node_of.p);
+        CST_HIP(hipGetLastError());
+    }
+    DevBuf<int64_t> rflag, root_of;
+    CST_TRY(rflag.alloc(size_t(pairs)));
+    CST_TRY(root_of.alloc(size_t(pairs)));
+    if (pairs > 0) {
+        sppair4_root_flag_kernel<<<p4_grid(pairs), 256, 0, st>>>(O, rflag.p);
+        CST_HIP(hipGetLastError());
+        CST_TRY(exscan(rflag.p, root_of.p, pairs, &roots));
+    }
+    CST_TRY(E->idx[0].alloc(size_t(roots)));
+    CST_TRY(E->ptr[0].alloc(size_t(roots + 1)));
+    CST_TRY(plan->p4_root_a.alloc(size_t(roots)));
+    E->nodes[0] = roots;
+    O = p4_out(plan);
+    sppair4_root_fill_kernel<<<p4_grid(pairs + 1), 256, 0, st>>>(A, O, rflag.p, root_of.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipStreamSynchronize(st));
+    plan->out_rows = nnz;
+    plan->row_elems = 1;
+    return CONSTSTN_OK;
+}
+
+conststn_status launch_sppair4(const conststn_plan_s *plan, double *out, hipStream_t stream) {
+    const P4Args A = p4_args(plan);
+    const P4Out O = p4_out(plan);
+    ProfScope prof(plan, stream);
+    if (O.pairs == 0) return CONSTSTN_OK;
+    const std::vector<int> &l = plan->p4_layout;
+    const P4NumLds L{l[0], l[1], l[2], l[3], l[4], l[5], l[6], l[7], l[8], l[9]};
+    sppair4_kernel<<<dim3(unsigned(O.pairs)), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
+    CST_HIP(hipGetLastError());
+    return CONSTSTN_OK;
+}
+
+}  // namespace cst

@@ -18,7 +18,7 @@ constexpr int kSpGroup = 16;          // root slices of U processed together (on
 constexpr int kSpMaxMTiles = 25;      // m tiles whose accumulators a wavefront holds (M <= 400)
 constexpr int kSpMaxJ = 32768;        // extent of the contracted mode j the LDS bit mask covers
 
-enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GENERIC, FAM_SPCHAIN3 };
+enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GENERIC, FAM_SPCHAIN3, FAM_SPPAIR4 };
 
 // One statement of the generic executor (generic.hip), passed to its kernel by value.
 // Dense loop indices: the first n_out are the result's dense indices in storage order, the
@@ -203,6 +203,14 @@ struct conststn_plan_s {
     cst::DevBuf<unsigned char> sc_roots;                     // per root of the result: the kernel's descriptor
     std::vector<int> sc_local_layout;      // byte offsets of the kernel's LDS arrays
 
+    // product of two sparse order-3 tensors with a sparse order-4 result (X = Ea, W = Eb; structure in sc_E)
+    cst::DevBuf<int64_t> p4_ua_ptr, p4_ub_ptr;           // per root: its distinct innermost indices ...
+    cst::DevBuf<int32_t> p4_ua_list, p4_ub_list;
+    cst::DevBuf<uint16_t> p4_a_slot, p4_b_slot;          // ... and every leaf's place among them
+    cst::DevBuf<int32_t> p4_node_a, p4_node_b, p4_root_a;   // per (i,j) node / per root of the result: root nodes of the operands
+    int p4_words = 0, p4_max_ua = 0, p4_max_ub = 0, p4_max_common = 0, p4_mp = 0, p4_np = 0;
+    std::vector<int> p4_layout;
+
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;
     mutable int64_t prof_count = 0;        // executes recorded since the last read
@@ -231,6 +239,13 @@ conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *d
 // kernels_spchain3.hip: three sparse tensors, sparse result
 conststn_status build_spchain3_tables(conststn_plan_s *plan);
 conststn_status launch_spchain3(const conststn_plan_s *plan, double *out, hipStream_t stream);
+// shared by the sparse x sparse kernels: distinct innermost indices under every root of an order-3 CSF
+// tensor, and every leaf's place among them
+conststn_status csf3_leaf_universe(const conststn_csf_s *T, DevBuf<int64_t> &u_ptr, DevBuf<int32_t> &u_list,
+                                   DevBuf<uint16_t> &slot, int64_t *largest, std::vector<int64_t> *host_ptr);
+// kernels_sppair4.hip: two sparse order-3 tensors, sparse order-4 result
+conststn_status build_sppair4_tables(conststn_plan_s *plan);
+conststn_status launch_sppair4(const conststn_plan_s *plan, double *out, hipStream_t stream);
 // generic.hip: any tree over one CSF operand that the tuned families do not take
 conststn_status build_generic(conststn_plan_s *plan);
 conststn_status launch_generic(const conststn_plan_s *plan, const double *const *dense, double *out,

@@ -56,3 +56,7 @@ def ttmc3_for(levels):
 SPCHAIN3 = "T[K,i,v] = I[K,u,v] * C[i,u] | K,i,u,v ; E[K,i,m] = T[K,i,v] * P[m,v] | K,i,m,v"
 SPCHAIN3_RESTRICTED = ("T[K,i,v] = I[K,u,v] * C[i,u] | K,i,u,v ; F[K,i,v] = T[K,i,v] * L[K,i] | K,i,v ; "
                        "E[K,i,m] = F[K,i,v] * P[m,v] | K,i,m,v")
+
+# Sec. 5.1: the four-index integrals V = E x E over the fitting index K; E stored i > K > m, bound twice
+# (two names for one handle), sparse result with levels i > j > m > n.
+SPPAIR4 = "V[i,j,m,n] = Ea[i,K,m] * Eb[j,K,n] | i,j,K,m,n"
