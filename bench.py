@@ -27,15 +27,15 @@ KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "ttmc3": ["kernels_ttmc3.hip", "partition.hip"],
                   "ttmc4": ["kernels_ttmc4.hip", "partition.hip"],
                   "sptn3": ["kernels_sptn3.hip", "partition.hip"],
-                  "spchain3": ["kernels_spchain3.hip"]}
+                  "spchain3": ["kernels_spchain3.hip"], "sppair4": ["kernels_sppair4.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
                 "ttmc3": "ttmc3_mfma_kernel<4,2>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
-                "spchain3": "spchain3_local_kernel",
+                "spchain3": "spchain3_local_kernel", "sppair4": "sppair4_kernel",
                 "generic": "generic_stmt_kernel (one launch per statement)"}
 # what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they
 # compute (HBM); the order-4 TTMc and the three-tensor network are dense contractions per fiber
 # (fp64 matrix cores)
-BOUND = {"mttkrp3": "hbm", "ttmc3": "hbm", "ttmc4": "mfma", "sptn3": "mfma", "spchain3": "hbm"}
+BOUND = {"mttkrp3": "hbm", "ttmc3": "hbm", "ttmc4": "mfma", "sptn3": "mfma", "spchain3": "hbm", "sppair4": "mfma"}
 
 
 def measured_traffic(family):
@@ -166,6 +166,46 @@ def build_spchain(cst, S, wl, dev, restricted):
     return [dict(plan=pl, factors=[], out=out, nodes=nodes, bytes=alg_bytes, flops=0, keep=ops)], build_s, nnz_in
 
 
+def build_sppair(cst, S, wl, dev):
+    """E by the three-index transformation (on the GPU, outside the timed step), then the plan of V = E x E."""
+    I, C, P = (wl.sparse[k] for k in "ICP")
+    on = lambda t: ([c.to(dev) for c in t.coords], t.vals.to(dev))
+    (ic, iv), (cc, cv), (pc, pv) = on(I), on(C), on(P)
+    hI = cst.build_csf(ic, iv, I.dims, [0, 1, 2])
+    hC = cst.build_csf(cc, cv, C.dims, [1, 0])
+    hP = cst.build_csf(pc, pv, P.dims, [1, 0])
+    chain = cst.plan(S.SPCHAIN3, [("I", hI), ("C", hC), ("P", hP)])
+    ev = cst.execute(chain, [])
+    E = chain.output_csf()
+    (i0, p0, _), (i1, p1, _), (i2, _, _) = E.export(0), E.export(1), E.export(2)
+    node_K = torch.repeat_interleave(i0, p0[1:] - p0[:-1])
+    eK = torch.repeat_interleave(node_K, p1[1:] - p1[:-1]).contiguous()
+    ei = torch.repeat_interleave(i1, p1[1:] - p1[:-1]).contiguous()
+    em = i2.clone()
+    n_K, n_i, _, n_m = wl.params["dims"]
+    wl.params["E"] = ([eK, ei, em], ev, (n_K, n_i, n_m))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    hE = cst.build_csf([eK, ei, em], ev, (n_K, n_i, n_m), [1, 0, 2])
+    pl = cst.plan(S.SPPAIR4, [("Ea", hE), ("Eb", hE)])
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    V = pl.output_csf()
+    vn = [V.nodes(l) for l in range(4)]
+    out = torch.empty(pl.n_rows, dtype=torch.float64, device=dev)
+    nodes = [hE.nodes(l) for l in range(3)]
+    # dense-block model of the contraction: per stored (i,j), shared K x (m of i) x (n of j) multiply-adds
+    ki = torch.zeros(n_i, n_K, dtype=torch.float32, device=dev)
+    ki[ei.long(), eK.long()] = 1.0
+    shared = ki @ ki.T                                                # K stored under both i and j
+    mi = torch.zeros(n_i, n_m, dtype=torch.float32, device=dev)
+    mi[ei.long(), em.long()] = 1.0
+    width = mi.sum(1)
+    flops = float(2.0 * (shared * width[:, None] * width[None, :]).sum())
+    alg_bytes = 2 * 12 * sum(nodes) + 12 * vn[3] + 12 * (vn[2] + vn[1] + vn[0])
+    return [dict(plan=pl, factors=[], out=out, nodes=nodes, bytes=alg_bytes, flops=flops, keep=(hE, chain))], build_s, 2 * ev.numel()
+
+
 def cpu_baseline(wl, budget_nnz):
     """The CPU oracle, as it stands, on a bounded sample (first nonzeros) of the same workload."""
     import oracle
@@ -210,6 +250,27 @@ def cpu_baseline(wl, budget_nnz):
         dt = time.perf_counter() - t0
         return dict(value=n / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
                     sample="order-4 TTMc of the first %d nonzeros, %.2f s" % (n, dt))
+    if wl.kind == "sppair4":
+        from oracle import spsp
+        (ek, ei, em), ev, dims = wl.params["E"]
+        Ec = [x.cpu().numpy() for x in (ek, ei, em)]
+        Ev = ev.cpu().numpy()
+        n_i = dims[1]
+        pairs = [(int(a), int(b)) for a, b in zip(torch.linspace(0, n_i - 1, 24), torch.linspace(n_i - 1, 0, 24))]
+        pairs += [(a, a) for a, _ in pairs]
+        t0 = time.perf_counter()
+        for a, b in pairs:
+            spsp.pair4_block(Ec, Ev, dims, a, b)
+        dt = time.perf_counter() - t0
+        per_pair = 2 * len(Ev) / (n_i * n_i)                    # input nonzeros an (i,j) block accounts for
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+        except ImportError:
+            cores = 1
+        return dict(value=per_pair * len(pairs) / dt, unit="nnz/s", cores=cores, kind="oracle",
+                    sample="%d of the %d (i,j) blocks, dense slab products, %.2f s; nonzeros counted as 2 nnz(E) spread "
+                           "evenly over the blocks" % (len(pairs), n_i * n_i, dt))
     if wl.kind == "spchain3":
         from oracle import spsp
         I, C, P, L = (wl.sparse[k] for k in "ICPL")
@@ -239,7 +300,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2,
-                    help="benchmark configuration 1..5 (default 2); 6 = the sparse chain of Sec. 5.1 on lattice maps")
+                    help="benchmark configuration 1..5 (default 2); 6 = the sparse chain of Sec. 5.1 on lattice maps, "
+                         "7 = the four-index product of the same section")
     ap.add_argument("--restricted", action="store_true", help="configuration 6: the form with the K -> i filter")
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -287,6 +349,10 @@ def main():
         name = "C%d TTMc order-%d %s nnz=%d ranks=%s" % (
             args.config, wl.sparse["X"].order, "x".join(map(str, wl.sparse["X"].dims)),
             wl.sparse["X"].nnz, wl.params["ranks"])
+    elif wl.kind == "sppair4":
+        launches, build_s, nnz_per_step = build_sppair(cst, S, wl, dev)
+        name = "C7 V=E.E lattice %dx%d nnzE=%d nnzV=%d" % (wl.params["side"], wl.params["side"], nnz_per_step // 2,
+                                                          launches[0]["plan"].n_rows)
     elif wl.kind == "spchain3":
         wl.params["restricted"] = args.restricted
         launches, build_s, nnz_per_step = build_spchain(cst, S, wl, dev, args.restricted)

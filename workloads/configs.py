@@ -1,6 +1,7 @@
 """The five benchmark configurations and reduced copies of each, plus configuration 6: the
 sparse three-index integral transformation of Sec. 5.1 on lattice sparse maps (a stand-in for
-the quantum-chemistry inputs, which are not public).
+the quantum-chemistry inputs, which are not public), and configuration 7: the four-index product
+V = E x E of the same section on a smaller lattice.
 
 CONFIGS[c] are the full sizes; SMALL[c] keep the same recipe (distribution
 family, skew, rank) at sizes a CPU loop finishes in seconds, chosen so that
@@ -59,7 +60,17 @@ def _c6(device, **kw):
                               kw.get("r_filter", 3.0), device=device)
 
 
-CONFIGS = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5, 6: _c6}
+def _c7(device, **kw):
+    # the four-index product V = E x E of Sec. 5.1 on a 12 x 12 lattice (E: 1440 x 144 x 432 with ~4 M
+    # structural nonzeros, made from these inputs by the three-index transformation; V: ~224 M)
+    wl = make_lattice_chain("c7", BASE_SEED + 7, kw.get("side", 12), kw.get("n_ao", 3), kw.get("n_df", 10),
+                            kw.get("r_int", 2.0), kw.get("r_mo", 2.0), kw.get("r_pao", 2.0),
+                            kw.get("r_filter", 3.0), device=device)
+    wl.kind = "sppair4"
+    return wl
+
+
+CONFIGS = {1: _c1, 2: _c2, 3: _c3, 4: _c4, 5: _c5, 6: _c6, 7: _c7}
 
 # reduced copies: same recipe, sizes for CPU-second oracle runs
 SMALL = {
@@ -69,11 +80,12 @@ SMALL = {
     4: dict(dims=(60, 80, 40, 60, 40), nblocks=4, n_sel_u=6, n_sel_w=7),
     5: dict(dims=(20_011, 19_997, 2503), nnz=200_003, ranks=(64, 64)),
     6: dict(side=5, n_df=6, r_int=1.5, r_pao=1.5, r_filter=2.5),
+    7: dict(side=5, n_df=6, r_int=1.5, r_pao=1.5, r_filter=2.5),
 }
 
 
 def make(cid, device="cpu", small=False, **overrides):
-    """Build configuration `cid` (1..6); small=True gives the reduced copy."""
+    """Build configuration `cid` (1..7); small=True gives the reduced copy."""
     kw = dict(SMALL[cid]) if small else {}
     kw.update(overrides)
     return CONFIGS[cid](device, **kw)
