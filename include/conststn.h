@@ -132,7 +132,9 @@ void conststn_csf_destroy(conststn_csf_t *csf);
  * Sec. 5.1 (every operand a CSF handle, sparse result: see conststn_plan_output_csf),
  *      "T[K,i,v] = I[K,u,v] * C[i,u] | K,i,u,v ; E[K,i,m] = T[K,i,v] * P[m,v] | K,i,m,v"
  * and its restricted form with a statement "F[K,i,v] = T[K,i,v] * L[K,i] | K,i,v" in between,
- * fused on the two outer loops, has a kernel of its own.  Every other legal tree over ONE CSF
+ * fused on the two outer loops, has a kernel of its own, and so has the four-index product of the
+ * same section, "V[i,j,m,n] = Ea[i,K,m] * Eb[j,K,n] | i,j,K,m,n" (two CSF operands of order 3, which
+ * may be one handle under two names; sparse result with levels i > j > m > n).  Every other legal tree over ONE CSF
  * operand and dense operands -- other orders and ranks, dense-only subtrees, several CSF levels
  * summed by one statement, a fully contracted result, a result indexed by CSF levels other than
  * the root (every output mode on one CSF; such a result is a dense array over the extents of all

@@ -23,9 +23,9 @@
 
 namespace cst {
 
-constexpr int kP4Waves = 8;                 // wavefronts per workgroup
-constexpr int kP4Chunk = 16;                // shared K staged per pass
-constexpr int kP4Tiles = 16;                // result tiles a wavefront keeps in registers
+constexpr int kP4Waves = 16;                 // wavefronts per workgroup
+constexpr int kP4Chunk = 8;                // shared K staged per pass
+constexpr int kP4Tiles = 8;                // result tiles a wavefront keeps in registers
 
 typedef double p4_v4d __attribute__((ext_vector_type(4)));
 
