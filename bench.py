@@ -87,6 +87,30 @@ def build_mttkrp(cst, S, wl, dev):
     return launches, build_s, 2 * X.nnz
 
 
+def build_mttkrp_all_modes(cst, S, wl, dev):
+    """One CP-ALS sweep's worth of MTTKRPs (Sec. 5.2 times all three): a CSF rooted at every mode."""
+    X = wl.sparse["X"]
+    coords = [c.to(dev) for c in X.coords]
+    vals = X.vals.to(dev)
+    F = [wl.dense[k].to(dev) for k in ("A", "B", "C")]
+    R = F[0].shape[1]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    launches = []
+    for levels in ([0, 1, 2], [1, 0, 2], [2, 1, 0]):
+        csf = cst.build_csf(coords, vals, X.dims, levels)
+        text, names = S.mttkrp3_for(levels)
+        facs = [F[levels[2]], F[levels[1]]]
+        pl = cst.plan(text, [("X", csf), (names[1], facs[0]), (names[2], facs[1])])
+        nodes = [csf.nodes(l) for l in range(3)]
+        out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
+        alg_bytes = 12 * sum(nodes) + 8 * R * (facs[0].shape[0] + facs[1].shape[0]) + 8 * pl.n_rows * pl.row_elems
+        launches.append(dict(plan=pl, factors=facs, out=out, nodes=nodes, bytes=alg_bytes,
+                             flops=2 * R * (nodes[2] + nodes[1]), keep=csf))
+    torch.cuda.synchronize()
+    return launches, time.perf_counter() - t0, 3 * X.nnz
+
+
 def build_chain(cst, S, wl, dev, compact):
     X = wl.sparse["X"]
     coords = [c.to(dev) for c in X.coords]
@@ -302,6 +326,8 @@ def main():
     ap.add_argument("--config", type=int, default=2,
                     help="benchmark configuration 1..5 (default 2); 6 = the sparse chain of Sec. 5.1 on lattice maps, "
                          "7 = the four-index product of the same section")
+    ap.add_argument("--all-modes", action="store_true",
+                    help="configuration 2: a step is the MTTKRP of every mode (0, 1, 2), each on a CSF rooted at its mode")
     ap.add_argument("--restricted", action="store_true", help="configuration 6: the form with the K -> i filter")
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -340,7 +366,11 @@ def main():
         args.config, wl.kind, time.perf_counter() - t0,
         {k: (v.dims, v.nnz) for k, v in wl.sparse.items()}))
 
-    if wl.kind == "mttkrp3":
+    if wl.kind == "mttkrp3" and args.all_modes:
+        launches, build_s, nnz_per_step = build_mttkrp_all_modes(cst, S, wl, dev)
+        name = "C2 MTTKRP order-3 %s nnz=%d rank=%d, modes 0, 1 and 2" % (
+            "x".join(map(str, wl.sparse["X"].dims)), wl.sparse["X"].nnz, wl.params["rank"])
+    elif wl.kind == "mttkrp3":
         launches, build_s, nnz_per_step = build_mttkrp(cst, S, wl, dev)
         name = "C2 MTTKRP order-3 %s nnz=%d rank=%d, modes 0 and 2" % (
             "x".join(map(str, wl.sparse["X"].dims)), wl.sparse["X"].nnz, wl.params["rank"])
@@ -386,9 +416,11 @@ def main():
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    kernel_ms = []
+    kernel_ms, per_launch_ms = [], []
     for L in launches:
-        kernel_ms += L["plan"].kernel_times()
+        kt = L["plan"].kernel_times()
+        kernel_ms += kt
+        per_launch_ms.append(sum(kt) / max(len(kt), 1))
         L["plan"].profile(0)
     ms_per_step = dt / args.steps * 1e3
     avg_kernel_ms = sum(kernel_ms) / max(len(kernel_ms), 1)
@@ -412,6 +444,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(family),
                      "kernel": KERNEL_NAMES.get(family, family),
                      "kernel_ms_avg": avg_kernel_ms, "launches_timed": len(kernel_ms),
+                     "kernel_ms_per_contraction": per_launch_ms,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
     if BOUND.get(family) == "mfma":
