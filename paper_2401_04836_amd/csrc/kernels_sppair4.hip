@@ -16,7 +16,8 @@
 //             arrays of V (CSF i > j > m > n), a second run lists the m and n (ascending).
 //   numeric   one workgroup per stored (i,j): the list of shared K in order, the same bit matrix
 //             (it gives every stored element its place), then per chunk of shared K the two dense
-//             chunk matrices and one matrix-core pass over the 16 x 16 tiles of the block, whose
+//             chunk matrices (double-buffered: the next chunk is fetched during the pass over the
+//             current one) and one matrix-core pass over the 16 x 16 tiles of the block, whose
 //             accumulators stay in registers; stored elements are written in place.  No atomics on
 //             values; the K are visited in ascending order.
 #include "plan.hpp"
@@ -275,18 +276,47 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
         p4_v4d acc[kP4Tiles];
 #pragma unroll
         for (int s = 0; s < kP4Tiles; ++s) acc[s] = p4_v4d{0.0, 0.0, 0.0, 0.0};
-        for (int k0 = 0; k0 < n_shared; k0 += kP4Chunk) {
-            const int kc = min(kP4Chunk, n_shared - k0);
-            __syncthreads();                                           // the previous chunk is no longer read
-            for (int x = threadIdx.x; x < kP4Chunk * mp; x += nthreads) Ac[x] = 0.0;
-            for (int x = threadIdx.x; x < kP4Chunk * np; x += nthreads) Bc[x] = 0.0;
-            __syncthreads();
-            for (int k = wave; k < kc; k += kP4Waves) {
-                const int64_t na = match_a[k0 + k], nb = match_b[k0 + k];
-                for (int64_t l = A.a.ptr1[na] + lane; l < A.a.ptr1[na + 1]; l += 64) Ac[k * mp + A.a.slot[l]] = A.a.vals[l];
-                for (int64_t l = A.b.ptr1[nb] + lane; l < A.b.ptr1[nb + 1]; l += 64) Bc[k * np + A.b.slot[l]] = A.b.vals[l];
+        // Chunks of kP4Chunk shared K, double-buffered: every wavefront owns one row of one of the two
+        // chunk matrices (K number wave / 2, operand wave % 2); it fetches its row of the NEXT chunk
+        // before the matrix-core pass over the current one and lays it out afterwards.
+        static_assert(2 * kP4Chunk == kP4Waves, "one chunk row per wavefront");
+        const int side = wave & 1, krow = wave >> 1;
+        const P4Side &T = side ? A.b : A.a;
+        const int stride = side ? np : mp;
+        int sl[2];
+        double vl[2];
+        int64_t l0 = 0, l1 = 0;
+        auto fetch = [&](int k0) {
+            sl[0] = sl[1] = -1;
+            l0 = l1 = 0;
+            if (k0 + krow < n_shared) {
+                const int64_t node = side ? match_b[k0 + krow] : match_a[k0 + krow];
+                l0 = T.ptr1[node];
+                l1 = T.ptr1[node + 1];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int64_t l = l0 + 64 * h + lane;
+                    if (l < l1) { sl[h] = T.slot[l]; vl[h] = T.vals[l]; }
+                }
             }
-            __syncthreads();
+        };
+        auto lay_out = [&](int buf) {
+            double *row = (side ? Bc + buf * kP4Chunk * np : Ac + buf * kP4Chunk * mp) + krow * stride;
+            for (int x = lane; x < stride; x += 64) row[x] = 0.0;
+            p4_wave_sync();
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                if (sl[h] >= 0) row[sl[h]] = vl[h];
+            for (int64_t l = l0 + 128 + lane; l < l1; l += 64) row[T.slot[l]] = T.vals[l];      // rows beyond 128 leaves
+        };
+        __syncthreads();                                               // the buffers of the previous group are no longer read
+        fetch(0);
+        lay_out(0);
+        for (int k0 = 0, c = 0; k0 < n_shared; k0 += kP4Chunk, ++c) {
+            __syncthreads();                                           // chunk c laid out; chunk c-1 no longer read
+            const bool more = k0 + kP4Chunk < n_shared;
+            if (more) fetch(k0 + kP4Chunk);
+            const double *Ab = Ac + (c & 1) * kP4Chunk * mp, *Bb = Bc + (c & 1) * kP4Chunk * np;
 #pragma unroll
             for (int s = 0; s < kP4Tiles; ++s) {
                 const int tile = g0 + wave + s * kP4Waves;
@@ -295,10 +325,11 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
                     // chunk matrices are zero beyond the block, so no guards: strides cover the padded tiles
 #pragma unroll
                     for (int kk = 0; kk < kP4Chunk; kk += 4)
-                        acc[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(Ac[(kk + lk) * mp + m0 + li], Bc[(kk + lk) * np + n0 + li],
+                        acc[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(Ab[(kk + lk) * mp + m0 + li], Bb[(kk + lk) * np + n0 + li],
                                                                        acc[s], 0, 0, 0);
                 }
             }
+            if (more) lay_out((c + 1) & 1);
         }
         // lane holds V[i,j][m0 + lk + 4v][n0 + li]; stored elements go to their place
 #pragma unroll
@@ -377,8 +408,12 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     plan->p4_words = int((max_ub + 31) / 32);
     plan->p4_max_common = int(std::min<int64_t>(max_k, int64_t(1) << 20));
     // chunk matrices: rows padded to whole tiles
+    // ... and to an odd number of 16-double units: the four depth rows one matrix-core operand reads
+    // then fall into alternating halves of the LDS banks instead of all into the same ones
     plan->p4_mp = int((max_ua + 15) / 16 * 16);
     plan->p4_np = int((max_ub + 15) / 16 * 16);
+    if (plan->p4_mp % 32 == 0) plan->p4_mp += 16;
+    if (plan->p4_np % 32 == 0) plan->p4_np += 16;
     auto up16 = [](int64_t x) { return (x + 15) / 16 * 16; };
     int64_t at = 0;
     P4NumLds L{};
@@ -390,8 +425,8 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     L.rowrank = int(at); at = up16(at + 4 * (max_ua + 1));
     L.scratch = int(at); at = up16(at + 4 * (kP4Waves + 1));
     const int64_t sym_bytes = at;
-    L.achunk = int(at); at = up16(at + 8 * int64_t(kP4Chunk) * plan->p4_mp);
-    L.bchunk = int(at); at = up16(at + 8 * int64_t(kP4Chunk) * plan->p4_np);
+    L.achunk = int(at); at = up16(at + 2 * 8 * int64_t(kP4Chunk) * plan->p4_mp);       // two buffers each
+    L.bchunk = int(at); at = up16(at + 2 * 8 * int64_t(kP4Chunk) * plan->p4_np);
     L.total = int(at);
     if (at > 160 * 1024) {
         set_error("the blocks of one (i,j) pair need %lld bytes of LDS (shared K up to %d, %lld x %lld distinct inner indices)",
