@@ -53,6 +53,13 @@ struct P4Out {
     int32_t *node_a, *node_b;               // per (i,j) node: root node of Ea, of Eb
     int32_t *root_a;                        // per root of V: root node of Ea
     int64_t roots, pairs, rows, nnz;
+    // kept from the symbolic pass when they fit: per (i,j) node the shared K (level-1 nodes of the two
+    // operands, ascending K) and the bit matrix, so that the numeric pass need not find them again
+    int64_t *k_ptr;                         // [pairs + 1]
+    int64_t *k_a, *k_b;                     // first leaf of the K's row in Ea / Eb ...
+    int32_t *k_alen, *k_blen;               // ... and its length
+    uint32_t *masks;                        // [pairs x mask_stride]
+    int64_t mask_stride;
 };
 
 __device__ __forceinline__ int64_t p4_find(const int32_t *a, int64_t lo, int64_t hi, int32_t key) {
@@ -168,8 +175,8 @@ struct P4SymLds {
 
 // mode 0: count rows and leaves of every candidate (i,j); mode 1: write them
 __global__ void __launch_bounds__(64 * kP4Waves)
-sppair4_symbolic_kernel(P4Args A, P4Out V, P4SymLds O, int mode, int64_t *rows, int64_t *leaves,
-                        const int64_t *__restrict__ row_off, const int64_t *__restrict__ leaf_off,
+sppair4_symbolic_kernel(P4Args A, P4Out V, P4SymLds O, int mode, int64_t *rows, int64_t *leaves, int64_t *shared,
+                        const int64_t *__restrict__ k_off, const int64_t *__restrict__ row_off, const int64_t *__restrict__ leaf_off,
                         const int64_t *__restrict__ node_of) {
     extern __shared__ unsigned char lds[];
     int32_t *match_a = reinterpret_cast<int32_t *>(lds + O.match_a), *match_b = reinterpret_cast<int32_t *>(lds + O.match_b);
@@ -183,16 +190,28 @@ sppair4_symbolic_kernel(P4Args A, P4Out V, P4SymLds O, int mode, int64_t *rows, 
     // the lists hold max_common entries, the longest K list of any root of Ea: every shared K fits
     const int n_shared = p4_shared_k<kP4Waves>(A, ra, rb, match_a, match_b, A.max_common, scratch);
     if (n_shared == 0) {
-        if (mode == 0 && threadIdx.x == 0) { rows[c] = 0; leaves[c] = 0; }
+        if (mode == 0 && threadIdx.x == 0) { rows[c] = 0; leaves[c] = 0; shared[c] = 0; }
         return;
     }
     p4_bit_matrix<kP4Waves>(A, match_a, match_b, n_shared, n_ua, rowmask, nmask);
     p4_row_offsets<kP4Waves>(A, rowmask, n_ua, rowleaf, rowrank);
     if (mode == 0) {
-        if (threadIdx.x == 0) { rows[c] = rowrank[n_ua]; leaves[c] = rowleaf[n_ua]; }
+        if (threadIdx.x == 0) { rows[c] = rowrank[n_ua]; leaves[c] = rowleaf[n_ua]; shared[c] = rowleaf[n_ua] > 0 ? n_shared : 0; }
         return;
     }
     const int64_t node = node_of[c], r0 = row_off[c], l0 = leaf_off[c];
+    if (V.k_ptr) {
+        const int64_t k0 = k_off[c];
+        if (threadIdx.x == 0) V.k_ptr[node] = k0;
+        for (int x = threadIdx.x; x < n_shared; x += 64 * kP4Waves) {
+            const int64_t a0 = A.a.ptr1[match_a[x]], b0 = A.b.ptr1[match_b[x]];
+            V.k_a[k0 + x] = a0;
+            V.k_alen[k0 + x] = int32_t(A.a.ptr1[match_a[x] + 1] - a0);
+            V.k_b[k0 + x] = b0;
+            V.k_blen[k0 + x] = int32_t(A.b.ptr1[match_b[x] + 1] - b0);
+        }
+        for (int x = threadIdx.x; x < n_ua * A.W; x += 64 * kP4Waves) V.masks[node * V.mask_stride + x] = rowmask[x];
+    }
     if (threadIdx.x == 0) {
         V.idx1[node] = A.b.idx0[rb];
         V.ptr1[node] = r0;
@@ -265,57 +284,83 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
     const int64_t ra = V.node_a[node], rb = V.node_b[node];
     const int n_ua = int(A.a.u_ptr[ra + 1] - A.a.u_ptr[ra]), n_ub = int(A.b.u_ptr[rb + 1] - A.b.u_ptr[rb]);
     const int64_t leaf0 = V.ptr2[V.ptr1[node]];
-    const int n_shared = p4_shared_k<kP4Waves>(A, ra, rb, match_a, match_b, A.max_common, scratch);
-    p4_bit_matrix<kP4Waves>(A, match_a, match_b, n_shared, n_ua, rowmask, nmask);
+    int n_shared;
+    const int64_t *k_first = nullptr;       // kept by the plan: leaf range of every shared K, this wavefront's operand
+    const int32_t *k_len = nullptr;
+    if (V.k_ptr) {
+        const int64_t kp = V.k_ptr[node];
+        n_shared = int(V.k_ptr[node + 1] - kp);
+        k_first = ((threadIdx.x >> 6) & 1 ? V.k_b : V.k_a) + kp;
+        k_len = ((threadIdx.x >> 6) & 1 ? V.k_blen : V.k_alen) + kp;
+        for (int x = threadIdx.x; x < n_ua * A.W; x += nthreads) rowmask[x] = V.masks[node * V.mask_stride + x];
+        __syncthreads();
+    } else {
+        n_shared = p4_shared_k<kP4Waves>(A, ra, rb, match_a, match_b, A.max_common, scratch);
+        p4_bit_matrix<kP4Waves>(A, match_a, match_b, n_shared, n_ua, rowmask, nmask);
+    }
     p4_row_offsets<kP4Waves>(A, rowmask, n_ua, rowleaf, rowrank);
 
     const int tiles_n = (n_ub + 15) >> 4, tiles = ((n_ua + 15) >> 4) * tiles_n;
     const int li = lane & 15, lk = lane >> 4;
     const int mp = A.mp, np = A.np;
+    // Chunks of kP4Chunk shared K, double-buffered: every wavefront owns one row of one of the two chunk
+    // matrices (K number wave / 2, operand wave % 2).  During the matrix-core pass over chunk c the leaves
+    // of its row of chunk c+1 and the leaf range of its row of chunk c+2 are in flight; the row of chunk
+    // c+1 is laid out in the other LDS buffer after the pass.
+    static_assert(2 * kP4Chunk == kP4Waves, "one chunk row per wavefront");
+    const int side = wave & 1, krow = wave >> 1;
+    const P4Side &T = side ? A.b : A.a;
+    const int32_t *kn = side ? match_b : match_a;
+    const int stride = side ? np : mp;
     for (int g0 = 0; g0 < tiles; g0 += kP4Waves * kP4Tiles) {          // groups of tiles whose accumulators fit
         p4_v4d acc[kP4Tiles];
 #pragma unroll
         for (int s = 0; s < kP4Tiles; ++s) acc[s] = p4_v4d{0.0, 0.0, 0.0, 0.0};
-        // Chunks of kP4Chunk shared K, double-buffered: every wavefront owns one row of one of the two
-        // chunk matrices (K number wave / 2, operand wave % 2); it fetches its row of the NEXT chunk
-        // before the matrix-core pass over the current one and lays it out afterwards.
-        static_assert(2 * kP4Chunk == kP4Waves, "one chunk row per wavefront");
-        const int side = wave & 1, krow = wave >> 1;
-        const P4Side &T = side ? A.b : A.a;
-        const int stride = side ? np : mp;
         int sl[2];
         double vl[2];
-        int64_t l0 = 0, l1 = 0;
-        auto fetch = [&](int k0) {
-            sl[0] = sl[1] = -1;
-            l0 = l1 = 0;
-            if (k0 + krow < n_shared) {
-                const int64_t node = side ? match_b[k0 + krow] : match_a[k0 + krow];
-                l0 = T.ptr1[node];
-                l1 = T.ptr1[node + 1];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int64_t l = l0 + 64 * h + lane;
-                    if (l < l1) { sl[h] = T.slot[l]; vl[h] = T.vals[l]; }
-                }
+        int64_t r1 = 0, r2 = 0;            // first leaf of this wavefront's row of the next chunk / the one after
+        int n1 = 0, n2 = 0;                // ... and their lengths
+        auto get_range = [&](int k0, int64_t &first, int &len) {
+            first = 0;
+            len = 0;
+            const int k = k0 + krow;
+            if (k < n_shared) {
+                if (k_first) { first = k_first[k]; len = k_len[k]; }
+                else { const int64_t nd = kn[k]; first = T.ptr1[nd]; len = int(T.ptr1[nd + 1] - first); }
             }
         };
-        auto lay_out = [&](int buf) {
+        auto get_leaves = [&](int64_t first, int len) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int l = 64 * h + lane;
+                sl[h] = -1;
+                vl[h] = 0.0;
+                if (l < len) { sl[h] = T.slot[first + l]; vl[h] = T.vals[first + l]; }
+            }
+        };
+        auto lay_out = [&](int buf, int64_t first, int len) {
             double *row = (side ? Bc + buf * kP4Chunk * np : Ac + buf * kP4Chunk * mp) + krow * stride;
             for (int x = lane; x < stride; x += 64) row[x] = 0.0;
             p4_wave_sync();
 #pragma unroll
             for (int h = 0; h < 2; ++h)
                 if (sl[h] >= 0) row[sl[h]] = vl[h];
-            for (int64_t l = l0 + 128 + lane; l < l1; l += 64) row[T.slot[l]] = T.vals[l];      // rows beyond 128 leaves
+            for (int l = 128 + lane; l < len; l += 64) row[T.slot[first + l]] = T.vals[first + l];    // rows beyond 128 leaves
         };
         __syncthreads();                                               // the buffers of the previous group are no longer read
-        fetch(0);
-        lay_out(0);
+        get_range(0, r1, n1);
+        get_range(kP4Chunk, r2, n2);
+        get_leaves(r1, n1);
+        lay_out(0, r1, n1);
+        r1 = r2;
+        n1 = n2;
         for (int k0 = 0, c = 0; k0 < n_shared; k0 += kP4Chunk, ++c) {
             __syncthreads();                                           // chunk c laid out; chunk c-1 no longer read
             const bool more = k0 + kP4Chunk < n_shared;
-            if (more) fetch(k0 + kP4Chunk);
+            if (more) {
+                get_leaves(r1, n1);                                    // chunk c+1 (range fetched a pass ago)
+                get_range(k0 + 2 * kP4Chunk, r2, n2);                  // chunk c+2
+            }
             const double *Ab = Ac + (c & 1) * kP4Chunk * mp, *Bb = Bc + (c & 1) * kP4Chunk * np;
 #pragma unroll
             for (int s = 0; s < kP4Tiles; ++s) {
@@ -329,7 +374,11 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
                                                                        acc[s], 0, 0, 0);
                 }
             }
-            if (more) lay_out((c + 1) & 1);
+            if (more) {
+                lay_out((c + 1) & 1, r1, n1);
+                r1 = r2;
+                n1 = n2;
+            }
         }
         // lane holds V[i,j][m0 + lk + 4v][n0 + li]; stored elements go to their place
 #pragma unroll
@@ -389,6 +438,12 @@ static P4Out p4_out(const conststn_plan_s *plan) {
     o.ptr0 = E->ptr[0].p; o.ptr1 = E->ptr[1].p; o.ptr2 = E->ptr[2].p;
     o.node_a = plan->p4_node_a.p; o.node_b = plan->p4_node_b.p; o.root_a = plan->p4_root_a.p;
     o.roots = E->nodes[0]; o.pairs = E->nodes[1]; o.rows = E->nodes[2]; o.nnz = E->nodes[3];
+    if (plan->p4_stored) {
+        o.k_ptr = plan->p4_k_ptr.p; o.k_a = plan->p4_k_a.p; o.k_b = plan->p4_k_b.p;
+        o.k_alen = plan->p4_k_alen.p; o.k_blen = plan->p4_k_blen.p;
+        o.masks = plan->p4_masks.p;
+        o.mask_stride = int64_t(plan->p4_max_ua) * plan->p4_words;
+    }
     return o;
 }
 
@@ -449,17 +504,19 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     for (int l = 0; l < 4; ++l) E->mode_order[l] = l;
     E->device = Ea->device;
     P4Args A = p4_args(plan);
-    int64_t pairs = 0, rows = 0, nnz = 0, roots = 0;
-    DevBuf<int64_t> c_rows, c_leaves, row_off, leaf_off, flag, node_of;
+    int64_t pairs = 0, rows = 0, nnz = 0, roots = 0, total_k = 0;
+    DevBuf<int64_t> c_rows, c_leaves, c_shared, k_off, row_off, leaf_off, flag, node_of;
     if (nc > 0) {
         CST_TRY(c_rows.alloc(size_t(nc)));
         CST_TRY(c_leaves.alloc(size_t(nc)));
+        CST_TRY(c_shared.alloc(size_t(nc)));
+        CST_TRY(k_off.alloc(size_t(nc)));
         CST_TRY(row_off.alloc(size_t(nc)));
         CST_TRY(leaf_off.alloc(size_t(nc)));
         CST_TRY(flag.alloc(size_t(nc)));
         CST_TRY(node_of.alloc(size_t(nc)));
         P4Out none{};
-        sppair4_symbolic_kernel<<<dim3(unsigned(nc)), 64 * kP4Waves, size_t(sym_bytes), st>>>(A, none, S, 0, c_rows.p, c_leaves.p,
+        sppair4_symbolic_kernel<<<dim3(unsigned(nc)), 64 * kP4Waves, size_t(sym_bytes), st>>>(A, none, S, 0, c_rows.p, c_leaves.p, c_shared.p, nullptr,
                                                                                            nullptr, nullptr, nullptr);
         CST_HIP(hipGetLastError());
         CST_TRY(exscan(c_rows.p, row_off.p, nc, &rows));
@@ -467,6 +524,20 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
         sppair4_flag_kernel<<<p4_grid(nc), 256, 0, st>>>(c_leaves.p, nc, flag.p);
         CST_HIP(hipGetLastError());
         CST_TRY(exscan(flag.p, node_of.p, nc, &pairs));
+        CST_TRY(exscan(c_shared.p, k_off.p, nc, &total_k));
+    }
+    // shared K lists and bit matrices are kept for the numeric pass when they are of modest size
+    const int64_t mask_words = pairs * int64_t(plan->p4_max_ua) * plan->p4_words;
+    plan->p4_stored = (mask_words * 4 + total_k * 24) <= (env_int("CONSTSTN_SPPAIR4_KEEP_GB", 4) << 30) &&
+                      env_int("CONSTSTN_SPPAIR4_KEEP", 1) == 1;
+    if (plan->p4_stored) {
+        CST_TRY(plan->p4_k_ptr.alloc(size_t(pairs + 1)));
+        CST_TRY(plan->p4_k_a.alloc(size_t(total_k)));
+        CST_TRY(plan->p4_k_b.alloc(size_t(total_k)));
+        CST_TRY(plan->p4_k_alen.alloc(size_t(total_k)));
+        CST_TRY(plan->p4_k_blen.alloc(size_t(total_k)));
+        CST_TRY(plan->p4_masks.alloc(size_t(mask_words)));
+        CST_HIP(hipMemcpy(plan->p4_k_ptr.p + pairs, &total_k, sizeof(int64_t), hipMemcpyHostToDevice));
     }
     CST_TRY(E->idx[1].alloc(size_t(pairs)));
     CST_TRY(E->ptr[1].alloc(size_t(pairs + 1)));
@@ -479,7 +550,7 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     E->nnz = nnz;
     P4Out O = p4_out(plan);
     if (pairs > 0) {
-        sppair4_symbolic_kernel<<<dim3(unsigned(nc)), 64 * kP4Waves, size_t(sym_bytes), st>>>(A, O, S, 1, c_rows.p, c_leaves.p,
+        sppair4_symbolic_kernel<<<dim3(unsigned(nc)), 64 * kP4Waves, size_t(sym_bytes), st>>>(A, O, S, 1, c_rows.p, c_leaves.p, c_shared.p, k_off.p,
                                                                                            row_off.p, leaf_off.p, node_of.p);
         CST_HIP(hipGetLastError());
     }

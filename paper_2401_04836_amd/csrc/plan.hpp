@@ -210,6 +210,11 @@ struct conststn_plan_s {
     cst::DevBuf<int32_t> p4_node_a, p4_node_b, p4_root_a;   // per (i,j) node / per root of the result: root nodes of the operands
     int p4_words = 0, p4_max_ua = 0, p4_max_ub = 0, p4_max_common = 0, p4_mp = 0, p4_np = 0;
     std::vector<int> p4_layout;
+    bool p4_stored = false;                              // shared-K lists and bit matrices kept from the symbolic pass
+    cst::DevBuf<int64_t> p4_k_ptr;
+    cst::DevBuf<int64_t> p4_k_a, p4_k_b;                 // first leaf of each shared K's row in the two operands
+    cst::DevBuf<int32_t> p4_k_alen, p4_k_blen;           // and its length
+    cst::DevBuf<uint32_t> p4_masks;
 
     // measurement hook: event pairs around the dominant kernel of each execute
     mutable std::vector<hipEvent_t> prof_start, prof_stop;
