@@ -462,6 +462,12 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
         else snprintf(b, sizeof(b), " kernel=general lds %d", plan->sc_lds_bytes);
         plan->description += b;
     }
+    if (plan->family == FAM_SPPAIR4) {
+        char b[96];
+        snprintf(b, sizeof(b), " kernel=%s lds %d", plan->p4_dense ? "dense rows" : plan->p4_stored ? "leaf lists kept" : "nothing kept",
+                 plan->p4_layout.empty() ? 0 : plan->p4_layout.back());
+        plan->description += b;
+    }
     for (size_t p = 0; p + 1 < plan->sched.stmts.size(); ++p) {
         char b[128];
         snprintf(b, sizeof(b), " %s:order%d", plan->sched.stmts[p].out.name.c_str(), plan->sched.stmts[p].reduced_order);

@@ -21,12 +21,13 @@
 //             accumulators stay in registers; stored elements are written in place.  No atomics on
 //             values; the K are visited in ascending order.
 #include "plan.hpp"
+#include <type_traits>
 
 namespace cst {
 
 constexpr int kP4Waves = 16;                 // wavefronts per workgroup
 constexpr int kP4Chunk = 8;                // shared K staged per pass
-constexpr int kP4Tiles = 8;                // result tiles a wavefront keeps in registers
+constexpr int kP4Tiles = 9;                // result tiles a wavefront keeps in registers
 
 typedef double p4_v4d __attribute__((ext_vector_type(4)));
 
@@ -38,6 +39,10 @@ struct P4Side {                             // one operand: levels (root, K, lea
     const int32_t *u_list;
     const uint16_t *slot;                   // ... and every leaf's place among them
     int64_t roots;
+    // dense rows (when the plan keeps them): every level-1 node's leaves spread over its root's distinct
+    // innermost indices, padded to whole tiles; row_at = first element of the node's row
+    const double *dense;
+    const int64_t *row_at;
 };
 
 struct P4Args {
@@ -56,8 +61,9 @@ struct P4Out {
     // kept from the symbolic pass when they fit: per (i,j) node the shared K (level-1 nodes of the two
     // operands, ascending K) and the bit matrix, so that the numeric pass need not find them again
     int64_t *k_ptr;                         // [pairs + 1]
-    int64_t *k_a, *k_b;                     // first leaf of the K's row in Ea / Eb ...
+    int64_t *k_a, *k_b;                     // first leaf of the K's row in Ea / Eb (first element of its dense row if dense) ...
     int32_t *k_alen, *k_blen;               // ... and its length
+    int dense;                              // the operands' dense rows are kept
     uint32_t *masks;                        // [pairs x mask_stride]
     int64_t mask_stride;
 };
@@ -205,9 +211,9 @@ sppair4_symbolic_kernel(P4Args A, P4Out V, P4SymLds O, int mode, int64_t *rows, 
         if (threadIdx.x == 0) V.k_ptr[node] = k0;
         for (int x = threadIdx.x; x < n_shared; x += 64 * kP4Waves) {
             const int64_t a0 = A.a.ptr1[match_a[x]], b0 = A.b.ptr1[match_b[x]];
-            V.k_a[k0 + x] = a0;
+            V.k_a[k0 + x] = V.dense ? A.a.row_at[match_a[x]] : a0;
             V.k_alen[k0 + x] = int32_t(A.a.ptr1[match_a[x] + 1] - a0);
-            V.k_b[k0 + x] = b0;
+            V.k_b[k0 + x] = V.dense ? A.b.row_at[match_b[x]] : b0;
             V.k_blen[k0 + x] = int32_t(A.b.ptr1[match_b[x] + 1] - b0);
         }
         for (int x = threadIdx.x; x < n_ua * A.W; x += 64 * kP4Waves) V.masks[node * V.mask_stride + x] = rowmask[x];
@@ -265,11 +271,49 @@ __global__ void sppair4_root_fill_kernel(P4Args A, P4Out V, const int64_t *__res
     }
 }
 
+// ---- dense rows of an operand -----------------------------------------------------------------
+__device__ __forceinline__ int64_t p4_pitch(const P4Side &T, int64_t r) { return (T.u_ptr[r + 1] - T.u_ptr[r] + 15) / 16 * 16; }
+
+__global__ void sppair4_row_size_kernel(P4Side T, int64_t *size) {
+    const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (r < T.roots) size[r] = (T.ptr0[r + 1] - T.ptr0[r]) * p4_pitch(T, r);
+}
+
+__global__ void sppair4_row_at_kernel(P4Side T, const int64_t *__restrict__ base, int64_t n1, int64_t *row_at) {
+    const int64_t nd = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (nd >= n1) return;
+    const int64_t r = parent_of(T.ptr0, T.roots, nd);
+    row_at[nd] = base[r] + (nd - T.ptr0[r]) * p4_pitch(T, r);
+}
+
+// One wavefront per level-1 node: the row is put together in LDS (zeros, then the leaves at their
+// places) and written out whole.  `cap` doubles of LDS per wavefront hold the longest row.
+constexpr int kP4DenseWaves = 4;
+__global__ void __launch_bounds__(64 * kP4DenseWaves)
+sppair4_dense_kernel(P4Side T, const int64_t *__restrict__ row_at, int64_t n1, int cap, double *__restrict__ dense) {
+    extern __shared__ double p4_rows[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t nd = int64_t(blockIdx.x) * kP4DenseWaves + wave;
+    if (nd >= n1) return;
+    double *row = p4_rows + size_t(wave) * cap;
+    const int64_t r = parent_of(T.ptr0, T.roots, nd);
+    const int pitch = int(p4_pitch(T, r));
+    for (int x = lane; x < pitch; x += 64) row[x] = 0.0;
+    p4_wave_sync();
+    for (int64_t l = T.ptr1[nd] + lane; l < T.ptr1[nd + 1]; l += 64) row[T.slot[l]] = T.vals[l];
+    p4_wave_sync();
+    double *dst = dense + row_at[nd];
+    for (int x = lane; x < pitch; x += 64) dst[x] = row[x];
+}
+
 // LDS of the numeric kernel
 struct P4NumLds {
-    int match_a, match_b, rowmask, nmask, rowleaf, rowrank, scratch, achunk, bchunk, total;
+    int match_a, match_b, rowmask, nmask, rowleaf, rowrank, scratch, rowpre, achunk, bchunk, total;
 };
 
+// DENSE: the rows of the chunk matrices are copied from the operands' dense rows; otherwise they are
+// put together from the leaf lists.
+template <bool DENSE>
 __global__ void __launch_bounds__(64 * kP4Waves)
 sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
     extern __shared__ unsigned char lds[];
@@ -278,11 +322,15 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
     int32_t *rowleaf = reinterpret_cast<int32_t *>(lds + O.rowleaf), *rowrank = reinterpret_cast<int32_t *>(lds + O.rowrank);
     int *scratch = reinterpret_cast<int *>(lds + O.scratch);
     double *Ac = reinterpret_cast<double *>(lds + O.achunk), *Bc = reinterpret_cast<double *>(lds + O.bchunk);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t *rowpre = reinterpret_cast<int32_t *>(lds + O.rowpre);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave: the same in every lane
+    const int side = wave & 1, krow = wave >> 1;
     const int nthreads = 64 * kP4Waves;
     const int64_t node = blockIdx.x;
     const int64_t ra = V.node_a[node], rb = V.node_b[node];
-    const int n_ua = int(A.a.u_ptr[ra + 1] - A.a.u_ptr[ra]), n_ub = int(A.b.u_ptr[rb + 1] - A.b.u_ptr[rb]);
+    // block-wide values are moved to scalar registers, so that the tests on them cost no vector instructions
+    const int n_ua = __builtin_amdgcn_readfirstlane(int(A.a.u_ptr[ra + 1] - A.a.u_ptr[ra]));
+    const int n_ub = __builtin_amdgcn_readfirstlane(int(A.b.u_ptr[rb + 1] - A.b.u_ptr[rb]));
     const int64_t leaf0 = V.ptr2[V.ptr1[node]];
     int n_shared;
     const int64_t *k_first = nullptr;       // kept by the plan: leaf range of every shared K, this wavefront's operand
@@ -290,8 +338,8 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
     if (V.k_ptr) {
         const int64_t kp = V.k_ptr[node];
         n_shared = int(V.k_ptr[node + 1] - kp);
-        k_first = ((threadIdx.x >> 6) & 1 ? V.k_b : V.k_a) + kp;
-        k_len = ((threadIdx.x >> 6) & 1 ? V.k_blen : V.k_alen) + kp;
+        k_first = (side ? V.k_b : V.k_a) + kp;
+        k_len = (side ? V.k_blen : V.k_alen) + kp;
         for (int x = threadIdx.x; x < n_ua * A.W; x += nthreads) rowmask[x] = V.masks[node * V.mask_stride + x];
         __syncthreads();
     } else {
@@ -299,8 +347,18 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
         p4_bit_matrix<kP4Waves>(A, match_a, match_b, n_shared, n_ua, rowmask, nmask);
     }
     p4_row_offsets<kP4Waves>(A, rowmask, n_ua, rowleaf, rowrank);
+    n_shared = __builtin_amdgcn_readfirstlane(n_shared);
+    // position, within the pair's leaves, of the first stored element of every word of the bit matrix
+    for (int r = threadIdx.x; r < n_ua; r += nthreads) {
+        int at = rowleaf[r];
+        for (int w = 0; w < A.W; ++w) {
+            rowpre[r * A.W + w] = at;
+            at += __popc(rowmask[r * A.W + w]);
+        }
+    }
+    __syncthreads();
 
-    const int tiles_n = (n_ub + 15) >> 4, tiles = ((n_ua + 15) >> 4) * tiles_n;
+    const int tiles_n = (n_ub + 15) >> 4;
     const int li = lane & 15, lk = lane >> 4;
     const int mp = A.mp, np = A.np;
     // Chunks of kP4Chunk shared K, double-buffered: every wavefront owns one row of one of the two chunk
@@ -308,99 +366,150 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
     // of its row of chunk c+1 and the leaf range of its row of chunk c+2 are in flight; the row of chunk
     // c+1 is laid out in the other LDS buffer after the pass.
     static_assert(2 * kP4Chunk == kP4Waves, "one chunk row per wavefront");
-    const int side = wave & 1, krow = wave >> 1;
     const P4Side &T = side ? A.b : A.a;
     const int32_t *kn = side ? match_b : match_a;
     const int stride = side ? np : mp;
-    for (int g0 = 0; g0 < tiles; g0 += kP4Waves * kP4Tiles) {          // groups of tiles whose accumulators fit
-        p4_v4d acc[kP4Tiles];
-#pragma unroll
-        for (int s = 0; s < kP4Tiles; ++s) acc[s] = p4_v4d{0.0, 0.0, 0.0, 0.0};
-        int sl[2];
+    // Tiles: the 16 wavefronts form a 4 x 4 grid; wavefront (wm, wn) takes the tiles (wm + 4x, wn + 4y),
+    // x, y < 3, of a super-block of 12 x 12 tiles, so that per depth step three A and three B operands
+    // feed nine matrix-core instructions and the tile origins need no division.
+    static_assert(kP4Waves == 16 && kP4Tiles == 9, "4 x 4 wavefronts, 3 x 3 tiles each");
+    // (the four wavefronts of one SIMD, wave % 4 equal, get four different rows and columns of the grid:
+    // ragged blocks then load the SIMDs evenly)
+    const int wm = wave >> 2, wn = (wave + (wave >> 2)) & 3;
+    const int tiles_m = (n_ua + 15) >> 4;
+    for (int mg = 0; mg < tiles_m; mg += 12)
+    for (int ng = 0; ng < tiles_n; ng += 12) {
+        // tiles x < nx, y < ny of this wavefront lie inside the block (counts, kept in scalar registers)
+        const int nx = max(0, min(3, (tiles_m - mg - wm + 3) >> 2)), ny = max(0, min(3, (tiles_n - ng - wn + 3) >> 2));
+        const int shape = __builtin_amdgcn_readfirstlane(nx > 0 && ny > 0 ? 4 * nx + ny : 0);
+        const int a_off = lk * mp + 16 * (mg + wm) + li, b_off = lk * np + 16 * (ng + wn) + li;   // tile x lies 64 x further
+        int sl[2];                         // leaf lists: the first 128 leaves of the row being fetched
         double vl[2];
-        int64_t r1 = 0, r2 = 0;            // first leaf of this wavefront's row of the next chunk / the one after
-        int n1 = 0, n2 = 0;                // ... and their lengths
+        double dv[4];                      // dense rows: the row being fetched (at most 256 long)
+        int64_t r1 = 0, r2 = 0;            // start of this wavefront's row of the next chunk / the one after (-1: none)
+        int n1 = 0, n2 = 0;                // ... and their lengths (leaf lists)
+        const double *D = side ? A.b.dense : A.a.dense;
+        const int pitch = 16 * (side ? tiles_n : tiles_m);
         auto get_range = [&](int k0, int64_t &first, int &len) {
-            first = 0;
+            first = -1;
             len = 0;
             const int k = k0 + krow;
             if (k < n_shared) {
-                if (k_first) { first = k_first[k]; len = k_len[k]; }
+                if (DENSE) first = k_first[k];
+                else if (k_first) { first = k_first[k]; len = k_len[k]; }
                 else { const int64_t nd = kn[k]; first = T.ptr1[nd]; len = int(T.ptr1[nd + 1] - first); }
             }
         };
         auto get_leaves = [&](int64_t first, int len) {
+            if (DENSE) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int l = 64 * h + lane;
-                sl[h] = -1;
-                vl[h] = 0.0;
-                if (l < len) { sl[h] = T.slot[first + l]; vl[h] = T.vals[first + l]; }
+                for (int h = 0; h < 4; ++h) {
+                    const int x = 64 * h + lane;
+                    dv[h] = (first >= 0 && x < pitch) ? D[first + x] : 0.0;
+                }
+            } else {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int l = 64 * h + lane;
+                    sl[h] = -1;
+                    vl[h] = 0.0;
+                    if (l < len) { sl[h] = T.slot[first + l]; vl[h] = T.vals[first + l]; }
+                }
             }
         };
         auto lay_out = [&](int buf, int64_t first, int len) {
             double *row = (side ? Bc + buf * kP4Chunk * np : Ac + buf * kP4Chunk * mp) + krow * stride;
-            for (int x = lane; x < stride; x += 64) row[x] = 0.0;
-            p4_wave_sync();
+            if (DENSE) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                if (sl[h] >= 0) row[sl[h]] = vl[h];
-            for (int l = 128 + lane; l < len; l += 64) row[T.slot[first + l]] = T.vals[first + l];    // rows beyond 128 leaves
-        };
-        __syncthreads();                                               // the buffers of the previous group are no longer read
-        get_range(0, r1, n1);
-        get_range(kP4Chunk, r2, n2);
-        get_leaves(r1, n1);
-        lay_out(0, r1, n1);
-        r1 = r2;
-        n1 = n2;
-        for (int k0 = 0, c = 0; k0 < n_shared; k0 += kP4Chunk, ++c) {
-            __syncthreads();                                           // chunk c laid out; chunk c-1 no longer read
-            const bool more = k0 + kP4Chunk < n_shared;
-            if (more) {
-                get_leaves(r1, n1);                                    // chunk c+1 (range fetched a pass ago)
-                get_range(k0 + 2 * kP4Chunk, r2, n2);                  // chunk c+2
+                for (int h = 0; h < 4; ++h) {
+                    const int x = 64 * h + lane;
+                    if (x < pitch) row[x] = dv[h];
+                }
+            } else {
+                for (int x = lane; x < stride; x += 64) row[x] = 0.0;
+                p4_wave_sync();
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    if (sl[h] >= 0) row[sl[h]] = vl[h];
+                for (int l = 128 + lane; l < len; l += 64) row[T.slot[first + l]] = T.vals[first + l];    // rows beyond 128 leaves
             }
-            const double *Ab = Ac + (c & 1) * kP4Chunk * mp, *Bb = Bc + (c & 1) * kP4Chunk * np;
+        };
+        // The pass over the shared K and the write-out, compiled once per shape (CX x CY tiles) of the
+        // wavefront's tile set, so that the accumulators stay in fixed registers and no tile is tested
+        // inside the loop.  A wavefront without tiles still fetches and lays out its row.
+        auto run = [&](auto CX, auto CY) {
+            constexpr int cx = decltype(CX)::value, cy = decltype(CY)::value;
+            p4_v4d acc[cx ? cx : 1][cy ? cy : 1];
 #pragma unroll
-            for (int s = 0; s < kP4Tiles; ++s) {
-                const int tile = g0 + wave + s * kP4Waves;
-                if (tile < tiles) {
-                    const int m0 = (tile / tiles_n) << 4, n0 = (tile % tiles_n) << 4;
-                    // chunk matrices are zero beyond the block, so no guards: strides cover the padded tiles
+            for (int x = 0; x < cx; ++x)
 #pragma unroll
-                    for (int kk = 0; kk < kP4Chunk; kk += 4)
-                        acc[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(Ab[(kk + lk) * mp + m0 + li], Bb[(kk + lk) * np + n0 + li],
-                                                                       acc[s], 0, 0, 0);
+                for (int y = 0; y < cy; ++y) acc[x][y] = p4_v4d{0.0, 0.0, 0.0, 0.0};
+            __syncthreads();                                           // the buffers of the previous super-block are no longer read
+            get_range(0, r1, n1);
+            get_range(kP4Chunk, r2, n2);
+            get_leaves(r1, n1);
+            lay_out(0, r1, n1);
+            r1 = r2;
+            n1 = n2;
+            for (int k0 = 0, c = 0; k0 < n_shared; k0 += kP4Chunk, ++c) {
+                const bool more = k0 + kP4Chunk < n_shared;
+                if (more) {                                            // fetches touch no LDS: issued ahead of the barrier
+                    get_leaves(r1, n1);                                // chunk c+1 (range fetched a pass ago)
+                    get_range(k0 + 2 * kP4Chunk, r2, n2);              // chunk c+2
+                }
+                __syncthreads();                                       // chunk c laid out; chunk c-1 no longer read
+                if constexpr (cx > 0 && cy > 0) {
+                    const double *Ab = Ac + (c & 1) * kP4Chunk * mp + a_off, *Bb = Bc + (c & 1) * kP4Chunk * np + b_off;
+#pragma unroll
+                    for (int kk = 0; kk < kP4Chunk; kk += 4) {
+                        double av[cx ? cx : 1], bv[cy ? cy : 1];
+#pragma unroll
+                        for (int x = 0; x < cx; ++x) av[x] = Ab[kk * mp + 64 * x];
+#pragma unroll
+                        for (int y = 0; y < cy; ++y) bv[y] = Bb[kk * np + 64 * y];
+#pragma unroll
+                        for (int x = 0; x < cx; ++x)
+#pragma unroll
+                            for (int y = 0; y < cy; ++y)
+                                acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[x], bv[y], acc[x][y], 0, 0, 0);
+                    }
+                }
+                if (more) {
+                    lay_out((c + 1) & 1, r1, n1);
+                    r1 = r2;
+                    n1 = n2;
                 }
             }
-            if (more) {
-                lay_out((c + 1) & 1, r1, n1);
-                r1 = r2;
-                n1 = n2;
-            }
-        }
-        // lane holds V[i,j][m0 + lk + 4v][n0 + li]; stored elements go to their place
+            // lane holds V[i,j][m0 + lk + 4v][n0 + li]; stored elements go to their place
 #pragma unroll
-        for (int s = 0; s < kP4Tiles; ++s) {
-            const int tile = g0 + wave + s * kP4Waves;
-            if (tile < tiles) {
-                const int m0 = (tile / tiles_n) << 4, n0 = (tile % tiles_n) << 4;
-                const int n = n0 + li;
+            for (int x = 0; x < cx; ++x)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int m = m0 + lk + 4 * v;
-                    if (m < n_ua && n < n_ub) {
-                        const uint32_t *row = rowmask + m * A.W;
-                        const uint32_t word = row[n >> 5];
-                        if ((word >> (n & 31)) & 1u) {
-                            int before = __popc(word & ((1u << (n & 31)) - 1u));
-                            for (int w = 0; w < (n >> 5); ++w) before += __popc(row[w]);
-                            out[leaf0 + rowleaf[m] + before] = acc[s][v];
+                for (int y = 0; y < cy; ++y) {
+                    const int m0 = 16 * (mg + wm + 4 * x), n = 16 * (ng + wn + 4 * y) + li;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int m = m0 + lk + 4 * v;
+                        if (m < n_ua && n < n_ub) {
+                            const int w = m * A.W + (n >> 5);
+                            const uint32_t word = rowmask[w];
+                            if ((word >> (n & 31)) & 1u)
+                                out[leaf0 + rowpre[w] + __popc(word & ((1u << (n & 31)) - 1u))] = acc[x][y][v];
                         }
                     }
                 }
-            }
+        };
+        using std::integral_constant;
+        switch (shape) {
+            case 5: run(integral_constant<int, 1>{}, integral_constant<int, 1>{}); break;
+            case 6: run(integral_constant<int, 1>{}, integral_constant<int, 2>{}); break;
+            case 7: run(integral_constant<int, 1>{}, integral_constant<int, 3>{}); break;
+            case 9: run(integral_constant<int, 2>{}, integral_constant<int, 1>{}); break;
+            case 10: run(integral_constant<int, 2>{}, integral_constant<int, 2>{}); break;
+            case 11: run(integral_constant<int, 2>{}, integral_constant<int, 3>{}); break;
+            case 13: run(integral_constant<int, 3>{}, integral_constant<int, 1>{}); break;
+            case 14: run(integral_constant<int, 3>{}, integral_constant<int, 2>{}); break;
+            case 15: run(integral_constant<int, 3>{}, integral_constant<int, 3>{}); break;
+            default: run(integral_constant<int, 0>{}, integral_constant<int, 0>{}); break;
         }
     }
 }
@@ -416,6 +525,7 @@ static void p4_side(const conststn_csf_s *T, const DevBuf<int64_t> &u_ptr, const
     s.vals = T->vals.p;
     s.u_ptr = u_ptr.p; s.u_list = u_list.p; s.slot = slot.p;
     s.roots = T->nodes[0];
+    s.dense = nullptr; s.row_at = nullptr;
 }
 
 static P4Args p4_args(const conststn_plan_s *plan) {
@@ -428,6 +538,12 @@ static P4Args p4_args(const conststn_plan_s *plan) {
     A.max_common = plan->p4_max_common;
     A.mp = plan->p4_mp;
     A.np = plan->p4_np;
+    if (plan->p4_dense) {
+        const bool same = plan->X == plan->W;                      // one tensor in both places: one set of rows
+        A.a.dense = plan->p4_dense_a.p; A.a.row_at = plan->p4_row_at_a.p;
+        A.b.dense = same ? plan->p4_dense_a.p : plan->p4_dense_b.p;
+        A.b.row_at = same ? plan->p4_row_at_a.p : plan->p4_row_at_b.p;
+    }
     return A;
 }
 
@@ -444,7 +560,26 @@ static P4Out p4_out(const conststn_plan_s *plan) {
         o.masks = plan->p4_masks.p;
         o.mask_stride = int64_t(plan->p4_max_ua) * plan->p4_words;
     }
+    o.dense = plan->p4_dense ? 1 : 0;
     return o;
+}
+
+// Places of an operand's dense rows: per root, (its level-1 nodes) x (its distinct innermost indices,
+// padded to whole tiles) doubles, roots one after the other.
+static conststn_status p4_dense_places(const P4Side &T, int64_t n1, DevBuf<int64_t> &row_at, int64_t *elems) {
+    DevBuf<int64_t> size, base;
+    *elems = 0;
+    if (T.roots == 0 || n1 == 0) return CONSTSTN_OK;
+    CST_TRY(size.alloc(size_t(T.roots)));
+    CST_TRY(base.alloc(size_t(T.roots)));
+    sppair4_row_size_kernel<<<p4_grid(T.roots), 256>>>(T, size.p);
+    CST_HIP(hipGetLastError());
+    CST_TRY(exscan(size.p, base.p, T.roots, elems));
+    CST_TRY(row_at.alloc(size_t(n1)));
+    sppair4_row_at_kernel<<<p4_grid(n1), 256>>>(T, base.p, n1, row_at.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
 }
 
 conststn_status build_sppair4_tables(conststn_plan_s *plan) {
@@ -480,6 +615,7 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     L.rowrank = int(at); at = up16(at + 4 * (max_ua + 1));
     L.scratch = int(at); at = up16(at + 4 * (kP4Waves + 1));
     const int64_t sym_bytes = at;
+    L.rowpre = int(at); at = up16(at + 4 * int64_t(plan->p4_words) * max_ua);
     L.achunk = int(at); at = up16(at + 2 * 8 * int64_t(kP4Chunk) * plan->p4_mp);       // two buffers each
     L.bchunk = int(at); at = up16(at + 2 * 8 * int64_t(kP4Chunk) * plan->p4_np);
     L.total = int(at);
@@ -488,11 +624,12 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
                   (long long)at, plan->p4_max_common, (long long)max_ua, (long long)max_ub);
         return CONSTSTN_EUNSUPPORTED;
     }
-    const int lay[10] = {L.match_a, L.match_b, L.rowmask, L.nmask, L.rowleaf, L.rowrank, L.scratch, L.achunk, L.bchunk, L.total};
-    plan->p4_layout.assign(lay, lay + 10);
+    const int lay[11] = {L.match_a, L.match_b, L.rowmask, L.nmask, L.rowleaf, L.rowrank, L.scratch, L.rowpre, L.achunk, L.bchunk, L.total};
+    plan->p4_layout.assign(lay, lay + 11);
     const P4SymLds S{L.match_a, L.match_b, L.rowmask, L.nmask, L.rowleaf, L.rowrank, L.scratch, int(sym_bytes)};
     CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sppair4_symbolic_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(sym_bytes)));
-    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sppair4_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, L.total));
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sppair4_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, L.total));
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sppair4_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, L.total));
 
     const int64_t nc = Ea->nodes[0] * Eb->nodes[0];
     if (nc > (int64_t(1) << 28)) { set_error("%lld candidate (i,j) pairs; the symbolic pass holds counters per pair", (long long)nc); return CONSTSTN_EUNSUPPORTED; }
@@ -539,6 +676,21 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
         CST_TRY(plan->p4_masks.alloc(size_t(mask_words)));
         CST_HIP(hipMemcpy(plan->p4_k_ptr.p + pairs, &total_k, sizeof(int64_t), hipMemcpyHostToDevice));
     }
+    // Dense rows of the operands (rebuilt from the values by every execute) let the numeric pass copy the
+    // rows of its chunk matrices instead of putting them together leaf by leaf; a wavefront holds a row of
+    // at most 256 in registers while it is in flight.
+    plan->p4_dense = false;
+    if (plan->p4_stored && max_ua <= 256 && max_ub <= 256 && env_int("CONSTSTN_SPPAIR4_ROWS", 1) == 1) {
+        int64_t ea = 0, eb = 0;
+        CST_TRY(p4_dense_places(A.a, Ea->nodes[1], plan->p4_row_at_a, &ea));
+        if (Eb != Ea) CST_TRY(p4_dense_places(A.b, Eb->nodes[1], plan->p4_row_at_b, &eb));
+        if ((ea + eb) * 8 <= (env_int("CONSTSTN_SPPAIR4_ROWS_GB", 8) << 30)) {
+            CST_TRY(plan->p4_dense_a.alloc(size_t(std::max<int64_t>(ea, 1))));
+            if (Eb != Ea) CST_TRY(plan->p4_dense_b.alloc(size_t(std::max<int64_t>(eb, 1))));
+            plan->p4_dense = true;
+            A = p4_args(plan);
+        }
+    }
     CST_TRY(E->idx[1].alloc(size_t(pairs)));
     CST_TRY(E->ptr[1].alloc(size_t(pairs + 1)));
     CST_TRY(E->idx[2].alloc(size_t(rows)));
@@ -578,11 +730,24 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
 conststn_status launch_sppair4(const conststn_plan_s *plan, double *out, hipStream_t stream) {
     const P4Args A = p4_args(plan);
     const P4Out O = p4_out(plan);
-    ProfScope prof(plan, stream);
     if (O.pairs == 0) return CONSTSTN_OK;
     const std::vector<int> &l = plan->p4_layout;
-    const P4NumLds L{l[0], l[1], l[2], l[3], l[4], l[5], l[6], l[7], l[8], l[9]};
-    sppair4_kernel<<<dim3(unsigned(O.pairs)), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
+    const P4NumLds L{l[0], l[1], l[2], l[3], l[4], l[5], l[6], l[7], l[8], l[9], l[10]};
+    if (plan->p4_dense) {
+        const int64_t n1a = plan->X->nodes[1], n1b = plan->W->nodes[1];
+        const int cap_a = (plan->p4_max_ua + 15) / 16 * 16, cap_b = (plan->p4_max_ub + 15) / 16 * 16;
+        sppair4_dense_kernel<<<p4_grid(n1a, kP4DenseWaves), 64 * kP4DenseWaves, size_t(kP4DenseWaves) * cap_a * 8, stream>>>(
+            A.a, A.a.row_at, n1a, cap_a, plan->p4_dense_a.p);
+        CST_HIP(hipGetLastError());
+        if (plan->W != plan->X) {
+            sppair4_dense_kernel<<<p4_grid(n1b, kP4DenseWaves), 64 * kP4DenseWaves, size_t(kP4DenseWaves) * cap_b * 8, stream>>>(
+                A.b, A.b.row_at, n1b, cap_b, plan->p4_dense_b.p);
+            CST_HIP(hipGetLastError());
+        }
+    }
+    ProfScope prof(plan, stream);
+    if (plan->p4_dense) sppair4_kernel<true><<<dim3(unsigned(O.pairs)), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
+    else sppair4_kernel<false><<<dim3(unsigned(O.pairs)), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
     CST_HIP(hipGetLastError());
     return CONSTSTN_OK;
 }

@@ -111,6 +111,34 @@ def test_blocks_larger_than_one_tile_group_and_many_shared_k():
     assert worst <= TOL
 
 
+@pytest.mark.parametrize("env", [{"CONSTSTN_SPPAIR4_ROWS": "2"}, {"CONSTSTN_SPPAIR4_KEEP": "2"}, {}],
+                         ids=["leaf-lists", "nothing-kept", "dense-rows"])
+@pytest.mark.parametrize("n_m", [200, 300])
+def test_every_form_of_the_numeric_pass(env, n_m, monkeypatch):
+    # the chunk rows copied from dense rows (default, inner dimension <= 256), put together from leaf
+    # lists kept by the plan, or found again by every launch; 300 distinct inner indices exceed one
+    # 12 x 12 group of tiles and the dense form, and give rows of more than 128 leaves
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    dims = (40, 3, n_m)
+    Ec, Ev = _rand_e(5110 + n_m, dims, 40 * 3 * n_m * 6 // 10)
+    (ci, cj, cm, cn), vals, desc = _run(Ec, Ev, dims)
+    _say("%s: %s" % (env, desc.split("|")[0]))
+    want_kernel = "nothing kept" if "CONSTSTN_SPPAIR4_KEEP" in env else "dense rows" if not env and n_m <= 256 else "leaf lists kept"
+    assert "kernel=" + want_kernel in desc, desc
+    worst = 0.0
+    for i in range(3):
+        for j in range(3):
+            want, S_abs, N = spsp.pair4_block(Ec, Ev, dims, i, j)
+            sel = (ci == i) & (cj == j)
+            G = np.zeros_like(want); M = np.zeros(want.shape, dtype=bool)
+            G[cm[sel], cn[sel]] = vals[sel]
+            M[cm[sel], cn[sel]] = True
+            np.testing.assert_array_equal(M, N)
+            worst = max(worst, oracle.rel_err(G, want, S_abs))
+    assert worst <= TOL
+
+
 def test_lattice_integrals_from_the_three_index_tensor():
     # E from the reference of the chain on a 5 x 5 lattice, then V = E x E: the pipeline of Sec. 5.1
     wl = make_lattice_chain("lat5", 4101, 5, 3, 6, 1.5, 2.0, 1.5, 2.5)
