@@ -157,6 +157,9 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
     const int64_t s0 = int64_t(group) * kSpGroup;
     const int64_t k_lo = int64_t(kc) * a.k_per, k_hi = k_lo + a.k_per;
     const int64_t L = a.L;
+    const int L32 = int(a.L);
+    const char *Vbytes = reinterpret_cast<const char *>(a.V);
+    const uint32_t lane16 = uint32_t(lane) * 16u;
     const int nwords = a.nwords;
     double *Wbw = Wb + wave * (kStage * 256);
     // the same area through an LDS-typed pointer, so that reads of it stay LDS instructions
@@ -307,19 +310,21 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
                 };
                 auto issue = [&](const int32_t (&J)[kBatch], double (&Vv)[kBatch], double (&Uu)[kBatch], v2d (&Ww)[2]) {
                     const int tt = min(t2, NT - 1);
-                    const int col = int(min(int64_t(16 * (wave + 4 * (tr + tt)) + c), L - 1));
+                    const int col = min(16 * (wave + 4 * (tr + tt)) + c, L32 - 1);
+                    // 32-bit element offsets against the scalar base of V (J L < 2^29, checked by the plan):
+                    // one vector instruction per address
 #pragma unroll
                     for (int ks = 0; ks < kBatch; ++ks) {
-                        Vv[ks] = a.V[J[ks] + col];
+                        Vv[ks] = *reinterpret_cast<const double *>(Vbytes + (uint32_t(J[ks] + col) << 3));
                         Uu[ks] = Uc[q2 * (64 * kBatch) + ks * 64 + lane];
                     }
                     const uint32_t m2 = __builtin_amdgcn_readlane(mreg, tt);
                     const uint32_t f2 = __builtin_amdgcn_readlane(freg, tt);
-                    const int have = __popc(m2);
-                    const int tq = max(min(min(q2, kStage - 1), have - 1), 0);
-                    const double *tp = a.wtiles + (int64_t(f2) + tq) * 256 + lane * 2;
-                    Ww[0] = *reinterpret_cast<const v2d *>(tp);
-                    Ww[1] = *reinterpret_cast<const v2d *>(tp + 128);
+                    const int last = max(__popc(m2) - 1, 0);
+                    const int tq = min(min(q2, kStage - 1), last);            // all scalar
+                    const char *tb = reinterpret_cast<const char *>(a.wtiles + (int64_t(f2) + tq) * 256);
+                    Ww[0] = *reinterpret_cast<const v2d *>(tb + lane16);
+                    Ww[1] = *reinterpret_cast<const v2d *>(tb + lane16 + 1024);
                     if (q2 + 1 == nBt) { q2 = 0; ++t2; } else ++q2;
                 };
                 auto consume = [&](int b, const double (&Vv)[kBatch], const double (&Uu)[kBatch], const v2d (&Ww)[2]) {

@@ -859,7 +859,7 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     const int64_t K = W->dims[W->mode_order[0]];
     plan->w_tiled = false;
     if (env_int("CONSTSTN_SPTN3_TILED", 1) == 2) return CONSTSTN_OK;          // 2 = baseline kernel
-    if (M > 16 * kSpMaxMTiles || J > kSpMaxJ || J * L >= (int64_t(1) << 31) || W->nnz == 0 || U->nnz == 0)
+    if (M > 16 * kSpMaxMTiles || J > kSpMaxJ || J * L >= (int64_t(1) << 29) || W->nnz == 0 || U->nnz == 0)
         return CONSTSTN_OK;
     const int64_t roots = W->nodes[0], fibers = W->nodes[1];
     const int64_t LT = div_up(L, 16), cells = roots * LT;
