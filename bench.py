@@ -29,7 +29,7 @@ KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "sptn3": ["kernels_sptn3.hip", "partition.hip"],
                   "spchain3": ["kernels_spchain3.hip"], "sppair4": ["kernels_sppair4.hip"]}
 KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
-                "ttmc3": "ttmc3_mfma_kernel<4,2>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_tiled_kernel",
+                "ttmc3": "ttmc3_mfma_kernel<4,2>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_owned_kernel",
                 "spchain3": "spchain3_local_kernel", "sppair4": "sppair4_kernel",
                 "generic": "generic_stmt_kernel (one launch per statement)"}
 # what bounds the dominant kernel of each family: the order-3 forms stream far more bytes than they

@@ -450,7 +450,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
     if (plan->family == FAM_SPTN3) {
         char b[96];
         if (plan->w_tiled)
-            snprintf(b, sizeof(b), " kernel=tiled k chunks %d w tiles %lld", plan->sp_kc, (long long)plan->n_w_tiles);
+            snprintf(b, sizeof(b), " kernel=tiled %s k chunks %d w tiles %lld", plan->sp_two_waves ? "two waves per SIMD" : "one wave per SIMD",
+                     plan->sp_kc, (long long)plan->n_w_tiles);
         else
             snprintf(b, sizeof(b), " kernel=baseline");
         plan->description += b;

@@ -442,6 +442,356 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
     }
 }
 
+// ---- tiled kernel with two wavefronts per SIMD ------------------------------------------------
+// The kernel above keeps Z^t for all m tiles of its l tiles in 200 accumulator registers, which
+// leaves room for one wavefront per SIMD; fp64 matrix instructions then issue at two thirds of
+// the rate two wavefronts reach, and every vector instruction in between costs three times as
+// much.  Here a workgroup has eight wavefronts (two per SIMD).  The producer is unchanged: in a
+// *round* wavefront w computes T^t of l tile 8 r + w.  The consumer is split by m instead of by
+// l: wavefront w owns the m tiles w, w + 8, w + 16, w + 24 (four accumulator tiles, kept in
+// registers across all k of the workgroup), the eight T^t of a round go through LDS, and after
+// a barrier every wavefront multiplies its own W tiles of all eight l tiles.  The W tiles of a
+// round are fetched by the eight wavefronts in turn, one per producer batch, and parked in a pool
+// of LDS slots shared by the workgroup (slot = rank of the tile among the round's tiles); what
+// does not fit, or exceeds eight tiles per batch, is fetched when it is used.
+constexpr int kOwnWaves = 8;
+constexpr int kOwnZ = (kSpMaxMTiles + kOwnWaves - 1) / kOwnWaves;       // accumulator tiles per wavefront
+constexpr int kPool = 48;                                             // W tiles parked per round
+
+struct SpPipeO {
+    double Vr[kRing][kBatch], Ur[kRing][kBatch];
+    int32_t Jr[kRing][kBatch];
+    v2d Wr[kRing][2];
+    int Sr[kRing];                                                    // pool slot of the W tile (-1: not parked)
+};
+
+__global__ void __launch_bounds__(64 * kOwnWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
+sptn3_owned_kernel(Sptn3TileArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *Uc = reinterpret_cast<double *>(smem);                        // kCap x 16
+    double *Pool = Uc + kCap * 16;                                        // kPool x 256
+    double *Tx = Pool + kPool * 256;                                      // 8 x 256: T^t of the round's l tiles
+    int32_t *jl = reinterpret_cast<int32_t *>(Tx + kOwnWaves * 256);      // kCap: row offset j*L
+    uint32_t *mask = reinterpret_cast<uint32_t *>(jl + kCap);             // nwords
+    int32_t *wpre = reinterpret_cast<int32_t *>(mask + a.nwords);         // nwords
+    int32_t *scan = wpre + a.nwords;                                      // 8
+
+    const int tid = threadIdx.x, lane = tid & 63, slot = lane >> 4, c = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_wg = a.n_groups * a.n_kc, per_xcd = (n_wg + 7) / 8;
+    const int logical = a.xcd_ranges ? (int(blockIdx.x) % 8) * per_xcd + int(blockIdx.x) / 8 : int(blockIdx.x);
+    if (logical >= n_wg) return;
+    const int group = logical % a.n_groups, kc = logical / a.n_groups;
+    const int64_t s0 = int64_t(group) * kSpGroup;
+    const int64_t k_lo = int64_t(kc) * a.k_per, k_hi = k_lo + a.k_per;
+    const int64_t L = a.L;
+    const int L32 = int(a.L);
+    const int LT = int(a.LT);
+    const char *Vbytes = reinterpret_cast<const char *>(a.V);
+    const uint32_t lane16 = uint32_t(lane) * 16u;
+    const int nwords = a.nwords;
+    const lds_v2d *PoolV = (const lds_v2d *)(Pool);
+    const lds_v2d *TxV = (const lds_v2d *)(Tx);
+    // m tiles of this wavefront, as a mask over the 25
+    uint32_t own = 0u;
+#pragma unroll
+    for (int x = 0; x < kOwnZ; ++x)
+        if (wave + kOwnWaves * x < a.MT) own |= 1u << (wave + kOwnWaves * x);
+
+    // lane c (in each of the four lane rows) holds the cursor of slice s0 + c
+    int64_t cur = 0, end = 0;
+    if (s0 + c < a.slices) {
+        const int64_t na = a.uptr0[s0 + c], nb = a.uptr0[s0 + c + 1];
+        cur = lower_bound_i32(a.uidx1, na, nb, k_lo);
+        end = lower_bound_i32(a.uidx1, cur, nb, k_hi);
+    }
+    v4d accZ[kOwnZ];
+#pragma unroll
+    for (int x = 0; x < kOwnZ; ++x) accZ[x] = v4d{0.0, 0.0, 0.0, 0.0};
+    const int rounds = (LT + kOwnWaves - 1) / kOwnWaves;
+
+    for (;;) {
+        const int32_t kk = cur < end ? a.uidx1[cur] : INT32_MAX;
+        int32_t kmin = kk;
+        kmin = min(kmin, __shfl_xor(kmin, 8, 16));
+        kmin = min(kmin, __shfl_xor(kmin, 4, 16));
+        kmin = min(kmin, __shfl_xor(kmin, 2, 16));
+        kmin = min(kmin, __shfl_xor(kmin, 1, 16));
+        kmin = __builtin_amdgcn_readfirstlane(kmin);
+        if (kmin == INT32_MAX) break;
+        const bool has = kk == kmin;
+        const int64_t f = cur;
+        cur += has ? 1 : 0;
+        const int64_t root = a.w_root_of_k[kmin];                         // same address in every lane
+        if (root < 0) continue;                                           // W has nothing at this k
+        int64_t la = 0, lb = 0;
+        if (has) { la = a.uptr1[f]; lb = a.uptr1[f + 1]; }
+        // two lane rows per slice: slice 2*wave + slot/2, leaves of parity slot%2
+        const int irow = 2 * wave + (slot >> 1), half = slot & 1;
+        const int64_t ea = __shfl(la, irow), eb = __shfl(lb, irow);
+        __syncthreads();                                                  // LDS of the previous k is free
+        for (int w = tid; w < nwords; w += 64 * kOwnWaves) mask[w] = 0u;
+        __syncthreads();
+        // the first kHeldO leaves per lane stay in registers for the scatter below
+        constexpr int kHeldO = kHeld / 2;
+        int32_t jheld[kHeldO];
+        double vheld[kHeldO];
+#pragma unroll
+        for (int h = 0; h < kHeldO; ++h) {
+            const int64_t e = ea + c + 16 * (2 * h + half);
+            jheld[h] = e < eb ? a.uidx2[e] : -1;
+            vheld[h] = e < eb ? a.uvals[e] : 0.0;
+        }
+#pragma unroll
+        for (int h = 0; h < kHeldO; ++h)
+            if (jheld[h] >= 0) atomicOr(&mask[jheld[h] >> 5], 1u << (jheld[h] & 31));
+        for (int64_t e = ea + c + 16 * (2 * kHeldO + half); e < eb; e += 32) {
+            const int32_t j = a.uidx2[e];
+            atomicOr(&mask[j >> 5], 1u << (j & 31));
+        }
+        __syncthreads();
+        {   // exclusive prefix of the set-bit counts of the mask words (thread t: words 2t, 2t+1)
+            int cnt[2], mine = 0;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int w = 2 * tid + q;
+                cnt[q] = w < nwords ? __popc(mask[w]) : 0;
+                mine += cnt[q];
+            }
+            int incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d);
+                if (lane >= d) incl += up;
+            }
+            if (lane == 63) scan[wave] = incl;
+            __syncthreads();
+            int base = 0;
+            for (int w = 0; w < wave; ++w) base += scan[w];
+            int run = base + incl - mine;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int w = 2 * tid + q;
+                if (w < nwords) wpre[w] = run;
+                run += cnt[q];
+            }
+        }
+        int n_union = 0;
+#pragma unroll
+        for (int w = 0; w < kOwnWaves; ++w) n_union += scan[w];
+        n_union = __builtin_amdgcn_readfirstlane(n_union);
+        __syncthreads();
+
+        auto prepare = [&](int p0, int np, int npad, auto first) {
+            for (int x = tid; x < npad * 16; x += 64 * kOwnWaves) Uc[x] = 0.0;
+            if (tid < npad - np) jl[np + tid] = 0;
+            for (int w = tid; w < nwords; w += 64 * kOwnWaves) {
+                uint32_t m = mask[w];
+                int r = wpre[w] - p0;
+                while (m) {
+                    const int b = __builtin_ctz(m);
+                    m &= m - 1u;
+                    if (r >= 0 && r < np) jl[r] = int32_t(int64_t(w * 32 + b) * L);
+                    ++r;
+                }
+            }
+            __syncthreads();
+            auto place = [&](int32_t j, double v) {
+                const int r = wpre[j >> 5] + __popc(mask[j >> 5] & ((1u << (j & 31)) - 1u)) - p0;
+                if (r >= 0 && r < np) Uc[r * 16 + irow] = v;
+            };
+            if (decltype(first)::value) {
+#pragma unroll
+                for (int h = 0; h < kHeldO; ++h)
+                    if (jheld[h] >= 0) place(jheld[h], vheld[h]);
+            }
+            for (int64_t e = ea + c + 16 * ((decltype(first)::value ? 2 * kHeldO : 0) + half); e < eb; e += 32)
+                place(a.uidx2[e], a.uvals[e]);
+            __syncthreads();
+        };
+        int p0 = 0;
+        int np = min(kCap, n_union);
+        int npad = (np + 4 * kBatch - 1) & ~(4 * kBatch - 1);                 // whole batches
+        if (n_union > 0) prepare(0, np, npad, std::true_type{});
+        while (p0 < n_union) {
+            const int nBt = npad / (4 * kBatch);                          // batches per l tile
+            for (int r0 = 0; r0 < rounds; r0 += 8) {                      // 8 rounds = 64 l tiles: one mask per lane
+                const int NR = min(8, rounds - r0);
+                uint32_t mreg = 0u, freg = a.zero_tile;
+                if (8 * r0 + lane < LT) {
+                    const int64_t cell = root * a.LT + (8 * r0 + lane);
+                    mreg = a.wmask[cell];
+                    freg = mreg ? a.wfirst[cell] : a.zero_tile;
+                }
+                const int TB = NR * nBt;
+                SpPipeO P;
+                v4d accT0 = v4d{0.0, 0.0, 0.0, 0.0}, accT1 = accT0;
+                int t0 = 0, q0 = 0;                                       // batch being consumed: (round, batch in it)
+                int t2 = 0, q2 = 0;                                       // batch whose V/U/W loads are issued
+                int q3 = 0;                                               // batch whose j offsets are read
+                // The W tiles of round t2, in the order (l tile, m tile), are fetched by the eight wavefronts
+                // in turn (tile n by wavefront n % 8 with its batch n / 8) into pool slot n: cursor of that walk
+                int ct = 8;                                               // l tile of the round under the cursor (8: none left)
+                uint32_t cfull = 0u;                                      // its mask
+                int cbase = 0;                                            // tiles of the round before l tile ct
+
+                auto read_j = [&](int32_t (&J)[kBatch]) {
+#pragma unroll
+                    for (int ks = 0; ks < kBatch; ++ks) J[ks] = jl[q3 * (4 * kBatch) + ks * 4 + slot];
+                    q3 = q3 + 1 == nBt ? 0 : q3 + 1;
+                };
+                auto issue = [&](const int32_t (&J)[kBatch], double (&Vv)[kBatch], double (&Uu)[kBatch], v2d (&Ww)[2], int &S) {
+                    const int tt = min(t2, NR - 1);
+                    const int col = min(16 * (8 * (r0 + tt) + wave) + c, L32 - 1);
+#pragma unroll
+                    for (int ks = 0; ks < kBatch; ++ks) {
+                        Vv[ks] = *reinterpret_cast<const double *>(Vbytes + (uint32_t(J[ks] + col) << 3));
+                        Uu[ks] = Uc[q2 * (64 * kBatch) + ks * 64 + lane];
+                    }
+                    // next W tile of this wavefront in round t2 (one per batch)
+                    uint32_t tile = a.zero_tile;
+                    S = -1;
+                    if (t2 < NR) {
+                        if (q2 == 0) {
+                            ct = 0;
+                            cbase = 0;
+                            cfull = __builtin_amdgcn_readlane(mreg, 8 * t2);
+                        }
+                        const int n = wave + kOwnWaves * q2;
+                        while (ct < 8 && n >= cbase + __popc(cfull)) {
+                            cbase += __popc(cfull);
+                            ++ct;
+                            if (ct < 8) cfull = __builtin_amdgcn_readlane(mreg, 8 * t2 + ct);
+                        }
+                        if (ct < 8 && n < kPool) {
+                            tile = __builtin_amdgcn_readlane(freg, 8 * t2 + ct) + uint32_t(n - cbase);
+                            S = n;
+                        }
+                    }
+                    const char *tb = reinterpret_cast<const char *>(a.wtiles + int64_t(tile) * 256);
+                    Ww[0] = *reinterpret_cast<const v2d *>(tb + lane16);
+                    Ww[1] = *reinterpret_cast<const v2d *>(tb + lane16 + 1024);
+                    if (q2 + 1 == nBt) { q2 = 0; ++t2; } else ++q2;
+                };
+                auto consume = [&](int b, const double (&Vv)[kBatch], const double (&Uu)[kBatch], const v2d (&Ww)[2], int S) {
+                    if (b < TB) {
+                        if (S >= 0) {                                     // park the W tile that came with this batch
+                            double *wp = Pool + S * 256 + lane * 2;
+                            *reinterpret_cast<v2d *>(wp) = Ww[0];
+                            *reinterpret_cast<v2d *>(wp + 128) = Ww[1];
+                        }
+                        accT0 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[0], Uu[0], accT0, 0, 0, 0);
+                        accT1 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[1], Uu[1], accT1, 0, 0, 0);
+                        accT0 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[2], Uu[2], accT0, 0, 0, 0);
+                        accT1 = __builtin_amdgcn_mfma_f64_16x16x4f64(Vv[3], Uu[3], accT1, 0, 0, 0);
+                        if (q0 + 1 == nBt) {
+                            // end of the round: T^t of this wavefront's l tile goes to LDS ...
+                            const v4d T = accT0 + accT1;
+                            double *tp = Tx + wave * 256 + lane * 2;
+                            *reinterpret_cast<v2d *>(tp) = v2d{T.x, T.y};
+                            *reinterpret_cast<v2d *>(tp + 128) = v2d{T.z, T.w};
+                            __syncthreads();
+                            // ... and every wavefront multiplies the W tiles of its m tiles with the eight T^t,
+                            // even and odd l tiles into two accumulators (two independent instruction chains)
+                            uint32_t fm[8], any = 0u;
+                            int pre[8], seen = 0;
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) {
+                                fm[t] = __builtin_amdgcn_readlane(mreg, 8 * t0 + t);
+                                pre[t] = seen;
+                                seen += __popc(fm[t]);
+                                any |= fm[t];
+                            }
+                            if (any & own) {
+#pragma unroll
+                                for (int x = 0; x < kOwnZ; ++x) {
+                                    const int mt = wave + kOwnWaves * x;
+                                    if ((any >> mt) & 1u) {
+                                        v4d z0 = accZ[x], z1 = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                                        for (int t = 0; t < 8; ++t) {
+                                            if ((fm[t] >> mt) & 1u) {
+                                                const int r = __popc(fm[t] & ((1u << mt) - 1u));
+                                                const int n = pre[t] + r;             // place in the round's tile sequence
+                                                const lds_v2d *tr = TxV + (t * 128 + lane);
+                                                const v2d Ta = tr[0], Tb = tr[64];
+                                                v2d w0, w1;
+                                                if (n < kPool && (n >> 3) < nBt) {
+                                                    const lds_v2d *rp = PoolV + (n * 128 + lane);
+                                                    w0 = rp[0];
+                                                    w1 = rp[64];
+                                                } else {                              // not parked: fetched here
+                                                    const uint32_t tile = __builtin_amdgcn_readlane(freg, 8 * t0 + t) + uint32_t(r);
+                                                    const char *tb = reinterpret_cast<const char *>(a.wtiles + int64_t(tile) * 256);
+                                                    w0 = *reinterpret_cast<const v2d *>(tb + lane16);
+                                                    w1 = *reinterpret_cast<const v2d *>(tb + lane16 + 1024);
+                                                }
+                                                v4d z = (t & 1) ? z1 : z0;
+                                                z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.x, Ta.x, z, 0, 0, 0);
+                                                z = __builtin_amdgcn_mfma_f64_16x16x4f64(w0.y, Ta.y, z, 0, 0, 0);
+                                                z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.x, Tb.x, z, 0, 0, 0);
+                                                z = __builtin_amdgcn_mfma_f64_16x16x4f64(w1.y, Tb.y, z, 0, 0, 0);
+                                                if (t & 1) z1 = z; else z0 = z;
+                                            }
+                                        }
+                                        accZ[x] = z0 + z1;
+                                    }
+                                }
+                            }
+                            __syncthreads();                              // T^t and the pool are free for the next round
+                            accT0 = v4d{0.0, 0.0, 0.0, 0.0};
+                            accT1 = accT0;
+                            q0 = 0;
+                            ++t0;
+                        } else {
+                            ++q0;
+                        }
+                    }
+                };
+
+                if (TB > 0) {
+#pragma unroll
+                    for (int u = 0; u < kRing; ++u) read_j(P.Jr[u]);
+#pragma unroll
+                    for (int u = 0; u < kRing - 1; ++u) issue(P.Jr[u], P.Vr[u], P.Ur[u], P.Wr[u], P.Sr[u]);
+                    for (int b = 0; b < TB; b += kRing) {
+#pragma unroll
+                        for (int u = 0; u < kRing; ++u) {
+                            const int su = (u + kRing - 1) % kRing;
+                            issue(P.Jr[su], P.Vr[su], P.Ur[su], P.Wr[su], P.Sr[su]);
+                            read_j(P.Jr[u]);
+                            consume(b + u, P.Vr[u], P.Ur[u], P.Wr[u], P.Sr[u]);
+                        }
+                    }
+                }
+            }
+            p0 += kCap;
+            if (p0 < n_union) {
+                np = min(kCap, n_union - p0);
+                npad = (np + 4 * kBatch - 1) & ~(4 * kBatch - 1);
+                prepare(p0, np, npad, std::false_type{});
+            }
+        }
+    }
+
+    // ---- store the group's rows: lane holds Z^t[m = 16 mt + slot + 4 v][i = c] ----------------------
+    const int64_t M = a.M;
+    const int64_t s = s0 + c;
+    if (s < a.slices) {
+        const int64_t row = a.compact ? s : int64_t(a.uidx0[s]);
+        double *dst = a.n_kc == 1 ? a.out + row * M : a.partial + (int64_t(kc) * a.slices + s) * M;
+#pragma unroll
+        for (int x = 0; x < kOwnZ; ++x) {
+            const int mt = wave + kOwnWaves * x;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = 16 * mt + slot + 4 * v;
+                if (mt < a.MT && m < M) dst[m] = accZ[x][v];
+            }
+        }
+    }
+}
+
 // sums the partial results of the k chunks in chunk order
 __global__ void sptn3_fixup_kernel(int64_t slices, int64_t M, int n_kc, const int32_t *__restrict__ uidx0,
                                    const double *__restrict__ partial, double *out, int compact) {
@@ -453,6 +803,12 @@ __global__ void sptn3_fixup_kernel(int64_t slices, int64_t M, int n_kc, const in
     const int64_t row = compact ? s : int64_t(uidx0[s]);
     out[row * M + m] = z;
 }
+
+static size_t sptn3_owned_lds(int nwords) {
+    return size_t(kCap * 16 + kPool * 256 + kOwnWaves * 256) * 8 + size_t(kCap) * 4 + size_t(nwords) * 8 + 64;
+}
+
+bool sptn3_two_waves_fit(int nwords) { return sptn3_owned_lds(nwords) <= 160 * 1024; }
 
 static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const double *const *dense, double *out,
                                           hipStream_t stream) {
@@ -495,10 +851,20 @@ static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const dou
     if (!plan->compact && a.slices < plan->out_rows)
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.slices == 0) return CONSTSTN_OK;
+    // two wavefronts per SIMD (m tiles owned by wavefronts) when the plan chose it, else one (l tiles owned)
+    const size_t lds_owned = sptn3_owned_lds(a.nwords);
+    const bool owned = plan->sp_two_waves;
+    static bool attr_owned = false;
+    if (owned && !attr_owned) {
+        CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sptn3_owned_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_owned = true;
+    }
     {
         ProfScope prof(plan, stream);
         const unsigned n_wg = unsigned(a.n_groups) * unsigned(a.n_kc);
-        sptn3_tiled_kernel<<<dim3((n_wg + 7) / 8 * 8), dim3(256), lds_bytes, stream>>>(a);
+        if (owned) sptn3_owned_kernel<<<dim3((n_wg + 7) / 8 * 8), dim3(64 * kOwnWaves), lds_owned, stream>>>(a);
+        else sptn3_tiled_kernel<<<dim3((n_wg + 7) / 8 * 8), dim3(256), lds_bytes, stream>>>(a);
     }
     CST_HIP(hipGetLastError());
     if (a.n_kc > 1) {

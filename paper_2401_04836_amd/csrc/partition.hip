@@ -898,6 +898,7 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     if (plan->sp_kc > 1)
         CST_TRY(plan->partial.alloc(size_t(plan->sp_kc) * size_t(U->nodes[0]) * size_t(M)));
     plan->w_tiled = true;
+    plan->sp_two_waves = env_int("CONSTSTN_SPTN3_WAVES", 2) == 2 && sptn3_two_waves_fit(int((J + 31) / 32));
     return CONSTSTN_OK;
 }
 

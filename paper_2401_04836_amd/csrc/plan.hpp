@@ -167,6 +167,7 @@ struct conststn_plan_s {
     // three-tensor network
     cst::DevBuf<int64_t> w_root_of_k;      // [K] root node of W holding index k, or -1
     bool w_tiled = false;                  // W also stored as dense 16 x 16 (l, m) tiles
+    bool sp_two_waves = false;             // tiled kernel with two wavefronts per SIMD (m tiles owned by wavefronts)
     int64_t n_w_tiles = 0;
     cst::DevBuf<uint32_t> w_tile_mask;     // [roots x ceil(L/16)] m tiles present
     cst::DevBuf<uint32_t> w_tile_first;    // [roots x ceil(L/16)] index of the first of them
@@ -234,6 +235,8 @@ namespace cst {
 conststn_status build_mttkrp3_tables(conststn_plan_s *plan);
 conststn_status build_ttmc_tables(conststn_plan_s *plan);
 conststn_status build_sptn3_tables(conststn_plan_s *plan);
+// whether the LDS of the two-wavefront form of the tiled kernel fits a workgroup (nwords = 32-bit words of the j bit mask)
+bool sptn3_two_waves_fit(int nwords);
 
 // kernels_*.hip
 conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const *dense, double *out,

@@ -38,6 +38,16 @@ class _env:
 
 
 def _check(wl, label, flags=0, expect=None):
+    """Runs the default kernel choice and, where that is the tiled kernel with two wavefronts per SIMD,
+    also the form with one; both against the oracle."""
+    out = _check_one(wl, label, flags, expect)
+    with _env(CONSTSTN_SPTN3_WAVES=1):
+        _check_one(wl, label + " (one wavefront per SIMD)", flags,
+                   expect.replace("two waves", "one wave") if expect else None, "two waves")
+    return out
+
+
+def _check_one(wl, label, flags=0, expect=None, absent=None):
     _say("sptn3 %s: dims %s" % (label, wl.params["dims"]))
     out, pl, _ = run_gpu(wl, flags=flags)
     want, S_abs = run_oracle(wl)
@@ -47,13 +57,15 @@ def _check(wl, label, flags=0, expect=None):
     _say("  %s -> rel err %.3e" % (desc.split("|")[0], err))
     if expect is not None:
         assert expect in desc, desc
+    if absent is not None:
+        assert absent not in desc, desc
     assert err <= TOL
     return out
 
 
 def test_block_sparse_small_tiled_and_baseline_agree_with_oracle():
     wl = w.make(4, small=True)
-    a = _check(wl, "block-sparse reduced copy, tiled", expect="tiled")
+    a = _check(wl, "block-sparse reduced copy, tiled", expect="tiled two waves")
     with _env(CONSTSTN_SPTN3_TILED=2):
         b = _check(wl, "block-sparse reduced copy, baseline kernel", expect="baseline")
     assert a.shape == b.shape
