@@ -455,14 +455,15 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
 // of LDS slots shared by the workgroup (slot = rank of the tile among the round's tiles); what
 // does not fit, or exceeds eight tiles per batch, is fetched when it is used.
 constexpr int kOwnWaves = 8;
+constexpr int kRingO = 2;                                             // batches in flight in this kernel
 constexpr int kOwnZ = (kSpMaxMTiles + kOwnWaves - 1) / kOwnWaves;       // accumulator tiles per wavefront
 constexpr int kPool = 48;                                             // W tiles parked per round
 
 struct SpPipeO {
-    double Vr[kRing][kBatch], Ur[kRing][kBatch];
-    int32_t Jr[kRing][kBatch];
-    v2d Wr[kRing][2];
-    int Sr[kRing];                                                    // pool slot of the W tile (-1: not parked)
+    double Vr[kRingO][kBatch], Ur[kRingO][kBatch];
+    int32_t Jr[kRingO][kBatch];
+    v2d Wr[kRingO][2];
+    int Sr[kRingO];                                                    // pool slot of the W tile (-1: not parked)
 };
 
 __global__ void __launch_bounds__(64 * kOwnWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -702,7 +703,11 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
                                 seen += __popc(fm[t]);
                                 any |= fm[t];
                             }
-                            if (any & own) {
+                            // Parked tiles first, in a loop without global loads (a load that may or may not
+                            // have been issued makes the compiler wait for every load in flight, the
+                            // pipeline's included); the tiles that were not parked follow in a loop of their own.
+                            const int parked = min(kPool, kOwnWaves * nBt);      // tiles n < parked lie in the pool
+                            auto multiply = [&](auto from_pool) {
 #pragma unroll
                                 for (int x = 0; x < kOwnZ; ++x) {
                                     const int mt = wave + kOwnWaves * x;
@@ -710,17 +715,17 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
                                         v4d z0 = accZ[x], z1 = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                                         for (int t = 0; t < 8; ++t) {
-                                            if ((fm[t] >> mt) & 1u) {
-                                                const int r = __popc(fm[t] & ((1u << mt) - 1u));
-                                                const int n = pre[t] + r;             // place in the round's tile sequence
+                                            const int r = __popc(fm[t] & ((1u << mt) - 1u));
+                                            const int n = pre[t] + r;                 // place in the round's tile sequence
+                                            if (((fm[t] >> mt) & 1u) && (n < parked) == decltype(from_pool)::value) {
                                                 const lds_v2d *tr = TxV + (t * 128 + lane);
                                                 const v2d Ta = tr[0], Tb = tr[64];
                                                 v2d w0, w1;
-                                                if (n < kPool && (n >> 3) < nBt) {
+                                                if (decltype(from_pool)::value) {
                                                     const lds_v2d *rp = PoolV + (n * 128 + lane);
                                                     w0 = rp[0];
                                                     w1 = rp[64];
-                                                } else {                              // not parked: fetched here
+                                                } else {
                                                     const uint32_t tile = __builtin_amdgcn_readlane(freg, 8 * t0 + t) + uint32_t(r);
                                                     const char *tb = reinterpret_cast<const char *>(a.wtiles + int64_t(tile) * 256);
                                                     w0 = *reinterpret_cast<const v2d *>(tb + lane16);
@@ -737,6 +742,10 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
                                         accZ[x] = z0 + z1;
                                     }
                                 }
+                            };
+                            if (any & own) {
+                                multiply(std::true_type{});
+                                if (seen > parked) multiply(std::false_type{});
                             }
                             __syncthreads();                              // T^t and the pool are free for the next round
                             accT0 = v4d{0.0, 0.0, 0.0, 0.0};
@@ -751,13 +760,13 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
 
                 if (TB > 0) {
 #pragma unroll
-                    for (int u = 0; u < kRing; ++u) read_j(P.Jr[u]);
+                    for (int u = 0; u < kRingO; ++u) read_j(P.Jr[u]);
 #pragma unroll
-                    for (int u = 0; u < kRing - 1; ++u) issue(P.Jr[u], P.Vr[u], P.Ur[u], P.Wr[u], P.Sr[u]);
-                    for (int b = 0; b < TB; b += kRing) {
+                    for (int u = 0; u < kRingO - 1; ++u) issue(P.Jr[u], P.Vr[u], P.Ur[u], P.Wr[u], P.Sr[u]);
+                    for (int b = 0; b < TB; b += kRingO) {
 #pragma unroll
-                        for (int u = 0; u < kRing; ++u) {
-                            const int su = (u + kRing - 1) % kRing;
+                        for (int u = 0; u < kRingO; ++u) {
+                            const int su = (u + kRingO - 1) % kRingO;
                             issue(P.Jr[su], P.Vr[su], P.Ur[su], P.Wr[su], P.Sr[su]);
                             read_j(P.Jr[u]);
                             consume(b + u, P.Vr[u], P.Ur[u], P.Wr[u], P.Sr[u]);
