@@ -387,7 +387,8 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
                       const double *__restrict__ pk_blocks, const int32_t *__restrict__ e_c0,
                       const int32_t *__restrict__ e_clen) {
     extern __shared__ unsigned char lds[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);    // the same in every lane: loop counters built on it stay scalar
     const int nthreads = 64 * kScLocalWaves;
     double *Ik = reinterpret_cast<double *>(lds);
     double *Cd = reinterpret_cast<double *>(lds + O.cd);
@@ -464,6 +465,9 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
     const int li = lane & 15, lk = lane >> 4;
     // the first tile of E_K this wavefront will compute: its part of P_K is fetched now
     const double *Pk = pk_blocks + R.pk;
+    // 32-bit offsets against scalar bases: a block P_K and the leaves of one K stay far below 2^29 elements
+    const char *Pkb = reinterpret_cast<const char *>(Pk);
+    char *outb = reinterpret_cast<char *>(out + R.q0);
     const int tiles_m = (nm + 15) >> 4, tiles_e = ((nn + 15) >> 4) * tiles_m;
     double bpre[kScDepth];
     {
@@ -472,7 +476,7 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
 #pragma unroll
         for (int kb = 0; kb < kScDepth; ++kb) {
             const int k = 4 * kb + lk;
-            bpre[kb] = (jb && k < ns) ? Pk[int64_t(k) * nm + j0 + li] : 0.0;
+            bpre[kb] = (jb && k < ns) ? *reinterpret_cast<const double *>(Pkb + (uint32_t(k * nm + j0 + li) << 3)) : 0.0;
         }
     }
     // T_K = C_K . I_K
@@ -484,11 +488,17 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
             const double *crow = Cd + (xa ? x0 + li : 0) * cstride;
             const double *icol = Ik + (sb ? s0 + li : 0);
             sc_v4d acc = {0.0, 0.0, 0.0, 0.0};
-            for (int k0 = 0; k0 < nrows; k0 += 4) {
+            // Rows of C_K beyond the nodes and columns of I_K beyond the slots are read from a valid
+            // place as they are: what they produce lies in rows and columns of the tile that are
+            // not stored.  Only the last, partial depth step needs its operands masked.
+            int k0 = 0;
+            for (; k0 + 4 <= nrows; k0 += 4)
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(crow[k0 + lk], icol[(k0 + lk) * ns], acc, 0, 0, 0);
+            if (k0 < nrows) {
                 const int k = k0 + lk;
                 const bool kk = k < nrows;
-                const double av = (xa && kk) ? crow[kk ? k : 0] : 0.0;
-                const double bv = (sb && kk) ? icol[(kk ? k : 0) * ns] : 0.0;
+                const double av = kk ? crow[kk ? k : 0] : 0.0;
+                const double bv = kk ? icol[(kk ? k : 0) * ns] : 0.0;
                 acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
             }
             if (sb) {
@@ -532,22 +542,24 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
 #pragma unroll
             for (int kb = 0; kb < kScDepth; ++kb) {
                 const int k = 4 * kb + lk;
-                bnext[kb] = (jnb && k < ns) ? Pk[int64_t(k) * nm + jn + li] : 0.0;
+                bnext[kb] = (jnb && k < ns) ? *reinterpret_cast<const double *>(Pkb + (uint32_t(k * nm + jn + li) << 3)) : 0.0;
             }
         }
         sc_v4d acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int kb = 0; kb < kScDepth; ++kb) {
-            if (4 * kb < ns) {
+            if (4 * kb + 4 <= ns) {                                     // whole step: rows beyond the nodes are not stored
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(trow[4 * kb + lk], bpre[kb], acc, 0, 0, 0);
+            } else if (4 * kb < ns) {
                 const int k = 4 * kb + lk;
-                const double av = (xa && k < ns) ? trow[k < ns ? k : 0] : 0.0;
+                const double av = k < ns ? trow[k < ns ? k : 0] : 0.0;
                 acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bpre[kb], acc, 0, 0, 0);
             }
         }
         for (int k0 = 4 * kScDepth; k0 < ns; k0 += 4) {                 // more than 4 * kScDepth slots
             const int k = k0 + lk;
             const bool kk = k < ns;
-            const double av = (xa && kk) ? trow[kk ? k : 0] : 0.0;
+            const double av = kk ? trow[kk ? k : 0] : 0.0;
             const double bv = (jb && kk) ? pcol[int64_t(kk ? k : 0) * nm] : 0.0;
             acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
         }
@@ -558,7 +570,7 @@ spchain3_local_kernel(ScArgs A, ScOut E, double *__restrict__ out, ScLocalLds O,
                 const int x = x0 + lk + 4 * v;
                 if (x < nn) {
                     const uint16_t at = pos[x * nm + j0 + li];
-                    if (at != kNoSlot) out[R.q0 + qoff[x] + at] = acc[v] * lval[x];
+                    if (at != kNoSlot) *reinterpret_cast<double *>(outb + (uint32_t(qoff[x] + at) << 3)) = acc[v] * lval[x];
                 }
             }
         }
@@ -957,7 +969,8 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
         const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 78) * 1024;      // two workgroups per compute unit
         const bool offsets_fit = I->nnz < (int64_t(1) << 31) && C->nnz < (int64_t(1) << 31) && nnz < (int64_t(1) << 31);
         // a node holds each m of its K at most once, so nm_max also bounds the leaves of a node (16-bit positions)
-        if (rows_max <= 65534 && nm_max <= 65534 && offsets_fit && bytes <= budget && bytes <= 160 * 1024 &&
+        // (pk < 2^29: the kernel reaches into a block P_K with 32-bit byte offsets)
+        if (rows_max <= 65534 && nm_max <= 65534 && pk < (int64_t(1) << 29) && offsets_fit && bytes <= budget && bytes <= 160 * 1024 &&
             env_int("CONSTSTN_SPCHAIN3_FORM", 1) == 1) {
             ScArgs A2 = make_args(plan);
             // the dense blocks P_K, one per run of K with the same v and m lists
