@@ -624,6 +624,18 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
                     mreg = a.wmask[cell];
                     freg = mreg ? a.wfirst[cell] : a.zero_tile;
                 }
+                // tiles of the lane's round before the lane's l tile (rounds are groups of 8 lanes)
+                int preg;
+                {
+                    const int pc = __popc(mreg);
+                    int incl = pc;
+#pragma unroll
+                    for (int d = 1; d < 8; d <<= 1) {
+                        const int up = __shfl_up(incl, d, 8);
+                        if ((lane & 7) >= d) incl += up;
+                    }
+                    preg = incl - pc;
+                }
                 const int TB = NR * nBt;
                 SpPipeO P;
                 v4d accT0 = v4d{0.0, 0.0, 0.0, 0.0}, accT1 = accT0;
@@ -631,10 +643,7 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
                 int t2 = 0, q2 = 0;                                       // batch whose V/U/W loads are issued
                 int q3 = 0;                                               // batch whose j offsets are read
                 // The W tiles of round t2, in the order (l tile, m tile), are fetched by the eight wavefronts
-                // in turn (tile n by wavefront n % 8 with its batch n / 8) into pool slot n: cursor of that walk
-                int ct = 8;                                               // l tile of the round under the cursor (8: none left)
-                uint32_t cfull = 0u;                                      // its mask
-                int cbase = 0;                                            // tiles of the round before l tile ct
+                // in turn: tile n by wavefront n % 8 with its batch n / 8, into pool slot n.
 
                 auto read_j = [&](int32_t (&J)[kBatch]) {
 #pragma unroll
@@ -649,29 +658,19 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
                         Vv[ks] = *reinterpret_cast<const double *>(Vbytes + (uint32_t(J[ks] + col) << 3));
                         Uu[ks] = Uc[q2 * (64 * kBatch) + ks * 64 + lane];
                     }
-                    // next W tile of this wavefront in round t2 (one per batch)
-                    uint32_t tile = a.zero_tile;
-                    S = -1;
-                    if (t2 < NR) {
-                        if (q2 == 0) {
-                            ct = 0;
-                            cbase = 0;
-                            cfull = __builtin_amdgcn_readlane(mreg, 8 * t2);
-                        }
-                        const int n = wave + kOwnWaves * q2;
-                        while (ct < 8 && n >= cbase + __popc(cfull)) {
-                            cbase += __popc(cfull);
-                            ++ct;
-                            if (ct < 8) cfull = __builtin_amdgcn_readlane(mreg, 8 * t2 + ct);
-                        }
-                        if (ct < 8 && n < kPool) {
-                            tile = __builtin_amdgcn_readlane(freg, 8 * t2 + ct) + uint32_t(n - cbase);
-                            S = n;
-                        }
-                    }
+                    // W tile n = wave + 8 q2 of round t2, found without a loop or a branch: the l tile it
+                    // lies under is the last lane of the round's group whose prefix does not exceed n
+                    const int n = wave + kOwnWaves * q2;
+                    const uint64_t below = __ballot((lane >> 3) == tt && n >= preg);
+                    const int ln = 8 * tt + __popcll(below) - 1;          // the group's first lane always counts
+                    const uint32_t full = __builtin_amdgcn_readlane(mreg, ln);
+                    const int base = __builtin_amdgcn_readlane(preg, ln);
+                    const bool ok = t2 < NR && n < base + __popc(full) && n < kPool;
+                    const uint32_t tile = ok ? __builtin_amdgcn_readlane(freg, ln) + uint32_t(n - base) : a.zero_tile;
+                    S = ok ? n : -1;
                     const char *tb = reinterpret_cast<const char *>(a.wtiles + int64_t(tile) * 256);
-                    Ww[0] = *reinterpret_cast<const v2d *>(tb + lane16);
-                    Ww[1] = *reinterpret_cast<const v2d *>(tb + lane16 + 1024);
+                    Ww[0] = *reinterpret_cast<const v2d *>(tb + lane16);     // unconditional (the all-zero tile when there
+                    Ww[1] = *reinterpret_cast<const v2d *>(tb + lane16 + 1024);  // is none): skipping the fetch measured slower
                     if (q2 + 1 == nBt) { q2 = 0; ++t2; } else ++q2;
                 };
                 auto consume = [&](int b, const double (&Vv)[kBatch], const double (&Uu)[kBatch], const v2d (&Ww)[2], int S) {
