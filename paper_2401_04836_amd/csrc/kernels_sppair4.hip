@@ -50,6 +50,7 @@ struct P4Args {
     int W;                                  // 32-bit words per row of the bit matrix (n of j)
     int max_ua, max_ub, max_common;
     int mp, np;                             // row strides of the two chunk matrices (doubles)
+    int nbuf;                               // chunk buffers per matrix (2; 1 on request)
 };
 
 struct P4Out {
@@ -459,7 +460,8 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
                 }
                 __syncthreads();                                       // chunk c laid out; chunk c-1 no longer read
                 if constexpr (cx > 0 && cy > 0) {
-                    const double *Ab = Ac + (c & 1) * kP4Chunk * mp + a_off, *Bb = Bc + (c & 1) * kP4Chunk * np + b_off;
+                    const int cb = A.nbuf == 2 ? (c & 1) : 0;
+                    const double *Ab = Ac + cb * kP4Chunk * mp + a_off, *Bb = Bc + cb * kP4Chunk * np + b_off;
 #pragma unroll
                     for (int kk = 0; kk < kP4Chunk; kk += 4) {
                         double av[cx ? cx : 1], bv[cy ? cy : 1];
@@ -475,7 +477,8 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
                     }
                 }
                 if (more) {
-                    lay_out((c + 1) & 1, r1, n1);
+                    if (A.nbuf == 1) __syncthreads();                  // one buffer: every wavefront is done reading chunk c
+                    lay_out(A.nbuf == 2 ? (c + 1) & 1 : 0, r1, n1);
                     r1 = r2;
                     n1 = n2;
                 }
@@ -538,6 +541,7 @@ static P4Args p4_args(const conststn_plan_s *plan) {
     A.max_common = plan->p4_max_common;
     A.mp = plan->p4_mp;
     A.np = plan->p4_np;
+    A.nbuf = plan->p4_nbuf;
     if (plan->p4_dense) {
         const bool same = plan->X == plan->W;                      // one tensor in both places: one set of rows
         A.a.dense = plan->p4_dense_a.p; A.a.row_at = plan->p4_row_at_a.p;
@@ -616,8 +620,12 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     L.scratch = int(at); at = up16(at + 4 * (kP4Waves + 1));
     const int64_t sym_bytes = at;
     L.rowpre = int(at); at = up16(at + 4 * int64_t(plan->p4_words) * max_ua);
-    L.achunk = int(at); at = up16(at + 2 * 8 * int64_t(kP4Chunk) * plan->p4_mp);       // two buffers each
-    L.bchunk = int(at); at = up16(at + 2 * 8 * int64_t(kP4Chunk) * plan->p4_np);
+    // Two chunk buffers per matrix overlap the fetch of a chunk with the pass over the one before.  One
+    // buffer and a second barrier per chunk (CONSTSTN_SPPAIR4_BUFFERS=1) halve the LDS, which at the
+    // lattice workload lets two workgroups share a CU, but measured 5 % slower there.
+    plan->p4_nbuf = env_int("CONSTSTN_SPPAIR4_BUFFERS", 2) == 1 ? 1 : 2;
+    L.achunk = int(at); at = up16(at + plan->p4_nbuf * 8 * int64_t(kP4Chunk) * plan->p4_mp);
+    L.bchunk = int(at); at = up16(at + plan->p4_nbuf * 8 * int64_t(kP4Chunk) * plan->p4_np);
     L.total = int(at);
     if (at > 160 * 1024) {
         set_error("the blocks of one (i,j) pair need %lld bytes of LDS (shared K up to %d, %lld x %lld distinct inner indices)",

@@ -295,3 +295,59 @@ def test_config6_sparse_chain_full_size_sampled_slices():
         _say("  %d result nonzeros, sampled K %s, rel err %.3e" % (pl.n_rows, Ks, worst))
         assert worst <= TOL
         del pl, vals
+
+
+def test_config7_four_index_product_full_size_sampled_blocks():
+    """The four-index product of Sec. 5.1 at the size the benchmark times (12 x 12 lattice, E with 4 M
+    nonzeros, V with 224 M): E comes from the dense-slice reference of the chain, the GPU multiplies it
+    with itself, and sampled (i,j) blocks are compared in structure and value with the reference."""
+    from oracle import spsp
+    from paper_2401_04836_amd import schedules as S
+    _say("config 7 full size: generate")
+    wl = w.make(7, device="cpu")
+    n_K, n_i, n_u, n_m = wl.params["dims"]
+    as_np = lambda t: ([c.numpy() for c in t.coords], t.vals.numpy())
+    _say("config 7: reference E, %d slices" % n_K)
+    ek, ei, em, ev = [], [], [], []
+    for K0 in range(0, n_K, 96):                                   # a block of slices at a time keeps memory flat
+        ref = spsp.chain3(as_np(wl.sparse["I"]), as_np(wl.sparse["C"]), as_np(wl.sparse["P"]), wl.params["dims"],
+                          K_values=range(K0, min(K0 + 96, n_K)))
+        for K, (E, _, N) in ref.items():
+            ii, mm = np.nonzero(N)
+            ek.append(np.full(ii.size, K, dtype=np.int64)); ei.append(ii); em.append(mm); ev.append(E[ii, mm])
+    Ec = [np.concatenate(x) for x in (ek, ei, em)]
+    Ev = np.concatenate(ev)
+    dims = (n_K, n_i, n_m)
+    _say("config 7: E has %d structural nonzeros" % Ev.size)
+    hE = cst.build_csf([torch.as_tensor(c, dtype=torch.int32).cuda() for c in Ec], torch.as_tensor(Ev).cuda(), dims, [1, 0, 2])
+    pl = cst.plan(S.SPPAIR4, [("Ea", hE), ("Eb", hE)])
+    _say("config 7: %s" % pl.describe().split("|")[0])
+    assert "kernel=dense rows" in pl.describe()
+    vals = cst.execute(pl, [])
+    torch.cuda.synchronize()
+    V = pl.output_csf()
+    (i0, p0, _), (i1, p1, _), (i2, p2, _), (i3, _, _) = (V.export(l) for l in range(4))
+    assert pl.n_rows == i3.numel() == vals.numel()
+    i0c, p0c, i1c, p1c = i0.cpu().numpy(), p0.cpu().numpy(), i1.cpu().numpy(), p1.cpu().numpy()
+    p2c = p2.cpu().numpy()
+    worst = 0.0
+    samples = [(0, 0), (0, 1), (17, 29), (71, 72), (100, 3), (n_i - 1, n_i - 1), (60, 61), (5, 140)]
+    for (i, j) in samples:
+        want, S_abs, N = spsp.pair4_block(Ec, Ev, dims, i, j)
+        G = np.zeros_like(want)
+        M = np.zeros(want.shape, dtype=bool)
+        r = int(np.searchsorted(i0c, i))
+        if r < i0c.size and i0c[r] == i:
+            a, b = int(p0c[r]), int(p0c[r + 1])
+            x = a + int(np.searchsorted(i1c[a:b], j))
+            if x < b and i1c[x] == j:                              # the pair is stored
+                ra, rb = int(p1c[x]), int(p1c[x + 1])
+                qa, qb = int(p2c[ra]), int(p2c[rb])
+                mm = np.repeat(i2[ra:rb].cpu().numpy(), np.diff(p2c[ra:rb + 1]))
+                nn = i3[qa:qb].cpu().numpy()
+                G[mm, nn] = vals[qa:qb].cpu().numpy()
+                M[mm, nn] = True
+        np.testing.assert_array_equal(M, N, err_msg="structure of V[%d,%d]" % (i, j))
+        worst = max(worst, oracle.rel_err(G, want, S_abs))
+    _say("  %d result nonzeros, sampled pairs %s, rel err %.3e" % (pl.n_rows, samples, worst))
+    assert worst <= TOL

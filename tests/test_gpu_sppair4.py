@@ -111,8 +111,9 @@ def test_blocks_larger_than_one_tile_group_and_many_shared_k():
     assert worst <= TOL
 
 
-@pytest.mark.parametrize("env", [{"CONSTSTN_SPPAIR4_ROWS": "2"}, {"CONSTSTN_SPPAIR4_KEEP": "2"}, {}],
-                         ids=["leaf-lists", "nothing-kept", "dense-rows"])
+@pytest.mark.parametrize("env", [{"CONSTSTN_SPPAIR4_ROWS": "2"}, {"CONSTSTN_SPPAIR4_KEEP": "2"}, {},
+                                 {"CONSTSTN_SPPAIR4_BUFFERS": "1"}],
+                         ids=["leaf-lists", "nothing-kept", "dense-rows", "one-chunk-buffer"])
 @pytest.mark.parametrize("n_m", [200, 300])
 def test_every_form_of_the_numeric_pass(env, n_m, monkeypatch):
     # the chunk rows copied from dense rows (default, inner dimension <= 256), put together from leaf
@@ -124,7 +125,8 @@ def test_every_form_of_the_numeric_pass(env, n_m, monkeypatch):
     Ec, Ev = _rand_e(5110 + n_m, dims, 40 * 3 * n_m * 6 // 10)
     (ci, cj, cm, cn), vals, desc = _run(Ec, Ev, dims)
     _say("%s: %s" % (env, desc.split("|")[0]))
-    want_kernel = "nothing kept" if "CONSTSTN_SPPAIR4_KEEP" in env else "dense rows" if not env and n_m <= 256 else "leaf lists kept"
+    dense = "CONSTSTN_SPPAIR4_ROWS" not in env and "CONSTSTN_SPPAIR4_KEEP" not in env and n_m <= 256
+    want_kernel = "nothing kept" if "CONSTSTN_SPPAIR4_KEEP" in env else "dense rows" if dense else "leaf lists kept"
     assert "kernel=" + want_kernel in desc, desc
     worst = 0.0
     for i in range(3):
