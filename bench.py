@@ -38,13 +38,15 @@ KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2
 BOUND = {"mttkrp3": "hbm", "ttmc3": "hbm", "ttmc4": "mfma", "sptn3": "mfma", "spchain3": "hbm", "sppair4": "mfma"}
 
 
-def measured_traffic(family):
+def measured_traffic(family, config):
     """HBM bytes per launch from the rocprofv3 counter runs recorded under profiles/, or None when
-    the kernel sources have changed since the counters were taken."""
+    the counters were taken on another workload or the kernel sources have changed since."""
     import hashlib
     try:
         table = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
         entry = table[family]
+        if entry.get("config") != config:
+            return None
         h = hashlib.sha256()
         for f in KERNEL_SOURCES[family]:
             h.update(open(os.path.join(CSRC, f), "rb").read())
@@ -274,6 +276,26 @@ def cpu_baseline(wl, budget_nnz):
         dt = time.perf_counter() - t0
         return dict(value=n / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
                     sample="order-4 TTMc of the first %d nonzeros, %.2f s" % (n, dt))
+    if wl.kind == "sptn3":
+        import numpy as np
+        U, W = wl.sparse["U"], wl.sparse["W"]
+        ui = U.coords[0].cpu().numpy()
+        # slices are taken whole (the consumer works per slice): as many leading i as hold the budget
+        order = np.argsort(ui, kind="stable")
+        n = int(min(U.nnz, max(1000, budget_nnz // 5)))
+        n_rows = int(ui[order[n - 1]]) + 1
+        sel = order[:int(np.searchsorted(ui[order], n_rows))]
+        c = [x.cpu().numpy()[sel] for x in U.coords]
+        v = U.vals.cpu().numpy()[sel]
+        wc = [x.cpu().numpy() for x in W.coords]
+        oracle.lib()
+        t0 = time.perf_counter()
+        oracle.sptn3(c, v, (n_rows, U.dims[1], U.dims[2]), wl.dense["V"].cpu().numpy(), wc, W.vals.cpu().numpy(), W.dims)
+        dt = time.perf_counter() - t0
+        share = len(v) / U.nnz
+        return dict(value=(len(v) + share * W.nnz) / dt, unit="nnz/s", cores=oracle.num_threads(), kind="oracle",
+                    sample="the first %d slices i of U (%d nonzeros) against all of V and W, counted with the same "
+                           "share of W's nonzeros, %.2f s" % (n_rows, len(v), dt))
     if wl.kind == "sppair4":
         from oracle import spsp
         (ek, ei, em), ev, dims = wl.params["E"]
@@ -441,7 +463,7 @@ def main():
         "fp64_frac": flops_step / (dt / args.steps) / 1e12 / FP64_PEAK_TFLOPS,
         "csf_build": {"seconds": build_s, "nnz_per_s": nnz_per_step / build_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(family),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(family, None if (args.small or args.restricted or args.all_modes) else args.config),
                      "kernel": KERNEL_NAMES.get(family, family),
                      "kernel_ms_avg": avg_kernel_ms, "launches_timed": len(kernel_ms),
                      "kernel_ms_per_contraction": per_launch_ms,
