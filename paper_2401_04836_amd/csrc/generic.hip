@@ -88,7 +88,21 @@ generic_stmt_kernel(GenStmt g) {
         else { c0 = g.ptr[g.d_out - 1][p]; c1 = g.ptr[g.d_out - 1][p + 1]; }
         const int32_t *ix = g.idx[g.d_out];
         const int64_t fs = g.f_level_stride[g.d_out];
-        for (int64_t c = c0; c < c1; ++c)
+        // eight children at a time: their loads are in flight together, the sum keeps its order
+        int64_t c = c0;
+        for (; c + 8 <= c1; c += 8) {
+            int32_t iv[8];
+            double xv[8], yv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) iv[u] = ix[c + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xv[u] = g.in[(c + u) * g.in_block + in_off];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) yv[u] = g.f[f_off0 + int64_t(iv[u]) * fs];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = fma(xv[u], yv[u], acc);
+        }
+        for (; c < c1; ++c)
             acc = fma(g.in[c * g.in_block + in_off], g.f[f_off0 + int64_t(ix[c]) * fs], acc);
     } else {
         int64_t cur[CONSTSTN_MAX_ORDER], end[CONSTSTN_MAX_ORDER], foff[CONSTSTN_MAX_ORDER];
