@@ -107,6 +107,12 @@ def test_m_beyond_tiled_limit_uses_baseline():
     _check(wl, "M = 401", expect="baseline")
 
 
+def test_wide_j_extent_falls_back_to_one_wavefront_per_simd():
+    # the bit mask over j of the two-wavefront form no longer fits its LDS beyond J of about 27 000
+    wl = make_sptn3_scattered("sc7", 9107, (20, 30000, 6, 40, 33), 3000, 700)
+    _check_one(wl, "J = 30000", expect="tiled one wave", absent="two waves")
+
+
 def test_tiled_is_deterministic():
     wl = w.make(4, small=True)
     a, _, _ = run_gpu(wl)
