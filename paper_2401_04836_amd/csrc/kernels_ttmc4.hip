@@ -186,19 +186,23 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
     using W5 = std::integral_constant<int, 5>;
     using W6 = std::integral_constant<int, 6>;
     using W7 = std::integral_constant<int, 7>;
+    const char *U1b = reinterpret_cast<const char *>(a.U1), *U2b = reinterpret_cast<const char *>(a.U2),
+               *U3b = reinterpret_cast<const char *>(a.U3);
     auto load_rows = [&](uint32_t x, double &u2, double &x0, double &x1) {
         const int32_t kf = field(x, W0{}), l0 = field(x, W1{}), l1 = field(x, W2{});
         const int32_t k = kf >= 0 ? int32_t(uint32_t(kf) & kGrpIndexMask) : 0;         // empty record: row 0, value 0
-        u2 = a.U2[int64_t(k) * 16 + c];
-        x0 = a.U3[int64_t(l0 >= 0 ? l0 : 0) * 16 + c];
-        x1 = a.U3[int64_t(l1 >= 0 ? l1 : 0) * 16 + c];
+        // 32-bit byte offsets against the scalar bases of the factors (their extents stay below 2^25 on
+        // this path): one vector instruction per address
+        u2 = *reinterpret_cast<const double *>(U2b + (uint32_t(k * 16 + c) << 3));
+        x0 = *reinterpret_cast<const double *>(U3b + (uint32_t((l0 >= 0 ? l0 : 0) * 16 + c) << 3));
+        x1 = *reinterpret_cast<const double *>(U3b + (uint32_t((l1 >= 0 ? l1 : 0) * 16 + c) << 3));
     };
     auto consume = [&](uint32_t x, double u2, double x0, double x1) {
         const int32_t kf = field(x, W0{});
         const uint32_t flags = uint32_t(__builtin_amdgcn_readfirstlane(kf));            // same on the four records
         if (flags & kGrpStartsKstep) {
             const int32_t j = field(x, W3{});
-            av = j >= 0 ? a.U1[int64_t(j) * 16 + c] : 0.0;
+            av = j >= 0 ? *reinterpret_cast<const double *>(U1b + (uint32_t(j * 16 + c) << 3)) : 0.0;
         }
         // empty records and absent second leaves carry value 0
         const double t1 = fma(field64(x, W6{}, W7{}), x1, field64(x, W4{}, W5{}) * x0);

@@ -765,7 +765,12 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
         split = env_int("CONSTSTN_TTMC3_ROWSPLIT", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 256), 2048));
         order = 0;                                   // items carry no 'first fiber'
     }
-    if (order == 4 && plan->rank_of_level[1] == 16 && plan->rank_of_level[2] == 16 &&
+    // (extents below 2^25: the matrix-core kernel reaches the factor rows with 32-bit byte offsets)
+    const conststn_csf_s *X4 = plan->X;
+    const bool small_extents = order != 4 || (X4->dims[X4->mode_order[1]] < (int64_t(1) << 25) &&
+                                              X4->dims[X4->mode_order[2]] < (int64_t(1) << 25) &&
+                                              X4->dims[X4->mode_order[3]] < (int64_t(1) << 25));
+    if (order == 4 && plan->rank_of_level[1] == 16 && plan->rank_of_level[2] == 16 && small_extents &&
         plan->rank_of_level[3] == 16 && env_int("CONSTSTN_TTMC4_NO_MFMA", 0) == 0) {
         plan->use_rows = true;
         CST_TRY(build_piece_groups(plan));
