@@ -190,12 +190,12 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
                *U3b = reinterpret_cast<const char *>(a.U3);
     auto load_rows = [&](uint32_t x, double &u2, double &x0, double &x1) {
         const int32_t kf = field(x, W0{}), l0 = field(x, W1{}), l1 = field(x, W2{});
-        const int32_t k = kf >= 0 ? int32_t(uint32_t(kf) & kGrpIndexMask) : 0;         // empty record: row 0, value 0
+        const int32_t k = int32_t(uint32_t(kf) & kGrpIndexMask);
         // 32-bit byte offsets against the scalar bases of the factors (their extents stay below 2^25 on
         // this path): one vector instruction per address
         u2 = *reinterpret_cast<const double *>(U2b + (uint32_t(k * 16 + c) << 3));
-        x0 = *reinterpret_cast<const double *>(U3b + (uint32_t((l0 >= 0 ? l0 : 0) * 16 + c) << 3));
-        x1 = *reinterpret_cast<const double *>(U3b + (uint32_t((l1 >= 0 ? l1 : 0) * 16 + c) << 3));
+        x0 = *reinterpret_cast<const double *>(U3b + (uint32_t(l0 * 16 + c) << 3));
+        x1 = *reinterpret_cast<const double *>(U3b + (uint32_t(l1 * 16 + c) << 3));
     };
     auto consume = [&](uint32_t x, double u2, double x0, double x1) {
         const int32_t kf = field(x, W0{});
@@ -206,7 +206,7 @@ ttmc4_mfma_kernel(Ttmc4RowArgs a) {
         }
         // empty records and absent second leaves carry value 0
         const double t1 = fma(field64(x, W6{}, W7{}), x1, field64(x, W4{}, W5{}) * x0);
-        t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(kf >= 0 ? u2 : 0.0, t1, t2, 0, 0, 0);
+        t2 = __builtin_amdgcn_mfma_f64_16x16x4f64(u2, t1, t2, 0, 0, 0);
         if (flags & kGrpEndsFiber) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) lds[ft * kT2Stride + (slot + 4 * v) * 16 + c] = t2[v];

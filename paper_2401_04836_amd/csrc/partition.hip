@@ -650,9 +650,15 @@ __global__ void fill_groups_kernel(int64_t fibers, int64_t slices, const int64_t
     for (int64_t n = ptr1[f]; n < ptr1[f + 1]; ++n) {
         const int64_t end = ptr2[n + 1];
         for (int64_t e = ptr2[n]; e < end; e += kPieceLeaves)
-            put(idx2[n], idx3[e], e + 1 < end ? idx3[e + 1] : -1, vals[e], e + 1 < end ? vals[e + 1] : 0.0);
+            put(idx2[n], idx3[e], e + 1 < end ? idx3[e + 1] : idx3[e], vals[e], e + 1 < end ? vals[e + 1] : 0.0);
     }
-    while ((r - r0) & 3) put(int32_t(0x80000000u), -1, -1, 0.0, 0.0);          // empty records
+    // Empty records, and the absent second leaf above, name rows the fiber uses anyway and carry the
+    // value 0: the kernel then needs no test for them, and a factor row that is not finite spoils only
+    // results it belongs to.
+    {
+        const int64_t n0 = ptr1[f], e0 = ptr2[n0];
+        while ((r - r0) & 3) put(idx2[n0], idx3[e0], idx3[e0], 0.0, 0.0);
+    }
     // structure flags on every record of a group; level-1 indices on the first group of a K-step
     const int64_t groups = (r - r0) >> 2;
     for (int64_t g = 0; g < groups; ++g) {

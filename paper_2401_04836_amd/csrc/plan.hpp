@@ -82,8 +82,9 @@ struct alignas(16) RowDesc {
 // (i,j,k) node, copied out of the CSF so that one 32-byte read brings everything the leaf stage
 // needs and no second, dependent load of the leaves follows.
 struct alignas(32) PieceDesc {
-    int32_t k;              // level-2 index of the node | kGrp* flags; negative: empty record
-    int32_t l0, l1;         // leaf indices; l1 = -1 when the piece has one leaf
+    int32_t k;              // level-2 index of the node | kGrp* flags
+    int32_t l0, l1;         // leaf indices; l1 = l0 (with v1 = 0) when the piece has one leaf; an empty record
+                            // that pads a group repeats the fiber's first node and leaf with both values 0
     int32_t pad;            // first group of a K-step, slot s: level-1 index of the K-step's fiber s (-1: none)
     double v0, v1;          // leaf values (v1 = 0 when absent)
 };
