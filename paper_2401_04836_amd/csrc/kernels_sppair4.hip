@@ -59,6 +59,8 @@ struct P4Out {
     int32_t *node_a, *node_b;               // per (i,j) node: root node of Ea, of Eb
     int32_t *root_a;                        // per root of V: root node of Ea
     int64_t roots, pairs, rows, nnz;
+    const int32_t *wg_pair;                 // workgroup -> (i,j) node (-1: none), see sppair4_xcd_* below
+    int64_t n_wg;
     // kept from the symbolic pass when they fit: per (i,j) node the shared K (level-1 nodes of the two
     // operands, ascending K) and the bit matrix, so that the numeric pass need not find them again
     int64_t *k_ptr;                         // [pairs + 1]
@@ -307,6 +309,24 @@ sppair4_dense_kernel(P4Side T, const int64_t *__restrict__ row_at, int64_t n1, i
     for (int x = lane; x < pitch; x += 64) dst[x] = row[x];
 }
 
+// ---- which workgroup takes which (i,j) --------------------------------------------------------
+// Workgroups are dealt to the 8 XCDs round-robin, each XCD with an L2 of its own.  In node order
+// (i-major) the pairs an XCD works on at one time share a few i but hardly any j, and the dense rows of
+// E[j] miss L2 on almost every pair.  Instead XCD x takes the pairs with j % 8 == x, in node order: the
+// pairs of neighbouring i then meet the same few j on one XCD.
+__global__ void sppair4_xcd_flag_kernel(P4Out V, int x, int64_t *flag) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n < V.pairs) flag[n] = (V.idx1[n] & 7) == x ? 1 : 0;
+}
+__global__ void sppair4_xcd_fill_kernel(P4Out V, int x, const int64_t *__restrict__ rank, int32_t *wg_pair) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n < V.pairs && (V.idx1[n] & 7) == x) wg_pair[8 * rank[n] + x] = int32_t(n);
+}
+__global__ void sppair4_fill_minus1_kernel(int32_t *p, int64_t n) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x < n) p[x] = -1;
+}
+
 // LDS of the numeric kernel
 struct P4NumLds {
     int match_a, match_b, rowmask, nmask, rowleaf, rowrank, scratch, rowpre, achunk, bchunk, total;
@@ -327,7 +347,8 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave: the same in every lane
     const int side = wave & 1, krow = wave >> 1;
     const int nthreads = 64 * kP4Waves;
-    const int64_t node = blockIdx.x;
+    const int64_t node = V.wg_pair ? int64_t(V.wg_pair[blockIdx.x]) : int64_t(blockIdx.x);
+    if (node < 0) return;                                              // padding of a shorter XCD list
     const int64_t ra = V.node_a[node], rb = V.node_b[node];
     // block-wide values are moved to scalar registers, so that the tests on them cost no vector instructions
     const int n_ua = __builtin_amdgcn_readfirstlane(int(A.a.u_ptr[ra + 1] - A.a.u_ptr[ra]));
@@ -565,6 +586,8 @@ static P4Out p4_out(const conststn_plan_s *plan) {
         o.mask_stride = int64_t(plan->p4_max_ua) * plan->p4_words;
     }
     o.dense = plan->p4_dense ? 1 : 0;
+    o.wg_pair = plan->p4_wg_pair.p;
+    o.n_wg = plan->p4_n_wg;
     return o;
 }
 
@@ -730,6 +753,34 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     sppair4_root_fill_kernel<<<p4_grid(pairs + 1), 256, 0, st>>>(A, O, rflag.p, root_of.p);
     CST_HIP(hipGetLastError());
     CST_HIP(hipStreamSynchronize(st));
+    // workgroup order of the numeric pass (pairs < 2^31: a pair holds at least one of the nnz < 2^31 leaves)
+    plan->p4_n_wg = 0;
+    if (pairs > 0 && env_int("CONSTSTN_SPPAIR4_XCD", 1) == 1) {
+        DevBuf<int64_t> xflag, xrank;
+        CST_TRY(xflag.alloc(size_t(pairs)));
+        CST_TRY(xrank.alloc(size_t(pairs)));
+        int64_t longest = 0;
+        for (int x = 0; x < 8; ++x) {                                   // length of the longest XCD list
+            int64_t cnt = 0;
+            sppair4_xcd_flag_kernel<<<p4_grid(pairs), 256, 0, st>>>(O, x, xflag.p);
+            CST_HIP(hipGetLastError());
+            CST_TRY(exscan(xflag.p, xrank.p, pairs, &cnt));
+            longest = std::max(longest, cnt);
+        }
+        plan->p4_n_wg = 8 * longest;
+        CST_TRY(plan->p4_wg_pair.alloc(size_t(plan->p4_n_wg)));
+        sppair4_fill_minus1_kernel<<<p4_grid(plan->p4_n_wg), 256, 0, st>>>(plan->p4_wg_pair.p, plan->p4_n_wg);
+        CST_HIP(hipGetLastError());
+        for (int x = 0; x < 8; ++x) {
+            int64_t cnt = 0;
+            sppair4_xcd_flag_kernel<<<p4_grid(pairs), 256, 0, st>>>(O, x, xflag.p);
+            CST_HIP(hipGetLastError());
+            CST_TRY(exscan(xflag.p, xrank.p, pairs, &cnt));
+            sppair4_xcd_fill_kernel<<<p4_grid(pairs), 256, 0, st>>>(O, x, xrank.p, plan->p4_wg_pair.p);
+            CST_HIP(hipGetLastError());
+        }
+        CST_HIP(hipStreamSynchronize(st));
+    }
     plan->out_rows = nnz;
     plan->row_elems = 1;
     return CONSTSTN_OK;
@@ -754,8 +805,9 @@ conststn_status launch_sppair4(const conststn_plan_s *plan, double *out, hipStre
         }
     }
     ProfScope prof(plan, stream);
-    if (plan->p4_dense) sppair4_kernel<true><<<dim3(unsigned(O.pairs)), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
-    else sppair4_kernel<false><<<dim3(unsigned(O.pairs)), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
+    const unsigned n_wg = unsigned(O.wg_pair ? O.n_wg : O.pairs);
+    if (plan->p4_dense) sppair4_kernel<true><<<dim3(n_wg), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
+    else sppair4_kernel<false><<<dim3(n_wg), 64 * kP4Waves, size_t(L.total), stream>>>(A, O, L, out);
     CST_HIP(hipGetLastError());
     return CONSTSTN_OK;
 }

@@ -217,6 +217,8 @@ struct conststn_plan_s {
     cst::DevBuf<int64_t> p4_k_a, p4_k_b;                 // first leaf of each shared K's row in the two operands
     cst::DevBuf<int32_t> p4_k_alen, p4_k_blen;           // and its length
     cst::DevBuf<uint32_t> p4_masks;
+    cst::DevBuf<int32_t> p4_wg_pair;                     // workgroup -> (i,j) node of the numeric pass (-1: none)
+    int64_t p4_n_wg = 0;
     int p4_nbuf = 2;                                     // chunk buffers per matrix in LDS
     bool p4_dense = false;                               // dense rows of the operands kept (rebuilt by every execute)
     cst::DevBuf<int64_t> p4_row_at_a, p4_row_at_b;       // per level-1 node: first element of its dense row
