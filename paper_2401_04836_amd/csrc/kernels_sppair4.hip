@@ -30,6 +30,7 @@ constexpr int kP4Chunk = 8;                // shared K staged per pass
 constexpr int kP4Tiles = 9;                // result tiles a wavefront keeps in registers
 
 typedef double p4_v4d __attribute__((ext_vector_type(4)));
+typedef double p4_v2d __attribute__((ext_vector_type(2)));
 
 struct P4Side {                             // one operand: levels (root, K, leaf index)
     const int32_t *idx0, *idx1;
@@ -407,7 +408,7 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
         const int a_off = lk * mp + 16 * (mg + wm) + li, b_off = lk * np + 16 * (ng + wn) + li;   // tile x lies 64 x further
         int sl[2];                         // leaf lists: the first 128 leaves of the row being fetched
         double vl[2];
-        double dv[4];                      // dense rows: the row being fetched (at most 256 long)
+        p4_v2d dv[2];                      // dense rows: the row being fetched (at most 256 long), 16 bytes per lane and load
         int64_t r1 = 0, r2 = 0;            // start of this wavefront's row of the next chunk / the one after (-1: none)
         int n1 = 0, n2 = 0;                // ... and their lengths (leaf lists)
         const double *D = side ? A.b.dense : A.a.dense;
@@ -425,9 +426,9 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
         auto get_leaves = [&](int64_t first, int len) {
             if (DENSE) {
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    const int x = 64 * h + lane;
-                    dv[h] = (first >= 0 && x < pitch) ? D[first + x] : 0.0;
+                for (int h = 0; h < 2; ++h) {
+                    const int x = 128 * h + 2 * lane;                   // rows start at multiples of 16 doubles, x is even
+                    dv[h] = (first >= 0 && x < pitch) ? *reinterpret_cast<const p4_v2d *>(D + first + x) : p4_v2d{0.0, 0.0};
                 }
             } else {
 #pragma unroll
@@ -443,9 +444,9 @@ sppair4_kernel(P4Args A, P4Out V, P4NumLds O, double *__restrict__ out) {
             double *row = (side ? Bc + buf * kP4Chunk * np : Ac + buf * kP4Chunk * mp) + krow * stride;
             if (DENSE) {
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    const int x = 64 * h + lane;
-                    if (x < pitch) row[x] = dv[h];
+                for (int h = 0; h < 2; ++h) {
+                    const int x = 128 * h + 2 * lane;
+                    if (x < pitch) *reinterpret_cast<p4_v2d *>(row + x) = dv[h];
                 }
             } else {
                 for (int x = lane; x < stride; x += 64) row[x] = 0.0;
