@@ -112,8 +112,8 @@ def test_blocks_larger_than_one_tile_group_and_many_shared_k():
 
 
 @pytest.mark.parametrize("env", [{"CONSTSTN_SPPAIR4_ROWS": "2"}, {"CONSTSTN_SPPAIR4_KEEP": "2"}, {},
-                                 {"CONSTSTN_SPPAIR4_BUFFERS": "1"}],
-                         ids=["leaf-lists", "nothing-kept", "dense-rows", "one-chunk-buffer"])
+                                 {"CONSTSTN_SPPAIR4_BUFFERS": "1"}, {"CONSTSTN_SPPAIR4_XCD": "0"}],
+                         ids=["leaf-lists", "nothing-kept", "dense-rows", "one-chunk-buffer", "node-order"])
 @pytest.mark.parametrize("n_m", [200, 300])
 def test_every_form_of_the_numeric_pass(env, n_m, monkeypatch):
     # the chunk rows copied from dense rows (default, inner dimension <= 256), put together from leaf
