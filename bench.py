@@ -2,10 +2,13 @@
 """Benchmark of the fused sparse contraction path on one MI355X.
 
 A step is one pass of the fused contraction over one synthetic batch with the CSF already
-resident in HBM: for the default workload (configuration 2: order-3 MTTKRP, 76 M nonzeros,
-rank 32) a step is the mode-0 MTTKRP (CSF i>j>k) followed by the mode-2 MTTKRP (CSF k>j>i).
-The CSF build (sort + pointer construction + partition) is timed separately and reported
-under "csf_build".  Prints ONE JSON line.
+resident in HBM.  With no --config the five configurations run one after the other in one
+process (5, 2, 3, 4, 1); the headline (value, ms_per_step, roofline, cpu_baseline) is that of
+configuration 5, the largest that fits one GPU (order-3 TTMc, 140 M nonzeros, ranks 64 x 64,
+47 GB of output), and "configs" holds the same record for every configuration.  For
+configuration 2 a step is the mode-0 MTTKRP (CSF i>j>k) followed by the mode-2 MTTKRP (CSF
+k>j>i).  The CSF build (sort + pointer construction + partition) is timed separately and
+reported under "csf_build".  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -340,53 +343,44 @@ def cpu_baseline(wl, budget_nnz):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2,
-                    help="benchmark configuration 1..5 (default 2); 6 = the sparse chain of Sec. 5.1 on lattice maps, "
-                         "7 = the four-index product of the same section")
-    ap.add_argument("--all-modes", action="store_true",
-                    help="configuration 2: a step is the MTTKRP of every mode (0, 1, 2), each on a CSF rooted at its mode")
-    ap.add_argument("--restricted", action="store_true", help="configuration 6: the form with the K -> i filter")
-    ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--generic", action="store_true",
-                    help="plan with the generic executor instead of the tuned kernels (configs 1, 2, 3, 5)")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for the FETCH_SIZE / "
-                         "WRITE_SIZE counters of a profiler run)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures ONE GPU: the path has no multi-GPU part (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    if args.generic:
-        os.environ["CONSTSTN_FORCE_GENERIC"] = "1"
-    import paper_2401_04836_amd as cst
-    from paper_2401_04836_amd import schedules as S
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+def one_thread():
+    """Context manager: the oracle's OpenMP team cut to one thread (the paper's regime, Sec. 5)."""
+    import contextlib
+    import ctypes
 
-    if args.calibrate:
-        src = torch.ones(1 << 27, dtype=torch.float64, device=dev)        # 1 GiB
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)                                                     # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        log("calibration copy: 1 GiB read + 1 GiB written by one copy kernel")
-        del src, dst
+    @contextlib.contextmanager
+    def cm():
+        import oracle
+        oracle.lib()
+        omp = ctypes.CDLL("libgomp.so.1")
+        before = oracle.num_threads()
+        omp.omp_set_num_threads(1)
+        try:
+            yield
+        finally:
+            omp.omp_set_num_threads(before)
+    return cm()
 
+
+def measured_peaks(cst):
+    """What this GPU delivers on a plain copy, a plain fill and a loop of fp64 matrix instructions."""
+    try:
+        return {"copy_GBps": cst.measure_peak(cst.PEAK_COPY, 1 << 31, 5),
+                "write_GBps": cst.measure_peak(cst.PEAK_WRITE, 1 << 32, 5),
+                "mfma_f64_TFLOPs": cst.measure_peak(cst.PEAK_MFMA_F64, 4096, 3),
+                "what": "2 GiB device copy (bytes read + written), 4 GiB fill, 8 independent v_mfma_f64_16x16x4 chains "
+                        "with four wavefronts per SIMD; nominal 8000 GB/s and 78.6 TFLOP/s"}
+    except cst.ConststnError as e:
+        return {"error": str(e)}
+
+
+def run_config(cst, S, dev, args, cid, cpu_budget):
+    """Generate configuration `cid`, build its CSFs and plans, time args.steps steps; returns the record."""
     t0 = time.perf_counter()
-    wl = workloads.make(args.config, device=dev, small=args.small)
+    wl = workloads.make(cid, device=dev, small=args.small)
     torch.cuda.synchronize()
     log("generated config %d (%s) in %.1f s: %s" % (
-        args.config, wl.kind, time.perf_counter() - t0,
-        {k: (v.dims, v.nnz) for k, v in wl.sparse.items()}))
+        cid, wl.kind, time.perf_counter() - t0, {k: (v.dims, v.nnz) for k, v in wl.sparse.items()}))
 
     if wl.kind == "mttkrp3" and args.all_modes:
         launches, build_s, nnz_per_step = build_mttkrp_all_modes(cst, S, wl, dev)
@@ -398,9 +392,9 @@ def main():
             "x".join(map(str, wl.sparse["X"].dims)), wl.sparse["X"].nnz, wl.params["rank"])
     elif wl.kind in ("ttmc3", "ttmc4"):
         launches, build_s, nnz_per_step = build_chain(cst, S, wl, dev, wl.params.get("compact", False))
-        name = "C%d TTMc order-%d %s nnz=%d ranks=%s" % (
-            args.config, wl.sparse["X"].order, "x".join(map(str, wl.sparse["X"].dims)),
-            wl.sparse["X"].nnz, wl.params["ranks"])
+        name = "C%d TTMc order-%d %s nnz=%d ranks=%s%s" % (
+            cid, wl.sparse["X"].order, "x".join(map(str, wl.sparse["X"].dims)),
+            wl.sparse["X"].nnz, wl.params["ranks"], ", rows of nonempty slices only" if wl.params.get("compact") else "")
     elif wl.kind == "sppair4":
         launches, build_s, nnz_per_step = build_sppair(cst, S, wl, dev)
         name = "C7 V=E.E lattice %dx%d nnzE=%d nnzV=%d" % (wl.params["side"], wl.params["side"], nnz_per_step // 2,
@@ -449,36 +443,131 @@ def main():
     alg_bytes = sum(L["bytes"] for L in launches) / len(launches)          # per launch
     flops_step = sum(L["flops"] for L in launches)
     achieved = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    step_gbs = sum(L["bytes"] for L in launches) / (dt / args.steps) / 1e9
 
-    family = launches[0]["plan"].describe().split()[0].split("=")[1]
+    desc = launches[0]["plan"].describe().split("|")[0]
+    family = desc.split()[0].split("=")[1]
     if family == "generic":
         name += " [generic executor]"
-    result = {
-        "metric": "fused sparse contraction nnz/s", "value": nnz_per_step / (dt / args.steps),
-        "unit": "nnz/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": name, "step": "one fused contraction pass per CSF (build excluded)"},
+    plain = not (args.small or args.restricted or args.all_modes)
+    rec = {
+        "config_id": cid, "workload": name, "kind": wl.kind,
+        "ms_per_step": ms_per_step, "nnz_per_step": nnz_per_step, "nnz_per_s": nnz_per_step / (dt / args.steps),
         "gflops": flops_step / (dt / args.steps) / 1e9,
         "fp64_frac": flops_step / (dt / args.steps) / 1e12 / FP64_PEAK_TFLOPS,
         "csf_build": {"seconds": build_s, "nnz_per_s": nnz_per_step / build_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(family, None if (args.small or args.restricted or args.all_modes) else args.config),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(family, cid if plain else None),
                      "kernel": KERNEL_NAMES.get(family, family),
                      "kernel_ms_avg": avg_kernel_ms, "launches_timed": len(kernel_ms),
                      "kernel_ms_per_contraction": per_launch_ms,
-                     "algorithmic_bytes_per_launch": alg_bytes},
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     # the same bytes over the whole step (zero-fill and fix-up passes included)
+                     "frac_whole_step": step_gbs / HBM_PEAK_GBS},
     }
     if BOUND.get(family) == "mfma":
         flops_launch = flops_step / len(launches)
         tf = flops_launch / (avg_kernel_ms * 1e-3) / 1e12
-        result["roofline"].update({"bound": "mfma", "achieved": tf, "peak": FP64_PEAK_TFLOPS,
-                                   "unit": "TFLOP/s", "frac": tf / FP64_PEAK_TFLOPS,
-                                   "algorithmic_flops_per_launch": flops_launch})
+        rec["roofline"].update({"bound": "mfma", "achieved": tf, "peak": FP64_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": tf / FP64_PEAK_TFLOPS,
+                                "algorithmic_flops_per_launch": flops_launch,
+                                "frac_whole_step": flops_step / (dt / args.steps) / 1e12 / FP64_PEAK_TFLOPS})
+    # matrix instructions the plan's dominant kernel issues per launch ("mfma=<count>" in the plan text):
+    # utilisation of the matrix cores by the per-slice stage alone, padding included
+    for tok in desc.split():
+        if tok.startswith("mfma="):
+            n_mfma = int(tok[5:])
+            tf = n_mfma * 2048.0 / (avg_kernel_ms * 1e-3) / 1e12
+            rec["roofline"]["mfma_stage"] = {"instructions": n_mfma, "flop_per_instruction": 2048,
+                                             "achieved": tf, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                             "frac": tf / FP64_PEAK_TFLOPS}
+    if wl.kind in ("ttmc3", "mttkrp3", "ttmc4") and family != "generic" and cid == 1:
+        rec["roofline"]["note"] = "0.3 MB problem: launch latency, no roofline claim"
     if not args.no_cpu:
-        cb = cpu_baseline(wl, 400_000_000)
+        cb = cpu_baseline(wl, cpu_budget)
         if cb is not None:
-            result["cpu_baseline"] = cb
+            rec["cpu_baseline"] = cb
+        if cid in (1, 2, 3) and cb is not None:
+            with one_thread():
+                c1 = cpu_baseline(wl, max(cpu_budget // 8, 1_000_000))
+            rec["cpu_baseline_1thread"] = c1
+    log("C%d: %.3f ms/step, %.3g nnz/s, roofline %.3f (%s)" % (cid, ms_per_step, rec["nnz_per_s"],
+                                                                rec["roofline"]["frac"], rec["roofline"]["bound"]))
+    # free the device memory of this configuration before the next one is generated
+    for L in launches:
+        L["plan"].destroy()
+    del launches, wl
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=0,
+                    help="0 (default): configurations 5, 2, 3, 4, 1 in one run, the headline on 5, the largest; "
+                         "1..5: that configuration alone; 6 = the sparse chain of Sec. 5.1 on lattice maps, "
+                         "7 = the four-index product of the same section")
+    ap.add_argument("--all-modes", action="store_true",
+                    help="configuration 2: a step is the MTTKRP of every mode (0, 1, 2), each on a CSF rooted at its mode")
+    ap.add_argument("--restricted", action="store_true", help="configuration 6: the form with the K -> i filter")
+    ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured copy / matrix-core ceilings")
+    ap.add_argument("--generic", action="store_true",
+                    help="plan with the generic executor instead of the tuned kernels (configs 1, 2, 3, 5)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for the FETCH_SIZE / "
+                         "WRITE_SIZE counters of a profiler run)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures ONE GPU: the path has no multi-GPU part (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if args.generic:
+        os.environ["CONSTSTN_FORCE_GENERIC"] = "1"
+    import paper_2401_04836_amd as cst
+    from paper_2401_04836_amd import schedules as S
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.calibrate:
+        src = torch.ones(1 << 27, dtype=torch.float64, device=dev)        # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                                     # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        log("calibration copy: 1 GiB read + 1 GiB written by one copy kernel")
+        del src, dst
+
+    cids = [5, 2, 3, 4, 1] if args.config == 0 else [args.config]
+    # CPU-oracle sample: about 400 M multiply-adds' worth of nonzeros per configuration, less when five run
+    cpu_budget = 400_000_000 if len(cids) == 1 else 200_000_000
+    recs = [run_config(cst, S, dev, args, cid, cpu_budget) for cid in cids]
+    head = recs[0]
+    result = {
+        "metric": "fused sparse contraction nnz/s", "value": head["nnz_per_s"],
+        "unit": "nnz/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": head["workload"], "step": "one fused contraction pass per CSF (build excluded)"},
+        "gflops": head["gflops"], "fp64_frac": head["fp64_frac"], "csf_build": head["csf_build"],
+        "roofline": head["roofline"],
+    }
+    if "cpu_baseline" in head:
+        result["cpu_baseline"] = head["cpu_baseline"]
+    if "cpu_baseline_1thread" in head:
+        result["cpu_baseline_1thread"] = head["cpu_baseline_1thread"]
+    if not args.no_peaks:
+        result["measured_peak"] = measured_peaks(cst)
+    if len(recs) > 1:
+        result["configs"] = recs
     print(json.dumps(result), flush=True)
 
 

@@ -249,6 +249,21 @@ conststn_status conststn_execute(const conststn_plan_t *plan, const double *cons
 conststn_status conststn_plan_profile(conststn_plan_t *plan, int capacity);
 conststn_status conststn_plan_kernel_times(conststn_plan_t *plan, float *ms, int max_n, int *n);
 
+/* Measurement hook (for benchmarks; not part of the method): what the current device delivers on
+ * the ceilings the kernels are priced against, so that a benchmark can print a measured figure
+ * beside the published one.  Synchronous; allocates and frees its own device buffers.
+ *   CONSTSTN_PEAK_COPY      size = bytes (multiple of 16): a plain streaming copy of `size` bytes,
+ *                           repeated `repeats` times; *result = GB/s counting bytes read + written
+ *   CONSTSTN_PEAK_WRITE     size = bytes (multiple of 16): a plain fill; *result = GB/s written
+ *   CONSTSTN_PEAK_MFMA_F64  size = rounds: every wavefront of a full-chip launch (four per SIMD)
+ *                           issues 8 * size independent v_mfma_f64_16x16x4f64; *result = TFLOP/s
+ * Errors: EINVAL, ENOMEM, EHIP. */
+#define CONSTSTN_PEAK_COPY 0
+#define CONSTSTN_PEAK_WRITE 1
+#define CONSTSTN_PEAK_MFMA_F64 2
+conststn_status conststn_measure_peak(int what, int64_t size, int repeats, conststn_stream stream,
+                                      double *result);
+
 /* Message of the last failure on this thread ("" if none). */
 const char *conststn_last_error(void);
 

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "conststn_plan", "conststn_schedule_check", "conststn_schedule_search", "conststn_plan_output_size",
     "conststn_plan_output_rows", "conststn_plan_output_csf", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
-    "conststn_plan_profile", "conststn_plan_kernel_times",
+    "conststn_plan_profile", "conststn_plan_kernel_times", "conststn_measure_peak",
 ]
 
 
@@ -73,6 +73,7 @@ def _load():
     L.conststn_execute.argtypes = [vp, ctypes.POINTER(vp), vp, vp]
     L.conststn_plan_profile.argtypes = [vp, ctypes.c_int]
     L.conststn_plan_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.c_int, ip]
+    L.conststn_measure_peak.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double)]
     for name in EXPORTED_SYMBOLS:
         getattr(L, name)
     return L
@@ -87,6 +88,16 @@ def library_path():
 
 def version():
     return _lib.conststn_version().decode()
+
+
+PEAK_COPY, PEAK_WRITE, PEAK_MFMA_F64 = 0, 1, 2
+
+
+def measure_peak(what, size, repeats=5, stream=None):
+    """Measured ceiling of the current device (GB/s for the copy and the fill, TFLOP/s for the matrix loop)."""
+    r = ctypes.c_double(0.0)
+    _check(_lib.conststn_measure_peak(int(what), int(size), int(repeats), _stream_handle(stream), ctypes.byref(r)))
+    return r.value
 
 
 def _check(status):

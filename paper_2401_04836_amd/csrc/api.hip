@@ -456,6 +456,17 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
             snprintf(b, sizeof(b), " kernel=baseline");
         plan->description += b;
     }
+    if (plan->family == FAM_TTMC3 && plan->use_rows) {
+        char b[128];
+        if (plan->use_stream)
+            // mfma = matrix instructions one execute issues: K-steps x (R2/16) x (R3/16) tiles
+            snprintf(b, sizeof(b), " kernel=stream producers %d batches %lld ksteps %lld mfma=%lld", plan->stream_producers,
+                     (long long)plan->n_stream_wg, (long long)plan->n_ksteps,
+                     (long long)(plan->n_ksteps * (plan->rank_of_level[1] / 16) * (plan->rank_of_level[2] / 16)));
+        else
+            snprintf(b, sizeof(b), " kernel=rows");
+        plan->description += b;
+    }
     if (plan->family == FAM_SPCHAIN3) {
         char b[96];
         if (plan->sc_local)

@@ -8,6 +8,8 @@
 // slice, see partition.hip); lane = r3, the R2 accumulators of column r3 live in registers.
 // All control flow is wave-uniform, so leaf indices/values and the U2 row are fetched with
 // scalar loads and the update is R2 FMAs with a scalar operand.
+#include <type_traits>
+
 #include "plan.hpp"
 
 namespace cst {
@@ -257,6 +259,266 @@ ttmc3_mfma_kernel(Ttmc3RowArgs a) {
         }
 }
 
+// ---- streaming form of the MFMA kernel ---------------------------------------------------------
+//
+// The kernel above gathers, multiplies and stores in one wavefront.  Vector loads and stores of a
+// wavefront retire through one in-order counter, so a wavefront that has issued the 16 KB of stores
+// of a row block cannot see its next gathers arrive before those stores have drained, and the slot
+// stays occupied while they do: gather time and store time add up.  Here the two are separate
+// wavefronts of one workgroup:
+//   producers   (NP wavefronts) walk the plan's flat table of K-steps, every NP-th K-step each: leaf
+//               stage on the vector units (T_s += v * U3[k,:] for the four rows of the step), the four
+//               U2 rows, both written to a packet in LDS in exactly the lane layout of the matrix
+//               instruction's operands.  They never store to memory, so their loads stay in flight
+//               across K-steps and items (descriptors three, rows two, leaves one K-step ahead).
+//   consumers   (R3/32 wavefronts, two column tiles each) take the packets in K-step order, issue the
+//               matrix instructions, and at the last K-step of an item stream the row block out.  They
+//               never load from memory, so nothing waits on the stores.
+// Packets are double-buffered; one s_barrier per round (NP K-steps) orders the two sides.  A workgroup
+// takes a batch of whole items of about equal cost (plan table wg_kstep).  Empty rows of a partial
+// K-step repeat the step's last row with value 0 and a zero U2 operand, so every load is
+// unconditional.  (A ring of packets with ready flags instead of the barrier, letting the producers
+// run sixteen K-steps ahead, measured slower: 20.2 against 18.2 ms on the 140 M-nonzero tensor.)
+struct Ttmc3StreamArgs {
+    int R2, R3;
+    const int32_t *wg_kstep;
+    const KStepDesc *ksteps;
+    const RowDesc *rows;
+    const int32_t *idx2;
+    const double *vals;
+    const double *U2, *U3;
+    double *out, *partial;
+};
+
+typedef double v2f64 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) v2f64 lds_v2f64;
+
+template <int T>
+__device__ __forceinline__ int32_t row_bcast_i32(int32_t x) {
+    return __builtin_amdgcn_mov_dpp(x, 0x150 + T, 0xf, 0xf, false);
+}
+template <int T>
+__device__ __forceinline__ double row_bcast_f64(double x) {
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), 0x150 + T, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), 0x150 + T, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// wait for this wavefront's LDS traffic, then meet the other wavefronts of the workgroup (outstanding
+// vector loads stay in flight: the barrier orders LDS only)
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int PN, int NC, int NP>
+__global__ void __launch_bounds__(64 * (NP + NC))
+ttmc3_stream_kernel(Ttmc3StreamArgs a) {
+    constexpr int APV = (PN + 1) / 2;                 // 16-byte vectors of a lane's U2 operand
+    constexpr int PKT = (APV + NC) * 64;              // 16-byte vectors per packet
+    __shared__ v2f64 pkt[2][NP][PKT];
+    __shared__ int64_t pkt_dest[2][NP];
+    __shared__ int32_t pkt_meta[2][NP];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
+    const int ka = a.wg_kstep[blockIdx.x], kb = a.wg_kstep[blockIdx.x + 1];
+    if (kb <= ka) return;
+    const int rounds = (kb - ka + NP - 1) / NP;
+    const int slot = lane >> 4, c = lane & 15;
+    const int R2 = a.R2, R3 = a.R3;
+
+    if (wave < NP) {
+        // ------------------------------------------------------------------ producer
+        struct Rows { int64_t leaf; int cnt; int32_t j; bool live; };
+        struct Feed { int32_t k; double v; int maxcnt; v2f64 av[APV]; };
+        typedef int v4i32 __attribute__((ext_vector_type(4)));
+        auto kstep_of = [&](int r) -> KStepDesc {
+            int g = ka + r * NP + wave;
+            g = g < kb ? g : kb - 1;
+            // one 16-byte load of the whole record (wave-uniform address); fetched field by field the
+            // compiler moves the part only lane 0 uses under that lane's mask and then waits for it
+            const v4i32 raw = *reinterpret_cast<const v4i32 *>(a.ksteps + g);
+            KStepDesc d;
+            d.row0 = raw[0];
+            d.meta = raw[1];
+            d.dest = int64_t((uint64_t(uint32_t(raw[3])) << 32) | uint32_t(raw[2]));
+            return d;
+        };
+        auto load_rows = [&](const KStepDesc &d) -> Rows {
+            const int n = d.meta & 7;
+            const RowDesc r = a.rows[d.row0 + (slot < n ? slot : n - 1)];
+            return Rows{r.leaf, r.cnt, r.j, slot < n};
+        };
+        auto load_feed = [&](const Rows &r) -> Feed {
+            Feed f;
+            const int ci = c < r.cnt ? c : r.cnt - 1;   // lanes beyond the row repeat its last leaf, value 0
+            f.k = a.idx2[r.leaf + ci];
+            const double v = a.vals[r.leaf + ci];
+            const bool keep = (c < r.cnt) & r.live;     // no short circuit: a branch here draws the load under it
+            f.v = keep ? v : 0.0;
+            const v2f64 *src = reinterpret_cast<const v2f64 *>(a.U2 + int64_t(r.j) * R2 + PN * c);
+#pragma unroll
+            for (int x = 0; x < APV; ++x) {
+                v2f64 u;
+                if (PN % 2 == 1 && x == APV - 1) u = v2f64{a.U2[int64_t(r.j) * R2 + PN * c + PN - 1], 0.0};
+                else u = src[x];
+                f.av[x] = r.live ? u : v2f64{0.0, 0.0};
+            }
+            const int c0 = __builtin_amdgcn_readlane(r.cnt, 0), c1 = __builtin_amdgcn_readlane(r.cnt, 16),
+                      c2 = __builtin_amdgcn_readlane(r.cnt, 32), c3 = __builtin_amdgcn_readlane(r.cnt, 48);
+            f.maxcnt = max(max(c0, c1), max(c2, c3));
+            return f;
+        };
+        KStepDesc d1 = kstep_of(1), d2 = kstep_of(2);
+        Rows r1;
+        Feed cur;
+        int32_t meta_cur;
+        int64_t dest_cur;
+        {
+            const KStepDesc d0 = kstep_of(0);
+            const Rows r0 = load_rows(d0);
+            r1 = load_rows(d1);
+            cur = load_feed(r0);
+            meta_cur = d0.meta;
+            dest_cur = d0.dest;
+        }
+        const char *u3 = reinterpret_cast<const char *>(a.U3);
+        const uint32_t row_bytes = uint32_t(R3) * 8u, lane_off = uint32_t(c) * 16u;
+        for (int r = 0; r < rounds; ++r) {
+            // loads of the rounds ahead, issued before this round's gathers
+            const Feed nxt = load_feed(r1);
+            const int32_t meta_nxt = d1.meta;
+            const int64_t dest_nxt = d1.dest;
+            r1 = load_rows(d2);
+            d1 = d2;
+            d2 = kstep_of(r + 3);
+
+            double t[NC][2];
+#pragma unroll
+            for (int q = 0; q < NC; ++q) t[q][0] = t[q][1] = 0.0;
+            auto batch = [&](auto T0) {
+                constexpr int t0 = decltype(T0)::value;
+                const int32_t kk[4] = {row_bcast_i32<t0>(cur.k), row_bcast_i32<t0 + 1>(cur.k),
+                                       row_bcast_i32<t0 + 2>(cur.k), row_bcast_i32<t0 + 3>(cur.k)};
+                const double vv[4] = {row_bcast_f64<t0>(cur.v), row_bcast_f64<t0 + 1>(cur.v),
+                                      row_bcast_f64<t0 + 2>(cur.v), row_bcast_f64<t0 + 3>(cur.v)};
+                v2f64 uu[4][NC];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int q = 0; q < NC; ++q)
+                        uu[u][q] = *reinterpret_cast<const v2f64 *>(
+                            u3 + size_t(uint32_t(kk[u]) * row_bytes + lane_off) + q * 256);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int q = 0; q < NC; ++q) {
+                        t[q][0] = fma(vv[u], uu[u][q][0], t[q][0]);
+                        t[q][1] = fma(vv[u], uu[u][q][1], t[q][1]);
+                    }
+            };
+            const int maxcnt = cur.maxcnt;
+            batch(std::integral_constant<int, 0>{});
+            if (maxcnt > 4) {
+                batch(std::integral_constant<int, 4>{});
+                if (maxcnt > 8) {
+                    batch(std::integral_constant<int, 8>{});
+                    if (maxcnt > 12) batch(std::integral_constant<int, 12>{});
+                }
+            }
+            v2f64 *dst = &pkt[r & 1][wave][0];
+#pragma unroll
+            for (int x = 0; x < APV; ++x) dst[x * 64 + lane] = cur.av[x];
+#pragma unroll
+            for (int q = 0; q < NC; ++q) dst[(APV + q) * 64 + lane] = v2f64{t[q][0], t[q][1]};
+            if (lane == 0) {
+                pkt_meta[r & 1][wave] = meta_cur;
+                pkt_dest[r & 1][wave] = dest_cur;
+            }
+            cur = nxt;
+            meta_cur = meta_nxt;
+            dest_cur = dest_nxt;
+            lds_barrier();
+        }
+    } else {
+        // ------------------------------------------------------------------ consumer
+        const int part = wave - NP;                    // columns part*32 + 2c, +1 of the row block
+        v4f64 acc[PN][2];
+#pragma unroll
+        for (int p = 0; p < PN; ++p) acc[p][0] = acc[p][1] = v4f64{0.0, 0.0, 0.0, 0.0};
+        const int64_t RR = int64_t(R2) * R3;
+        lds_barrier();                                 // round 0 has been produced
+        for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+            for (int w = 0; w < NP; ++w) {
+                if (ka + r * NP + w < kb) {
+                    const v2f64 *src = &pkt[r & 1][w][0];
+                    v2f64 av[APV];
+#pragma unroll
+                    for (int x = 0; x < APV; ++x) av[x] = src[x * 64 + lane];
+                    const v2f64 tv = src[(APV + part) * 64 + lane];
+                    const int32_t meta = __builtin_amdgcn_readfirstlane(pkt_meta[r & 1][w]);
+#pragma unroll
+                    for (int p = 0; p < PN; ++p) {
+                        const double ap = av[p / 2][p % 2];
+                        acc[p][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(ap, tv[0], acc[p][0], 0, 0, 0);
+                        acc[p][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(ap, tv[1], acc[p][1], 0, 0, 0);
+                    }
+                    if (meta & 8) {
+                        const int64_t dest = uniform64(pkt_dest[r & 1][w]);
+                        double *base = dest >= 0 ? a.out + dest * RR : a.partial + (~dest) * RR;
+                        // tile (p,q): accumulator register v of a lane holds row PN*(slot + 4v) + p,
+                        // column part*32 + 2c + q; streaming stores, the block is never read here
+#pragma unroll
+                        for (int p = 0; p < PN; ++p)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                double *o = base + int64_t(PN * (slot + 4 * v) + p) * R3 + part * 32 + 2 * c;
+                                __builtin_nontemporal_store(v2f64{acc[p][0][v], acc[p][1][v]}, reinterpret_cast<v2f64 *>(o));
+                            }
+#pragma unroll
+                        for (int p = 0; p < PN; ++p) acc[p][0] = acc[p][1] = v4f64{0.0, 0.0, 0.0, 0.0};
+                    }
+                }
+            }
+            if (r + 1 < rounds) lds_barrier();
+        }
+    }
+}
+
+template <int PN, int NC>
+static conststn_status launch_stream_np(const conststn_plan_s *plan, const Ttmc3StreamArgs &a, hipStream_t stream) {
+    ProfScope prof(plan, stream);
+    const dim3 grid(unsigned(plan->n_stream_wg));
+    switch (plan->stream_producers) {
+        case 2: ttmc3_stream_kernel<PN, NC, 2><<<grid, dim3(64 * (2 + NC)), 0, stream>>>(a); break;
+        case 6: ttmc3_stream_kernel<PN, NC, 6><<<grid, dim3(64 * (6 + NC)), 0, stream>>>(a); break;
+        case 8: ttmc3_stream_kernel<PN, NC, 8><<<grid, dim3(64 * (8 + NC)), 0, stream>>>(a); break;
+        default: ttmc3_stream_kernel<PN, NC, 4><<<grid, dim3(64 * (4 + NC)), 0, stream>>>(a); break;
+    }
+    return CONSTSTN_OK;
+}
+
+static conststn_status launch_stream(const conststn_plan_s *plan, const Ttmc3StreamArgs &a, hipStream_t stream) {
+    const int pn = a.R2 / 16;
+    if (a.R3 == 64) {
+        switch (pn) {
+            case 1: return launch_stream_np<1, 2>(plan, a, stream);
+            case 2: return launch_stream_np<2, 2>(plan, a, stream);
+            case 3: return launch_stream_np<3, 2>(plan, a, stream);
+            default: return launch_stream_np<4, 2>(plan, a, stream);
+        }
+    }
+    switch (pn) {
+        case 1: return launch_stream_np<1, 1>(plan, a, stream);
+        case 2: return launch_stream_np<2, 1>(plan, a, stream);
+        case 3: return launch_stream_np<3, 1>(plan, a, stream);
+        default: return launch_stream_np<4, 1>(plan, a, stream);
+    }
+}
+
 template <int PN>
 static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3RowArgs &a, hipStream_t stream) {
     const int qt = a.R3 / 16;
@@ -330,6 +592,25 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
     if (!plan->compact && X->nodes[0] < plan->out_rows)
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.n_items == 0) return CONSTSTN_OK;
+    if (plan->use_rows && plan->use_stream &&
+        (reinterpret_cast<uintptr_t>(a.U2) | reinterpret_cast<uintptr_t>(a.U3) | reinterpret_cast<uintptr_t>(out)) % 16 == 0 &&
+        int64_t(X->dims[X->mode_order[2]]) * a.R3 * 8 < (int64_t(1) << 32)) {
+        Ttmc3StreamArgs sa{};
+        sa.R2 = a.R2;
+        sa.R3 = a.R3;
+        sa.wg_kstep = plan->wg_kstep.p;
+        sa.ksteps = plan->ksteps.p;
+        sa.rows = plan->rows.p;
+        sa.idx2 = a.idx2;
+        sa.vals = a.vals;
+        sa.U2 = a.U2;
+        sa.U3 = a.U3;
+        sa.out = out;
+        sa.partial = a.partial;
+        CST_TRY(launch_stream(plan, sa, stream));
+        CST_HIP(hipGetLastError());
+        return launch_ttmc_fixup(plan, out, stream);
+    }
     if (plan->use_rows) {
         Ttmc3RowArgs ra{};
         ra.n_items = plan->n_items;

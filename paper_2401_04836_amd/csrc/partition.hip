@@ -749,6 +749,91 @@ static conststn_status build_items_core(int64_t slices, const int64_t *unit_ptr,
     return CONSTSTN_OK;
 }
 
+// ---- TTMc order-3 streaming path: flat K-step table and workgroup batches ----------------------
+
+__global__ void item_ksteps_kernel(int64_t n_items, const SliceItem *__restrict__ items, int64_t item_cost,
+                                   int64_t *ksteps_of, int64_t *cost_of) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n_items) return;
+    const int64_t k = (items[i].end - items[i].begin + 3) / 4;
+    ksteps_of[i] = k;
+    cost_of[i] = k + item_cost;
+}
+
+// last i in [0, n) with off[i] <= x  (off ascending, off[0] <= x)
+__device__ __forceinline__ int64_t last_le(const int64_t *__restrict__ off, int64_t n, int64_t x) {
+    int64_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (off[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void fill_ksteps_kernel(int64_t n_ksteps, int64_t n_items, const SliceItem *__restrict__ items,
+                                   const int64_t *__restrict__ kstep_off, const int32_t *__restrict__ idx0,
+                                   int compact, KStepDesc *out) {
+    const int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (g >= n_ksteps) return;
+    const int64_t i = last_le(kstep_off, n_items, g);
+    const SliceItem it = items[i];
+    const int64_t r0 = it.begin + 4 * (g - kstep_off[i]);
+    const int64_t left = it.end - r0;
+    const bool last = left <= 4;
+    KStepDesc d;
+    d.row0 = int32_t(r0);
+    d.meta = int32_t(left < 4 ? left : 4) | (last ? 8 : 0);
+    d.dest = 0;
+    if (last) d.dest = it.dest < 0 ? (compact ? int64_t(it.slice) : int64_t(idx0[it.slice])) : ~it.dest;
+    out[g] = d;
+}
+
+// Workgroup w starts at the first item whose cost prefix reaches w * target: batches hold whole items.
+__global__ void stream_batches_kernel(int64_t n_wg, int64_t n_items, const int64_t *__restrict__ cost_off,
+                                      const int64_t *__restrict__ kstep_off, int64_t target, int64_t n_ksteps,
+                                      int32_t *wg_kstep) {
+    const int64_t w = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (w > n_wg) return;
+    if (w == n_wg) { wg_kstep[w] = int32_t(n_ksteps); return; }
+    const int64_t x = w * target;
+    int64_t i = last_le(cost_off, n_items, x);
+    if (cost_off[i] < x) ++i;                       // first item with prefix >= x
+    wg_kstep[w] = i < n_items ? int32_t(kstep_off[i]) : int32_t(n_ksteps);
+}
+
+static conststn_status build_stream_tables(conststn_plan_s *plan) {
+    const int64_t n_items = plan->n_items;
+    plan->n_ksteps = plan->n_stream_wg = 0;
+    if (n_items == 0) return CONSTSTN_OK;
+    // an item costs its K-steps plus the store of its row block
+    const int64_t item_cost = std::max<int64_t>(env_int("CONSTSTN_TTMC3_ITEMCOST", 2), 0);
+    const int64_t target = std::max<int64_t>(env_int("CONSTSTN_TTMC3_BATCH", 256), 1);
+    DevBuf<int64_t> ksteps_of, cost_of, kstep_off, cost_off;
+    CST_TRY(ksteps_of.alloc(n_items));
+    CST_TRY(cost_of.alloc(n_items));
+    CST_TRY(kstep_off.alloc(n_items));
+    CST_TRY(cost_off.alloc(n_items));
+    const dim3 block(256);
+    item_ksteps_kernel<<<dim3(unsigned(div_up(n_items, 256))), block>>>(n_items, plan->items.p, item_cost,
+                                                                       ksteps_of.p, cost_of.p);
+    CST_HIP(hipGetLastError());
+    int64_t total_cost = 0;
+    CST_TRY(exscan(ksteps_of.p, kstep_off.p, n_items, &plan->n_ksteps));
+    CST_TRY(exscan(cost_of.p, cost_off.p, n_items, &total_cost));
+    if (plan->n_ksteps >= (int64_t(1) << 31)) { set_error("more than 2^31 K-steps"); return CONSTSTN_EUNSUPPORTED; }
+    CST_TRY(plan->ksteps.alloc(size_t(plan->n_ksteps)));
+    fill_ksteps_kernel<<<dim3(unsigned(div_up(plan->n_ksteps, 256))), block>>>(
+        plan->n_ksteps, n_items, plan->items.p, kstep_off.p, plan->X->idx[0].p, plan->compact ? 1 : 0, plan->ksteps.p);
+    CST_HIP(hipGetLastError());
+    plan->n_stream_wg = div_up(total_cost, target);
+    CST_TRY(plan->wg_kstep.alloc(size_t(plan->n_stream_wg) + 1));
+    stream_batches_kernel<<<dim3(unsigned(div_up(plan->n_stream_wg + 1, 256))), block>>>(
+        plan->n_stream_wg, n_items, cost_off.p, kstep_off.p, target, plan->n_ksteps, plan->wg_kstep.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
 conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t slices = X->nodes[0];
@@ -787,6 +872,15 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
                              plan->items, plan->n_items, plan->n_partials, plan->n_split, plan->split_slices,
                              plan->split_first, plan->split_count, plan->partial));
     CST_HIP(hipDeviceSynchronize());
+    // streaming form of the order-3 matrix-core path: R3 of 32 or 64 (two column tiles per multiplying
+    // wavefront), rows and output blocks reachable with the table's 32-bit fields
+    plan->use_stream = X->order == 3 && plan->use_rows && (plan->rank_of_level[2] == 32 || plan->rank_of_level[2] == 64) &&
+                       env_int("CONSTSTN_TTMC3_STREAM", 1) == 1;
+    if (plan->use_stream) {
+        int np = int(env_int("CONSTSTN_TTMC3_PRODUCERS", 4));
+        plan->stream_producers = np == 2 || np == 6 || np == 8 ? np : 4;
+        CST_TRY(build_stream_tables(plan));
+    }
     return CONSTSTN_OK;
 }
 

@@ -78,6 +78,13 @@ struct alignas(16) RowDesc {
     int32_t j;              // level-1 index of the fiber
 };
 
+// One K-step (four rows, the K of one matrix instruction) of the streaming order-3 TTMc path.
+struct alignas(16) KStepDesc {
+    int32_t row0;           // first row
+    int32_t meta;           // bits 0-2: rows in the step (1..4); bit 3: last step of its item
+    int64_t dest;           // last step only: >= 0 row block of the output, < 0: ~(partial row block)
+};
+
 // One piece of the order-4 TTMc MFMA path: at most kPieceLeaves (= 2) consecutive leaves of one
 // (i,j,k) node, copied out of the CSF so that one 32-byte read brings everything the leaf stage
 // needs and no second, dependent load of the leaves follows.
@@ -159,6 +166,13 @@ struct conststn_plan_s {
     cst::DevBuf<cst::RowDesc> rows;        // [rows] order-3 path; rows of a slice ordered from long to short
     cst::DevBuf<int32_t> row_j;            // [rows] order-4 path: level-1 index of the row's fiber
     cst::DevBuf<int64_t> slice_row;        // [slices+1] first row of each slice
+    // streaming form of that path: the K-steps of all items as one flat table, and the first K-step of
+    // the batch of whole items each workgroup walks
+    bool use_stream = false;
+    int stream_producers = 4;              // wavefronts of a workgroup that gather (the others multiply and store)
+    int64_t n_ksteps = 0, n_stream_wg = 0;
+    cst::DevBuf<cst::KStepDesc> ksteps;
+    cst::DevBuf<int32_t> wg_kstep;         // [n_stream_wg + 1]
     // TTMc order-4 MFMA path: level-2 nodes cut into "pieces" of at most kPieceLeaves leaves,
     // level-1 fibers cut into rows of at most 4 pieces; rows index pieces, pieces index leaves
     int64_t n_pieces = 0;
