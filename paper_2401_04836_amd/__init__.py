@@ -268,6 +268,9 @@ class Plan:
         self._h = handle
         self._operands = operands          # keeps the CSF handles alive
         self.device = device
+        # shapes of the dense operands in the order execute() takes them
+        self._dense_shapes = [tuple(o.shape) if hasattr(o, "shape") else tuple(o) for o in operands
+                              if not isinstance(o, CSF)]
         r, e = ctypes.c_int64(), ctypes.c_int64()
         _check(_lib.conststn_plan_output_size(self._h, ctypes.byref(r), ctypes.byref(e)))
         self.n_rows, self.row_elems = r.value, e.value
@@ -330,22 +333,33 @@ def plan(schedule, operands, fusion=None, flags=0):
     return Plan(out, [obj for _, obj in operands], device)
 
 
-def execute(pl, dense_factors, out=None, stream=None):
-    """conststn_execute: dense_factors in the order the dense operands were listed in plan()."""
+def _marshal_execute(pl, dense_factors, out):
     n = len(dense_factors)
+    if n != len(pl._dense_shapes):
+        raise ValueError("the plan has %d dense operands, %d were given" % (len(pl._dense_shapes), n))
     ptrs = (ctypes.c_void_p * max(n, 1))()
-    keep = []
     for d, f in enumerate(dense_factors):
         if f.dtype != torch.float64 or f.device != pl.device:
             raise ValueError("dense factor %d must be an fp64 tensor on %s" % (d, pl.device))
-        f = f.contiguous()
-        keep.append(f)
+        if tuple(f.shape) != pl._dense_shapes[d]:
+            raise ValueError("dense factor %d has shape %s, the plan was made for %s"
+                             % (d, tuple(f.shape), pl._dense_shapes[d]))
+        if not f.is_contiguous():
+            # no hidden copy: it would be made on torch's current stream and freed while the kernels,
+            # enqueued on the caller's stream, may still read it
+            raise ValueError("dense factor %d must be contiguous (row-major)" % d)
         ptrs[d] = f.data_ptr()
     if out is None:
         out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=pl.device)
     elif out.dtype != torch.float64 or out.device != pl.device or out.numel() != pl.n_rows * pl.row_elems \
             or not out.is_contiguous():
         raise ValueError("out must be a contiguous fp64 tensor of n_rows*row_elems elements")
+    return ptrs, out
+
+
+def execute(pl, dense_factors, out=None, stream=None):
+    """conststn_execute: dense_factors in the order the dense operands were listed in plan()."""
+    ptrs, out = _marshal_execute(pl, dense_factors, out)
     with torch.cuda.device(pl.device):
         _check(_lib.conststn_execute(pl._h, ptrs, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream)))
     return out

@@ -398,34 +398,48 @@ ttmc3_stream_kernel(Ttmc3StreamArgs a) {
             double t[NC][2];
 #pragma unroll
             for (int q = 0; q < NC; ++q) t[q][0] = t[q][1] = 0.0;
-            auto batch = [&](auto T0) {
-                constexpr int t0 = decltype(T0)::value;
-                const int32_t kk[4] = {row_bcast_i32<t0>(cur.k), row_bcast_i32<t0 + 1>(cur.k),
-                                       row_bcast_i32<t0 + 2>(cur.k), row_bcast_i32<t0 + 3>(cur.k)};
-                const double vv[4] = {row_bcast_f64<t0>(cur.v), row_bcast_f64<t0 + 1>(cur.v),
-                                      row_bcast_f64<t0 + 2>(cur.v), row_bcast_f64<t0 + 3>(cur.v)};
-                v2f64 uu[4][NC];
+            // leaf steps t0 .. t0+N-1 of the four rows: 2N gathers in flight, then the products.  N is exact
+            // (not rounded up to four): most K-steps of a power-law tensor hold rows of a single leaf, and
+            // every gather instruction counts.
+            auto batch = [&](auto T0, auto NN) {
+                constexpr int t0 = decltype(T0)::value, N = decltype(NN)::value;
+                int32_t kk[4] = {row_bcast_i32<t0>(cur.k), 0, 0, 0};
+                double vv[4] = {row_bcast_f64<t0>(cur.v), 0.0, 0.0, 0.0};
+                if (N > 1) { kk[1] = row_bcast_i32<t0 + 1>(cur.k); vv[1] = row_bcast_f64<t0 + 1>(cur.v); }
+                if (N > 2) { kk[2] = row_bcast_i32<t0 + 2>(cur.k); vv[2] = row_bcast_f64<t0 + 2>(cur.v); }
+                if (N > 3) { kk[3] = row_bcast_i32<t0 + 3>(cur.k); vv[3] = row_bcast_f64<t0 + 3>(cur.v); }
+                v2f64 uu[N][NC];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < N; ++u)
 #pragma unroll
                     for (int q = 0; q < NC; ++q)
                         uu[u][q] = *reinterpret_cast<const v2f64 *>(
                             u3 + size_t(uint32_t(kk[u]) * row_bytes + lane_off) + q * 256);
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < N; ++u)
 #pragma unroll
                     for (int q = 0; q < NC; ++q) {
                         t[q][0] = fma(vv[u], uu[u][q][0], t[q][0]);
                         t[q][1] = fma(vv[u], uu[u][q][1], t[q][1]);
                     }
             };
+            auto chunk = [&](auto T0, int n) {
+                using I1 = std::integral_constant<int, 1>;
+                using I2 = std::integral_constant<int, 2>;
+                using I3 = std::integral_constant<int, 3>;
+                using I4 = std::integral_constant<int, 4>;
+                if (n >= 4) batch(T0, I4{});
+                else if (n == 3) batch(T0, I3{});
+                else if (n == 2) batch(T0, I2{});
+                else batch(T0, I1{});
+            };
             const int maxcnt = cur.maxcnt;
-            batch(std::integral_constant<int, 0>{});
+            chunk(std::integral_constant<int, 0>{}, maxcnt);
             if (maxcnt > 4) {
-                batch(std::integral_constant<int, 4>{});
+                chunk(std::integral_constant<int, 4>{}, maxcnt - 4);
                 if (maxcnt > 8) {
-                    batch(std::integral_constant<int, 8>{});
-                    if (maxcnt > 12) batch(std::integral_constant<int, 12>{});
+                    chunk(std::integral_constant<int, 8>{}, maxcnt - 8);
+                    if (maxcnt > 12) chunk(std::integral_constant<int, 12>{}, maxcnt - 12);
                 }
             }
             v2f64 *dst = &pkt[r & 1][wave][0];

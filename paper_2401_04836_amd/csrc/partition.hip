@@ -807,7 +807,7 @@ static conststn_status build_stream_tables(conststn_plan_s *plan) {
     if (n_items == 0) return CONSTSTN_OK;
     // an item costs its K-steps plus the store of its row block
     const int64_t item_cost = std::max<int64_t>(env_int("CONSTSTN_TTMC3_ITEMCOST", 2), 0);
-    const int64_t target = std::max<int64_t>(env_int("CONSTSTN_TTMC3_BATCH", 256), 1);
+    const int64_t target = std::max<int64_t>(env_int("CONSTSTN_TTMC3_BATCH", 1024), 1);
     DevBuf<int64_t> ksteps_of, cost_of, kstep_off, cost_off;
     CST_TRY(ksteps_of.alloc(n_items));
     CST_TRY(cost_of.alloc(n_items));
