@@ -238,6 +238,21 @@ void conststn_plan_destroy(conststn_plan_t *plan);
 conststn_status conststn_execute(const conststn_plan_t *plan, const double *const *dense_factors,
                                  double *out, conststn_stream stream);
 
+/* conststn_execute for callers that may not allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc -- and want no plan-owned scratch either:
+ * the partial row blocks of slices cut into several work items live in a static device array of
+ * CONSTSTN_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the library runs
+ * on holds its own copy until the process ends).  The call allocates and frees nothing.  Plans of
+ * the order-3 TTMc kernels only (CONSTSTN_EUNSUPPORTED otherwise, and when the plan's partial row
+ * blocks need more than the static area: the message names both sizes).  Arguments, output layout
+ * and results are those of conststn_execute.  Every call on one GPU shares that GPU's array,
+ * whatever the plan: calls that overlap in time on one GPU race (conststn_execute calls of other
+ * plans do not use it).  Nothing in the array needs clearing between calls: every partial block a
+ * call reads it has written before. */
+#define CONSTSTN_STATIC_SCRATCH_BYTES (64u << 20)
+conststn_status conststn_execute_static(const conststn_plan_t *plan, const double *const *dense_factors,
+                                        double *out, conststn_stream stream);
+
 /* Measurement hook (for benchmarks; not part of the method).  After
  * conststn_plan_profile(plan, capacity > 0) every conststn_execute of the plan brackets its
  * DOMINANT kernel (the fused traversal kernel, not the zero-fill or fix-up passes) with a pair

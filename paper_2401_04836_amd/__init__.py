@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "conststn_plan", "conststn_schedule_check", "conststn_schedule_search", "conststn_plan_output_size",
     "conststn_plan_output_rows", "conststn_plan_output_csf", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
-    "conststn_plan_profile", "conststn_plan_kernel_times", "conststn_measure_peak",
+    "conststn_plan_profile", "conststn_plan_kernel_times", "conststn_measure_peak", "conststn_execute_static",
 ]
 
 
@@ -71,6 +71,7 @@ def _load():
     L.conststn_plan_destroy.argtypes = [vp]
     L.conststn_plan_destroy.restype = None
     L.conststn_execute.argtypes = [vp, ctypes.POINTER(vp), vp, vp]
+    L.conststn_execute_static.argtypes = [vp, ctypes.POINTER(vp), vp, vp]
     L.conststn_plan_profile.argtypes = [vp, ctypes.c_int]
     L.conststn_plan_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.c_int, ip]
     L.conststn_measure_peak.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double)]
@@ -362,4 +363,15 @@ def execute(pl, dense_factors, out=None, stream=None):
     ptrs, out = _marshal_execute(pl, dense_factors, out)
     with torch.cuda.device(pl.device):
         _check(_lib.conststn_execute(pl._h, ptrs, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream)))
+    return out
+
+
+def execute_static(pl, dense_factors, out, stream=None):
+    """conststn_execute_static: as execute(), with the library's static scratch array; `out` is
+    required (the call itself allocates nothing)."""
+    if out is None:
+        raise ValueError("execute_static needs the output tensor")
+    ptrs, out = _marshal_execute(pl, dense_factors, out)
+    with torch.cuda.device(pl.device):
+        _check(_lib.conststn_execute_static(pl._h, ptrs, ctypes.c_void_p(out.data_ptr()), _stream_handle(stream)))
     return out

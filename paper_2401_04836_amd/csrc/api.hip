@@ -467,6 +467,11 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
             snprintf(b, sizeof(b), " kernel=rows");
         plan->description += b;
     }
+    if (plan->family == FAM_TTMC3 || plan->family == FAM_TTMC4) {
+        char b[64];
+        snprintf(b, sizeof(b), " partial_blocks=%lld", (long long)plan->n_partials);
+        plan->description += b;
+    }
     if (plan->family == FAM_SPCHAIN3) {
         char b[96];
         if (plan->sc_local)
@@ -581,6 +586,21 @@ conststn_status conststn_execute(const conststn_plan_t *plan, const double *cons
         case FAM_GENERIC: return launch_generic(plan, dense_factors, out, st);
         default: set_error("plan has no kernel family"); return CONSTSTN_EINVAL;
     }
+}
+
+conststn_status conststn_execute_static(const conststn_plan_t *plan, const double *const *dense_factors,
+                                        double *out, conststn_stream stream) {
+    clear_error();
+    if (!plan) { set_error("plan is null"); return CONSTSTN_EINVAL; }
+    if (plan->family != FAM_TTMC3) {
+        set_error("conststn_execute_static takes plans of the order-3 TTMc kernels only (this one is %s)", family_name(plan->family));
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    if (!out && plan->out_rows * plan->row_elems > 0) { set_error("out is null"); return CONSTSTN_EINVAL; }
+    if (!dense_factors) { set_error("dense_factors is null"); return CONSTSTN_EINVAL; }
+    for (int d = 0; d < plan->n_dense; ++d)
+        if (!dense_factors[d]) { set_error("dense_factors[%d] is null", d); return CONSTSTN_EINVAL; }
+    return launch_ttmc3_static(plan, dense_factors, out, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

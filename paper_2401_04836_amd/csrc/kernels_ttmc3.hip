@@ -572,19 +572,60 @@ ttmc_fixup_kernel(int64_t RR, const int32_t *__restrict__ split_slices,
     }
 }
 
-conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream) {
+conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream, const double *partial) {
     if (plan->n_split == 0) return CONSTSTN_OK;
+    if (!partial) partial = plan->partial.p;
     const int64_t RR = plan->row_elems;
     const unsigned gy = unsigned(std::min<int64_t>(div_up(RR, 256), 64));
     ttmc_fixup_kernel<<<dim3(unsigned(plan->n_split), gy), dim3(256), 0, stream>>>(
         RR, plan->split_slices.p, plan->split_first.p, plan->split_count.p, plan->X->idx[0].p,
-        plan->compact ? 1 : 0, plan->partial.p, out);
+        plan->compact ? 1 : 0, partial, out);
     CST_HIP(hipGetLastError());
     return CONSTSTN_OK;
 }
 
+// Partial row blocks for callers that may not allocate: one array per device, linked into the code
+// object, shared by every call of conststn_execute_static on that device.
+static __device__ __align__(256) unsigned char scratch[CONSTSTN_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static double *g_scratch_of_device[kMaxDevices];      // address of `scratch` on each device, looked up once
+
+static conststn_status static_scratch(double **p) {
+    int dev = 0;
+    CST_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d beyond %d", dev, kMaxDevices); return CONSTSTN_EUNSUPPORTED; }
+    if (!g_scratch_of_device[dev]) {
+        void *addr = nullptr;
+        CST_HIP(hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)));
+        g_scratch_of_device[dev] = static_cast<double *>(addr);
+    }
+    *p = g_scratch_of_device[dev];
+    return CONSTSTN_OK;
+}
+
+static conststn_status launch_ttmc3_with(const conststn_plan_s *plan, const double *const *dense, double *out,
+                                         hipStream_t stream, double *partial);
+
 conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream) {
+    return launch_ttmc3_with(plan, dense, out, stream, plan->partial.p);
+}
+
+conststn_status launch_ttmc3_static(const conststn_plan_s *plan, const double *const *dense, double *out,
+                                    hipStream_t stream) {
+    const int64_t need = plan->n_partials * plan->row_elems * int64_t(sizeof(double));
+    if (need > int64_t(CONSTSTN_STATIC_SCRATCH_BYTES)) {
+        set_error("the plan needs %lld bytes of partial row blocks, the static scratch area holds %lld: use conststn_execute",
+                  (long long)need, (long long)CONSTSTN_STATIC_SCRATCH_BYTES);
+        return CONSTSTN_EUNSUPPORTED;
+    }
+    double *ptr = nullptr;
+    CST_TRY(static_scratch(&ptr));
+    return launch_ttmc3_with(plan, dense, out, stream, ptr);
+}
+
+static conststn_status launch_ttmc3_with(const conststn_plan_s *plan, const double *const *dense, double *out,
+                                         hipStream_t stream, double *partial) {
     const conststn_csf_s *X = plan->X;
     Ttmc3Args a{};
     a.n_items = plan->n_items;
@@ -600,7 +641,7 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
     a.U2 = dense[plan->factor_of_level[1]];
     a.U3 = dense[plan->factor_of_level[2]];
     a.out = out;
-    a.partial = plan->partial.p;
+    a.partial = partial;
     a.compact = plan->compact ? 1 : 0;
     if (a.R2 > 64 || a.R3 > 64) { set_error("TTMc ranks above 64 are not implemented"); return CONSTSTN_EUNSUPPORTED; }
     if (!plan->compact && X->nodes[0] < plan->out_rows)
@@ -623,7 +664,7 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
         sa.partial = a.partial;
         CST_TRY(launch_stream(plan, sa, stream));
         CST_HIP(hipGetLastError());
-        return launch_ttmc_fixup(plan, out, stream);
+        return launch_ttmc_fixup(plan, out, stream, partial);
     }
     if (plan->use_rows) {
         Ttmc3RowArgs ra{};
@@ -647,7 +688,7 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
             default: CST_TRY(launch_mfma_pn<4>(plan, ra, stream)); break;
         }
         CST_HIP(hipGetLastError());
-        return launch_ttmc_fixup(plan, out, stream);
+        return launch_ttmc_fixup(plan, out, stream, partial);
     }
     const dim3 grid(unsigned(div_up(a.n_items, 4))), block(256);
     {
@@ -658,7 +699,7 @@ conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *d
         else ttmc3_kernel<64><<<grid, block, 0, stream>>>(a);
     }
     CST_HIP(hipGetLastError());
-    return launch_ttmc_fixup(plan, out, stream);
+    return launch_ttmc_fixup(plan, out, stream, partial);
 }
 
 }  // namespace cst

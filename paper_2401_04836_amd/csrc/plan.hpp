@@ -261,6 +261,9 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
                                hipStream_t stream);
 conststn_status launch_ttmc3(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream);
+// the same with the partial row blocks in the library's static scratch array instead of the plan's buffer
+conststn_status launch_ttmc3_static(const conststn_plan_s *plan, const double *const *dense, double *out,
+                                    hipStream_t stream);
 conststn_status launch_ttmc4(const conststn_plan_s *plan, const double *const *dense, double *out,
                              hipStream_t stream);
 conststn_status launch_sptn3(const conststn_plan_s *plan, const double *const *dense, double *out,
@@ -280,7 +283,7 @@ conststn_status build_generic(conststn_plan_s *plan);
 conststn_status launch_generic(const conststn_plan_s *plan, const double *const *dense, double *out,
                                hipStream_t stream);
 // sums the partial row blocks of slices made of several items (shared by the TTMc kernels)
-conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream);
+conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream, const double *partial = nullptr);
 
 // csf_build.hip
 conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
