@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 import workloads  # noqa: E402
 
+PLAN_OPTIONS = None          # tuning options handed to every plan (--generic, --plan-options)
 HBM_PEAK_GBS = 8000.0
 FP64_PEAK_TFLOPS = 78.6
 CSRC = os.path.join(ROOT, "paper_2401_04836_amd", "csrc")
@@ -73,9 +74,9 @@ def build_mttkrp(cst, S, wl, dev):
     t0 = time.perf_counter()
     csf0 = cst.build_csf(coords, vals, X.dims, [0, 1, 2])
     csf2 = cst.build_csf(coords, vals, X.dims, [2, 1, 0])
-    pl0 = cst.plan(S.MTTKRP3, [("X", csf0), ("C", C), ("B", B)])
+    pl0 = cst.plan(S.MTTKRP3, [("X", csf0), ("C", C), ("B", B)], options=PLAN_OPTIONS)
     pl2 = cst.plan("T[k,j,r] = X[k,j,i] * A[i,r] | k,j,i,r ; M[k,r] = T[k,j,r] * B[j,r] | k,j,r",
-                   [("X", csf2), ("A", A), ("B", B)])
+                   [("X", csf2), ("A", A), ("B", B)], options=PLAN_OPTIONS)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     R = B.shape[1]
@@ -106,7 +107,7 @@ def build_mttkrp_all_modes(cst, S, wl, dev):
         csf = cst.build_csf(coords, vals, X.dims, levels)
         text, names = S.mttkrp3_for(levels)
         facs = [F[levels[2]], F[levels[1]]]
-        pl = cst.plan(text, [("X", csf), (names[1], facs[0]), (names[2], facs[1])])
+        pl = cst.plan(text, [("X", csf), (names[1], facs[0]), (names[2], facs[1])], options=PLAN_OPTIONS)
         nodes = [csf.nodes(l) for l in range(3)]
         out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
         alg_bytes = 12 * sum(nodes) + 8 * R * (facs[0].shape[0] + facs[1].shape[0]) + 8 * pl.n_rows * pl.row_elems
@@ -126,11 +127,11 @@ def build_chain(cst, S, wl, dev, compact):
     flags = cst.OUT_COMPACT if compact else 0
     if wl.kind == "ttmc3":
         U2, U3 = wl.dense["U2"].to(dev), wl.dense["U3"].to(dev)
-        pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags)
+        pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags, options=PLAN_OPTIONS)
         facs = [U3, U2]
     else:
         U1, U2, U3 = (wl.dense[k].to(dev) for k in ("U1", "U2", "U3"))
-        pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)], flags=flags)
+        pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)], flags=flags, options=PLAN_OPTIONS)
         facs = [U3, U2, U1]
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
@@ -154,7 +155,7 @@ def build_sptn(cst, S, wl, dev):
     t0 = time.perf_counter()
     ucsf = cst.build_csf(uc, uv, U.dims, [0, 2, 1])
     wcsf = cst.build_csf(wc, wv, W.dims, [0, 1, 2])
-    pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)])
+    pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)], options=PLAN_OPTIONS)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
@@ -181,7 +182,7 @@ def build_spchain(cst, S, wl, dev, restricted):
     if restricted:
         hL = cst.build_csf(lc, lv, L.dims, [0, 1])
         ops = [("I", hI), ("C", hC), ("L", hL), ("P", hP)]
-    pl = cst.plan(S.SPCHAIN3_RESTRICTED if restricted else S.SPCHAIN3, ops)
+    pl = cst.plan(S.SPCHAIN3_RESTRICTED if restricted else S.SPCHAIN3, ops, options=PLAN_OPTIONS)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     E = pl.output_csf()
@@ -216,7 +217,7 @@ def build_sppair(cst, S, wl, dev):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     hE = cst.build_csf([eK, ei, em], ev, (n_K, n_i, n_m), [1, 0, 2])
-    pl = cst.plan(S.SPPAIR4, [("Ea", hE), ("Eb", hE)])
+    pl = cst.plan(S.SPPAIR4, [("Ea", hE), ("Eb", hE)], options=PLAN_OPTIONS)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     V = pl.output_csf()
@@ -520,6 +521,7 @@ def main():
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured copy / matrix-core ceilings")
     ap.add_argument("--generic", action="store_true",
                     help="plan with the generic executor instead of the tuned kernels (configs 1, 2, 3, 5)")
+    ap.add_argument("--plan-options", default=None, help="tuning options for every plan, \"name=value,...\"")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for the FETCH_SIZE / "
                          "WRITE_SIZE counters of a profiler run)")
@@ -530,8 +532,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    global PLAN_OPTIONS
+    PLAN_OPTIONS = args.plan_options
     if args.generic:
-        os.environ["CONSTSTN_FORCE_GENERIC"] = "1"
+        PLAN_OPTIONS = "force_generic=1" + ("," + PLAN_OPTIONS if PLAN_OPTIONS else "")
     import paper_2401_04836_amd as cst
     from paper_2401_04836_amd import schedules as S
     dev = torch.device("cuda:0")

@@ -139,8 +139,8 @@ void conststn_csf_destroy(conststn_csf_t *csf);
  * summed by one statement, a fully contracted result, a result indexed by CSF levels other than
  * the root (every output mode on one CSF; such a result is a dense array over the extents of all
  * its indices and is added into with fp64 atomics), any fusion choice -- runs on a generic
- * executor (one pass per statement, intermediates held whole in device memory; environment
- * variable CONSTSTN_GENERIC_MAX_GB bounds them, default 64).  A legal schedule outside all of
+ * executor (one pass per statement, intermediates held whole in device memory; plan option
+ * generic_max_gb bounds them, default 64).  A legal schedule outside all of
  * these gives CONSTSTN_EUNSUPPORTED with the reason.
  * The plan keeps pointers into the CSF handles: destroy the plan first.
  */
@@ -157,6 +157,23 @@ typedef struct {
 conststn_status conststn_plan(const char *schedule, const int *fusion, int n_operands,
                               const conststn_operand_desc *operands, unsigned flags,
                               conststn_plan_t **out);
+
+/* conststn_plan with tuning options: `options` is a host string "name=value,name=value" (NULL or ""
+ * = every default; values are non-negative integers; an unknown name is CONSTSTN_EINVAL).  The
+ * options choose among kernel forms and partition sizes that compute the same result; they are read
+ * while the plan is built and stored in it -- nothing is read from the environment, and an execute
+ * reads no option.  Names (default): force_generic (0; 1 = the generic executor also where a tuned
+ * kernel exists), generic_max_gb (64), generic_span (4096), mttkrp_split (1), mttkrp_hot (256),
+ * mttkrp_chunk (0 = by tensor size), ttmc3_mfma (1), ttmc3_stream (1), ttmc3_producers (4),
+ * ttmc3_batch (1024), ttmc3_itemcost (2), ttmc3_qn (2), ttmc3_split (4096), ttmc3_rowsplit (by size),
+ * ttmc4_mfma (1), ttmc4_split (256), ttmc4_ksplit (by size), sptn3_tiled (1; 0 = baseline kernel, 2 = tiled kernel
+ * also where W fills its 16 x 16 tiles to less than a sixteenth),
+ * sptn3_waves (2), sptn3_wgs (8000), sptn3_xcd (0), spchain3_form (1; 2 = general numeric pass),
+ * spchain3_local_kb (78), spchain3_pk_gb (4), sppair4_keep (1), sppair4_keep_gb (4), sppair4_rows (1),
+ * sppair4_rows_gb (8), sppair4_buffers (2), sppair4_xcd (1). */
+conststn_status conststn_plan_options(const char *schedule, const int *fusion, int n_operands,
+                                      const conststn_operand_desc *operands, unsigned flags,
+                                      const char *options, conststn_plan_t **out);
 
 /* Host-only: parse and check a schedule exactly as conststn_plan does, and lower it to
  * nested forall / where text (the concrete-index-notation shape of Sec. 4.1, produced by the

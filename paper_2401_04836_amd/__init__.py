@@ -22,7 +22,7 @@ OPERAND_CSF, OPERAND_DENSE = 0, 1
 
 EXPORTED_SYMBOLS = [
     "conststn_build_csf", "conststn_csf_info", "conststn_csf_export", "conststn_csf_destroy",
-    "conststn_plan", "conststn_schedule_check", "conststn_schedule_search", "conststn_plan_output_size",
+    "conststn_plan", "conststn_plan_options", "conststn_schedule_check", "conststn_schedule_search", "conststn_plan_output_size",
     "conststn_plan_output_rows", "conststn_plan_output_csf", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
     "conststn_plan_profile", "conststn_plan_kernel_times", "conststn_measure_peak", "conststn_execute_static",
@@ -60,6 +60,8 @@ def _load():
     L.conststn_csf_destroy.restype = None
     L.conststn_plan.argtypes = [ctypes.c_char_p, ip, ctypes.c_int, ctypes.POINTER(_OperandDesc),
                                 ctypes.c_uint, ctypes.POINTER(vp)]
+    L.conststn_plan_options.argtypes = [ctypes.c_char_p, ip, ctypes.c_int, ctypes.POINTER(_OperandDesc),
+                                        ctypes.c_uint, ctypes.c_char_p, ctypes.POINTER(vp)]
     L.conststn_schedule_check.argtypes = [ctypes.c_char_p, ip, ctypes.c_int, ctypes.POINTER(_OperandDesc),
                                           ctypes.c_char_p, ctypes.c_size_t, ip]
     L.conststn_schedule_search.argtypes = [ctypes.c_char_p, ctypes.c_int, ctypes.POINTER(_OperandDesc), ctypes.c_uint,
@@ -318,8 +320,11 @@ class Plan:
             pass
 
 
-def plan(schedule, operands, fusion=None, flags=0):
-    """conststn_plan: operands = list of (name, CSF) or (name, dense tensor / shape)."""
+def plan(schedule, operands, fusion=None, flags=0, options=None):
+    """conststn_plan / conststn_plan_options: operands = list of (name, CSF) or (name, dense tensor /
+    shape); options = None, a "name=value,..." string or a dict of tuning options."""
+    if isinstance(options, dict):
+        options = ",".join("%s=%d" % (k, int(v)) for k, v in options.items())
     descs, keep = _make_descs(operands)
     cf = (ctypes.c_int * len(fusion))(*fusion) if fusion is not None else None
     out = ctypes.c_void_p()
@@ -330,7 +335,8 @@ def plan(schedule, operands, fusion=None, flags=0):
     if device is None:
         raise ValueError("a plan needs at least one CSF operand")
     with torch.cuda.device(device):
-        _check(_lib.conststn_plan(schedule.encode(), cf, len(operands), descs, flags, ctypes.byref(out)))
+        _check(_lib.conststn_plan_options(schedule.encode(), cf, len(operands), descs, flags,
+                                          options.encode() if options else None, ctypes.byref(out)))
     return Plan(out, [obj for _, obj in operands], device)
 
 

@@ -376,6 +376,35 @@ conststn_status conststn_schedule_search(const char *tree, int n_operands, const
 conststn_status conststn_plan(const char *schedule, const int *fusion, int n_operands,
                               const conststn_operand_desc *operands, unsigned flags,
                               conststn_plan_t **out) {
+    return conststn_plan_options(schedule, fusion, n_operands, operands, flags, nullptr, out);
+}
+
+// "name=value,name=value" (spaces allowed around the separators) into the plan's option table
+static conststn_status parse_plan_options(const char *text, conststn_plan_s *plan) {
+    if (!text) return CONSTSTN_OK;
+    std::string s(text), item;
+    size_t pos = 0;
+    while (pos <= s.size()) {
+        const size_t end = std::min(s.find(',', pos), s.size());
+        item = s.substr(pos, end - pos);
+        pos = end + 1;
+        item.erase(std::remove(item.begin(), item.end(), ' '), item.end());
+        if (item.empty()) continue;
+        const size_t eq = item.find('=');
+        if (eq == std::string::npos || eq == 0 || eq + 1 == item.size()) { set_error("plan option '%s' is not of the form name=value", item.c_str()); return CONSTSTN_EINVAL; }
+        const std::string name = item.substr(0, eq);
+        char *stop = nullptr;
+        const long long v = std::strtoll(item.c_str() + eq + 1, &stop, 10);
+        if (!stop || *stop != 0 || v < 0) { set_error("plan option '%s': the value must be a non-negative integer", item.c_str()); return CONSTSTN_EINVAL; }
+        if (!known_plan_option(name)) { set_error("unknown plan option '%s'", name.c_str()); return CONSTSTN_EINVAL; }
+        plan->options[name] = int64_t(v);
+    }
+    return CONSTSTN_OK;
+}
+
+conststn_status conststn_plan_options(const char *schedule, const int *fusion, int n_operands,
+                                      const conststn_operand_desc *operands, unsigned flags,
+                                      const char *options, conststn_plan_t **out) {
     clear_error();
     if (!out) { set_error("out is null"); return CONSTSTN_EINVAL; }
     *out = nullptr;
@@ -385,6 +414,14 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
     struct Guard { conststn_plan_s *p; ~Guard() { delete p; } } guard{plan};
     plan->flags = flags;
     plan->compact = (flags & CONSTSTN_OUT_COMPACT) != 0;
+    CST_TRY(parse_plan_options(options, plan));
+    {
+        int dev = 0;
+        CST_HIP(hipGetDevice(&dev));
+        CST_HIP(hipDeviceGetAttribute(&plan->n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const int64_t qn = plan->opt("ttmc3_qn", 2);
+        plan->ttmc3_qn = (qn == 1 || qn == 2 || qn == 4) ? int(qn) : 2;
+    }
     CST_TRY(parse_schedule(schedule, plan->sched));
     CST_TRY(validate_schedule(plan->sched, fusion, n_operands, operands));
     for (const auto &o : plan->sched.operands)
@@ -414,7 +451,7 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
     // tuned kernels have rank limits; beyond them, and for every other tree over one CSF operand,
     // the generic executor takes over
     if (st == CONSTSTN_OK && !tuned_kernel_fits(plan)) st = CONSTSTN_EUNSUPPORTED;
-    if (st == CONSTSTN_OK && env_int("CONSTSTN_FORCE_GENERIC", 0) == 1 && plan->family != FAM_SPTN3 &&
+    if (st == CONSTSTN_OK && plan->opt("force_generic", 0) == 1 && plan->family != FAM_SPTN3 &&
         plan->family != FAM_SPCHAIN3 && plan->family != FAM_SPPAIR4)
         st = CONSTSTN_EUNSUPPORTED;
     if (st == CONSTSTN_EUNSUPPORTED) {

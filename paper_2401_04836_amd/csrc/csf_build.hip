@@ -207,6 +207,40 @@ radix_scatter_kernel(int64_t n, const uint64_t *__restrict__ keys_in, const uint
     }
 }
 
+// Sorts n (key, payload) pairs by the low `bits` bits of the key, stably; a and b are two buffers of n
+// entries each, the input is in a, the result in whichever *keys_sorted / *pay_sorted name.  Waits
+// for the stream before it returns (the pass tables are released then).
+conststn_status radix_sort_pairs_u64(uint64_t *keys_a, uint64_t *keys_b, uint32_t *pay_a, uint32_t *pay_b, int64_t n,
+                                     int bits, hipStream_t stream, const uint64_t **keys_sorted,
+                                     const uint32_t **pay_sorted) {
+    *keys_sorted = keys_a;
+    *pay_sorted = pay_a;
+    if (bits <= 0 || n <= 1) return CONSTSTN_OK;
+    const int64_t stiles = div_up(n, kSortTile);
+    DevBuf<unsigned> scounts;
+    DevBuf<int64_t> soffsets, stotals, sbases;
+    CST_TRY(scounts.alloc(size_t(stiles) * 256));
+    CST_TRY(soffsets.alloc(size_t(stiles) * 256));
+    CST_TRY(stotals.alloc(256));
+    CST_TRY(sbases.alloc(256));
+    uint64_t *kin = keys_a, *kout = keys_b;
+    uint32_t *pin = pay_a, *pout = pay_b;
+    const dim3 sgrid(unsigned(div_up(stiles, 4))), sblock(256);
+    for (int shift = 0; shift < bits; shift += 8) {
+        radix_count_kernel<<<sgrid, sblock, 0, stream>>>(n, kin, shift, scounts.p, stiles);
+        scan_tiles_kernel<<<dim3(256), dim3(1024), 0, stream>>>(scounts.p, soffsets.p, stiles, stotals.p);
+        radix_bases_kernel<<<dim3(1), dim3(64), 0, stream>>>(stotals.p, sbases.p);
+        radix_scatter_kernel<<<sgrid, sblock, 0, stream>>>(n, kin, pin, kout, pout, shift, soffsets.p, sbases.p, stiles);
+        CST_HIP(hipGetLastError());
+        std::swap(kin, kout);
+        std::swap(pin, pout);
+    }
+    CST_HIP(hipStreamSynchronize(stream));
+    *keys_sorted = kin;
+    *pay_sorted = pin;
+    return CONSTSTN_OK;
+}
+
 __device__ __forceinline__ unsigned block_exclusive_scan(unsigned v, unsigned *wtot /*[4]*/) {
     const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
     unsigned inc = v;
@@ -352,31 +386,7 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
 
     const uint64_t *skeys = keys_a.p;
     const uint32_t *spay = pay_a.p;
-    if (total_bits > 0 && nnz > 1) {
-        const int64_t stiles = div_up(nnz, kSortTile);
-        DevBuf<unsigned> scounts;
-        DevBuf<int64_t> soffsets, stotals, sbases;
-        CST_TRY(scounts.alloc(size_t(stiles) * 256));
-        CST_TRY(soffsets.alloc(size_t(stiles) * 256));
-        CST_TRY(stotals.alloc(256));
-        CST_TRY(sbases.alloc(256));
-        uint64_t *kin = keys_a.p, *kout = keys_b.p;
-        uint32_t *pin = pay_a.p, *pout = pay_b.p;
-        const dim3 sgrid(unsigned(div_up(stiles, 4))), sblock(256);
-        for (int shift = 0; shift < total_bits; shift += 8) {
-            radix_count_kernel<<<sgrid, sblock, 0, stream>>>(nnz, kin, shift, scounts.p, stiles);
-            scan_tiles_kernel<<<dim3(256), dim3(1024), 0, stream>>>(scounts.p, soffsets.p, stiles, stotals.p);
-            radix_bases_kernel<<<dim3(1), dim3(64), 0, stream>>>(stotals.p, sbases.p);
-            radix_scatter_kernel<<<sgrid, sblock, 0, stream>>>(nnz, kin, pin, kout, pout, shift, soffsets.p,
-                                                             sbases.p, stiles);
-            CST_HIP(hipGetLastError());
-            std::swap(kin, kout);
-            std::swap(pin, pout);
-        }
-        CST_HIP(hipStreamSynchronize(stream));      // the pass tables are released at scope exit
-        skeys = kin;
-        spay = pin;
-    }
+    CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, total_bits, stream, &skeys, &spay));
 
     const int64_t ntiles = div_up(nnz, kTile);
     DevBuf<unsigned> tile_counts;

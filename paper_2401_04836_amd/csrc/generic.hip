@@ -310,7 +310,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
 
     // one thread summing a whole subtree is fine for short fibers and hopeless for a power-law slice:
     // beyond span_limit nodes below one result node the sum is cut into segments (two passes)
-    const int64_t span_limit = env_int("CONSTSTN_GENERIC_SPAN", 4096);
+    const int64_t span_limit = plan->opt("generic_span", 4096);
     std::map<std::pair<int, int>, int64_t> span_cache;
     conststn_status span_status = CONSTSTN_OK;
     auto max_span = [&](int d_out, int d_in) -> int64_t {
@@ -515,7 +515,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
     // intermediates, held whole
     int64_t total = 0;
     for (int64_t e : buffer_elems) total += e;
-    const int64_t cap = env_int("CONSTSTN_GENERIC_MAX_GB", 64) << 27;      // doubles
+    const int64_t cap = plan->opt("generic_max_gb", 64) << 27;      // doubles
     if (total > cap) {
         set_error("the generic executor would hold %.1f GB of intermediates (limit %lld GB)", double(total) * 8e-9,
                   (long long)(cap >> 27));

@@ -247,7 +247,7 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
             return make_double2(src->x, src->y);
         };
         auto fetch_cold = [&](uint32_t cd) -> double2 {
-            double2 r;                                  // only read where the condition holds
+            double2 r = make_double2(0.0, 0.0);        // only used where the condition holds
             if (MODE == 1) return make_double2(0.0, 0.0);
             if (MODE == 2) return Cv[(cd & kRowMask) * 16u + uint32_t(gl)];
             if (!(cd & kHotBit)) r = Cv[(cd & kRowMask) * 16u + uint32_t(gl)];
@@ -260,7 +260,7 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
         };
         // B row of the fiber that ends at this leaf (no load when the leaf ends no fiber)
         auto fetch_b = [&](uint32_t cd, int32_t j) -> double2 {
-            double2 r;                                  // only read where the condition holds
+            double2 r = make_double2(0.0, 0.0);        // only used where the condition holds
             if (cd & kFiberEnd) r = Bv[uint32_t(j) * 16u + uint32_t(gl)];
             return r;
         };
@@ -476,6 +476,18 @@ static conststn_status launch_lpr(const conststn_plan_s *plan, const MttkrpArgs 
     return launch_fixup<LPR>(a, stream);
 }
 
+// The rank-32 kernels keep the hot factor rows in LDS (256 B per row): the dynamic-LDS limit of the two
+// forms that use them is raised when the plan is built.
+conststn_status prepare_mttkrp3_launch(conststn_plan_s *plan) {
+    if (plan->n_hot <= 0) return CONSTSTN_OK;
+    const int lds = plan->n_hot * 256;
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    return CONSTSTN_OK;
+}
+
 conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const *dense, double *out,
                                hipStream_t stream) {
     const conststn_csf_s *X = plan->X;
@@ -510,9 +522,7 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
                          (reinterpret_cast<uintptr_t>(out) % 16 == 0);
     if (R > 128) { set_error("MTTKRP rank %d above 128 is not implemented", R); return CONSTSTN_EUNSUPPORTED; }
     if (R == 32 && aligned && plan->n_hot > 0 && plan->leaf_code.p) {
-        int dev = 0, cus = 256;
-        CST_HIP(hipGetDevice(&dev));
-        CST_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const int cus = plan->n_cus;
         const size_t lds = size_t(plan->n_hot) * 256;
         auto run = [&](const MttkrpR32Args &aa, int mode) -> conststn_status {
             const size_t l = mode == 2 ? 0 : lds;
@@ -520,12 +530,8 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
             const int64_t wgs = std::min<int64_t>(div_up(aa.base.n_chunks, 32), int64_t(cus) * per_cu);
             const dim3 grid(unsigned(std::max<int64_t>(wgs, 1))), block(512);
             if (mode == 0) {
-                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 0>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(l)));
                 mttkrp3_r32_kernel<512, 0><<<grid, block, l, stream>>>(aa);
             } else if (mode == 1) {
-                CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 1>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(l)));
                 mttkrp3_r32_kernel<512, 1><<<grid, block, l, stream>>>(aa);
             } else {
                 mttkrp3_r32_kernel<512, 2><<<grid, block, 0, stream>>>(aa);

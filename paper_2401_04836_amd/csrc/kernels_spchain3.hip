@@ -966,12 +966,12 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
         at = up16(at + 2 * n_m); o_umap = at;
         at = up16(at + 4 * ((n_u + 1) / 2));
         const int64_t bytes = at;
-        const int64_t budget = env_int("CONSTSTN_SPCHAIN3_LOCAL_KB", 78) * 1024;      // two workgroups per compute unit
+        const int64_t budget = plan->opt("spchain3_local_kb", 78) * 1024;      // two workgroups per compute unit
         const bool offsets_fit = I->nnz < (int64_t(1) << 31) && C->nnz < (int64_t(1) << 31) && nnz < (int64_t(1) << 31);
         // a node holds each m of its K at most once, so nm_max also bounds the leaves of a node (16-bit positions)
         // (pk < 2^29: the kernel reaches into a block P_K with 32-bit byte offsets)
         if (rows_max <= 65534 && nm_max <= 65534 && pk < (int64_t(1) << 29) && offsets_fit && bytes <= budget && bytes <= 160 * 1024 &&
-            env_int("CONSTSTN_SPCHAIN3_FORM", 1) == 1) {
+            plan->opt("spchain3_form", 1) == 1) {
             ScArgs A2 = make_args(plan);
             // the dense blocks P_K, one per run of K with the same v and m lists
             DevBuf<int64_t> cflag, celems, coff;
@@ -982,7 +982,7 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
             CST_HIP(hipGetLastError());
             int64_t pk_total = 0;
             CST_TRY(exscan(celems.p, coff.p, roots, &pk_total));
-            const int64_t pk_cap = env_int("CONSTSTN_SPCHAIN3_PK_GB", 4) << 27;       // doubles
+            const int64_t pk_cap = plan->opt("spchain3_pk_gb", 4) << 27;       // doubles
             if (pk_total <= pk_cap) {
                 CST_TRY(plan->sc_pk_blocks.alloc(size_t(pk_total)));
                 CST_TRY(zero_fill(plan->sc_pk_blocks.p, pk_total, st));

@@ -647,7 +647,7 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     // Two chunk buffers per matrix overlap the fetch of a chunk with the pass over the one before.  One
     // buffer and a second barrier per chunk (CONSTSTN_SPPAIR4_BUFFERS=1) halve the LDS, which at the
     // lattice workload lets two workgroups share a CU, but measured 5 % slower there.
-    plan->p4_nbuf = env_int("CONSTSTN_SPPAIR4_BUFFERS", 2) == 1 ? 1 : 2;
+    plan->p4_nbuf = plan->opt("sppair4_buffers", 2) == 1 ? 1 : 2;
     L.achunk = int(at); at = up16(at + plan->p4_nbuf * 8 * int64_t(kP4Chunk) * plan->p4_mp);
     L.bchunk = int(at); at = up16(at + plan->p4_nbuf * 8 * int64_t(kP4Chunk) * plan->p4_np);
     L.total = int(at);
@@ -697,8 +697,8 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     }
     // shared K lists and bit matrices are kept for the numeric pass when they are of modest size
     const int64_t mask_words = pairs * int64_t(plan->p4_max_ua) * plan->p4_words;
-    plan->p4_stored = (mask_words * 4 + total_k * 24) <= (env_int("CONSTSTN_SPPAIR4_KEEP_GB", 4) << 30) &&
-                      env_int("CONSTSTN_SPPAIR4_KEEP", 1) == 1;
+    plan->p4_stored = (mask_words * 4 + total_k * 24) <= (plan->opt("sppair4_keep_gb", 4) << 30) &&
+                      plan->opt("sppair4_keep", 1) == 1;
     if (plan->p4_stored) {
         CST_TRY(plan->p4_k_ptr.alloc(size_t(pairs + 1)));
         CST_TRY(plan->p4_k_a.alloc(size_t(total_k)));
@@ -712,11 +712,11 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     // rows of its chunk matrices instead of putting them together leaf by leaf; a wavefront holds a row of
     // at most 256 in registers while it is in flight.
     plan->p4_dense = false;
-    if (plan->p4_stored && max_ua <= 256 && max_ub <= 256 && env_int("CONSTSTN_SPPAIR4_ROWS", 1) == 1) {
+    if (plan->p4_stored && max_ua <= 256 && max_ub <= 256 && plan->opt("sppair4_rows", 1) == 1) {
         int64_t ea = 0, eb = 0;
         CST_TRY(p4_dense_places(A.a, Ea->nodes[1], plan->p4_row_at_a, &ea));
         if (Eb != Ea) CST_TRY(p4_dense_places(A.b, Eb->nodes[1], plan->p4_row_at_b, &eb));
-        if ((ea + eb) * 8 <= (env_int("CONSTSTN_SPPAIR4_ROWS_GB", 8) << 30)) {
+        if ((ea + eb) * 8 <= (plan->opt("sppair4_rows_gb", 8) << 30)) {
             CST_TRY(plan->p4_dense_a.alloc(size_t(std::max<int64_t>(ea, 1))));
             if (Eb != Ea) CST_TRY(plan->p4_dense_b.alloc(size_t(std::max<int64_t>(eb, 1))));
             plan->p4_dense = true;
@@ -756,7 +756,7 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     CST_HIP(hipStreamSynchronize(st));
     // workgroup order of the numeric pass (pairs < 2^31: a pair holds at least one of the nnz < 2^31 leaves)
     plan->p4_n_wg = 0;
-    if (pairs > 0 && env_int("CONSTSTN_SPPAIR4_XCD", 1) == 1) {
+    if (pairs > 0 && plan->opt("sppair4_xcd", 1) == 1) {
         DevBuf<int64_t> xflag, xrank;
         CST_TRY(xflag.alloc(size_t(pairs)));
         CST_TRY(xrank.alloc(size_t(pairs)));

@@ -847,27 +847,15 @@ static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const dou
     a.out = out;
     a.partial = plan->partial.p;
     a.compact = plan->compact ? 1 : 0;
-    a.xcd_ranges = env_int("CONSTSTN_SPTN3_XCD", 0) == 1 ? 1 : 0;      // measured: halves the HBM fetch, 4 % slower
+    a.xcd_ranges = plan->sp_xcd_ranges ? 1 : 0;      // measured: halves the HBM fetch, 4 % slower
     const size_t lds_bytes = size_t(kCap) * 16 * 8 + size_t(4 * kStage) * 256 * 8 + size_t(a.MT) * 256 * 8 +
                              size_t(kCap) * 4 + size_t(a.nwords) * 8 + 64;
-    static bool attr_set = false;
-    if (!attr_set) {
-        CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sptn3_tiled_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
-    }
     if (!plan->compact && a.slices < plan->out_rows)
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     if (a.slices == 0) return CONSTSTN_OK;
     // two wavefronts per SIMD (m tiles owned by wavefronts) when the plan chose it, else one (l tiles owned)
     const size_t lds_owned = sptn3_owned_lds(a.nwords);
     const bool owned = plan->sp_two_waves;
-    static bool attr_owned = false;
-    if (owned && !attr_owned) {
-        CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sptn3_owned_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_owned = true;
-    }
     {
         ProfScope prof(plan, stream);
         const unsigned n_wg = unsigned(a.n_groups) * unsigned(a.n_kc);
@@ -881,6 +869,16 @@ static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const dou
             a.slices, a.M, a.n_kc, a.uidx0, a.partial, out, a.compact);
         CST_HIP(hipGetLastError());
     }
+    return CONSTSTN_OK;
+}
+
+// Both tiled kernels take up to the whole 160 KB of a CU's LDS: the limit is raised when the plan is built.
+conststn_status prepare_sptn3_launch(conststn_plan_s *plan) {
+    plan->sp_xcd_ranges = plan->opt("sptn3_xcd", 0) == 1;
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sptn3_tiled_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sptn3_owned_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     return CONSTSTN_OK;
 }
 

@@ -539,8 +539,7 @@ static conststn_status launch_mfma_pn(const conststn_plan_s *plan, const Ttmc3Ro
     ProfScope prof(plan, stream);
     const dim3 grid(unsigned(a.n_items));
     // column tiles per wavefront: two where R3 allows it (vector accesses need the alignment)
-    int qn = int(env_int("CONSTSTN_TTMC3_QN", 2));
-    if (qn != 1 && qn != 2 && qn != 4) qn = 2;
+    int qn = plan->ttmc3_qn;
     while (qn > 1 && (qt % qn != 0 ||
                       (reinterpret_cast<uintptr_t>(a.U3) | reinterpret_cast<uintptr_t>(a.out) |
                        reinterpret_cast<uintptr_t>(a.partial)) % (8u * unsigned(qn)) != 0))

@@ -9,7 +9,6 @@
 //     size; a slice made of several items is summed from partial row blocks by a fix-up pass.
 #include <cstring>
 #include <algorithm>
-#include <rocprim/rocprim.hpp>
 
 #include <cstdlib>
 
@@ -17,12 +16,18 @@
 
 namespace cst {
 
-int64_t env_int(const char *name, int64_t dflt) {
-    const char *v = std::getenv(name);
-    if (!v || !*v) return dflt;
-    char *end = nullptr;
-    long long x = std::strtoll(v, &end, 10);
-    return (end && *end == 0 && x > 0) ? int64_t(x) : dflt;
+bool known_plan_option(const std::string &name) {
+    static const char *const names[] = {
+        "force_generic", "generic_max_gb", "generic_span",
+        "mttkrp_split", "mttkrp_hot", "mttkrp_chunk",
+        "ttmc3_mfma", "ttmc3_stream", "ttmc3_producers", "ttmc3_batch", "ttmc3_itemcost", "ttmc3_qn", "ttmc3_split",
+        "ttmc3_rowsplit", "ttmc4_mfma", "ttmc4_split", "ttmc4_ksplit",
+        "sptn3_tiled", "sptn3_waves", "sptn3_wgs", "sptn3_xcd",
+        "spchain3_form", "spchain3_local_kb", "spchain3_pk_gb",
+        "sppair4_keep", "sppair4_keep_gb", "sppair4_rows", "sppair4_rows_gb", "sppair4_buffers", "sppair4_xcd"};
+    for (const char *n : names)
+        if (name == n) return true;
+    return false;
 }
 
 __global__ void zero_fill_kernel(double *p, int64_t n) {
@@ -134,14 +139,19 @@ __global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
     if (i < n) p[i] = v;
 }
 
-__global__ void hot_slots_kernel(int n_hot, const int32_t *__restrict__ rows_by_count,
-                                 const unsigned *__restrict__ counts_sorted, int32_t *slot_of_row,
+__global__ void rank_keys_kernel(int64_t n, const unsigned *__restrict__ counts, uint64_t *keys, uint32_t *rows) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    keys[i] = uint64_t(0xffffffffu - counts[i]);
+    rows[i] = uint32_t(i);
+}
+
+__global__ void hot_slots_kernel(int n_hot, const uint32_t *__restrict__ rows_by_count, int32_t *slot_of_row,
                                  int32_t *hot_rows) {
     const int h = blockIdx.x * blockDim.x + threadIdx.x;
     if (h >= n_hot) return;
-    hot_rows[h] = rows_by_count[h];
+    hot_rows[h] = int32_t(rows_by_count[h]);
     slot_of_row[rows_by_count[h]] = h;
-    (void)counts_sorted;
 }
 
 __global__ void encode_leaves_kernel(int64_t nnz, const int32_t *__restrict__ leaf,
@@ -329,15 +339,18 @@ static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
     if (plan->rank_of_level[1] != 32 || dim >= (int64_t(1) << 28) || nnz == 0 ||
         X->dims[X->mode_order[1]] >= (int64_t(1) << 28))
         return CONSTSTN_OK;                               // the kernel indexes factor rows with 32 bits
-    int64_t want = env_int("CONSTSTN_MTTKRP_HOT", 256);
+    int64_t want = plan->opt("mttkrp_hot", 256);
     if (want > dim) want = dim;
     want = std::min<int64_t>(want, 608);                 // 608 rows x 256 B = 152 KB of LDS at most
-    DevBuf<unsigned> counts, counts_sorted;
-    DevBuf<int32_t> rows, rows_sorted, slot_of_row;
+    DevBuf<unsigned> counts;
+    DevBuf<int32_t> slot_of_row;
+    DevBuf<uint64_t> rank_key_a, rank_key_b;
+    DevBuf<uint32_t> rank_row_a, rank_row_b;
     CST_TRY(counts.alloc(dim));
-    CST_TRY(counts_sorted.alloc(dim));
-    CST_TRY(rows.alloc(dim));
-    CST_TRY(rows_sorted.alloc(dim));
+    CST_TRY(rank_key_a.alloc(dim));
+    CST_TRY(rank_key_b.alloc(dim));
+    CST_TRY(rank_row_a.alloc(dim));
+    CST_TRY(rank_row_b.alloc(dim));
     CST_TRY(slot_of_row.alloc(dim));
     CST_HIP(hipMemset(counts.p, 0, size_t(dim) * sizeof(unsigned)));
     const dim3 block(256);
@@ -349,17 +362,17 @@ static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
         leaf_histogram_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 8192))), block>>>(nnz, X->idx[2].p, counts.p);
     }
     CST_HIP(hipGetLastError());
-    iota_i32_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(rows.p, dim);
+    // rows by falling count: ascending stable sort on (2^32 - 1 - count), ties keep the lower row first
+    rank_keys_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(dim, counts.p, rank_key_a.p, rank_row_a.p);
     fill_i32_kernel<<<dim3(unsigned(div_up(dim, 256))), block>>>(slot_of_row.p, dim, -1);
     CST_HIP(hipGetLastError());
-    size_t bytes = 0;
-    CST_HIP(rocprim::radix_sort_pairs_desc(nullptr, bytes, counts.p, counts_sorted.p, rows.p, rows_sorted.p, size_t(dim)));
-    DevBuf<char> temp;
-    CST_TRY(temp.alloc(bytes));
-    CST_HIP(rocprim::radix_sort_pairs_desc(temp.p, bytes, counts.p, counts_sorted.p, rows.p, rows_sorted.p, size_t(dim)));
+    const uint64_t *keys_sorted = nullptr;
+    const uint32_t *rows_sorted = nullptr;
+    CST_TRY(radix_sort_pairs_u64(rank_key_a.p, rank_key_b.p, rank_row_a.p, rank_row_b.p, dim, 32, hipStream_t(0),
+                                 &keys_sorted, &rows_sorted));
     CST_TRY(plan->hot_rows.alloc(size_t(want)));
-    hot_slots_kernel<<<dim3(unsigned(div_up(want, 256))), block>>>(int(want), rows_sorted.p, counts_sorted.p,
-                                                                  slot_of_row.p, plan->hot_rows.p);
+    hot_slots_kernel<<<dim3(unsigned(div_up(want, 256))), block>>>(int(want), rows_sorted, slot_of_row.p,
+                                                                  plan->hot_rows.p);
     CST_HIP(hipGetLastError());
     CST_TRY(plan->leaf_code.alloc(size_t(nnz)));
     encode_leaves_kernel<<<dim3(unsigned(std::min<int64_t>(div_up(nnz, 256), 16384))), block>>>(
@@ -372,7 +385,7 @@ static conststn_status build_mttkrp3_r32_encoding(conststn_plan_s *plan) {
     CST_HIP(hipGetLastError());
     CST_HIP(hipDeviceSynchronize());
     plan->n_hot = int(want);
-    if (env_int("CONSTSTN_MTTKRP_SPLIT", 1) == 1) CST_TRY(build_mttkrp3_split(plan, slot_of_row.p));
+    if (plan->opt("mttkrp_split", 1) == 1) CST_TRY(build_mttkrp3_split(plan, slot_of_row.p));
     return CONSTSTN_OK;
 }
 
@@ -383,7 +396,7 @@ conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
     CST_TRY(make_slice_leaf(plan));
     // chunk length: short enough for >= ~64K independent lane groups, long enough that the
     // two partial rows per chunk stay a small fraction of the traffic
-    int64_t q = env_int("CONSTSTN_MTTKRP_CHUNK", 0);
+    int64_t q = plan->opt("mttkrp_chunk", 0);
     if (q <= 0) {
         q = nnz / 262144;
         q = std::max<int64_t>(64, std::min<int64_t>(q, 512));
@@ -415,7 +428,8 @@ conststn_status build_mttkrp3_tables(conststn_plan_s *plan) {
     CST_HIP(hipMemcpy(&plan->n_heavy, hcount.p, sizeof(int), hipMemcpyDeviceToHost));
     CST_TRY(plan->heavy_partial.alloc(size_t(plan->n_heavy) * kHeavySegments * size_t(R)));
     CST_HIP(hipDeviceSynchronize());
-    return build_mttkrp3_r32_encoding(plan);
+    CST_TRY(build_mttkrp3_r32_encoding(plan));
+    return prepare_mttkrp3_launch(plan);
 }
 
 // ---- TTMc: bounded items inside slices ----------------------------------------------------
@@ -461,14 +475,63 @@ __global__ void ttmc_fill_kernel(int64_t slices, const int64_t *__restrict__ uni
     }
 }
 
+// Exclusive prefix sum in three steps: every workgroup scans a tile of 2048 entries and reports its sum,
+// the tile sums are scanned (recursively, the same way), every tile adds its offset.
+constexpr int kScanTile = 2048;      // 256 threads x 8 entries
+
+__global__ void __launch_bounds__(256)
+scan_tile_kernel(const int64_t *in, int64_t *out, int64_t n, int64_t *tile_sums) {
+    __shared__ int64_t wave_sum[4];
+    const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * 8;
+    int64_t v[8], s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { v[i] = base + i < n ? in[base + i] : 0; s += v[i]; }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t inc = s;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    int64_t run = inc - s;
+    for (int w = 0; w < wave; ++w) run += wave_sum[w];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { if (base + i < n) out[base + i] = run; run += v[i]; }
+    if (threadIdx.x == 255) tile_sums[blockIdx.x] = run;
+}
+
+__global__ void __launch_bounds__(256)
+scan_add_kernel(int64_t *out, int64_t n, const int64_t *__restrict__ tile_offsets) {
+    const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * 8;
+    const int64_t off = tile_offsets[blockIdx.x];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (base + i < n) out[base + i] += off;
+}
+
+static conststn_status exscan_device(const int64_t *in, int64_t *out, int64_t n) {
+    const int64_t tiles = div_up(n, kScanTile);
+    DevBuf<int64_t> sums, offs;
+    CST_TRY(sums.alloc(size_t(tiles)));
+    scan_tile_kernel<<<dim3(unsigned(tiles)), dim3(256)>>>(in, out, n, sums.p);
+    CST_HIP(hipGetLastError());
+    if (tiles > 1) {
+        CST_TRY(offs.alloc(size_t(tiles)));
+        CST_TRY(exscan_device(sums.p, offs.p, tiles));
+        scan_add_kernel<<<dim3(unsigned(tiles)), dim3(256)>>>(out, n, offs.p);
+        CST_HIP(hipGetLastError());
+    }
+    CST_HIP(hipDeviceSynchronize());      // the tile tables are released on return
+    return CONSTSTN_OK;
+}
+
 conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host) {
-    size_t bytes = 0;
-    CST_HIP(rocprim::exclusive_scan(nullptr, bytes, in, out, int64_t(0), size_t(n), rocprim::plus<int64_t>(), hipStream_t(0)));
-    DevBuf<char> temp;
-    CST_TRY(temp.alloc(bytes));
-    CST_HIP(rocprim::exclusive_scan(temp.p, bytes, in, out, int64_t(0), size_t(n), rocprim::plus<int64_t>(), hipStream_t(0)));
+    if (n <= 0) { *total_host = 0; return CONSTSTN_OK; }
+    // the last input is read before the scan, so that in and out may be one array
     int64_t last_in = 0, last_out = 0;
     CST_HIP(hipMemcpy(&last_in, in + (n - 1), sizeof(int64_t), hipMemcpyDeviceToHost));
+    CST_TRY(exscan_device(in, out, n));
     CST_HIP(hipMemcpy(&last_out, out + (n - 1), sizeof(int64_t), hipMemcpyDeviceToHost));
     *total_host = last_in + last_out;
     return CONSTSTN_OK;
@@ -487,7 +550,7 @@ __global__ void fiber_rows_kernel(int64_t fibers, const int64_t *__restrict__ pt
 __global__ void fill_rows_kernel(int64_t fibers, int64_t slices, const int64_t *__restrict__ ptr0,
                                  const int64_t *__restrict__ ptr1, const int32_t *__restrict__ idx1,
                                  const int64_t *__restrict__ row_off, int64_t *row_leaf, int32_t *row_j,
-                                 int32_t *row_cnt, uint64_t *row_key, int32_t *row_id) {
+                                 int32_t *row_cnt, uint64_t *row_key, uint32_t *row_id) {
     const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (f >= fibers) return;
     int64_t lo = 0, hi = slices;                // slice of fiber f: last s with ptr0[s] <= f
@@ -503,16 +566,16 @@ __global__ void fill_rows_kernel(int64_t fibers, int64_t slices, const int64_t *
         row_j[r] = idx1[f];
         row_cnt[r] = cnt;
         row_key[r] = (uint64_t(lo) << 8) | uint64_t(kRowLeaves - cnt);
-        row_id[r] = int32_t(r);
+        row_id[r] = uint32_t(r);
     }
 }
 
-__global__ void permute_rows_kernel(int64_t rows, const int32_t *__restrict__ order,
+__global__ void permute_rows_kernel(int64_t rows, const uint32_t *__restrict__ order,
                                     const int64_t *__restrict__ leaf_in, const int32_t *__restrict__ j_in,
                                     const int32_t *__restrict__ cnt_in, RowDesc *out) {
     const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (r >= rows) return;
-    const int32_t src = order[r];
+    const uint32_t src = order[r];
     out[r] = RowDesc{leaf_in[src], cnt_in[src], j_in[src]};
 }
 
@@ -542,13 +605,14 @@ static conststn_status build_rows_core(int64_t slices, int64_t fibers, const int
     CST_TRY(slice_row.alloc(size_t(slices) + 1));
     {
         DevBuf<int64_t> leaf0;
-        DevBuf<int32_t> j0, cnt0, id0, order;
+        DevBuf<int32_t> j0, cnt0;
+        DevBuf<uint32_t> id0, id1;
         DevBuf<uint64_t> key0, key1;
         CST_TRY(leaf0.alloc(size_t(rows)));
         CST_TRY(j0.alloc(size_t(rows)));
         CST_TRY(cnt0.alloc(size_t(rows)));
         CST_TRY(id0.alloc(size_t(rows)));
-        CST_TRY(order.alloc(size_t(rows)));
+        CST_TRY(id1.alloc(size_t(rows)));
         CST_TRY(key0.alloc(size_t(rows)));
         CST_TRY(key1.alloc(size_t(rows)));
         fill_rows_kernel<<<dim3(unsigned(div_up(fibers, 256))), block>>>(
@@ -556,14 +620,12 @@ static conststn_status build_rows_core(int64_t slices, int64_t fibers, const int
         CST_HIP(hipGetLastError());
         if (rows > 0) {
             // stable sort by (slice, 16 - leaves): rows stay inside their slice, longest first
-            const unsigned end_bit = unsigned(8 + ceil_log2_u64(uint64_t(slices) + 1));
-            size_t bytes = 0;
-            CST_HIP(rocprim::radix_sort_pairs(nullptr, bytes, key0.p, key1.p, id0.p, order.p, size_t(rows), 0u, end_bit));
-            DevBuf<char> temp;
-            CST_TRY(temp.alloc(bytes));
-            CST_HIP(rocprim::radix_sort_pairs(temp.p, bytes, key0.p, key1.p, id0.p, order.p, size_t(rows), 0u, end_bit));
+            const int end_bit = 8 + ceil_log2_u64(uint64_t(slices) + 1);
+            const uint64_t *keys_sorted = nullptr;
+            const uint32_t *order = nullptr;
+            CST_TRY(radix_sort_pairs_u64(key0.p, key1.p, id0.p, id1.p, rows, end_bit, hipStream_t(0), &keys_sorted, &order));
             permute_rows_kernel<<<dim3(unsigned(div_up(rows, 256))), block>>>(
-                rows, order.p, leaf0.p, j0.p, cnt0.p, rows_out.p);
+                rows, order, leaf0.p, j0.p, cnt0.p, rows_out.p);
             CST_HIP(hipGetLastError());
         }
         CST_HIP(hipDeviceSynchronize());
@@ -806,8 +868,8 @@ static conststn_status build_stream_tables(conststn_plan_s *plan) {
     plan->n_ksteps = plan->n_stream_wg = 0;
     if (n_items == 0) return CONSTSTN_OK;
     // an item costs its K-steps plus the store of its row block
-    const int64_t item_cost = std::max<int64_t>(env_int("CONSTSTN_TTMC3_ITEMCOST", 2), 0);
-    const int64_t target = std::max<int64_t>(env_int("CONSTSTN_TTMC3_BATCH", 1024), 1);
+    const int64_t item_cost = std::max<int64_t>(plan->opt("ttmc3_itemcost", 2), 0);
+    const int64_t target = std::max<int64_t>(plan->opt("ttmc3_batch", 1024), 1);
     DevBuf<int64_t> ksteps_of, cost_of, kstep_off, cost_off;
     CST_TRY(ksteps_of.alloc(n_items));
     CST_TRY(cost_of.alloc(n_items));
@@ -843,17 +905,17 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     int order = X->order;
     // order 3 splits by leaves, order 4 by level-1 fibers (each carries a whole sub-tree)
     const int64_t *unit_ptr = order == 3 ? plan->slice_leaf.p : X->ptr[0].p;
-    int64_t split = order == 3 ? env_int("CONSTSTN_TTMC3_SPLIT", 4096) : env_int("CONSTSTN_TTMC4_SPLIT", 256);
+    int64_t split = order == 3 ? plan->opt("ttmc3_split", 4096) : plan->opt("ttmc4_split", 256);
     // ranks that are multiples of 16 take the MFMA kernel, whose items are ranges of rows
     plan->use_rows = order == 3 && plan->rank_of_level[1] % 16 == 0 && plan->rank_of_level[2] % 16 == 0 &&
                      plan->rank_of_level[1] <= 64 && plan->rank_of_level[2] <= 64 &&
-                     env_int("CONSTSTN_TTMC3_NO_MFMA", 0) == 0;
+                     plan->opt("ttmc3_mfma", 1) == 1;
     if (plan->use_rows) {
         CST_TRY(build_rows(plan));
         unit_ptr = plan->slice_row.p;
         // larger items mean fewer partial row blocks for the fix-up pass to add; keep at least
         // about 8192 items for the chip
-        split = env_int("CONSTSTN_TTMC3_ROWSPLIT", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 256), 2048));
+        split = plan->opt("ttmc3_rowsplit", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 256), 2048));
         order = 0;                                   // items carry no 'first fiber'
     }
     // (extents below 2^25: the matrix-core kernel reaches the factor rows with 32-bit byte offsets)
@@ -862,11 +924,11 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
                                               X4->dims[X4->mode_order[2]] < (int64_t(1) << 25) &&
                                               X4->dims[X4->mode_order[3]] < (int64_t(1) << 25));
     if (order == 4 && plan->rank_of_level[1] == 16 && plan->rank_of_level[2] == 16 && small_extents &&
-        plan->rank_of_level[3] == 16 && env_int("CONSTSTN_TTMC4_NO_MFMA", 0) == 0) {
+        plan->rank_of_level[3] == 16 && plan->opt("ttmc4_mfma", 1) == 1) {
         plan->use_rows = true;
         CST_TRY(build_piece_groups(plan));
         unit_ptr = plan->slice_row.p;                 // items are ranges of K-steps (four fibers each)
-        split = env_int("CONSTSTN_TTMC4_KSPLIT", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 64), 192));
+        split = plan->opt("ttmc4_ksplit", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 64), 192));
     }
     CST_TRY(build_items_core(slices, unit_ptr, split, 0, order, X->ptr[0].p, X->ptr[1].p, plan->row_elems,
                              plan->items, plan->n_items, plan->n_partials, plan->n_split, plan->split_slices,
@@ -875,9 +937,9 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     // streaming form of the order-3 matrix-core path: R3 of 32 or 64 (two column tiles per multiplying
     // wavefront), rows and output blocks reachable with the table's 32-bit fields
     plan->use_stream = X->order == 3 && plan->use_rows && (plan->rank_of_level[2] == 32 || plan->rank_of_level[2] == 64) &&
-                       env_int("CONSTSTN_TTMC3_STREAM", 1) == 1;
+                       plan->opt("ttmc3_stream", 1) == 1;
     if (plan->use_stream) {
-        int np = int(env_int("CONSTSTN_TTMC3_PRODUCERS", 4));
+        int np = int(plan->opt("ttmc3_producers", 4));
         plan->stream_producers = np == 2 || np == 6 || np == 8 ? np : 4;
         CST_TRY(build_stream_tables(plan));
     }
@@ -963,7 +1025,7 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     const int64_t L = W->dims[W->mode_order[1]], M = W->dims[W->mode_order[2]];
     const int64_t K = W->dims[W->mode_order[0]];
     plan->w_tiled = false;
-    if (env_int("CONSTSTN_SPTN3_TILED", 1) == 2) return CONSTSTN_OK;          // 2 = baseline kernel
+    if (plan->opt("sptn3_tiled", 1) == 0) return CONSTSTN_OK;          // 0 = baseline kernel
     if (M > 16 * kSpMaxMTiles || J > kSpMaxJ || J * L >= (int64_t(1) << 29) || W->nnz == 0 || U->nnz == 0)
         return CONSTSTN_OK;
     const int64_t roots = W->nodes[0], fibers = W->nodes[1];
@@ -983,6 +1045,15 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     int64_t n_tiles = 0;
     CST_TRY(exscan(cnt.p, first.p, cells, &n_tiles));
     if (n_tiles >= (int64_t(1) << 31) - 1) return CONSTSTN_OK;
+    // The dense tiles pay off when they are reasonably full.  A scattered W (about one nonzero per
+    // tile) would be blown up 256-fold: below one nonzero in sixteen cells, or when the tiles do not fit
+    // the free device memory, the baseline kernel (which needs no tiles) takes the plan instead.
+    size_t free_b = 0, total_b = 0;
+    CST_HIP(hipMemGetInfo(&free_b, &total_b));
+    if (plan->opt("sptn3_tiled", 1) != 2 && (n_tiles * 16 > W->nnz || size_t(n_tiles + 1) * 2048 > free_b / 2)) {
+        plan->w_tile_mask.release();
+        return CONSTSTN_OK;
+    }
     plan->n_w_tiles = n_tiles;
     // one more, all-zero tile at the end: the target of loads that have nothing to fetch
     CST_TRY(plan->w_tiles.alloc(size_t(n_tiles + 1) * 256));
@@ -996,14 +1067,14 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     CST_HIP(hipGetLastError());
     // slices go in groups of 16; the k range is cut into chunks so that the grid fills the chip
     const int64_t groups = div_up(U->nodes[0], kSpGroup);
-    int64_t want = env_int("CONSTSTN_SPTN3_WGS", 8000);
+    int64_t want = plan->opt("sptn3_wgs", 8000);
     int64_t n_kc = std::min<int64_t>(std::max<int64_t>(div_up(want, groups), 1), std::min<int64_t>(K, 64));
     plan->sp_k_per = div_up(K, n_kc);
     plan->sp_kc = int(div_up(K, plan->sp_k_per));
     if (plan->sp_kc > 1)
         CST_TRY(plan->partial.alloc(size_t(plan->sp_kc) * size_t(U->nodes[0]) * size_t(M)));
     plan->w_tiled = true;
-    plan->sp_two_waves = env_int("CONSTSTN_SPTN3_WAVES", 2) == 2 && sptn3_two_waves_fit(int((J + 31) / 32));
+    plan->sp_two_waves = plan->opt("sptn3_waves", 2) == 2 && sptn3_two_waves_fit(int((J + 31) / 32));
     return CONSTSTN_OK;
 }
 
@@ -1020,7 +1091,7 @@ conststn_status build_sptn3_tables(conststn_plan_s *plan) {
     }
     CST_TRY(build_w_tiles(plan));
     CST_HIP(hipDeviceSynchronize());
-    return CONSTSTN_OK;
+    return prepare_sptn3_launch(plan);
 }
 
 }  // namespace cst

@@ -2,6 +2,7 @@
 // work tables (load-balanced partition of the CSF tree) and scratch the kernels need.
 #pragma once
 
+#include <map>
 #include <memory>
 
 #include "common.hpp"
@@ -126,6 +127,14 @@ struct conststn_plan_s {
     cst::Family family = cst::FAM_NONE;
     unsigned flags = 0;
     std::string description;
+    // tuning options given to conststn_plan_options ("name=value,..."): read while the plan is built,
+    // never by an execute
+    std::map<std::string, int64_t> options;
+    int64_t opt(const char *name, int64_t dflt) const {
+        const auto it = options.find(name);
+        return it == options.end() ? dflt : it->second;
+    }
+    int n_cus = 256;                      // compute units of the device the plan was made on
 
     const conststn_csf_s *X = nullptr;    // the sparse operand walked by the fused loops
     const conststn_csf_s *W = nullptr;    // second sparse operand (three-tensor network only)
@@ -168,6 +177,7 @@ struct conststn_plan_s {
     cst::DevBuf<int64_t> slice_row;        // [slices+1] first row of each slice
     // streaming form of that path: the K-steps of all items as one flat table, and the first K-step of
     // the batch of whole items each workgroup walks
+    int ttmc3_qn = 2;                      // column tiles per wavefront of the one-wavefront-per-item kernel
     bool use_stream = false;
     int stream_producers = 4;              // wavefronts of a workgroup that gather (the others multiply and store)
     int64_t n_ksteps = 0, n_stream_wg = 0;
@@ -187,6 +197,7 @@ struct conststn_plan_s {
     cst::DevBuf<uint32_t> w_tile_mask;     // [roots x ceil(L/16)] m tiles present
     cst::DevBuf<uint32_t> w_tile_first;    // [roots x ceil(L/16)] index of the first of them
     cst::DevBuf<double> w_tiles;           // [(tiles + 1) x 256], the last one all zero
+    bool sp_xcd_ranges = false;            // contiguous workgroup ranges per XCD
     int sp_kc = 1;                         // chunks of the k range (one workgroup per group and chunk)
     int64_t sp_k_per = 0;                  // k values per chunk
 
@@ -291,6 +302,11 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
                                  const int *mode_order, unsigned flags, hipStream_t stream,
                                  conststn_csf_s *csf);
 
+// stable radix sort of (64-bit key, 32-bit payload) pairs by the low `bits` key bits (csf_build.hip)
+conststn_status radix_sort_pairs_u64(uint64_t *keys_a, uint64_t *keys_b, uint32_t *pay_a, uint32_t *pay_b, int64_t n,
+                                     int bits, hipStream_t stream, const uint64_t **keys_sorted,
+                                     const uint32_t **pay_sorted);
+
 // exclusive prefix sum of n int64 on the default stream; *total_host = sum of all inputs
 conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
 
@@ -326,7 +342,10 @@ struct ProfScope {
     }
 };
 
-// tuning knob read from the environment (0 = use the built-in choice)
-int64_t env_int(const char *name, int64_t dflt);
+// names conststn_plan_options accepts
+bool known_plan_option(const std::string &name);
+// kernels with more dynamic LDS than the default limit: raised once per plan build
+conststn_status prepare_mttkrp3_launch(conststn_plan_s *plan);
+conststn_status prepare_sptn3_launch(conststn_plan_s *plan);
 
 }  // namespace cst

@@ -28,7 +28,7 @@ def check_csf_bit_exact(csf, coo_np, vals_np, dims, mode_order):
             assert np.array_equal(gv.cpu().numpy().view(np.int64), v.view(np.int64)), "vals differ"
 
 
-def run_gpu(wl, flags=0, check_csf=False):
+def run_gpu(wl, flags=0, check_csf=False, options=None):
     """Build CSF(s), plan, execute.  Returns (out tensor [rows, ...], plan, csf handles)."""
     dev = "cuda"
     if wl.kind in ("ttmc3", "ttmc4", "mttkrp3"):
@@ -40,17 +40,17 @@ def run_gpu(wl, flags=0, check_csf=False):
             check_csf_bit_exact(csf, c, v, X.dims, list(range(X.order)))
         if wl.kind == "ttmc3":
             U2, U3 = wl.dense["U2"].to(dev), wl.dense["U3"].to(dev)
-            pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags)
+            pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags, options=options)
             out = cst.execute(pl, [U3, U2])
             shape = (pl.n_rows, U2.shape[1], U3.shape[1])
         elif wl.kind == "ttmc4":
             U1, U2, U3 = (wl.dense[k].to(dev) for k in ("U1", "U2", "U3"))
-            pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)], flags=flags)
+            pl = cst.plan(S.TTMC4, [("X", csf), ("U3", U3), ("U2", U2), ("U1", U1)], flags=flags, options=options)
             out = cst.execute(pl, [U3, U2, U1])
             shape = (pl.n_rows, U1.shape[1], U2.shape[1], U3.shape[1])
         else:
             B, C = wl.dense["B"].to(dev), wl.dense["C"].to(dev)
-            pl = cst.plan(S.MTTKRP3, [("X", csf), ("C", C), ("B", B)], flags=flags)
+            pl = cst.plan(S.MTTKRP3, [("X", csf), ("C", C), ("B", B)], flags=flags, options=options)
             out = cst.execute(pl, [C, B])
             shape = (pl.n_rows, B.shape[1])
         torch.cuda.synchronize()
@@ -67,7 +67,7 @@ def run_gpu(wl, flags=0, check_csf=False):
             c, v = W.numpy()
             check_csf_bit_exact(wcsf, c, v, W.dims, [0, 1, 2])
         V = wl.dense["V"].to(dev)
-        pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)], flags=flags)
+        pl = cst.plan(S.SPTN3, [("U", ucsf), ("V", V), ("W", wcsf)], flags=flags, options=options)
         out = cst.execute(pl, [V])
         torch.cuda.synchronize()
         return out.reshape(pl.n_rows, W.dims[2]), pl, [ucsf, wcsf]

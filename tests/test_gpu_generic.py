@@ -1,7 +1,6 @@
 """Generic executor (any contraction tree over one CSF tensor, Sec. 2.2 / 4.2) on the GPU against
 the N-ary reference: orders and ranks beyond the tuned kernels, other trees over the same
 network, every fusion choice, a fully contracted result, and what it must refuse."""
-import os
 
 import numpy as np
 import pytest
@@ -37,12 +36,12 @@ def _dense(seed, *shape):
     return torch.rand(*shape, generator=g, dtype=torch.float64) * 2 - 1
 
 
-def _run(text, x, mode_order, dense, out_shape, fusion=None, flags=0, expect="generic"):
+def _run(text, x, mode_order, dense, out_shape, fusion=None, flags=0, expect="generic", options=None):
     """x = (coords, vals, dims); dense = [(name, tensor)] in operand order.  Returns a CPU array."""
     coords, vals, dims = x
     csf = cst.build_csf([c.cuda() for c in coords], vals.cuda(), dims, mode_order)
     dev = [(n, t.cuda()) for n, t in dense]
-    pl = cst.plan(text, [("X", csf)] + dev, fusion=fusion, flags=flags)
+    pl = cst.plan(text, [("X", csf)] + dev, fusion=fusion, flags=flags, options=options)
     desc = pl.describe()
     _say("  " + desc.split("|")[0])
     assert ("family=" + expect) in desc, desc
@@ -148,14 +147,10 @@ def test_generic_matches_tuned_kernels_and_compact_rows():
     B, C = _dense(352, 40, 32), _dense(353, 30, 32)
     text = "T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[i,r] = T[i,j,r] * B[j,r] | i,j,r"
     tuned, _ = _run(text, (coords, vals, dims), [0, 1, 2], [("C", C), ("B", B)], (64, 32), expect="mttkrp3")
-    os.environ["CONSTSTN_FORCE_GENERIC"] = "1"
-    try:
-        gen, _ = _run(text, (coords, vals, dims), [0, 1, 2], [("C", C), ("B", B)], (64, 32))
-        nrows = int(np.unique(coords[0].numpy()).size)
-        comp, pl = _run(text, (coords, vals, dims), [0, 1, 2], [("C", C), ("B", B)], (nrows, 32),
-                        flags=cst.OUT_COMPACT)
-    finally:
-        del os.environ["CONSTSTN_FORCE_GENERIC"]
+    gen, _ = _run(text, (coords, vals, dims), [0, 1, 2], [("C", C), ("B", B)], (64, 32), options="force_generic=1")
+    nrows = int(np.unique(coords[0].numpy()).size)
+    comp, pl = _run(text, (coords, vals, dims), [0, 1, 2], [("C", C), ("B", B)], (nrows, 32),
+                    flags=cst.OUT_COMPACT, options="force_generic=1")
     _check(gen, coords, vals, "ijk", [(B, "jr"), (C, "kr")], "ir", {"i": 64, "r": 32})
     _check(tuned, coords, vals, "ijk", [(B, "jr"), (C, "kr")], "ir", {"i": 64, "r": 32})
     assert not gen[1::2].any()                          # odd rows: no nonzeros, exact zeros
@@ -216,10 +211,6 @@ def test_generic_refuses_what_it_cannot_store():
     csf = cst.build_csf([c.cuda() for c in coords], vals.cuda(), dims, [0, 1, 2])
     B, C = _dense(362, 4000, 16).cuda(), _dense(363, 4000, 16).cuda()
     text = "P[j,k,r] = B[j,r] * C[k,r] | j,k,r ; M[i,r] = X[i,j,k] * P[j,k,r] | i,j,k,r"
-    os.environ["CONSTSTN_GENERIC_MAX_GB"] = "1"
-    try:
-        with pytest.raises(cst.ConststnError) as e:
-            cst.plan(text, [("X", csf), ("B", B), ("C", C)])
-        assert "intermediates" in str(e.value)
-    finally:
-        del os.environ["CONSTSTN_GENERIC_MAX_GB"]
+    with pytest.raises(cst.ConststnError) as e:
+        cst.plan(text, [("X", csf), ("B", B), ("C", C)], options={"generic_max_gb": 1})
+    assert "intermediates" in str(e.value)

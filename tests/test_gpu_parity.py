@@ -93,7 +93,7 @@ def test_config1_full_size():
     assert compare(out, want, S_abs) <= TOL
 
 
-@pytest.mark.parametrize("cid", [1, 5])
+@pytest.mark.parametrize("cid", [1, 2, 3, 5])
 def test_compact_output(cid):
     _say("compact output config %d" % cid)
     wl = w.make(cid, small=True)
@@ -102,6 +102,37 @@ def test_compact_output(cid):
     want, S_abs = run_oracle(wl)
     assert rows.numel() == pl.n_rows and bool((rows[1:] > rows[:-1]).all())
     assert compare(out, want, S_abs, rows=rows) <= TOL
+
+
+@pytest.mark.parametrize("rank", [32, 20])
+def test_mttkrp_compact_rows_with_empty_and_heavy_slices(rank):
+    """Rank 32 takes the kernels that split the leaves into hot and cold sub-tensors (rows of the output
+    renumbered per sub-tensor); 4001 root indices for 40 003 power-law nonzeros leave most slices empty
+    and put a fifth of the leaves into one."""
+    _say("mttkrp rank %d, compact rows, empty and heavy slices" % rank)
+    wl = w.make(2, small=True, dims=(4001, 211, 503), nnz=40_003, rank=rank)
+    out, pl, _ = run_gpu(wl, flags=cst.OUT_COMPACT)
+    rows = pl.output_rows()
+    assert 0 < rows.numel() < 4001 and bool((rows[1:] > rows[:-1]).all())
+    want, S_abs = run_oracle(wl)
+    assert compare(out, want, S_abs, rows=rows) <= TOL
+    dense, _, _ = run_gpu(wl)
+    assert torch.equal(dense[rows.long()], out)
+
+
+def test_plan_options_are_checked():
+    wl = w.make(1)
+    X = wl.sparse["X"]
+    dc, dv = to_dev(X)
+    csf = cst.build_csf(dc, dv, X.dims, [0, 1, 2])
+    U2, U3 = wl.dense["U2"].cuda(), wl.dense["U3"].cuda()
+    ops = [("X", csf), ("U3", U3), ("U2", U2)]
+    assert "family=generic" in cst.plan(S.TTMC3, ops, options="force_generic=1").describe()
+    assert "family=ttmc3" in cst.plan(S.TTMC3, ops, options=" ttmc3_split = 64 , ttmc3_mfma=0 ").describe()
+    for bad in ("no_such_option=1", "ttmc3_split", "ttmc3_split=-4", "ttmc3_split=many"):
+        with pytest.raises(cst.ConststnError) as e:
+            cst.plan(S.TTMC3, ops, options=bad)
+        assert e.value.status_name == "EINVAL", bad
 
 
 def test_mttkrp_mode2_by_rerooted_csf():

@@ -1,7 +1,6 @@
 """Chain of three sparse tensors with a sparse result (Sec. 5.1, both forms) on the GPU against
 the dense-slice reference: the structure of the result must be identical (it is index work), the
 values within the tolerance of every other contraction."""
-import os
 
 import numpy as np
 import pytest
@@ -32,16 +31,12 @@ def _run(I, C, P, L=None, kernel=None):
     """Returns (coords of E as three host arrays, values, plan description).  kernel: None = the
     plan's choice, "general" = the form without dense blocks, "block-local" = expect that form."""
     hI, hC, hP = _csf(I, [0, 1, 2]), _csf(C, [1, 0]), _csf(P, [1, 0])
-    if kernel == "general":
-        os.environ["CONSTSTN_SPCHAIN3_FORM"] = "2"
-    try:
-        if L is None:
-            pl = cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)])
-        else:
-            hL = _csf(L, [0, 1])
-            pl = cst.plan(RESTRICTED, [("I", hI), ("C", hC), ("L", hL), ("P", hP)])
-    finally:
-        os.environ.pop("CONSTSTN_SPCHAIN3_FORM", None)
+    options = "spchain3_form=2" if kernel == "general" else None
+    if L is None:
+        pl = cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)], options=options)
+    else:
+        hL = _csf(L, [0, 1])
+        pl = cst.plan(RESTRICTED, [("I", hI), ("C", hC), ("L", hL), ("P", hP)], options=options)
     desc = pl.describe()
     assert "family=spchain3" in desc, desc
     if kernel is not None:

@@ -18,14 +18,14 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _run(Ec, Ev, dims, Fc=None, Fv=None, fdims=None):
+def _run(Ec, Ev, dims, Fc=None, Fv=None, fdims=None, options=None):
     """E (and optionally a second tensor F) as COO over (K, i, m).  Returns V's coordinates and values."""
     def csf(c, v, d):
         return cst.build_csf([torch.as_tensor(x, dtype=torch.int32).cuda() for x in c],
                              torch.as_tensor(v, dtype=torch.float64).cuda(), d, [1, 0, 2])
     hE = csf(Ec, Ev, dims)
     hF = hE if Fc is None else csf(Fc, Fv, fdims)
-    pl = cst.plan(S.SPPAIR4, [("Ea", hE), ("Eb", hF)])
+    pl = cst.plan(S.SPPAIR4, [("Ea", hE), ("Eb", hF)], options=options)
     desc = pl.describe()
     assert "family=sppair4" in desc, desc
     vals = cst.execute(pl, [])
@@ -111,22 +111,20 @@ def test_blocks_larger_than_one_tile_group_and_many_shared_k():
     assert worst <= TOL
 
 
-@pytest.mark.parametrize("env", [{"CONSTSTN_SPPAIR4_ROWS": "2"}, {"CONSTSTN_SPPAIR4_KEEP": "2"}, {},
-                                 {"CONSTSTN_SPPAIR4_BUFFERS": "1"}, {"CONSTSTN_SPPAIR4_XCD": "0"}],
+@pytest.mark.parametrize("env", [{"sppair4_rows": 2}, {"sppair4_keep": 2}, {},
+                                 {"sppair4_buffers": 1}, {"sppair4_xcd": 0}],
                          ids=["leaf-lists", "nothing-kept", "dense-rows", "one-chunk-buffer", "node-order"])
 @pytest.mark.parametrize("n_m", [200, 300])
-def test_every_form_of_the_numeric_pass(env, n_m, monkeypatch):
+def test_every_form_of_the_numeric_pass(env, n_m):
     # the chunk rows copied from dense rows (default, inner dimension <= 256), put together from leaf
     # lists kept by the plan, or found again by every launch; 300 distinct inner indices exceed one
     # 12 x 12 group of tiles and the dense form, and give rows of more than 128 leaves
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
     dims = (40, 3, n_m)
     Ec, Ev = _rand_e(5110 + n_m, dims, 40 * 3 * n_m * 6 // 10)
-    (ci, cj, cm, cn), vals, desc = _run(Ec, Ev, dims)
+    (ci, cj, cm, cn), vals, desc = _run(Ec, Ev, dims, options=env)
     _say("%s: %s" % (env, desc.split("|")[0]))
-    dense = "CONSTSTN_SPPAIR4_ROWS" not in env and "CONSTSTN_SPPAIR4_KEEP" not in env and n_m <= 256
-    want_kernel = "nothing kept" if "CONSTSTN_SPPAIR4_KEEP" in env else "dense rows" if dense else "leaf lists kept"
+    dense = "sppair4_rows" not in env and "sppair4_keep" not in env and n_m <= 256
+    want_kernel = "nothing kept" if "sppair4_keep" in env else "dense rows" if dense else "leaf lists kept"
     assert "kernel=" + want_kernel in desc, desc
     worst = 0.0
     for i in range(3):
