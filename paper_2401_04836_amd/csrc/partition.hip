@@ -896,6 +896,47 @@ static conststn_status build_stream_tables(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// Order-4 matrix-core path: one wavefront per item, so the longest items go first (the last round of
+// workgroups then holds the short ones).  Cost = matrix instructions: one per group, sixteen per K-step.
+__global__ void item_cost_keys_kernel(int64_t n_items, const SliceItem *__restrict__ items,
+                                      const int64_t *__restrict__ kstep_group, uint64_t *keys, uint32_t *ids) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n_items) return;
+    const int64_t cost = (kstep_group[items[i].end] - kstep_group[items[i].begin]) + 16 * (items[i].end - items[i].begin);
+    keys[i] = uint64_t(0xffffffffu) - uint64_t(cost < 0xffffffffll ? cost : 0xffffffffll);
+    ids[i] = uint32_t(i);
+}
+
+__global__ void permute_items_kernel(int64_t n_items, const uint32_t *__restrict__ order,
+                                     const SliceItem *__restrict__ in, SliceItem *out) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n_items) out[i] = in[order[i]];
+}
+
+static conststn_status order_items_by_cost(conststn_plan_s *plan) {
+    const int64_t n = plan->n_items;
+    if (n >= (int64_t(1) << 32)) return CONSTSTN_OK;
+    DevBuf<uint64_t> ka, kb;
+    DevBuf<uint32_t> ia, ib;
+    DevBuf<SliceItem> sorted;
+    CST_TRY(ka.alloc(n));
+    CST_TRY(kb.alloc(n));
+    CST_TRY(ia.alloc(n));
+    CST_TRY(ib.alloc(n));
+    CST_TRY(sorted.alloc(n));
+    const dim3 grid(unsigned(div_up(n, 256))), block(256);
+    item_cost_keys_kernel<<<grid, block>>>(n, plan->items.p, plan->kstep_group.p, ka.p, ia.p);
+    CST_HIP(hipGetLastError());
+    const uint64_t *ks = nullptr;
+    const uint32_t *order = nullptr;
+    CST_TRY(radix_sort_pairs_u64(ka.p, kb.p, ia.p, ib.p, n, 32, hipStream_t(0), &ks, &order));
+    permute_items_kernel<<<grid, block>>>(n, order, plan->items.p, sorted.p);
+    CST_HIP(hipGetLastError());
+    CST_HIP(hipMemcpy(plan->items.p, sorted.p, size_t(n) * sizeof(SliceItem), hipMemcpyDeviceToDevice));
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
 conststn_status build_ttmc_tables(conststn_plan_s *plan) {
     const conststn_csf_s *X = plan->X;
     const int64_t slices = X->nodes[0];
@@ -928,12 +969,15 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
         plan->use_rows = true;
         CST_TRY(build_piece_groups(plan));
         unit_ptr = plan->slice_row.p;                 // items are ranges of K-steps (four fibers each)
-        split = plan->opt("ttmc4_ksplit", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 64), 192));
+        // (with the items ordered by cost their length matters little: 2.95 ms per launch on the 40 M-nonzero
+        // tensor for 64 to 128 K-steps per item, and the fewer partial row blocks the shorter the fix-up pass)
+        split = plan->opt("ttmc4_ksplit", std::min<int64_t>(std::max<int64_t>(plan->n_rows_tab / 8192, 64), 128));
     }
     CST_TRY(build_items_core(slices, unit_ptr, split, 0, order, X->ptr[0].p, X->ptr[1].p, plan->row_elems,
                              plan->items, plan->n_items, plan->n_partials, plan->n_split, plan->split_slices,
                              plan->split_first, plan->split_count, plan->partial));
     CST_HIP(hipDeviceSynchronize());
+    if (X->order == 4 && plan->use_rows && plan->n_items > 1) CST_TRY(order_items_by_cost(plan));
     // streaming form of the order-3 matrix-core path: R3 of 32 or 64 (two column tiles per multiplying
     // wavefront), rows and output blocks reachable with the table's 32-bit fields
     plan->use_stream = X->order == 3 && plan->use_rows && (plan->rank_of_level[2] == 32 || plan->rank_of_level[2] == 64) &&
