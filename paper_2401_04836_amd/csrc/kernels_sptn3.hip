@@ -118,6 +118,7 @@ struct Sptn3TileArgs {
     const double *V;
     double *out, *partial;
     int compact, xcd_ranges;
+    const int32_t *wg_order;               // workgroup -> (k chunk, group) pair, heaviest pairs first (or null)
 };
 
 __device__ inline int64_t lower_bound_i32(const int32_t *__restrict__ a, int64_t lo, int64_t hi, int64_t key) {
@@ -151,7 +152,9 @@ sptn3_tiled_kernel(Sptn3TileArgs a) {
     // of (k chunk, group) pairs instead, so that the workgroups sharing one L2 walk the same k
     // values over neighbouring groups (same W tiles, largely the same rows of V).
     const int n_wg = a.n_groups * a.n_kc, per_xcd = (n_wg + 7) / 8;
-    const int logical = a.xcd_ranges ? (int(blockIdx.x) % 8) * per_xcd + int(blockIdx.x) / 8 : int(blockIdx.x);
+    if (int(blockIdx.x) >= n_wg && !a.xcd_ranges) return;
+    const int logical = a.xcd_ranges ? (int(blockIdx.x) % 8) * per_xcd + int(blockIdx.x) / 8
+                                     : (a.wg_order ? a.wg_order[blockIdx.x] : int(blockIdx.x));
     if (logical >= n_wg) return;
     const int group = logical % a.n_groups, kc = logical / a.n_groups;
     const int64_t s0 = int64_t(group) * kSpGroup;
@@ -480,7 +483,9 @@ sptn3_owned_kernel(Sptn3TileArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, slot = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n_wg = a.n_groups * a.n_kc, per_xcd = (n_wg + 7) / 8;
-    const int logical = a.xcd_ranges ? (int(blockIdx.x) % 8) * per_xcd + int(blockIdx.x) / 8 : int(blockIdx.x);
+    if (int(blockIdx.x) >= n_wg && !a.xcd_ranges) return;
+    const int logical = a.xcd_ranges ? (int(blockIdx.x) % 8) * per_xcd + int(blockIdx.x) / 8
+                                     : (a.wg_order ? a.wg_order[blockIdx.x] : int(blockIdx.x));
     if (logical >= n_wg) return;
     const int group = logical % a.n_groups, kc = logical / a.n_groups;
     const int64_t s0 = int64_t(group) * kSpGroup;
@@ -847,6 +852,7 @@ static conststn_status launch_sptn3_tiled(const conststn_plan_s *plan, const dou
     a.out = out;
     a.partial = plan->partial.p;
     a.compact = plan->compact ? 1 : 0;
+    a.wg_order = plan->sp_xcd_ranges ? nullptr : plan->sp_wg_order.p;
     a.xcd_ranges = plan->sp_xcd_ranges ? 1 : 0;      // measured: halves the HBM fetch, 4 % slower
     const size_t lds_bytes = size_t(kCap) * 16 * 8 + size_t(4 * kStage) * 256 * 8 + size_t(a.MT) * 256 * 8 +
                              size_t(kCap) * 4 + size_t(a.nwords) * 8 + 64;

@@ -1063,6 +1063,52 @@ __global__ void w_first_u32_kernel(int64_t n, const int64_t *__restrict__ first,
     if (x < n) out[x] = uint32_t(first[x]);
 }
 
+// Leaves of U per (k chunk, group of 16 slices) pair: the workgroups of the tiled kernels take the pairs
+// in falling order of it, so that the last round of workgroups holds the light ones.
+__global__ void sp_pair_cost_kernel(int64_t fibers, int64_t slices, const int64_t *__restrict__ ptr0,
+                                    const int64_t *__restrict__ ptr1, const int32_t *__restrict__ idx1,
+                                    int64_t k_per, int n_groups, unsigned *cost) {
+    const int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (f >= fibers) return;
+    const int64_t s = root_of_fiber(ptr0, slices, f);
+    const int64_t pair = (int64_t(idx1[f]) / k_per) * n_groups + s / kSpGroup;
+    atomicAdd(&cost[pair], unsigned(ptr1[f + 1] - ptr1[f]));
+}
+
+__global__ void sp_pair_keys_kernel(int64_t n, const unsigned *__restrict__ cost, uint64_t *keys, uint32_t *ids) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    keys[i] = uint64_t(0xffffffffu - cost[i]);
+    ids[i] = uint32_t(i);
+}
+
+static conststn_status build_sp_wg_order(conststn_plan_s *plan) {
+    const conststn_csf_s *U = plan->X;
+    const int64_t groups = div_up(U->nodes[0], kSpGroup), n = groups * plan->sp_kc;
+    if (n <= 1 || n >= (int64_t(1) << 31) || U->nodes[1] == 0) return CONSTSTN_OK;
+    DevBuf<unsigned> cost;
+    DevBuf<uint64_t> ka, kb;
+    DevBuf<uint32_t> ia, ib;
+    CST_TRY(cost.alloc(n));
+    CST_TRY(ka.alloc(n));
+    CST_TRY(kb.alloc(n));
+    CST_TRY(ia.alloc(n));
+    CST_TRY(ib.alloc(n));
+    const dim3 block(256);
+    fill_i32_kernel<<<dim3(unsigned(div_up(n, 256))), block>>>(reinterpret_cast<int32_t *>(cost.p), n, 0);
+    sp_pair_cost_kernel<<<dim3(unsigned(div_up(U->nodes[1], 256))), block>>>(
+        U->nodes[1], U->nodes[0], U->ptr[0].p, U->ptr[1].p, U->idx[1].p, plan->sp_k_per, int(groups), cost.p);
+    sp_pair_keys_kernel<<<dim3(unsigned(div_up(n, 256))), block>>>(n, cost.p, ka.p, ia.p);
+    CST_HIP(hipGetLastError());
+    const uint64_t *ks = nullptr;
+    const uint32_t *order = nullptr;
+    CST_TRY(radix_sort_pairs_u64(ka.p, kb.p, ia.p, ib.p, n, 32, hipStream_t(0), &ks, &order));
+    CST_TRY(plan->sp_wg_order.alloc(size_t(n)));
+    CST_HIP(hipMemcpy(plan->sp_wg_order.p, order, size_t(n) * sizeof(uint32_t), hipMemcpyDeviceToDevice));
+    CST_HIP(hipDeviceSynchronize());
+    return CONSTSTN_OK;
+}
+
 static conststn_status build_w_tiles(conststn_plan_s *plan) {
     const conststn_csf_s *U = plan->X, *W = plan->W;
     const int64_t J = U->dims[U->mode_order[2]];
@@ -1118,6 +1164,7 @@ static conststn_status build_w_tiles(conststn_plan_s *plan) {
     if (plan->sp_kc > 1)
         CST_TRY(plan->partial.alloc(size_t(plan->sp_kc) * size_t(U->nodes[0]) * size_t(M)));
     plan->w_tiled = true;
+    CST_TRY(build_sp_wg_order(plan));
     plan->sp_two_waves = plan->opt("sptn3_waves", 2) == 2 && sptn3_two_waves_fit(int((J + 31) / 32));
     return CONSTSTN_OK;
 }

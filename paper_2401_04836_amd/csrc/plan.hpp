@@ -198,6 +198,7 @@ struct conststn_plan_s {
     cst::DevBuf<uint32_t> w_tile_first;    // [roots x ceil(L/16)] index of the first of them
     cst::DevBuf<double> w_tiles;           // [(tiles + 1) x 256], the last one all zero
     bool sp_xcd_ranges = false;            // contiguous workgroup ranges per XCD
+    cst::DevBuf<int32_t> sp_wg_order;      // [groups x k chunks] pairs by falling number of U leaves, or empty
     int sp_kc = 1;                         // chunks of the k range (one workgroup per group and chunk)
     int64_t sp_k_per = 0;                  // k values per chunk
 
