@@ -369,6 +369,8 @@ def measured_peaks(cst):
         return {"copy_GBps": cst.measure_peak(cst.PEAK_COPY, 1 << 31, 5),
                 "write_GBps": cst.measure_peak(cst.PEAK_WRITE, 1 << 32, 5),
                 "mfma_f64_TFLOPs": cst.measure_peak(cst.PEAK_MFMA_F64, 4096, 3),
+                "clock_MHz_under_mfma_f64": cst.measure_peak(cst.PEAK_MFMA_CLOCK, 4096, 2),
+                "clock_MHz_light_load": cst.measure_peak(cst.PEAK_VALU_CLOCK, 200000, 2),
                 "what": "2 GiB device copy (bytes read + written), 4 GiB fill, 8 independent v_mfma_f64_16x16x4 chains "
                         "with four wavefronts per SIMD; nominal 8000 GB/s and 78.6 TFLOP/s"}
     except cst.ConststnError as e:

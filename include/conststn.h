@@ -165,7 +165,7 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
  * reads no option.  Names (default): force_generic (0; 1 = the generic executor also where a tuned
  * kernel exists), generic_max_gb (64), generic_span (4096), mttkrp_split (1), mttkrp_hot (256),
  * mttkrp_chunk (0 = by tensor size), ttmc3_mfma (1), ttmc3_stream (1), ttmc3_producers (4),
- * ttmc3_batch (1024), ttmc3_itemcost (2), ttmc3_qn (2), ttmc3_split (4096), ttmc3_rowsplit (by size),
+ * ttmc3_batch (2048), ttmc3_itemcost (2), ttmc3_qn (2), ttmc3_split (4096), ttmc3_rowsplit (by size),
  * ttmc4_mfma (1), ttmc4_split (256), ttmc4_ksplit (by size), sptn3_tiled (1; 0 = baseline kernel, 2 = tiled kernel
  * also where W fills its 16 x 16 tiles to less than a sixteenth),
  * sptn3_waves (2), sptn3_wgs (8000), sptn3_xcd (0), spchain3_form (1; 2 = general numeric pass),
@@ -289,10 +289,16 @@ conststn_status conststn_plan_kernel_times(conststn_plan_t *plan, float *ms, int
  *   CONSTSTN_PEAK_WRITE     size = bytes (multiple of 16): a plain fill; *result = GB/s written
  *   CONSTSTN_PEAK_MFMA_F64  size = rounds: every wavefront of a full-chip launch (four per SIMD)
  *                           issues 8 * size independent v_mfma_f64_16x16x4f64; *result = TFLOP/s
+ *   CONSTSTN_PEAK_MFMA_CLOCK  the same loop; *result = shader clock in MHz while it runs (cycle counter
+ *                           of one wavefront against the constant-rate wall clock)
+ *   CONSTSTN_PEAK_VALU_CLOCK  size = rounds of a loop of dependent 32-bit adds on one wavefront per CU;
+ *                           *result = shader clock in MHz of a lightly loaded chip
  * Errors: EINVAL, ENOMEM, EHIP. */
 #define CONSTSTN_PEAK_COPY 0
 #define CONSTSTN_PEAK_WRITE 1
 #define CONSTSTN_PEAK_MFMA_F64 2
+#define CONSTSTN_PEAK_MFMA_CLOCK 3
+#define CONSTSTN_PEAK_VALU_CLOCK 4
 conststn_status conststn_measure_peak(int what, int64_t size, int repeats, conststn_stream stream,
                                       double *result);
 

@@ -93,7 +93,7 @@ def version():
     return _lib.conststn_version().decode()
 
 
-PEAK_COPY, PEAK_WRITE, PEAK_MFMA_F64 = 0, 1, 2
+PEAK_COPY, PEAK_WRITE, PEAK_MFMA_F64, PEAK_MFMA_CLOCK, PEAK_VALU_CLOCK = 0, 1, 2, 3, 4
 
 
 def measure_peak(what, size, repeats=5, stream=None):

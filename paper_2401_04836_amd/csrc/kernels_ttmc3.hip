@@ -508,6 +508,7 @@ static conststn_status launch_stream_np(const conststn_plan_s *plan, const Ttmc3
     const dim3 grid(unsigned(plan->n_stream_wg));
     switch (plan->stream_producers) {
         case 2: ttmc3_stream_kernel<PN, NC, 2><<<grid, dim3(64 * (2 + NC)), 0, stream>>>(a); break;
+        case 3: ttmc3_stream_kernel<PN, NC, 3><<<grid, dim3(64 * (3 + NC)), 0, stream>>>(a); break;
         case 6: ttmc3_stream_kernel<PN, NC, 6><<<grid, dim3(64 * (6 + NC)), 0, stream>>>(a); break;
         case 8: ttmc3_stream_kernel<PN, NC, 8><<<grid, dim3(64 * (8 + NC)), 0, stream>>>(a); break;
         default: ttmc3_stream_kernel<PN, NC, 4><<<grid, dim3(64 * (4 + NC)), 0, stream>>>(a); break;

@@ -850,14 +850,18 @@ __global__ void fill_ksteps_kernel(int64_t n_ksteps, int64_t n_items, const Slic
     out[g] = d;
 }
 
-// Workgroup w starts at the first item whose cost prefix reaches w * target: batches hold whole items.
+// Workgroup w starts at the first item whose cost prefix reaches the w-th cut: batches hold whole items.
+// The cuts are `target` apart for the first n1 batches, a quarter of it for the next n2 and a sixteenth
+// after that, so that the last workgroups to start are short ones and the chip drains evenly.
 __global__ void stream_batches_kernel(int64_t n_wg, int64_t n_items, const int64_t *__restrict__ cost_off,
-                                      const int64_t *__restrict__ kstep_off, int64_t target, int64_t n_ksteps,
-                                      int32_t *wg_kstep) {
+                                      const int64_t *__restrict__ kstep_off, int64_t target, int64_t n1, int64_t n2,
+                                      int64_t n_ksteps, int32_t *wg_kstep) {
     const int64_t w = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (w > n_wg) return;
     if (w == n_wg) { wg_kstep[w] = int32_t(n_ksteps); return; }
-    const int64_t x = w * target;
+    const int64_t t4 = target / 4 > 0 ? target / 4 : 1, t16 = target / 16 > 0 ? target / 16 : 1;
+    const int64_t x = w < n1 ? w * target : (w < n1 + n2 ? n1 * target + (w - n1) * t4
+                                                          : n1 * target + n2 * t4 + (w - n1 - n2) * t16);
     int64_t i = last_le(cost_off, n_items, x);
     if (cost_off[i] < x) ++i;                       // first item with prefix >= x
     wg_kstep[w] = i < n_items ? int32_t(kstep_off[i]) : int32_t(n_ksteps);
@@ -869,7 +873,7 @@ static conststn_status build_stream_tables(conststn_plan_s *plan) {
     if (n_items == 0) return CONSTSTN_OK;
     // an item costs its K-steps plus the store of its row block
     const int64_t item_cost = std::max<int64_t>(plan->opt("ttmc3_itemcost", 2), 0);
-    const int64_t target = std::max<int64_t>(plan->opt("ttmc3_batch", 1024), 1);
+    const int64_t target = std::max<int64_t>(plan->opt("ttmc3_batch", 2048), 1);
     DevBuf<int64_t> ksteps_of, cost_of, kstep_off, cost_off;
     CST_TRY(ksteps_of.alloc(n_items));
     CST_TRY(cost_of.alloc(n_items));
@@ -887,10 +891,15 @@ static conststn_status build_stream_tables(conststn_plan_s *plan) {
     fill_ksteps_kernel<<<dim3(unsigned(div_up(plan->n_ksteps, 256))), block>>>(
         plan->n_ksteps, n_items, plan->items.p, kstep_off.p, plan->X->idx[0].p, plan->compact ? 1 : 0, plan->ksteps.p);
     CST_HIP(hipGetLastError());
-    plan->n_stream_wg = div_up(total_cost, target);
+    // three quarters of the work in full batches, a fifth in quarter batches, the rest in sixteenths
+    const int64_t t4 = std::max<int64_t>(target / 4, 1), t16 = std::max<int64_t>(target / 16, 1);
+    const int64_t n1 = total_cost * 3 / 4 / target;
+    const int64_t n2 = std::max<int64_t>(total_cost - n1 * target, 0) * 4 / 5 / t4;
+    const int64_t n3 = div_up(std::max<int64_t>(total_cost - n1 * target - n2 * t4, 0), t16);
+    plan->n_stream_wg = n1 + n2 + n3;
     CST_TRY(plan->wg_kstep.alloc(size_t(plan->n_stream_wg) + 1));
     stream_batches_kernel<<<dim3(unsigned(div_up(plan->n_stream_wg + 1, 256))), block>>>(
-        plan->n_stream_wg, n_items, cost_off.p, kstep_off.p, target, plan->n_ksteps, plan->wg_kstep.p);
+        plan->n_stream_wg, n_items, cost_off.p, kstep_off.p, target, n1, n2, plan->n_ksteps, plan->wg_kstep.p);
     CST_HIP(hipGetLastError());
     CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
@@ -984,7 +993,7 @@ conststn_status build_ttmc_tables(conststn_plan_s *plan) {
                        plan->opt("ttmc3_stream", 1) == 1;
     if (plan->use_stream) {
         int np = int(plan->opt("ttmc3_producers", 4));
-        plan->stream_producers = np == 2 || np == 6 || np == 8 ? np : 4;
+        plan->stream_producers = np == 2 || np == 3 || np == 6 || np == 8 ? np : 4;
         CST_TRY(build_stream_tables(plan));
     }
     return CONSTSTN_OK;

@@ -30,8 +30,10 @@ peak_fill_kernel(v2f64 *__restrict__ dst, int64_t n, double v) {
 }
 
 // Every wavefront runs `iters` rounds of eight independent v_mfma_f64_16x16x4f64 chains.
+// sink[2], sink[3]: cycles and wall-clock ticks (100 MHz) the first wavefront spent in the loop
 __global__ void __launch_bounds__(256)
 peak_mfma_kernel(int iters, double seed, double *sink) {
+    const long long c0 = clock64(), w0 = wall_clock64();
     v4f64 acc[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = v4f64{0.0, 0.0, 0.0, 0.0};
@@ -44,6 +46,19 @@ peak_mfma_kernel(int iters, double seed, double *sink) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) s += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
     if (s == 12345.678) sink[0] = s;      // keeps the chains alive; never true for the seeds used
+    if (blockIdx.x == 0 && threadIdx.x == 0) { sink[2] = double(clock64() - c0); sink[3] = double(wall_clock64() - w0); }
+}
+
+__global__ void __launch_bounds__(64)
+peak_valu_kernel(int iters, int seed, double *sink) {
+    const long long c0 = clock64(), w0 = wall_clock64();
+    int x = seed + int(threadIdx.x);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) x = x * 3 + u;
+    }
+    if (x == 0x7fffffff) sink[0] = double(x);
+    if (blockIdx.x == 0 && threadIdx.x == 0) { sink[2] = double(clock64() - c0); sink[3] = double(wall_clock64() - w0); }
 }
 
 }  // namespace cst
@@ -98,10 +113,28 @@ extern "C" conststn_status conststn_measure_peak(int what, int64_t size, int rep
         *result = double(size) * repeats / (double(ms) * 1e-3) / 1e9;                // GB/s written
         return CONSTSTN_OK;
     }
+    if (what == CONSTSTN_PEAK_MFMA_CLOCK || what == CONSTSTN_PEAK_VALU_CLOCK) {
+        if (size > 100000000) { set_error("at most 100000000 rounds"); return CONSTSTN_EINVAL; }
+        DevBuf<double> sink;
+        CST_TRY(sink.alloc(4));
+        int wall_khz = 100000;
+        CST_HIP(hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, dev));
+        for (int r = 0; r < repeats + 1; ++r) {
+            if (what == CONSTSTN_PEAK_MFMA_CLOCK) peak_mfma_kernel<<<unsigned(cus) * 4, 256, 0, st>>>(int(size), 1.0, sink.p);
+            else peak_valu_kernel<<<unsigned(cus), 64, 0, st>>>(int(size), 1, sink.p);
+        }
+        CST_HIP(hipStreamSynchronize(st));
+        CST_HIP(hipGetLastError());
+        double h[4] = {0, 0, 0, 0};
+        CST_HIP(hipMemcpy(h, sink.p, sizeof(h), hipMemcpyDeviceToHost));
+        if (h[3] <= 0.0) { set_error("the wall clock did not advance"); return CONSTSTN_EHIP; }
+        *result = h[2] / h[3] * double(wall_khz) * 1e-3;                              // MHz
+        return CONSTSTN_OK;
+    }
     if (what == CONSTSTN_PEAK_MFMA_F64) {
         if (size > 1000000) { set_error("at most 1000000 rounds"); return CONSTSTN_EINVAL; }
         DevBuf<double> sink;
-        CST_TRY(sink.alloc(1));
+        CST_TRY(sink.alloc(4));
         const unsigned grid = unsigned(cus) * 4;          // four workgroups of four wavefronts per CU: four per SIMD
         peak_mfma_kernel<<<grid, 256, 0, st>>>(int(size), 1.0, sink.p);
         CST_HIP(hipEventRecord(e0, st));
