@@ -521,6 +521,8 @@ def main():
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured copy / matrix-core ceilings")
+    ap.add_argument("--peaks-only", action="store_true",
+                    help="measure the copy, fill and fp64 matrix-core ceilings of this GPU, print them and stop")
     ap.add_argument("--generic", action="store_true",
                     help="plan with the generic executor instead of the tuned kernels (configs 1, 2, 3, 5)")
     ap.add_argument("--plan-options", default=None, help="tuning options for every plan, \"name=value,...\"")
@@ -543,6 +545,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.peaks_only:
+        print(json.dumps({"measured_peak": measured_peaks(cst)}), flush=True)
+        return
     if args.calibrate:
         src = torch.ones(1 << 27, dtype=torch.float64, device=dev)        # 1 GiB
         dst = torch.empty_like(src)
@@ -553,8 +558,9 @@ def main():
         del src, dst
 
     cids = [5, 2, 3, 4, 1] if args.config == 0 else [args.config]
-    # CPU-oracle sample: about 400 M multiply-adds' worth of nonzeros per configuration, less when five run
-    cpu_budget = 400_000_000 if len(cids) == 1 else 200_000_000
+    # CPU-oracle sample, in multiply-adds' worth of nonzeros per configuration: a few seconds to about ten per
+    # configuration in the five-configuration run
+    cpu_budget = 400_000_000 if len(cids) == 1 else 1_200_000_000
     recs = [run_config(cst, S, dev, args, cid, cpu_budget) for cid in cids]
     head = recs[0]
     result = {

@@ -226,6 +226,98 @@ static conststn_status match_sppair4(conststn_plan_s *plan) {
     return CONSTSTN_OK;
 }
 
+// Order-3 MTTKRP or TTMc whose result is indexed by a level of X other than the root, written as any
+// legal two-statement tree (the factor of the leaf level first, or the two dense factors first, ...):
+//      MTTKRP   M[x_m, r]      = X[x_0,x_1,x_2] . Fa[x_a, r]  . Fb[x_b, r]
+//      TTMc     Y[x_m, ra, rb] = X[x_0,x_1,x_2] . Fa[x_a, ra] . Fb[x_b, rb]          {m, a, b} = {0, 1, 2}, m != 0
+// The value does not depend on the tree (Sec. 2.2), so the plan re-sorts a private copy of X with level m
+// at the root and hands it to the kernels of the root-mode case.
+static conststn_status match_rerooted(conststn_plan_s *plan) {
+    Schedule &s = plan->sched;
+    if (s.stmts.size() != 2 || s.operands.size() != 3) return CONSTSTN_EUNSUPPORTED;
+    int xop = -1;
+    for (size_t o = 0; o < s.operands.size(); ++o)
+        if (s.operands[o].kind == CONSTSTN_OPERAND_CSF) { if (xop >= 0) return CONSTSTN_EUNSUPPORTED; xop = int(o); }
+    if (xop < 0 || s.operands[xop].order != 3 || !s.operands[xop].csf) return CONSTSTN_EUNSUPPORTED;
+    // references to the operands, and what each statement's other input still holds when a factor joins
+    const Ref *xref = nullptr;
+    struct Fac { int level = -1; int ordinal = -1; std::string rank; int extent = 0; };
+    std::vector<Fac> facs;
+    std::vector<std::pair<const Ref *, const Ref *>> joins;       // (factor reference, the other input)
+    for (const Stmt &st : s.stmts) {
+        const Ref *refs[2] = {&st.a, &st.b};
+        const int ops[2] = {st.op_a, st.op_b};
+        for (int side = 0; side < 2; ++side) {
+            if (ops[side] < 0) continue;
+            if (ops[side] == xop) { if (xref) return CONSTSTN_EUNSUPPORTED; xref = refs[side]; continue; }
+            const OperandInfo &o = s.operands[ops[side]];
+            if (o.kind != CONSTSTN_OPERAND_DENSE || o.order != 2) return CONSTSTN_EUNSUPPORTED;
+            joins.push_back({refs[side], refs[1 - side]});
+        }
+    }
+    if (!xref || joins.size() != 2) return CONSTSTN_EUNSUPPORTED;
+    const std::vector<std::string> &x = xref->idx;
+    for (const auto &jn : joins) {
+        const Ref *f = jn.first;
+        Fac fc;
+        for (int l = 0; l < 3; ++l) if (f->idx[0] == x[l]) fc.level = l;       // F[x_l, r], row-major
+        if (fc.level < 0) return CONSTSTN_EUNSUPPORTED;
+        fc.rank = f->idx[1];
+        for (int l = 0; l < 3; ++l) if (fc.rank == x[l]) return CONSTSTN_EUNSUPPORTED;
+        for (const auto &o : s.operands)
+            if (o.name == f->name) { fc.ordinal = o.dense_ordinal; fc.extent = int(o.dims[1]); }
+        facs.push_back(fc);
+    }
+    if (facs[0].level == facs[1].level || facs[0].ordinal == facs[1].ordinal) return CONSTSTN_EUNSUPPORTED;
+    const int m = 3 - facs[0].level - facs[1].level;
+    if (m == 0) return CONSTSTN_EUNSUPPORTED;           // the root-mode kernels take that, without a copy
+    // the tree must be this network: every statement keeps x_m and the rank indices, and a level's index is
+    // summed only by the statement that joins its factor (with X or the other intermediate) or after it
+    const Stmt &first = s.stmts[0], &last = s.stmts[1];
+    if (first.consumer != 1) return CONSTSTN_EUNSUPPORTED;
+    auto holds = [](const Ref &r, const std::string &i) { return std::find(r.idx.begin(), r.idx.end(), i) != r.idx.end(); };
+    const bool x_first = first.op_a == xop || first.op_b == xop;
+    for (const Fac &fc : facs) {
+        // where does this factor join?
+        const bool in_first = (first.op_a >= 0 && s.operands[first.op_a].dense_ordinal == fc.ordinal && first.op_a != xop) ||
+                              (first.op_b >= 0 && s.operands[first.op_b].dense_ordinal == fc.ordinal && first.op_b != xop);
+        if (!holds(first.out, fc.rank) && in_first) return CONSTSTN_EUNSUPPORTED;          // a rank index summed away
+        if (in_first && x_first) continue;                    // joined with X itself: x_l is there
+        if (in_first && !x_first) {                           // the two factors first: both level indices must survive
+            if (!holds(first.out, x[fc.level])) return CONSTSTN_EUNSUPPORTED;
+            continue;
+        }
+        // joined by the last statement: the intermediate must still hold x_l (when X came first) -- or X itself does
+        if (x_first && !holds(first.out, x[fc.level])) return CONSTSTN_EUNSUPPORTED;
+    }
+    if (x_first && !holds(first.out, x[m])) return CONSTSTN_EUNSUPPORTED;
+    const bool mttkrp = facs[0].rank == facs[1].rank;
+    // order of the two other levels in the copy: for TTMc the result lists the ranks in level order
+    int a = facs[0].level < facs[1].level ? 0 : 1, b = 1 - a;
+    if (mttkrp) {
+        if (last.out.idx != std::vector<std::string>{x[m], facs[0].rank}) return CONSTSTN_EUNSUPPORTED;
+        if (facs[0].extent != facs[1].extent) { set_error("batch index with two extents"); return CONSTSTN_ESCHED; }
+    } else {
+        if (last.out.idx.size() != 3 || last.out.idx[0] != x[m]) return CONSTSTN_EUNSUPPORTED;
+        if (last.out.idx[1] == facs[b].rank && last.out.idx[2] == facs[a].rank) std::swap(a, b);
+        else if (!(last.out.idx[1] == facs[a].rank && last.out.idx[2] == facs[b].rank)) return CONSTSTN_EUNSUPPORTED;
+    }
+    const int new_levels[3] = {m, facs[a].level, facs[b].level};
+    std::unique_ptr<conststn_csf_s> copy(new (std::nothrow) conststn_csf_s());
+    if (!copy) { set_error("host allocation failed"); return CONSTSTN_ENOMEM; }
+    CST_TRY(reroot_csf3(s.operands[xop].csf, new_levels, copy.get()));
+    plan->rerooted_x = std::move(copy);
+    plan->rerooted_level = m;
+    plan->X = plan->rerooted_x.get();
+    plan->factor_of_level[1] = facs[a].ordinal;
+    plan->rank_of_level[1] = facs[a].extent;
+    plan->factor_of_level[2] = facs[b].ordinal;
+    plan->rank_of_level[2] = facs[b].extent;
+    plan->family = mttkrp ? FAM_MTTKRP3 : FAM_TTMC3;
+    plan->row_elems = mttkrp ? facs[a].extent : int64_t(facs[a].extent) * facs[b].extent;
+    return CONSTSTN_OK;
+}
+
 // rank extents the tuned kernels are built for
 static bool tuned_kernel_fits(const conststn_plan_s *plan) {
     switch (plan->family) {
@@ -448,6 +540,12 @@ conststn_status conststn_plan_options(const char *schedule, const int *fusion, i
         st = match_sppair4(plan);
         if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
     }
+    if (st == CONSTSTN_EUNSUPPORTED && plan->family == FAM_NONE && plan->opt("reroot", 1) == 1) {
+        std::string why = get_error();
+        clear_error();
+        st = match_rerooted(plan);
+        if (st == CONSTSTN_EUNSUPPORTED && !*get_error() && !why.empty()) set_error("%s", why.c_str());
+    }
     // tuned kernels have rank limits; beyond them, and for every other tree over one CSF operand,
     // the generic executor takes over
     if (st == CONSTSTN_OK && !tuned_kernel_fits(plan)) st = CONSTSTN_EUNSUPPORTED;
@@ -458,6 +556,9 @@ conststn_status conststn_plan_options(const char *schedule, const int *fusion, i
         std::string why = get_error();
         clear_error();
         plan->family = FAM_NONE;
+        plan->rerooted_x.reset();
+        plan->rerooted_level = -1;
+        plan->X = nullptr;
         st = build_generic(plan);
         if (st == CONSTSTN_EUNSUPPORTED) {
             std::string why2 = get_error();
@@ -484,6 +585,11 @@ conststn_status conststn_plan_options(const char *schedule, const int *fusion, i
     snprintf(head, sizeof(head), "family=%s rows=%lld row_elems=%lld compact=%d", family_name(plan->family),
              (long long)plan->out_rows, (long long)plan->row_elems, plan->compact ? 1 : 0);
     plan->description = head;
+    if (plan->rerooted_level >= 0) {
+        char b[96];
+        snprintf(b, sizeof(b), " private copy of the tensor with level %d at the root", plan->rerooted_level);
+        plan->description += b;
+    }
     if (plan->family == FAM_SPTN3) {
         char b[96];
         if (plan->w_tiled)

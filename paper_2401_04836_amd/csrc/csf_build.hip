@@ -14,7 +14,7 @@
 #include <algorithm>
 #include <cstring>
 
-#include "common.hpp"
+#include "plan.hpp"
 
 namespace cst {
 
@@ -433,6 +433,46 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     close_ptrs_kernel<<<dim3(1), dim3(64), 0, stream>>>(lo, order, totals.p);
     CST_HIP(hipGetLastError());
     CST_HIP(hipStreamSynchronize(stream));
+    return CONSTSTN_OK;
+}
+
+// ---- a second layout of a tensor that is already a CSF ------------------------------------------
+//
+// The level order fixes the loop order (Sec. 3.2), and a result indexed by a level other than the root
+// would have to be added into from everywhere.  For the order-3 MTTKRP / TTMc of such a mode the plan
+// therefore keeps a copy of the tensor with that level at the root: the coordinates are read back
+// out of the level arrays (a leaf's ancestors by binary search in the pointer arrays) and sorted again.
+__global__ void expand_csf3_kernel(int64_t nnz, int64_t n0, int64_t n1, const int64_t *__restrict__ ptr0,
+                                   const int64_t *__restrict__ ptr1, const int32_t *__restrict__ idx0,
+                                   const int32_t *__restrict__ idx1, const int32_t *__restrict__ idx2,
+                                   int32_t *c0, int32_t *c1, int32_t *c2) {
+    const int64_t e = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    const int64_t f = parent_of(ptr1, n1, e);
+    const int64_t s = parent_of(ptr0, n0, f);
+    c0[e] = idx0[s];
+    c1[e] = idx1[f];
+    c2[e] = idx2[e];
+}
+
+conststn_status reroot_csf3(const conststn_csf_s *src, const int new_levels[3], conststn_csf_s *dst) {
+    if (src->order != 3) { set_error("only order-3 tensors are re-sorted"); return CONSTSTN_EUNSUPPORTED; }
+    const int64_t nnz = src->nnz;
+    DevBuf<int32_t> c[3];
+    for (int l = 0; l < 3; ++l) CST_TRY(c[l].alloc(size_t(nnz)));
+    if (nnz > 0) {
+        expand_csf3_kernel<<<dim3(unsigned(div_up(nnz, 256))), dim3(256)>>>(
+            nnz, src->nodes[0], src->nodes[1], src->ptr[0].p, src->ptr[1].p, src->idx[0].p, src->idx[1].p,
+            src->idx[2].p, c[0].p, c[1].p, c[2].p);
+        CST_HIP(hipGetLastError());
+    }
+    // coordinates by tensor mode, and the new level order in tensor modes
+    const int32_t *by_mode[3] = {nullptr, nullptr, nullptr};
+    int mode_order[3];
+    for (int l = 0; l < 3; ++l) by_mode[src->mode_order[l]] = c[l].p;
+    for (int l = 0; l < 3; ++l) mode_order[l] = src->mode_order[new_levels[l]];
+    CST_TRY(build_csf_device(3, src->dims, nnz, by_mode, src->vals.p, mode_order, 0, hipStream_t(0), dst));
+    CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
 }
 

@@ -137,6 +137,11 @@ struct conststn_plan_s {
     int n_cus = 256;                      // compute units of the device the plan was made on
 
     const conststn_csf_s *X = nullptr;    // the sparse operand walked by the fused loops
+    // MTTKRP / TTMc of order 3 whose output index is not the root level of the caller's CSF: the plan keeps a
+    // private copy of the tensor sorted with the output mode at the root (X points to it) and runs the
+    // kernels written for that case
+    std::unique_ptr<conststn_csf_s> rerooted_x;
+    int rerooted_level = -1;              // level of the caller's CSF that indexes the output, or -1
     const conststn_csf_s *W = nullptr;    // second sparse operand (three-tensor network only)
     int n_dense = 0;
     int factor_of_level[CONSTSTN_MAX_ORDER] = {0};   // dense ordinal of the factor contracted at CSF level l
@@ -298,6 +303,8 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
 conststn_status launch_ttmc_fixup(const conststn_plan_s *plan, double *out, hipStream_t stream, const double *partial = nullptr);
 
 // csf_build.hip
+// a copy of an order-3 CSF tensor with its levels in the order `new_levels` (levels of `src`)
+conststn_status reroot_csf3(const conststn_csf_s *src, const int new_levels[3], conststn_csf_s *dst);
 conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
                                  const int32_t *const *coords, const double *vals,
                                  const int *mode_order, unsigned flags, hipStream_t stream,

@@ -137,26 +137,28 @@ def test_config2_mttkrp_other_modes_on_the_mode0_csf():
     for mode, sched, ops in (
             (1, "T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,j,r] * A[i,r] | i,j,r", (("C", C), ("A", A))),
             (2, "T[i,j,r] = A[i,r] * B[j,r] | i,j,r ; M[k,r] = X[i,j,k] * T[i,j,r] | i,j,k,r", (("A", A), ("B", B)))):
-        pl = cst.plan(sched, [("X", csf)] + list(ops))
-        _say("config 2 mode %d on CSF [0,1,2]: %s" % (mode, pl.describe().split("|")[0]))
-        facs = [t for _, t in ops]
-        out = cst.execute(pl, facs)
-        torch.cuda.synchronize()
-        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0.record()
-        out = cst.execute(pl, facs)
-        t1.record()
-        torch.cuda.synchronize()
-        _say("  %.2f ms per contraction" % t0.elapsed_time(t1))
-        out = out.reshape(X.dims[mode], -1)
-        others = [m for m in range(3) if m != mode]
-        Fa, Fb = ([A, B, C][others[0]].cpu().numpy(), [A, B, C][others[1]].cpu().numpy())
-        want = oracle.mttkrp3(cn, vn, X.dims, Fa, Fb, mode)
-        S_abs = oracle.mttkrp3_abs(cn, vn, X.dims, Fa, Fb, mode)
-        err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
-        _say("  rel err %.3e" % err)
-        assert err <= TOL
-        del pl, out
+        for options in (None, "reroot=0"):
+            pl = cst.plan(sched, [("X", csf)] + list(ops), options=options)
+            _say("config 2 mode %d on CSF [0,1,2]: %s" % (mode, pl.describe().split("|")[0]))
+            assert ("family=generic" in pl.describe()) == (options is not None)
+            facs = [t for _, t in ops]
+            out = cst.execute(pl, facs)
+            torch.cuda.synchronize()
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0.record()
+            out = cst.execute(pl, facs)
+            t1.record()
+            torch.cuda.synchronize()
+            _say("  %.2f ms per contraction" % t0.elapsed_time(t1))
+            out = out.reshape(X.dims[mode], -1)
+            others = [m for m in range(3) if m != mode]
+            Fa, Fb = ([A, B, C][others[0]].cpu().numpy(), [A, B, C][others[1]].cpu().numpy())
+            want = oracle.mttkrp3(cn, vn, X.dims, Fa, Fb, mode)
+            S_abs = oracle.mttkrp3_abs(cn, vn, X.dims, Fa, Fb, mode)
+            err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
+            _say("  rel err %.3e" % err)
+            assert err <= TOL
+            del pl, out
 
 
 def test_config5_ttmc3_full_size_compact():

@@ -158,32 +158,60 @@ def test_generic_matches_tuned_kernels_and_compact_rows():
     np.testing.assert_array_equal(comp, gen[rows])
 
 
-def test_every_output_mode_on_one_csf():
-    # Sec. 5.3 runs MTTKRP / TTMc for every mode; here all of them on the SAME CSF (i > j > k): a result
-    # that keeps a level other than the root is stored dense and added into
+@pytest.mark.parametrize("reroot", [0, 1])
+def test_every_output_mode_on_one_csf(reroot):
+    # Sec. 5.3 runs MTTKRP / TTMc for every mode; here all of them on the SAME CSF (i > j > k).  reroot=0: the
+    # generic executor (a result that keeps a level other than the root is stored dense and added into);
+    # reroot=1 (default): the plan's private copy of the tensor with the output level at the root and the
+    # kernels of the root-mode case
+    opts = {"reroot": reroot}
+    fam_m, fam_t = ("mttkrp3", "ttmc3") if reroot else ("generic", "generic")
     dims = (33, 21, 27)
     coords, vals = _tensor(371, dims, 3500)
     x = (coords, vals, dims)
     A, B, C = _dense(372, 33, 12), _dense(373, 21, 12), _dense(374, 27, 12)
     _say("MTTKRP mode 1: leaf factor first, then the root factor, result indexed by the middle level")
     got, _ = _run("T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,j,r] * A[i,r] | i,j,r",
-                  x, [0, 1, 2], [("C", C), ("A", A)], (21, 12))
+                  x, [0, 1, 2], [("C", C), ("A", A)], (21, 12), expect=fam_m, options=opts)
     _check(got, coords, vals, "ijk", [(A, "ir"), (C, "kr")], "jr", {"j": 21, "r": 12})
     _say("MTTKRP mode 2: Khatri-Rao rows of the two upper levels at X's fibers only, result indexed by the leaf level")
     got, pl = _run("T[i,j,r] = A[i,r] * B[j,r] | i,j,r ; M[k,r] = X[i,j,k] * T[i,j,r] | i,j,k,r",
-                   x, [0, 1, 2], [("A", A), ("B", B)], (27, 12))
+                   x, [0, 1, 2], [("A", A), ("B", B)], (27, 12), expect=fam_m, options=opts)
+    assert ("private copy of the tensor with level 2 at the root" in pl.describe()) == bool(reroot)
     _check(got, coords, vals, "ijk", [(A, "ir"), (B, "jr")], "kr", {"k": 27, "r": 12})
     again = cst.execute(pl, [A.cuda(), B.cuda()]).cpu().numpy().reshape(27, 12)     # cleared before each run
     np.testing.assert_allclose(again, got, rtol=0, atol=1e-9)
     U1, U2, U3 = _dense(375, 33, 3), _dense(376, 21, 4), _dense(377, 27, 5)
     _say("TTMc mode 1")
     got, _ = _run("T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s ; Y[j,a,s] = T[i,j,s] * U1[i,a] | i,j,a,s",
-                  x, [0, 1, 2], [("U3", U3), ("U1", U1)], (21, 3, 5))
+                  x, [0, 1, 2], [("U3", U3), ("U1", U1)], (21, 3, 5), expect=fam_t, options=opts)
     _check(got, coords, vals, "ijk", [(U1, "ia"), (U3, "ks")], "jas", {"j": 21, "a": 3, "s": 5})
     _say("TTMc mode 2")
     got, _ = _run("P[i,j,a,b] = U1[i,a] * U2[j,b] | i,j,a,b ; Y[k,a,b] = X[i,j,k] * P[i,j,a,b] | i,j,k,a,b",
-                  x, [0, 1, 2], [("U1", U1), ("U2", U2)], (27, 3, 4))
+                  x, [0, 1, 2], [("U1", U1), ("U2", U2)], (27, 3, 4), expect=fam_t, options=opts)
     _check(got, coords, vals, "ijk", [(U1, "ia"), (U2, "jb")], "kab", {"k": 27, "a": 3, "b": 4})
+    _say("TTMc mode 2 with the ranks listed the other way round, MTTKRP mode 1 with rank 32 and compact rows")
+    got, _ = _run("P[i,j,a,b] = U1[i,a] * U2[j,b] | i,j,a,b ; Y[k,b,a] = X[i,j,k] * P[i,j,a,b] | i,j,k,b,a",
+                  x, [0, 1, 2], [("U1", U1), ("U2", U2)], (27, 4, 3), expect=fam_t, options=opts)
+    _check(got, coords, vals, "ijk", [(U1, "ia"), (U2, "jb")], "kba", {"k": 27, "a": 3, "b": 4})
+    A32, C32 = _dense(378, 33, 32), _dense(379, 27, 32)
+    got, pl = _run("T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,j,r] * A[i,r] | i,j,r",
+                   x, [0, 1, 2], [("C", C32), ("A", A32)], (21, 32), expect=fam_m, options=opts)
+    _check(got, coords, vals, "ijk", [(A32, "ir"), (C32, "kr")], "jr", {"j": 21, "r": 32})
+
+
+def test_trees_that_only_look_like_a_non_root_mttkrp_stay_with_the_generic_executor():
+    # the middle index is summed before its factor joins: an outer product with B's rows, not an MTTKRP
+    dims = (9, 7, 8)
+    coords, vals = _tensor(381, dims, 200)
+    B, C = _dense(382, 7, 5), _dense(383, 8, 5)
+    got, _ = _run("T[i,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,r] * B[j,r] | i,j,r",
+                  (coords, vals, dims), [0, 1, 2], [("C", C), ("B", B)], (7, 5), expect="generic")
+    c = [t.numpy() for t in coords]
+    T = np.zeros((9, 5))
+    np.add.at(T, c[0], vals.numpy()[:, None] * C.numpy()[c[2]])
+    want = T.sum(0)[None, :] * B.numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
 
 
 def test_inputs_indexed_by_kept_levels_and_results_with_several_sparse_indices():
