@@ -163,7 +163,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
  * options choose among kernel forms and partition sizes that compute the same result; they are read
  * while the plan is built and stored in it -- nothing is read from the environment, and an execute
  * reads no option.  Names (default): force_generic (0; 1 = the generic executor also where a tuned
- * kernel exists), generic_max_gb (64), generic_span (4096), reroot (1; 0 = no private re-sorted copy of the
+ * kernel exists), generic_max_gb (64), generic_span (4096), generic_fuse (1; 0 = the generic
+ * executor stores every intermediate whole even where the schedule fuses), reroot (1; 0 = no private re-sorted copy of the
  * tensor for MTTKRP / TTMc of a non-root level: the generic executor takes those), mttkrp_split (1), mttkrp_hot (256),
  * mttkrp_chunk (0 = by tensor size), ttmc3_mfma (1), ttmc3_stream (1), ttmc3_producers (4),
  * ttmc3_batch (2048), ttmc3_itemcost (2), ttmc3_qn (2), ttmc3_split (4096), ttmc3_rowsplit (by size),

@@ -615,6 +615,13 @@ conststn_status conststn_plan_options(const char *schedule, const int *fusion, i
         snprintf(b, sizeof(b), " partial_blocks=%lld", (long long)plan->n_partials);
         plan->description += b;
     }
+    if (plan->family == FAM_GENERIC) {
+        int fused = 0;
+        for (const GenStmt &g : plan->gen) fused += g.skip;
+        char b[64];
+        snprintf(b, sizeof(b), " kernels=%d inlined_producers=%d", int(plan->gen.size()) - fused, fused);
+        plan->description += b;
+    }
     if (plan->family == FAM_SPCHAIN3) {
         char b[96];
         if (plan->sc_local)

@@ -35,6 +35,7 @@
 #include <set>
 
 #include "plan.hpp"
+#include <type_traits>
 
 namespace cst {
 
@@ -135,16 +136,206 @@ generic_stmt_kernel(GenStmt g) {
     g.out[row * g.out_block + out_off] = acc;
 }
 
-// second pass of a long sum: the partial sums of each result node, added in segment order
+// A fused producer / consumer pair (Sec. 2.2, Fig. 3b) in the shape the chains of Sec. 5.2 have:
+//        T[x_0..x_d, O...]   = X[x_0..x_d, x_{d+1}] * F1[x_{d+1}, O'...]           (X's leaf level summed)
+//        out[x_0..x_{d-1}, O...] = T[x_0..x_d, O...] * F[x_d, O''...]              (level d summed)
+// with the same dense indices O on both results.  The intermediate is one scalar per thread: a
+// group of W lanes owns one result node (or one segment of its leaves) and W of its result elements,
+// lane j element j.  What every lane of the group needs alike -- the leaves' indices and values, the
+// fibers' ends and indices -- is read once, lane j taking the j-th leaf (fiber) of a window of W, and
+// handed round with lane shuffles; only the rows of the two factors are read by every lane.  Fixed
+// order of addition, no atomics.
+// SMALL: both factors are below 2 GiB with fewer than 2^24 rows of fewer than 2^24 bytes, so that a row's
+// byte offset is one 24-bit multiply-add instead of 64-bit arithmetic.
+template <int W, bool SMALL>
+__global__ void __launch_bounds__(256)
+generic_fused_kernel(GenStmt g) {
+    using offs = typename std::conditional<SMALL, uint32_t, int64_t>::type;
+    const int64_t grp = (int64_t(blockIdx.x) * 256 + threadIdx.x) / W;
+    const int j = int(threadIdx.x) % W;
+    const bool segmented = g.n_segs > 0;
+    const int64_t chunks = (g.out_block + W - 1) / W;
+    if (grp >= (segmented ? g.n_segs : g.out_nodes) * chunks) return;        // whole groups leave together
+    const int64_t unit = grp / chunks;
+    const int64_t p = segmented ? g.seg[3 * unit] : unit;
+    const int64_t o_lin = (grp - unit * chunks) * W + j;
+    const bool live = o_lin < g.out_block;                   // idle lanes compute element 0 and store nothing
+    int64_t rem = live ? o_lin : 0;
+    int64_t f_off0 = 0, f1_off0 = 0, out_off = 0;
+    for (int q = g.n_out - 1; q >= 0; --q) {
+        const int64_t o = rem % g.extent[q];
+        rem /= g.extent[q];
+        f_off0 += o * g.f_stride[q];
+        f1_off0 += o * g.f1_stride[q];
+        out_off += o * g.out_stride[q];
+    }
+    int64_t c0, c1;                                          // the result node's children (fibers of X)
+    if (g.d_out == 0) { c0 = 0; c1 = g.roots; }
+    else { c0 = g.ptr[g.d_out - 1][p]; c1 = g.ptr[g.d_out - 1][p + 1]; }
+    const int32_t *ix = g.idx[g.d_out];
+    const int64_t *lptr = g.ptr[g.d_in - 1];                 // children of the consumer's children: X's leaves
+    // byte offsets of this lane's element in a row of F and of F1, and the rows' strides in bytes
+    const offs f_lane = offs(f_off0 * 8), f1_lane = offs(f1_off0 * 8);
+    const offs fs = offs(g.f_level_stride[g.d_out] * 8), fs1 = offs(g.f1_level_stride * 8);
+    const char *fb = reinterpret_cast<const char *>(g.f), *f1b = reinterpret_cast<const char *>(g.f1);
+    auto row = [](const char *base, int32_t i, offs stride, offs lane) -> double {
+        if constexpr (SMALL) return *reinterpret_cast<const double *>(base + (__umul24(uint32_t(i), stride) + lane));
+        else return *reinterpret_cast<const double *>(base + (int64_t(i) * stride + lane));
+    };
+    // A segment is a range of leaves and may begin and end inside a fiber: then the fiber's factor
+    // multiplies each part of its sum, and the second pass adds the parts.
+    int64_t e0 = 0, e_end = 0;
+    if (c0 < c1) {
+        e0 = segmented ? g.seg[3 * unit + 1] : lptr[c0];
+        e_end = segmented ? g.seg[3 * unit + 2] : lptr[c1];
+    }
+    constexpr int kFar = 1 << 30;                            // positions count from e0 and saturate here
+    const int n_total = e_end - e0 < kFar ? int(e_end - e0) : kFar;          // the plan keeps a unit's leaves below that
+    double acc = 0.0;
+    if (n_total > 0) {
+        int64_t c = c0;
+        if (segmented) {                                     // the fiber that holds leaf e0: the last c with lptr[c] <= e0
+            int64_t lo = c0, hi = c1;
+            while (hi - lo > 1) {
+                const int64_t mid = lo + ((hi - lo) >> 1);
+                if (lptr[mid] <= e0) lo = mid; else hi = mid;
+            }
+            c = lo;
+        }
+        const int32_t *lix = g.idx[g.d_in] + e0;
+        const double *lx = g.in + e0;
+        // window of W fibers from cw on: lane j holds the end and the index of fiber cw + j
+        int64_t cw = c;
+        int w_end, w_ix;
+        auto load_fibers = [&]() {
+            const int64_t cc = cw + j < c1 ? cw + j : c1 - 1;
+            const int64_t d = lptr[cc + 1] - e0;
+            w_end = d < kFar ? int(d) : kFar;
+            w_ix = ix[cc];
+        };
+        load_fibers();
+        int next = __shfl(w_end, 0, W);                      // end of the current fiber, its factor; then the same one fiber ahead
+        double fv = row(fb, __shfl(w_ix, 0, W), fs, f_lane);
+        int next2 = kFar;
+        double fv2 = 0.0;
+        auto look_ahead = [&]() {                            // (next2, fv2) for fiber c + 1
+            if (c + 1 >= c1) { next2 = kFar; return; }
+            if (c + 1 - cw == W) { cw = c + 1; load_fibers(); }
+            const int k = int(c + 1 - cw);
+            next2 = __shfl(w_end, k, W);
+            fv2 = row(fb, __shfl(w_ix, k, W), fs, f_lane);
+        };
+        look_ahead();
+        // window of W leaves: lane j holds leaf ew + j; the next window is read while this one is summed
+        int32_t l_ix, l_ix2;
+        double l_x, l_x2;
+        auto load_leaves = [&](int ew, int32_t &iv, double &xv) {
+            const bool in = ew + j < n_total;
+            iv = in ? lix[ew + j] : 0;
+            xv = in ? lx[ew + j] : 0.0;
+        };
+        load_leaves(0, l_ix, l_x);
+        double t = 0.0;
+        for (int ew = 0; ew < n_total; ew += W) {
+            load_leaves(ew + W, l_ix2, l_x2);
+            const int n = n_total - ew < W ? n_total - ew : W;
+            double yv[4], yv2[4];                            // rows of F1 four leaves at a time, one batch ahead
+#pragma unroll
+            for (int k = 0; k < 4; ++k) yv[k] = row(f1b, __shfl(l_ix, k, W), fs1, f1_lane);      // past the end: row 0, never added
+            for (int u0 = 0; u0 < n; u0 += 4) {
+                if (u0 + 4 < n) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) yv2[k] = row(f1b, __shfl(l_ix, u0 + 4 + k, W), fs1, f1_lane);
+                }
+                double xv[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) xv[k] = __shfl(l_x, u0 + k, W);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (u0 + k < n) {
+                        if (ew + u0 + k >= next) {           // the fiber ended (every fiber of a CSF has a leaf): its sum
+                            acc = fma(t, fv, acc);           // times the consumer's factor
+                            t = 0.0;
+                            ++c;
+                            next = next2;
+                            fv = fv2;
+                            look_ahead();
+                        }
+                        t = fma(xv[k], yv[k], t);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) yv[k] = yv2[k];
+            }
+            l_ix = l_ix2;
+            l_x = l_x2;
+        }
+        acc = fma(t, fv, acc);
+    }
+    if (!live) return;
+    if (segmented) { g.partial[unit * g.out_block + out_off] = acc; return; }
+    const int64_t row_out = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
+    g.out[row_out * g.out_block + out_off] = acc;
+}
+
+template <int W>
+static void launch_fused(const GenStmt &g, dim3 grid, hipStream_t stream) {
+    if (g.fused_small) generic_fused_kernel<W, true><<<grid, dim3(256), 0, stream>>>(g);
+    else generic_fused_kernel<W, false><<<grid, dim3(256), 0, stream>>>(g);
+}
+
+// second pass of a long sum: the partial sums of each result node, added in segment order.  Nodes
+// with more than kGenHeavy segments are left to the kernel below.
+constexpr int64_t kGenHeavy = 64;
 __global__ void __launch_bounds__(256)
 generic_segsum_kernel(GenStmt g) {
     const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (gid >= g.out_nodes * g.out_block) return;
     const int64_t p = gid / g.out_block, o = gid - p * g.out_block;
+    const int64_t s0 = g.seg_ptr[p], s1 = g.seg_ptr[p + 1];
+    if (s1 - s0 > kGenHeavy) return;
     double acc = 0.0;
-    for (int64_t sg = g.seg_ptr[p]; sg < g.seg_ptr[p + 1]; ++sg) acc += g.partial[sg * g.out_block + o];
+    for (int64_t sg = s0; sg < s1; ++sg) acc += g.partial[sg * g.out_block + o];
     const int64_t row = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
     g.out[row * g.out_block + o] = acc;
+}
+
+// One workgroup per node with many segments (a slice of a power-law tensor has thousands): thread
+// (s, j) adds every S-th segment's element j, S = 256 / W, then thread (0, j) adds the S sums in
+// order.  The order of addition depends on the launch shape only.
+template <int W>
+__global__ void __launch_bounds__(256)
+generic_segsum_heavy_kernel(GenStmt g) {
+    constexpr int S = 256 / W;
+    __shared__ double part[256];
+    const int64_t p = g.heavy[blockIdx.x];
+    const int64_t s0 = g.seg_ptr[p], s1 = g.seg_ptr[p + 1];
+    const int j = int(threadIdx.x) % W, sl = int(threadIdx.x) / W;
+    const int64_t row = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
+    for (int64_t o0 = 0; o0 < g.out_block; o0 += W) {
+        const int64_t o = o0 + j;
+        double acc = 0.0;
+        if (o < g.out_block)
+            for (int64_t sg = s0 + sl; sg < s1; sg += S) acc += g.partial[sg * g.out_block + o];
+        part[threadIdx.x] = acc;
+        __syncthreads();
+        if (sl == 0 && o < g.out_block) {
+            double sum = 0.0;
+#pragma unroll
+            for (int k = 0; k < S; ++k) sum += part[k * W + j];
+            g.out[row * g.out_block + o] = sum;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void generic_heavy_flag_kernel(const int64_t *seg_ptr, int64_t nodes, int64_t *flag) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p < nodes) flag[p] = seg_ptr[p + 1] - seg_ptr[p] > kGenHeavy ? 1 : 0;
+}
+__global__ void generic_heavy_list_kernel(const int64_t *flag, const int64_t *pos, int64_t nodes, int64_t *list) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p < nodes && flag[p]) list[pos[p]] = p;
 }
 
 // segments of kGenSegment children: how many per result node, then their ranges
@@ -164,6 +355,29 @@ __global__ void generic_seg_fill_kernel(const int64_t *ptr, int64_t nodes, int64
         seg[3 * sg] = p;
         seg[3 * sg + 1] = c;
         seg[3 * sg + 2] = c + kGenSegment < c1 ? c + kGenSegment : c1;
+    }
+}
+
+// The same for a statement whose producer is inlined: its work is counted in X's leaves, so the
+// leaves below a result node are cut into ranges of kGenLeafSegment, wherever the fibers end.
+constexpr int64_t kGenLeafSegment = 512;
+__global__ void generic_leafseg_count_kernel(const int64_t *ptr, const int64_t *lptr, int64_t nodes, int64_t roots, int64_t *count) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= nodes) return;
+    const int64_t c0 = ptr ? ptr[p] : 0, c1 = ptr ? ptr[p + 1] : roots;
+    count[p] = (lptr[c1] - lptr[c0] + kGenLeafSegment - 1) / kGenLeafSegment;
+}
+__global__ void generic_leafseg_fill_kernel(const int64_t *ptr, const int64_t *lptr, int64_t nodes, int64_t roots, const int64_t *seg_ptr,
+                                            int64_t *seg) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= nodes) return;
+    const int64_t c0 = ptr ? ptr[p] : 0, c1 = ptr ? ptr[p + 1] : roots;
+    const int64_t l1 = lptr[c1];
+    int64_t e = lptr[c0];
+    for (int64_t sg = seg_ptr[p]; sg < seg_ptr[p + 1]; ++sg, e += kGenLeafSegment) {
+        seg[3 * sg] = p;
+        seg[3 * sg + 1] = e;
+        seg[3 * sg + 2] = e + kGenLeafSegment < l1 ? e + kGenLeafSegment : l1;
     }
 }
 
@@ -387,7 +601,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
             if (keeps_beyond_prefix(st.out.idx, d_out, d_node) || (last && d_out > 1)) { kind = 1; out_by_prefix = false; d_out = 0; }
             else if (fa.depth > 0 || f_uses_kept) kind = 1;
         }
-        const bool long_sum = kind == 0 && d_node > 0 && d_out < d_node && max_span(d_out, d_node) > span_limit;
+        bool long_sum = kind == 0 && d_node > 0 && d_out < d_node && max_span(d_out, d_node) > span_limit;
         if (span_status != CONSTSTN_OK) { set_error("could not measure the subtree sizes of the CSF operand"); return span_status; }
         auto is_level = [&](const std::string &nm) { const int L = level_of(nm); return L >= 0 && L < d_node; };
 
@@ -458,6 +672,61 @@ conststn_status build_generic(conststn_plan_s *plan) {
             g.idx[l] = csf->idx[l].p;
             g.ptr[l] = l + 1 < n ? csf->ptr[l].p : nullptr;
         }
+        // Fusion (Sec. 2.2): when this statement consumes a result that the statement before it in the tree forms
+        // from X's leaves and a dense operand one level deeper, with the same dense indices, and the
+        // schedule fuses the two on the whole prefix, the producer is computed inside this statement's kernel.
+        {
+            const int prod = tb.from_x ? st.src_b : st.src_a;
+            if (kind == 0 && prod >= 0 && in.from_x && g.n_red == 0 && d_node - d_out == 1 && d_node == n - 1 &&
+                plan->opt("generic_fuse", 1) == 1 && s.stmts[prod].fused_depth >= d_node) {
+                GenStmt &g1 = plan->gen[size_t(prod)];
+                const Stmt &sp = s.stmts[prod];
+                const Ref *f1ref = nullptr;
+                if (sp.op_a >= 0 && sp.op_a == g1.f_operand) f1ref = &sp.a;
+                else if (sp.op_b >= 0 && sp.op_b == g1.f_operand) f1ref = &sp.b;
+                bool ok = g1.kind == 0 && g1.in_is_leaf && g1.n_red == 0 && g1.d_node == n &&
+                          g1.d_out == d_node && g1.out_buffer == in.buffer && g1.f_operand >= 0 && f1ref &&
+                          g1.n_out == g.n_out && g1.skip == 0 && g1.fused == 0;
+                std::map<std::string, int64_t> sf1;
+                if (ok) {
+                    strides(f1ref->idx, sf1);
+                    // the same dense indices on both results (any order), none of them summed
+                    for (size_t q = 0; q < out_dense.size() && ok; ++q)
+                        if (find_name(in.dense, out_dense[q]) < 0) ok = false;
+                    if (in.dense.size() != out_dense.size()) ok = false;
+                    for (const auto &nm : f1ref->idx)
+                        if (nm != level_name[n - 1] && find_name(out_dense, nm) < 0) ok = false;
+                }
+                if (ok) {
+                    g.fused = 1;
+                    g.f1_operand = g1.f_operand;
+                    for (size_t q = 0; q < out_dense.size(); ++q) g.f1_stride[q] = sf1.count(out_dense[q]) ? sf1[out_dense[q]] : 0;
+                    g.f1_level_stride = sf1.count(level_name[n - 1]) ? sf1[level_name[n - 1]] : 0;
+                    {
+                        // the largest byte offset into either factor, the largest row number and row stride
+                        auto reach = [&](const int64_t *stride, int64_t level_stride, int64_t level_extent, int64_t &row_bytes) {
+                            int64_t elems = (level_extent - 1) * level_stride;
+                            for (size_t q = 0; q < out_dense.size(); ++q) elems += (g.extent[q] - 1) * stride[q];
+                            row_bytes = level_stride * 8;
+                            return elems * 8 + 8;
+                        };
+                        int64_t rb = 0, rb1 = 0;
+                        const int64_t ext = s.extent[level_name[d_out]], ext1 = s.extent[level_name[n - 1]];
+                        const int64_t top = reach(g.f_stride, g.f_level_stride[d_out], ext, rb);
+                        const int64_t top1 = reach(g.f1_stride, g.f1_level_stride, ext1, rb1);
+                        const int64_t lim24 = int64_t(1) << 24, lim31 = int64_t(1) << 31;
+                        g.fused_small = (top < lim31 && top1 < lim31 && ext < lim24 && ext1 < lim24 && rb < lim24 && rb1 < lim24) ? 1 : 0;
+                    }
+                    g.in_is_leaf = 1;                       // reads X's values, not the intermediate
+                    g.in_operand = -1;
+                    g.in_buffer = -1;
+                    g1.skip = 1;
+                    buffer_elems[size_t(in.buffer)] = 1;    // the intermediate is never stored,
+                    if (g1.n_segs > 0) buffer_elems[size_t(g1.partial_buffer)] = 1;      // nor are its partial sums
+                    long_sum = max_span(d_out, n) > std::min<int64_t>(span_limit, int64_t(1) << 29);     // work counted in leaves
+                }
+            }
+        }
         if (long_sum) {
             // the children of every result node in segments of kGenSegment
             const int64_t on = g.out_nodes;
@@ -467,7 +736,9 @@ conststn_status build_generic(conststn_plan_s *plan) {
             plan->gen_tables.emplace_back(new DevBuf<int64_t>());
             DevBuf<int64_t> &sptr = *plan->gen_tables.back();
             CST_TRY(sptr.alloc(size_t(on + 1)));
-            generic_seg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], count.p);
+            const int64_t *lptr = g.fused ? csf->ptr[d_node - 1].p : nullptr;
+            if (g.fused) generic_leafseg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, lptr, on, csf->nodes[0], count.p);
+            else generic_seg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], count.p);
             CST_HIP(hipGetLastError());
             int64_t n_segs = 0;
             CST_TRY(exscan(count.p, sptr.p, on, &n_segs));
@@ -475,11 +746,29 @@ conststn_status build_generic(conststn_plan_s *plan) {
             plan->gen_tables.emplace_back(new DevBuf<int64_t>());
             DevBuf<int64_t> &seg = *plan->gen_tables.back();
             CST_TRY(seg.alloc(size_t(3 * n_segs)));
-            generic_seg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], sptr.p, seg.p);
+            if (g.fused) generic_leafseg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, lptr, on, csf->nodes[0], sptr.p, seg.p);
+            else generic_seg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], sptr.p, seg.p);
             CST_HIP(hipGetLastError());
             CST_HIP(hipDeviceSynchronize());
             g.n_segs = n_segs;
             g.seg_table = int(plan->gen_tables.size()) - 2;
+            {
+                // the nodes with many segments, listed for the second pass
+                DevBuf<int64_t> flag, pos;
+                CST_TRY(flag.alloc(size_t(on)));
+                CST_TRY(pos.alloc(size_t(on)));
+                generic_heavy_flag_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(sptr.p, on, flag.p);
+                CST_HIP(hipGetLastError());
+                int64_t n_heavy = 0;
+                CST_TRY(exscan(flag.p, pos.p, on, &n_heavy));
+                plan->gen_tables.emplace_back(new DevBuf<int64_t>());
+                DevBuf<int64_t> &heavy = *plan->gen_tables.back();
+                CST_TRY(heavy.alloc(size_t(std::max<int64_t>(n_heavy, 1))));
+                generic_heavy_list_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(flag.p, pos.p, on, heavy.p);
+                CST_HIP(hipGetLastError());
+                CST_HIP(hipDeviceSynchronize());
+                g.n_heavy = n_heavy;
+            }
             g.partial_buffer = int(buffer_elems.size());
             buffer_elems.push_back(n_segs * g.out_block);
         }
@@ -540,6 +829,7 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         CST_TRY(zero_fill(out, plan->out_rows * plan->row_elems, stream));
     ProfScope prof(plan, stream);
     for (const GenStmt &g0 : plan->gen) {
+        if (g0.skip) continue;                     // computed inside its consumer's kernel
         GenStmt g = g0;
         auto where = [&](int operand, int buffer) -> const double * {
             if (buffer >= 0) return plan->gen_buffers[size_t(buffer)]->p;
@@ -548,6 +838,7 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         };
         g.in = g.in_is_leaf ? csf->vals.p : where(g.in_operand, g.in_buffer);      // X: the leaf values
         g.f = where(g.f_operand, g.f_buffer);
+        if (g.fused) g.f1 = where(g.f1_operand, -1);
         g.out = g.out_buffer >= 0 ? plan->gen_buffers[size_t(g.out_buffer)]->p : out;
         if (!g.in || !g.f || !g.out) { set_error("internal: unresolved tensor in the generic executor"); return CONSTSTN_EINVAL; }
         double *final_out = g.out;
@@ -560,14 +851,24 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         if (g.n_segs > 0) {
             g.seg_ptr = plan->gen_tables[size_t(g.seg_table)]->p;
             g.seg = plan->gen_tables[size_t(g.seg_table) + 1]->p;
+            g.heavy = plan->gen_tables[size_t(g.seg_table) + 2]->p;
             g.partial = plan->gen_buffers[size_t(g.partial_buffer)]->p;
         }
+        // lanes that share a result node in the fused kernel: the power of two that holds its elements, 8 to 64
+        int fused_w = 8;
+        while (fused_w < 64 && fused_w < g.out_block) fused_w *= 2;
+        const int64_t units = g.n_segs > 0 ? g.n_segs : g.out_nodes;
         const int64_t total = g.kind == 1 ? g.nodes[g.d_node - 1] * g.out_threads
-                                          : (g.n_segs > 0 ? g.n_segs : g.out_nodes) * g.out_block;
+                              : g.fused   ? units * ((g.out_block + fused_w - 1) / fused_w) * fused_w
+                                          : units * g.out_block;
         if (total > (int64_t(1) << 31) * 256) { set_error("statement result too large for one launch"); return CONSTSTN_EUNSUPPORTED; }
         const dim3 grid(unsigned((total + 255) / 256)), block(256);
         if (total > 0) {
             if (g.kind == 1) generic_node_kernel<<<grid, block, 0, stream>>>(g);
+            else if (g.fused && fused_w == 8) launch_fused<8>(g, grid, stream);
+            else if (g.fused && fused_w == 16) launch_fused<16>(g, grid, stream);
+            else if (g.fused && fused_w == 32) launch_fused<32>(g, grid, stream);
+            else if (g.fused) launch_fused<64>(g, grid, stream);
             else generic_stmt_kernel<<<grid, block, 0, stream>>>(g);
             CST_HIP(hipGetLastError());
         }
@@ -579,6 +880,14 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
             const int64_t t2 = g.out_nodes * g.out_block;
             generic_segsum_kernel<<<dim3(unsigned((t2 + 255) / 256)), block, 0, stream>>>(g);
             CST_HIP(hipGetLastError());
+            if (g.n_heavy > 0) {
+                const dim3 hg{unsigned(g.n_heavy)};
+                if (g.out_block <= 8) generic_segsum_heavy_kernel<8><<<hg, block, 0, stream>>>(g);
+                else if (g.out_block <= 32) generic_segsum_heavy_kernel<32><<<hg, block, 0, stream>>>(g);
+                else if (g.out_block <= 128) generic_segsum_heavy_kernel<128><<<hg, block, 0, stream>>>(g);
+                else generic_segsum_heavy_kernel<256><<<hg, block, 0, stream>>>(g);
+                CST_HIP(hipGetLastError());
+            }
         }
     }
     return CONSTSTN_OK;

@@ -52,13 +52,25 @@ struct GenStmt {
     // kind 0, long sums: the children of a result node cut into segments, one thread per (segment,
     // element) writes a partial sum, a second pass adds the partial sums of each node in order
     int64_t n_segs;
-    const int64_t *seg;                        // [3 * n_segs] result node, first child, end child
+    const int64_t *seg;                        // [3 * n_segs] result node, first child, end child (fused: first leaf, end leaf)
     const int64_t *seg_ptr;                    // [out_nodes + 1] segments of each result node
+    int64_t n_heavy;                           // result nodes with so many segments that a workgroup adds them
+    const int64_t *heavy;                      // [n_heavy] their numbers
     double *partial;                           // [n_segs * out_block]
     int seg_table, partial_buffer;             // resolved to pointers at launch
     // kind 1 with atomics: workgroups add into `copies` private copies of the result in turn, so that a
     // result element every node meets in (a power-law index) is not one queue; a second pass adds the copies
     int copies, copies_buffer;
+    // fused pair (Fig. 3b): this statement consumes a result that the statement before it forms from X's
+    // leaves and a dense factor F1, one level deeper; the consumer's thread sums the leaves below each of
+    // its children itself, so that the intermediate is a scalar in a register and is never stored
+    int fused;                                 // 1: producer inlined (its own entry has skip = 1)
+    int fused_small;                           // 1: both factors within reach of 32-bit byte offsets formed by 24-bit multiplies
+    int skip;                                  // 1: computed inside its consumer's kernel
+    int f1_operand;                            // the producer's dense factor, resolved at launch
+    const double *f1;
+    int64_t f1_stride[kGenMaxIdx];             // its strides for this statement's dense result indices
+    int64_t f1_level_stride;                   // and for the index of the leaf level
 };
 
 // One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1

@@ -158,6 +158,69 @@ def test_generic_matches_tuned_kernels_and_compact_rows():
     np.testing.assert_array_equal(comp, gen[rows])
 
 
+def test_fused_leaf_producer_is_inlined_and_equals_the_stored_intermediate():
+    # Sec. 2.2: a producer fused with its consumer on the whole sparse prefix needs a scalar only.  The
+    # executor then sums the leaves inside the consumer's kernel; fusion depth 0 and generic_fuse=0 store T.
+    dims = (70, 45, 38)
+    coords, vals = _tensor(391, dims, 9000)
+    heavy = torch.randperm(45 * 38, generator=torch.Generator().manual_seed(392))[:1500]     # one long slice
+    coords = [torch.cat([c, h]) for c, h in zip(coords, (torch.full((1500,), 5, dtype=torch.int32),
+                                                        (heavy // 38).to(torch.int32), (heavy % 38).to(torch.int32)))]
+    vals = torch.cat([vals, _dense(393, 1500)])
+    key = (coords[0].long() * 45 + coords[1]) * 38 + coords[2]
+    _, first = np.unique(key.numpy(), return_index=True)
+    coords, vals = [c[first] for c in coords], vals[first]
+    x = (coords, vals, dims)
+    B, C = _dense(394, 45, 24), _dense(395, 38, 24)
+    text = "T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[i,r] = T[i,j,r] * B[j,r] | i,j,r"
+    f = [("C", C), ("B", B)]
+    fused, pl = _run(text, x, [0, 1, 2], f, (70, 24), options="force_generic=1")
+    assert "inlined_producers=1" in pl.describe(), pl.describe()
+    _check(fused, coords, vals, "ijk", [(B, "jr"), (C, "kr")], "ir", {"i": 70, "r": 24})
+    for opts, fusion in (("force_generic=1,generic_fuse=0", None), ("force_generic=1", [0, 0])):
+        stored, pl = _run(text, x, [0, 1, 2], f, (70, 24), fusion=fusion, options=opts)
+        assert "inlined_producers=0" in pl.describe(), pl.describe()
+        np.testing.assert_allclose(stored, fused, rtol=0, atol=1e-11)
+    _say("long slices cut into segments (span 16), then compact rows")
+    seg, pl = _run(text, x, [0, 1, 2], f, (70, 24), options="force_generic=1,generic_span=16")
+    assert "inlined_producers=1" in pl.describe()
+    _check(seg, coords, vals, "ijk", [(B, "jr"), (C, "kr")], "ir", {"i": 70, "r": 24})
+    _say("order 4: only the deepest pair is inlined; a TTMc (the producer's result has fewer dense indices) is not")
+    dims4 = (30, 14, 12, 11)
+    c4, v4 = _tensor(396, dims4, 6000)
+    B4, C4, D4 = _dense(397, 14, 8), _dense(398, 12, 8), _dense(399, 11, 8)
+    t4 = ("T1[i,j,k,r] = X[i,j,k,l] * D[l,r] | i,j,k,l,r ; T2[i,j,r] = T1[i,j,k,r] * C[k,r] | i,j,k,r ; "
+          "M[i,r] = T2[i,j,r] * B[j,r] | i,j,r")
+    got, pl = _run(t4, (c4, v4, dims4), [0, 1, 2, 3], [("D", D4), ("C", C4), ("B", B4)], (30, 8))
+    assert "inlined_producers=1" in pl.describe(), pl.describe()
+    _check(got, c4, v4, "ijkl", [(B4, "jr"), (C4, "kr"), (D4, "lr")], "ir", {"i": 30, "r": 8})
+    _say("a slice of 40 000 leaves in 20 000 fibers: more segments than one thread adds in the second pass")
+    dimsh = (10, 20000, 4)
+    ch, vh = _tensor(405, dimsh, 3000)
+    cells = torch.randperm(20000 * 4, generator=torch.Generator().manual_seed(406))[:40000]
+    keep = ch[0] != 3
+    ch = [torch.cat([c[keep], h]) for c, h in zip(ch, (torch.full((40000,), 3, dtype=torch.int32),
+                                                       (cells // 4).to(torch.int32), (cells % 4).to(torch.int32)))]
+    vh = torch.cat([vh[keep], _dense(407, 40000)])
+    Bh, Ch = _dense(408, 20000, 24), _dense(409, 4, 24)
+    for opts in ("force_generic=1", "force_generic=1,generic_fuse=0"):
+        got, pl = _run(text, (ch, vh, dimsh), [0, 1, 2], [("C", Ch), ("B", Bh)], (10, 24), options=opts)
+        _check(got, ch, vh, "ijk", [(Bh, "jr"), (Ch, "kr")], "ir", {"i": 10, "r": 24})
+    _say("a leaf mode of 2^24 + 5 indices: row offsets in 64-bit arithmetic")
+    dimsw = (20, 30, (1 << 24) + 5)
+    cw, vw = _tensor(402, (20, 30, 4096), 6000)
+    cw[2] = (cw[2].long() * 4097 % dimsw[2]).to(torch.int32)          # distinct, spread over the whole mode
+    cw[2][0] = dimsw[2] - 1
+    Bw, Cw = _dense(403, 30, 8), _dense(404, dimsw[2], 8)
+    got, pl = _run(text, (cw, vw, dimsw), [0, 1, 2], [("C", Cw), ("B", Bw)], (20, 8), options="force_generic=1")
+    assert "inlined_producers=1" in pl.describe(), pl.describe()
+    _check(got, cw, vw, "ijk", [(Bw, "jr"), (Cw, "kr")], "ir", {"i": 20, "r": 8})
+    U2, U3 = _dense(400, 45, 72), _dense(401, 38, 8)
+    got, pl = _run("T[i,j,s] = X[i,j,k] * U3[k,s] | i,j,k,s ; Y[i,r,s] = T[i,j,s] * U2[j,r] | i,j,r,s",
+                   x, [0, 1, 2], [("U3", U3), ("U2", U2)], (70, 72, 8))
+    assert "inlined_producers=0" in pl.describe(), pl.describe()
+
+
 @pytest.mark.parametrize("reroot", [0, 1])
 def test_every_output_mode_on_one_csf(reroot):
     # Sec. 5.3 runs MTTKRP / TTMc for every mode; here all of them on the SAME CSF (i > j > k).  reroot=0: the
