@@ -32,7 +32,7 @@ KERNEL_SOURCES = {"mttkrp3": ["kernels_mttkrp3.hip", "partition.hip"],
                   "ttmc4": ["kernels_ttmc4.hip", "partition.hip"],
                   "sptn3": ["kernels_sptn3.hip", "partition.hip"],
                   "spchain3": ["kernels_spchain3.hip"], "sppair4": ["kernels_sppair4.hip"]}
-KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_kernel<512,1> + mttkrp3_r32_kernel<512,2> (hot and cold sub-tensor passes, back to back)",
+KERNEL_NAMES = {"mttkrp3": "mttkrp3_r32_dual_kernel<4,4> (hot and cold sub-tensor as two teams of wavefronts in one launch)",
                 "ttmc3": "ttmc3_stream_kernel<4,2,4>", "ttmc4": "ttmc4_mfma_kernel<1>", "sptn3": "sptn3_owned_kernel",
                 "spchain3": "spchain3_local_kernel", "sppair4": "sppair4_kernel",
                 "generic": "generic executor (generic_fused_kernel + generic_segsum kernels, or one kernel per statement)"}

@@ -165,7 +165,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
  * reads no option.  Names (default): force_generic (0; 1 = the generic executor also where a tuned
  * kernel exists), generic_max_gb (64), generic_span (4096), generic_fuse (1; 0 = the generic
  * executor stores every intermediate whole even where the schedule fuses), reroot (1; 0 = no private re-sorted copy of the
- * tensor for MTTKRP / TTMc of a non-root level: the generic executor takes those), mttkrp_split (1), mttkrp_hot (256),
+ * tensor for MTTKRP / TTMc of a non-root level: the generic executor takes those), mttkrp_split (1), mttkrp_dual (44 = hot and cold sub-tensor in one launch, four
+ * wavefronts of a workgroup each; 35, 53, 88 likewise; 0 = two launches), mttkrp_hot (256),
  * mttkrp_chunk (0 = by tensor size), ttmc3_mfma (1), ttmc3_stream (1), ttmc3_producers (4),
  * ttmc3_batch (2048), ttmc3_itemcost (2), ttmc3_qn (2), ttmc3_split (4096), ttmc3_rowsplit (by size),
  * ttmc4_mfma (1), ttmc4_split (256), ttmc4_ksplit (by size), sptn3_tiled (1; 0 = baseline kernel, 2 = tiled kernel

@@ -188,26 +188,22 @@ __device__ __forceinline__ int row_rank_of_flag(bool flag, int gl, int &row_tota
 // MODE 2: every leaf is cold (no LDS).  Modes 1 and 2 serve the split path, where the plan has
 // separated the tensor into a hot and a cold sub-tensor: the hot pass then issues no gather to
 // the vector-memory path for leaf rows and the cold pass issues only fully populated ones.
-template <int BLOCK, int MODE>
-__global__ void __launch_bounds__(BLOCK)
-mttkrp3_r32_kernel(MttkrpR32Args aa) {
-    extern __shared__ double2 hot[];                       // n_hot rows x 16 double2
+// The traversal itself, for NT threads (tid = 0 .. NT-1, whole wavefronts) that are the `part`-th of
+// `parts` such teams: the teams share the chunks round-robin.  `hot` = the staged hot rows (MODE 0, 1).
+template <int NT, int MODE>
+__device__ __forceinline__ void mttkrp3_r32_body(const MttkrpR32Args &aa, int tid, int64_t part, int64_t parts,
+                                                 const double2 *hot) {
     const MttkrpArgs &a = aa.base;
-    if (MODE != 2) {
-        for (int e = threadIdx.x; e < aa.n_hot * 16; e += BLOCK)
-            hot[e] = reinterpret_cast<const double2 *>(a.C + int64_t(aa.hot_rows[e >> 4]) * 32)[e & 15];
-        __syncthreads();
-    }
-    const int gl = threadIdx.x & 15;
+    const int gl = tid & 15;
     const lds_double2 *hot_lds = (const lds_double2 *)hot;
     const double2 *Cv = reinterpret_cast<const double2 *>(a.C);
     const double2 *Bv = reinterpret_cast<const double2 *>(a.B);
-    const int64_t groups = int64_t(gridDim.x) * (BLOCK / 16);
+    const int64_t groups = parts * (NT / 16);
     // every lane group of a wave runs the same number of rounds so that the wave-wide ballot
     // and the row broadcasts below always execute with all rows present
     const int64_t rounds = (a.n_chunks + groups - 1) / groups;
     for (int64_t rnd = 0; rnd < rounds; ++rnd) {
-        const int64_t c = rnd * groups + int64_t(blockIdx.x) * (BLOCK / 16) + threadIdx.x / 16;
+        const int64_t c = rnd * groups + part * (NT / 16) + tid / 16;
         const bool live = c < a.n_chunks;
         const int64_t n0 = live ? c * a.q : 0;
         const int64_t n1 = live ? (n0 + a.q < a.nnz ? n0 + a.q : a.nnz) : 0;
@@ -360,6 +356,45 @@ mttkrp3_r32_kernel(MttkrpR32Args aa) {
     }
 }
 
+template <int BLOCK, int MODE>
+__global__ void __launch_bounds__(BLOCK)
+mttkrp3_r32_kernel(MttkrpR32Args aa) {
+    extern __shared__ double2 hot[];                       // n_hot rows x 16 double2
+    if (MODE != 2) {
+        for (int e = threadIdx.x; e < aa.n_hot * 16; e += BLOCK)
+            hot[e] = reinterpret_cast<const double2 *>(aa.base.C + int64_t(aa.hot_rows[e >> 4]) * 32)[e & 15];
+        __syncthreads();
+    }
+    mttkrp3_r32_body<BLOCK, MODE>(aa, int(threadIdx.x), int64_t(blockIdx.x), int64_t(gridDim.x), hot);
+}
+
+// Hot and cold sub-tensor in ONE launch: the first NH wavefronts of every workgroup walk chunks of the
+// hot sub-tensor (rows from LDS: vector issue slots and LDS bandwidth), the other NC chunks of the cold
+// one (rows from L2 / memory: the vector-memory path), so that the two passes load different units of
+// a CU at the same time instead of one after the other.  The two write different buffers (the cold team
+// `cold.base.out`), added afterwards: both may own the same output row.
+struct MttkrpDualArgs { MttkrpR32Args hot, cold; };
+
+template <int NH, int NC>
+__global__ void __launch_bounds__(64 * (NH + NC))
+mttkrp3_r32_dual_kernel(MttkrpDualArgs d) {
+    extern __shared__ double2 hot[];
+    for (int e = threadIdx.x; e < d.hot.n_hot * 16; e += 64 * (NH + NC))
+        hot[e] = reinterpret_cast<const double2 *>(d.hot.base.C + int64_t(d.hot.hot_rows[e >> 4]) * 32)[e & 15];
+    __syncthreads();
+    if (threadIdx.x < 64 * NH) mttkrp3_r32_body<64 * NH, 1>(d.hot, int(threadIdx.x), int64_t(blockIdx.x), int64_t(gridDim.x), hot);
+    else mttkrp3_r32_body<64 * NC, 2>(d.cold, int(threadIdx.x) - 64 * NH, int64_t(blockIdx.x), int64_t(gridDim.x), hot);
+}
+
+__global__ void __launch_bounds__(256)
+mttkrp3_add_kernel(double2 *__restrict__ out, const double2 *__restrict__ add, int64_t n) {
+    const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (e < n) {
+        const double2 x = out[e], y = add[e];
+        out[e] = make_double2(x.x + y.x, x.y + y.y);
+    }
+}
+
 // Rows of slices shared by several chunks: add the partial rows in chunk order.
 // One block per slice; G lane groups stride over the chunks, then a fixed-order LDS reduction.
 template <int LPR>
@@ -485,6 +520,15 @@ conststn_status prepare_mttkrp3_launch(conststn_plan_s *plan) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     CST_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&mttkrp3_r32_kernel<512, 1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    const void *dual = nullptr;
+    switch (plan->mttkrp_dual) {
+        case 44: dual = reinterpret_cast<const void *>(&mttkrp3_r32_dual_kernel<4, 4>); break;
+        case 35: dual = reinterpret_cast<const void *>(&mttkrp3_r32_dual_kernel<3, 5>); break;
+        case 53: dual = reinterpret_cast<const void *>(&mttkrp3_r32_dual_kernel<5, 3>); break;
+        case 88: dual = reinterpret_cast<const void *>(&mttkrp3_r32_dual_kernel<8, 8>); break;
+        default: break;
+    }
+    if (dual) CST_HIP(hipFuncSetAttribute(dual, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     return CONSTSTN_OK;
 }
 
@@ -571,6 +615,33 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
                 aa.hot_rows = plan->hot_rows.p;
                 aa.n_hot = plan->n_hot;
                 aa.fibers = P.fibers;
+            }
+            if (plan->mttkrp_dual && plan->part[0].nnz > 0 && plan->part[1].nnz > 0) {
+                // one launch for both sub-tensors; the cold team writes its own buffer
+                const int64_t n = plan->out_rows * plan->row_elems;
+                CST_TRY(zero_fill(plan->mttkrp_out2.p, n, stream));
+                pa[1].base.out = plan->mttkrp_out2.p;
+                MttkrpDualArgs d{pa[0], pa[1]};
+                // wavefronts per workgroup, and as many workgroups per CU as its LDS and its registers (96 per
+                // lane: five wavefronts per SIMD) hold
+                const int waves = plan->mttkrp_dual / 10 + plan->mttkrp_dual % 10;
+                const int per_cu = std::max(1, std::min(int(160 * 1024 / lds), 20 / waves));
+                const dim3 grid(unsigned(cus * per_cu)), block(unsigned(64 * waves));
+                {
+                    ProfScope prof(plan, stream);
+                    switch (plan->mttkrp_dual) {
+                        case 44: mttkrp3_r32_dual_kernel<4, 4><<<grid, block, lds, stream>>>(d); break;
+                        case 35: mttkrp3_r32_dual_kernel<3, 5><<<grid, block, lds, stream>>>(d); break;
+                        case 53: mttkrp3_r32_dual_kernel<5, 3><<<grid, block, lds, stream>>>(d); break;
+                        default: mttkrp3_r32_dual_kernel<8, 8><<<grid, block, lds, stream>>>(d); break;
+                    }
+                    CST_HIP(hipGetLastError());
+                }
+                for (int part = 0; part < 2; ++part) CST_TRY(launch_fixup<16>(pa[part].base, stream));
+                mttkrp3_add_kernel<<<dim3(unsigned(div_up(n / 2, 256))), dim3(256), 0, stream>>>(
+                    reinterpret_cast<double2 *>(out), reinterpret_cast<const double2 *>(plan->mttkrp_out2.p), n / 2);
+                CST_HIP(hipGetLastError());
+                return CONSTSTN_OK;
             }
             {
                 ProfScope prof(plan, stream);             // the two traversal kernels, back to back

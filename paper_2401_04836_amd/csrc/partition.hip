@@ -19,7 +19,7 @@ namespace cst {
 bool known_plan_option(const std::string &name) {
     static const char *const names[] = {
         "force_generic", "generic_max_gb", "generic_span", "generic_fuse", "reroot",
-        "mttkrp_split", "mttkrp_hot", "mttkrp_chunk",
+        "mttkrp_split", "mttkrp_dual", "mttkrp_hot", "mttkrp_chunk",
         "ttmc3_mfma", "ttmc3_stream", "ttmc3_producers", "ttmc3_batch", "ttmc3_itemcost", "ttmc3_qn", "ttmc3_split",
         "ttmc3_rowsplit", "ttmc4_mfma", "ttmc4_split", "ttmc4_ksplit",
         "sptn3_tiled", "sptn3_waves", "sptn3_wgs", "sptn3_xcd",
@@ -328,6 +328,14 @@ static conststn_status build_mttkrp3_split(conststn_plan_s *plan, const int32_t 
         CST_HIP(hipDeviceSynchronize());
     }
     plan->split = true;
+    {
+        // hot and cold wavefronts per workgroup of the one-launch form (44 = four and four); 0 = two launches
+        const int64_t dual = plan->opt("mttkrp_dual", 44);
+        if (dual == 44 || dual == 35 || dual == 53 || dual == 88) {
+            plan->mttkrp_dual = int(dual);
+            CST_TRY(plan->mttkrp_out2.alloc(size_t(plan->out_rows * plan->row_elems)));
+        }
+    }
     return CONSTSTN_OK;
 }
 

@@ -120,6 +120,22 @@ def test_mttkrp_compact_rows_with_empty_and_heavy_slices(rank):
     assert torch.equal(dense[rows.long()], out)
 
 
+@pytest.mark.parametrize("dual", [0, 35, 53, 88])
+def test_mttkrp_hot_and_cold_passes_in_one_launch_or_two(dual):
+    """The default runs the hot and the cold sub-tensor as two teams of wavefronts in one launch (the cold
+    team into a buffer of its own, added afterwards); other team sizes and the two-launch form must agree."""
+    _say("mttkrp rank 32, mttkrp_dual=%d" % dual)
+    wl = w.make(2, small=True, dims=(4001, 211, 503), nnz=40_003, rank=32)
+    want, S_abs = run_oracle(wl)
+    for flags in (0, cst.OUT_COMPACT):
+        out, pl, _ = run_gpu(wl, flags=flags, options={"mttkrp_dual": dual})
+        assert compare(out, want, S_abs, rows=pl.output_rows() if flags else None) <= TOL
+    wl = w.make(2, small=True)
+    out, pl, _ = run_gpu(wl, options={"mttkrp_dual": dual})
+    want, S_abs = run_oracle(wl)
+    assert compare(out, want, S_abs) <= TOL
+
+
 def test_plan_options_are_checked():
     wl = w.make(1)
     X = wl.sparse["X"]
