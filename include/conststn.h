@@ -163,7 +163,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
  * options choose among kernel forms and partition sizes that compute the same result; they are read
  * while the plan is built and stored in it -- nothing is read from the environment, and an execute
  * reads no option.  Names (default): force_generic (0; 1 = the generic executor also where a tuned
- * kernel exists), generic_max_gb (64), generic_span (4096), generic_fuse (1; 0 = the generic
+ * kernel exists), generic_max_gb (64), generic_span (4096), generic_densify (1: a tree over several CSF operands runs on the generic executor, which walks the
+ * largest and keeps dense copies of the others; 0 = such trees are refused), generic_fuse (1; 0 = the generic
  * executor stores every intermediate whole even where the schedule fuses), reroot (1; 0 = no private re-sorted copy of the
  * tensor for MTTKRP / TTMc of a non-root level: the generic executor takes those), mttkrp_split (1), mttkrp_dual (44 = hot and cold sub-tensor in one launch, four
  * wavefronts of a workgroup each; 35, 53, 88 likewise; 0 = two launches), mttkrp_hot (256),

@@ -621,6 +621,10 @@ conststn_status conststn_plan_options(const char *schedule, const int *fusion, i
         char b[64];
         snprintf(b, sizeof(b), " kernels=%d inlined_producers=%d", int(plan->gen.size()) - fused, fused);
         plan->description += b;
+        if (!plan->gen_densified.empty()) {
+            snprintf(b, sizeof(b), " dense_copies_of_csf_operands=%d", int(plan->gen_densified.size()));
+            plan->description += b;
+        }
     }
     if (plan->family == FAM_SPCHAIN3) {
         char b[96];

@@ -466,17 +466,89 @@ int find_name(const std::vector<std::string> &v, const std::string &n) {
     return -1;
 }
 
+// dense[level-order offset of the leaf's coordinates] = value, one thread per leaf (the array was cleared)
+__global__ void densify_csf_kernel(GenStmt g, int order, double *dense) {
+    int64_t node = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (node >= g.nodes[order - 1]) return;
+    const double v = g.in[node];
+    int64_t off = 0, stride = 1;
+    for (int l = order - 1; l >= 0; --l) {
+        off += int64_t(g.idx[l][node]) * stride;
+        stride *= g.extent[l];
+        if (l > 0) node = parent_of(g.ptr[l - 1], g.nodes[l - 1], node);
+    }
+    dense[off] = v;
+}
+
+// A tree over several CSF operands (Sec. 3.1's running example has four): the executor walks ONE of them,
+// the one with the most nonzeros; the others are spread out into dense arrays in their level order when
+// the plan is built (their values are fixed by their handles) and take part as dense operands.  Slow
+// and always applicable, within the memory bound; no co-iteration.
+static conststn_status densify_other_operands(conststn_plan_s *plan, int keep) {
+    Schedule &s = plan->sched;
+    const int64_t limit = plan->opt("generic_max_gb", 64) << 30;
+    for (size_t o = 0; o < s.operands.size(); ++o) {
+        OperandInfo &oi = s.operands[o];
+        if (oi.kind != CONSTSTN_OPERAND_CSF || int(o) == keep) continue;
+        const conststn_csf_s *c = oi.csf;
+        if (!c) { set_error("CSF operand %s has no handle", oi.name.c_str()); return CONSTSTN_EINVAL; }
+        if (c->order > kGenMaxIdx) { set_error("CSF operand %s has more levels than the generic executor spreads out", oi.name.c_str()); return CONSTSTN_EUNSUPPORTED; }
+        int64_t elems = 1;
+        for (int l = 0; l < c->order; ++l) {
+            if (oi.dims[l] > 0 && elems > limit / 8 / oi.dims[l]) {
+                set_error("a dense copy of CSF operand %s would exceed generic_max_gb", oi.name.c_str());
+                return CONSTSTN_EUNSUPPORTED;
+            }
+            elems *= oi.dims[l];
+        }
+        plan->gen_densified.emplace_back(new DevBuf<double>());
+        DevBuf<double> &buf = *plan->gen_densified.back();
+        CST_TRY(buf.alloc(size_t(std::max<int64_t>(elems, 1))));
+        CST_HIP(hipMemset(buf.p, 0, size_t(std::max<int64_t>(elems, 1)) * sizeof(double)));
+        if (c->nnz > 0) {
+            GenStmt g{};
+            for (int l = 0; l < c->order; ++l) {
+                g.nodes[l] = c->nodes[l];
+                g.idx[l] = c->idx[l].p;
+                g.ptr[l] = l + 1 < c->order ? c->ptr[l].p : nullptr;
+                g.extent[l] = oi.dims[l];
+            }
+            g.in = c->vals.p;
+            densify_csf_kernel<<<dim3(unsigned(div_up(c->nnz, 256))), dim3(256)>>>(g, c->order, buf.p);
+            CST_HIP(hipGetLastError());
+            CST_HIP(hipDeviceSynchronize());
+        }
+        oi.kind = CONSTSTN_OPERAND_DENSE;         // from here on a dense operand that the plan owns
+        oi.owned = buf.p;
+    }
+    return CONSTSTN_OK;
+}
+
 }  // namespace
 
 conststn_status build_generic(conststn_plan_s *plan) {
     Schedule &s = plan->sched;
     const int m = int(s.stmts.size());
-    int xop = -1;
+    int xop = -1, n_csf = 0;
     for (size_t o = 0; o < s.operands.size(); ++o)
         if (s.operands[o].kind == CONSTSTN_OPERAND_CSF) {
-            if (xop >= 0) { set_error("the generic executor takes one CSF operand; the schedule has more"); return CONSTSTN_EUNSUPPORTED; }
-            xop = int(o);
+            ++n_csf;
+            // the operand the executor walks: the one with the most nonzeros among those used once
+            int uses = 0;
+            for (const Stmt &st : s.stmts)
+                for (const Ref *r : {&st.a, &st.b})
+                    if (r->name == s.operands[o].name) ++uses;
+            const conststn_csf_s *c = s.operands[o].csf;
+            if (uses == 1 && c && (xop < 0 || c->nnz > s.operands[size_t(xop)].csf->nnz)) xop = int(o);
         }
+    if (n_csf > 1) {
+        if (plan->opt("generic_densify", 1) != 1) { set_error("the generic executor takes one CSF operand; the schedule has more"); return CONSTSTN_EUNSUPPORTED; }
+        if (xop < 0) { set_error("the generic executor needs a CSF operand that is used exactly once"); return CONSTSTN_EUNSUPPORTED; }
+        CST_TRY(densify_other_operands(plan, xop));
+    } else if (n_csf == 1 && xop < 0) {
+        for (size_t o = 0; o < s.operands.size(); ++o)
+            if (s.operands[o].kind == CONSTSTN_OPERAND_CSF) xop = int(o);     // reported below: used more than once
+    }
     if (xop < 0) { set_error("the generic executor needs a CSF operand"); return CONSTSTN_EUNSUPPORTED; }
     const OperandInfo &X = s.operands[xop];
     const conststn_csf_s *csf = X.csf;
@@ -833,6 +905,7 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         GenStmt g = g0;
         auto where = [&](int operand, int buffer) -> const double * {
             if (buffer >= 0) return plan->gen_buffers[size_t(buffer)]->p;
+            if (operand >= 0 && s.operands[size_t(operand)].owned) return s.operands[size_t(operand)].owned;
             if (operand >= 0) return dense[s.operands[size_t(operand)].dense_ordinal];
             return nullptr;
         };

@@ -18,7 +18,7 @@ namespace cst {
 
 bool known_plan_option(const std::string &name) {
     static const char *const names[] = {
-        "force_generic", "generic_max_gb", "generic_span", "generic_fuse", "reroot",
+        "force_generic", "generic_max_gb", "generic_span", "generic_fuse", "generic_densify", "reroot",
         "mttkrp_split", "mttkrp_dual", "mttkrp_hot", "mttkrp_chunk",
         "ttmc3_mfma", "ttmc3_stream", "ttmc3_producers", "ttmc3_batch", "ttmc3_itemcost", "ttmc3_qn", "ttmc3_split",
         "ttmc3_rowsplit", "ttmc4_mfma", "ttmc4_split", "ttmc4_ksplit",

@@ -174,6 +174,7 @@ struct conststn_plan_s {
     cst::DevBuf<int32_t> hot_rows;         // [n_hot] leaf index held by each LDS slot
     int n_hot = 0;
     bool split = false;                    // hot and cold leaves run as two sub-tensors
+    std::vector<std::unique_ptr<cst::DevBuf<double>>> gen_densified;   // generic executor: dense copies of further CSF operands
     int mttkrp_dual = 0;                   // 0: two launches; NH * 10 + NC: one launch, NH hot and NC cold wavefronts per workgroup
     cst::DevBuf<double> mttkrp_out2;       // the cold team's output in that form, added to the result afterwards
     cst::MttkrpPart part[2];

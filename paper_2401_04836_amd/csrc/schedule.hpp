@@ -33,6 +33,7 @@ struct OperandInfo {
     int order = 0;
     int64_t dims[CONSTSTN_MAX_ORDER] = {0};   // CSF: extents in LEVEL order; dense: storage order
     int dense_ordinal = -1;                   // position among the dense operands
+    const double *owned = nullptr;            // dense copy kept by the plan (a CSF operand the generic executor spread out)
 };
 
 struct Schedule {

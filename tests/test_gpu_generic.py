@@ -295,6 +295,40 @@ def test_inputs_indexed_by_kept_levels_and_results_with_several_sparse_indices()
     _check(got, coords, vals, "ijk", [(U3, "ks")], "ijs", {"i": 20, "j": 12, "s": 4})
 
 
+def test_running_example_with_four_sparse_operands():
+    # Sec. 3.1 / Fig. 4: R_ijk = A_ipq B_jpr C_kqr D_jkr as X = A.B ; Y = X.C ; R = Y.D with the layouts and loop
+    # orders of the paper's constraint solution, all four tensors sparse.  The executor walks the operand
+    # with the most nonzeros and keeps dense copies of the other three.
+    P, Q, I, R, J, K = 7, 4, 8, 5, 6, 9
+    Ac, Av = _tensor(411, (P, Q, I), 90)
+    Bc, Bv = _tensor(412, (R, J, P), 70)
+    Cc, Cv = _tensor(413, (R, Q, K), 50)
+    Dc, Dv = _tensor(414, (R, J, K), 80)
+    text = ("X[r,j,q,i] = A[p,q,i] * B[r,j,p] | r,j,p,q,i ; Y[r,j,k,i] = X[r,j,q,i] * C[r,q,k] | r,j,q,k,i ; "
+            "R[j,k,i] = Y[r,j,k,i] * D[r,j,k] | r,j,k,i")
+    ops = [(n, cst.build_csf([c.cuda() for c in cc], vv.cuda(), dims, [0, 1, 2]))
+           for n, cc, vv, dims in (("A", Ac, Av, (P, Q, I)), ("B", Bc, Bv, (R, J, P)), ("C", Cc, Cv, (R, Q, K)), ("D", Dc, Dv, (R, J, K)))]
+    pl = cst.plan(text, ops, fusion=[2, 2, 0])
+    desc = pl.describe()
+    _say("  " + desc.split("|")[0])
+    assert "family=generic" in desc and "dense_copies_of_csf_operands=3" in desc and "X:order2 Y:order2" in desc, desc
+    got = cst.execute(pl, []).cpu().numpy().reshape(J, K, I)
+
+    def spread(cc, vv, dims):
+        t = np.zeros(dims)
+        t[tuple(c.numpy() for c in cc)] = vv.numpy()
+        return t
+    _check(got, Ac, Av, "pqi", [(torch.from_numpy(spread(Bc, Bv, (R, J, P))), "rjp"), (torch.from_numpy(spread(Cc, Cv, (R, Q, K))), "rqk"),
+                                (torch.from_numpy(spread(Dc, Dv, (R, J, K))), "rjk")], "jki", {"j": J, "k": K, "i": I})
+    with pytest.raises(cst.ConststnError) as e:
+        cst.plan(text, ops, fusion=[2, 2, 0], options={"generic_densify": 0})
+    assert e.value.status_name == "EUNSUPPORTED"
+    big = cst.build_csf([torch.zeros(1, dtype=torch.int32).cuda()] * 3, torch.ones(1, dtype=torch.float64).cuda(), (R, P, 1 << 30), [0, 1, 2])
+    with pytest.raises(cst.ConststnError) as e:       # 5 x 7 x 2^30 doubles: beyond the bound on dense copies
+        cst.plan("T[r,j,i] = A2[r,j,p] * B2[r,p,i] | r,j,p,i", [("A2", ops[1][1]), ("B2", big)])
+    assert "generic_max_gb" in str(e.value)
+
+
 def test_generic_refuses_what_it_cannot_store():
     # a Khatri-Rao product over two non-root levels is not a CSF prefix: held dense, 2 GB here
     dims = (20, 4000, 4000)
