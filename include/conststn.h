@@ -79,7 +79,7 @@ typedef void *conststn_stream;                    /* a hipStream_t (NULL = the d
  *   vals    fp64[nnz]           aligned with the last level (nodes_{order-1} = nnz)
  * No explicit root node: the root's children are all nodes of level 0.
  *
- * Errors: EINVAL, ERANGE, EDUP, EUNSUPPORTED (packed sort key wider than 64 bits), ENOMEM, EHIP.
+ * Errors: EINVAL, ERANGE, EDUP, EUNSUPPORTED (the packed coordinate tuple does not fit two 64-bit sort keys), ENOMEM, EHIP.
  */
 conststn_status conststn_build_csf(int order, const int64_t *dims, int64_t nnz,
                                    const int32_t *const *coords, const double *vals,

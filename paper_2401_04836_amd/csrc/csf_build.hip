@@ -2,7 +2,8 @@
 //
 // Steps, all on the device:
 //   1. pack each coordinate tuple, permuted into level order, into one 64-bit key (outermost
-//      level in the most significant bits) and check ranges;
+//      level in the most significant bits) and check ranges; tuples that need 65 to 128 bits get a
+//      second, more significant word holding the outer levels (no level straddles the two words);
 //   2. stable radix sort of (key, original position) -- lexicographic order in mode_order
 //      (own LSD sort, 8 bits per pass, see below);
 //   3. per tile, count for every level the positions where the key prefix of that level
@@ -24,7 +25,8 @@ constexpr int kTile = kTileThreads * kItems;
 
 struct Levels {
     int order;
-    int shift[CONSTSTN_MAX_ORDER];          // bit offset of the level's field inside the key
+    int word[CONSTSTN_MAX_ORDER];           // 0: the level's field lies in the low key word, 1: in the high one
+    int shift[CONSTSTN_MAX_ORDER];          // bit offset of the level's field inside its word
     uint64_t mask[CONSTSTN_MAX_ORDER];      // field mask (after shifting)
     int64_t dim[CONSTSTN_MAX_ORDER];        // extent of the mode at this level
     const int32_t *coord[CONSTSTN_MAX_ORDER];
@@ -39,22 +41,48 @@ __device__ __forceinline__ uint64_t prefix_of(uint64_t key, int shift) {
     return shift >= 64 ? 0 : (key >> shift);
 }
 
+// keys_hi = nullptr for keys of one word
 __global__ void __launch_bounds__(256)
-pack_keys_kernel(int64_t nnz, Levels lv, uint64_t *keys, uint32_t *payload, int *flags) {
+pack_keys_kernel(int64_t nnz, Levels lv, uint64_t *keys, uint64_t *keys_hi, uint32_t *payload, int *flags) {
     int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     const int64_t stride = int64_t(gridDim.x) * blockDim.x;
     bool bad = false;
     for (; n < nnz; n += stride) {
-        uint64_t key = 0;
+        uint64_t key = 0, hi = 0;
         for (int l = 0; l < lv.order; ++l) {
             int32_t c = lv.coord[l][n];
             if (c < 0 || int64_t(c) >= lv.dim[l]) { bad = true; c = 0; }
-            if (lv.shift[l] < 64) key |= uint64_t(uint32_t(c)) << lv.shift[l];
+            if (lv.shift[l] < 64) {
+                if (lv.word[l]) hi |= uint64_t(uint32_t(c)) << lv.shift[l];
+                else key |= uint64_t(uint32_t(c)) << lv.shift[l];
+            }
         }
         keys[n] = key;
+        if (keys_hi) keys_hi[n] = hi;
         payload[n] = uint32_t(n);
     }
     if (bad) atomicOr(&flags[0], 1);
+}
+
+// out[i] = in[index[i]]
+__global__ void __launch_bounds__(256)
+gather_u64_kernel(int64_t n, const uint64_t *__restrict__ in, const uint32_t *__restrict__ index, uint64_t *__restrict__ out) {
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) out[i] = in[index[i]];
+}
+
+// A two-word key (hi = 0 throughout for keys of one word).  The prefix of level l is every bit from the
+// level's field upwards: inside the high word for a level stored there, the whole high word plus the
+// upper part of the low word otherwise.
+struct Key2 { uint64_t hi, lo; };
+template <bool WIDE>
+__device__ __forceinline__ Key2 load_key(const uint64_t *keys, const uint64_t *keys_hi, int64_t n) {
+    return Key2{WIDE ? keys_hi[n] : 0, keys[n]};
+}
+template <bool WIDE>
+__device__ __forceinline__ bool same_prefix(const Levels &lv, int l, Key2 a, Key2 b) {
+    if (WIDE && lv.word[l]) return prefix_of(a.hi, lv.shift[l]) == prefix_of(b.hi, lv.shift[l]);
+    return (!WIDE || a.hi == b.hi) && prefix_of(a.lo, lv.shift[l]) == prefix_of(b.lo, lv.shift[l]);
 }
 
 __device__ __forceinline__ unsigned wave_sum(unsigned v) {
@@ -63,24 +91,25 @@ __device__ __forceinline__ unsigned wave_sum(unsigned v) {
 }
 
 // For every level the number of node heads inside each tile; leaf-level non-heads are duplicates.
+template <bool WIDE>
 __global__ void __launch_bounds__(kTileThreads)
-count_heads_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
+count_heads_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys, const uint64_t *__restrict__ keys_hi,
                    unsigned *__restrict__ tile_counts, int64_t ntiles, int *flags) {
     __shared__ unsigned wsum[CONSTSTN_MAX_ORDER][kTileThreads / 64];
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile + int64_t(threadIdx.x) * kItems;
     unsigned cnt[CONSTSTN_MAX_ORDER];
     for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) cnt[l] = 0;
-    uint64_t prev = 0;
+    Key2 prev{0, 0};
     bool have_prev = false;
-    if (base > 0 && base <= nnz) { prev = keys[base - 1]; have_prev = true; }
+    if (base > 0 && base <= nnz) { prev = load_key<WIDE>(keys, keys_hi, base - 1); have_prev = true; }
     bool dup = false;
     for (int i = 0; i < kItems; ++i) {
         const int64_t n = base + i;
         if (n >= nnz) break;
-        const uint64_t k = keys[n];
+        const Key2 k = load_key<WIDE>(keys, keys_hi, n);
         for (int l = 0; l < lv.order; ++l) {
-            const bool head = !have_prev || prefix_of(k, lv.shift[l]) != prefix_of(prev, lv.shift[l]);
+            const bool head = !have_prev || !same_prefix<WIDE>(lv, l, k, prev);
             cnt[l] += head ? 1u : 0u;
             if (l == lv.order - 1 && !head) dup = true;
         }
@@ -258,29 +287,30 @@ __device__ __forceinline__ unsigned block_exclusive_scan(unsigned v, unsigned *w
 
 // Rank heads and write the level arrays.  A head at level l is also a head at every deeper
 // level, so its child pointer is simply its own rank one level down.
+template <bool WIDE>
 __global__ void __launch_bounds__(kTileThreads)
-emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
+emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys, const uint64_t *__restrict__ keys_hi,
                    const uint32_t *__restrict__ payload, const double *__restrict__ vals_in,
                    const int64_t *__restrict__ tile_offsets, int64_t ntiles, LevelOut out,
                    double *__restrict__ vals_out, int has_dups) {
     __shared__ unsigned wtot[kTileThreads / 64];
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile + int64_t(threadIdx.x) * kItems;
-    uint64_t k[kItems];
+    Key2 k[kItems];
     unsigned headbits[kItems];                       // bit l set: head at level l
-    uint64_t prev = 0;
+    Key2 prev{0, 0};
     bool have_prev = false;
-    if (base > 0 && base <= nnz) { prev = keys[base - 1]; have_prev = true; }
+    if (base > 0 && base <= nnz) { prev = load_key<WIDE>(keys, keys_hi, base - 1); have_prev = true; }
     unsigned cnt[CONSTSTN_MAX_ORDER];
     for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) cnt[l] = 0;
     for (int i = 0; i < kItems; ++i) {
         const int64_t n = base + i;
         headbits[i] = 0;
-        k[i] = 0;
+        k[i] = Key2{0, 0};
         if (n < nnz) {
-            k[i] = keys[n];
+            k[i] = load_key<WIDE>(keys, keys_hi, n);
             for (int l = 0; l < lv.order; ++l) {
-                const bool head = !have_prev || prefix_of(k[i], lv.shift[l]) != prefix_of(prev, lv.shift[l]);
+                const bool head = !have_prev || !same_prefix<WIDE>(lv, l, k[i], prev);
                 if (head) { headbits[i] |= 1u << l; cnt[l]++; }
             }
             prev = k[i];
@@ -296,7 +326,8 @@ emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
         if (n >= nnz) break;
         for (int l = 0; l < lv.order; ++l) {
             if (headbits[i] & (1u << l)) {
-                out.idx[l][pos[l]] = int32_t((lv.shift[l] >= 64 ? 0 : (k[i] >> lv.shift[l])) & lv.mask[l]);
+                const uint64_t w = (WIDE && lv.word[l]) ? k[i].hi : k[i].lo;
+                out.idx[l][pos[l]] = int32_t((lv.shift[l] >= 64 ? 0 : (w >> lv.shift[l])) & lv.mask[l]);
                 if (l < last) out.ptr[l][pos[l]] = pos[l + 1];
             }
         }
@@ -305,7 +336,7 @@ emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys,
             // (the sort is stable); without duplicates the run has length one
             double s = vals_in[payload[n]];
             if (has_dups)
-                for (int64_t m = n + 1; m < nnz && keys[m] == k[i]; ++m) s += vals_in[payload[m]];
+                for (int64_t m = n + 1; m < nnz && keys[m] == k[i].lo && (!WIDE || keys_hi[m] == k[i].hi); ++m) s += vals_in[payload[m]];
             vals_out[pos[last]] = s;
         }
         for (int l = 0; l < lv.order; ++l)
@@ -333,16 +364,21 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
         lv.dim[l] = dims[m];
         lv.coord[l] = coords[m];
     }
-    if (total_bits > 64) {
-        set_error("packed coordinate key needs %d bits; only keys up to 64 bits are implemented",
-                  total_bits);
-        return CONSTSTN_EUNSUPPORTED;
-    }
-    int sh = 0;
+    // The innermost levels fill the low word as far as whole fields fit, the others the high word.
+    int sh = 0, lo_bits = 0, hi_bits = 0;
+    bool in_hi = false;
     for (int l = order - 1; l >= 0; --l) {
+        if (!in_hi && sh + bits[l] > 64) { in_hi = true; lo_bits = sh; sh = 0; }
+        lv.word[l] = in_hi ? 1 : 0;
         lv.shift[l] = sh;
         lv.mask[l] = bits[l] >= 64 ? ~uint64_t(0) : ((uint64_t(1) << bits[l]) - 1);
         sh += bits[l];
+    }
+    if (in_hi) hi_bits = sh; else lo_bits = sh;
+    const bool wide = in_hi;
+    if (hi_bits > 64) {
+        set_error("packed coordinate key needs %d bits in fields that do not fit two 64-bit words", total_bits);
+        return CONSTSTN_EUNSUPPORTED;
     }
 
     csf->order = order;
@@ -378,15 +414,40 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     CST_TRY(dflags.alloc(2));
     CST_HIP(hipMemsetAsync(dflags.p, 0, 2 * sizeof(int), stream));
 
+    DevBuf<uint64_t> lo_orig, hi_orig;                 // two-word keys only: the words in input order
+    if (wide) {
+        CST_TRY(lo_orig.alloc(nnz));
+        CST_TRY(hi_orig.alloc(nnz));
+    }
     {
         const int64_t blocks = std::min<int64_t>(div_up(nnz, 256), 65536);
-        pack_keys_kernel<<<dim3(unsigned(blocks)), dim3(256), 0, stream>>>(nnz, lv, keys_a.p, pay_a.p, dflags.p);
+        pack_keys_kernel<<<dim3(unsigned(blocks)), dim3(256), 0, stream>>>(nnz, lv, wide ? lo_orig.p : keys_a.p,
+                                                                          wide ? hi_orig.p : nullptr, pay_a.p, dflags.p);
         CST_HIP(hipGetLastError());
     }
 
-    const uint64_t *skeys = keys_a.p;
+    const uint64_t *skeys = keys_a.p, *skeys_hi = nullptr;
     const uint32_t *spay = pay_a.p;
-    CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, total_bits, stream, &skeys, &spay));
+    if (!wide) {
+        CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, total_bits, stream, &skeys, &spay));
+    } else {
+        // least significant word first: sort (low word, position), bring the high words into that order, sort
+        // again by the high word (stable), then fetch the low words in the final order
+        const unsigned gb = unsigned(div_up(nnz, 256));
+        CST_HIP(hipMemcpyAsync(keys_a.p, lo_orig.p, size_t(nnz) * sizeof(uint64_t), hipMemcpyDeviceToDevice, stream));
+        CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, lo_bits, stream, &skeys, &spay));
+        uint64_t *k_free = skeys == keys_a.p ? keys_b.p : keys_a.p, *k_used = skeys == keys_a.p ? keys_a.p : keys_b.p;
+        uint32_t *p_used = spay == pay_a.p ? pay_a.p : pay_b.p, *p_free = spay == pay_a.p ? pay_b.p : pay_a.p;
+        gather_u64_kernel<<<dim3(gb), dim3(256), 0, stream>>>(nnz, hi_orig.p, p_used, k_free);
+        CST_HIP(hipGetLastError());
+        const uint64_t *shi = nullptr;
+        CST_TRY(radix_sort_pairs_u64(k_free, k_used, p_used, p_free, nnz, hi_bits, stream, &shi, &spay));
+        uint64_t *lo_sorted = shi == k_free ? k_used : k_free;
+        gather_u64_kernel<<<dim3(gb), dim3(256), 0, stream>>>(nnz, lo_orig.p, spay, lo_sorted);
+        CST_HIP(hipGetLastError());
+        skeys = lo_sorted;
+        skeys_hi = shi;
+    }
 
     const int64_t ntiles = div_up(nnz, kTile);
     DevBuf<unsigned> tile_counts;
@@ -394,8 +455,12 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     CST_TRY(tile_counts.alloc(size_t(ntiles) * order));
     CST_TRY(tile_offsets.alloc(size_t(ntiles) * order));
     CST_TRY(totals.alloc(CONSTSTN_MAX_ORDER));
-    count_heads_kernel<<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
-        nnz, lv, skeys, tile_counts.p, ntiles, dflags.p);
+    if (wide)
+        count_heads_kernel<true><<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
+            nnz, lv, skeys, skeys_hi, tile_counts.p, ntiles, dflags.p);
+    else
+        count_heads_kernel<false><<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
+            nnz, lv, skeys, nullptr, tile_counts.p, ntiles, dflags.p);
     CST_HIP(hipGetLastError());
     scan_tiles_kernel<<<dim3(unsigned(order)), dim3(1024), 0, stream>>>(tile_counts.p, tile_offsets.p,
                                                                       ntiles, totals.p);
@@ -427,8 +492,12 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     CST_TRY(csf->vals.alloc(size_t(htotals[order - 1])));
     csf->nnz = htotals[order - 1];
 
-    emit_levels_kernel<<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
-        nnz, lv, skeys, spay, vals, tile_offsets.p, ntiles, lo, csf->vals.p, hflags[1]);
+    if (wide)
+        emit_levels_kernel<true><<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
+            nnz, lv, skeys, skeys_hi, spay, vals, tile_offsets.p, ntiles, lo, csf->vals.p, hflags[1]);
+    else
+        emit_levels_kernel<false><<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
+            nnz, lv, skeys, nullptr, spay, vals, tile_offsets.p, ntiles, lo, csf->vals.p, hflags[1]);
     CST_HIP(hipGetLastError());
     close_ptrs_kernel<<<dim3(1), dim3(64), 0, stream>>>(lo, order, totals.p);
     CST_HIP(hipGetLastError());

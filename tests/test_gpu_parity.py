@@ -35,6 +35,74 @@ def test_csf_bit_exact_every_mode_order(dims, nnz):
         csf.destroy()
 
 
+@pytest.mark.parametrize("dims,nnz", [(((1 << 22) + 3, (1 << 22) + 1, (1 << 25) + 7), 30_011),        # 72 key bits
+                                      (((1 << 20) + 1,) * 4, 9_001),                                   # 84
+                                      (((1 << 30) + 5, 3, (1 << 30) + 9, (1 << 29) + 1, 7), 5_003)])   # 31+2+31+30+3 = 97
+def test_csf_keys_of_two_words(dims, nnz):
+    """Coordinate tuples that do not fit one 64-bit sort key (a tensor the size of FROSTT's largest needs 69
+    bits): the outer levels go to a second key word.  Clustered coordinates so that every level has nodes
+    with several children, plus duplicates of one tuple for the coalescing path."""
+    rng = np.random.default_rng(17)
+    order = len(dims)
+    coords = []
+    for m, d in enumerate(dims):
+        pool = np.unique(rng.integers(0, d, size=max(2, min(40, d))))           # few distinct values per mode, spread over its range
+        pool[-1] = d - 1
+        coords.append(pool[rng.integers(0, pool.size, size=nnz)].astype(np.int64))
+    key = np.stack(coords, 1)
+    _, first = np.unique(key, axis=0, return_index=True)
+    coords = [c[np.sort(first)].astype(np.int32) for c in coords]
+    n = coords[0].size
+    vals = rng.normal(size=n)
+    dc = [torch.from_numpy(c).cuda() for c in coords]
+    dv = torch.from_numpy(vals).cuda()
+    orders = list(itertools.permutations(range(order))) if order <= 3 else [tuple(range(order)), tuple(reversed(range(order))), (1, 3, 0, 2, 4)[:order] if order == 5 else (2, 0, 3, 1)]
+    for mo in orders:
+        _say("csf dims=%s mode_order=%s (%d nonzeros)" % (dims, mo, n))
+        csf = cst.build_csf(dc, dv, dims, list(mo))
+        check_csf_bit_exact(csf, coords, vals, dims, mo)
+        csf.destroy()
+    # the same tuple three times: refused as a set, summed in input order with the flag
+    dup_c = [torch.cat([c, c[:1], c[:1]]) for c in dc]
+    dup_v = torch.cat([dv, dv[:1] * 2, dv[:1] * 4])
+    with pytest.raises(cst.ConststnError) as e:
+        cst.build_csf(dup_c, dup_v, dims, list(range(order)))
+    assert e.value.status_name == "EDUP"
+    csf = cst.build_csf(dup_c, dup_v, dims, list(range(order)), flags=cst.COALESCE_DUPS)
+    vals2 = vals.copy()
+    vals2[0] = (vals[0] + 2 * vals[0]) + 4 * vals[0]
+    check_csf_bit_exact(csf, coords, vals2, dims, tuple(range(order)))
+    with pytest.raises(cst.ConststnError) as e:           # 5 x 31 bits: the outer fields alone exceed a word
+        cst.build_csf([c[:4] for c in dc[:1]] * 5, dv[:4], ((1 << 30) + 5,) * 5, [0, 1, 2, 3, 4])
+    assert e.value.status_name == "EUNSUPPORTED"
+
+
+def test_mttkrp_on_a_tensor_with_two_word_keys():
+    """The contraction kernels read the level arrays only: a CSF built from 72-bit tuples runs like any other."""
+    dims = ((1 << 22) + 3, (1 << 22) + 1, (1 << 25) + 7)
+    rng = np.random.default_rng(23)
+    nnz = 20_000
+    coords = [rng.integers(0, 300, size=nnz) * (d // 300) for d in dims]
+    key = np.stack(coords, 1)
+    _, first = np.unique(key, axis=0, return_index=True)
+    coords = [c[first].astype(np.int32) for c in coords]
+    vals = rng.normal(size=coords[0].size)
+    csf = cst.build_csf([torch.from_numpy(c).cuda() for c in coords], torch.from_numpy(vals).cuda(), dims, [0, 1, 2])
+    B = (torch.rand(dims[1], 4, generator=torch.Generator().manual_seed(1), dtype=torch.float64) * 2 - 1)
+    C = (torch.rand(dims[2], 4, generator=torch.Generator().manual_seed(2), dtype=torch.float64) * 2 - 1)
+    pl = cst.plan(S.MTTKRP3, [("X", csf), ("C", C.cuda()), ("B", B.cuda())], flags=cst.OUT_COMPACT)
+    out = cst.execute(pl, [C.cuda(), B.cuda()]).reshape(pl.n_rows, 4).cpu().numpy()
+    rows = pl.output_rows().cpu().numpy().astype(np.int64)
+    want = oracle.mttkrp3(coords, vals, dims, B.numpy(), C.numpy(), 0)
+    S_abs = oracle.mttkrp3_abs(coords, vals, dims, B.numpy(), C.numpy(), 0)
+    np.testing.assert_array_equal(rows, np.unique(coords[0]))
+    keep = np.zeros(dims[0], dtype=bool)
+    keep[rows] = True
+    assert not S_abs[~keep].any()
+    want, S_abs = want[rows], S_abs[rows]
+    assert oracle.rel_err(out, want, S_abs) <= TOL
+
+
 def test_csf_spans_many_tiles_with_ragged_tail():
     wl = w.make(2, small=True)                       # 150 001 nonzeros: 74 tiles, ragged tail
     X = wl.sparse["X"]
@@ -241,8 +309,18 @@ def test_unsupported_and_illegal_plans():
     # legal but unfused: none of the tuned kernels, so the generic executor takes it
     pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], fusion=[0, 0])
     assert "family=generic" in pl.describe()
-    with pytest.raises(cst.ConststnError) as e:      # two CSF operands outside the (U.V).W form
-        cst.plan("Z[i,j] = X[i,j,k] * W[i,j,k] | i,j,k", [("X", csf), ("W", csf)])
+    # two CSF operands outside the tuned sparse x sparse forms: the generic executor walks one and keeps a
+    # dense copy of the other (here the same tensor under two names: Z_ij = sum_k X_ijk^2)
+    text2 = "Z[i,j] = X[i,j,k] * W[i,j,k] | i,j,k"
+    pl = cst.plan(text2, [("X", csf), ("W", csf)])
+    assert "family=generic" in pl.describe() and "dense_copies_of_csf_operands=1" in pl.describe()
+    got = cst.execute(pl, []).cpu().numpy().reshape(X.dims[0], X.dims[1])
+    c, v = X.numpy()
+    want = np.zeros((X.dims[0], X.dims[1]))
+    np.add.at(want, (c[0], c[1]), v * v)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=0)
+    with pytest.raises(cst.ConststnError) as e:
+        cst.plan(text2, [("X", csf), ("W", csf)], options={"generic_densify": 0})
     assert e.value.status_name == "EUNSUPPORTED"
     with pytest.raises(cst.ConststnError) as e:      # loop order against the CSF layout
         cst.plan(S.TTMC3.replace("| i,j,k,s", "| j,i,k,s"), [("X", csf), ("U3", U3), ("U2", U2)])
