@@ -95,6 +95,12 @@ conststn_status conststn_csf_info(const conststn_csf_t *csf, int *order, int64_t
 conststn_status conststn_csf_export(const conststn_csf_t *csf, int level, const int32_t **idx,
                                     const int64_t **ptr, int64_t *nodes, const double **vals);
 
+/* Debugging aid: checks on the device every invariant of the array layout above (indices inside their
+ * mode extents, ptr[l][0] = 0, every node with at least one child, ptr[l][nodes_l] = nodes_{l+1},
+ * children of one parent and the roots strictly ascending).  CONSTSTN_OK, or CONSTSTN_EINVAL with the
+ * violated invariants named in conststn_last_error().  Reads only inside the arrays' sizes. */
+conststn_status conststn_csf_check(const conststn_csf_t *csf);
+
 void conststn_csf_destroy(conststn_csf_t *csf);
 
 /* ------------------------------------------------------------------------------------------
@@ -236,6 +242,15 @@ conststn_status conststn_plan_output_rows(const conststn_plan_t *plan, const int
  * structure, in leaf order.  Borrowed: valid until the plan is destroyed; never pass it to
  * conststn_csf_destroy.  CONSTSTN_EINVAL when the plan's result is dense. */
 conststn_status conststn_plan_output_csf(const conststn_plan_t *plan, const conststn_csf_t **structure);
+
+/* Debugging aid: the kernels trust the tables a plan holds (an index out of range there is a memory
+ * fault, not an error code).  This pass checks, on the device, that every table of an order-3 MTTKRP
+ * or TTMc plan (Sec. 5.2, 5.3) stays inside the arrays it indexes: chunk tables against the pointer arrays,
+ * the re-encoded leaf stream (LDS slots, factor rows, end-of-fiber / end-of-slice marks), row
+ * descriptors, items, K-steps and workgroup batches of the TTMc kernels, and the tensor the kernels
+ * walk (conststn_csf_check of it).  CONSTSTN_OK; CONSTSTN_EINVAL with the violations named;
+ * CONSTSTN_EUNSUPPORTED for plans of other kernel families. */
+conststn_status conststn_plan_check(const conststn_plan_t *plan);
 
 /* Text description of the lowered plan (kernel family, loop tree in forall/where form,
  * order of each intermediate after fusion).  Writes at most len-1 characters + NUL. */

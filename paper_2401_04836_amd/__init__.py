@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = [
     "conststn_plan_output_rows", "conststn_plan_output_csf", "conststn_plan_describe", "conststn_plan_destroy",
     "conststn_execute", "conststn_last_error", "conststn_version",
     "conststn_plan_profile", "conststn_plan_kernel_times", "conststn_measure_peak", "conststn_execute_static",
+    "conststn_csf_check", "conststn_plan_check",
 ]
 
 
@@ -77,6 +78,8 @@ def _load():
     L.conststn_plan_profile.argtypes = [vp, ctypes.c_int]
     L.conststn_plan_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.c_int, ip]
     L.conststn_measure_peak.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double)]
+    L.conststn_csf_check.argtypes = [vp]
+    L.conststn_plan_check.argtypes = [vp]
     for name in EXPORTED_SYMBOLS:
         getattr(L, name)
     return L
@@ -159,6 +162,10 @@ class CSF:
         tp = _borrow(ptr.value, n + 1, torch.int64, self.device, self) if ptr.value else None
         tv = _borrow(vals.value, n, torch.float64, self.device, self) if vals.value else None
         return ti, tp, tv
+
+    def check(self):
+        """conststn_csf_check: every invariant of the level arrays, checked on the device (raises on a violation)."""
+        _check(_lib.conststn_csf_check(self._h))
 
     def nodes(self, level):
         nodes = ctypes.c_int64()
@@ -282,6 +289,10 @@ class Plan:
         buf = ctypes.create_string_buffer(1 << 16)
         _check(_lib.conststn_plan_describe(self._h, buf, len(buf)))
         return buf.value.decode()
+
+    def check(self):
+        """conststn_plan_check: the plan's tables stay inside the arrays they index (order-3 MTTKRP / TTMc plans)."""
+        _check(_lib.conststn_plan_check(self._h))
 
     def output_rows(self):
         p, n = ctypes.c_void_p(), ctypes.c_int64()

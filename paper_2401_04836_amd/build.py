@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconststn.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "schedule.cpp", "search.cpp", "csf_build.hip", "partition.hip", "kernels_mttkrp3.hip",
-           "kernels_ttmc3.hip", "kernels_ttmc4.hip", "kernels_sptn3.hip", "kernels_spchain3.hip", "kernels_sppair4.hip", "generic.hip", "peaks.hip"]
+           "kernels_ttmc3.hip", "kernels_ttmc4.hip", "kernels_sptn3.hip", "kernels_spchain3.hip", "kernels_sppair4.hip", "generic.hip", "peaks.hip", "check.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

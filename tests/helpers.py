@@ -29,18 +29,23 @@ def check_csf_bit_exact(csf, coo_np, vals_np, dims, mode_order):
 
 
 def run_gpu(wl, flags=0, check_csf=False, options=None):
-    """Build CSF(s), plan, execute.  Returns (out tensor [rows, ...], plan, csf handles)."""
+    """Build CSF(s), plan, execute.  Returns (out tensor [rows, ...], plan, csf handles).  Every CSF goes
+    through the library's own invariant check and every order-3 MTTKRP / TTMc plan through its table
+    check before it is executed."""
     dev = "cuda"
     if wl.kind in ("ttmc3", "ttmc4", "mttkrp3"):
         X = wl.sparse["X"]
         coords, vals = to_dev(X, dev)
         csf = cst.build_csf(coords, vals, X.dims, list(range(X.order)))
+        csf.check()
         if check_csf:
             c, v = X.numpy()
             check_csf_bit_exact(csf, c, v, X.dims, list(range(X.order)))
         if wl.kind == "ttmc3":
             U2, U3 = wl.dense["U2"].to(dev), wl.dense["U3"].to(dev)
             pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=flags, options=options)
+            if "family=ttmc3" in pl.describe():
+                pl.check()
             out = cst.execute(pl, [U3, U2])
             shape = (pl.n_rows, U2.shape[1], U3.shape[1])
         elif wl.kind == "ttmc4":
@@ -51,6 +56,8 @@ def run_gpu(wl, flags=0, check_csf=False, options=None):
         else:
             B, C = wl.dense["B"].to(dev), wl.dense["C"].to(dev)
             pl = cst.plan(S.MTTKRP3, [("X", csf), ("C", C), ("B", B)], flags=flags, options=options)
+            if "family=mttkrp3" in pl.describe():
+                pl.check()
             out = cst.execute(pl, [C, B])
             shape = (pl.n_rows, B.shape[1])
         torch.cuda.synchronize()
@@ -61,6 +68,8 @@ def run_gpu(wl, flags=0, check_csf=False, options=None):
         wc, wv = to_dev(W, dev)
         ucsf = cst.build_csf(uc, uv, U.dims, [0, 2, 1])          # i > k > j
         wcsf = cst.build_csf(wc, wv, W.dims, [0, 1, 2])          # k > l > m
+        ucsf.check()
+        wcsf.check()
         if check_csf:
             c, v = U.numpy()
             check_csf_bit_exact(ucsf, c, v, U.dims, [0, 2, 1])

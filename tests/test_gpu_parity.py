@@ -204,6 +204,30 @@ def test_mttkrp_hot_and_cold_passes_in_one_launch_or_two(dual):
     assert compare(out, want, S_abs) <= TOL
 
 
+def test_table_check_covers_what_it_says():
+    """The table check runs inside run_gpu for every MTTKRP / TTMc case; here: other families say so, the
+    private re-rooted copy is checked like the caller's tensor, and the sparse-result structure handed out by a
+    plan passes the CSF check."""
+    wl = w.make(3, small=True)
+    _, pl, _ = run_gpu(wl)
+    with pytest.raises(cst.ConststnError) as e:
+        pl.check()
+    assert e.value.status_name == "EUNSUPPORTED"
+    wl = w.make(2, small=True)
+    X = wl.sparse["X"]
+    dc, dv = to_dev(X)
+    csf = cst.build_csf(dc, dv, X.dims, [0, 1, 2])
+    A, C = wl.dense["B"].new_ones(X.dims[0], 32).cuda(), wl.dense["C"].cuda()
+    pl = cst.plan("T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; M[j,r] = T[i,j,r] * A[i,r] | i,j,r", [("X", csf), ("C", C), ("A", A)])
+    assert "private copy" in pl.describe()
+    pl.check()
+    for opts in ({"mttkrp_split": 0}, {"mttkrp_dual": 0}, {"ttmc3_stream": 0}):
+        for cid in (2, 5):
+            _, pl, csfs = run_gpu(w.make(cid, small=True), options=opts)
+            pl.check()
+            csfs[0].check()
+
+
 def test_plan_options_are_checked():
     wl = w.make(1)
     X = wl.sparse["X"]

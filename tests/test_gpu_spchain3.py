@@ -198,8 +198,18 @@ def test_plans_outside_the_family_are_refused():
     wl = make_lattice_chain("lat5", 4101, 5, 3, 6, 1.5, 2.0, 1.5, 2.5)
     I, C, P = (wl.sparse[k] for k in "ICP")
     hI, hC, hP = _csf(I, [0, 1, 2]), _csf(C, [1, 0]), _csf(P, [1, 0])
+    # fused on K only (depth 1): not the tuned kernel's schedule.  The generic executor takes it with dense
+    # copies of C and P and a DENSE result E[K,i,m]; without them it is refused.
     with pytest.raises(cst.ConststnError):
-        # fused on K only (depth 1): no kernel for that
-        cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)], fusion=[1, 0])
+        cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)], fusion=[1, 0], options={"generic_densify": 0})
+    pl = cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)], fusion=[1, 0])
+    assert "family=generic" in pl.describe() and "dense_copies_of_csf_operands=2" in pl.describe(), pl.describe()
+    dims = wl.params["dims"]
+    got = cst.execute(pl, []).cpu().numpy().reshape(dims[0], dims[1], dims[3])
+    ref = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=range(dims[0]))
+    for K in range(dims[0]):
+        E, S_abs, N = ref[K]
+        assert not got[K][~N].any()                        # no term, exact zero
+        assert oracle.rel_err(got[K], E, S_abs) <= TOL
     with pytest.raises(cst.ConststnError):
         cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)], flags=cst.OUT_COMPACT)
