@@ -65,6 +65,11 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+# seconds and algorithmic bytes of the CSF builds alone of the configuration being set up (the builders
+# that time them fill it in; "csf_build" of the record then carries a roofline of its own)
+CSF_ONLY = {}
+
+
 def build_mttkrp(cst, S, wl, dev):
     X = wl.sparse["X"]
     coords = [c.to(dev) for c in X.coords]
@@ -74,6 +79,10 @@ def build_mttkrp(cst, S, wl, dev):
     t0 = time.perf_counter()
     csf0 = cst.build_csf(coords, vals, X.dims, [0, 1, 2])
     csf2 = cst.build_csf(coords, vals, X.dims, [2, 1, 0])
+    torch.cuda.synchronize()
+    CSF_ONLY["seconds"] = time.perf_counter() - t0
+    # bytes a build has to move: the coordinate lists and values in, the level arrays out
+    CSF_ONLY["bytes"] = sum((4 * X.order + 8) * X.nnz + 12 * sum(c.nodes(l) for l in range(X.order)) for c in (csf0, csf2))
     pl0 = cst.plan(S.MTTKRP3, [("X", csf0), ("C", C), ("B", B)], options=PLAN_OPTIONS)
     pl2 = cst.plan("T[k,j,r] = X[k,j,i] * A[i,r] | k,j,i,r ; M[k,r] = T[k,j,r] * B[j,r] | k,j,r",
                    [("X", csf2), ("A", A), ("B", B)], options=PLAN_OPTIONS)
@@ -124,6 +133,9 @@ def build_chain(cst, S, wl, dev, compact):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     csf = cst.build_csf(coords, vals, X.dims, list(range(X.order)))
+    torch.cuda.synchronize()
+    CSF_ONLY["seconds"] = time.perf_counter() - t0
+    CSF_ONLY["bytes"] = (4 * X.order + 8) * X.nnz + 12 * sum(csf.nodes(l) for l in range(X.order))
     flags = cst.OUT_COMPACT if compact else 0
     if wl.kind == "ttmc3":
         U2, U3 = wl.dense["U2"].to(dev), wl.dense["U3"].to(dev)
@@ -382,6 +394,7 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
     t0 = time.perf_counter()
     wl = workloads.make(cid, device=dev, small=args.small)
     torch.cuda.synchronize()
+    CSF_ONLY.clear()
     log("generated config %d (%s) in %.1f s: %s" % (
         cid, wl.kind, time.perf_counter() - t0, {k: (v.dims, v.nnz) for k, v in wl.sparse.items()}))
 
@@ -458,7 +471,12 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
         "ms_per_step": ms_per_step, "nnz_per_step": nnz_per_step, "nnz_per_s": nnz_per_step / (dt / args.steps),
         "gflops": flops_step / (dt / args.steps) / 1e9,
         "fp64_frac": flops_step / (dt / args.steps) / 1e12 / FP64_PEAK_TFLOPS,
-        "csf_build": {"seconds": build_s, "nnz_per_s": nnz_per_step / build_s},
+        "csf_build": dict({"seconds": build_s, "nnz_per_s": nnz_per_step / build_s,
+                           "what": "CSF build(s) + plan, once per tensor, outside the timed step"},
+                          **({"csf_only_seconds": CSF_ONLY["seconds"], "csf_only_algorithmic_bytes": CSF_ONLY["bytes"],
+                              "csf_only_GBps": CSF_ONLY["bytes"] / CSF_ONLY["seconds"] / 1e9,
+                              "csf_only_hbm_frac": CSF_ONLY["bytes"] / CSF_ONLY["seconds"] / 1e9 / HBM_PEAK_GBS}
+                             if CSF_ONLY else {})),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(family, cid if plain else None),
                      "kernel": KERNEL_NAMES.get(family, family),
