@@ -121,7 +121,17 @@ def test_config2_mttkrp_full_size_both_modes():
         err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
         _say("  rel err %.3e" % err)
         assert err <= TOL
-        del pl, csf, out
+        pl.check()                                          # the plan's tables at full size
+        # the same contraction on the generic executor with the leaf-level producer inlined (segments of 512
+        # leaves, the heaviest slices added by a workgroup)
+        gen = cst.plan(sched, [("X", csf), (names[0], facs[0]), (names[1], facs[1])], options="force_generic=1")
+        assert "inlined_producers=1" in gen.describe(), gen.describe()
+        out = cst.execute(gen, list(facs)).reshape(gen.n_rows, -1)
+        torch.cuda.synchronize()
+        err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
+        _say("  generic executor, fused pair: rel err %.3e" % err)
+        assert err <= TOL
+        del pl, gen, csf, out
 
 
 def test_config2_mttkrp_other_modes_on_the_mode0_csf():
