@@ -180,6 +180,8 @@ def test_config5_ttmc3_full_size_compact():
     _say("config 5: CSF check")
     check_csf_full(csf, X.coords, X.vals, X.dims, [0, 1, 2])
     pl = cst.plan(S.TTMC3, [("X", csf), ("U3", U3), ("U2", U2)], flags=cst.OUT_COMPACT)
+    csf.check()
+    pl.check()                                              # rows, K-steps, batches and partial blocks at full size
     out = cst.execute(pl, [U3, U2]).reshape(pl.n_rows, 64, 64)
     torch.cuda.synchronize()
     rows = pl.output_rows()
