@@ -3,9 +3,11 @@
 
 A step is one pass of the fused contraction over one synthetic batch with the CSF already
 resident in HBM.  With no --config the five configurations run one after the other in one
-process (5, 2, 3, 4, 1); the headline (value, ms_per_step, roofline, cpu_baseline) is that of
-configuration 5, the largest that fits one GPU (order-3 TTMc, 140 M nonzeros, ranks 64 x 64,
-47 GB of output), and "configs" holds the same record for every configuration.  For
+process (5, 2, 3, 4, 1), followed by the two sparse-result networks of Sec. 5.1 (6: the three-index
+transformation, 7: the four-index product); the headline (value, ms_per_step, roofline,
+cpu_baseline) is that of configuration 5, the largest that fits one GPU (order-3 TTMc, 140 M
+nonzeros, ranks 64 x 64, 47 GB of output), and "configs" holds the same record for every
+configuration.  For
 configuration 2 a step is the mode-0 MTTKRP (CSF i>j>k) followed by the mode-2 MTTKRP (CSF
 k>j>i).  The CSF build (sort + pointer construction + partition) is timed separately and
 reported under "csf_build".  Prints ONE JSON line.
@@ -575,7 +577,7 @@ def main():
         log("calibration copy: 1 GiB read + 1 GiB written by one copy kernel")
         del src, dst
 
-    cids = [5, 2, 3, 4, 1] if args.config == 0 else [args.config]
+    cids = [5, 2, 3, 4, 1, 6, 7] if args.config == 0 else [args.config]
     # CPU-oracle sample, in multiply-adds' worth of nonzeros per configuration: a few seconds to about ten per
     # configuration in the five-configuration run
     cpu_budget = 400_000_000 if len(cids) == 1 else 1_200_000_000
