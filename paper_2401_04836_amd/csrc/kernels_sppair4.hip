@@ -315,6 +315,23 @@ sppair4_dense_kernel(P4Side T, const int64_t *__restrict__ row_at, int64_t n1, i
 // (i-major) the pairs an XCD works on at one time share a few i but hardly any j, and the dense rows of
 // E[j] miss L2 on almost every pair.  Instead XCD x takes the pairs with j % 8 == x, in node order: the
 // pairs of neighbouring i then meet the same few j on one XCD.
+// Cost of a pair's workgroup in matrix instructions (shared K x tiles of the block), as a key that sorts
+// the costliest first: the grid then starts its long workgroups first and fills the tail with short ones.
+__global__ void sppair4_cost_key_kernel(P4Args A, P4Out V, uint64_t *keys, uint32_t *pair) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n >= V.pairs) return;
+    const int64_t ra = V.node_a[n], rb = V.node_b[n];
+    const int64_t ta = (A.a.u_ptr[ra + 1] - A.a.u_ptr[ra] + 15) / 16, tb = (A.b.u_ptr[rb + 1] - A.b.u_ptr[rb] + 15) / 16;
+    const int64_t shared = V.k_ptr ? V.k_ptr[n + 1] - V.k_ptr[n] : 8;
+    const uint64_t cost = uint64_t(ta * tb) * uint64_t((shared + 3) / 4) + uint64_t(ta * tb);      // + write-out
+    keys[n] = ~cost & 0xffffffffffull;                    // 40 bits are plenty; ascending sort = falling cost
+    pair[n] = uint32_t(n);
+}
+__global__ void sppair4_order_fill_kernel(int64_t pairs, const uint32_t *__restrict__ sorted, int32_t *wg_pair) {
+    const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (n < pairs) wg_pair[n] = int32_t(sorted[n]);
+}
+
 __global__ void sppair4_xcd_flag_kernel(P4Out V, int x, int64_t *flag) {
     const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (n < V.pairs) flag[n] = (V.idx1[n] & 7) == x ? 1 : 0;
@@ -756,7 +773,25 @@ conststn_status build_sppair4_tables(conststn_plan_s *plan) {
     CST_HIP(hipStreamSynchronize(st));
     // workgroup order of the numeric pass (pairs < 2^31: a pair holds at least one of the nnz < 2^31 leaves)
     plan->p4_n_wg = 0;
-    if (pairs > 0 && plan->opt("sppair4_xcd", 1) == 1) {
+    if (pairs > 0 && plan->opt("sppair4_xcd", 2) == 2) {
+        // costliest first (stable: equal costs stay in node order)
+        DevBuf<uint64_t> ka, kb;
+        DevBuf<uint32_t> pa, pb;
+        CST_TRY(ka.alloc(size_t(pairs)));
+        CST_TRY(kb.alloc(size_t(pairs)));
+        CST_TRY(pa.alloc(size_t(pairs)));
+        CST_TRY(pb.alloc(size_t(pairs)));
+        sppair4_cost_key_kernel<<<p4_grid(pairs), 256, 0, st>>>(A, O, ka.p, pa.p);
+        CST_HIP(hipGetLastError());
+        const uint64_t *ks = nullptr;
+        const uint32_t *ps = nullptr;
+        CST_TRY(radix_sort_pairs_u64(ka.p, kb.p, pa.p, pb.p, pairs, 40, st, &ks, &ps));
+        plan->p4_n_wg = pairs;
+        CST_TRY(plan->p4_wg_pair.alloc(size_t(pairs)));
+        sppair4_order_fill_kernel<<<p4_grid(pairs), 256, 0, st>>>(pairs, ps, plan->p4_wg_pair.p);
+        CST_HIP(hipGetLastError());
+        CST_HIP(hipStreamSynchronize(st));
+    } else if (pairs > 0 && plan->opt("sppair4_xcd", 2) == 1) {
         DevBuf<int64_t> xflag, xrank;
         CST_TRY(xflag.alloc(size_t(pairs)));
         CST_TRY(xrank.alloc(size_t(pairs)));

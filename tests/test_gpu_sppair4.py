@@ -112,8 +112,8 @@ def test_blocks_larger_than_one_tile_group_and_many_shared_k():
 
 
 @pytest.mark.parametrize("env", [{"sppair4_rows": 2}, {"sppair4_keep": 2}, {},
-                                 {"sppair4_buffers": 1}, {"sppair4_xcd": 0}],
-                         ids=["leaf-lists", "nothing-kept", "dense-rows", "one-chunk-buffer", "node-order"])
+                                 {"sppair4_buffers": 1}, {"sppair4_xcd": 0}, {"sppair4_xcd": 1}],
+                         ids=["leaf-lists", "nothing-kept", "dense-rows", "one-chunk-buffer", "node-order", "xcd-order"])
 @pytest.mark.parametrize("n_m", [200, 300])
 def test_every_form_of_the_numeric_pass(env, n_m):
     # the chunk rows copied from dense rows (default, inner dimension <= 256), put together from leaf
