@@ -180,6 +180,7 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
  * also where W fills its 16 x 16 tiles to less than a sixteenth),
  * sptn3_waves (2), sptn3_wgs (8000), sptn3_xcd (0), spchain3_form (1; 2 = general numeric pass),
  * spchain3_local_kb (78), spchain3_pk_gb (4), sppair4_keep (1), sppair4_keep_gb (4), sppair4_rows (1),
+ * spchain3_order (1 = workgroups take the roots of the result by falling cost, 0 = in root order),
  * sppair4_rows_gb (8), sppair4_buffers (2), sppair4_xcd (2 = workgroups take the pairs by falling cost,
  * 1 = by j mod 8 per XCD, 0 = in node order). */
 conststn_status conststn_plan_options(const char *schedule, const int *fusion, int n_operands,

@@ -628,11 +628,28 @@ spchain3_pk_fill_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ flag, con
     }
 }
 
-// the descriptor of every root of E; class_of[r] = the root that opened r's class
-__global__ void spchain3_root_desc_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ flag,
-                                          const int64_t *__restrict__ block_off, ScRoot *roots) {
+// Cost of a root's workgroup in matrix instructions (T_K = C_K . I_K, then E_K = T_K . P_K), as a key that
+// sorts the costliest first: the grid starts its long workgroups first and fills the tail with short ones.
+__global__ void spchain3_cost_key_kernel(ScArgs A, ScOut E, uint64_t *keys, uint32_t *root) {
     const int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (r >= E.roots) return;
+    const int64_t a = E.root_knode[r];
+    const int64_t ns = A.nu_ptr[a + 1] - A.nu_ptr[a], nrows = A.i_ptr0[a + 1] - A.i_ptr0[a];
+    const int64_t nm = A.mu_ptr[r + 1] - A.mu_ptr[r], nn = E.ptr0[r + 1] - E.ptr0[r];
+    const int64_t tn = (nn + 15) / 16, ts = (ns + 15) / 16, tm = (nm + 15) / 16;
+    const uint64_t cost = uint64_t(tn * ts * ((nrows + 3) / 4) + tn * tm * ((ns + 3) / 4) + tn * tm);
+    keys[r] = ~cost & 0xffffffffffull;
+    root[r] = uint32_t(r);
+}
+
+// the descriptor of every root of E, written in the order the workgroups take the roots (`order`, or
+// root order when it is null); flag / block_off: the root that opened r's class of equal lists and its block
+__global__ void spchain3_root_desc_kernel(ScArgs A, ScOut E, const int64_t *__restrict__ flag,
+                                          const int64_t *__restrict__ block_off, const uint32_t *__restrict__ order,
+                                          ScRoot *roots) {
+    const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= E.roots) return;
+    const int64_t r = order ? int64_t(order[p]) : p;
     const int64_t a = E.root_knode[r];
     ScRoot R{};
     R.ns = int32_t(A.nu_ptr[a + 1] - A.nu_ptr[a]);
@@ -648,7 +665,7 @@ __global__ void spchain3_root_desc_kernel(ScArgs A, ScOut E, const int64_t *__re
     int64_t opener = r;
     while (!flag[opener]) --opener;
     R.pk = block_off[opener];
-    roots[r] = R;
+    roots[p] = R;
 }
 
 // ---- host side -------------------------------------------------------------------------------
@@ -993,7 +1010,20 @@ conststn_status build_spchain3_tables(conststn_plan_s *plan) {
                 CST_TRY(plan->sc_roots.alloc(size_t(roots) * sizeof(ScRoot)));
                 spchain3_row_tables_kernel<<<grid_for(nodes), 256, 0, st>>>(A2, O, plan->sc_e_c0.p, plan->sc_e_clen.p);
                 CST_HIP(hipGetLastError());
-                spchain3_root_desc_kernel<<<grid_for(roots), 256, 0, st>>>(A2, O, cflag.p, coff.p,
+                DevBuf<uint64_t> ka, kb;
+                DevBuf<uint32_t> ra, rb;
+                const uint32_t *order = nullptr;
+                if (plan->opt("spchain3_order", 1) == 1) {           // costliest roots first (stable)
+                    CST_TRY(ka.alloc(size_t(roots)));
+                    CST_TRY(kb.alloc(size_t(roots)));
+                    CST_TRY(ra.alloc(size_t(roots)));
+                    CST_TRY(rb.alloc(size_t(roots)));
+                    spchain3_cost_key_kernel<<<grid_for(roots), 256, 0, st>>>(A2, O, ka.p, ra.p);
+                    CST_HIP(hipGetLastError());
+                    const uint64_t *ks = nullptr;
+                    CST_TRY(radix_sort_pairs_u64(ka.p, kb.p, ra.p, rb.p, roots, 40, st, &ks, &order));
+                }
+                spchain3_root_desc_kernel<<<grid_for(roots), 256, 0, st>>>(A2, O, cflag.p, coff.p, order,
                                                                           reinterpret_cast<ScRoot *>(plan->sc_roots.p));
                 CST_HIP(hipGetLastError());
                 CST_HIP(hipStreamSynchronize(st));

@@ -23,7 +23,7 @@ bool known_plan_option(const std::string &name) {
         "ttmc3_mfma", "ttmc3_stream", "ttmc3_producers", "ttmc3_batch", "ttmc3_itemcost", "ttmc3_qn", "ttmc3_split",
         "ttmc3_rowsplit", "ttmc4_mfma", "ttmc4_split", "ttmc4_ksplit",
         "sptn3_tiled", "sptn3_waves", "sptn3_wgs", "sptn3_xcd",
-        "spchain3_form", "spchain3_local_kb", "spchain3_pk_gb",
+        "spchain3_form", "spchain3_order", "spchain3_local_kb", "spchain3_pk_gb",
         "sppair4_keep", "sppair4_keep_gb", "sppair4_rows", "sppair4_rows_gb", "sppair4_buffers", "sppair4_xcd"};
     for (const char *n : names)
         if (name == n) return true;

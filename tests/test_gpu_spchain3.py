@@ -27,11 +27,13 @@ def _csf(t, mode_order):
     return cst.build_csf([c.cuda() for c in t.coords], t.vals.cuda(), t.dims, mode_order)
 
 
-def _run(I, C, P, L=None, kernel=None):
+def _run(I, C, P, L=None, kernel=None, extra=None):
     """Returns (coords of E as three host arrays, values, plan description).  kernel: None = the
     plan's choice, "general" = the form without dense blocks, "block-local" = expect that form."""
     hI, hC, hP = _csf(I, [0, 1, 2]), _csf(C, [1, 0]), _csf(P, [1, 0])
     options = "spchain3_form=2" if kernel == "general" else None
+    if extra:
+        options = extra if options is None else options + "," + extra
     if L is None:
         pl = cst.plan(UNRESTRICTED, [("I", hI), ("C", hC), ("P", hP)], options=options)
     else:
@@ -113,6 +115,8 @@ def test_small_lattice_both_forms():
     Ks = range(dims[0])
     ref_u = spsp.chain3(_np(I), _np(C), _np(P), dims, K_values=Ks)
     ref_r = spsp.chain3(_np(I), _np(C), _np(P), dims, _np(L), K_values=Ks)
+    coords, vals, desc = _run(I, C, P, kernel="block-local", extra="spchain3_order=0")     # roots in root order
+    assert _compare(coords, vals, ref_u, dims, Ks) <= TOL
     for kernel in ("block-local", "general"):
         coords, vals, desc = _run(I, C, P, kernel=kernel)
         err = _compare(coords, vals, ref_u, dims, Ks)
