@@ -295,6 +295,21 @@ def test_inputs_indexed_by_kept_levels_and_results_with_several_sparse_indices()
     _check(got, coords, vals, "ijk", [(U3, "ks")], "ijs", {"i": 20, "j": 12, "s": 4})
 
 
+def test_fused_pair_whose_result_keeps_no_sparse_index():
+    # order-2 X: z[r] = sum_{i,k} X[i,k] C[k,r] A[i,r]; the consumer's result node is the (absent) root, so all
+    # leaves of X hang below ONE node: leaf segments and the workgroup that adds their partial sums
+    dims = (900, 700)
+    for nnz in (300, 60_000):
+        coords, vals = _tensor(421 + nnz, dims, nnz)
+        A, C = _dense(422, 900, 12), _dense(423, 700, 12)
+        text = "T[i,r] = X[i,k] * C[k,r] | i,k,r ; z[r] = T[i,r] * A[i,r] | i,r"
+        got, pl = _run(text, (coords, vals, dims), [0, 1], [("C", C), ("A", A)], (12,))
+        assert "inlined_producers=1" in pl.describe(), pl.describe()
+        _check(got, coords, vals, "ik", [(A, "ir"), (C, "kr")], "r", {"r": 12})
+        stored, _ = _run(text, (coords, vals, dims), [0, 1], [("C", C), ("A", A)], (12,), options="generic_fuse=0")
+        np.testing.assert_allclose(stored, got, rtol=0, atol=1e-9)
+
+
 def test_running_example_with_four_sparse_operands():
     # Sec. 3.1 / Fig. 4: R_ijk = A_ipq B_jpr C_kqr D_jkr as X = A.B ; Y = X.C ; R = Y.D with the layouts and loop
     # orders of the paper's constraint solution, all four tensors sparse.  The executor walks the operand
