@@ -302,16 +302,21 @@ generic_segsum_kernel(GenStmt g) {
 
 // One workgroup per node with many segments (a slice of a power-law tensor has thousands): thread
 // (s, j) adds every S-th segment's element j, S = 256 / W, then thread (0, j) adds the S sums in
-// order.  The order of addition depends on the launch shape only.
+// order.  The order of addition depends on the launch shape only.  kGenHeavyParts workgroups share a
+// node, each a contiguous range of its segments; their sums go to `heavy_sums` and a last small kernel
+// adds them in order.
+constexpr int kGenHeavyParts = 16;
 template <int W>
 __global__ void __launch_bounds__(256)
 generic_segsum_heavy_kernel(GenStmt g) {
     constexpr int S = 256 / W;
     __shared__ double part[256];
     const int64_t p = g.heavy[blockIdx.x];
-    const int64_t s0 = g.seg_ptr[p], s1 = g.seg_ptr[p + 1];
+    const int64_t a0 = g.seg_ptr[p], a1 = g.seg_ptr[p + 1];
+    const int64_t s0 = a0 + (a1 - a0) * int64_t(blockIdx.y) / kGenHeavyParts,
+                  s1 = a0 + (a1 - a0) * int64_t(blockIdx.y + 1) / kGenHeavyParts;
     const int j = int(threadIdx.x) % W, sl = int(threadIdx.x) / W;
-    const int64_t row = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
+    double *dst = g.heavy_sums + (int64_t(blockIdx.x) * kGenHeavyParts + blockIdx.y) * g.out_block;
     for (int64_t o0 = 0; o0 < g.out_block; o0 += W) {
         const int64_t o = o0 + j;
         double acc = 0.0;
@@ -323,10 +328,22 @@ generic_segsum_heavy_kernel(GenStmt g) {
             double sum = 0.0;
 #pragma unroll
             for (int k = 0; k < S; ++k) sum += part[k * W + j];
-            g.out[row * g.out_block + o] = sum;
+            dst[o] = sum;
         }
         __syncthreads();
     }
+}
+__global__ void __launch_bounds__(256)
+generic_segsum_heavy_final_kernel(GenStmt g) {
+    const int64_t gid = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (gid >= g.n_heavy * g.out_block) return;
+    const int64_t h = gid / g.out_block, o = gid - h * g.out_block;
+    double sum = 0.0;
+#pragma unroll
+    for (int k = 0; k < kGenHeavyParts; ++k) sum += g.heavy_sums[(h * kGenHeavyParts + k) * g.out_block + o];
+    const int64_t p = g.heavy[h];
+    const int64_t row = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
+    g.out[row * g.out_block + o] = sum;
 }
 
 __global__ void generic_heavy_flag_kernel(const int64_t *seg_ptr, int64_t nodes, int64_t *flag) {
@@ -840,6 +857,8 @@ conststn_status build_generic(conststn_plan_s *plan) {
                 CST_HIP(hipGetLastError());
                 CST_HIP(hipDeviceSynchronize());
                 g.n_heavy = n_heavy;
+                g.heavy_buffer = int(buffer_elems.size());
+                buffer_elems.push_back(std::max<int64_t>(n_heavy, 1) * kGenHeavyParts * g.out_block);
             }
             g.partial_buffer = int(buffer_elems.size());
             buffer_elems.push_back(n_segs * g.out_block);
@@ -925,6 +944,7 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
             g.seg_ptr = plan->gen_tables[size_t(g.seg_table)]->p;
             g.seg = plan->gen_tables[size_t(g.seg_table) + 1]->p;
             g.heavy = plan->gen_tables[size_t(g.seg_table) + 2]->p;
+            g.heavy_sums = plan->gen_buffers[size_t(g.heavy_buffer)]->p;
             g.partial = plan->gen_buffers[size_t(g.partial_buffer)]->p;
         }
         // lanes that share a result node in the fused kernel: the power of two that holds its elements, 8 to 64
@@ -954,11 +974,13 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
             generic_segsum_kernel<<<dim3(unsigned((t2 + 255) / 256)), block, 0, stream>>>(g);
             CST_HIP(hipGetLastError());
             if (g.n_heavy > 0) {
-                const dim3 hg{unsigned(g.n_heavy)};
+                const dim3 hg{unsigned(g.n_heavy), unsigned(kGenHeavyParts)};
                 if (g.out_block <= 8) generic_segsum_heavy_kernel<8><<<hg, block, 0, stream>>>(g);
                 else if (g.out_block <= 32) generic_segsum_heavy_kernel<32><<<hg, block, 0, stream>>>(g);
                 else if (g.out_block <= 128) generic_segsum_heavy_kernel<128><<<hg, block, 0, stream>>>(g);
                 else generic_segsum_heavy_kernel<256><<<hg, block, 0, stream>>>(g);
+                CST_HIP(hipGetLastError());
+                generic_segsum_heavy_final_kernel<<<dim3(unsigned(div_up(g.n_heavy * g.out_block, 256))), block, 0, stream>>>(g);
                 CST_HIP(hipGetLastError());
             }
         }

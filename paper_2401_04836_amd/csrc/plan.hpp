@@ -56,6 +56,8 @@ struct GenStmt {
     const int64_t *seg_ptr;                    // [out_nodes + 1] segments of each result node
     int64_t n_heavy;                           // result nodes with so many segments that a workgroup adds them
     const int64_t *heavy;                      // [n_heavy] their numbers
+    double *heavy_sums;                        // [n_heavy x parts x out_block] sums of the workgroups that share a node
+    int heavy_buffer;                          // resolved to heavy_sums at launch
     double *partial;                           // [n_segs * out_block]
     int seg_table, partial_buffer;             // resolved to pointers at launch
     // kind 1 with atomics: workgroups add into `copies` private copies of the result in turn, so that a
