@@ -160,6 +160,29 @@ def build_chain(cst, S, wl, dev, compact):
     return [dict(plan=pl, factors=facs, out=out, nodes=nodes, bytes=alg_bytes, flops=flops)], build_s, X.nnz
 
 
+def build_mttkrp4(cst, S, wl, dev):
+    """Order-4 MTTKRP of rank 32 on an order-4 workload's tensor (the second operation of Sec. 5.3 at
+    the next order up): three statements fused on the whole prefix, which the generic executor runs as
+    one kernel with scalar intermediates."""
+    X = wl.sparse["X"]
+    csf = cst.build_csf([c.to(dev) for c in X.coords], X.vals.to(dev), X.dims, list(range(X.order)))
+    R = 32
+    g = torch.Generator().manual_seed(20240104)
+    B, C, D = (torch.rand(X.dims[m], R, generator=g, dtype=torch.float64).to(dev) for m in (1, 2, 3))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    text = ("T1[i,j,k,r] = X[i,j,k,l] * D[l,r] | i,j,k,l,r ; T2[i,j,r] = T1[i,j,k,r] * C[k,r] | i,j,k,r ; "
+            "M[i,r] = T2[i,j,r] * B[j,r] | i,j,r")
+    pl = cst.plan(text, [("X", csf), ("D", D), ("C", C), ("B", B)], options=PLAN_OPTIONS)
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    nodes = [csf.nodes(l) for l in range(X.order)]
+    out = torch.empty(pl.n_rows * pl.row_elems, dtype=torch.float64, device=dev)
+    alg_bytes = 12 * sum(nodes) + 8 * R * sum(X.dims)
+    flops = 2 * R * sum(nodes[1:])
+    return [dict(plan=pl, factors=[D, C, B], out=out, nodes=nodes, bytes=alg_bytes, flops=flops, keep=csf)], build_s, X.nnz
+
+
 def build_sptn(cst, S, wl, dev):
     U, W = wl.sparse["U"], wl.sparse["W"]
     uc, uv = [c.to(dev) for c in U.coords], U.vals.to(dev)
@@ -408,6 +431,10 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
         launches, build_s, nnz_per_step = build_mttkrp(cst, S, wl, dev)
         name = "C2 MTTKRP order-3 %s nnz=%d rank=%d, modes 0 and 2" % (
             "x".join(map(str, wl.sparse["X"].dims)), wl.sparse["X"].nnz, wl.params["rank"])
+    elif wl.kind == "ttmc4" and args.mttkrp4:
+        launches, build_s, nnz_per_step = build_mttkrp4(cst, S, wl, dev)
+        name = "MTTKRP order-4 %s nnz=%d rank=32 on the tensor of C%d" % (
+            "x".join(map(str, wl.sparse["X"].dims)), wl.sparse["X"].nnz, cid)
     elif wl.kind in ("ttmc3", "ttmc4"):
         launches, build_s, nnz_per_step = build_chain(cst, S, wl, dev, wl.params.get("compact", False))
         name = "C%d TTMc order-%d %s nnz=%d ranks=%s%s" % (
@@ -467,7 +494,7 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
     family = desc.split()[0].split("=")[1]
     if family == "generic":
         name += " [generic executor]"
-    plain = not (args.small or args.restricted or args.all_modes)
+    plain = not (args.small or args.restricted or args.all_modes or args.mttkrp4)
     rec = {
         "config_id": cid, "workload": name, "kind": wl.kind,
         "ms_per_step": ms_per_step, "nnz_per_step": nnz_per_step, "nnz_per_s": nnz_per_step / (dt / args.steps),
@@ -506,7 +533,7 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
                                              "frac": tf / FP64_PEAK_TFLOPS}
     if wl.kind in ("ttmc3", "mttkrp3", "ttmc4") and family != "generic" and cid == 1:
         rec["roofline"]["note"] = "0.3 MB problem: launch latency, no roofline claim"
-    if not args.no_cpu:
+    if not args.no_cpu and not args.mttkrp4:
         cb = cpu_baseline(wl, cpu_budget)
         if cb is not None:
             rec["cpu_baseline"] = cb
@@ -537,6 +564,9 @@ def main():
                          "7 = the four-index product of the same section")
     ap.add_argument("--all-modes", action="store_true",
                     help="configuration 2: a step is the MTTKRP of every mode (0, 1, 2), each on a CSF rooted at its mode")
+    ap.add_argument("--mttkrp4", action="store_true",
+                    help="configuration 3: instead of the TTMc, the order-4 MTTKRP of rank 32 on the same tensor, "
+                         "a chain of three fused statements the generic executor runs as one kernel")
     ap.add_argument("--restricted", action="store_true", help="configuration 6: the form with the K -> i filter")
     ap.add_argument("--small", action="store_true", help="reduced copy of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")

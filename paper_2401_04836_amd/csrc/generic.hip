@@ -147,7 +147,7 @@ generic_stmt_kernel(GenStmt g) {
 // order of addition, no atomics.
 // SMALL: both factors are below 2 GiB with fewer than 2^24 rows of fewer than 2^24 bytes, so that a row's
 // byte offset is one 24-bit multiply-add instead of 64-bit arithmetic.
-template <int W, bool SMALL>
+template <int W, bool SMALL, int U>
 __global__ void __launch_bounds__(256)
 generic_fused_kernel(GenStmt g) {
     using offs = typename std::conditional<SMALL, uint32_t, int64_t>::type;
@@ -161,47 +161,86 @@ generic_fused_kernel(GenStmt g) {
     const int64_t o_lin = (grp - unit * chunks) * W + j;
     const bool live = o_lin < g.out_block;                   // idle lanes compute element 0 and store nothing
     int64_t rem = live ? o_lin : 0;
-    int64_t f_off0 = 0, f1_off0 = 0, out_off = 0;
+    int64_t f_off0 = 0, f1_off0 = 0, out_off = 0, fu_off0[U + 1] = {};
     for (int q = g.n_out - 1; q >= 0; --q) {
         const int64_t o = rem % g.extent[q];
         rem /= g.extent[q];
         f_off0 += o * g.f_stride[q];
         f1_off0 += o * g.f1_stride[q];
         out_off += o * g.out_stride[q];
+#pragma unroll
+        for (int v = 0; v < U; ++v) fu_off0[v] += o * g.fu_stride[v][q];
     }
-    int64_t c0, c1;                                          // the result node's children (fibers of X)
-    if (g.d_out == 0) { c0 = 0; c1 = g.roots; }
-    else { c0 = g.ptr[g.d_out - 1][p]; c1 = g.ptr[g.d_out - 1][p + 1]; }
-    const int32_t *ix = g.idx[g.d_out];
-    const int64_t *lptr = g.ptr[g.d_in - 1];                 // children of the consumer's children: X's leaves
-    // byte offsets of this lane's element in a row of F and of F1, and the rows' strides in bytes
-    const offs f_lane = offs(f_off0 * 8), f1_lane = offs(f1_off0 * 8);
-    const offs fs = offs(g.f_level_stride[g.d_out] * 8), fs1 = offs(g.f1_level_stride * 8);
-    const char *fb = reinterpret_cast<const char *>(g.f), *f1b = reinterpret_cast<const char *>(g.f1);
+    // The levels above the leaves are numbered from the fibers (0) up to the summed level (U).  For
+    // each: the factor's base, this lane's byte offset in a row of it, the rows' stride in bytes.
+    const int fiber_level = g.d_in - 1;
+    const char *lb[U + 1];
+    offs l_lane[U + 1], l_fs[U + 1];
+#pragma unroll
+    for (int v = 0; v < U; ++v) {
+        lb[v] = reinterpret_cast<const char *>(g.fu[v]);
+        l_lane[v] = offs(fu_off0[v] * 8);
+        l_fs[v] = offs(g.fu_level_stride[v] * 8);
+    }
+    lb[U] = reinterpret_cast<const char *>(g.f);
+    l_lane[U] = offs(f_off0 * 8);
+    l_fs[U] = offs(g.f_level_stride[g.d_out] * 8);
+    const offs f1_lane = offs(f1_off0 * 8), fs1 = offs(g.f1_level_stride * 8);
+    const char *f1b = reinterpret_cast<const char *>(g.f1);
     auto row = [](const char *base, int32_t i, offs stride, offs lane) -> double {
         if constexpr (SMALL) return *reinterpret_cast<const double *>(base + (__umul24(uint32_t(i), stride) + lane));
         else return *reinterpret_cast<const double *>(base + (int64_t(i) * stride + lane));
     };
-    // A segment is a range of leaves and may begin and end inside a fiber: then the fiber's factor
-    // multiplies each part of its sum, and the second pass adds the parts.
+    int64_t c0, c1;                                          // the result node's children
+    if (g.d_out == 0) { c0 = 0; c1 = g.roots; }
+    else { c0 = g.ptr[g.d_out - 1][p]; c1 = g.ptr[g.d_out - 1][p + 1]; }
+    const int32_t *ix = g.idx[fiber_level];
+    const int64_t *lptr = g.ptr[fiber_level];                // X's leaves below each fiber
+    // A segment is a range of leaves and may begin and end inside a fiber, or inside a node of a level
+    // above: then the node's factor multiplies each part of its sum, and the second pass adds the parts.
     int64_t e0 = 0, e_end = 0;
     if (c0 < c1) {
-        e0 = segmented ? g.seg[3 * unit + 1] : lptr[c0];
-        e_end = segmented ? g.seg[3 * unit + 2] : lptr[c1];
+        if (segmented) { e0 = g.seg[3 * unit + 1]; e_end = g.seg[3 * unit + 2]; }
+        else if (U == 0) { e0 = lptr[c0]; e_end = lptr[c1]; }
+        else if (g.out_leaf) { e0 = g.out_leaf[p]; e_end = g.out_leaf[p + 1]; }
+        else e_end = g.nodes[g.d_in];
     }
     constexpr int kFar = 1 << 30;                            // positions count from e0 and saturate here
-    const int n_total = e_end - e0 < kFar ? int(e_end - e0) : kFar;          // the plan keeps a unit's leaves below that
-    double acc = 0.0;
-    if (n_total > 0) {
-        int64_t c = c0;
-        if (segmented) {                                     // the fiber that holds leaf e0: the last c with lptr[c] <= e0
-            int64_t lo = c0, hi = c1;
+    auto near = [&](int64_t e) { const int64_t d = e - e0; return d < kFar ? int(d) : kFar; };
+    const int n_total = near(e_end);                         // the plan keeps a unit's leaves below kFar
+    double s[U + 1] = {};                                    // running sums: s[v] over the finished children of the
+    if (n_total > 0) {                                       // current node of level v + 1 (s[U]: of the result node)
+        // the last node of [lo, hi) whose first leaf is not after e0
+        auto holder = [&](const int64_t *first_leaf, int64_t lo, int64_t hi) {
             while (hi - lo > 1) {
                 const int64_t mid = lo + ((hi - lo) >> 1);
-                if (lptr[mid] <= e0) lo = mid; else hi = mid;
+                if (first_leaf[mid] <= e0) lo = mid; else hi = mid;
             }
-            c = lo;
+            return lo;
+        };
+        // levels above the fibers: the current node, where it ends, its factor, and the same one node ahead
+        int64_t cu[U + 1];
+        int endu[U + 1], endu2[U + 1];
+        double fvu[U + 1], fvu2[U + 1];
+        auto upper_ahead = [&](int v) {                      // (endu2, fvu2) of node cu + 1 of level v
+            const int L = fiber_level - v;
+            if (cu[v] + 1 >= g.nodes[L]) { endu2[v] = kFar; return; }
+            endu2[v] = near(g.leaf_end[v - 1][cu[v] + 2]);
+            fvu2[v] = row(lb[v], g.idx[L][cu[v] + 1], l_fs[v], l_lane[v]);
+        };
+#pragma unroll
+        for (int v = U; v >= 1; --v) {
+            const int L = fiber_level - v;
+            const int64_t lo = segmented ? holder(g.leaf_end[v - 1], c0, c1) : c0;
+            cu[v] = lo;
+            endu[v] = near(g.leaf_end[v - 1][lo + 1]);
+            fvu[v] = row(lb[v], g.idx[L][lo], l_fs[v], l_lane[v]);
+            upper_ahead(v);
+            c0 = g.ptr[L][lo];
+            c1 = g.ptr[L][lo + 1];
         }
+        int64_t c = segmented ? holder(lptr, c0, c1) : c0;   // the fiber that holds leaf e0
+        if (U > 0) c1 = g.nodes[fiber_level];                // fibers past the unit's last end at or after its last leaf
         const int32_t *lix = g.idx[g.d_in] + e0;
         const double *lx = g.in + e0;
         // window of W fibers from cw on: lane j holds the end and the index of fiber cw + j
@@ -209,13 +248,12 @@ generic_fused_kernel(GenStmt g) {
         int w_end, w_ix;
         auto load_fibers = [&]() {
             const int64_t cc = cw + j < c1 ? cw + j : c1 - 1;
-            const int64_t d = lptr[cc + 1] - e0;
-            w_end = d < kFar ? int(d) : kFar;
+            w_end = near(lptr[cc + 1]);
             w_ix = ix[cc];
         };
         load_fibers();
         int next = __shfl(w_end, 0, W);                      // end of the current fiber, its factor; then the same one fiber ahead
-        double fv = row(fb, __shfl(w_ix, 0, W), fs, f_lane);
+        double fv = row(lb[0], __shfl(w_ix, 0, W), l_fs[0], l_lane[0]);
         int next2 = kFar;
         double fv2 = 0.0;
         auto look_ahead = [&]() {                            // (next2, fv2) for fiber c + 1
@@ -223,7 +261,7 @@ generic_fused_kernel(GenStmt g) {
             if (c + 1 - cw == W) { cw = c + 1; load_fibers(); }
             const int k = int(c + 1 - cw);
             next2 = __shfl(w_end, k, W);
-            fv2 = row(fb, __shfl(w_ix, k, W), fs, f_lane);
+            fv2 = row(lb[0], __shfl(w_ix, k, W), l_fs[0], l_lane[0]);
         };
         look_ahead();
         // window of W leaves: lane j holds leaf ew + j; the next window is read while this one is summed
@@ -253,13 +291,28 @@ generic_fused_kernel(GenStmt g) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     if (u0 + k < n) {
-                        if (ew + u0 + k >= next) {           // the fiber ended (every fiber of a CSF has a leaf): its sum
-                            acc = fma(t, fv, acc);           // times the consumer's factor
+                        const int pos = ew + u0 + k;
+                        if (pos >= next) {                   // the fiber ended (every fiber of a CSF has a leaf): its sum
+                            s[0] = fma(t, fv, s[0]);         // times the factor of its level
                             t = 0.0;
                             ++c;
                             next = next2;
                             fv = fv2;
                             look_ahead();
+                            bool up = true;                  // and so for each level above whose node ended with it
+#pragma unroll
+                            for (int v = 1; v <= U; ++v) {
+                                if (up && pos >= endu[v]) {
+                                    s[v] = fma(s[v - 1], fvu[v], s[v]);
+                                    s[v - 1] = 0.0;
+                                    ++cu[v];
+                                    endu[v] = endu2[v];
+                                    fvu[v] = fvu2[v];
+                                    upper_ahead(v);
+                                } else {
+                                    up = false;
+                                }
+                            }
                         }
                         t = fma(xv[k], yv[k], t);
                     }
@@ -270,18 +323,27 @@ generic_fused_kernel(GenStmt g) {
             l_ix = l_ix2;
             l_x = l_x2;
         }
-        acc = fma(t, fv, acc);
+        s[0] = fma(t, fv, s[0]);
+#pragma unroll
+        for (int v = 1; v <= U; ++v) s[v] = fma(s[v - 1], fvu[v], s[v]);
     }
     if (!live) return;
-    if (segmented) { g.partial[unit * g.out_block + out_off] = acc; return; }
+    if (segmented) { g.partial[unit * g.out_block + out_off] = s[U]; return; }
     const int64_t row_out = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
-    g.out[row_out * g.out_block + out_off] = acc;
+    g.out[row_out * g.out_block + out_off] = s[U];
 }
 
+template <int W, int U>
+static void launch_fused_u(const GenStmt &g, dim3 grid, hipStream_t stream) {
+    if (g.fused_small) generic_fused_kernel<W, true, U><<<grid, dim3(256), 0, stream>>>(g);
+    else generic_fused_kernel<W, false, U><<<grid, dim3(256), 0, stream>>>(g);
+}
 template <int W>
 static void launch_fused(const GenStmt &g, dim3 grid, hipStream_t stream) {
-    if (g.fused_small) generic_fused_kernel<W, true><<<grid, dim3(256), 0, stream>>>(g);
-    else generic_fused_kernel<W, false><<<grid, dim3(256), 0, stream>>>(g);
+    static_assert(kGenMaxUpper == 2, "one instance per number of inlined levels");
+    if (g.fused_upper == 0) launch_fused_u<W, 0>(g, grid, stream);
+    else if (g.fused_upper == 1) launch_fused_u<W, 1>(g, grid, stream);
+    else launch_fused_u<W, 2>(g, grid, stream);
 }
 
 // second pass of a long sum: the partial sums of each result node, added in segment order.  Nodes
@@ -378,24 +440,27 @@ __global__ void generic_seg_fill_kernel(const int64_t *ptr, int64_t nodes, int64
 // The same for a statement whose producer is inlined: its work is counted in X's leaves, so the
 // leaves below a result node are cut into ranges of kGenLeafSegment, wherever the fibers end.
 constexpr int64_t kGenLeafSegment = 512;
-__global__ void generic_leafseg_count_kernel(const int64_t *ptr, const int64_t *lptr, int64_t nodes, int64_t roots, int64_t *count) {
+__global__ void generic_leafseg_count_kernel(const int64_t *out_leaf, int64_t nodes, int64_t leaves, int64_t *count) {
     const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (p >= nodes) return;
-    const int64_t c0 = ptr ? ptr[p] : 0, c1 = ptr ? ptr[p + 1] : roots;
-    count[p] = (lptr[c1] - lptr[c0] + kGenLeafSegment - 1) / kGenLeafSegment;
+    const int64_t e0 = out_leaf ? out_leaf[p] : 0, e1 = out_leaf ? out_leaf[p + 1] : leaves;
+    count[p] = (e1 - e0 + kGenLeafSegment - 1) / kGenLeafSegment;
 }
-__global__ void generic_leafseg_fill_kernel(const int64_t *ptr, const int64_t *lptr, int64_t nodes, int64_t roots, const int64_t *seg_ptr,
-                                            int64_t *seg) {
+__global__ void generic_leafseg_fill_kernel(const int64_t *out_leaf, int64_t nodes, int64_t leaves, const int64_t *seg_ptr, int64_t *seg) {
     const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (p >= nodes) return;
-    const int64_t c0 = ptr ? ptr[p] : 0, c1 = ptr ? ptr[p + 1] : roots;
-    const int64_t l1 = lptr[c1];
-    int64_t e = lptr[c0];
+    const int64_t l1 = out_leaf ? out_leaf[p + 1] : leaves;
+    int64_t e = out_leaf ? out_leaf[p] : 0;
     for (int64_t sg = seg_ptr[p]; sg < seg_ptr[p + 1]; ++sg, e += kGenLeafSegment) {
         seg[3 * sg] = p;
         seg[3 * sg + 1] = e;
         seg[3 * sg + 2] = e + kGenLeafSegment < l1 ? e + kGenLeafSegment : l1;
     }
+}
+// first leaf below each node of a level, from the level below: out[x] = below[ptr[x]], x = 0 .. nodes
+__global__ void generic_leaf_ptr_kernel(const int64_t *ptr, const int64_t *below, int64_t nodes, int64_t *out) {
+    const int64_t x = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (x <= nodes) out[x] = below[ptr[x]];
 }
 
 __global__ void __launch_bounds__(256)
@@ -637,6 +702,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
     plan->gen.clear();
     plan->gen_buffers.clear();
     plan->gen_tables.clear();
+    plan->gen_leaf_tables.clear();
     plan->gen_zero_out = false;
     std::vector<int64_t> buffer_elems;
     auto tensor_of_ref = [&](const Ref &r, int src, int op, GenTensor &t) {
@@ -658,6 +724,26 @@ conststn_status build_generic(conststn_plan_s *plan) {
         for (int q = int(names.size()) - 1; q >= 0; --q) { out[names[q]] = stride; stride *= s.extent[names[q]]; }
         return stride;
     };
+
+    // first leaf below each node of level L (and the leaf count after the last): X's own pointers for the
+    // fibers, composed level by level above them; built when a fused statement asks, kept with the plan
+    std::vector<const int64_t *> leaf_ptr_of(size_t(n), nullptr);
+    auto leaf_ptr = [&](int L, const int64_t **out) -> conststn_status {
+        if (L < 0 || L > n - 2) { set_error("internal: no leaf pointers for level %d", L); return CONSTSTN_EINVAL; }
+        leaf_ptr_of[size_t(n - 2)] = csf->ptr[n - 2].p;
+        for (int l = n - 3; l >= L; --l) {
+            if (leaf_ptr_of[size_t(l)]) continue;
+            plan->gen_leaf_tables.emplace_back(new DevBuf<int64_t>());
+            DevBuf<int64_t> &t = *plan->gen_leaf_tables.back();
+            CST_TRY(t.alloc(size_t(csf->nodes[l] + 1)));
+            generic_leaf_ptr_kernel<<<dim3(unsigned((csf->nodes[l] + 256) / 256)), dim3(256)>>>(csf->ptr[l].p, leaf_ptr_of[size_t(l + 1)], csf->nodes[l], t.p);
+            CST_HIP(hipGetLastError());
+            leaf_ptr_of[size_t(l)] = t.p;
+        }
+        *out = leaf_ptr_of[size_t(L)];
+        return CONSTSTN_OK;
+    };
+    std::vector<std::vector<std::string>> out_dense_of(static_cast<size_t>(m));     // each statement's dense result indices, in loop order
 
     for (int p = 0; p < m; ++p) {
         const Stmt &st = s.stmts[p];
@@ -706,6 +792,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
         };
         for (const auto &nm : in.dense) consider(nm);
         for (const auto &nm : fa.dense) consider(nm);
+        out_dense_of[size_t(p)] = out_dense;
         if (out_dense.size() + red.size() > size_t(kGenMaxIdx)) { set_error("statement %d has more than %d dense indices", p, kGenMaxIdx); return CONSTSTN_EUNSUPPORTED; }
 
         GenStmt g{};
@@ -763,55 +850,87 @@ conststn_status build_generic(conststn_plan_s *plan) {
         }
         // Fusion (Sec. 2.2): when this statement consumes a result that the statement before it in the tree forms
         // from X's leaves and a dense operand one level deeper, with the same dense indices, and the
-        // schedule fuses the two on the whole prefix, the producer is computed inside this statement's kernel.
+        // schedule fuses the two on the whole prefix, the producer is computed inside this statement's
+        // kernel.  The producer may have inlined its own producer the same way: a chain of statements that
+        // each sum one more level becomes one kernel, and none of their results is stored.
         {
             const int prod = tb.from_x ? st.src_b : st.src_a;
-            if (kind == 0 && prod >= 0 && in.from_x && g.n_red == 0 && d_node - d_out == 1 && d_node == n - 1 &&
+            if (kind == 0 && prod >= 0 && in.from_x && g.n_red == 0 && d_node - d_out == 1 &&
                 plan->opt("generic_fuse", 1) == 1 && s.stmts[prod].fused_depth >= d_node) {
                 GenStmt &g1 = plan->gen[size_t(prod)];
                 const Stmt &sp = s.stmts[prod];
+                const bool chain = g1.fused == 1;
                 const Ref *f1ref = nullptr;
                 if (sp.op_a >= 0 && sp.op_a == g1.f_operand) f1ref = &sp.a;
                 else if (sp.op_b >= 0 && sp.op_b == g1.f_operand) f1ref = &sp.b;
-                bool ok = g1.kind == 0 && g1.in_is_leaf && g1.n_red == 0 && g1.d_node == n &&
+                bool ok = g1.kind == 0 && g1.in_is_leaf && g1.n_red == 0 && g1.d_node == d_node + 1 && g1.d_f == 0 &&
                           g1.d_out == d_node && g1.out_buffer == in.buffer && g1.f_operand >= 0 && f1ref &&
-                          g1.n_out == g.n_out && g1.skip == 0 && g1.fused == 0;
+                          g1.n_out == g.n_out && g1.skip == 0;
+                if (chain) ok = ok && g1.fused_upper < kGenMaxUpper;
+                else ok = ok && d_node == n - 1;
+                const std::vector<std::string> &dense1 = out_dense_of[size_t(prod)];
                 std::map<std::string, int64_t> sf1;
                 if (ok) {
                     strides(f1ref->idx, sf1);
                     // the same dense indices on both results (any order), none of them summed
                     for (size_t q = 0; q < out_dense.size() && ok; ++q)
-                        if (find_name(in.dense, out_dense[q]) < 0) ok = false;
-                    if (in.dense.size() != out_dense.size()) ok = false;
+                        if (find_name(in.dense, out_dense[q]) < 0 || find_name(dense1, out_dense[q]) < 0) ok = false;
+                    if (in.dense.size() != out_dense.size() || dense1.size() != out_dense.size()) ok = false;
                     for (const auto &nm : f1ref->idx)
-                        if (nm != level_name[n - 1] && find_name(out_dense, nm) < 0) ok = false;
+                        if (nm != level_name[d_node] && find_name(out_dense, nm) < 0) ok = false;
                 }
                 if (ok) {
                     g.fused = 1;
-                    g.f1_operand = g1.f_operand;
-                    for (size_t q = 0; q < out_dense.size(); ++q) g.f1_stride[q] = sf1.count(out_dense[q]) ? sf1[out_dense[q]] : 0;
-                    g.f1_level_stride = sf1.count(level_name[n - 1]) ? sf1[level_name[n - 1]] : 0;
-                    {
-                        // the largest byte offset into either factor, the largest row number and row stride
-                        auto reach = [&](const int64_t *stride, int64_t level_stride, int64_t level_extent, int64_t &row_bytes) {
-                            int64_t elems = (level_extent - 1) * level_stride;
-                            for (size_t q = 0; q < out_dense.size(); ++q) elems += (g.extent[q] - 1) * stride[q];
-                            row_bytes = level_stride * 8;
-                            return elems * 8 + 8;
-                        };
-                        int64_t rb = 0, rb1 = 0;
-                        const int64_t ext = s.extent[level_name[d_out]], ext1 = s.extent[level_name[n - 1]];
-                        const int64_t top = reach(g.f_stride, g.f_level_stride[d_out], ext, rb);
-                        const int64_t top1 = reach(g.f1_stride, g.f1_level_stride, ext1, rb1);
+                    // the largest byte offset into a factor, the largest row number and row stride
+                    auto within_reach = [&](const int64_t *stride, int64_t level_stride, int64_t level_extent) {
+                        int64_t elems = (level_extent - 1) * level_stride;
+                        for (size_t q = 0; q < out_dense.size(); ++q) elems += (g.extent[q] - 1) * stride[q];
                         const int64_t lim24 = int64_t(1) << 24, lim31 = int64_t(1) << 31;
-                        g.fused_small = (top < lim31 && top1 < lim31 && ext < lim24 && ext1 < lim24 && rb < lim24 && rb1 < lim24) ? 1 : 0;
+                        return elems * 8 + 8 < lim31 && level_extent < lim24 && level_stride * 8 < lim24;
+                    };
+                    bool small = within_reach(g.f_stride, g.f_level_stride[d_out], s.extent[level_name[d_out]]);
+                    int64_t sf1_dense[kGenMaxIdx] = {};
+                    for (size_t q = 0; q < out_dense.size(); ++q) sf1_dense[q] = sf1.count(out_dense[q]) ? sf1[out_dense[q]] : 0;
+                    const int64_t sf1_level = sf1.count(level_name[d_node]) ? sf1[level_name[d_node]] : 0;
+                    small = small && within_reach(sf1_dense, sf1_level, s.extent[level_name[d_node]]);
+                    if (!chain) {
+                        g.fused_upper = 0;
+                        g.f1_operand = g1.f_operand;
+                        for (size_t q = 0; q < out_dense.size(); ++q) g.f1_stride[q] = sf1_dense[q];
+                        g.f1_level_stride = sf1_level;
+                    } else {
+                        // what the producer had inlined, its dense indices in this statement's order, then its own factor
+                        const int u1 = g1.fused_upper;
+                        g.fused_upper = u1 + 1;
+                        g.f1_operand = g1.f1_operand;
+                        g.f1_level_stride = g1.f1_level_stride;
+                        for (int v = 0; v < u1; ++v) {
+                            g.fu_operand[v] = g1.fu_operand[v];
+                            g.fu_level_stride[v] = g1.fu_level_stride[v];
+                        }
+                        for (size_t q = 0; q < out_dense.size(); ++q) {
+                            const int q1 = find_name(dense1, out_dense[q]);
+                            g.f1_stride[q] = g1.f1_stride[q1];
+                            for (int v = 0; v < u1; ++v) g.fu_stride[v][q] = g1.fu_stride[v][q1];
+                            g.fu_stride[u1][q] = sf1_dense[q];
+                        }
+                        g.fu_operand[u1] = g1.f_operand;
+                        g.fu_level_stride[u1] = sf1_level;
+                        small = small && g1.fused_small == 1;
                     }
+                    g.fused_small = small ? 1 : 0;
+                    for (int v = 1; v <= g.fused_upper; ++v) CST_TRY(leaf_ptr(n - 2 - v, &g.leaf_end[v - 1]));
+                    if (d_out > 0) CST_TRY(leaf_ptr(d_out - 1, &g.out_leaf));
                     g.in_is_leaf = 1;                       // reads X's values, not the intermediate
+                    g.d_in = n - 1;
                     g.in_operand = -1;
                     g.in_buffer = -1;
                     g1.skip = 1;
                     buffer_elems[size_t(in.buffer)] = 1;    // the intermediate is never stored,
-                    if (g1.n_segs > 0) buffer_elems[size_t(g1.partial_buffer)] = 1;      // nor are its partial sums
+                    if (g1.n_segs > 0) {                    // nor are its partial sums
+                        buffer_elems[size_t(g1.partial_buffer)] = 1;
+                        buffer_elems[size_t(g1.heavy_buffer)] = 1;
+                    }
                     long_sum = max_span(d_out, n) > std::min<int64_t>(span_limit, int64_t(1) << 29);     // work counted in leaves
                 }
             }
@@ -825,8 +944,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
             plan->gen_tables.emplace_back(new DevBuf<int64_t>());
             DevBuf<int64_t> &sptr = *plan->gen_tables.back();
             CST_TRY(sptr.alloc(size_t(on + 1)));
-            const int64_t *lptr = g.fused ? csf->ptr[d_node - 1].p : nullptr;
-            if (g.fused) generic_leafseg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, lptr, on, csf->nodes[0], count.p);
+            if (g.fused) generic_leafseg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(g.out_leaf, on, csf->nnz, count.p);
             else generic_seg_count_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], count.p);
             CST_HIP(hipGetLastError());
             int64_t n_segs = 0;
@@ -835,7 +953,7 @@ conststn_status build_generic(conststn_plan_s *plan) {
             plan->gen_tables.emplace_back(new DevBuf<int64_t>());
             DevBuf<int64_t> &seg = *plan->gen_tables.back();
             CST_TRY(seg.alloc(size_t(3 * n_segs)));
-            if (g.fused) generic_leafseg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, lptr, on, csf->nodes[0], sptr.p, seg.p);
+            if (g.fused) generic_leafseg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(g.out_leaf, on, csf->nnz, sptr.p, seg.p);
             else generic_seg_fill_kernel<<<dim3(unsigned((on + 255) / 256)), dim3(256)>>>(cptr, on, csf->nodes[0], sptr.p, seg.p);
             CST_HIP(hipGetLastError());
             CST_HIP(hipDeviceSynchronize());
@@ -930,7 +1048,10 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
         };
         g.in = g.in_is_leaf ? csf->vals.p : where(g.in_operand, g.in_buffer);      // X: the leaf values
         g.f = where(g.f_operand, g.f_buffer);
-        if (g.fused) g.f1 = where(g.f1_operand, -1);
+        if (g.fused) {
+            g.f1 = where(g.f1_operand, -1);
+            for (int v = 0; v < g.fused_upper; ++v) g.fu[v] = where(g.fu_operand[v], -1);
+        }
         g.out = g.out_buffer >= 0 ? plan->gen_buffers[size_t(g.out_buffer)]->p : out;
         if (!g.in || !g.f || !g.out) { set_error("internal: unresolved tensor in the generic executor"); return CONSTSTN_EINVAL; }
         double *final_out = g.out;

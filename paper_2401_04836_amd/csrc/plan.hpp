@@ -25,6 +25,7 @@ enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GE
 // Dense loop indices: the first n_out are the result's dense indices in storage order, the
 // next n_red are summed over; strides are in elements, 0 where a tensor lacks the index.
 constexpr int kGenMaxIdx = 8;
+constexpr int kGenMaxUpper = 2;
 struct GenStmt {
     int kind;                                  // 0: one thread per result element walks the subtree below its node;
                                                // 1: one thread per (node of depth d_node, dense result element)
@@ -73,6 +74,16 @@ struct GenStmt {
     const double *f1;
     int64_t f1_stride[kGenMaxIdx];             // its strides for this statement's dense result indices
     int64_t f1_level_stride;                   // and for the index of the leaf level
+    // fused chain: the producer may itself have inlined its producer, and so on, kGenMaxUpper times.  Then
+    // `fused_upper` levels lie between this statement's summed level and X's fibers; the factor of the
+    // fiber level is fu[0], of the level above it fu[1], and `f` is the factor of the summed level.
+    int fused_upper;
+    int fu_operand[kGenMaxUpper];
+    const double *fu[kGenMaxUpper];
+    int64_t fu_stride[kGenMaxUpper][kGenMaxIdx];
+    int64_t fu_level_stride[kGenMaxUpper];
+    const int64_t *leaf_end[kGenMaxUpper];     // [nodes + 1] first leaf below each node of the level above the fibers, the next one up
+    const int64_t *out_leaf;                   // [out_nodes + 1] the same for the result's nodes; null: one node over every leaf
 };
 
 // One unit of work of the TTMc kernels: a range of leaf positions (order 3) or of level-1
@@ -228,6 +239,7 @@ struct conststn_plan_s {
     std::vector<cst::GenStmt> gen;
     std::vector<std::unique_ptr<cst::DevBuf<double>>> gen_buffers;
     std::vector<std::unique_ptr<cst::DevBuf<int64_t>>> gen_tables;   // segment tables of long sums
+    std::vector<std::unique_ptr<cst::DevBuf<int64_t>>> gen_leaf_tables;   // first leaf below each node of a level, for fused statements
     bool gen_rooted = false;               // the result has one row block per root index
     bool gen_zero_out = false;             // the last statement adds into the result: cleared before every run
 

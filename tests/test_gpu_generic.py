@@ -185,14 +185,14 @@ def test_fused_leaf_producer_is_inlined_and_equals_the_stored_intermediate():
     seg, pl = _run(text, x, [0, 1, 2], f, (70, 24), options="force_generic=1,generic_span=16")
     assert "inlined_producers=1" in pl.describe()
     _check(seg, coords, vals, "ijk", [(B, "jr"), (C, "kr")], "ir", {"i": 70, "r": 24})
-    _say("order 4: only the deepest pair is inlined; a TTMc (the producer's result has fewer dense indices) is not")
+    _say("order 4: the whole chain is inlined; a TTMc (the producer's result has fewer dense indices) is not")
     dims4 = (30, 14, 12, 11)
     c4, v4 = _tensor(396, dims4, 6000)
     B4, C4, D4 = _dense(397, 14, 8), _dense(398, 12, 8), _dense(399, 11, 8)
     t4 = ("T1[i,j,k,r] = X[i,j,k,l] * D[l,r] | i,j,k,l,r ; T2[i,j,r] = T1[i,j,k,r] * C[k,r] | i,j,k,r ; "
           "M[i,r] = T2[i,j,r] * B[j,r] | i,j,r")
     got, pl = _run(t4, (c4, v4, dims4), [0, 1, 2, 3], [("D", D4), ("C", C4), ("B", B4)], (30, 8))
-    assert "inlined_producers=1" in pl.describe(), pl.describe()
+    assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
     _check(got, c4, v4, "ijkl", [(B4, "jr"), (C4, "kr"), (D4, "lr")], "ir", {"i": 30, "r": 8})
     _say("a slice of 40 000 leaves in 20 000 fibers: more segments than one thread adds in the second pass")
     dimsh = (10, 20000, 4)
@@ -308,6 +308,88 @@ def test_fused_pair_whose_result_keeps_no_sparse_index():
         _check(got, coords, vals, "ik", [(A, "ir"), (C, "kr")], "r", {"r": 12})
         stored, _ = _run(text, (coords, vals, dims), [0, 1], [("C", C), ("A", A)], (12,), options="generic_fuse=0")
         np.testing.assert_allclose(stored, got, rtol=0, atol=1e-9)
+
+
+def _with_heavy_slice(seed, coords, vals, dims, root, count):
+    """Adds `count` nonzeros in root slice `root`, at distinct cells below it, and drops duplicates."""
+    g = torch.Generator().manual_seed(seed)
+    below = int(np.prod(dims[1:]))
+    cells = torch.randperm(below, generator=g)[:count]
+    extra = []
+    for d in reversed(dims[1:]):
+        extra.append((cells % d).to(torch.int32))
+        cells = cells // d
+    extra.append(torch.full((count,), root, dtype=torch.int32))
+    extra.reverse()
+    coords = [torch.cat([c, e]) for c, e in zip(coords, extra)]
+    vals = torch.cat([vals, torch.rand(count, generator=g, dtype=torch.float64) - 0.5])
+    key = torch.zeros(vals.numel(), dtype=torch.int64)
+    for c, d in zip(coords, dims):
+        key = key * d + c.long()
+    _, first = np.unique(key.numpy(), return_index=True)
+    return [c[first] for c in coords], vals[first]
+
+
+def test_fused_chain_of_producers_is_one_kernel():
+    # Sec. 2.2 / Fig. 3b: every statement of an MTTKRP chain fused with the next on the whole prefix leaves one
+    # loop nest with scalar intermediates.  The executor then runs the chain as ONE kernel, up to three
+    # producers deep; it must equal the N-ary sum, the stored form, and itself when cut into leaf segments.
+    dims = (40, 17, 19, 15)
+    coords, vals = _tensor(431, dims, 9000)
+    coords, vals = _with_heavy_slice(432, coords, vals, dims, 7, 3000)
+    x = (coords, vals, dims)
+    for R in (24, 40):
+        B, C, D = _dense(433, 17, R), _dense(434, R, 19), _dense(435, 15, R)         # C stored rank-major
+        text = ("T1[i,j,k,r] = X[i,j,k,l] * D[l,r] | i,j,k,l,r ; T2[i,j,r] = T1[i,j,k,r] * C[r,k] | i,j,k,r ; "
+                "M[i,r] = T2[i,j,r] * B[j,r] | i,j,r")
+        ops = [("D", D), ("C", C), ("B", B)]
+        f = [(B, "jr"), (C, "rk"), (D, "lr")]
+        _say("order 4, rank %d" % R)
+        got, pl = _run(text, x, [0, 1, 2, 3], ops, (40, R))
+        assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
+        _check(got, coords, vals, "ijkl", f, "ir", {"i": 40, "r": R})
+        stored, pl = _run(text, x, [0, 1, 2, 3], ops, (40, R), options="generic_fuse=0")
+        assert "kernels=3 inlined_producers=0" in pl.describe(), pl.describe()
+        np.testing.assert_allclose(stored, got, rtol=0, atol=1e-10)
+        for span in (16, 700):
+            seg, pl = _run(text, x, [0, 1, 2, 3], ops, (40, R), options="generic_span=%d" % span)
+            assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
+            _check(seg, coords, vals, "ijkl", f, "ir", {"i": 40, "r": R})
+        pair, pl = _run(text, x, [0, 1, 2, 3], ops, (40, R), fusion=[3, 1, 0])       # the second pair fused on i only
+        assert "kernels=2 inlined_producers=1" in pl.describe(), pl.describe()
+        np.testing.assert_allclose(pair, got, rtol=0, atol=1e-10)
+
+    _say("order 5 in one kernel, order 6 in two; two dense indices whose order changes along the chain")
+    dims5 = (12, 9, 8, 7, 6)
+    c5, v5 = _tensor(436, dims5, 7000)
+    c5, v5 = _with_heavy_slice(437, c5, v5, dims5, 2, 2500)
+    F = [_dense(438 + m, dims5[m], 5, 3) for m in range(1, 5)]
+    t5 = ("T1[i,j,k,l,r,s] = X[i,j,k,l,m] * F4[m,r,s] | i,j,k,l,m,r,s ; T2[i,j,k,s,r] = T1[i,j,k,l,r,s] * F3[l,r,s] | i,j,k,l,s,r ; "
+          "T3[i,j,r,s] = T2[i,j,k,s,r] * F2[k,r,s] | i,j,k,r,s ; M[i,s,r] = T3[i,j,r,s] * F1[j,r,s] | i,j,s,r")
+    ops5 = [("F4", F[3]), ("F3", F[2]), ("F2", F[1]), ("F1", F[0])]
+    f5 = [(F[0], "jrs"), (F[1], "krs"), (F[2], "lrs"), (F[3], "mrs")]
+    for opts in (None, "generic_span=32"):
+        got, pl = _run(t5, (c5, v5, dims5), [0, 1, 2, 3, 4], ops5, (12, 3, 5), options=opts)
+        assert "kernels=1 inlined_producers=3" in pl.describe(), pl.describe()
+        _check(got, c5, v5, "ijklm", f5, "isr", {"i": 12, "s": 3, "r": 5})
+    dims6 = (6, 5, 6, 5, 4, 7)
+    c6, v6 = _tensor(443, dims6, 6000)
+    G = [_dense(444 + m, dims6[m], 16) for m in range(1, 6)]
+    t6 = ("T1[a,b,c,d,e,r] = X[a,b,c,d,e,f] * G5[f,r] | a,b,c,d,e,f,r ; T2[a,b,c,d,r] = T1[a,b,c,d,e,r] * G4[e,r] | a,b,c,d,e,r ; "
+          "T3[a,b,c,r] = T2[a,b,c,d,r] * G3[d,r] | a,b,c,d,r ; T4[a,b,r] = T3[a,b,c,r] * G2[c,r] | a,b,c,r ; "
+          "M[a,r] = T4[a,b,r] * G1[b,r] | a,b,r")
+    got, pl = _run(t6, (c6, v6, dims6), [0, 1, 2, 3, 4, 5], [("G5", G[4]), ("G4", G[3]), ("G3", G[2]), ("G2", G[1]), ("G1", G[0])], (6, 16))
+    assert "kernels=2 inlined_producers=3" in pl.describe(), pl.describe()
+    _check(got, c6, v6, "abcdef", [(G[0], "br"), (G[1], "cr"), (G[2], "dr"), (G[3], "er"), (G[4], "fr")], "ar", {"a": 6, "r": 16})
+
+    _say("a chain whose result keeps no sparse index: every leaf below one node")
+    dims3 = (300, 40, 50)
+    c3, v3 = _tensor(451, dims3, 30_000)
+    A, B3, C3 = _dense(452, 300, 12), _dense(453, 40, 12), _dense(454, 50, 12)
+    t3 = "T[i,j,r] = X[i,j,k] * C[k,r] | i,j,k,r ; T2[i,r] = T[i,j,r] * B[j,r] | i,j,r ; z[r] = T2[i,r] * A[i,r] | i,r"
+    got, pl = _run(t3, (c3, v3, dims3), [0, 1, 2], [("C", C3), ("B", B3), ("A", A)], (12,))
+    assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
+    _check(got, c3, v3, "ijk", [(A, "ir"), (B3, "jr"), (C3, "kr")], "r", {"r": 12})
 
 
 def test_running_example_with_four_sparse_operands():
