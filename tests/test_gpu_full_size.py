@@ -262,6 +262,31 @@ def test_config3_ttmc4_full_size():
     err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
     _say("  rel err %.3e over %d elements" % (err, want.size))
     assert err <= TOL
+    del pl, out, want, S_abs
+    # the order-4 MTTKRP on the same CSF: three statements fused on the whole prefix, one generic kernel with
+    # scalar intermediates (leaf segments, every level's running sum); sampled slices against the N-ary sum
+    from oracle import nary
+    R = 32
+    g = torch.Generator().manual_seed(77)
+    B, C, D = (torch.rand(X.dims[m], R, generator=g, dtype=torch.float64) * 2 - 1 for m in (1, 2, 3))
+    text = ("T1[i,j,k,r] = X[i,j,k,l] * D[l,r] | i,j,k,l,r ; T2[i,j,r] = T1[i,j,k,r] * C[k,r] | i,j,k,r ; "
+            "M[i,r] = T2[i,j,r] * B[j,r] | i,j,r")
+    dev = [t.cuda() for t in (D, C, B)]
+    pl = cst.plan(text, [("X", csf), ("D", dev[0]), ("C", dev[1]), ("B", dev[2])])
+    assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
+    out = cst.execute(pl, dev).reshape(pl.n_rows, R)
+    torch.cuda.synchronize()
+    picks = pick_slices(slice_sizes(csf), n_light=16, seed=3)
+    roots = csf.export(0)[0][picks].long()
+    sub_c, sub_v = subset(X.coords, X.vals, 0, roots.tolist())
+    _say("config 3: order-4 MTTKRP in one kernel, %d sampled slices with %d nonzeros" % (len(picks), sub_v.size))
+    f = [(B.numpy(), "jr"), (C.numpy(), "kr"), (D.numpy(), "lr")]
+    ext = {"i": len(picks), "r": R}
+    want = nary.contract(sub_c, sub_v, "ijkl", f, "ir", ext)
+    S_abs = nary.contract_abs(sub_c, sub_v, "ijkl", f, "ir", ext)
+    err = oracle.rel_err(out[roots.to(out.device)].cpu().numpy(), want, S_abs)
+    _say("  rel err %.3e" % err)
+    assert err <= TOL
 
 
 def test_config4_three_tensor_network_full_size():
