@@ -131,59 +131,80 @@ count_heads_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys, co
 }
 
 // Exclusive scan of the tile counts of every level (one block per level); totals[l] = node count.
+// The block walks its row in chunks of 4096 counts, four adjacent ones per thread, and carries the
+// running total from chunk to chunk.
 __global__ void __launch_bounds__(1024)
 scan_tiles_kernel(const unsigned *__restrict__ tile_counts, int64_t *__restrict__ tile_offsets,
                   int64_t ntiles, int64_t *totals) {
-    __shared__ int64_t part[1024];
+    __shared__ int64_t wtot[16];
     const int l = blockIdx.x;
     const unsigned *in = tile_counts + int64_t(l) * ntiles;
     int64_t *out = tile_offsets + int64_t(l) * ntiles;
-    const int64_t per = (ntiles + blockDim.x - 1) / blockDim.x;
-    const int64_t b = int64_t(threadIdx.x) * per;
-    const int64_t e = b + per < ntiles ? b + per : ntiles;
-    int64_t s = 0;
-    for (int64_t t = b; t < e; ++t) s += in[t];
-    part[threadIdx.x] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int64_t run = 0;
-        for (unsigned t = 0; t < blockDim.x; ++t) { int64_t v = part[t]; part[t] = run; run += v; }
-        totals[l] = run;
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    int64_t carry = 0;
+    for (int64_t t0 = 0; t0 < ntiles; t0 += 4096) {
+        const int64_t t = t0 + int64_t(threadIdx.x) * 4;
+        unsigned v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = t + k < ntiles ? in[t + k] : 0u;
+        const int64_t mine = int64_t(v[0]) + v[1] + v[2] + v[3];
+        int64_t inc = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int64_t up = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += up;
+        }
+        if (lane == 63) wtot[wave] = inc;
+        __syncthreads();
+        int64_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int64_t x = wtot[w];
+            before += w < wave ? x : 0;
+            total += x;
+        }
+        int64_t run = carry + before + inc - mine;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (t + k < ntiles) out[t + k] = run;
+            run += v[k];
+        }
+        carry += total;
+        __syncthreads();
     }
-    __syncthreads();
-    int64_t run = part[threadIdx.x];
-    for (int64_t t = b; t < e; ++t) { out[t] = run; run += in[t]; }
+    if (threadIdx.x == 0) totals[l] = carry;
 }
 
 // ---- stable LSD radix sort of (key, position) pairs, 8 bits per pass ------------------------
 //
-// One wavefront owns a tile of kSortItems*64 consecutive pairs.  Per pass: (1) every wave counts
-// the digits of its tile; (2) scan_tiles_kernel (one block per digit value) turns the counts into
-// the tile's starting offset inside each digit's bucket, a one-wave kernel turns the bucket totals
-// into bucket bases; (3) every wave re-reads its tile in order, 64 pairs at a time, ranks each
-// pair among the lanes holding the same digit (eight ballots narrow the set of peers) and scatters.
-// Tiles are visited in index order inside a bucket and pairs in order inside a tile, so the sort
-// is stable, which the CSF needs: equal keys (duplicates) must keep input order.
+// A workgroup of four wavefronts owns a tile of kSortTile consecutive pairs, wavefront w the w-th
+// quarter of it.  Per pass: (1) every workgroup counts the digits of its tile; (2) scan_tiles_kernel
+// (one block per digit value) turns the counts into the tile's starting offset inside each digit's
+// bucket, a one-wave kernel turns the bucket totals into bucket bases; (3) every workgroup re-reads
+// its tile, ranks each pair among the pairs of the tile with the same digit that come before it (in
+// a wavefront: 64 pairs at a time, eight ballots narrow the set of peers; across wavefronts: their
+// digit counts), lays the tile out by digit in LDS and writes it from there, so that neighbouring
+// threads write neighbouring addresses of a bucket.  Tiles are visited in index order inside a
+// bucket and pairs in order inside a tile, so the sort is stable, which the CSF needs: equal keys
+// (duplicates) must keep input order.
 constexpr int kSortItems = 16;
-constexpr int kSortTile = kSortItems * 64;
+constexpr int kSortWave = kSortItems * 64;            // pairs of one wavefront
+constexpr int kSortTile = 4 * kSortWave;
 
 __global__ void __launch_bounds__(256)
 radix_count_kernel(int64_t n, const uint64_t *__restrict__ keys, int shift, unsigned *__restrict__ tile_counts,
                    int64_t ntiles) {
-    __shared__ unsigned hist[4][256];
-    const int wv = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const int64_t tile = int64_t(blockIdx.x) * 4 + wv;
-    for (int d = lane; d < 256; d += 64) hist[wv][d] = 0;
-    __builtin_amdgcn_wave_barrier();
-    if (tile < ntiles) {
-        const int64_t base = tile * kSortTile;
-        for (int i = 0; i < kSortItems; ++i) {
-            const int64_t e = base + int64_t(i) * 64 + lane;
-            if (e < n) atomicAdd(&hist[wv][unsigned(keys[e] >> shift) & 255u], 1u);
-        }
-        __builtin_amdgcn_wave_barrier();
-        for (int d = lane; d < 256; d += 64) tile_counts[int64_t(d) * ntiles + tile] = hist[wv][d];
+    __shared__ unsigned hist[256];
+    const int64_t tile = blockIdx.x;
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = tile * kSortTile;
+#pragma unroll 4
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t e = base + int64_t(i) * 256 + threadIdx.x;
+        if (e < n) atomicAdd(&hist[unsigned(keys[e] >> shift) & 255u], 1u);
     }
+    __syncthreads();
+    tile_counts[int64_t(threadIdx.x) * ntiles + tile] = hist[threadIdx.x];
 }
 
 __global__ void radix_bases_kernel(const int64_t *__restrict__ totals, int64_t *__restrict__ bases) {
@@ -204,35 +225,83 @@ __global__ void __launch_bounds__(256)
 radix_scatter_kernel(int64_t n, const uint64_t *__restrict__ keys_in, const uint32_t *__restrict__ pay_in,
                      uint64_t *__restrict__ keys_out, uint32_t *__restrict__ pay_out, int shift,
                      const int64_t *__restrict__ tile_offsets, const int64_t *__restrict__ bases, int64_t ntiles) {
-    __shared__ int64_t run[4][256];
+    __shared__ uint64_t lkey[kSortTile];
+    __shared__ uint32_t lpay[kSortTile];
+    __shared__ unsigned run[4][256];                  // per wavefront: pairs of each digit seen so far
+    __shared__ unsigned start[4][256];                // first place in the tile's layout of a wavefront's pairs of a digit
+    __shared__ int64_t gbase[256];                    // address of the tile's place p holding digit d: gbase[d] + p
+    __shared__ unsigned wsum[4];
     const int wv = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const int64_t tile = int64_t(blockIdx.x) * 4 + wv;
-    if (tile >= ntiles) return;
-    for (int d = lane; d < 256; d += 64) run[wv][d] = bases[d] + tile_offsets[int64_t(d) * ntiles + tile];
-    __builtin_amdgcn_wave_barrier();
-    const int64_t base = tile * kSortTile;
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kSortTile + int64_t(wv) * kSortWave;
+    for (int w = 0; w < 4; ++w) run[w][threadIdx.x] = 0;
+    __syncthreads();
     const unsigned long long lt = (1ull << lane) - 1ull;
+    uint64_t key[kSortItems];
+    uint32_t pay[kSortItems];
+    unsigned rank[kSortItems];                        // among the wavefront's earlier pairs of the same digit
+    // pairs past the end sort last: all-ones keys, and they are the last pairs of the last tile
+#pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         const int64_t e = base + int64_t(i) * 64 + lane;
         const bool live = e < n;
-        uint64_t key = 0;
-        uint32_t pay = 0;
-        if (live) { key = keys_in[e]; pay = pay_in[e]; }
-        const unsigned digit = unsigned(key >> shift) & 255u;
-        unsigned long long peers = __builtin_amdgcn_ballot_w64(live);
+        key[i] = live ? keys_in[e] : ~uint64_t(0);
+        pay[i] = live ? pay_in[e] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const unsigned digit = unsigned(key[i] >> shift) & 255u;
+        unsigned long long peers = ~0ull;
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
             const bool bit = (digit >> b) & 1u;
             const unsigned long long m = __builtin_amdgcn_ballot_w64(bit);
             peers &= bit ? m : ~m;
         }
-        const int rank = __popcll(peers & lt);
-        int64_t pos = 0;
-        if (live) pos = run[wv][digit] + rank;
+        const unsigned before = unsigned(__popcll(peers & lt));
+        rank[i] = run[wv][digit] + before;
         __builtin_amdgcn_wave_barrier();
-        if (live && rank == 0) run[wv][digit] += __popcll(peers);      // the lowest peer advances the bucket
+        if (before == 0) run[wv][digit] += unsigned(__popcll(peers));      // the lowest peer advances the digit's count
         __builtin_amdgcn_wave_barrier();
-        if (live) { keys_out[pos] = key; pay_out[pos] = pay; }
+    }
+    __syncthreads();
+    {
+        // thread d: where digit d begins in the tile's layout, and inside that where each wavefront's share begins
+        const int d = threadIdx.x;
+        unsigned c[4], total = 0;
+        for (int w = 0; w < 4; ++w) { c[w] = run[w][d]; total += c[w]; }
+        unsigned inc = total;
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned up = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += up;
+        }
+        if (lane == 63) wsum[wv] = inc;
+        __syncthreads();
+        unsigned first = inc - total;
+        for (int w = 0; w < wv; ++w) first += wsum[w];
+        gbase[d] = bases[d] + tile_offsets[int64_t(d) * ntiles + tile] - int64_t(first);
+        for (int w = 0; w < 4; ++w) { start[w][d] = first; first += c[w]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const unsigned digit = unsigned(key[i] >> shift) & 255u;
+        const unsigned p = start[wv][digit] + rank[i];
+        lkey[p] = key[i];
+        lpay[p] = pay[i];
+    }
+    __syncthreads();
+    const int64_t rest = n - tile * kSortTile;
+    const int live_pairs = rest < kSortTile ? int(rest) : kSortTile;
+#pragma unroll 4
+    for (int i = 0; i < kSortItems; ++i) {
+        const int p = i * 256 + int(threadIdx.x);
+        if (p < live_pairs) {
+            const uint64_t k = lkey[p];
+            const int64_t pos = gbase[unsigned(k >> shift) & 255u] + p;
+            keys_out[pos] = k;
+            pay_out[pos] = lpay[p];
+        }
     }
 }
 
@@ -254,7 +323,7 @@ conststn_status radix_sort_pairs_u64(uint64_t *keys_a, uint64_t *keys_b, uint32_
     CST_TRY(sbases.alloc(256));
     uint64_t *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
-    const dim3 sgrid(unsigned(div_up(stiles, 4))), sblock(256);
+    const dim3 sgrid{unsigned(stiles)}, sblock(256);
     for (int shift = 0; shift < bits; shift += 8) {
         radix_count_kernel<<<sgrid, sblock, 0, stream>>>(n, kin, shift, scounts.p, stiles);
         scan_tiles_kernel<<<dim3(256), dim3(1024), 0, stream>>>(scounts.p, soffsets.p, stiles, stotals.p);
