@@ -355,61 +355,102 @@ __device__ __forceinline__ unsigned block_exclusive_scan(unsigned v, unsigned *w
 }
 
 // Rank heads and write the level arrays.  A head at level l is also a head at every deeper
-// level, so its child pointer is simply its own rank one level down.
+// level, so its child pointer is simply its own rank one level down.  Thread t of a tile takes the
+// pairs t, t + 256, ...: every read and write of a wavefront is to neighbouring addresses, the tile's
+// keys go through LDS so that each pair sees the one before it, and the values (one read through
+// the sorted position per pair, at random) are requested before anything else is done.  A pair's
+// rank among the heads of a level is its rank in its wavefront's ballot plus the heads of the
+// wavefronts and chunks of 256 before it in the tile.
 template <bool WIDE>
 __global__ void __launch_bounds__(kTileThreads)
 emit_levels_kernel(int64_t nnz, Levels lv, const uint64_t *__restrict__ keys, const uint64_t *__restrict__ keys_hi,
                    const uint32_t *__restrict__ payload, const double *__restrict__ vals_in,
                    const int64_t *__restrict__ tile_offsets, int64_t ntiles, LevelOut out,
                    double *__restrict__ vals_out, int has_dups) {
-    __shared__ unsigned wtot[kTileThreads / 64];
-    const int64_t tile = blockIdx.x;
-    const int64_t base = tile * kTile + int64_t(threadIdx.x) * kItems;
+    static_assert(CONSTSTN_MAX_ORDER * kItems * (kTileThreads / 64) == kTileThreads, "one thread per (level, chunk, wavefront)");
+    constexpr int kWaves = kTileThreads / 64, kSlots = kItems * kWaves;
+    __shared__ uint64_t lkey[kTile + 1];                       // [0]: the last key of the tile before
+    __shared__ uint64_t lkey_hi[WIDE ? kTile + 1 : 1];
+    __shared__ unsigned heads[CONSTSTN_MAX_ORDER][kSlots];     // heads of (chunk, wavefront), then those before it in the tile
+    const int64_t tile = blockIdx.x, base = tile * kTile;
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
     Key2 k[kItems];
-    unsigned headbits[kItems];                       // bit l set: head at level l
-    Key2 prev{0, 0};
-    bool have_prev = false;
-    if (base > 0 && base <= nnz) { prev = load_key<WIDE>(keys, keys_hi, base - 1); have_prev = true; }
-    unsigned cnt[CONSTSTN_MAX_ORDER];
-    for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) cnt[l] = 0;
+    double v[kItems];
+#pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        const int64_t n = base + i;
-        headbits[i] = 0;
+        const int m = i * kTileThreads + int(threadIdx.x);
+        const int64_t n = base + m;
         k[i] = Key2{0, 0};
+        v[i] = 0.0;
         if (n < nnz) {
             k[i] = load_key<WIDE>(keys, keys_hi, n);
-            for (int l = 0; l < lv.order; ++l) {
-                const bool head = !have_prev || !same_prefix<WIDE>(lv, l, k[i], prev);
-                if (head) { headbits[i] |= 1u << l; cnt[l]++; }
-            }
-            prev = k[i];
-            have_prev = true;
+            v[i] = vals_in[payload[n]];
+        }
+        lkey[1 + m] = k[i].lo;
+        if (WIDE) lkey_hi[1 + m] = k[i].hi;
+    }
+    if (threadIdx.x == 0) {
+        lkey[0] = base > 0 ? keys[base - 1] : 0;
+        if (WIDE) lkey_hi[0] = base > 0 ? keys_hi[base - 1] : 0;
+    }
+    __syncthreads();
+    unsigned headbits[kItems];                       // bit l set: head at level l
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int m = i * kTileThreads + int(threadIdx.x);
+        const int64_t n = base + m;
+        headbits[i] = 0;
+        if (n < nnz) {
+            const Key2 prev{WIDE ? lkey_hi[m] : 0, lkey[m]};
+            for (int l = 0; l < lv.order; ++l)
+                if (n == 0 || !same_prefix<WIDE>(lv, l, k[i], prev)) headbits[i] |= 1u << l;
+        }
+#pragma unroll
+        for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) {
+            const unsigned long long mask = __builtin_amdgcn_ballot_w64((headbits[i] >> l) & 1u);
+            if (lane == 0) heads[l][i * kWaves + wave] = unsigned(__popcll(mask));
         }
     }
-    int64_t pos[CONSTSTN_MAX_ORDER];
-    for (int l = 0; l < lv.order; ++l)
-        pos[l] = tile_offsets[int64_t(l) * ntiles + tile] + block_exclusive_scan(cnt[l], wtot);
+    __syncthreads();
+    {
+        // thread (l, slot): exclusive scan over the 32 (chunk, wavefront) slots of level l, in tile order
+        const int l = int(threadIdx.x) / kSlots, slot = int(threadIdx.x) % kSlots;
+        const unsigned mine = heads[l][slot];
+        unsigned inc = mine;
+        for (int off = 1; off < kSlots; off <<= 1) {
+            const unsigned up = __shfl_up(inc, off, kSlots);
+            if (slot >= off) inc += up;
+        }
+        heads[l][slot] = inc - mine;
+    }
+    __syncthreads();
+    const unsigned long long lt = (1ull << lane) - 1ull;
     const int last = lv.order - 1;
+#pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        const int64_t n = base + i;
-        if (n >= nnz) break;
-        for (int l = 0; l < lv.order; ++l) {
-            if (headbits[i] & (1u << l)) {
+        const int64_t n = base + i * kTileThreads + int(threadIdx.x);
+        int64_t pos[CONSTSTN_MAX_ORDER];
+#pragma unroll
+        for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) {
+            const unsigned long long mask = __builtin_amdgcn_ballot_w64((headbits[i] >> l) & 1u);
+            pos[l] = l < lv.order ? tile_offsets[int64_t(l) * ntiles + tile] + heads[l][i * kWaves + wave] + __popcll(mask & lt) : 0;
+        }
+#pragma unroll
+        for (int l = 0; l < CONSTSTN_MAX_ORDER; ++l) {
+            if (l < lv.order && (headbits[i] & (1u << l))) {
                 const uint64_t w = (WIDE && lv.word[l]) ? k[i].hi : k[i].lo;
                 out.idx[l][pos[l]] = int32_t((lv.shift[l] >= 64 ? 0 : (w >> lv.shift[l])) & lv.mask[l]);
-                if (l < last) out.ptr[l][pos[l]] = pos[l + 1];
+                if (l < last) out.ptr[l][pos[l]] = pos[l + 1 < CONSTSTN_MAX_ORDER ? l + 1 : l];
+                if (l == last) {
+                    // leaf head: its value is the sum of the run of equal keys, in input order
+                    // (the sort is stable); without duplicates the run has length one
+                    double sum = v[i];
+                    if (has_dups)
+                        for (int64_t m = n + 1; m < nnz && keys[m] == k[i].lo && (!WIDE || keys_hi[m] == k[i].hi); ++m) sum += vals_in[payload[m]];
+                    vals_out[pos[l]] = sum;
+                }
             }
         }
-        if (headbits[i] & (1u << last)) {
-            // leaf head: its value is the sum of the run of equal keys, in input order
-            // (the sort is stable); without duplicates the run has length one
-            double s = vals_in[payload[n]];
-            if (has_dups)
-                for (int64_t m = n + 1; m < nnz && keys[m] == k[i].lo && (!WIDE || keys_hi[m] == k[i].hi); ++m) s += vals_in[payload[m]];
-            vals_out[pos[last]] = s;
-        }
-        for (int l = 0; l < lv.order; ++l)
-            if (headbits[i] & (1u << l)) pos[l]++;
     }
 }
 
