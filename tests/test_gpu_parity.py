@@ -114,6 +114,45 @@ def test_csf_spans_many_tiles_with_ragged_tail():
         check_csf_bit_exact(csf, c, v, X.dims, mo)
 
 
+@pytest.mark.parametrize("nnz", [1, 63, 64, 65, 255, 256, 257, 2047, 2048, 2049, 4095, 4096, 4097, 6145, 8191, 8192, 8193, 12289])
+def test_csf_sizes_at_tile_edges(nnz):
+    """Sizes one below, at and one above the lengths the build kernels cut their input into (wavefronts of
+    64, chunks of 256, tiles of 2048 and 4096 pairs), and runs of duplicates that begin in one tile and end
+    in the next: summed in input order with the flag, refused without."""
+    dims = (6, 50, 70)
+    rng = np.random.default_rng(300 + nnz)
+    flat = rng.choice(int(np.prod(dims)), size=nnz, replace=False)
+    coords = [c.astype(np.int32) for c in np.unravel_index(flat, dims)]
+    vals = rng.normal(size=nnz)
+    dc = [torch.from_numpy(c).cuda() for c in coords]
+    dv = torch.from_numpy(vals).cuda()
+    for mo in ([0, 1, 2], [2, 0, 1]):
+        _say("csf %d nonzeros, mode_order=%s" % (nnz, mo))
+        csf = cst.build_csf(dc, dv, dims, mo)
+        csf.check()
+        check_csf_bit_exact(csf, coords, vals, dims, mo)
+    if nnz < 2049:
+        return
+    # three more copies of the tuples that sort to places 2047 and 4091: the runs then cover places
+    # 2047..2050 and, three places further back because of the first run, 4094..4097 -- across the edge of a
+    # 2048-pair tile and of a 4096-pair tile
+    key = (coords[0].astype(np.int64) * dims[1] + coords[1]) * dims[2] + coords[2]
+    rank = np.argsort(key, kind="stable")
+    picks = [int(rank[2047])] + ([int(rank[4091])] if nnz > 4094 else [])
+    extra = np.array([p for p in picks for _ in range(3)], dtype=np.int64)
+    weights = rng.integers(2, 9, size=extra.size).astype(np.float64)
+    dup_c = [torch.from_numpy(np.concatenate([c, c[extra]])).cuda() for c in coords]
+    dup_v = torch.from_numpy(np.concatenate([vals, vals[extra] * weights])).cuda()
+    with pytest.raises(cst.ConststnError) as e:
+        cst.build_csf(dup_c, dup_v, dims, [0, 1, 2])
+    assert e.value.status_name == "EDUP"
+    csf = cst.build_csf(dup_c, dup_v, dims, [0, 1, 2], flags=cst.COALESCE_DUPS)
+    want = vals.copy()
+    for p, wgt in zip(extra, weights):                    # in input order: the original first, then the copies as appended
+        want[p] = want[p] + vals[p] * wgt
+    check_csf_bit_exact(csf, coords, want, dims, (0, 1, 2))
+
+
 def test_csf_errors_and_edge_cases():
     dims = (4, 5, 6)
     c = [torch.tensor([1, 1], dtype=torch.int32).cuda(), torch.tensor([2, 2], dtype=torch.int32).cuda(),
