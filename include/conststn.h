@@ -165,7 +165,8 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
                               conststn_plan_t **out);
 
 /* conststn_plan with tuning options: `options` is a host string "name=value,name=value" (NULL or ""
- * = every default; values are non-negative integers; an unknown name is CONSTSTN_EINVAL).  The
+ * = every default; values are non-negative integers; an unknown name, or a value outside what the
+ * option takes, is CONSTSTN_EINVAL and the message names the values it takes).  The
  * options choose among kernel forms and partition sizes that compute the same result; they are read
  * while the plan is built and stored in it -- nothing is read from the environment, and an execute
  * reads no option.  Names (default): force_generic (0; 1 = the generic executor also where a tuned

@@ -488,7 +488,10 @@ static conststn_status parse_plan_options(const char *text, conststn_plan_s *pla
         char *stop = nullptr;
         const long long v = std::strtoll(item.c_str() + eq + 1, &stop, 10);
         if (!stop || *stop != 0 || v < 0) { set_error("plan option '%s': the value must be a non-negative integer", item.c_str()); return CONSTSTN_EINVAL; }
-        if (!known_plan_option(name)) { set_error("unknown plan option '%s'", name.c_str()); return CONSTSTN_EINVAL; }
+        std::string takes;
+        const int known = check_plan_option(name, int64_t(v), takes);
+        if (known == 0) { set_error("unknown plan option '%s'", name.c_str()); return CONSTSTN_EINVAL; }
+        if (known < 0) { set_error("plan option '%s': %s takes %s", item.c_str(), name.c_str(), takes.c_str()); return CONSTSTN_EINVAL; }
         plan->options[name] = int64_t(v);
     }
     return CONSTSTN_OK;

@@ -276,10 +276,14 @@ def test_plan_options_are_checked():
     ops = [("X", csf), ("U3", U3), ("U2", U2)]
     assert "family=generic" in cst.plan(S.TTMC3, ops, options="force_generic=1").describe()
     assert "family=ttmc3" in cst.plan(S.TTMC3, ops, options=" ttmc3_split = 64 , ttmc3_mfma=0 ").describe()
-    for bad in ("no_such_option=1", "ttmc3_split", "ttmc3_split=-4", "ttmc3_split=many"):
-        with pytest.raises(cst.ConststnError) as e:
+    for bad in ("no_such_option=1", "ttmc3_split", "ttmc3_split=-4", "ttmc3_split=many",
+                "ttmc3_split=0", "ttmc3_producers=5", "mttkrp_dual=45", "ttmc3_qn=3", "generic_span=0", "sptn3_tiled=3"):
+        with pytest.raises(cst.ConststnError) as e:       # a value outside what the option takes is refused, never clamped
             cst.plan(S.TTMC3, ops, options=bad)
         assert e.value.status_name == "EINVAL", bad
+    with pytest.raises(cst.ConststnError) as e:
+        cst.plan(S.TTMC3, ops, options="ttmc3_producers=5")
+    assert "2, 3, 4, 6, 8" in str(e.value)
 
 
 def test_mttkrp_mode2_by_rerooted_csf():
