@@ -251,7 +251,10 @@ conststn_status conststn_plan_output_csf(const conststn_plan_t *plan, const cons
  * or TTMc plan (Sec. 5.2, 5.3) stays inside the arrays it indexes: chunk tables against the pointer arrays,
  * the re-encoded leaf stream (LDS slots, factor rows, end-of-fiber / end-of-slice marks), row
  * descriptors, items, K-steps and workgroup batches of the TTMc kernels, and the tensor the kernels
- * walk (conststn_csf_check of it).  CONSTSTN_OK; CONSTSTN_EINVAL with the violations named;
+ * walk (conststn_csf_check of it).  For a plan of the generic executor: the segment tables of its long
+ * sums (every result node's children, or leaves, tiled in order by segments of the stated length), the
+ * lists of nodes with many segments, and the first-leaf tables of fused statements against the
+ * composition of the pointer arrays.  CONSTSTN_OK; CONSTSTN_EINVAL with the violations named;
  * CONSTSTN_EUNSUPPORTED for plans of other kernel families. */
 conststn_status conststn_plan_check(const conststn_plan_t *plan);
 

@@ -1,6 +1,6 @@
 // Index checking: every array the contraction kernels index through another array is checked
 // against the size of what it indexes -- the level arrays of a CSF (conststn_csf_check) and the tables a plan
-// holds for the order-3 MTTKRP and TTMc kernels (conststn_plan_check).  The kernels themselves trust their
+// holds for the order-3 MTTKRP and TTMc kernels and for the generic executor (conststn_plan_check).  The kernels themselves trust their
 // tables (an index out of range there is a memory fault, not an error code); these passes are the
 // debugging aid that turns a wrong table into a message.  One thread per entry, violations are OR-ed
 // into a word of flags that the host reads.  Not part of the timed path.
@@ -23,6 +23,9 @@ enum : unsigned {
     kBadKstep = 1u << 9,       // a K-step with no rows, more than four, rows outside the table or a destination out of range
     kBadBatch = 1u << 10,      // workgroup batches not ascending, not covering the K-steps, or ending inside an item
     kBadItem = 1u << 11,       // an item outside its slice or with a destination out of range
+    kBadLeafTable = 1u << 12,  // a table of first leaves per node that is not the composition of the pointer arrays
+    kBadSegment = 1u << 13,    // segments of a long sum that do not tile the children (or leaves) of their result node in order
+    kBadHeavy = 1u << 14,      // the list of result nodes with many segments names a node that is not one, or misses one
 };
 
 struct CsfView {
@@ -158,6 +161,69 @@ check_ttmc3_kernel(Ttmc3View v, unsigned *flags) {
     if (bad) atomicOr(flags, bad);
 }
 
+// Generic executor, one statement with a long sum: thread t checks segment t against its neighbours and
+// its result node, node t's range of segments, and entry t of the heavy list.
+struct GenSegView {
+    int64_t out_nodes, n_segs, n_heavy, heavy_limit, seg_len;
+    int64_t total;                    // children of the (absent) root, or every leaf, when `range` is null
+    const int64_t *range;             // [out_nodes + 1] first child (fused: first leaf) of each result node
+    const int64_t *seg_ptr, *seg, *heavy;
+};
+__global__ void __launch_bounds__(256)
+check_gen_segments_kernel(GenSegView v, unsigned *flags) {
+    const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    unsigned bad = 0;
+    if (t <= v.out_nodes) {
+        const int64_t a = v.seg_ptr[t];
+        if (a < 0 || a > v.n_segs || (t == 0 && a != 0) || (t == v.out_nodes && a != v.n_segs)) bad |= kBadSegment;
+        else if (t < v.out_nodes) {
+            const int64_t b = v.seg_ptr[t + 1];
+            const int64_t lo = v.range ? v.range[t] : 0, hi = v.range ? v.range[t + 1] : v.total;
+            if (b < a || b > v.n_segs) bad |= kBadSegment;
+            else if (b - a != (hi - lo + v.seg_len - 1) / v.seg_len) bad |= kBadSegment;
+            else if (b > a && (v.seg[3 * a + 1] != lo || v.seg[3 * (b - 1) + 2] != hi)) bad |= kBadSegment;
+            else if (b - a > v.heavy_limit) {                 // then the node is on the heavy list
+                int64_t l0 = 0, l1 = v.n_heavy;
+                while (l1 - l0 > 1) {
+                    const int64_t mid = (l0 + l1) >> 1;
+                    if (v.heavy[mid] <= t) l0 = mid; else l1 = mid;
+                }
+                if (v.n_heavy == 0 || v.heavy[l0] != t) bad |= kBadHeavy;
+            }
+        }
+    }
+    if (t < v.n_segs) {
+        const int64_t p = v.seg[3 * t], e0 = v.seg[3 * t + 1], e1 = v.seg[3 * t + 2];
+        if (p < 0 || p >= v.out_nodes) bad |= kBadSegment;
+        else {
+            const int64_t a = v.seg_ptr[p], b = v.seg_ptr[p + 1];
+            if (t < a || t >= b || e1 <= e0 || e1 - e0 > v.seg_len) bad |= kBadSegment;
+            else if (t + 1 < b && v.seg[3 * (t + 1) + 1] != e1) bad |= kBadSegment;
+        }
+    }
+    if (t < v.n_heavy) {
+        const int64_t p = v.heavy[t];
+        if (p < 0 || p >= v.out_nodes || (t > 0 && v.heavy[t - 1] >= p)) bad |= kBadHeavy;
+        else if (v.seg_ptr[p + 1] - v.seg_ptr[p] <= v.heavy_limit) bad |= kBadHeavy;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+// table[x] = below[ptr[x]] for x = 0 .. nodes (below = null: the identity, i.e. table = ptr)
+__global__ void __launch_bounds__(256)
+check_gen_leaf_table_kernel(const int64_t *table, const int64_t *ptr, const int64_t *below, int64_t nodes, unsigned *flags) {
+    const int64_t x = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (x > nodes) return;
+    const int64_t c = ptr[x];
+    if (table[x] != (below ? below[c] : c)) atomicOr(flags, unsigned(kBadLeafTable));
+}
+
+// out[x] = below ? below[ptr[x]] : ptr[x]
+__global__ void __launch_bounds__(256)
+gather_i64_kernel(const int64_t *ptr, const int64_t *below, int64_t count, int64_t *out) {
+    const int64_t x = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (x < count) out[x] = below ? below[ptr[x]] : ptr[x];
+}
+
 conststn_status report(unsigned bits, const char *what) {
     if (!bits) return CONSTSTN_OK;
     static const char *const names[] = {"an index outside its extent", "a pointer array that does not start at 0",
@@ -166,9 +232,10 @@ conststn_status report(unsigned bits, const char *what) {
                                         "siblings that are not strictly ascending", "a chunk table entry off its leaf",
                                         "slice_leaf off the pointer arrays", "a re-encoded leaf out of range or with a wrong end mark",
                                         "a row descriptor out of range", "a K-step out of range", "workgroup batches that are not whole items in order",
-                                        "an item outside its slice"};
+                                        "an item outside its slice", "a first-leaf table off the pointer arrays",
+                                        "segments that do not tile their result node", "a wrong list of nodes with many segments"};
     std::string msg;
-    for (int b = 0; b < 12; ++b)
+    for (int b = 0; b < 15; ++b)
         if (bits & (1u << b)) { if (!msg.empty()) msg += "; "; msg += names[b]; }
     set_error("%s: %s", what, msg.c_str());
     return CONSTSTN_EINVAL;
@@ -181,6 +248,64 @@ conststn_status run_csf_check(const conststn_csf_s *c, unsigned *dflags) {
         check_level_kernel<<<dim3(unsigned(div_up(c->nodes[l], 256))), dim3(256)>>>(v, l, dflags);
         CST_HIP(hipGetLastError());
     }
+    return CONSTSTN_OK;
+}
+
+// The tables of a generic plan: per statement with a long sum the segment table and the list of nodes
+// with many segments; per fused statement the first-leaf tables of the levels it walks.
+conststn_status check_generic_tables(const conststn_plan_s *plan, unsigned *dflags) {
+    const conststn_csf_s *X = plan->X;
+    const int n = X->order;
+    for (const GenStmt &g : plan->gen) {
+        if (g.skip) continue;
+        if (g.fused) {
+            // (table, level): the result's nodes and the levels between the summed level and the fibers
+            std::vector<std::pair<const int64_t *, int>> tables;
+            if (g.out_leaf) tables.push_back({g.out_leaf, g.d_out - 1});
+            for (int v = 1; v <= g.fused_upper; ++v) tables.push_back({g.leaf_end[v - 1], n - 2 - v});
+            for (const auto &tl : tables) {
+                const int L = tl.second;
+                if (L < 0 || L > n - 2 || !tl.first) { set_error("plan tables: a first-leaf table for level %d of an order-%d tensor", L, n); return CONSTSTN_EINVAL; }
+                // compare with the composition from the fibers upwards, one level at a time through scratch tables
+                DevBuf<int64_t> scratch[2];
+                int which = 0;
+                const int64_t *cur = nullptr;                         // first leaves of level l + 1 (null: the leaves themselves)
+                for (int l = n - 2; l >= L; --l) {
+                    if (l == L) {
+                        check_gen_leaf_table_kernel<<<dim3(unsigned(div_up(X->nodes[l] + 1, 256))), dim3(256)>>>(
+                            tl.first, X->ptr[l].p, cur, X->nodes[l], dflags);
+                        CST_HIP(hipGetLastError());
+                        break;
+                    }
+                    DevBuf<int64_t> &mine = scratch[which];
+                    which ^= 1;
+                    CST_TRY(mine.alloc(size_t(X->nodes[l] + 1)));
+                    gather_i64_kernel<<<dim3(unsigned(div_up(X->nodes[l] + 1, 256))), dim3(256)>>>(X->ptr[l].p, cur, X->nodes[l] + 1, mine.p);
+                    CST_HIP(hipGetLastError());
+                    CST_HIP(hipDeviceSynchronize());                     // the other buffer may be released at the next turn
+                    cur = mine.p;
+                }
+                CST_HIP(hipDeviceSynchronize());
+            }
+        }
+        if (g.n_segs > 0) {
+            GenSegView v{};
+            v.out_nodes = g.out_nodes;
+            v.n_segs = g.n_segs;
+            v.n_heavy = g.n_heavy;
+            v.heavy_limit = kGenHeavy;
+            v.seg_len = g.fused ? kGenLeafSegment : kGenSegment;
+            v.total = g.fused ? X->nnz : X->nodes[0];
+            v.range = g.fused ? g.out_leaf : (g.d_out > 0 ? X->ptr[g.d_out - 1].p : nullptr);
+            v.seg_ptr = plan->gen_tables[size_t(g.seg_table)]->p;
+            v.seg = plan->gen_tables[size_t(g.seg_table) + 1]->p;
+            v.heavy = plan->gen_tables[size_t(g.seg_table) + 2]->p;
+            const int64_t threads = std::max(std::max(v.out_nodes + 1, v.n_segs), v.n_heavy);
+            check_gen_segments_kernel<<<dim3(unsigned(div_up(threads, 256))), dim3(256)>>>(v, dflags);
+            CST_HIP(hipGetLastError());
+        }
+    }
+    CST_HIP(hipDeviceSynchronize());
     return CONSTSTN_OK;
 }
 
@@ -209,14 +334,20 @@ extern "C" conststn_status conststn_plan_check(const conststn_plan_t *plan) {
     clear_error();
     if (!plan) { set_error("null argument"); return CONSTSTN_EINVAL; }
     const conststn_csf_s *X = plan->X;
-    if (!X || (plan->family != FAM_MTTKRP3 && plan->family != FAM_TTMC3)) {
-        set_error("the table check covers the order-3 MTTKRP and TTMc plans");
+    if (!X || (plan->family != FAM_MTTKRP3 && plan->family != FAM_TTMC3 && plan->family != FAM_GENERIC)) {
+        set_error("the table check covers the order-3 MTTKRP and TTMc plans and those of the generic executor");
         return CONSTSTN_EUNSUPPORTED;
     }
     DevBuf<unsigned> flags;
     CST_TRY(flags.alloc(1));
     CST_HIP(hipMemset(flags.p, 0, sizeof(unsigned)));
     CST_TRY(run_csf_check(X, flags.p));                    // the tensor the kernels walk (the private copy, if one was made)
+    if (plan->family == FAM_GENERIC) {
+        CST_TRY(check_generic_tables(plan, flags.p));
+        unsigned hg = 0;
+        CST_HIP(hipMemcpy(&hg, flags.p, sizeof(hg), hipMemcpyDeviceToHost));
+        return report(hg, "plan tables");
+    }
     const int64_t dim1 = X->dims[X->mode_order[1]], dim2 = X->dims[X->mode_order[2]];
     if (X->nnz > 0 && plan->family == FAM_MTTKRP3) {
         auto launch = [&](const MttkrpView &m) -> conststn_status {

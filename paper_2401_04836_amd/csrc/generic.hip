@@ -348,7 +348,6 @@ static void launch_fused(const GenStmt &g, dim3 grid, hipStream_t stream) {
 
 // second pass of a long sum: the partial sums of each result node, added in segment order.  Nodes
 // with more than kGenHeavy segments are left to the kernel below.
-constexpr int64_t kGenHeavy = 64;
 __global__ void __launch_bounds__(256)
 generic_segsum_kernel(GenStmt g) {
     const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -418,7 +417,6 @@ __global__ void generic_heavy_list_kernel(const int64_t *flag, const int64_t *po
 }
 
 // segments of kGenSegment children: how many per result node, then their ranges
-constexpr int64_t kGenSegment = 256;
 __global__ void generic_seg_count_kernel(const int64_t *ptr, int64_t nodes, int64_t roots, int64_t *count) {
     const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (p >= nodes) return;
@@ -439,7 +437,6 @@ __global__ void generic_seg_fill_kernel(const int64_t *ptr, int64_t nodes, int64
 
 // The same for a statement whose producer is inlined: its work is counted in X's leaves, so the
 // leaves below a result node are cut into ranges of kGenLeafSegment, wherever the fibers end.
-constexpr int64_t kGenLeafSegment = 512;
 __global__ void generic_leafseg_count_kernel(const int64_t *out_leaf, int64_t nodes, int64_t leaves, int64_t *count) {
     const int64_t p = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (p >= nodes) return;

@@ -26,6 +26,9 @@ enum Family { FAM_NONE = 0, FAM_TTMC3, FAM_TTMC4, FAM_MTTKRP3, FAM_SPTN3, FAM_GE
 // next n_red are summed over; strides are in elements, 0 where a tensor lacks the index.
 constexpr int kGenMaxIdx = 8;
 constexpr int kGenMaxUpper = 2;
+constexpr int64_t kGenSegment = 256;          // children per segment of a long sum
+constexpr int64_t kGenLeafSegment = 512;      // leaves per segment when the producers are inlined
+constexpr int64_t kGenHeavy = 64;             // a result node with more segments than this is added up by workgroups
 struct GenStmt {
     int kind;                                  // 0: one thread per result element walks the subtree below its node;
                                                // 1: one thread per (node of depth d_node, dense result element)

@@ -126,6 +126,7 @@ def test_config2_mttkrp_full_size_both_modes():
         # leaves, the heaviest slices added by a workgroup)
         gen = cst.plan(sched, [("X", csf), (names[0], facs[0]), (names[1], facs[1])], options="force_generic=1")
         assert "inlined_producers=1" in gen.describe(), gen.describe()
+        gen.check()
         out = cst.execute(gen, list(facs)).reshape(gen.n_rows, -1)
         torch.cuda.synchronize()
         err = oracle.rel_err(out.cpu().numpy(), want, S_abs)
@@ -274,6 +275,7 @@ def test_config3_ttmc4_full_size():
     dev = [t.cuda() for t in (D, C, B)]
     pl = cst.plan(text, [("X", csf), ("D", dev[0]), ("C", dev[1]), ("B", dev[2])])
     assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
+    pl.check()
     out = cst.execute(pl, dev).reshape(pl.n_rows, R)
     torch.cuda.synchronize()
     picks = pick_slices(slice_sizes(csf), n_light=16, seed=3)

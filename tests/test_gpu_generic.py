@@ -45,6 +45,8 @@ def _run(text, x, mode_order, dense, out_shape, fusion=None, flags=0, expect="ge
     desc = pl.describe()
     _say("  " + desc.split("|")[0])
     assert ("family=" + expect) in desc, desc
+    if expect == "generic":
+        pl.check()                                # segment tables, heavy-node lists, first-leaf tables
     out = cst.execute(pl, [t for _, t in dev])
     torch.cuda.synchronize()
     assert pl.n_rows * pl.row_elems == int(np.prod(out_shape)), (pl.n_rows, pl.row_elems, out_shape)

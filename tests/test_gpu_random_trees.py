@@ -108,6 +108,7 @@ def test_random_chain(seed):
     dev = [(n, torch.from_numpy(np.ascontiguousarray(a)).cuda()) for n, _, a in ops]
     pl = cst.plan(text, [("X", csf)] + dev, fusion=fusion, options=options)
     print("       " + pl.describe().split("|")[0], flush=True)
+    pl.check()
     out = cst.execute(pl, [t for _, t in dev])
     torch.cuda.synchronize()
     shape = [extents[c] for c in out_idx]
