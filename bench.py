@@ -4,7 +4,8 @@
 A step is one pass of the fused contraction over one synthetic batch with the CSF already
 resident in HBM.  With no --config the five configurations run one after the other in one
 process (5, 2, 3, 4, 1), followed by the two sparse-result networks of Sec. 5.1 (6: the three-index
-transformation, 7: the four-index product); the headline (value, ms_per_step, roofline,
+transformation, 7: the four-index product) and, as record 8, the order-4 MTTKRP on configuration 3's
+tensor; the headline (value, ms_per_step, roofline,
 cpu_baseline) is that of configuration 5, the largest that fits one GPU (order-3 TTMc, 140 M
 nonzeros, ranks 64 x 64, 47 GB of output), and "configs" holds the same record for every
 configuration.  For
@@ -273,6 +274,22 @@ def build_sppair(cst, S, wl, dev):
     return [dict(plan=pl, factors=[], out=out, nodes=nodes, bytes=alg_bytes, flops=flops, keep=(hE, chain))], build_s, 2 * ev.numel()
 
 
+def cpu_baseline_mttkrp4(wl, factors, budget_nnz):
+    """The N-ary reference (numpy) on the first nonzeros of the order-4 tensor; factors = [D, C, B]."""
+    from oracle import nary
+    X = wl.sparse["X"]
+    n = int(min(X.nnz, max(1000, budget_nnz // 400)))
+    c = [x[:n].cpu().numpy() for x in X.coords]
+    v = X.vals[:n].cpu().numpy()
+    D, C, B = (f.cpu().numpy() for f in factors)
+    t0 = time.perf_counter()
+    nary.contract(c, v, "ijkl", [(B, "jr"), (C, "kr"), (D, "lr")], "ir", {"i": X.dims[0], "r": B.shape[1]})
+    dt = time.perf_counter() - t0
+    # numpy's einsum (no BLAS in this product) and add.at run on the calling thread
+    return dict(value=n / dt, unit="nnz/s", cores=1, kind="oracle",
+                sample="N-ary sum over the first %d nonzeros (input order), %.2f s" % (n, dt))
+
+
 def cpu_baseline(wl, budget_nnz):
     """The CPU oracle, as it stands, on a bounded sample (first nonzeros) of the same workload."""
     import oracle
@@ -533,6 +550,8 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
                                              "frac": tf / FP64_PEAK_TFLOPS}
     if wl.kind in ("ttmc3", "mttkrp3", "ttmc4") and family != "generic" and cid == 1:
         rec["roofline"]["note"] = "0.3 MB problem: launch latency, no roofline claim"
+    if not args.no_cpu and args.mttkrp4 and wl.kind == "ttmc4":
+        rec["cpu_baseline"] = cpu_baseline_mttkrp4(wl, launches[0]["factors"], cpu_budget)
     if not args.no_cpu and not args.mttkrp4:
         cb = cpu_baseline(wl, cpu_budget)
         if cb is not None:
@@ -612,6 +631,13 @@ def main():
     # configuration in the five-configuration run
     cpu_budget = 400_000_000 if len(cids) == 1 else 1_200_000_000
     recs = [run_config(cst, S, dev, args, cid, cpu_budget) for cid in cids]
+    if args.config == 0 and not args.mttkrp4:
+        # beside the configurations: the order-4 MTTKRP on configuration 3's tensor (a fused chain in one generic kernel)
+        args.mttkrp4 = True
+        extra = run_config(cst, S, dev, args, 3, cpu_budget)
+        extra["config_id"] = 8
+        recs.append(extra)
+        args.mttkrp4 = False
     head = recs[0]
     result = {
         "metric": "fused sparse contraction nnz/s", "value": head["nnz_per_s"],

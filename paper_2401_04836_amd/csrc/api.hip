@@ -471,6 +471,49 @@ conststn_status conststn_plan(const char *schedule, const int *fusion, int n_ope
     return conststn_plan_options(schedule, fusion, n_operands, operands, flags, nullptr, out);
 }
 
+// Every plan option with the values it takes: a range, or (lo > hi) the listed values only.
+struct PlanOptionRange { const char *name; int64_t lo, hi; int64_t listed[5]; };
+static const PlanOptionRange kPlanOptions[] = {
+    {"force_generic", 0, 1, {}},       {"generic_max_gb", 1, 4096, {}},   {"generic_span", 1, int64_t(1) << 30, {}},
+    {"generic_fuse", 0, 1, {}},        {"generic_densify", 0, 1, {}},     {"reroot", 0, 1, {}},
+    {"mttkrp_split", 0, 1, {}},        {"mttkrp_dual", 1, 0, {0, 35, 44, 53, 88}},
+    {"mttkrp_hot", 1, int64_t(1) << 20, {}},                              {"mttkrp_chunk", 0, int64_t(1) << 24, {}},
+    {"ttmc3_mfma", 0, 1, {}},          {"ttmc3_stream", 0, 1, {}},        {"ttmc3_producers", 1, 0, {2, 3, 4, 6, 8}},
+    {"ttmc3_batch", 1, int64_t(1) << 30, {}},                             {"ttmc3_itemcost", 0, int64_t(1) << 20, {}},
+    {"ttmc3_qn", 1, 0, {1, 2, 4, 4, 4}},
+    {"ttmc3_split", 1, int64_t(1) << 40, {}},                             {"ttmc3_rowsplit", 1, int64_t(1) << 40, {}},
+    {"ttmc4_mfma", 0, 1, {}},          {"ttmc4_split", 1, int64_t(1) << 40, {}},
+    {"ttmc4_ksplit", 1, int64_t(1) << 40, {}},
+    {"sptn3_tiled", 0, 2, {}},         {"sptn3_waves", 1, 2, {}},         {"sptn3_wgs", 1, int64_t(1) << 24, {}},
+    {"sptn3_xcd", 0, 1, {}},
+    {"spchain3_form", 1, 2, {}},       {"spchain3_order", 0, 1, {}},      {"spchain3_local_kb", 1, 160, {}},
+    {"spchain3_pk_gb", 0, 4096, {}},
+    {"sppair4_keep", 1, 2, {}},        {"sppair4_keep_gb", 0, 4096, {}},  {"sppair4_rows", 1, 2, {}},
+    {"sppair4_rows_gb", 0, 4096, {}},  {"sppair4_buffers", 1, 2, {}},     {"sppair4_xcd", 0, 2, {}}};
+
+// 0: no such option; 1: the value is one it takes; -1: it is not, and `takes` says which are
+static int check_plan_option(const std::string &name, int64_t value, std::string &takes) {
+    for (const PlanOptionRange &o : kPlanOptions) {
+        if (name != o.name) continue;
+        char b[96];
+        if (o.lo <= o.hi) {
+            if (value >= o.lo && value <= o.hi) return 1;
+            snprintf(b, sizeof(b), "%lld to %lld", (long long)o.lo, (long long)o.hi);
+            takes = b;
+            return -1;
+        }
+        takes.clear();
+        for (int k = 0; k < 5; ++k) {
+            if (value == o.listed[k]) return 1;
+            if (k > 0 && o.listed[k] == o.listed[k - 1]) continue;
+            snprintf(b, sizeof(b), "%s%lld", k ? ", " : "", (long long)o.listed[k]);
+            takes += b;
+        }
+        return -1;
+    }
+    return 0;
+}
+
 // "name=value,name=value" (spaces allowed around the separators) into the plan's option table
 static conststn_status parse_plan_options(const char *text, conststn_plan_s *plan) {
     if (!text) return CONSTSTN_OK;

@@ -383,7 +383,6 @@ struct ProfScope {
 };
 
 // names conststn_plan_options accepts
-int check_plan_option(const std::string &name, int64_t value, std::string &takes);   // 0 unknown, 1 fine, -1 value not taken
 // kernels with more dynamic LDS than the default limit: raised once per plan build
 conststn_status prepare_mttkrp3_launch(conststn_plan_s *plan);
 conststn_status prepare_sptn3_launch(conststn_plan_s *plan);
