@@ -434,11 +434,8 @@ mttkrp3_add_kernel(double2 *__restrict__ out, const double2 *__restrict__ add, i
 // Rows of slices shared by several chunks: add the partial rows in chunk order.
 // One block per slice; G lane groups stride over the chunks, then a fixed-order LDS reduction.
 template <int LPR>
-__global__ void __launch_bounds__(256)
-mttkrp3_fixup_kernel(MttkrpArgs a) {
+__device__ __forceinline__ void mttkrp3_fixup_body(const MttkrpArgs &a, int64_t s, double *red) {
     constexpr int G = 256 / LPR;
-    __shared__ double red[256 * 2];
-    const int64_t s = blockIdx.x;
     const int64_t lo = a.slice_leaf[s], hi = a.slice_leaf[s + 1];
     const int64_t ca = lo / a.q, cb = (hi - 1) / a.q;
     if (ca == cb) return;                           // stored directly by the main kernel
@@ -469,16 +466,19 @@ mttkrp3_fixup_kernel(MttkrpArgs a) {
         if (r0 + 1 < R) a.out[row * R + r0 + 1] = y;
     }
 }
+template <int LPR>
+__global__ void __launch_bounds__(256)
+mttkrp3_fixup_kernel(MttkrpArgs a) {
+    __shared__ double red[256 * 2];
+    mttkrp3_fixup_body<LPR>(a, blockIdx.x, red);
+}
 
 // Heavy slices (shared by at least kHeavySpan chunks): stage 1 reduces kHeavySegments equal
 // segments of the slice's chunk range in parallel, stage 2 adds the segment sums in order.
 template <int LPR>
-__global__ void __launch_bounds__(256)
-mttkrp3_fixup_heavy_kernel(MttkrpArgs a) {
+__device__ __forceinline__ void mttkrp3_fixup_heavy_body(const MttkrpArgs &a, int64_t h, int seg, double *red) {
     constexpr int G = 256 / LPR;
-    __shared__ double red[256 * 2];
-    const int64_t s = a.heavy_slices[blockIdx.x];
-    const int seg = blockIdx.y;
+    const int64_t s = a.heavy_slices[h];
     const int64_t lo = a.slice_leaf[s], hi = a.slice_leaf[s + 1];
     const int64_t ca = lo / a.q, cb = (hi - 1) / a.q;
     const int64_t n = cb - ca + 1;
@@ -500,23 +500,70 @@ mttkrp3_fixup_heavy_kernel(MttkrpArgs a) {
             x += red[(gg * LPR + gl) * 2];
             y += red[(gg * LPR + gl) * 2 + 1];
         }
-        double *dst = a.heavy_partial + (int64_t(blockIdx.x) * kHeavySegments + seg) * R;
+        double *dst = a.heavy_partial + (h * kHeavySegments + seg) * R;
         if (r0 < R) dst[r0] = x;
         if (r0 + 1 < R) dst[r0 + 1] = y;
     }
 }
+template <int LPR>
+__global__ void __launch_bounds__(256)
+mttkrp3_fixup_heavy_kernel(MttkrpArgs a) {
+    __shared__ double red[256 * 2];
+    mttkrp3_fixup_heavy_body<LPR>(a, blockIdx.x, int(blockIdx.y), red);
+}
 
-__global__ void __launch_bounds__(128)
-mttkrp3_fixup_final_kernel(MttkrpArgs a) {
-    const int64_t s = a.heavy_slices[blockIdx.x];
+__device__ __forceinline__ void mttkrp3_fixup_final_body(const MttkrpArgs &a, int64_t h) {
+    const int64_t s = a.heavy_slices[h];
     const int r = threadIdx.x;
     if (r >= a.R) return;
     double x = 0.0;
     for (int seg = 0; seg < kHeavySegments; ++seg)
-        x += a.heavy_partial[(int64_t(blockIdx.x) * kHeavySegments + seg) * a.R + r];
+        x += a.heavy_partial[(h * kHeavySegments + seg) * a.R + r];
     const int64_t row = a.compact ? s : int64_t(a.idx0[s]);
     if (a.accumulate) x += a.out[row * a.R + r];
     a.out[row * a.R + r] = x;
+}
+__global__ void __launch_bounds__(128)
+mttkrp3_fixup_final_kernel(MttkrpArgs a) {
+    mttkrp3_fixup_final_body(a, blockIdx.x);
+}
+
+// The same three passes for two sub-tensors that write different outputs, in one launch each: the
+// first blocks take the first sub-tensor's slices (heavy slices), the others the second's.
+struct MttkrpPairArgs { MttkrpArgs first, second; };
+template <int LPR>
+__global__ void __launch_bounds__(256)
+mttkrp3_fixup_pair_kernel(MttkrpPairArgs p) {
+    __shared__ double red[256 * 2];
+    if (int64_t(blockIdx.x) < p.first.slices) mttkrp3_fixup_body<LPR>(p.first, blockIdx.x, red);
+    else mttkrp3_fixup_body<LPR>(p.second, int64_t(blockIdx.x) - p.first.slices, red);
+}
+template <int LPR>
+__global__ void __launch_bounds__(256)
+mttkrp3_fixup_heavy_pair_kernel(MttkrpPairArgs p) {
+    __shared__ double red[256 * 2];
+    if (int(blockIdx.x) < p.first.n_heavy) mttkrp3_fixup_heavy_body<LPR>(p.first, blockIdx.x, int(blockIdx.y), red);
+    else mttkrp3_fixup_heavy_body<LPR>(p.second, int64_t(blockIdx.x) - p.first.n_heavy, int(blockIdx.y), red);
+}
+__global__ void __launch_bounds__(128)
+mttkrp3_fixup_final_pair_kernel(MttkrpPairArgs p) {
+    if (int(blockIdx.x) < p.first.n_heavy) mttkrp3_fixup_final_body(p.first, blockIdx.x);
+    else mttkrp3_fixup_final_body(p.second, int64_t(blockIdx.x) - p.first.n_heavy);
+}
+
+template <int LPR>
+static conststn_status launch_fixup_pair(const MttkrpArgs &a0, const MttkrpArgs &a1, hipStream_t stream) {
+    const MttkrpPairArgs p{a0, a1};
+    mttkrp3_fixup_pair_kernel<LPR><<<dim3(unsigned(a0.slices + a1.slices)), dim3(256), 0, stream>>>(p);
+    CST_HIP(hipGetLastError());
+    const int nh = a0.n_heavy + a1.n_heavy;
+    if (nh > 0) {
+        mttkrp3_fixup_heavy_pair_kernel<LPR><<<dim3(unsigned(nh), kHeavySegments), dim3(256), 0, stream>>>(p);
+        CST_HIP(hipGetLastError());
+        mttkrp3_fixup_final_pair_kernel<<<dim3(unsigned(nh)), dim3(128), 0, stream>>>(p);
+        CST_HIP(hipGetLastError());
+    }
+    return CONSTSTN_OK;
 }
 
 template <int LPR>
@@ -673,7 +720,7 @@ conststn_status launch_mttkrp3(const conststn_plan_s *plan, const double *const 
                     }
                     CST_HIP(hipGetLastError());
                 }
-                for (int part = 0; part < 2; ++part) CST_TRY(launch_fixup<16>(pa[part].base, stream));
+                CST_TRY(launch_fixup_pair<16>(pa[0].base, pa[1].base, stream));      // different outputs: no order between them
                 mttkrp3_add_kernel<<<dim3(unsigned(div_up(n / 2, 256))), dim3(256), 0, stream>>>(
                     reinterpret_cast<double2 *>(out), reinterpret_cast<const double2 *>(plan->mttkrp_out2.p), n / 2);
                 CST_HIP(hipGetLastError());
