@@ -513,7 +513,7 @@ def run_config(cst, S, dev, args, cid, cpu_budget):
         name += " [generic executor]"
     plain = not (args.small or args.restricted or args.all_modes or args.mttkrp4)
     rec = {
-        "config_id": cid, "workload": name, "kind": wl.kind,
+        "config_id": cid, "workload": name, "kind": "mttkrp4" if (args.mttkrp4 and wl.kind == "ttmc4") else wl.kind,
         "ms_per_step": ms_per_step, "nnz_per_step": nnz_per_step, "nnz_per_s": nnz_per_step / (dt / args.steps),
         "gflops": flops_step / (dt / args.steps) / 1e9,
         "fp64_frac": flops_step / (dt / args.steps) / 1e12 / FP64_PEAK_TFLOPS,
