@@ -662,10 +662,12 @@ conststn_status conststn_plan_options(const char *schedule, const int *fusion, i
         plan->description += b;
     }
     if (plan->family == FAM_GENERIC) {
-        int fused = 0;
-        for (const GenStmt &g : plan->gen) fused += g.skip;
-        char b[64];
+        int fused = 0, pairs = 0;
+        for (const GenStmt &g : plan->gen) { fused += g.skip; pairs += (g.fused && !g.skip && g.fused_pairs) ? 1 : 0; }
+        char b[96];
         snprintf(b, sizeof(b), " kernels=%d inlined_producers=%d", int(plan->gen.size()) - fused, fused);
+        plan->description += b;
+        snprintf(b, sizeof(b), " two_elements_per_lane=%d", pairs);
         plan->description += b;
         if (!plan->gen_densified.empty()) {
             snprintf(b, sizeof(b), " dense_copies_of_csf_operands=%d", int(plan->gen_densified.size()));

@@ -147,18 +147,24 @@ generic_stmt_kernel(GenStmt g) {
 // order of addition, no atomics.
 // SMALL: both factors are below 2 GiB with fewer than 2^24 rows of fewer than 2^24 bytes, so that a row's
 // byte offset is one 24-bit multiply-add instead of 64-bit arithmetic.
-template <int W, bool SMALL, int U>
+// V: result elements per lane, 1 or 2.  Two when the plan found that the innermost dense index is even,
+// runs with stride 1 through every factor and the result, and every row begins on 16 bytes: a lane then
+// reads its two entries of a row with one 16-byte load, and a gather instruction costs the address unit
+// about as much for 16 bytes per lane as for 8.
+template <int V> struct GenVals { double v[V]; };
+template <int W, bool SMALL, int U, int V>
 __global__ void __launch_bounds__(256)
 generic_fused_kernel(GenStmt g) {
     using offs = typename std::conditional<SMALL, uint32_t, int64_t>::type;
+    using vals = GenVals<V>;
     const int64_t grp = (int64_t(blockIdx.x) * 256 + threadIdx.x) / W;
     const int j = int(threadIdx.x) % W;
     const bool segmented = g.n_segs > 0;
-    const int64_t chunks = (g.out_block + W - 1) / W;
+    const int64_t chunks = (g.out_block + W * V - 1) / (W * V);
     if (grp >= (segmented ? g.n_segs : g.out_nodes) * chunks) return;        // whole groups leave together
     const int64_t unit = grp / chunks;
     const int64_t p = segmented ? g.seg[3 * unit] : unit;
-    const int64_t o_lin = (grp - unit * chunks) * W + j;
+    const int64_t o_lin = ((grp - unit * chunks) * W + j) * V;
     const bool live = o_lin < g.out_block;                   // idle lanes compute element 0 and store nothing
     int64_t rem = live ? o_lin : 0;
     int64_t f_off0 = 0, f1_off0 = 0, out_off = 0, fu_off0[U + 1] = {};
@@ -187,10 +193,23 @@ generic_fused_kernel(GenStmt g) {
     l_fs[U] = offs(g.f_level_stride[g.d_out] * 8);
     const offs f1_lane = offs(f1_off0 * 8), fs1 = offs(g.f1_level_stride * 8);
     const char *f1b = reinterpret_cast<const char *>(g.f1);
-    auto row = [](const char *base, int32_t i, offs stride, offs lane) -> double {
-        if constexpr (SMALL) return *reinterpret_cast<const double *>(base + (__umul24(uint32_t(i), stride) + lane));
-        else return *reinterpret_cast<const double *>(base + (int64_t(i) * stride + lane));
+    auto row = [](const char *base, int32_t i, offs stride, offs lane) -> vals {
+        const char *at;
+        if constexpr (SMALL) at = base + (__umul24(uint32_t(i), stride) + lane);
+        else at = base + (int64_t(i) * stride + lane);
+        vals r;
+        if constexpr (V == 2) {
+            const double2 x = *reinterpret_cast<const double2 *>(at);
+            r.v[0] = x.x;
+            r.v[1] = x.y;
+        } else {
+            r.v[0] = *reinterpret_cast<const double *>(at);
+        }
+        return r;
     };
+    auto zero = []() { vals r; for (int e = 0; e < V; ++e) r.v[e] = 0.0; return r; };
+    auto fma_s = [](double x, const vals &y, vals &acc) { for (int e = 0; e < V; ++e) acc.v[e] = fma(x, y.v[e], acc.v[e]); };
+    auto fma_v = [](const vals &x, const vals &y, vals &acc) { for (int e = 0; e < V; ++e) acc.v[e] = fma(x.v[e], y.v[e], acc.v[e]); };
     int64_t c0, c1;                                          // the result node's children
     if (g.d_out == 0) { c0 = 0; c1 = g.roots; }
     else { c0 = g.ptr[g.d_out - 1][p]; c1 = g.ptr[g.d_out - 1][p + 1]; }
@@ -208,7 +227,9 @@ generic_fused_kernel(GenStmt g) {
     constexpr int kFar = 1 << 30;                            // positions count from e0 and saturate here
     auto near = [&](int64_t e) { const int64_t d = e - e0; return d < kFar ? int(d) : kFar; };
     const int n_total = near(e_end);                         // the plan keeps a unit's leaves below kFar
-    double s[U + 1] = {};                                    // running sums: s[v] over the finished children of the
+    vals s[U + 1];                                           // running sums: s[v] over the finished children of the
+#pragma unroll
+    for (int v = 0; v <= U; ++v) s[v] = zero();
     if (n_total > 0) {                                       // current node of level v + 1 (s[U]: of the result node)
         // the last node of [lo, hi) whose first leaf is not after e0
         auto holder = [&](const int64_t *first_leaf, int64_t lo, int64_t hi) {
@@ -221,7 +242,7 @@ generic_fused_kernel(GenStmt g) {
         // levels above the fibers: the current node, where it ends, its factor, and the same one node ahead
         int64_t cu[U + 1];
         int endu[U + 1], endu2[U + 1];
-        double fvu[U + 1], fvu2[U + 1];
+        vals fvu[U + 1], fvu2[U + 1];
         auto upper_ahead = [&](int v) {                      // (endu2, fvu2) of node cu + 1 of level v
             const int L = fiber_level - v;
             if (cu[v] + 1 >= g.nodes[L]) { endu2[v] = kFar; return; }
@@ -253,9 +274,9 @@ generic_fused_kernel(GenStmt g) {
         };
         load_fibers();
         int next = __shfl(w_end, 0, W);                      // end of the current fiber, its factor; then the same one fiber ahead
-        double fv = row(lb[0], __shfl(w_ix, 0, W), l_fs[0], l_lane[0]);
+        vals fv = row(lb[0], __shfl(w_ix, 0, W), l_fs[0], l_lane[0]);
         int next2 = kFar;
-        double fv2 = 0.0;
+        vals fv2 = zero();
         auto look_ahead = [&]() {                            // (next2, fv2) for fiber c + 1
             if (c + 1 >= c1) { next2 = kFar; return; }
             if (c + 1 - cw == W) { cw = c + 1; load_fibers(); }
@@ -273,11 +294,11 @@ generic_fused_kernel(GenStmt g) {
             xv = in ? lx[ew + j] : 0.0;
         };
         load_leaves(0, l_ix, l_x);
-        double t = 0.0;
+        vals t = zero();
         for (int ew = 0; ew < n_total; ew += W) {
             load_leaves(ew + W, l_ix2, l_x2);
             const int n = n_total - ew < W ? n_total - ew : W;
-            double yv[4], yv2[4];                            // rows of F1 four leaves at a time, one batch ahead
+            vals yv[4], yv2[4];                              // rows of F1 four leaves at a time, one batch ahead
 #pragma unroll
             for (int k = 0; k < 4; ++k) yv[k] = row(f1b, __shfl(l_ix, k, W), fs1, f1_lane);      // past the end: row 0, never added
             for (int u0 = 0; u0 < n; u0 += 4) {
@@ -293,8 +314,8 @@ generic_fused_kernel(GenStmt g) {
                     if (u0 + k < n) {
                         const int pos = ew + u0 + k;
                         if (pos >= next) {                   // the fiber ended (every fiber of a CSF has a leaf): its sum
-                            s[0] = fma(t, fv, s[0]);         // times the factor of its level
-                            t = 0.0;
+                            fma_v(t, fv, s[0]);              // times the factor of its level
+                            t = zero();
                             ++c;
                             next = next2;
                             fv = fv2;
@@ -303,8 +324,8 @@ generic_fused_kernel(GenStmt g) {
 #pragma unroll
                             for (int v = 1; v <= U; ++v) {
                                 if (up && pos >= endu[v]) {
-                                    s[v] = fma(s[v - 1], fvu[v], s[v]);
-                                    s[v - 1] = 0.0;
+                                    fma_v(s[v - 1], fvu[v], s[v]);
+                                    s[v - 1] = zero();
                                     ++cu[v];
                                     endu[v] = endu2[v];
                                     fvu[v] = fvu2[v];
@@ -314,7 +335,7 @@ generic_fused_kernel(GenStmt g) {
                                 }
                             }
                         }
-                        t = fma(xv[k], yv[k], t);
+                        fma_s(xv[k], yv[k], t);
                     }
                 }
 #pragma unroll
@@ -323,27 +344,33 @@ generic_fused_kernel(GenStmt g) {
             l_ix = l_ix2;
             l_x = l_x2;
         }
-        s[0] = fma(t, fv, s[0]);
+        fma_v(t, fv, s[0]);
 #pragma unroll
-        for (int v = 1; v <= U; ++v) s[v] = fma(s[v - 1], fvu[v], s[v]);
+        for (int v = 1; v <= U; ++v) fma_v(s[v - 1], fvu[v], s[v]);
     }
     if (!live) return;
-    if (segmented) { g.partial[unit * g.out_block + out_off] = s[U]; return; }
-    const int64_t row_out = g.scatter_rows ? int64_t(g.idx[0][p]) : p;
-    g.out[row_out * g.out_block + out_off] = s[U];
+    const int64_t row_out = segmented ? unit : (g.scatter_rows ? int64_t(g.idx[0][p]) : p);
+    double *dst = (segmented ? g.partial : g.out) + row_out * g.out_block + out_off;
+    if constexpr (V == 2) *reinterpret_cast<double2 *>(dst) = make_double2(s[U].v[0], s[U].v[1]);
+    else dst[0] = s[U].v[0];
 }
 
 template <int W, int U>
-static void launch_fused_u(const GenStmt &g, dim3 grid, hipStream_t stream) {
-    if (g.fused_small) generic_fused_kernel<W, true, U><<<grid, dim3(256), 0, stream>>>(g);
-    else generic_fused_kernel<W, false, U><<<grid, dim3(256), 0, stream>>>(g);
+static void launch_fused_u(const GenStmt &g, bool pairs, dim3 grid, hipStream_t stream) {
+    if (pairs) {
+        if (g.fused_small) generic_fused_kernel<W, true, U, 2><<<grid, dim3(256), 0, stream>>>(g);
+        else generic_fused_kernel<W, false, U, 2><<<grid, dim3(256), 0, stream>>>(g);
+    } else {
+        if (g.fused_small) generic_fused_kernel<W, true, U, 1><<<grid, dim3(256), 0, stream>>>(g);
+        else generic_fused_kernel<W, false, U, 1><<<grid, dim3(256), 0, stream>>>(g);
+    }
 }
 template <int W>
-static void launch_fused(const GenStmt &g, dim3 grid, hipStream_t stream) {
+static void launch_fused(const GenStmt &g, bool pairs, dim3 grid, hipStream_t stream) {
     static_assert(kGenMaxUpper == 2, "one instance per number of inlined levels");
-    if (g.fused_upper == 0) launch_fused_u<W, 0>(g, grid, stream);
-    else if (g.fused_upper == 1) launch_fused_u<W, 1>(g, grid, stream);
-    else launch_fused_u<W, 2>(g, grid, stream);
+    if (g.fused_upper == 0) launch_fused_u<W, 0>(g, pairs, grid, stream);
+    else if (g.fused_upper == 1) launch_fused_u<W, 1>(g, pairs, grid, stream);
+    else launch_fused_u<W, 2>(g, pairs, grid, stream);
 }
 
 // second pass of a long sum: the partial sums of each result node, added in segment order.  Nodes
@@ -916,6 +943,21 @@ conststn_status build_generic(conststn_plan_s *plan) {
                         small = small && g1.fused_small == 1;
                     }
                     g.fused_small = small ? 1 : 0;
+                    {
+                        // two adjacent elements of the innermost dense index per lane: stride 1 there, every other stride even
+                        const int last_q = g.n_out - 1;
+                        auto fits = [&](const int64_t *stride, int64_t level_stride) {
+                            if (stride[last_q] != 1 || level_stride % 2 != 0) return false;
+                            for (int q = 0; q < last_q; ++q)
+                                if (stride[q] % 2 != 0) return false;
+                            return true;
+                        };
+                        bool pairs = last_q >= 0 && g.extent[last_q] % 2 == 0 && g.out_block % 2 == 0 &&
+                                     fits(g.f_stride, g.f_level_stride[d_out]) && fits(g.f1_stride, g.f1_level_stride) &&
+                                     fits(g.out_stride, 0);
+                        for (int v = 0; v < g.fused_upper; ++v) pairs = pairs && fits(g.fu_stride[v], g.fu_level_stride[v]);
+                        g.fused_pairs = pairs ? 1 : 0;
+                    }
                     for (int v = 1; v <= g.fused_upper; ++v) CST_TRY(leaf_ptr(n - 2 - v, &g.leaf_end[v - 1]));
                     if (d_out > 0) CST_TRY(leaf_ptr(d_out - 1, &g.out_leaf));
                     g.in_is_leaf = 1;                       // reads X's values, not the intermediate
@@ -1065,21 +1107,29 @@ conststn_status launch_generic(const conststn_plan_s *plan, const double *const 
             g.heavy_sums = plan->gen_buffers[size_t(g.heavy_buffer)]->p;
             g.partial = plan->gen_buffers[size_t(g.partial_buffer)]->p;
         }
+        // two result elements per lane where the plan found the layouts fit and the caller's arrays begin on 16 bytes
+        bool pairs = false;
+        if (g.fused && g.fused_pairs) {
+            auto on16 = [](const void *q) { return reinterpret_cast<uintptr_t>(q) % 16 == 0; };
+            pairs = on16(g.f) && on16(g.f1) && on16(g.out) && (g.n_segs == 0 || on16(g.partial));
+            for (int v = 0; v < g.fused_upper; ++v) pairs = pairs && on16(g.fu[v]);
+        }
         // lanes that share a result node in the fused kernel: the power of two that holds its elements, 8 to 64
+        const int64_t lane_elems = pairs ? g.out_block / 2 : g.out_block;
         int fused_w = 8;
-        while (fused_w < 64 && fused_w < g.out_block) fused_w *= 2;
+        while (fused_w < 64 && fused_w < lane_elems) fused_w *= 2;
         const int64_t units = g.n_segs > 0 ? g.n_segs : g.out_nodes;
         const int64_t total = g.kind == 1 ? g.nodes[g.d_node - 1] * g.out_threads
-                              : g.fused   ? units * ((g.out_block + fused_w - 1) / fused_w) * fused_w
+                              : g.fused   ? units * ((lane_elems + fused_w - 1) / fused_w) * fused_w
                                           : units * g.out_block;
         if (total > (int64_t(1) << 31) * 256) { set_error("statement result too large for one launch"); return CONSTSTN_EUNSUPPORTED; }
         const dim3 grid(unsigned((total + 255) / 256)), block(256);
         if (total > 0) {
             if (g.kind == 1) generic_node_kernel<<<grid, block, 0, stream>>>(g);
-            else if (g.fused && fused_w == 8) launch_fused<8>(g, grid, stream);
-            else if (g.fused && fused_w == 16) launch_fused<16>(g, grid, stream);
-            else if (g.fused && fused_w == 32) launch_fused<32>(g, grid, stream);
-            else if (g.fused) launch_fused<64>(g, grid, stream);
+            else if (g.fused && fused_w == 8) launch_fused<8>(g, pairs, grid, stream);
+            else if (g.fused && fused_w == 16) launch_fused<16>(g, pairs, grid, stream);
+            else if (g.fused && fused_w == 32) launch_fused<32>(g, pairs, grid, stream);
+            else if (g.fused) launch_fused<64>(g, pairs, grid, stream);
             else generic_stmt_kernel<<<grid, block, 0, stream>>>(g);
             CST_HIP(hipGetLastError());
         }

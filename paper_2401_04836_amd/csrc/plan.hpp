@@ -72,6 +72,7 @@ struct GenStmt {
     // its children itself, so that the intermediate is a scalar in a register and is never stored
     int fused;                                 // 1: producer inlined (its own entry has skip = 1)
     int fused_small;                           // 1: both factors within reach of 32-bit byte offsets formed by 24-bit multiplies
+    int fused_pairs;                           // 1: the layouts allow two adjacent result elements per lane (16-byte row reads)
     int skip;                                  // 1: computed inside its consumer's kernel
     int f1_operand;                            // the producer's dense factor, resolved at launch
     const double *f1;

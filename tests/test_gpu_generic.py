@@ -357,6 +357,21 @@ def test_fused_chain_of_producers_is_one_kernel():
             seg, pl = _run(text, x, [0, 1, 2, 3], ops, (40, R), options="generic_span=%d" % span)
             assert "kernels=1 inlined_producers=2" in pl.describe(), pl.describe()
             _check(seg, coords, vals, "ijkl", f, "ir", {"i": 40, "r": R})
+        # rows of 24 or 40 doubles with the rank index innermost in D and B, rank-major C: one element per lane;
+        # all three rank-innermost: two per lane, unless an array does not begin on 16 bytes
+        assert "two_elements_per_lane=0" in pl.describe(), pl.describe()
+        Ct = C.t().contiguous()
+        text2 = text.replace("C[r,k]", "C[k,r]")
+        two, pl = _run(text2, x, [0, 1, 2, 3], [("D", D), ("C", Ct), ("B", B)], (40, R), options="generic_span=700")
+        assert "two_elements_per_lane=1" in pl.describe(), pl.describe()
+        np.testing.assert_allclose(two, got, rtol=0, atol=1e-10)
+        # an operand that begins 8 bytes past a 16-byte boundary
+        csf = cst.build_csf([c.cuda() for c in coords], vals.cuda(), dims, [0, 1, 2, 3])
+        dev = [D.cuda(), Ct.cuda(), torch.zeros(B.numel() + 1, dtype=torch.float64).cuda()[1:].view_as(B).copy_(B.cuda())]
+        assert dev[2].data_ptr() % 16 == 8
+        pl = cst.plan(text2, [("X", csf), ("D", dev[0]), ("C", dev[1]), ("B", dev[2])])
+        one = cst.execute(pl, dev).cpu().numpy().reshape(40, R)
+        np.testing.assert_allclose(one, got, rtol=0, atol=1e-10)
         pair, pl = _run(text, x, [0, 1, 2, 3], ops, (40, R), fusion=[3, 1, 0])       # the second pair fused on i only
         assert "kernels=2 inlined_producers=1" in pl.describe(), pl.describe()
         np.testing.assert_allclose(pair, got, rtol=0, atol=1e-10)
