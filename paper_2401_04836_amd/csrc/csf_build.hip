@@ -308,19 +308,39 @@ radix_scatter_kernel(int64_t n, const uint64_t *__restrict__ keys_in, const uint
 // Sorts n (key, payload) pairs by the low `bits` bits of the key, stably; a and b are two buffers of n
 // entries each, the input is in a, the result in whichever *keys_sorted / *pay_sorted name.  Waits
 // for the stream before it returns (the pass tables are released then).
+static size_t up256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+// bytes of pass tables a sort of n pairs needs (handed in by callers that keep one allocation for all their
+// temporaries; every device allocation and release costs a fraction of a millisecond)
+size_t radix_sort_scratch_bytes(int64_t n) {
+    const size_t stiles = size_t(div_up(std::max<int64_t>(n, 1), kSortTile));
+    return up256(stiles * 256 * sizeof(unsigned)) + up256(stiles * 256 * sizeof(int64_t)) + 2 * up256(256 * sizeof(int64_t));
+}
+
 conststn_status radix_sort_pairs_u64(uint64_t *keys_a, uint64_t *keys_b, uint32_t *pay_a, uint32_t *pay_b, int64_t n,
                                      int bits, hipStream_t stream, const uint64_t **keys_sorted,
-                                     const uint32_t **pay_sorted) {
+                                     const uint32_t **pay_sorted, void *scratch) {
     *keys_sorted = keys_a;
     *pay_sorted = pay_a;
     if (bits <= 0 || n <= 1) return CONSTSTN_OK;
     const int64_t stiles = div_up(n, kSortTile);
-    DevBuf<unsigned> scounts;
-    DevBuf<int64_t> soffsets, stotals, sbases;
-    CST_TRY(scounts.alloc(size_t(stiles) * 256));
-    CST_TRY(soffsets.alloc(size_t(stiles) * 256));
-    CST_TRY(stotals.alloc(256));
-    CST_TRY(sbases.alloc(256));
+    DevBuf<char> own;
+    if (!scratch) {
+        CST_TRY(own.alloc(radix_sort_scratch_bytes(n)));
+        scratch = own.p;
+    }
+    struct { unsigned *p; } scounts;
+    struct { int64_t *p; } soffsets, stotals, sbases;
+    {
+        char *at = static_cast<char *>(scratch);
+        scounts.p = reinterpret_cast<unsigned *>(at);
+        at += up256(size_t(stiles) * 256 * sizeof(unsigned));
+        soffsets.p = reinterpret_cast<int64_t *>(at);
+        at += up256(size_t(stiles) * 256 * sizeof(int64_t));
+        stotals.p = reinterpret_cast<int64_t *>(at);
+        at += up256(256 * sizeof(int64_t));
+        sbases.p = reinterpret_cast<int64_t *>(at);
+    }
     uint64_t *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
     const dim3 sgrid{unsigned(stiles)}, sblock(256);
@@ -514,21 +534,27 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
         return CONSTSTN_OK;
     }
 
-    DevBuf<uint64_t> keys_a, keys_b;
-    DevBuf<uint32_t> pay_a, pay_b;
-    DevBuf<int> dflags;
-    CST_TRY(keys_a.alloc(nnz));
-    CST_TRY(keys_b.alloc(nnz));
-    CST_TRY(pay_a.alloc(nnz));
-    CST_TRY(pay_b.alloc(nnz));
-    CST_TRY(dflags.alloc(2));
+    // every temporary of the build in one allocation
+    const int64_t ntiles = div_up(nnz, kTile);
+    const size_t sort_bytes = radix_sort_scratch_bytes(nnz);
+    const size_t arena_bytes = 2 * up256(size_t(nnz) * 8) + 2 * up256(size_t(nnz) * 4) + up256(2 * sizeof(int)) +
+                               (wide ? 2 * up256(size_t(nnz) * 8) : 0) + sort_bytes +
+                               up256(size_t(ntiles) * order * sizeof(unsigned)) + up256(size_t(ntiles) * order * sizeof(int64_t)) +
+                               up256(CONSTSTN_MAX_ORDER * sizeof(int64_t));
+    DevBuf<char> arena;
+    CST_TRY(arena.alloc(arena_bytes));
+    size_t arena_at = 0;
+    auto take = [&](size_t bytes) { char *q = arena.p + arena_at; arena_at += up256(bytes); return q; };
+    struct { uint64_t *p; } keys_a{reinterpret_cast<uint64_t *>(take(size_t(nnz) * 8))}, keys_b{reinterpret_cast<uint64_t *>(take(size_t(nnz) * 8))};
+    struct { uint32_t *p; } pay_a{reinterpret_cast<uint32_t *>(take(size_t(nnz) * 4))}, pay_b{reinterpret_cast<uint32_t *>(take(size_t(nnz) * 4))};
+    struct { int *p; } dflags{reinterpret_cast<int *>(take(2 * sizeof(int)))};
     CST_HIP(hipMemsetAsync(dflags.p, 0, 2 * sizeof(int), stream));
-
-    DevBuf<uint64_t> lo_orig, hi_orig;                 // two-word keys only: the words in input order
+    struct { uint64_t *p; } lo_orig{nullptr}, hi_orig{nullptr};      // two-word keys only: the words in input order
     if (wide) {
-        CST_TRY(lo_orig.alloc(nnz));
-        CST_TRY(hi_orig.alloc(nnz));
+        lo_orig.p = reinterpret_cast<uint64_t *>(take(size_t(nnz) * 8));
+        hi_orig.p = reinterpret_cast<uint64_t *>(take(size_t(nnz) * 8));
     }
+    void *sort_scratch = take(sort_bytes);
     {
         const int64_t blocks = std::min<int64_t>(div_up(nnz, 256), 65536);
         pack_keys_kernel<<<dim3(unsigned(blocks)), dim3(256), 0, stream>>>(nnz, lv, wide ? lo_orig.p : keys_a.p,
@@ -539,19 +565,19 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
     const uint64_t *skeys = keys_a.p, *skeys_hi = nullptr;
     const uint32_t *spay = pay_a.p;
     if (!wide) {
-        CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, total_bits, stream, &skeys, &spay));
+        CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, total_bits, stream, &skeys, &spay, sort_scratch));
     } else {
         // least significant word first: sort (low word, position), bring the high words into that order, sort
         // again by the high word (stable), then fetch the low words in the final order
         const unsigned gb = unsigned(div_up(nnz, 256));
         CST_HIP(hipMemcpyAsync(keys_a.p, lo_orig.p, size_t(nnz) * sizeof(uint64_t), hipMemcpyDeviceToDevice, stream));
-        CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, lo_bits, stream, &skeys, &spay));
+        CST_TRY(radix_sort_pairs_u64(keys_a.p, keys_b.p, pay_a.p, pay_b.p, nnz, lo_bits, stream, &skeys, &spay, sort_scratch));
         uint64_t *k_free = skeys == keys_a.p ? keys_b.p : keys_a.p, *k_used = skeys == keys_a.p ? keys_a.p : keys_b.p;
         uint32_t *p_used = spay == pay_a.p ? pay_a.p : pay_b.p, *p_free = spay == pay_a.p ? pay_b.p : pay_a.p;
         gather_u64_kernel<<<dim3(gb), dim3(256), 0, stream>>>(nnz, hi_orig.p, p_used, k_free);
         CST_HIP(hipGetLastError());
         const uint64_t *shi = nullptr;
-        CST_TRY(radix_sort_pairs_u64(k_free, k_used, p_used, p_free, nnz, hi_bits, stream, &shi, &spay));
+        CST_TRY(radix_sort_pairs_u64(k_free, k_used, p_used, p_free, nnz, hi_bits, stream, &shi, &spay, sort_scratch));
         uint64_t *lo_sorted = shi == k_free ? k_used : k_free;
         gather_u64_kernel<<<dim3(gb), dim3(256), 0, stream>>>(nnz, lo_orig.p, spay, lo_sorted);
         CST_HIP(hipGetLastError());
@@ -559,12 +585,9 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
         skeys_hi = shi;
     }
 
-    const int64_t ntiles = div_up(nnz, kTile);
-    DevBuf<unsigned> tile_counts;
-    DevBuf<int64_t> tile_offsets, totals;
-    CST_TRY(tile_counts.alloc(size_t(ntiles) * order));
-    CST_TRY(tile_offsets.alloc(size_t(ntiles) * order));
-    CST_TRY(totals.alloc(CONSTSTN_MAX_ORDER));
+    struct { unsigned *p; } tile_counts{reinterpret_cast<unsigned *>(take(size_t(ntiles) * order * sizeof(unsigned)))};
+    struct { int64_t *p; } tile_offsets{reinterpret_cast<int64_t *>(take(size_t(ntiles) * order * sizeof(int64_t)))},
+        totals{reinterpret_cast<int64_t *>(take(CONSTSTN_MAX_ORDER * sizeof(int64_t)))};
     if (wide)
         count_heads_kernel<true><<<dim3(unsigned(ntiles)), dim3(kTileThreads), 0, stream>>>(
             nnz, lv, skeys, skeys_hi, tile_counts.p, ntiles, dflags.p);

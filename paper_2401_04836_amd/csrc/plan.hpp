@@ -346,7 +346,8 @@ conststn_status build_csf_device(int order, const int64_t *dims, int64_t nnz,
 // stable radix sort of (64-bit key, 32-bit payload) pairs by the low `bits` key bits (csf_build.hip)
 conststn_status radix_sort_pairs_u64(uint64_t *keys_a, uint64_t *keys_b, uint32_t *pay_a, uint32_t *pay_b, int64_t n,
                                      int bits, hipStream_t stream, const uint64_t **keys_sorted,
-                                     const uint32_t **pay_sorted);
+                                     const uint32_t **pay_sorted, void *scratch = nullptr);
+size_t radix_sort_scratch_bytes(int64_t n);     // device bytes `scratch` must hold when it is handed in
 
 // exclusive prefix sum of n int64 on the default stream; *total_host = sum of all inputs
 conststn_status exscan(int64_t *in, int64_t *out, int64_t n, int64_t *total_host);
